@@ -1,0 +1,146 @@
+"""Test-side helpers: a float64 forward pass, layer linearisation, a second DeepPoly in NumPy.
+
+Nothing here is used by the HIP library or by the oracle.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+import torch.nn.functional as F
+
+import workloads as wl
+
+
+def forward(net: wl.Net, X: np.ndarray):
+    """Concrete float64 forward pass.  X: [batch, n_in] (CHW-flattened).  Returns {layer id: [batch, n]}."""
+    X = torch.as_tensor(np.asarray(X, dtype=np.float64))
+    B = X.shape[0]
+    vals = {0: X.reshape(B, *net.input_shape)}
+    for i, L in enumerate(net.layers, start=1):
+        t = L["type"]
+        if t == "dense":
+            v = vals[L["src"]].reshape(B, -1) @ torch.as_tensor(L["W"].astype(np.float64)).T
+            v = v + torch.as_tensor(L["b"].astype(np.float64))
+            v = v.reshape(B, -1, 1, 1)
+        elif t == "conv":
+            v = F.conv2d(vals[L["src"]], torch.as_tensor(L["W"].astype(np.float64)),
+                         torch.as_tensor(L["b"].astype(np.float64)), stride=L["stride"], padding=L["pad"])
+        elif t == "relu":
+            v = torch.clamp(vals[L["src"]], min=0.0)
+        elif t == "add":
+            v = vals[L["a"]] + vals[L["b"]]
+        else:
+            raise ValueError(t)
+        vals[i] = v
+    return {k: v.reshape(B, -1).numpy() for k, v in vals.items()}
+
+
+def affine_matrix(net: wl.Net, lid: int):
+    """(A, b) with layer_lid(x_src) = A x_src + b for a dense or conv layer, by pushing basis vectors."""
+    L = net.layers[lid - 1]
+    src = L["src"]
+    shp = net.shape_of(src)
+    n = int(np.prod(shp))
+    eye = torch.eye(n, dtype=torch.float64).reshape(n, *shp)
+    zero = torch.zeros(1, *shp, dtype=torch.float64)
+    if L["type"] == "dense":
+        return L["W"].astype(np.float64), L["b"].astype(np.float64)
+    W = torch.as_tensor(L["W"].astype(np.float64))
+    bvec = F.conv2d(zero, W, torch.as_tensor(L["b"].astype(np.float64)), stride=L["stride"], padding=L["pad"])
+    cols = F.conv2d(eye, W, None, stride=L["stride"], padding=L["pad"])
+    return cols.reshape(n, -1).T.numpy().copy(), bvec.reshape(-1).numpy().copy()
+
+
+def sample_box(lo, hi, n, rng, corners=True):
+    lo = np.asarray(lo, np.float64)
+    hi = np.asarray(hi, np.float64)
+    X = lo + (hi - lo) * rng.random((n, lo.size))
+    if corners:
+        m = n // 2
+        pick = rng.random((m, lo.size)) < 0.5
+        X[:m] = np.where(pick, lo, hi)
+    return X
+
+
+def ball_box(center, eps, clip_lo=0.0, clip_hi=1.0):
+    c = np.asarray(center, np.float32).astype(np.float64)
+    e = float(np.float32(eps))
+    return np.maximum(c - e, clip_lo), np.minimum(c + e, clip_hi)
+
+
+# ---- a second, independent DeepPoly: round-to-nearest float64, matrix form -----------------------
+def _np_backsub(net, mats, bounds, relax, start, c0, upper, candidates):
+    """start: {layer: matrix [rows, n_layer]}, c0: [rows].  Returns the best candidate per row."""
+    expr = dict(start)
+    c = np.array(c0, dtype=np.float64)
+    best = np.full(c.shape[0], np.inf if upper else -np.inf)
+    while True:
+        k = max(expr)
+        if len(expr) == 1 and k in bounds and (k == 0 or candidates == 0):
+            l, u = bounds[k]
+            Mp, Mn = np.maximum(expr[k], 0), np.minimum(expr[k], 0)
+            v = (Mp @ u + Mn @ l + c) if upper else (Mp @ l + Mn @ u + c)
+            best = np.minimum(best, v) if upper else np.maximum(best, v)
+        if k == 0:
+            return best
+        M = expr.pop(k)
+        L = net.layers[k - 1]
+        if L["type"] in ("dense", "conv"):
+            A, b = mats[k]
+            expr[L["src"]] = expr.get(L["src"], 0) + M @ A
+            c = c + M @ b
+        elif L["type"] == "add":
+            expr[L["a"]] = expr.get(L["a"], 0) + M
+            expr[L["b"]] = expr.get(L["b"], 0) + M
+        else:
+            g, d, lam = relax[k]
+            Mp, Mn = np.maximum(M, 0), np.minimum(M, 0)
+            if upper:
+                expr[L["src"]] = expr.get(L["src"], 0) + Mp * g + Mn * lam
+                c = c + Mp @ d
+            else:
+                expr[L["src"]] = expr.get(L["src"], 0) + Mp * lam + Mn * g
+                c = c + Mn @ d
+
+
+def np_deeppoly(net: wl.Net, lo0, hi0, lambda_policy=0, candidates=0, extra_rows=None):
+    """All-neurons-at-once DeepPoly with plain float64 matrices (no outward rounding).
+
+    Returns {layer id: (l, u)} for the input, ReLU inputs, ReLU layers and the last layer.
+    extra_rows: optional matrix over the last layer; its lower bounds are returned under key "extra"."""
+    nL = len(net.layers)
+    mats = {i: affine_matrix(net, i) for i, L in enumerate(net.layers, start=1) if L["type"] in ("dense", "conv")}
+    feeds_relu = {L["src"] for L in net.layers if L["type"] == "relu"}
+    bounds = {0: (np.asarray(lo0, np.float64), np.asarray(hi0, np.float64))}
+    relax = {}
+
+    def first_step(i, R):
+        L = net.layers[i - 1]
+        if L["type"] in ("dense", "conv"):
+            A, b = mats[i]
+            return {L["src"]: R @ A}, R @ b
+        s = {}
+        s[L["a"]] = s.get(L["a"], 0) + R
+        s[L["b"]] = s.get(L["b"], 0) + R
+        return s, np.zeros(R.shape[0])
+
+    for i, L in enumerate(net.layers, start=1):
+        if L["type"] == "relu":
+            l, u = bounds[L["src"]]
+            uns = (l < 0) & (u > 0)
+            den = np.where(uns, u - l, 1.0)
+            g = np.where(l >= 0, 1.0, np.where(u <= 0, 0.0, u / den))
+            d = np.where(uns, -l * u / den, 0.0)
+            lam_u = {0: (u > -l).astype(np.float64), 1: np.zeros_like(l), 2: np.ones_like(l)}[lambda_policy]
+            lam = np.where(l >= 0, 1.0, np.where(u <= 0, 0.0, lam_u))
+            relax[i] = (g, d, lam)
+            bounds[i] = (np.maximum(l, 0), np.maximum(u, 0))
+        elif i in feeds_relu or i == nL:
+            s, c0 = first_step(i, np.eye(net.n_neurons(i)))
+            up = _np_backsub(net, mats, bounds, relax, s, c0, True, candidates)
+            lw = _np_backsub(net, mats, bounds, relax, s, c0, False, candidates)
+            bounds[i] = (lw, up)
+    if extra_rows is not None:
+        s, c0 = first_step(nL, np.asarray(extra_rows, np.float64))
+        bounds["extra"] = _np_backsub(net, mats, bounds, relax, s, c0, False, candidates)
+    return bounds
