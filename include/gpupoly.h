@@ -1,0 +1,128 @@
+/*
+ * gpupoly — DeepPoly back-substitution on one AMD MI355X (gfx950).  C ABI.
+ *
+ * The library bounds every neuron of a ReLU network over an L-infinity box by the DeepPoly
+ * relaxation with back-substitution (paper Section 2, "DeepPoly analysis" and "Bottleneck
+ * Backsubstitution"), using dependence windows for convolutional and residual layers
+ * (Sections 3.1, 4.3, Algorithm 1) and floating-point-sound arithmetic (Section 4.1).
+ *
+ * Conventions
+ *   - All pointers are HOST pointers unless the name ends in _dev (then: device memory on the
+ *     current HIP device).  Host arrays are read or written during the call and never retained.
+ *   - Layer id 0 is the input; every gp_add_* call creates the next id and returns it.
+ *     A layer may only reference earlier ids, so ids are a topological order of the network DAG
+ *     (Section 3.1 "Network DAG").
+ *   - Neurons of a layer are numbered C,H,W-flattened (channel outermost) at this boundary.
+ *   - Every call returns a gp_status; nothing throws or aborts across the boundary; a failed call
+ *     leaves the net usable.  gp_last_error() gives a message for the last failure on that net.
+ *   - Bounds are reported for: the input, every layer that feeds a ReLU, every ReLU layer, the last
+ *     layer, and layers marked with gp_request_bounds().  Other layers: GP_ERR_STATE.
+ *   - Soundness: reported bounds contain the exact real-arithmetic output range of the network
+ *     with the given float32 weights over the box (rounding of the analysis itself is accounted
+ *     for; rounding of a float inference of the network is not).
+ *   - Calls on one net must not overlap in time.  Different nets may be used from different threads.
+ */
+#ifndef GPUPOLY_H
+#define GPUPOLY_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gp_net gp_net; /* opaque; owns device copies of weights and of all bounds */
+
+typedef enum {
+    GP_OK = 0,
+    GP_ERR_ARG = 1,         /* null pointer, id out of range, negative size or eps             */
+    GP_ERR_SHAPE = 2,       /* shapes of layers do not fit                                      */
+    GP_ERR_STATE = 3,       /* call order: no analysis yet, layer has no bounds, ...            */
+    GP_ERR_NOMEM = 4,       /* host or device allocation failed                                 */
+    GP_ERR_DEVICE = 5,      /* no usable GPU, or a HIP call failed                              */
+    GP_ERR_NONFINITE = 6,   /* NaN/Inf in weights, inputs or computed bounds                    */
+    GP_ERR_WORKSPACE = 7,   /* workspace too small even for one row                             */
+    GP_ERR_UNSUPPORTED = 8  /* topology the back-substitution engine cannot handle              */
+} gp_status;
+
+/* Input layer of shape (c,h,w); a flat input of n values is (n,1,1).  Paper Section 2. */
+gp_status gp_net_create(int32_t c, int32_t h, int32_t w, gp_net** out);
+void gp_net_destroy(gp_net* net);
+
+/* Affine layers (paper Section 2 "Classification network": x' = A x + b).
+ * W: [out_dim][n_in] row-major, n_in = C*H*W of in_layer, flattened C,H,W.  b: [out_dim] or NULL. */
+gp_status gp_add_dense(gp_net* net, int32_t in_layer, int32_t out_dim, const float* W, const float* b,
+                       int32_t* layer_id);
+/* W: [c_out][c_in][kh][kw]; b: [c_out] or NULL; zero padding; output (y,x), tap (f,g) reads input
+ * (y*stride_h - pad_h + f, x*stride_w - pad_w + g)  (index map of Algorithm 1). */
+gp_status gp_add_conv2d(gp_net* net, int32_t in_layer, int32_t c_out, int32_t kh, int32_t kw,
+                        int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
+                        const float* W, const float* b, int32_t* layer_id);
+/* Element-wise max(x,0) of in_layer. */
+gp_status gp_add_relu(gp_net* net, int32_t in_layer, int32_t* layer_id);
+/* Element-wise sum of two layers of equal shape: the exit of a residual block (Section 3.1,
+ * "Dependence set and residual networks"). */
+gp_status gp_add_residual(gp_net* net, int32_t layer_a, int32_t layer_b, int32_t* layer_id);
+/* Also compute bounds for this (affine or sum) layer although no ReLU reads it. */
+gp_status gp_request_bounds(gp_net* net, int32_t layer_id);
+
+/* HIP stream (hipStream_t) all work of this net is enqueued on; NULL = the default stream. */
+gp_status gp_set_stream(gp_net* net, void* hip_stream);
+/* Scratch memory for the coefficient blocks of the rows in flight (Section 4.2 "Memory
+ * management": rows are processed in chunks that fit).  min_bytes: smallest workable size for this
+ * net and batch; full_bytes: size at which no layer needs chunking. */
+gp_status gp_workspace_size(const gp_net* net, int32_t batch, int64_t* min_bytes, int64_t* full_bytes);
+/* Device memory owned by the caller (e.g. a torch tensor), 256-byte aligned, kept alive until
+ * replaced or the net is destroyed.  Without it the library allocates its own on first use. */
+gp_status gp_set_workspace(gp_net* net, void* ptr_dev, int64_t bytes);
+
+/* Analyse the box  [max(center-eps, clip_lo), min(center+eps, clip_hi)]  (Section 2, L-infinity
+ * robustness).  center: [n_in].  Blocks until the bounds are on the device. */
+gp_status gp_analyze(gp_net* net, const float* center, float eps, float clip_lo, float clip_hi);
+/* Analyse an explicit box lo <= x <= hi, both [n_in]. */
+gp_status gp_analyze_box(gp_net* net, const float* lo, const float* hi);
+/* `batch` independent boxes at once; rows of all boxes share the kernel launches.
+ * centers: [batch][n_in]. */
+gp_status gp_analyze_batch(gp_net* net, int32_t batch, const float* centers, float eps, float clip_lo,
+                           float clip_hi);
+/* Same with the centres already in device memory ([batch][n_in] float). */
+gp_status gp_analyze_batch_dev(gp_net* net, int32_t batch, const float* centers_dev, float eps,
+                               float clip_lo, float clip_hi);
+
+/* Bounds of one layer for box `batch_index` of the last analysis: lower/upper [n_layer] float32,
+ * rounded outward from the internal float64 values. */
+gp_status gp_get_bounds(const gp_net* net, int32_t layer_id, float* lower, float* upper);
+gp_status gp_get_bounds_batch(const gp_net* net, int32_t layer_id, int32_t batch_index, float* lower,
+                              float* upper);
+/* The same as float64 (the values the analysis itself uses for later layers). */
+gp_status gp_get_bounds_f64(const gp_net* net, int32_t layer_id, int32_t batch_index, double* lower,
+                            double* upper);
+/* Lower relaxation slope (0 or 1) chosen for each neuron of a ReLU layer; [n_layer] bytes. */
+gp_status gp_get_relu_lambda(const gp_net* net, int32_t relu_layer_id, int32_t batch_index, int8_t* lam);
+
+/* Robustness of `label` over the analysed box: margins[r] = sound lower bound of
+ * y_label - y_j over the last layer for the r-th j != label (increasing j), obtained by
+ * back-substituting the difference; verified = all margins > 0.  margins: [n_out-1]. */
+gp_status gp_certify(gp_net* net, int32_t label, int32_t* verified, float* margins);
+/* labels: [batch]; verified: [batch]; margins: [batch][n_out-1]. */
+gp_status gp_certify_batch(gp_net* net, const int32_t* labels, int32_t* verified, float* margins);
+
+/* Introspection (host only, no GPU needed): the sequence of back-substitution steps planned for
+ * the rows of `layer_id`.  Each step is 8 int32: {kind, layer, window_h, window_w, channels,
+ * acc_stride_h, acc_pad_h, merged}; kind 0 = initial block, 1 = affine crossing, 2 = ReLU,
+ * 3 = residual fork.  Window sizes are those of eqs. (4),(5) of Section 4.3 clipped to the layer.
+ * Returns the number of steps in *n_steps (at most max_steps are written). */
+gp_status gp_debug_plan(const gp_net* net, int32_t layer_id, int32_t* steps, int32_t max_steps,
+                        int32_t* n_steps);
+
+int32_t gp_num_layers(const gp_net* net);
+int32_t gp_layer_size(const gp_net* net, int32_t layer_id);
+/* Seconds of GPU time of the last analyse call's back-substitution kernels is not tracked here;
+ * use HIP events on the stream given to gp_set_stream. */
+const char* gp_last_error(const gp_net* net);
+const char* gp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GPUPOLY_H */

@@ -563,9 +563,10 @@ int dp_analyze(dp_net *N) {
 
 /* lower bounds of y_label - y_j over the last layer, j != label, in increasing j */
 int dp_certify(dp_net *N, int label, int *verified, double *margins) {
-    if (!N || !N->analyzed) return DP_ERR_STATE;
+    if (!N) return DP_ERR_STATE;
     int lid = N->n_layers - 1;
     layer_t *l = &N->L[lid];
+    if (!l->has_bounds) return DP_ERR_STATE;   /* the analysis (whole or layer by layer) must have reached the end */
     if (label < 0 || label >= l->n || l->type == L_RELU) return DP_ERR_ARG;
     int ok = 1;
 #pragma omp parallel

@@ -1,0 +1,998 @@
+// Host side of the gpupoly C ABI: network description, dependence-window planning, and the
+// back-substitution driver that enqueues the kernels of kernels.hip.
+//
+// Driver (paper Section 2 "Bottleneck Backsubstitution", Section 4.2 for the order of layers):
+// layers are visited in id order; every layer that needs intervals is the start layer of a batch
+// of rows which are back-substituted, chunk by chunk, through all earlier layers down to the
+// input; candidates are taken wherever the expression ranges over a single layer.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <string>
+#include <vector>
+
+#include "../../include/gpupoly.h"
+#include "kernels.hpp"
+
+namespace {
+
+enum LType { T_INPUT = 0, T_DENSE = 1, T_CONV = 2, T_RELU = 3, T_ADD = 4 };
+
+// Dependence window of a row in some layer, before clipping to the layer (Section 4.3):
+// origin = S*pos - P (accumulated stride S, eq. 9; P accumulates padding), size W (eq. 4).
+struct Geom {
+    int Sy = 0, Sx = 0, Py = 0, Px = 0, Wy = 1, Wx = 1;
+};
+
+struct Layer {
+    int type = T_INPUT, a = -1, b = -1;
+    int C = 0, H = 0, W = 0;
+    long long n = 0;
+    int kh = 1, kw = 1, sh = 1, sw = 1, ph = 0, pw = 0;
+    std::vector<float> wt_host;    // device layout [tap][C][C_in], kept until uploaded
+    std::vector<float> bias_host;  // [C]
+    double rowabs = 0.0;           // max_i sum_j |F_ij|
+    bool need_bounds = false;      // intervals are computed for this layer (derived from the topology)
+    bool req_bounds = false;       // asked for through gp_request_bounds
+    // topology-derived
+    std::vector<int> land;         // affine layers a block over this layer is crossed through next
+    std::vector<double> beff_host; // [C] summed bias of those layers (float64: the sum of two float32 is kept exact)
+    // device
+    float* d_wt = nullptr;
+    double* d_beff = nullptr;
+    double *d_lo = nullptr, *d_hi = nullptr, *d_del = nullptr, *d_xmax = nullptr;
+    float *d_gam = nullptr, *d_lam = nullptr;
+};
+
+struct PlanOp {
+    enum Kind { INIT = 0, SCAN = 1, CROSS = 2, FINALIZE = 3 } kind = INIT;
+    int slot_in = -1, slot_out = -1, slot_add = -1;
+    Geom g_in, g_out, g_add;
+    int layer_in = -1, relax_in = -1, layer_out = -1, relax_add = -1;
+    bool do_consts = false, update_best = false, rounded = false;
+};
+
+struct Plan {
+    bool valid = false;
+    std::vector<PlanOp> ops;
+    int n_slots = 0;
+    long long slot_elems = 0;         // largest block, elements per row
+    std::vector<int32_t> steps;       // gp_debug_plan records, 8 ints each
+};
+
+const double kRoundCoef = 0x1p-24 * (1.0 + 0x1p-20);   // float32 rounding of a float64 value
+const int kMaxSlots = 6;
+
+}  // namespace
+
+struct gp_net {
+    std::vector<Layer> L;
+    std::string err;
+    hipStream_t stream = nullptr;
+    void* ws_user = nullptr;
+    long long ws_user_bytes = 0;
+    void* ws_own = nullptr;
+    long long ws_own_bytes = 0;
+    bool topo_ready = false;
+    std::vector<Plan> plans;     // per layer
+    Plan cert_plan;
+    int batch = 0;               // batch the device bound arrays are sized for
+    bool analyzed = false;
+    bool weights_uploaded = false;
+    int* d_flag = nullptr;
+    int* d_labels = nullptr;
+    float* d_margins = nullptr;
+    float* d_centers = nullptr;
+    long long d_centers_cap = 0;
+    int device = -1;
+};
+
+namespace {
+
+gp_status fail(const gp_net* net, gp_status st, const char* fmt, ...) {
+    if (net) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof(buf), fmt, ap);
+        va_end(ap);
+        const_cast<gp_net*>(net)->err = buf;
+    }
+    return st;
+}
+
+#define HIP_TRY(net, call)                                                                          \
+    do {                                                                                            \
+        hipError_t e__ = (call);                                                                    \
+        if (e__ != hipSuccess)                                                                      \
+            return fail(net, e__ == hipErrorOutOfMemory ? GP_ERR_NOMEM : GP_ERR_DEVICE, "%s: %s", #call, \
+                        hipGetErrorString(e__));                                                    \
+    } while (0)
+
+void dfree(void* p) {
+    if (p) (void)hipFree(p);
+}
+
+bool all_finite(const float* p, size_t n) {
+    for (size_t i = 0; i < n; ++i)
+        if (!std::isfinite(p[i])) return false;
+    return true;
+}
+
+bool is_affine(const Layer& l) { return l.type == T_DENSE || l.type == T_CONV; }
+
+// ---- window geometry -------------------------------------------------------------------------
+void normalise(Geom& g, const Layer& l) {
+    if (g.Wy >= l.H) { g.Sy = 0; g.Py = 0; g.Wy = l.H; }
+    if (g.Wx >= l.W) { g.Sx = 0; g.Px = 0; g.Wx = l.W; }
+}
+
+// window in the input layer of affine layer `a` from the window g in its output (eqs. 4, 6-9)
+Geom cross_geom(const Geom& g, const Layer& a, const Layer& pred) {
+    Geom o;
+    if (a.type == T_DENSE) {
+        o.Sy = o.Sx = o.Py = o.Px = 0;
+        o.Wy = pred.H;
+        o.Wx = pred.W;
+    } else {
+        o.Sy = g.Sy * a.sh; o.Py = g.Py * a.sh + a.ph; o.Wy = (g.Wy - 1) * a.sh + a.kh;
+        o.Sx = g.Sx * a.sw; o.Px = g.Px * a.sw + a.pw; o.Wx = (g.Wx - 1) * a.sw + a.kw;
+    }
+    normalise(o, pred);
+    return o;
+}
+
+bool hull_dim(int S1, int P1, int W1, int S2, int P2, int W2, int H, int& S, int& P, int& W) {
+    bool full1 = (W1 >= H), full2 = (W2 >= H);
+    if (full1 || full2) { S = 0; P = 0; W = H; return true; }
+    if (S1 != S2) return false;
+    S = S1;
+    P = std::max(P1, P2);
+    W = std::max(W1 - P1, W2 - P2) + P;
+    return true;
+}
+
+bool hull(const Geom& a, const Geom& b, const Layer& l, Geom& o) {
+    if (!hull_dim(a.Sy, a.Py, a.Wy, b.Sy, b.Py, b.Wy, l.H, o.Sy, o.Py, o.Wy)) return false;
+    if (!hull_dim(a.Sx, a.Px, a.Wx, b.Sx, b.Px, b.Wx, l.W, o.Sx, o.Px, o.Wx)) return false;
+    normalise(o, l);
+    return true;
+}
+
+long long block_elems(const Geom& g, const Layer& l) {
+    return (long long)std::min(g.Wy, l.H) * std::min(g.Wx, l.W) * l.C;
+}
+
+// ---- topology-derived data ---------------------------------------------------------------------
+void land_of(const gp_net* net, int q, std::vector<int>& out) {   // where a coefficient over layer q goes next
+    const Layer& l = net->L[q];
+    if (is_affine(l)) out.push_back(q);
+    else if (l.type == T_ADD) { land_of(net, l.a, out); land_of(net, l.b, out); }
+}
+
+gp_status prepare_topology(gp_net* net) {
+    if (net->topo_ready) return GP_OK;
+    int nl = (int)net->L.size();
+    for (int i = 0; i < nl; ++i) net->L[i].need_bounds = net->L[i].req_bounds;
+    for (int i = 1; i < nl; ++i) {
+        Layer& l = net->L[i];
+        // every crossing must land on a layer with intervals (they bound the rounding slack)
+        if (is_affine(l)) net->L[l.a].need_bounds = true;
+        if (l.type == T_RELU) net->L[l.a].need_bounds = true;
+    }
+    net->L[nl - 1].need_bounds = true;
+    for (int i = 0; i < nl; ++i) {
+        Layer& l = net->L[i];
+        l.land.clear();
+        if (is_affine(l)) l.land.push_back(i);
+        else if (l.type == T_RELU) land_of(net, l.a, l.land);
+        else if (l.type == T_ADD) { land_of(net, l.a, l.land); land_of(net, l.b, l.land); }
+        if (l.land.size() > 2) return fail(net, GP_ERR_UNSUPPORTED, "layer %d: more than two affine branches meet", i);
+        l.beff_host.assign(l.C, 0.0);
+        for (int q : l.land)
+            for (int c = 0; c < l.C; ++c) l.beff_host[c] += (double)net->L[q].bias_host[c];
+    }
+    net->plans.assign(nl, Plan());
+    net->cert_plan = Plan();
+    net->topo_ready = true;
+    return GP_OK;
+}
+
+// ---- planning ------------------------------------------------------------------------------------
+struct Desc {
+    int slot = -1;
+    Geom g;
+    int relax = -1;
+    bool consumed = false;
+};
+
+void push_step(Plan& pl, int kind, int layer, const Geom& g, const Layer& l, int merged) {
+    int32_t rec[8] = {kind, layer, std::min(g.Wy, l.H), std::min(g.Wx, l.W), l.C, g.Sy, g.Py, merged};
+    pl.steps.insert(pl.steps.end(), rec, rec + 8);
+}
+
+gp_status build_plan(gp_net* net, int start, bool certify, Plan& pl) {
+    pl = Plan();
+    const std::vector<Layer>& L = net->L;
+    std::vector<int> ref(kMaxSlots, 0);
+    auto alloc_slot = [&]() {
+        for (int i = 0; i < kMaxSlots; ++i)
+            if (ref[i] == 0) { ref[i] = 1; pl.n_slots = std::max(pl.n_slots, i + 1); return i; }
+        return -1;
+    };
+    std::map<int, Desc> expr;
+    Geom g0;
+    if (certify) { g0.Sy = g0.Sx = g0.Py = g0.Px = 0; g0.Wy = L[start].H; g0.Wx = L[start].W; }
+    else { g0.Sy = g0.Sx = 1; g0.Py = g0.Px = 0; g0.Wy = g0.Wx = 1; }
+    normalise(g0, L[start]);
+    {
+        PlanOp op;
+        op.kind = PlanOp::INIT;
+        op.slot_out = alloc_slot();
+        op.g_out = g0;
+        op.layer_out = start;
+        pl.ops.push_back(op);
+        pl.slot_elems = std::max(pl.slot_elems, block_elems(g0, L[start]));
+        PlanOp sc;
+        sc.kind = PlanOp::SCAN;
+        sc.slot_in = op.slot_out; sc.g_in = g0; sc.layer_in = start;
+        sc.do_consts = true; sc.update_best = false; sc.rounded = false;
+        pl.ops.push_back(sc);
+        Desc d; d.slot = op.slot_out; d.g = g0; d.consumed = true;
+        expr[start] = d;
+        push_step(pl, 0, start, g0, L[start], 0);
+    }
+    auto insert = [&](int t, const Desc& d) -> bool {
+        if (expr.count(t)) return false;
+        expr[t] = d;
+        return true;
+    };
+    while (true) {
+        int k = expr.rbegin()->first;
+        if (k == 0) break;
+        Desc d = expr[k];
+        expr.erase(k);
+        const Layer& l = L[k];
+        if (!d.consumed) {
+            PlanOp sc;
+            sc.kind = PlanOp::SCAN;
+            sc.slot_in = d.slot; sc.g_in = d.g; sc.layer_in = k;
+            sc.do_consts = true; sc.update_best = false; sc.rounded = false;
+            sc.relax_in = -2;   // marks: constants only, no interval terms
+            pl.ops.push_back(sc);
+            d.consumed = true;
+        }
+        if (l.type == T_RELU) {
+            if (d.relax != -1) return fail(net, GP_ERR_UNSUPPORTED, "layer %d: ReLU of a ReLU output", k);
+            d.relax = k;
+            if (!insert(l.a, d))
+                return fail(net, GP_ERR_UNSUPPORTED, "layer %d: two expressions meet before an affine layer", l.a);
+            push_step(pl, 2, k, d.g, l, 0);
+        } else if (l.type == T_ADD) {
+            if (l.a == l.b) return fail(net, GP_ERR_UNSUPPORTED, "layer %d: sum of a layer with itself", k);
+            if (!insert(l.a, d) || !insert(l.b, d))
+                return fail(net, GP_ERR_UNSUPPORTED, "layer %d: two expressions meet before an affine layer", k);
+            ref[d.slot] += 1;
+            push_step(pl, 3, k, d.g, l, 0);
+        } else if (is_affine(l)) {
+            const int p = l.a;
+            Geom g = cross_geom(d.g, l, L[p]);
+            PlanOp op;
+            op.kind = PlanOp::CROSS;
+            op.slot_in = d.slot; op.g_in = d.g; op.layer_in = k; op.relax_in = d.relax; op.layer_out = p;
+            Desc ad;
+            bool has_add = expr.count(p) > 0;
+            if (has_add) {
+                ad = expr[p];
+                expr.erase(p);
+                Geom h;
+                if (!hull(g, ad.g, L[p], h))
+                    return fail(net, GP_ERR_UNSUPPORTED, "layer %d: branches with different accumulated strides", p);
+                g = h;
+                if (l.type == T_DENSE && block_elems(ad.g, L[p]) != L[p].n)
+                    return fail(net, GP_ERR_UNSUPPORTED, "layer %d: windowed block joins a dense branch", p);
+                op.slot_add = ad.slot; op.g_add = ad.g; op.relax_add = ad.relax;
+            }
+            op.slot_out = alloc_slot();
+            if (op.slot_out < 0) return fail(net, GP_ERR_UNSUPPORTED, "too many live coefficient blocks");
+            op.g_out = g;
+            pl.ops.push_back(op);
+            pl.slot_elems = std::max(pl.slot_elems, block_elems(g, L[p]));
+            ref[d.slot] -= 1;
+            if (has_add) ref[ad.slot] -= 1;
+            bool complete = true;
+            for (auto& kv : expr)
+                if (kv.first > p) complete = false;
+            PlanOp sc;
+            sc.kind = PlanOp::SCAN;
+            sc.slot_in = op.slot_out; sc.g_in = g; sc.layer_in = p;
+            sc.do_consts = complete; sc.update_best = expr.empty(); sc.rounded = true;
+            pl.ops.push_back(sc);
+            Desc nd; nd.slot = op.slot_out; nd.g = g; nd.relax = -1; nd.consumed = complete;
+            expr[p] = nd;
+            push_step(pl, 1, k, g, L[p], has_add ? 1 : 0);
+        } else {
+            return fail(net, GP_ERR_UNSUPPORTED, "layer %d: unexpected type", k);
+        }
+    }
+    if (expr.size() != 1) return fail(net, GP_ERR_UNSUPPORTED, "expression did not reach the input layer alone");
+    PlanOp fin;
+    fin.kind = PlanOp::FINALIZE;
+    pl.ops.push_back(fin);
+    pl.valid = true;
+    return GP_OK;
+}
+
+gp_status get_plan(gp_net* net, int lid, Plan** out) {
+    gp_status st = prepare_topology(net);
+    if (st != GP_OK) return st;
+    Plan& pl = net->plans[lid];
+    if (!pl.valid) {
+        st = build_plan(net, lid, false, pl);
+        if (st != GP_OK) return st;
+    }
+    *out = &pl;
+    return GP_OK;
+}
+
+// ---- device state ------------------------------------------------------------------------------
+void free_layer_bounds(Layer& l) {
+    dfree(l.d_lo); dfree(l.d_hi); dfree(l.d_del); dfree(l.d_xmax); dfree(l.d_gam); dfree(l.d_lam);
+    l.d_lo = l.d_hi = l.d_del = l.d_xmax = nullptr;
+    l.d_gam = l.d_lam = nullptr;
+}
+
+bool has_bounds(const gp_net* net, int lid) {
+    const Layer& l = net->L[lid];
+    return lid == 0 || l.type == T_RELU || l.need_bounds;
+}
+
+gp_status ensure_device(gp_net* net, int batch) {
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) return fail(net, GP_ERR_DEVICE, "no HIP device");
+    if (net->device < 0) HIP_TRY(net, hipGetDevice(&net->device));
+    if (!net->d_flag) HIP_TRY(net, hipMalloc((void**)&net->d_flag, sizeof(int)));
+    if (!net->weights_uploaded) {
+        for (auto& l : net->L) {
+            if (!l.wt_host.empty() && !l.d_wt) {
+                HIP_TRY(net, hipMalloc((void**)&l.d_wt, l.wt_host.size() * sizeof(float)));
+                HIP_TRY(net, hipMemcpy(l.d_wt, l.wt_host.data(), l.wt_host.size() * sizeof(float), hipMemcpyHostToDevice));
+            }
+            if (!l.d_beff && l.C > 0) {
+                HIP_TRY(net, hipMalloc((void**)&l.d_beff, l.C * sizeof(double)));
+                HIP_TRY(net, hipMemcpy(l.d_beff, l.beff_host.data(), l.C * sizeof(double), hipMemcpyHostToDevice));
+            }
+        }
+        net->weights_uploaded = true;
+    }
+    if (net->batch != batch) {
+        for (auto& l : net->L) free_layer_bounds(l);
+        dfree(net->d_labels); net->d_labels = nullptr;
+        dfree(net->d_margins); net->d_margins = nullptr;
+        for (size_t i = 0; i < net->L.size(); ++i) {
+            Layer& l = net->L[i];
+            size_t cnt = (size_t)l.n * batch;
+            if (has_bounds(net, (int)i)) {
+                HIP_TRY(net, hipMalloc((void**)&l.d_lo, cnt * sizeof(double)));
+                HIP_TRY(net, hipMalloc((void**)&l.d_hi, cnt * sizeof(double)));
+                HIP_TRY(net, hipMalloc((void**)&l.d_xmax, sizeof(double)));
+            }
+            if (l.type == T_RELU) {
+                HIP_TRY(net, hipMalloc((void**)&l.d_gam, cnt * sizeof(float)));
+                HIP_TRY(net, hipMalloc((void**)&l.d_lam, cnt * sizeof(float)));
+                HIP_TRY(net, hipMalloc((void**)&l.d_del, cnt * sizeof(double)));
+            }
+        }
+        long long nout = net->L.back().n;
+        HIP_TRY(net, hipMalloc((void**)&net->d_labels, sizeof(int) * batch));
+        HIP_TRY(net, hipMalloc((void**)&net->d_margins, sizeof(float) * batch * std::max<long long>(nout - 1, 1)));
+        net->batch = batch;
+    }
+    return GP_OK;
+}
+
+long long align_up(long long v, long long a) { return (v + a - 1) / a * a; }
+
+// bytes one task (both signs) needs for this plan
+long long task_bytes(const Plan& pl, int nsign) {
+    return (long long)nsign * (pl.n_slots * align_up(pl.slot_elems * 4, 16) + 3 * 8);
+}
+
+gp_status get_workspace(gp_net* net, long long want, char** ws, long long* bytes) {
+    if (net->ws_user) { *ws = (char*)net->ws_user; *bytes = net->ws_user_bytes; return GP_OK; }
+    const long long cap = 32LL << 30;
+    long long need = std::min(want, cap);
+    need = align_up(std::max(need, 1LL << 20), 1 << 20);
+    if (net->ws_own_bytes < need) {
+        dfree(net->ws_own);
+        net->ws_own = nullptr; net->ws_own_bytes = 0;
+        HIP_TRY(net, hipMalloc(&net->ws_own, need));
+        net->ws_own_bytes = need;
+    }
+    *ws = (char*)net->ws_own; *bytes = net->ws_own_bytes;
+    return GP_OK;
+}
+
+gp::BlockDesc make_desc(const gp_net* net, const float* data, const Geom& g, int layer, int relax) {
+    const Layer& l = net->L[layer];
+    gp::BlockDesc b;
+    b.data = data;
+    b.H = l.H; b.W = l.W; b.C = l.C;
+    b.wy = std::min(g.Wy, l.H); b.wx = std::min(g.Wx, l.W);
+    b.Sy = g.Sy; b.Sx = g.Sx; b.Py = g.Py; b.Px = g.Px;
+    b.gam = relax >= 0 ? net->L[relax].d_gam : nullptr;
+    b.lam = relax >= 0 ? net->L[relax].d_lam : nullptr;
+    return b;
+}
+
+// run one plan over all its tasks, chunk by chunk (Section 4.2 "Memory management")
+gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int batch) {
+    const Layer& ls = net->L[start];
+    const int nsign = certify ? 1 : 2;
+    const long long n_start = certify ? (ls.n - 1) : ls.n;
+    const long long total = n_start * batch;
+    if (total <= 0) return GP_OK;
+    const long long tb = task_bytes(pl, nsign);
+    char* ws; long long ws_bytes;
+    gp_status st = get_workspace(net, tb * total + 4096, &ws, &ws_bytes);
+    if (st != GP_OK) return st;
+    long long Rc_max = (ws_bytes - 4096) / tb;
+    Rc_max = std::min(Rc_max, (long long)(1 << 28) / nsign);
+    // keep M = rows * window pixels below 2^31 work-groups' worth and int-safe
+    if (Rc_max <= 0) return fail(net, GP_ERR_WORKSPACE, "workspace of %lld bytes cannot hold one row (%lld bytes)", ws_bytes, tb);
+    Rc_max = std::min(Rc_max, total);
+    const long long nrows_max = Rc_max * nsign;
+    double* d_c = (double*)ws;
+    double* d_err = d_c + nrows_max;
+    double* d_best = d_err + nrows_max;
+    char* slots0 = ws + align_up(3 * nrows_max * 8, 256);
+    const long long slot_bytes = align_up(nrows_max * pl.slot_elems * 4, 256);
+    if (slots0 + slot_bytes * pl.n_slots > ws + ws_bytes) {   // alignment slack: shrink
+        Rc_max = std::max<long long>(1, Rc_max - 64);
+        return fail(net, GP_ERR_WORKSPACE, "workspace layout overflow");
+    }
+    auto slot_ptr = [&](int s) { return (float*)(slots0 + slot_bytes * s); };
+
+    for (long long row0 = 0; row0 < total; row0 += Rc_max) {
+        gp::RowMap rm;
+        rm.row0 = row0;
+        rm.Rc = (int)std::min(Rc_max, total - row0);
+        rm.nsign = nsign;
+        rm.n_start = (int)n_start;
+        if (certify) { rm.Hs = 1; rm.Ws = 1; rm.Cs = (int)n_start; }
+        else { rm.Hs = ls.H; rm.Ws = ls.W; rm.Cs = ls.C; }
+        const int nrows = rm.Rc * nsign;
+        for (const PlanOp& op : pl.ops) {
+            if (op.kind == PlanOp::INIT) {
+                gp::InitParams ip;
+                ip.out = slot_ptr(op.slot_out);
+                ip.rm = rm; ip.nrows = nrows;
+                ip.nelem = (int)block_elems(op.g_out, ls);
+                ip.labels = net->d_labels;
+                ip.certify = certify ? 1 : 0;
+                ip.H = ls.H; ip.W = ls.W; ip.C = ls.C;
+                ip.c = d_c; ip.err = d_err; ip.best = d_best;
+                gp::launch_init(ip, net->stream);
+            } else if (op.kind == PlanOp::SCAN) {
+                const Layer& l = net->L[op.layer_in];
+                gp::ScanParams sp;
+                sp.blk = make_desc(net, slot_ptr(op.slot_in), op.g_in, op.layer_in, -1);
+                sp.rm = rm; sp.nrows = nrows;
+                sp.batch_stride = (int)l.n;
+                bool interval_terms = (op.relax_in != -2) && has_bounds(net, op.layer_in) && op.layer_in != start;
+                sp.lo = interval_terms ? l.d_lo : nullptr;
+                sp.hi = interval_terms ? l.d_hi : nullptr;
+                sp.gam = l.type == T_RELU ? l.d_gam : nullptr;
+                sp.lam = l.type == T_RELU ? l.d_lam : nullptr;
+                sp.del = l.type == T_RELU ? l.d_del : nullptr;
+                sp.beff = l.land.empty() ? nullptr : l.d_beff;
+                sp.e1_a = sp.e1_b = 0.0;
+                sp.xmax_a = sp.xmax_b = nullptr;
+                for (size_t i = 0; i < l.land.size(); ++i) {
+                    const Layer& q = net->L[l.land[i]];
+                    double K = (double)q.kh * q.kw * q.C;
+                    double e1 = (K + 8.0) * 0x1p-50 * q.rowabs;
+                    if (i == 0) { sp.e1_a = e1; sp.xmax_a = net->L[q.a].d_xmax; }
+                    else { sp.e1_b = e1; sp.xmax_b = net->L[q.a].d_xmax; }
+                }
+                sp.round_coef = op.rounded ? kRoundCoef : 0.0;
+                sp.do_consts = op.do_consts ? 1 : 0;
+                sp.update_best = op.update_best ? 1 : 0;
+                sp.c = d_c; sp.err = d_err; sp.best = d_best;
+                gp::launch_scan(sp, net->stream);
+            } else if (op.kind == PlanOp::CROSS) {
+                const Layer& a = net->L[op.layer_in];
+                const Layer& p = net->L[op.layer_out];
+                gp::CrossParams cp;
+                cp.in = make_desc(net, slot_ptr(op.slot_in), op.g_in, op.layer_in, op.relax_in);
+                cp.wt = a.d_wt;
+                cp.kh = a.kh; cp.kw = a.kw; cp.sh = a.sh; cp.sw = a.sw; cp.ph = a.ph; cp.pw = a.pw;
+                cp.out = slot_ptr(op.slot_out);
+                if (a.type == T_DENSE) {   // a dense layer is a 1x1 convolution over the flattened predecessor
+                    cp.Ho = 1; cp.Wo = 1; cp.Co = (int)p.n;
+                    cp.owy = cp.owx = 1; cp.oSy = cp.oSx = cp.oPy = cp.oPx = 0;
+                    cp.add.data = nullptr; cp.add.gam = cp.add.lam = nullptr;
+                    if (op.slot_add >= 0) {
+                        cp.add = make_desc(net, slot_ptr(op.slot_add), op.g_add, op.layer_out, op.relax_add);
+                        // full-layer addend seen as one pixel with n channels
+                        cp.add.H = cp.add.W = 1; cp.add.C = (int)p.n; cp.add.wy = cp.add.wx = 1;
+                        cp.add.Sy = cp.add.Sx = cp.add.Py = cp.add.Px = 0;
+                    }
+                } else {
+                    cp.Ho = p.H; cp.Wo = p.W; cp.Co = p.C;
+                    cp.owy = std::min(op.g_out.Wy, p.H); cp.owx = std::min(op.g_out.Wx, p.W);
+                    cp.oSy = op.g_out.Sy; cp.oSx = op.g_out.Sx; cp.oPy = op.g_out.Py; cp.oPx = op.g_out.Px;
+                    cp.add.data = nullptr; cp.add.gam = cp.add.lam = nullptr;
+                    if (op.slot_add >= 0) cp.add = make_desc(net, slot_ptr(op.slot_add), op.g_add, op.layer_out, op.relax_add);
+                }
+                cp.rm = rm; cp.nrows = nrows;
+                gp::launch_cross(cp, net->stream);
+            } else if (op.kind == PlanOp::FINALIZE) {
+                if (certify) {
+                    gp::launch_margins(d_best, net->d_margins + row0, rm.Rc, net->d_flag, net->stream);
+                } else {
+                    gp::FinalizeParams fp;
+                    fp.rm = rm; fp.best = d_best;
+                    fp.lo = net->L[start].d_lo; fp.hi = net->L[start].d_hi;
+                    fp.xmax = net->L[start].d_xmax; fp.flag = net->d_flag;
+                    gp::launch_finalize(fp, net->stream);
+                }
+            }
+        }
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(net, GP_ERR_DEVICE, "kernel launch: %s", hipGetErrorString(e));
+    return GP_OK;
+}
+
+gp_status check_flag(gp_net* net) {
+    int flag = 0;
+    HIP_TRY(net, hipMemcpyAsync(&flag, net->d_flag, sizeof(int), hipMemcpyDeviceToHost, net->stream));
+    HIP_TRY(net, hipStreamSynchronize(net->stream));
+    if (flag) return fail(net, GP_ERR_NONFINITE, "NaN or Inf in the inputs or in computed bounds");
+    return GP_OK;
+}
+
+// all layers after the input box is on the device
+gp_status analyze_layers(gp_net* net, int batch) {
+    int nl = (int)net->L.size();
+    for (int i = 1; i < nl; ++i) {
+        Layer& l = net->L[i];
+        if (l.d_xmax) gp::launch_fill_f64(l.d_xmax, 0.0, 1, net->stream);
+        if (l.type == T_RELU) {
+            gp::ReluParams rp;
+            rp.plo = net->L[l.a].d_lo; rp.phi = net->L[l.a].d_hi;
+            rp.lo = l.d_lo; rp.hi = l.d_hi; rp.gam = l.d_gam; rp.lam = l.d_lam; rp.del = l.d_del;
+            rp.xmax = l.d_xmax; rp.flag = net->d_flag;
+            rp.total = l.n * batch;
+            gp::launch_relu(rp, net->stream);
+        } else if (l.need_bounds) {
+            Plan* pl;
+            gp_status st = get_plan(net, i, &pl);
+            if (st != GP_OK) return st;
+            st = run_plan(net, *pl, i, false, batch);
+            if (st != GP_OK) return st;
+        }
+    }
+    gp_status st = check_flag(net);
+    if (st != GP_OK) return st;
+    net->analyzed = true;
+    return GP_OK;
+}
+
+gp_status begin_analysis(gp_net* net, int batch) {
+    if (!net) return GP_ERR_ARG;
+    if (batch <= 0) return fail(net, GP_ERR_ARG, "batch must be positive");
+    if (net->L.size() < 2) return fail(net, GP_ERR_STATE, "network has no layers");
+    net->analyzed = false;
+    gp_status st = prepare_topology(net);
+    if (st != GP_OK) return st;
+    // plan everything first so that unsupported topologies fail before any GPU work
+    for (size_t i = 1; i < net->L.size(); ++i)
+        if (net->L[i].type != T_RELU && net->L[i].need_bounds) {
+            Plan* pl;
+            st = get_plan(net, (int)i, &pl);
+            if (st != GP_OK) return st;
+        }
+    st = ensure_device(net, batch);
+    if (st != GP_OK) return st;
+    gp::launch_fill_i32(net->d_flag, 0, 1, net->stream);
+    gp::launch_fill_f64(net->L[0].d_xmax, 0.0, 1, net->stream);
+    return GP_OK;
+}
+
+void hwc_from_chw(const Layer& l, const float* src, double* dst) {
+    long long hw = (long long)l.H * l.W;
+    for (long long pix = 0; pix < hw; ++pix)
+        for (int c = 0; c < l.C; ++c) dst[pix * l.C + c] = (double)src[c * hw + pix];
+}
+
+}  // namespace
+
+// ================================================================================================
+extern "C" {
+
+const char* gp_version(void) { return "gpupoly-hip 0.1 (gfx950)"; }
+
+gp_status gp_net_create(int32_t c, int32_t h, int32_t w, gp_net** out) {
+    if (!out) return GP_ERR_ARG;
+    *out = nullptr;
+    if (c <= 0 || h <= 0 || w <= 0) return GP_ERR_ARG;
+    if ((long long)c * h * w > (1LL << 30)) return GP_ERR_SHAPE;
+    gp_net* net = new (std::nothrow) gp_net();
+    if (!net) return GP_ERR_NOMEM;
+    Layer in;
+    in.type = T_INPUT; in.C = c; in.H = h; in.W = w; in.n = (long long)c * h * w;
+    net->L.push_back(in);
+    *out = net;
+    return GP_OK;
+}
+
+void gp_net_destroy(gp_net* net) {
+    if (!net) return;
+    for (auto& l : net->L) {
+        free_layer_bounds(l);
+        dfree(l.d_wt); dfree(l.d_beff);
+    }
+    dfree(net->d_flag); dfree(net->d_labels); dfree(net->d_margins); dfree(net->d_centers);
+    dfree(net->ws_own);
+    delete net;
+}
+
+static gp_status check_new_layer(gp_net* net, int32_t in_layer, int32_t* layer_id) {
+    if (!net) return GP_ERR_ARG;
+    if (!layer_id) return fail(net, GP_ERR_ARG, "layer_id is null");
+    if (in_layer < 0 || in_layer >= (int)net->L.size()) return fail(net, GP_ERR_ARG, "layer %d does not exist", in_layer);
+    return GP_OK;
+}
+
+static void topology_changed(gp_net* net) {
+    net->topo_ready = false;
+    net->analyzed = false;
+    net->weights_uploaded = false;
+    if (net->batch) {
+        for (auto& l : net->L) free_layer_bounds(l);
+        for (auto& l : net->L) { dfree(l.d_beff); l.d_beff = nullptr; }
+        net->batch = 0;
+    }
+}
+
+gp_status gp_add_dense(gp_net* net, int32_t in_layer, int32_t out_dim, const float* W, const float* b,
+                       int32_t* layer_id) {
+    gp_status st = check_new_layer(net, in_layer, layer_id);
+    if (st != GP_OK) return st;
+    if (out_dim <= 0 || !W) return fail(net, GP_ERR_ARG, "dense: bad out_dim or null weights");
+    const Layer& p = net->L[in_layer];
+    const long long n_in = p.n;
+    if (n_in * (long long)out_dim > (1LL << 31)) return fail(net, GP_ERR_SHAPE, "dense layer too large");
+    if (!all_finite(W, (size_t)n_in * out_dim) || (b && !all_finite(b, out_dim)))
+        return fail(net, GP_ERR_NONFINITE, "dense: NaN/Inf in weights");
+    Layer l;
+    l.type = T_DENSE; l.a = in_layer; l.C = out_dim; l.H = 1; l.W = 1; l.n = out_dim;
+    l.wt_host.resize((size_t)n_in * out_dim);
+    const long long hw = (long long)p.H * p.W;
+    double rowabs = 0;
+    for (int o = 0; o < out_dim; ++o) {
+        double s = 0;
+        const float* src = W + (size_t)o * n_in;
+        float* dst = l.wt_host.data() + (size_t)o * n_in;
+        for (long long pix = 0; pix < hw; ++pix)
+            for (int c = 0; c < p.C; ++c) {
+                float v = src[c * hw + pix];
+                dst[pix * p.C + c] = v;
+                s += std::fabs((double)v);
+            }
+        rowabs = std::max(rowabs, s);
+    }
+    l.rowabs = rowabs * (1.0 + 1e-9);
+    l.bias_host.assign(out_dim, 0.f);
+    if (b) std::copy(b, b + out_dim, l.bias_host.begin());
+    net->L.push_back(std::move(l));
+    topology_changed(net);
+    *layer_id = (int)net->L.size() - 1;
+    return GP_OK;
+}
+
+gp_status gp_add_conv2d(gp_net* net, int32_t in_layer, int32_t c_out, int32_t kh, int32_t kw, int32_t stride_h,
+                        int32_t stride_w, int32_t pad_h, int32_t pad_w, const float* W, const float* b,
+                        int32_t* layer_id) {
+    gp_status st = check_new_layer(net, in_layer, layer_id);
+    if (st != GP_OK) return st;
+    if (c_out <= 0 || kh <= 0 || kw <= 0 || stride_h <= 0 || stride_w <= 0 || pad_h < 0 || pad_w < 0 || !W)
+        return fail(net, GP_ERR_ARG, "conv2d: bad argument");
+    const Layer& p = net->L[in_layer];
+    if (p.H + 2 * pad_h < kh || p.W + 2 * pad_w < kw) return fail(net, GP_ERR_SHAPE, "conv2d: kernel larger than padded input");
+    if (pad_h >= kh || pad_w >= kw) return fail(net, GP_ERR_SHAPE, "conv2d: padding must be smaller than the kernel");
+    const int ho = (p.H + 2 * pad_h - kh) / stride_h + 1, wo = (p.W + 2 * pad_w - kw) / stride_w + 1;
+    const size_t nw = (size_t)c_out * p.C * kh * kw;
+    if (!all_finite(W, nw) || (b && !all_finite(b, c_out))) return fail(net, GP_ERR_NONFINITE, "conv2d: NaN/Inf in weights");
+    if ((long long)c_out * ho * wo > (1LL << 30)) return fail(net, GP_ERR_SHAPE, "conv2d: layer too large");
+    Layer l;
+    l.type = T_CONV; l.a = in_layer; l.C = c_out; l.H = ho; l.W = wo; l.n = (long long)c_out * ho * wo;
+    l.kh = kh; l.kw = kw; l.sh = stride_h; l.sw = stride_w; l.ph = pad_h; l.pw = pad_w;
+    l.wt_host.resize(nw);
+    double rowabs = 0;
+    for (int co = 0; co < c_out; ++co) {
+        double s = 0;
+        for (int ci = 0; ci < p.C; ++ci)
+            for (int f = 0; f < kh; ++f)
+                for (int g = 0; g < kw; ++g) {
+                    float v = W[(((size_t)co * p.C + ci) * kh + f) * kw + g];
+                    l.wt_host[((size_t)(f * kw + g) * c_out + co) * p.C + ci] = v;
+                    s += std::fabs((double)v);
+                }
+        rowabs = std::max(rowabs, s);
+    }
+    l.rowabs = rowabs * (1.0 + 1e-9);
+    l.bias_host.assign(c_out, 0.f);
+    if (b) std::copy(b, b + c_out, l.bias_host.begin());
+    net->L.push_back(std::move(l));
+    topology_changed(net);
+    *layer_id = (int)net->L.size() - 1;
+    return GP_OK;
+}
+
+gp_status gp_add_relu(gp_net* net, int32_t in_layer, int32_t* layer_id) {
+    gp_status st = check_new_layer(net, in_layer, layer_id);
+    if (st != GP_OK) return st;
+    const Layer& p = net->L[in_layer];
+    Layer l;
+    l.type = T_RELU; l.a = in_layer; l.C = p.C; l.H = p.H; l.W = p.W; l.n = p.n;
+    net->L.push_back(l);
+    topology_changed(net);
+    *layer_id = (int)net->L.size() - 1;
+    return GP_OK;
+}
+
+gp_status gp_add_residual(gp_net* net, int32_t layer_a, int32_t layer_b, int32_t* layer_id) {
+    gp_status st = check_new_layer(net, layer_a, layer_id);
+    if (st != GP_OK) return st;
+    if (layer_b < 0 || layer_b >= (int)net->L.size()) return fail(net, GP_ERR_ARG, "layer %d does not exist", layer_b);
+    const Layer &pa = net->L[layer_a], &pb = net->L[layer_b];
+    if (pa.C != pb.C || pa.H != pb.H || pa.W != pb.W) return fail(net, GP_ERR_SHAPE, "residual: shapes differ");
+    Layer l;
+    l.type = T_ADD; l.a = layer_a; l.b = layer_b; l.C = pa.C; l.H = pa.H; l.W = pa.W; l.n = pa.n;
+    net->L.push_back(l);
+    topology_changed(net);
+    *layer_id = (int)net->L.size() - 1;
+    return GP_OK;
+}
+
+gp_status gp_request_bounds(gp_net* net, int32_t layer_id) {
+    if (!net) return GP_ERR_ARG;
+    if (layer_id <= 0 || layer_id >= (int)net->L.size()) return fail(net, GP_ERR_ARG, "layer %d does not exist", layer_id);
+    if (net->L[layer_id].type == T_RELU) return GP_OK;
+    net->L[layer_id].req_bounds = true;
+    topology_changed(net);
+    return GP_OK;
+}
+
+gp_status gp_set_stream(gp_net* net, void* hip_stream) {
+    if (!net) return GP_ERR_ARG;
+    net->stream = (hipStream_t)hip_stream;
+    return GP_OK;
+}
+
+gp_status gp_workspace_size(const gp_net* cnet, int32_t batch, int64_t* min_bytes, int64_t* full_bytes) {
+    gp_net* net = const_cast<gp_net*>(cnet);
+    if (!net || batch <= 0 || !min_bytes || !full_bytes) return GP_ERR_ARG;
+    gp_status st = prepare_topology(net);
+    if (st != GP_OK) return st;
+    long long mn = 0, full = 0;
+    for (size_t i = 1; i < net->L.size(); ++i) {
+        if (net->L[i].type == T_RELU || !net->L[i].need_bounds) continue;
+        Plan* pl;
+        st = get_plan(net, (int)i, &pl);
+        if (st != GP_OK) return st;
+        long long tb = task_bytes(*pl, 2);
+        mn = std::max(mn, tb + 8192);
+        full = std::max(full, tb * net->L[i].n * batch + 8192);
+    }
+    *min_bytes = mn;
+    *full_bytes = full;
+    return GP_OK;
+}
+
+gp_status gp_set_workspace(gp_net* net, void* ptr_dev, int64_t bytes) {
+    if (!net) return GP_ERR_ARG;
+    if (ptr_dev && (bytes <= 0 || ((uintptr_t)ptr_dev & 255))) return fail(net, GP_ERR_ARG, "workspace must be 256-byte aligned and non-empty");
+    net->ws_user = ptr_dev;
+    net->ws_user_bytes = ptr_dev ? bytes : 0;
+    return GP_OK;
+}
+
+gp_status gp_analyze_batch_dev(gp_net* net, int32_t batch, const float* centers_dev, float eps, float clip_lo,
+                               float clip_hi) {
+    if (!net) return GP_ERR_ARG;
+    if (!centers_dev) return fail(net, GP_ERR_ARG, "centers is null");
+    if (!(eps >= 0.f) || !std::isfinite(eps)) return fail(net, GP_ERR_ARG, "eps must be finite and >= 0");
+    if (!(clip_lo <= clip_hi)) return fail(net, GP_ERR_ARG, "clip_lo > clip_hi");
+    gp_status st = begin_analysis(net, batch);
+    if (st != GP_OK) return st;
+    const Layer& in = net->L[0];
+    gp::BoxParams bp;
+    bp.centers = centers_dev; bp.eps = eps; bp.clip_lo = clip_lo; bp.clip_hi = clip_hi;
+    bp.lo = in.d_lo; bp.hi = in.d_hi; bp.xmax = in.d_xmax; bp.flag = net->d_flag;
+    bp.C = in.C; bp.H = in.H; bp.W = in.W; bp.batch = batch;
+    gp::launch_box(bp, net->stream);
+    return analyze_layers(net, batch);
+}
+
+gp_status gp_analyze_batch(gp_net* net, int32_t batch, const float* centers, float eps, float clip_lo, float clip_hi) {
+    if (!net) return GP_ERR_ARG;
+    if (!centers) return fail(net, GP_ERR_ARG, "centers is null");
+    if (batch <= 0) return fail(net, GP_ERR_ARG, "batch must be positive");
+    const long long cnt = net->L[0].n * batch;
+    if (!all_finite(centers, (size_t)cnt)) return fail(net, GP_ERR_NONFINITE, "NaN/Inf in the centres");
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) return fail(net, GP_ERR_DEVICE, "no HIP device");
+    if (net->d_centers_cap < cnt) {
+        dfree(net->d_centers); net->d_centers = nullptr; net->d_centers_cap = 0;
+        HIP_TRY(net, hipMalloc((void**)&net->d_centers, cnt * sizeof(float)));
+        net->d_centers_cap = cnt;
+    }
+    HIP_TRY(net, hipMemcpyAsync(net->d_centers, centers, cnt * sizeof(float), hipMemcpyHostToDevice, net->stream));
+    HIP_TRY(net, hipStreamSynchronize(net->stream));
+    return gp_analyze_batch_dev(net, batch, net->d_centers, eps, clip_lo, clip_hi);
+}
+
+gp_status gp_analyze(gp_net* net, const float* center, float eps, float clip_lo, float clip_hi) {
+    return gp_analyze_batch(net, 1, center, eps, clip_lo, clip_hi);
+}
+
+gp_status gp_analyze_box(gp_net* net, const float* lo, const float* hi) {
+    if (!net) return GP_ERR_ARG;
+    if (!lo || !hi) return fail(net, GP_ERR_ARG, "box is null");
+    const Layer& in = net->L[0];
+    for (long long i = 0; i < in.n; ++i) {
+        if (!std::isfinite(lo[i]) || !std::isfinite(hi[i])) return fail(net, GP_ERR_NONFINITE, "NaN/Inf in the box");
+        if (lo[i] > hi[i]) return fail(net, GP_ERR_ARG, "box: lo > hi at %lld", i);
+    }
+    gp_status st = begin_analysis(net, 1);
+    if (st != GP_OK) return st;
+    std::vector<double> l(in.n), h(in.n);
+    hwc_from_chw(in, lo, l.data());
+    hwc_from_chw(in, hi, h.data());
+    double xmax = 0;
+    for (long long i = 0; i < in.n; ++i) xmax = std::max(xmax, std::max(std::fabs(l[i]), std::fabs(h[i])));
+    HIP_TRY(net, hipMemcpyAsync(in.d_lo, l.data(), in.n * sizeof(double), hipMemcpyHostToDevice, net->stream));
+    HIP_TRY(net, hipMemcpyAsync(in.d_hi, h.data(), in.n * sizeof(double), hipMemcpyHostToDevice, net->stream));
+    HIP_TRY(net, hipMemcpyAsync(in.d_xmax, &xmax, sizeof(double), hipMemcpyHostToDevice, net->stream));
+    HIP_TRY(net, hipStreamSynchronize(net->stream));
+    return analyze_layers(net, 1);
+}
+
+gp_status gp_get_bounds_f64(const gp_net* net, int32_t layer_id, int32_t batch_index, double* lower, double* upper) {
+    if (!net) return GP_ERR_ARG;
+    if (!lower || !upper) return fail(net, GP_ERR_ARG, "output pointer is null");
+    if (layer_id < 0 || layer_id >= (int)net->L.size()) return fail(net, GP_ERR_ARG, "layer %d does not exist", layer_id);
+    if (!net->analyzed) return fail(net, GP_ERR_STATE, "no successful analysis yet");
+    if (batch_index < 0 || batch_index >= net->batch) return fail(net, GP_ERR_ARG, "batch index out of range");
+    const Layer& l = net->L[layer_id];
+    if (!has_bounds(net, layer_id) || !l.d_lo) return fail(net, GP_ERR_STATE, "layer %d has no bounds (see gp_request_bounds)", layer_id);
+    std::vector<double> lo(l.n), hi(l.n);
+    HIP_TRY(net, hipMemcpy(lo.data(), l.d_lo + (size_t)batch_index * l.n, l.n * sizeof(double), hipMemcpyDeviceToHost));
+    HIP_TRY(net, hipMemcpy(hi.data(), l.d_hi + (size_t)batch_index * l.n, l.n * sizeof(double), hipMemcpyDeviceToHost));
+    const long long hw = (long long)l.H * l.W;
+    for (long long pix = 0; pix < hw; ++pix)
+        for (int c = 0; c < l.C; ++c) {
+            lower[c * hw + pix] = lo[pix * l.C + c];
+            upper[c * hw + pix] = hi[pix * l.C + c];
+        }
+    return GP_OK;
+}
+
+gp_status gp_get_bounds_batch(const gp_net* net, int32_t layer_id, int32_t batch_index, float* lower, float* upper) {
+    if (!net) return GP_ERR_ARG;
+    if (!lower || !upper) return fail(net, GP_ERR_ARG, "output pointer is null");
+    if (layer_id < 0 || layer_id >= (int)net->L.size()) return fail(net, GP_ERR_ARG, "layer %d does not exist", layer_id);
+    std::vector<double> lo(net->L[layer_id].n), hi(net->L[layer_id].n);
+    gp_status st = gp_get_bounds_f64(net, layer_id, batch_index, lo.data(), hi.data());
+    if (st != GP_OK) return st;
+    for (size_t i = 0; i < lo.size(); ++i) {
+        float f = (float)lo[i];
+        if ((double)f > lo[i]) f = std::nextafterf(f, -INFINITY);
+        lower[i] = f;
+        f = (float)hi[i];
+        if ((double)f < hi[i]) f = std::nextafterf(f, INFINITY);
+        upper[i] = f;
+    }
+    return GP_OK;
+}
+
+gp_status gp_get_bounds(const gp_net* net, int32_t layer_id, float* lower, float* upper) {
+    return gp_get_bounds_batch(net, layer_id, 0, lower, upper);
+}
+
+gp_status gp_get_relu_lambda(const gp_net* net, int32_t layer_id, int32_t batch_index, int8_t* lam) {
+    if (!net) return GP_ERR_ARG;
+    if (!lam) return fail(net, GP_ERR_ARG, "output pointer is null");
+    if (layer_id <= 0 || layer_id >= (int)net->L.size() || net->L[layer_id].type != T_RELU)
+        return fail(net, GP_ERR_ARG, "layer %d is not a ReLU layer", layer_id);
+    if (!net->analyzed) return fail(net, GP_ERR_STATE, "no successful analysis yet");
+    if (batch_index < 0 || batch_index >= net->batch) return fail(net, GP_ERR_ARG, "batch index out of range");
+    const Layer& l = net->L[layer_id];
+    std::vector<float> v(l.n);
+    HIP_TRY(net, hipMemcpy(v.data(), l.d_lam + (size_t)batch_index * l.n, l.n * sizeof(float), hipMemcpyDeviceToHost));
+    const long long hw = (long long)l.H * l.W;
+    for (long long pix = 0; pix < hw; ++pix)
+        for (int c = 0; c < l.C; ++c) lam[c * hw + pix] = v[pix * l.C + c] != 0.f ? 1 : 0;
+    return GP_OK;
+}
+
+gp_status gp_certify_batch(gp_net* net, const int32_t* labels, int32_t* verified, float* margins) {
+    if (!net) return GP_ERR_ARG;
+    if (!labels || !margins) return fail(net, GP_ERR_ARG, "null pointer");
+    if (!net->analyzed) return fail(net, GP_ERR_STATE, "no successful analysis yet");
+    const int last = (int)net->L.size() - 1;
+    const Layer& lo = net->L[last];
+    if (lo.type == T_RELU) return fail(net, GP_ERR_UNSUPPORTED, "the last layer must be affine or a sum");
+    if (lo.n < 2) return fail(net, GP_ERR_SHAPE, "need at least two outputs");
+    for (int b = 0; b < net->batch; ++b)
+        if (labels[b] < 0 || labels[b] >= lo.n) return fail(net, GP_ERR_ARG, "label out of range");
+    if (!net->cert_plan.valid) {
+        gp_status st = build_plan(net, last, true, net->cert_plan);
+        if (st != GP_OK) return st;
+    }
+    HIP_TRY(net, hipMemcpyAsync(net->d_labels, labels, sizeof(int) * net->batch, hipMemcpyHostToDevice, net->stream));
+    HIP_TRY(net, hipStreamSynchronize(net->stream));
+    gp::launch_fill_i32(net->d_flag, 0, 1, net->stream);
+    gp_status st = run_plan(net, net->cert_plan, last, true, net->batch);
+    if (st != GP_OK) return st;
+    st = check_flag(net);
+    if (st != GP_OK) return st;
+    const long long cnt = (lo.n - 1) * net->batch;
+    HIP_TRY(net, hipMemcpy(margins, net->d_margins, cnt * sizeof(float), hipMemcpyDeviceToHost));
+    if (verified)
+        for (int b = 0; b < net->batch; ++b) {
+            int ok = 1;
+            for (long long j = 0; j < lo.n - 1; ++j)
+                if (!(margins[b * (lo.n - 1) + j] > 0.f)) ok = 0;
+            verified[b] = ok;
+        }
+    return GP_OK;
+}
+
+gp_status gp_certify(gp_net* net, int32_t label, int32_t* verified, float* margins) {
+    if (!net) return GP_ERR_ARG;
+    if (net->analyzed && net->batch != 1) return fail(net, GP_ERR_STATE, "the last analysis was a batch: use gp_certify_batch");
+    return gp_certify_batch(net, &label, verified, margins);
+}
+
+gp_status gp_debug_plan(const gp_net* cnet, int32_t layer_id, int32_t* steps, int32_t max_steps, int32_t* n_steps) {
+    gp_net* net = const_cast<gp_net*>(cnet);
+    if (!net || !n_steps) return GP_ERR_ARG;
+    if (layer_id <= 0 || layer_id >= (int)net->L.size() || net->L[layer_id].type == T_RELU)
+        return fail(net, GP_ERR_ARG, "layer %d cannot start a back-substitution", layer_id);
+    gp_status st = prepare_topology(net);
+    if (st != GP_OK) return st;
+    Plan pl;
+    st = build_plan(net, layer_id, false, pl);
+    if (st != GP_OK) return st;
+    int n = (int)pl.steps.size() / 8;
+    *n_steps = n;
+    if (steps)
+        for (int i = 0; i < std::min(n, (int)max_steps) * 8; ++i) steps[i] = pl.steps[i];
+    return GP_OK;
+}
+
+int32_t gp_num_layers(const gp_net* net) { return net ? (int32_t)net->L.size() : -1; }
+int32_t gp_layer_size(const gp_net* net, int32_t layer_id) {
+    if (!net || layer_id < 0 || layer_id >= (int)net->L.size()) return -1;
+    return (int32_t)net->L[layer_id].n;
+}
+const char* gp_last_error(const gp_net* net) { return net ? net->err.c_str() : "null net"; }
+
+// test hook: D[16][16] = A[16][K] * B[K][16] with the float64 MFMA instruction (device pointers)
+gp_status gp_debug_mfma_f64(const double* A_dev, const double* B_dev, double* D_dev, int32_t K, void* hip_stream) {
+    if (!A_dev || !B_dev || !D_dev || K <= 0 || (K & 3)) return GP_ERR_ARG;
+    gp::launch_mfma_check(A_dev, B_dev, D_dev, K, (hipStream_t)hip_stream);
+    return hipGetLastError() == hipSuccess ? GP_OK : GP_ERR_DEVICE;
+}
+
+}  // extern "C"

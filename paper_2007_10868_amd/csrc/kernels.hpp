@@ -1,0 +1,116 @@
+// Plain-data kernel parameter blocks and launchers of the back-substitution kernels (gfx950).
+//
+// Vocabulary (paper Sections 2, 3.1, 4.3):
+//   row     one back-substitution task: the upper-bound expression of +x_i or of -x_i for a neuron
+//           x_i of the start layer (a lower bound of x_i is minus an upper bound of -x_i, so every
+//           row is an upper-bound expression and all kernels have a single sign convention);
+//   block   a row's dense coefficient cuboid M^k(x_i) over its dependence window in layer k,
+//           stored [window_y][window_x][channel] in float32, channel innermost;
+//   window  the dependence set D^{l-k}(x_i) of Section 4.3, clipped to the layer: every row of a
+//           step has the same window size, and an origin that depends on the row's position.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gp {
+
+// which neurons the rows of a launch stand for
+struct RowMap {
+    long long row0;  // first task of this chunk, counted over batch * n_start
+    int Rc;          // tasks in the chunk
+    int nsign;       // 2: rows [0,Rc) are +x, rows [Rc,2Rc) are -x;  1: one row per task
+    int n_start;     // tasks per box of the batch
+    int Hs, Ws, Cs;  // start layer dims; task i sits at position ((i/Cs)/Ws, (i/Cs)%Ws), channel i%Cs
+};
+
+struct BlockDesc {
+    const float* data;   // [nrows][wy][wx][C]
+    int H, W, C;         // dims of the layer the block ranges over
+    int wy, wx;          // window size (already clipped to the layer)
+    int Sy, Sx, Py, Px;  // window origin of a row at (ys,xs): clamp(S*ys - P, 0, H - wy)  (eqs. 6-9 with padding)
+    const float* gam;    // pending ReLU substitution: coefficient a stands for a*(a>=0 ? gam : lam);
+    const float* lam;    //   [batch][H*W*C]; null when none
+};
+
+struct CrossParams {       // one back-substitution step through an affine layer (Algorithm 1 per row)
+    BlockDesc in;          // block over the layer's OUTPUT neurons
+    const float* wt;       // [kh*kw][C_out_of_layer = in.C][Co]  (Co innermost)
+    int kh, kw, sh, sw, ph, pw;
+    float* out;            // new block over the layer's INPUT neurons
+    int Ho, Wo, Co;        // dims of the input layer
+    int owy, owx, oSy, oSx, oPy, oPx;
+    BlockDesc add;         // optional block over the same input layer to be summed in (residual join)
+    RowMap rm;
+    int nrows;
+};
+
+struct ScanParams {        // per-row reductions over a block
+    BlockDesc blk;
+    RowMap rm;
+    int nrows;
+    int batch_stride;      // H*W*C
+    const double* lo;      // intervals of the block's layer [batch][n]; null: no candidate, no rounding term
+    const double* hi;
+    const float* gam;      // relaxation that the NEXT step applies to this block (its layer is a ReLU); null if none
+    const float* lam;
+    const double* del;
+    const double* beff;    // [C] bias of the affine layer(s) crossed next; null if none
+    double e1_a, e1_b;     // accumulation-error constants of the next crossing(s), times *xmax_a / *xmax_b
+    const double* xmax_a;
+    const double* xmax_b;
+    double round_coef;     // relative rounding error of the stored coefficients (0 for exact blocks)
+    int do_consts;         // add the constants of the next step (relaxation intercepts, bias) to c
+    int update_best;       // the expression ranges over this layer only: fold the candidate into best
+    double* c;             // per-row constant
+    double* err;           // per-row accumulated slack (>= 0)
+    double* best;          // per-row best candidate so far
+};
+
+struct InitParams {
+    float* out;            // identity block over the start layer: [nrows][1][1][Cs]  (or full layer for certify)
+    RowMap rm;
+    int nrows;
+    int nelem;             // elements per row
+    const int* labels;     // certify only: [batch]
+    int certify;           // 0: one-hot +/-1 at the row's own channel; 1: e_j - e_label over the full layer
+    int H, W, C;           // certify: dims of the last layer (to map C,H,W numbering to the block order)
+    double* c; double* err; double* best;
+};
+
+struct FinalizeParams {
+    RowMap rm;
+    const double* best;
+    double* lo; double* hi;   // [batch][n_start] of the start layer
+    double* xmax;             // running max of |bounds| of that layer
+    int* flag;                // set to 1 on NaN/Inf
+};
+
+struct ReluParams {
+    const double* plo; const double* phi;   // predecessor intervals [total]
+    double* lo; double* hi;                 // this layer's intervals
+    float* gam; float* lam; double* del;
+    double* xmax; int* flag;
+    long long total;                        // batch * n
+};
+
+struct BoxParams {
+    const float* centers;   // [batch][n] in C,H,W order (device)
+    float eps, clip_lo, clip_hi;
+    double* lo; double* hi;  // [batch][n] in H,W,C order
+    double* xmax; int* flag;
+    int C, H, W, batch;
+};
+
+void launch_cross(const CrossParams& p, hipStream_t s);
+void launch_scan(const ScanParams& p, hipStream_t s);
+void launch_init(const InitParams& p, hipStream_t s);
+void launch_finalize(const FinalizeParams& p, hipStream_t s);
+void launch_relu(const ReluParams& p, hipStream_t s);
+void launch_box(const BoxParams& p, hipStream_t s);
+void launch_fill_f64(double* p, double v, long long n, hipStream_t s);
+void launch_fill_i32(int* p, int v, long long n, hipStream_t s);
+void launch_margins(const double* best, float* margins, long long n, int* flag, hipStream_t s);
+// float64 MFMA self-check: D[16][16] = A[16][K] * B[K][16], same instruction and layout as the crossing kernel
+void launch_mfma_check(const double* A, const double* B, double* D, int K, hipStream_t s);
+
+}  // namespace gp

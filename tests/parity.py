@@ -1,0 +1,88 @@
+"""Shared harness of the GPU parity tests: run the HIP library and the CPU oracle on the same
+seeded arrays and compare every reported interval."""
+from __future__ import annotations
+
+import numpy as np
+
+import workloads as wl
+from oracle import OracleNet
+
+REL_TOL = 1e-3          # a GPU bound may be looser than the oracle's by at most REL_TOL * (1 + |b|)
+CONTAIN_TOL = 2e-6      # and must contain it, up to the effect of float32-rounded relaxation slopes
+
+
+def analysed_layers(net: wl.Net):
+    feeds = {L["src"] for L in net.layers if L["type"] == "relu"}
+    return [i for i, L in enumerate(net.layers, start=1)
+            if L["type"] == "relu" or i in feeds or i == len(net.layers)]
+
+
+def make_gpu(net: wl.Net):
+    from paper_2007_10868_amd import Net
+    g = Net(*net.input_shape)
+    wl.build_into(net, g)
+    return g
+
+
+def make_oracle(net: wl.Net, **opts):
+    o = OracleNet(*net.input_shape)
+    wl.build_into(net, o)
+    if opts:
+        o.set_options(**opts)
+    return o
+
+
+def oracle_with_gpu_ties(net: wl.Net, o: OracleNet, g, center, eps, batch_index=0, clip=(0.0, 1.0), tie=1e-6):
+    """Oracle analysis layer by layer.  The choice lam in {0,1} of the lower relaxation is the only
+    discontinuity of the analysis: where the oracle's own interval is within `tie` of the switching
+    point u = -l, it is told to take the GPU's choice.  Returns the number of such neurons."""
+    o.set_ball(center, eps, clip[0], clip[1])
+    forced = 0
+    for lid in range(1, o.num_layers):
+        L = net.layers[lid - 1]
+        if L["type"] == "relu":
+            lo, hi = o.get_bounds(L["src"])
+            near = (lo < 0) & (hi > 0) & (np.abs(hi + lo) <= tie * (hi - lo))
+            if near.any():
+                lam = g.get_relu_lambda(lid, batch_index)
+                o.set_lambda_override(lid, np.where(near, lam, -1).astype(np.int8))
+                forced += int(near.sum())
+            else:
+                o.set_lambda_override(lid, None)
+            o.analyze_layer(lid)
+        elif lid in analysed_layers(net):
+            o.analyze_layer(lid)
+    return forced
+
+
+def compare_layer(glo, ghi, olo, ohi, what=""):
+    """Returns (max looseness / allowed, max containment violation / scale); asserts the bar."""
+    glo, ghi = np.asarray(glo, np.float64), np.asarray(ghi, np.float64)
+    assert np.all(np.isfinite(glo)) and np.all(np.isfinite(ghi)), what
+    s_lo, s_hi = 1.0 + np.abs(olo), 1.0 + np.abs(ohi)
+    loose = max(np.max((olo - glo) / s_lo), np.max((ghi - ohi) / s_hi))
+    viol = max(np.max((glo - olo) / s_lo), np.max((ohi - ghi) / s_hi))
+    assert loose <= REL_TOL, f"{what}: GPU bound looser than oracle by {loose:.3e} (relative), allowed {REL_TOL}"
+    assert viol <= CONTAIN_TOL, f"{what}: GPU bound inside the oracle bound by {viol:.3e} (relative)"
+    return loose / REL_TOL, viol
+
+
+def compare_all(net, g, o, batch_index=0, what="", f64=True):
+    worst = 0.0
+    for lid in analysed_layers(net):
+        olo, ohi = o.get_bounds(lid)
+        glo, ghi = (g.get_bounds_f64 if f64 else g.get_bounds)(lid, batch_index)
+        r, _ = compare_layer(glo, ghi, olo, ohi, f"{what} layer {lid}")
+        worst = max(worst, r)
+    return worst
+
+
+def check_samples_inside(net, g, lo0, hi0, n, rng, batch_index=0, what=""):
+    from helpers import forward, sample_box
+    X = sample_box(lo0, hi0, n, rng)
+    vals = forward(net, X)
+    for lid in analysed_layers(net):
+        glo, ghi = g.get_bounds(lid, batch_index)
+        v = vals[lid]
+        assert np.all(v.min(0) >= glo.astype(np.float64)), f"{what} layer {lid}: sampled output below the lower bound"
+        assert np.all(v.max(0) <= ghi.astype(np.float64)), f"{what} layer {lid}: sampled output above the upper bound"
