@@ -115,10 +115,22 @@ gp_status gp_certify_batch(gp_net* net, const int32_t* labels, int32_t* verified
 gp_status gp_debug_plan(const gp_net* net, int32_t layer_id, int32_t* steps, int32_t max_steps,
                         int32_t* n_steps);
 
+/* Per-kernel timing with HIP events on the net's stream.  While enabled, every launch of the two
+ * back-substitution kernels is bracketed by events: index 0 = affine crossing (the product
+ * M^{k-1} = M^k F^k of Section 2 / Algorithm 1), index 1 = per-row scan (candidate bound,
+ * relaxation constants).  gp_profile_read synchronises, returns for each of the two kernels the
+ * number of launches, their summed duration in ms, and the algorithmic flops and bytes of the
+ * steps they carried out, then resets the counters.  All four arrays have 2 entries. */
+gp_status gp_profile_enable(gp_net* net, int32_t on);
+gp_status gp_profile_read(gp_net* net, int64_t* launches, double* total_ms, double* alg_flop, double* alg_bytes);
+
+/* Self-check of the matrix instruction the crossing kernel relies on: D[16][16] = A[16][K] * B[K][16]
+ * in float64 MFMA (K a multiple of 4; A, B, D row-major in device memory), enqueued on hip_stream.
+ * The rounding slack of a crossing assumes |D - exact| <= (K+8) * 2^-50 * sum|terms|; tests check it. */
+gp_status gp_debug_mfma_f64(const double* A_dev, const double* B_dev, double* D_dev, int32_t K, void* hip_stream);
+
 int32_t gp_num_layers(const gp_net* net);
 int32_t gp_layer_size(const gp_net* net, int32_t layer_id);
-/* Seconds of GPU time of the last analyse call's back-substitution kernels is not tracked here;
- * use HIP events on the stream given to gp_set_stream. */
 const char* gp_last_error(const gp_net* net);
 const char* gp_version(void);
 

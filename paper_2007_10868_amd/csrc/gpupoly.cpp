@@ -90,6 +90,11 @@ struct gp_net {
     float* d_centers = nullptr;
     long long d_centers_cap = 0;
     int device = -1;
+    // optional per-kernel timing (gp_profile_*): index 0 = affine crossing, 1 = row scan
+    bool prof_on = false;
+    std::vector<hipEvent_t> prof_ev[2];     // start/stop pairs
+    size_t prof_used[2] = {0, 0};
+    double prof_flop[2] = {0, 0}, prof_bytes[2] = {0, 0};
 };
 
 namespace {
@@ -380,7 +385,7 @@ gp_status ensure_device(gp_net* net, int batch) {
             if (has_bounds(net, (int)i)) {
                 HIP_TRY(net, hipMalloc((void**)&l.d_lo, cnt * sizeof(double)));
                 HIP_TRY(net, hipMalloc((void**)&l.d_hi, cnt * sizeof(double)));
-                HIP_TRY(net, hipMalloc((void**)&l.d_xmax, sizeof(double)));
+                HIP_TRY(net, hipMalloc((void**)&l.d_xmax, sizeof(double) * batch));
             }
             if (l.type == T_RELU) {
                 HIP_TRY(net, hipMalloc((void**)&l.d_gam, cnt * sizeof(float)));
@@ -428,6 +433,19 @@ gp::BlockDesc make_desc(const gp_net* net, const float* data, const Geom& g, int
     b.gam = relax >= 0 ? net->L[relax].d_gam : nullptr;
     b.lam = relax >= 0 ? net->L[relax].d_lam : nullptr;
     return b;
+}
+
+void prof_mark(gp_net* net, int kind, bool stop) {
+    if (!net->prof_on) return;
+    std::vector<hipEvent_t>& ev = net->prof_ev[kind];
+    size_t& used = net->prof_used[kind];
+    if (used == ev.size()) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) return;
+        ev.push_back(e);
+    }
+    (void)stop;
+    (void)hipEventRecord(ev[used++], net->stream);
 }
 
 // run one plan over all its tasks, chunk by chunk (Section 4.2 "Memory management")
@@ -504,7 +522,10 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                 sp.do_consts = op.do_consts ? 1 : 0;
                 sp.update_best = op.update_best ? 1 : 0;
                 sp.c = d_c; sp.err = d_err; sp.best = d_best;
+                prof_mark(net, 1, false);
                 gp::launch_scan(sp, net->stream);
+                prof_mark(net, 1, true);
+                if (net->prof_on) net->prof_bytes[1] += 4.0 * nrows * (double)block_elems(op.g_in, l);
             } else if (op.kind == PlanOp::CROSS) {
                 const Layer& a = net->L[op.layer_in];
                 const Layer& p = net->L[op.layer_out];
@@ -531,7 +552,20 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                     if (op.slot_add >= 0) cp.add = make_desc(net, slot_ptr(op.slot_add), op.g_add, op.layer_out, op.relax_add);
                 }
                 cp.rm = rm; cp.nrows = nrows;
+                prof_mark(net, 0, false);
                 gp::launch_cross(cp, net->stream);
+                prof_mark(net, 0, true);
+                if (net->prof_on) {
+                    // algorithmic work of the step (Section 2: one product M^k * F^k): every coefficient of the
+                    // row's block meets every filter tap and every input channel once; the one-hot start block
+                    // of a row is bookkeeping, not part of the method, and counts as zero
+                    const double in_el = (double)block_elems(op.g_in, a), out_el = (double)block_elems(op.g_out, p);
+                    const double taps = (a.type == T_DENSE) ? 1.0 : (double)a.kh * a.kw;
+                    const double cin = (a.type == T_DENSE) ? (double)p.n : (double)p.C;
+                    const bool first = (op.layer_in == start);
+                    if (!first) net->prof_flop[0] += 2.0 * nrows * in_el * taps * cin;
+                    net->prof_bytes[0] += 4.0 * nrows * (in_el + out_el) + 4.0 * (double)a.wt_host.size();
+                }
             } else if (op.kind == PlanOp::FINALIZE) {
                 if (certify) {
                     gp::launch_margins(d_best, net->d_margins + row0, rm.Rc, net->d_flag, net->stream);
@@ -563,13 +597,14 @@ gp_status analyze_layers(gp_net* net, int batch) {
     int nl = (int)net->L.size();
     for (int i = 1; i < nl; ++i) {
         Layer& l = net->L[i];
-        if (l.d_xmax) gp::launch_fill_f64(l.d_xmax, 0.0, 1, net->stream);
+        if (l.d_xmax) gp::launch_fill_f64(l.d_xmax, 0.0, batch, net->stream);
         if (l.type == T_RELU) {
             gp::ReluParams rp;
             rp.plo = net->L[l.a].d_lo; rp.phi = net->L[l.a].d_hi;
             rp.lo = l.d_lo; rp.hi = l.d_hi; rp.gam = l.d_gam; rp.lam = l.d_lam; rp.del = l.d_del;
             rp.xmax = l.d_xmax; rp.flag = net->d_flag;
             rp.total = l.n * batch;
+            rp.n = l.n;
             gp::launch_relu(rp, net->stream);
         } else if (l.need_bounds) {
             Plan* pl;
@@ -602,7 +637,7 @@ gp_status begin_analysis(gp_net* net, int batch) {
     st = ensure_device(net, batch);
     if (st != GP_OK) return st;
     gp::launch_fill_i32(net->d_flag, 0, 1, net->stream);
-    gp::launch_fill_f64(net->L[0].d_xmax, 0.0, 1, net->stream);
+    gp::launch_fill_f64(net->L[0].d_xmax, 0.0, batch, net->stream);
     return GP_OK;
 }
 
@@ -641,6 +676,8 @@ void gp_net_destroy(gp_net* net) {
     }
     dfree(net->d_flag); dfree(net->d_labels); dfree(net->d_margins); dfree(net->d_centers);
     dfree(net->ws_own);
+    for (int k = 0; k < 2; ++k)
+        for (hipEvent_t e : net->prof_ev[k]) (void)hipEventDestroy(e);
     delete net;
 }
 
@@ -827,6 +864,8 @@ gp_status gp_analyze_batch(gp_net* net, int32_t batch, const float* centers, flo
     if (!net) return GP_ERR_ARG;
     if (!centers) return fail(net, GP_ERR_ARG, "centers is null");
     if (batch <= 0) return fail(net, GP_ERR_ARG, "batch must be positive");
+    if (!(eps >= 0.f) || !std::isfinite(eps)) return fail(net, GP_ERR_ARG, "eps must be finite and >= 0");
+    if (!(clip_lo <= clip_hi)) return fail(net, GP_ERR_ARG, "clip_lo > clip_hi");
     const long long cnt = net->L[0].n * batch;
     if (!all_finite(centers, (size_t)cnt)) return fail(net, GP_ERR_NONFINITE, "NaN/Inf in the centres");
     int ndev = 0;
@@ -987,6 +1026,33 @@ int32_t gp_layer_size(const gp_net* net, int32_t layer_id) {
     return (int32_t)net->L[layer_id].n;
 }
 const char* gp_last_error(const gp_net* net) { return net ? net->err.c_str() : "null net"; }
+
+gp_status gp_profile_enable(gp_net* net, int32_t on) {
+    if (!net) return GP_ERR_ARG;
+    net->prof_on = on != 0;
+    for (int k = 0; k < 2; ++k) { net->prof_used[k] = 0; net->prof_flop[k] = net->prof_bytes[k] = 0.0; }
+    return GP_OK;
+}
+
+gp_status gp_profile_read(gp_net* net, int64_t* launches, double* total_ms, double* alg_flop, double* alg_bytes) {
+    if (!net || !launches || !total_ms || !alg_flop || !alg_bytes) return GP_ERR_ARG;
+    HIP_TRY(net, hipStreamSynchronize(net->stream));
+    for (int k = 0; k < 2; ++k) {
+        double ms = 0.0;
+        for (size_t i = 0; i + 1 < net->prof_used[k]; i += 2) {
+            float t = 0.f;
+            HIP_TRY(net, hipEventElapsedTime(&t, net->prof_ev[k][i], net->prof_ev[k][i + 1]));
+            ms += t;
+        }
+        launches[k] = (int64_t)(net->prof_used[k] / 2);
+        total_ms[k] = ms;
+        alg_flop[k] = net->prof_flop[k];
+        alg_bytes[k] = net->prof_bytes[k];
+        net->prof_used[k] = 0;
+        net->prof_flop[k] = net->prof_bytes[k] = 0.0;
+    }
+    return GP_OK;
+}
 
 // test hook: D[16][16] = A[16][K] * B[K][16] with the float64 MFMA instruction (device pointers)
 gp_status gp_debug_mfma_f64(const double* A_dev, const double* B_dev, double* D_dev, int32_t K, void* hip_stream) {

@@ -101,8 +101,11 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
         a_rbase[i] = (long long)ri.b * ((long long)p.in.H * p.in.W * Ck);
     }
 
-    double a_reg[APT][4];
-    double b_reg[BPT][4];
+    // global -> register staging holds the raw float32 words only, so that nothing depends on the
+    // loads before the MFMA loop of the current tile has been issued; conversion happens at the
+    // register -> LDS copy
+    float4 a_raw[APT], a_gam[APT], a_lam[APT];
+    float4 b_raw[BPT];
 
     auto load_tiles = [&](int it) {
         const int t = it / kchunks;
@@ -111,7 +114,9 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
         // A
 #pragma unroll
         for (int i = 0; i < APT; ++i) {
-            a_reg[i][0] = a_reg[i][1] = a_reg[i][2] = a_reg[i][3] = 0.0;
+            a_raw[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            a_gam[i] = make_float4(1.f, 1.f, 1.f, 1.f);
+            a_lam[i] = make_float4(1.f, 1.f, 1.f, 1.f);
             if (!a_ok[i]) continue;
             int yy = a_A[i] + p.ph - f, xx = a_B[i] + p.pw - g;
             if (yy < 0 || xx < 0) continue;
@@ -122,39 +127,30 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
             const int d = d0 + 4 * q;
             if (d >= Ck) continue;
             const float* src = a_base[i] + ((size_t)(yi * p.in.wx + xi) * Ck + d);
-            float v[4] = {0.f, 0.f, 0.f, 0.f};
+            const long long ridx = a_rbase[i] + ((long long)(y * p.in.W + x) * Ck + d);
             if (vecA) {
-                float4 t4 = *reinterpret_cast<const float4*>(src);
-                v[0] = t4.x; v[1] = t4.y; v[2] = t4.z; v[3] = t4.w;
+                a_raw[i] = *reinterpret_cast<const float4*>(src);
+                if (relax) {
+                    a_gam[i] = *reinterpret_cast<const float4*>(p.in.gam + ridx);
+                    a_lam[i] = *reinterpret_cast<const float4*>(p.in.lam + ridx);
+                }
             } else {
+                float v[4] = {0.f, 0.f, 0.f, 0.f}, gm[4] = {1.f, 1.f, 1.f, 1.f}, lm[4] = {1.f, 1.f, 1.f, 1.f};
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    if (d + j < Ck) v[j] = src[j];
-            }
-            if (relax) {
-                const long long ridx = a_rbase[i] + ((long long)(y * p.in.W + x) * Ck + d);
-                float gm[4] = {0.f, 0.f, 0.f, 0.f}, lm[4] = {0.f, 0.f, 0.f, 0.f};
-                if (vecA) {
-                    float4 g4 = *reinterpret_cast<const float4*>(p.in.gam + ridx);
-                    float4 l4 = *reinterpret_cast<const float4*>(p.in.lam + ridx);
-                    gm[0] = g4.x; gm[1] = g4.y; gm[2] = g4.z; gm[3] = g4.w;
-                    lm[0] = l4.x; lm[1] = l4.y; lm[2] = l4.z; lm[3] = l4.w;
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        if (d + j < Ck) { gm[j] = p.in.gam[ridx + j]; lm[j] = p.in.lam[ridx + j]; }
-                }
-#pragma unroll
-                for (int j = 0; j < 4; ++j) a_reg[i][j] = (double)v[j] * (double)(v[j] >= 0.f ? gm[j] : lm[j]);
-            } else {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) a_reg[i][j] = (double)v[j];
+                    if (d + j < Ck) {
+                        v[j] = src[j];
+                        if (relax) { gm[j] = p.in.gam[ridx + j]; lm[j] = p.in.lam[ridx + j]; }
+                    }
+                a_raw[i] = make_float4(v[0], v[1], v[2], v[3]);
+                a_gam[i] = make_float4(gm[0], gm[1], gm[2], gm[3]);
+                a_lam[i] = make_float4(lm[0], lm[1], lm[2], lm[3]);
             }
         }
         // B
 #pragma unroll
         for (int i = 0; i < BPT; ++i) {
-            b_reg[i][0] = b_reg[i][1] = b_reg[i][2] = b_reg[i][3] = 0.0;
+            b_raw[i] = make_float4(0.f, 0.f, 0.f, 0.f);
             int idx = tid + 256 * i;
             if (idx >= BK * BN / 4) continue;
             int kk = idx / (BN / 4), nq = idx - kk * (BN / 4);
@@ -162,30 +158,40 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
             if (d >= Ck || n >= N) continue;
             const float* src = p.wt + ((size_t)(t * Ck + d) * N + n);
             if (vecB) {
-                float4 t4 = *reinterpret_cast<const float4*>(src);
-                b_reg[i][0] = t4.x; b_reg[i][1] = t4.y; b_reg[i][2] = t4.z; b_reg[i][3] = t4.w;
+                b_raw[i] = *reinterpret_cast<const float4*>(src);
             } else {
+                float v[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    if (n + j < N) b_reg[i][j] = src[j];
+                    if (n + j < N) v[j] = src[j];
+                b_raw[i] = make_float4(v[0], v[1], v[2], v[3]);
             }
         }
+    };
+
+    auto relaxed = [&](float v, float gm, float lm) -> double {
+        // coefficient after the pending ReLU substitution; float32 x float32 is exact in float64
+        return relax ? (double)v * (double)(v >= 0.f ? gm : lm) : (double)v;
     };
 
     auto store_tiles = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < APT; ++i) {
             int pm = (tid >> 2) + 64 * i;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) As[buf][4 * q + j][pm] = a_reg[i][j];
+            As[buf][4 * q + 0][pm] = relaxed(a_raw[i].x, a_gam[i].x, a_lam[i].x);
+            As[buf][4 * q + 1][pm] = relaxed(a_raw[i].y, a_gam[i].y, a_lam[i].y);
+            As[buf][4 * q + 2][pm] = relaxed(a_raw[i].z, a_gam[i].z, a_lam[i].z);
+            As[buf][4 * q + 3][pm] = relaxed(a_raw[i].w, a_gam[i].w, a_lam[i].w);
         }
 #pragma unroll
         for (int i = 0; i < BPT; ++i) {
             int idx = tid + 256 * i;
             if (idx >= BK * BN / 4) continue;
             int kk = idx / (BN / 4), nq = idx - kk * (BN / 4);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) Bs[buf][kk][4 * nq + j] = b_reg[i][j];
+            Bs[buf][kk][4 * nq + 0] = (double)b_raw[i].x;
+            Bs[buf][kk][4 * nq + 1] = (double)b_raw[i].y;
+            Bs[buf][kk][4 * nq + 2] = (double)b_raw[i].z;
+            Bs[buf][kk][4 * nq + 3] = (double)b_raw[i].w;
         }
     };
 
@@ -363,8 +369,8 @@ __global__ __launch_bounds__(256) void scan_kernel(const ScanParams p) {
         if (p.do_consts) {
             double cn = c + cst;
             double e1 = 0.0;
-            if (p.xmax_a) e1 += p.e1_a * (*p.xmax_a);
-            if (p.xmax_b) e1 += p.e1_b * (*p.xmax_b);
+            if (p.xmax_a) e1 += p.e1_a * p.xmax_a[ri.b];
+            if (p.xmax_b) e1 += p.e1_b * p.xmax_b[ri.b];
             err += cstabs * esum + (fabs(c) + fabs(cst)) * 0x1p-51 + s1 * e1 * (1.0 + esum);
             c = cn;
         }
@@ -430,7 +436,7 @@ __global__ void finalize_kernel(const FinalizeParams p) {
     p.hi[g] = u;
     p.lo[g] = l;
     double x = fmax(fabs(u), fabs(l));
-    if (isfinite(x)) atomic_max_nonneg(p.xmax, x);
+    if (isfinite(x)) atomic_max_nonneg(p.xmax + g / p.rm.n_start, x);
 }
 
 void launch_finalize(const FinalizeParams& p, hipStream_t s) {
@@ -464,7 +470,7 @@ __global__ void relu_kernel(const ReluParams p) {
     p.lam[i] = lam;
     p.del[i] = d;
     double x = fmax(u, 0.0);
-    if (isfinite(x)) atomic_max_nonneg(p.xmax, x);
+    if (isfinite(x)) atomic_max_nonneg(p.xmax + i / p.n, x);
 }
 
 void launch_relu(const ReluParams& p, hipStream_t s) {
@@ -493,7 +499,7 @@ __global__ void box_kernel(const BoxParams p) {
     p.lo[idx] = lo;
     p.hi[idx] = hi;
     double x = fmax(fabs(lo), fabs(hi));
-    if (isfinite(x)) atomic_max_nonneg(p.xmax, x);
+    if (isfinite(x)) atomic_max_nonneg(p.xmax + b, x);
 }
 
 void launch_box(const BoxParams& p, hipStream_t s) {

@@ -55,7 +55,7 @@ struct ScanParams {        // per-row reductions over a block
     const float* lam;
     const double* del;
     const double* beff;    // [C] bias of the affine layer(s) crossed next; null if none
-    double e1_a, e1_b;     // accumulation-error constants of the next crossing(s), times *xmax_a / *xmax_b
+    double e1_a, e1_b;     // accumulation-error constants of the next crossing(s), times xmax_a[box] / xmax_b[box]
     const double* xmax_a;
     const double* xmax_b;
     double round_coef;     // relative rounding error of the stored coefficients (0 for exact blocks)
@@ -81,7 +81,7 @@ struct FinalizeParams {
     RowMap rm;
     const double* best;
     double* lo; double* hi;   // [batch][n_start] of the start layer
-    double* xmax;             // running max of |bounds| of that layer
+    double* xmax;             // [batch] running max of |bounds| of that layer, per box
     int* flag;                // set to 1 on NaN/Inf
 };
 
@@ -91,6 +91,7 @@ struct ReluParams {
     float* gam; float* lam; double* del;
     double* xmax; int* flag;
     long long total;                        // batch * n
+    long long n;                            // neurons per box
 };
 
 struct BoxParams {

@@ -1,0 +1,135 @@
+"""Host-side checks of the HIP library that need no GPU: it loads, exports every declared symbol,
+validates arguments, and plans dependence windows as the paper's formulas say."""
+import ctypes as C
+import json
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from paper_2007_10868_amd import GpuPolyError, Net, lib_path, load_library
+from paper_2007_10868_amd.gpupoly import EXPORTS
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "gpupoly.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(gp_[a-z0-9_]+)\s*\(", hdr))
+    assert declared == set(EXPORTS), declared ^ set(EXPORTS)
+    lib = C.CDLL(lib_path())
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert b"gfx950" in load_library().gp_version()
+
+
+def test_dependence_window_example_of_the_paper():
+    """Section 4.3: W^1 = 3, W^2 = 4 for the 3x3 then 2x2 filters of the figure of Section 3.1."""
+    g = json.load(open(os.path.join(GOLD, "dependence_window_example.json")))
+    (h0, w0, c0) = g["layer_shapes_hwc"][0]
+    n = Net(c0, h0, w0)
+    cur = 0
+    cin = c0
+    for f, s, shp in zip(g["filters"], g["strides"], g["layer_shapes_hwc"][1:]):
+        cur = n.add_conv2d(cur, np.ones((shp[2], cin, f, f), np.float32), None, s, 0)
+        cin = shp[2]
+        assert n.layer_size(cur) == shp[0] * shp[1] * shp[2]
+    plan = n.debug_plan(cur)
+    wins = [(p["window_h"], p["window_w"], p["channels"]) for p in plan if p["kind"] in (0, 1)]
+    assert wins[0] == (g["W0"], g["W0"], 2)
+    assert wins[1] == (g["W1"], g["W1"], 2) and wins[1][0] * wins[1][1] * wins[1][2] == g["size1"]
+    assert wins[2] == (g["W2"], g["W2"], 2) and wins[2][0] * wins[2][1] * wins[2][2] == g["size2"]
+    assert all(p["acc_stride_h"] == 1 for p in plan)
+
+
+def test_window_recurrence_with_stride_and_padding():
+    """W' = (W-1)*s + f (eq. 4) and accumulated stride S' = s*S (eq. 9), clipped to the layer."""
+    net = wl.config(3)
+    g = Net(*net.input_shape)
+    wl.build_into(net, g)
+    # start at the last conv (layer 11: 64x8x8 after two stride-2 convs)
+    plan = [p for p in g.debug_plan(11) if p["kind"] in (0, 1)]
+    W, S = 1, 1
+    convs = [L for L in net.layers[:11] if L["type"] == "conv"][::-1]
+    assert plan[0]["window_h"] == 1
+    for p, L in zip(plan[1:], convs):
+        W = (W - 1) * L["stride"] + L["W"].shape[2]
+        S *= L["stride"]
+        H = net.shape_of(L["src"])[1]
+        assert p["window_h"] == min(W, H), (p, W, H)
+        if W < H:
+            assert p["acc_stride_h"] == S
+    assert plan[-1]["channels"] == 3
+
+
+def test_residual_plan_merges_branches():
+    net = wl.scaled_resnet(8, 16)
+    g = Net(*net.input_shape)
+    wl.build_into(net, g)
+    adds = [i for i, L in enumerate(net.layers, start=1) if L["type"] == "add"]
+    plan = g.debug_plan(adds[1])
+    kinds = [p["kind"] for p in plan]
+    assert kinds.count(3) == 2                      # forks at both sum layers on the way down
+    assert sum(p["merged"] for p in plan) == 2      # ... and both are joined again at the block heads
+    assert plan[-1]["layer"] == 1 and plan[-1]["channels"] == 3
+    mn, full = g.workspace_size(1)
+    assert 0 < mn <= full
+
+
+def test_argument_errors():
+    n = Net(4, 1, 1)
+    with pytest.raises(GpuPolyError) as e:
+        n.add_dense(3, np.zeros((2, 4), np.float32))
+    assert e.value.status == 1
+    with pytest.raises(GpuPolyError) as e:
+        n.add_dense(0, np.full((2, 4), np.nan, np.float32))
+    assert e.value.status == 6
+    a = n.add_dense(0, np.zeros((3, 4), np.float32))
+    b = n.add_dense(0, np.zeros((2, 4), np.float32))
+    with pytest.raises(GpuPolyError) as e:
+        n.add_residual(a, b)
+    assert e.value.status == 2
+    with pytest.raises(GpuPolyError) as e:
+        n.get_bounds(a)                                   # nothing analysed yet
+    assert e.value.status == 3
+    with pytest.raises(GpuPolyError) as e:
+        n.analyze(np.zeros(4, np.float32), -1.0)
+    assert e.value.status == 1
+    with pytest.raises(GpuPolyError) as e:
+        n.analyze_box(np.ones(4, np.float32), np.zeros(4, np.float32))
+    assert e.value.status == 1
+    with pytest.raises(GpuPolyError) as e:
+        n.analyze(np.array([0, np.inf, 0, 0], np.float32), 0.1)
+    assert e.value.status == 6
+    m = Net(2, 4, 4)
+    with pytest.raises(GpuPolyError) as e:
+        m.add_conv2d(0, np.zeros((2, 2, 7, 7), np.float32), None, 1, 0)   # kernel larger than the input
+    assert e.value.status == 2
+    lib = load_library()
+    assert lib.gp_net_create(0, 1, 1, C.byref(C.c_void_p())) == 1
+    assert lib.gp_num_layers(None) == -1
+
+
+def test_unsupported_topology_is_reported_not_guessed():
+    n = Net(4, 1, 1)
+    a = n.add_dense(0, np.eye(4, dtype=np.float32))
+    r = n.add_relu(a)
+    s = n.add_residual(r, r)                # x + x
+    n.add_dense(s, np.eye(4, dtype=np.float32))
+    with pytest.raises(GpuPolyError) as e:
+        n.debug_plan(4)
+    assert e.value.status == 8
+
+
+@pytest.mark.skipif(torch.cuda.is_available(), reason="only meaningful without a GPU")
+def test_no_gpu_is_an_error_not_a_fallback():
+    n = Net(4, 1, 1)
+    n.add_dense(0, np.eye(4, dtype=np.float32))
+    with pytest.raises(GpuPolyError) as e:
+        n.analyze(np.zeros(4, np.float32), 0.1)
+    assert e.value.status == 5

@@ -1,0 +1,311 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element, on
+the same seeded inputs; plus soundness by sampling and the library's own edge cases.
+
+Bar (stated by the benchmark spec): every GPU interval contains every sampled concrete output and the
+oracle's interval, and is looser than the oracle's by at most 1e-3 * (1 + |b|)."""
+import ctypes as C
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from helpers import ball_box, forward
+from parity import (REL_TOL, analysed_layers, check_samples_inside, compare_all, compare_layer, make_gpu,
+                    make_oracle, oracle_with_gpu_ties)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    torch.cuda.init()
+
+
+def tiny_fc(seed=0):
+    return wl.fc_net("tiny_fc", [6, 6], n_in=4, n_out=3, seed=seed)
+
+
+def odd_fc(seed=0):          # widths that are no multiple of 4: scalar load paths, ragged tiles
+    return wl.fc_net("odd_fc", [37, 101, 19], n_in=23, n_out=7, seed=seed)
+
+
+def tiny_conv(seed=0):       # channel counts 2,3,4: unaligned paths; stride 2 with an even kernel
+    return wl.conv_net("tiny_conv", (2, 6, 6), [(3, 3, 1, 1), (4, 4, 2, 1)], [8], n_out=3, seed=seed)
+
+
+def pad0_conv(seed=0):       # no padding, window never clipped before it covers the layer
+    return wl.conv_net("pad0_conv", (1, 12, 12), [(4, 3, 1, 0), (8, 3, 2, 0), (8, 2, 1, 0)], [16], n_out=5, seed=seed)
+
+
+def tiny_resnet(seed=0):
+    return wl.resnet("tiny_res", (2, 8, 8), channels=(3, 4), blocks=(2, 1), n_out=3, seed=seed)
+
+
+def mid_resnet(seed=0):      # 16x16, two stages, identity and 1x1-stride-2 shortcuts, several M tiles
+    return wl.resnet("mid_res", (3, 16, 16), channels=(8, 16), blocks=(2, 2), n_out=10, seed=seed)
+
+
+def rect_conv(seed=0):
+    """Rectangular image, kh != kw, stride_h != stride_w, pad_h != pad_w."""
+    rng = np.random.default_rng(seed)
+    net = wl.Net("rect", (3, 9, 14))
+
+    def cv(src, co, kh, kw):
+        ci = net.shape_of(src)[0]
+        W = (rng.standard_normal((co, ci, kh, kw)) * np.sqrt(2.0 / (ci * kh * kw))).astype(np.float32)
+        b = (rng.standard_normal(co) * 0.1).astype(np.float32)
+        return W, b
+    # Net.conv only knows square strides/pads: describe the layers by hand
+    W, b = cv(0, 5, 3, 2)
+    net.layers.append(dict(type="conv", src=0, W=W, b=b, stride=(1, 2), pad=(1, 0), shape=(5, 9, 7)))
+    net.layers.append(dict(type="relu", src=1, shape=(5, 9, 7)))
+    W, b = cv(2, 6, 2, 3)
+    net.layers.append(dict(type="conv", src=2, W=W, b=b, stride=(2, 1), pad=(0, 1), shape=(6, 4, 7)))
+    net.layers.append(dict(type="relu", src=3, shape=(6, 4, 7)))
+    W = (rng.standard_normal((4, 6 * 4 * 7)) * 0.1).astype(np.float32)
+    net.layers.append(dict(type="dense", src=4, W=W, b=np.zeros(4, np.float32), shape=(4, 1, 1)))
+    return net
+
+
+def run_pair(net, center, eps, clip=(0.0, 1.0)):
+    g = make_gpu(net)
+    g.analyze(center, eps, clip[0], clip[1])
+    o = make_oracle(net)
+    oracle_with_gpu_ties(net, o, g, center, eps, clip=clip)
+    return g, o
+
+
+# ------------------------------------------------------------------------------------------------
+def test_mfma_f64_error_model():
+    """The crossing kernel's slack assumes |MFMA sum - exact sum| <= (K+8) * 2^-50 * sum|terms|.
+    Checked against exact rational arithmetic on float32-valued operands with heavy cancellation."""
+    from paper_2007_10868_amd import load_library
+    lib = load_library()
+    rng = np.random.default_rng(0)
+    K = 512
+    A = (rng.standard_normal((16, K)) * np.exp2(rng.integers(-20, 20, (16, K)))).astype(np.float32).astype(np.float64)
+    B = rng.standard_normal((K, 16)).astype(np.float32).astype(np.float64)
+    A[:, 1::2] = -A[:, 0::2]           # cancellation
+    B[1::2, :] = B[0::2, :] * (1 + 2.0 ** -20)
+    B = B.astype(np.float32).astype(np.float64)
+    tA, tB = torch.tensor(A, device="cuda"), torch.tensor(B, device="cuda")
+    tD = torch.zeros(16, 16, dtype=torch.float64, device="cuda")
+    st = lib.gp_debug_mfma_f64(C.c_void_p(tA.data_ptr()), C.c_void_p(tB.data_ptr()), C.c_void_p(tD.data_ptr()), K,
+                               C.c_void_p(torch.cuda.current_stream().cuda_stream))
+    assert st == 0
+    torch.cuda.synchronize()
+    D = tD.cpu().numpy()
+    worst = 0.0
+    for i in range(16):
+        for j in range(0, 16, 5):
+            terms = [Fraction(float(A[i, k])) * Fraction(float(B[k, j])) for k in range(K)]
+            exact = sum(terms)
+            mag = sum(abs(t) for t in terms)
+            err = abs(Fraction(float(D[i, j])) - exact)
+            assert err <= Fraction((K + 8) * 2.0 ** -50) * mag, (i, j, float(err), float(mag))
+            worst = max(worst, float(err / mag))
+    # plain layout check against NumPy as well
+    assert np.allclose(D, A @ B, rtol=0, atol=1e-9 * np.abs(A).max())
+    print("worst |err|/sum|terms| =", worst)
+
+
+@pytest.mark.parametrize("maker,eps", [(tiny_fc, 0.1), (odd_fc, 0.05), (tiny_conv, 0.05), (pad0_conv, 0.03),
+                                       (tiny_resnet, 0.02), (mid_resnet, 0.01), (rect_conv, 0.04)])
+def test_small_networks_match_oracle_and_contain_samples(maker, eps):
+    net = maker(1)
+    rng = np.random.default_rng(5)
+    c = rng.random(net.n_in).astype(np.float32)
+    g, o = run_pair(net, c, eps)
+    worst = compare_all(net, g, o, what=net.name)
+    compare_all(net, g, o, what=net.name + " (float32 output)", f64=False)
+    lo0, hi0 = ball_box(c, eps)
+    check_samples_inside(net, g, lo0, hi0, 20_000, rng, what=net.name)
+    n_uns = sum(int(np.sum((o.get_bounds(l)[0] < 0) & (o.get_bounds(l)[1] > 0))) for l in analysed_layers(net))
+    assert n_uns > 0
+    print(net.name, "worst looseness / allowed =", worst)
+
+
+def test_config0_fc6x100_all_inputs_and_certify():
+    net = wl.config(0)
+    g = make_gpu(net)
+    o = make_oracle(net)
+    rng = np.random.default_rng(0)
+    for j in range(net.n_inputs):
+        c = net.center(j)
+        g.analyze(c, net.eps)
+        oracle_with_gpu_ties(net, o, g, c, net.eps)
+        compare_all(net, g, o, what=f"fc6x100 input {j}")
+        y = forward(net, c[None, :].astype(np.float64))[net.out_layer][0]
+        label = int(np.argmax(y))
+        ok_g, m_g = g.certify(label)
+        ok_o, m_o = o.certify(label)
+        compare_layer(m_g, m_g, m_o, m_g, f"fc6x100 input {j} margins")      # lower ends only
+        assert np.all(m_g.astype(np.float64) <= m_o + 2e-6 * (1 + np.abs(m_o)))
+        assert ok_g == bool(np.all(m_g > 0))
+        if ok_g:
+            assert ok_o
+        if j == 0:
+            lo0, hi0 = ball_box(c, net.eps)
+            check_samples_inside(net, g, lo0, hi0, 5_000, rng, what="fc6x100")
+
+
+def test_config1_fc9x500_single_and_batched():
+    net = wl.config(1)
+    g = make_gpu(net)
+    o = make_oracle(net)
+    centers = np.stack([net.center(j) for j in range(4)])
+    g.analyze(centers[0], net.eps)
+    single = {l: g.get_bounds_f64(l) for l in analysed_layers(net)}
+    oracle_with_gpu_ties(net, o, g, centers[0], net.eps)
+    worst = compare_all(net, g, o, what="fc9x500 input 0")
+    print("fc9x500 worst looseness / allowed =", worst)
+    # the batched pass must give, for every box, what the single pass gives (same kernels, same order)
+    g.analyze_batch(centers, net.eps)
+    for l in analysed_layers(net):
+        lo, hi = g.get_bounds_f64(l, 0)
+        assert np.array_equal(lo, single[l][0]) and np.array_equal(hi, single[l][1]), l
+    oracle_with_gpu_ties(net, o, g, centers[3], net.eps, batch_index=3)
+    compare_all(net, g, o, batch_index=3, what="fc9x500 input 3 (batched)")
+    # device-resident centres
+    t = torch.tensor(centers, device="cuda")
+    g.analyze_batch_dev(t, net.eps)
+    lo, hi = g.get_bounds_f64(net.out_layer, 3)
+    olo, ohi = o.get_bounds(net.out_layer)
+    compare_layer(lo, hi, olo, ohi, "fc9x500 device centres")
+
+
+def test_config2_small_conv():
+    net = wl.config(2)
+    g = make_gpu(net)
+    o = make_oracle(net)
+    rng = np.random.default_rng(1)
+    for j in (0, 7):
+        c = net.center(j)
+        g.analyze(c, net.eps)
+        oracle_with_gpu_ties(net, o, g, c, net.eps)
+        worst = compare_all(net, g, o, what=f"conv_small input {j}")
+    lo0, hi0 = ball_box(c, net.eps)
+    check_samples_inside(net, g, lo0, hi0, 2_000, rng, what="conv_small")
+    print("conv_small worst looseness / allowed =", worst)
+
+
+def test_row_chunking_gives_identical_bounds():
+    """A workspace that holds only a few rows forces the chunked path (Section 4.2, memory management)."""
+    net = mid_resnet(3)
+    c = np.random.default_rng(2).random(net.n_in).astype(np.float32)
+    g = make_gpu(net)
+    g.analyze(c, 0.01)
+    ref = {l: g.get_bounds_f64(l) for l in analysed_layers(net)}
+    mn, full = g.workspace_size(1)
+    small = torch.empty(mn * 37 + 4096, dtype=torch.uint8, device="cuda")   # 37 rows at a time: ragged chunks
+    assert small.numel() < full
+    g.set_workspace(small)
+    g.analyze(c, 0.01)
+    for l in analysed_layers(net):
+        lo, hi = g.get_bounds_f64(l)
+        assert np.array_equal(lo, ref[l][0]) and np.array_equal(hi, ref[l][1]), l
+    g.set_workspace(torch.empty(1024, dtype=torch.uint8, device="cuda"))
+    from paper_2007_10868_amd import GpuPolyError
+    with pytest.raises(GpuPolyError) as e:
+        g.analyze(c, 0.01)
+    assert e.value.status == 7
+    g.set_workspace(None)
+    g.analyze(c, 0.01)                     # still usable after the failure
+    assert np.array_equal(g.get_bounds_f64(net.out_layer)[0], ref[net.out_layer][0])
+
+
+def test_batched_conv_matches_single_and_certify_batch():
+    net = wl.config(2)
+    g = make_gpu(net)
+    centers = np.stack([net.center(j) for j in range(3)])
+    g.analyze_batch(centers, net.eps)
+    batched = [g.get_bounds_f64(net.out_layer, b) for b in range(3)]
+    labels = [int(np.argmax((lo + hi) / 2)) for lo, hi in batched]
+    ok_b, m_b = g.certify_batch(labels)
+    for b in range(3):
+        g.analyze(centers[b], net.eps)
+        lo, hi = g.get_bounds_f64(net.out_layer)
+        assert np.array_equal(lo, batched[b][0]) and np.array_equal(hi, batched[b][1])
+        ok, m = g.certify(labels[b])
+        assert np.array_equal(m, m_b[b]) and ok == ok_b[b]
+    o = make_oracle(net)
+    oracle_with_gpu_ties(net, o, g, centers[2], net.eps)
+    _, m_o = o.certify(labels[2])
+    assert np.all(m_b[2] <= m_o + 2e-6 * (1 + np.abs(m_o)))
+    assert np.all(m_o - m_b[2] <= REL_TOL * (1 + np.abs(m_o)))
+
+
+def test_stream_and_workspace_from_torch():
+    net = tiny_conv(2)
+    c = np.random.default_rng(3).random(net.n_in).astype(np.float32)
+    g = make_gpu(net)
+    g.analyze(c, 0.05)
+    ref = g.get_bounds_f64(net.out_layer)
+    s = torch.cuda.Stream()
+    g.set_stream(s)
+    _, full = g.workspace_size(1)
+    g.set_workspace(torch.empty(full, dtype=torch.uint8, device="cuda"))
+    g.analyze(c, 0.05)
+    got = g.get_bounds_f64(net.out_layer)
+    assert np.array_equal(ref[0], got[0]) and np.array_equal(ref[1], got[1])
+
+
+def test_degenerate_cases():
+    # eps = 0: every interval collapses onto the concrete forward pass
+    net = tiny_resnet(4)
+    c = np.random.default_rng(4).random(net.n_in).astype(np.float32)
+    g = make_gpu(net)
+    g.analyze(c, 0.0)
+    vals = forward(net, c[None, :].astype(np.float64))
+    for l in analysed_layers(net):
+        lo, hi = g.get_bounds_f64(l)
+        v = vals[l][0]
+        assert np.all(lo <= v) and np.all(v <= hi)
+        assert np.max(hi - lo) < 1e-5 * (1 + np.max(np.abs(v)))
+    # a single affine layer: closed form of the first layer
+    one = wl.fc_net("one", [], n_in=9, n_out=4, seed=3)
+    g1 = make_gpu(one)
+    x = np.random.default_rng(1).random(9).astype(np.float32)
+    g1.analyze(x, 0.25, -5.0, 5.0)
+    W, b = one.layers[0]["W"].astype(np.float64), one.layers[0]["b"].astype(np.float64)
+    lo0, hi0 = ball_box(x, 0.25, -5.0, 5.0)
+    l_ref = np.maximum(W, 0) @ lo0 + np.minimum(W, 0) @ hi0 + b
+    u_ref = np.maximum(W, 0) @ hi0 + np.minimum(W, 0) @ lo0 + b
+    lo, hi = g1.get_bounds_f64(1)
+    assert np.all(lo <= l_ref) and np.all(hi >= u_ref)
+    assert np.max(l_ref - lo) < 1e-6 and np.max(hi - u_ref) < 1e-6
+    # the box is clipped: centre at the clip end, huge eps
+    g1.analyze(np.ones(9, np.float32), 100.0, 0.0, 1.0)
+    lo, hi = g1.get_bounds_f64(0)
+    assert np.all(lo == 0.0) and np.all(hi == 1.0)
+    # explicit box
+    g1.analyze_box(lo0.astype(np.float32) - 1e-3, hi0.astype(np.float32) + 1e-3)
+    lo, hi = g1.get_bounds_f64(1)
+    assert np.all(lo <= l_ref) and np.all(hi >= u_ref)
+
+
+def test_overflow_is_reported():
+    """Bounds beyond the float64 range are an error, never a number.  (A float32 overflow of single
+    coefficients only loses the later candidates: the earlier ones stay valid and finite.)"""
+    from paper_2007_10868_amd import GpuPolyError
+    net = wl.fc_net("big", [8] * 10, n_in=4, n_out=2, seed=0)
+    for L in net.layers:
+        if L["type"] == "dense":
+            L["W"] = (L["W"] * np.float32(1e36)).astype(np.float32)
+    g = make_gpu(net)
+    with pytest.raises(GpuPolyError) as e:
+        g.analyze(np.full(4, 0.5, np.float32), 0.1)
+    assert e.value.status == 6
+    mild = wl.fc_net("mild", [8, 8, 8], n_in=4, n_out=2, seed=0)
+    for L in mild.layers:
+        if L["type"] == "dense":
+            L["W"] = (L["W"] * np.float32(1e30)).astype(np.float32)
+    g = make_gpu(mild)
+    c = np.full(4, 0.5, np.float32)
+    g.analyze(c, 0.1)                       # coefficients overflow float32 on the way down
+    lo0, hi0 = ball_box(c, 0.1)
+    check_samples_inside(mild, g, lo0, hi0, 2_000, np.random.default_rng(0), what="mild overflow")
