@@ -10,7 +10,7 @@ LIB = os.path.join(HERE, "libgpupoly_hip.so")
 SOURCES = ["gpupoly.cpp", "kernels.hip"]
 # packed-fp32 instructions are switched off for every kernel of this library
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-x", "hip",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-mllvm", "-amdgpu-mfma-vgpr-form", "-Wno-unused-command-line-argument"]
 
 
 def build(force: bool = True, verbose: bool = False) -> str:

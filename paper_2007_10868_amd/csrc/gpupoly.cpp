@@ -34,7 +34,8 @@ struct Layer {
     int C = 0, H = 0, W = 0;
     long long n = 0;
     int kh = 1, kw = 1, sh = 1, sw = 1, ph = 0, pw = 0;
-    std::vector<float> wt_host;    // device layout [tap][C][C_in], kept until uploaded
+    std::vector<float> wt_host;    // crossing layout [tap][C_in][C] (own channels innermost), kept until uploaded
+    std::vector<float> wti_host;   // initial-expression layout [tap][C][C_in] (dense: [C][n_in])
     std::vector<float> bias_host;  // [C]
     double rowabs = 0.0;           // max_i sum_j |F_ij|
     bool need_bounds = false;      // intervals are computed for this layer (derived from the topology)
@@ -44,17 +45,23 @@ struct Layer {
     std::vector<double> beff_host; // [C] summed bias of those layers (float64: the sum of two float32 is kept exact)
     // device
     float* d_wt = nullptr;
+    float* d_wti = nullptr;
+    float* d_bias = nullptr;
     double* d_beff = nullptr;
-    double *d_lo = nullptr, *d_hi = nullptr, *d_del = nullptr, *d_xmax = nullptr;
-    float *d_gam = nullptr, *d_lam = nullptr;
+    double *d_lo = nullptr, *d_hi = nullptr, *d_xmax = nullptr;
+    double *d_rho = nullptr, *d_kap = nullptr;   // ReLU layers: candidate and intercept multipliers after substitution
+    float* d_grl = nullptr;        // packed ReLU relaxation (see relax_factor in kernels.hip)
 };
 
 struct PlanOp {
     enum Kind { INIT = 0, SCAN = 1, CROSS = 2, FINALIZE = 3 } kind = INIT;
     int slot_in = -1, slot_out = -1, slot_add = -1;
     Geom g_in, g_out, g_add;
-    int layer_in = -1, relax_in = -1, layer_out = -1, relax_add = -1;
+    int layer_in = -1, layer_out = -1;
+    bool relaxed = false;  // CROSS/INIT: apply the ReLU substitution of layer_out to the new block; SCAN: block holds such coefficients
+    bool consts_only = false;
     bool do_consts = false, update_best = false, rounded = false;
+    int init_mode = 0;     // INIT: 0 one-hot over the start layer, 1 certification rows, 2 the start layer's own matrix rows
 };
 
 struct Plan {
@@ -212,8 +219,7 @@ gp_status prepare_topology(gp_net* net) {
 struct Desc {
     int slot = -1;
     Geom g;
-    int relax = -1;
-    bool consumed = false;
+    bool consumed = false;   // the constants of the next step have been added to the rows' constant
 };
 
 void push_step(Plan& pl, int kind, int layer, const Geom& g, const Layer& l, int merged) {
@@ -235,9 +241,35 @@ gp_status build_plan(gp_net* net, int start, bool certify, Plan& pl) {
     if (certify) { g0.Sy = g0.Sx = g0.Py = g0.Px = 0; g0.Wy = L[start].H; g0.Wx = L[start].W; }
     else { g0.Sy = g0.Sx = 1; g0.Py = g0.Px = 0; g0.Wy = g0.Wx = 1; }
     normalise(g0, L[start]);
-    {
+    if (!certify && is_affine(L[start])) {
+        // the neuron's own affine expression (Section 2): the filter placed in the window over the predecessor
+        const int pr = L[start].a;
+        Geom g1 = cross_geom(g0, L[start], L[pr]);
+        const bool relu_pred = L[pr].type == T_RELU;
         PlanOp op;
         op.kind = PlanOp::INIT;
+        op.init_mode = 2;
+        op.slot_out = alloc_slot();
+        op.g_out = g1;
+        op.layer_in = start;
+        op.layer_out = pr;
+        op.relaxed = relu_pred;
+        pl.ops.push_back(op);
+        pl.slot_elems = std::max(pl.slot_elems, block_elems(g1, L[pr]));
+        PlanOp sc;
+        sc.kind = PlanOp::SCAN;
+        sc.slot_in = op.slot_out; sc.g_in = g1; sc.layer_in = pr;
+        sc.do_consts = true; sc.update_best = true; sc.rounded = relu_pred; sc.relaxed = relu_pred;
+        pl.ops.push_back(sc);
+        Desc d; d.slot = op.slot_out; d.g = g1; d.consumed = true;
+        expr[relu_pred ? L[pr].a : pr] = d;
+        push_step(pl, 0, start, g0, L[start], 0);
+        push_step(pl, 1, start, g1, L[pr], 0);
+        if (relu_pred) push_step(pl, 2, pr, g1, L[pr], 0);
+    } else {
+        PlanOp op;
+        op.kind = PlanOp::INIT;
+        op.init_mode = certify ? 1 : 0;
         op.slot_out = alloc_slot();
         op.g_out = g0;
         op.layer_out = start;
@@ -264,20 +296,18 @@ gp_status build_plan(gp_net* net, int start, bool certify, Plan& pl) {
         expr.erase(k);
         const Layer& l = L[k];
         if (!d.consumed) {
+            if (l.type == T_RELU)
+                return fail(net, GP_ERR_UNSUPPORTED, "layer %d: a partial expression over a ReLU layer is never joined", k);
             PlanOp sc;
             sc.kind = PlanOp::SCAN;
             sc.slot_in = d.slot; sc.g_in = d.g; sc.layer_in = k;
             sc.do_consts = true; sc.update_best = false; sc.rounded = false;
-            sc.relax_in = -2;   // marks: constants only, no interval terms
+            sc.consts_only = true;
             pl.ops.push_back(sc);
             d.consumed = true;
         }
         if (l.type == T_RELU) {
-            if (d.relax != -1) return fail(net, GP_ERR_UNSUPPORTED, "layer %d: ReLU of a ReLU output", k);
-            d.relax = k;
-            if (!insert(l.a, d))
-                return fail(net, GP_ERR_UNSUPPORTED, "layer %d: two expressions meet before an affine layer", l.a);
-            push_step(pl, 2, k, d.g, l, 0);
+            return fail(net, GP_ERR_UNSUPPORTED, "layer %d: ReLU of a layer that is not crossed by an affine layer", k);
         } else if (l.type == T_ADD) {
             if (l.a == l.b) return fail(net, GP_ERR_UNSUPPORTED, "layer %d: sum of a layer with itself", k);
             if (!insert(l.a, d) || !insert(l.b, d))
@@ -289,7 +319,7 @@ gp_status build_plan(gp_net* net, int start, bool certify, Plan& pl) {
             Geom g = cross_geom(d.g, l, L[p]);
             PlanOp op;
             op.kind = PlanOp::CROSS;
-            op.slot_in = d.slot; op.g_in = d.g; op.layer_in = k; op.relax_in = d.relax; op.layer_out = p;
+            op.slot_in = d.slot; op.g_in = d.g; op.layer_in = k; op.layer_out = p;
             Desc ad;
             bool has_add = expr.count(p) > 0;
             if (has_add) {
@@ -301,26 +331,34 @@ gp_status build_plan(gp_net* net, int start, bool certify, Plan& pl) {
                 g = h;
                 if (l.type == T_DENSE && block_elems(ad.g, L[p]) != L[p].n)
                     return fail(net, GP_ERR_UNSUPPORTED, "layer %d: windowed block joins a dense branch", p);
-                op.slot_add = ad.slot; op.g_add = ad.g; op.relax_add = ad.relax;
+                op.slot_add = ad.slot; op.g_add = ad.g;
             }
             op.slot_out = alloc_slot();
             if (op.slot_out < 0) return fail(net, GP_ERR_UNSUPPORTED, "too many live coefficient blocks");
             op.g_out = g;
+            bool complete = true;
+            for (auto& kv : expr)
+                if (kv.first > p) complete = false;
+            // a complete block over a ReLU layer takes the ReLU substitution at once (sign-split, Section 2)
+            // and then ranges over the ReLU's input layer
+            const bool relaxed = complete && L[p].type == T_RELU;
+            const int key = relaxed ? L[p].a : p;
+            if (relaxed && expr.count(key))
+                return fail(net, GP_ERR_UNSUPPORTED, "layer %d: two expressions meet before an affine layer", key);
+            op.relaxed = relaxed;
             pl.ops.push_back(op);
             pl.slot_elems = std::max(pl.slot_elems, block_elems(g, L[p]));
             ref[d.slot] -= 1;
             if (has_add) ref[ad.slot] -= 1;
-            bool complete = true;
-            for (auto& kv : expr)
-                if (kv.first > p) complete = false;
             PlanOp sc;
             sc.kind = PlanOp::SCAN;
             sc.slot_in = op.slot_out; sc.g_in = g; sc.layer_in = p;
-            sc.do_consts = complete; sc.update_best = expr.empty(); sc.rounded = true;
+            sc.do_consts = complete; sc.update_best = expr.empty(); sc.rounded = true; sc.relaxed = relaxed;
             pl.ops.push_back(sc);
-            Desc nd; nd.slot = op.slot_out; nd.g = g; nd.relax = -1; nd.consumed = complete;
-            expr[p] = nd;
+            Desc nd; nd.slot = op.slot_out; nd.g = g; nd.consumed = complete;
+            expr[key] = nd;
             push_step(pl, 1, k, g, L[p], has_add ? 1 : 0);
+            if (relaxed) push_step(pl, 2, p, g, L[p], 0);
         } else {
             return fail(net, GP_ERR_UNSUPPORTED, "layer %d: unexpected type", k);
         }
@@ -347,9 +385,9 @@ gp_status get_plan(gp_net* net, int lid, Plan** out) {
 
 // ---- device state ------------------------------------------------------------------------------
 void free_layer_bounds(Layer& l) {
-    dfree(l.d_lo); dfree(l.d_hi); dfree(l.d_del); dfree(l.d_xmax); dfree(l.d_gam); dfree(l.d_lam);
-    l.d_lo = l.d_hi = l.d_del = l.d_xmax = nullptr;
-    l.d_gam = l.d_lam = nullptr;
+    dfree(l.d_lo); dfree(l.d_hi); dfree(l.d_rho); dfree(l.d_kap); dfree(l.d_xmax); dfree(l.d_grl);
+    l.d_lo = l.d_hi = l.d_rho = l.d_kap = l.d_xmax = nullptr;
+    l.d_grl = nullptr;
 }
 
 bool has_bounds(const gp_net* net, int lid) {
@@ -367,6 +405,12 @@ gp_status ensure_device(gp_net* net, int batch) {
             if (!l.wt_host.empty() && !l.d_wt) {
                 HIP_TRY(net, hipMalloc((void**)&l.d_wt, l.wt_host.size() * sizeof(float)));
                 HIP_TRY(net, hipMemcpy(l.d_wt, l.wt_host.data(), l.wt_host.size() * sizeof(float), hipMemcpyHostToDevice));
+            }
+            if (!l.wti_host.empty() && !l.d_wti) {
+                HIP_TRY(net, hipMalloc((void**)&l.d_wti, l.wti_host.size() * sizeof(float)));
+                HIP_TRY(net, hipMemcpy(l.d_wti, l.wti_host.data(), l.wti_host.size() * sizeof(float), hipMemcpyHostToDevice));
+                HIP_TRY(net, hipMalloc((void**)&l.d_bias, l.C * sizeof(float)));
+                HIP_TRY(net, hipMemcpy(l.d_bias, l.bias_host.data(), l.C * sizeof(float), hipMemcpyHostToDevice));
             }
             if (!l.d_beff && l.C > 0) {
                 HIP_TRY(net, hipMalloc((void**)&l.d_beff, l.C * sizeof(double)));
@@ -388,9 +432,9 @@ gp_status ensure_device(gp_net* net, int batch) {
                 HIP_TRY(net, hipMalloc((void**)&l.d_xmax, sizeof(double) * batch));
             }
             if (l.type == T_RELU) {
-                HIP_TRY(net, hipMalloc((void**)&l.d_gam, cnt * sizeof(float)));
-                HIP_TRY(net, hipMalloc((void**)&l.d_lam, cnt * sizeof(float)));
-                HIP_TRY(net, hipMalloc((void**)&l.d_del, cnt * sizeof(double)));
+                HIP_TRY(net, hipMalloc((void**)&l.d_grl, cnt * sizeof(float)));
+                HIP_TRY(net, hipMalloc((void**)&l.d_rho, cnt * sizeof(double)));
+                HIP_TRY(net, hipMalloc((void**)&l.d_kap, cnt * sizeof(double)));
             }
         }
         long long nout = net->L.back().n;
@@ -423,15 +467,13 @@ gp_status get_workspace(gp_net* net, long long want, char** ws, long long* bytes
     return GP_OK;
 }
 
-gp::BlockDesc make_desc(const gp_net* net, const float* data, const Geom& g, int layer, int relax) {
+gp::BlockDesc make_desc(const gp_net* net, const float* data, const Geom& g, int layer) {
     const Layer& l = net->L[layer];
     gp::BlockDesc b;
     b.data = data;
     b.H = l.H; b.W = l.W; b.C = l.C;
     b.wy = std::min(g.Wy, l.H); b.wx = std::min(g.Wx, l.W);
     b.Sy = g.Sy; b.Sx = g.Sx; b.Py = g.Py; b.Px = g.Px;
-    b.gam = relax >= 0 ? net->L[relax].d_gam : nullptr;
-    b.lam = relax >= 0 ? net->L[relax].d_lam : nullptr;
     return b;
 }
 
@@ -487,27 +529,44 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
         const int nrows = rm.Rc * nsign;
         for (const PlanOp& op : pl.ops) {
             if (op.kind == PlanOp::INIT) {
+                const Layer& lo = net->L[op.layer_out];
                 gp::InitParams ip;
+                std::memset(&ip, 0, sizeof(ip));
                 ip.out = slot_ptr(op.slot_out);
                 ip.rm = rm; ip.nrows = nrows;
-                ip.nelem = (int)block_elems(op.g_out, ls);
+                ip.nelem = (int)block_elems(op.g_out, lo);
+                ip.mode = op.init_mode;
                 ip.labels = net->d_labels;
-                ip.certify = certify ? 1 : 0;
-                ip.H = ls.H; ip.W = ls.W; ip.C = ls.C;
+                ip.H = lo.H; ip.W = lo.W; ip.C = lo.C;
+                if (op.init_mode == 2) {
+                    ip.wy = std::min(op.g_out.Wy, lo.H); ip.wx = std::min(op.g_out.Wx, lo.W);
+                    ip.Sy = op.g_out.Sy; ip.Sx = op.g_out.Sx; ip.Py = op.g_out.Py; ip.Px = op.g_out.Px;
+                    ip.kh = ls.kh; ip.kw = ls.kw; ip.sh = ls.sh; ip.sw = ls.sw; ip.ph = ls.ph; ip.pw = ls.pw;
+                    ip.dense = ls.type == T_DENSE ? 1 : 0;
+                    ip.Cs = ls.C;
+                    ip.wt = ls.d_wti; ip.bias = ls.d_bias;
+                    ip.out_grl = op.relaxed ? lo.d_grl : nullptr;
+                }
                 ip.c = d_c; ip.err = d_err; ip.best = d_best;
                 gp::launch_init(ip, net->stream);
             } else if (op.kind == PlanOp::SCAN) {
                 const Layer& l = net->L[op.layer_in];
                 gp::ScanParams sp;
-                sp.blk = make_desc(net, slot_ptr(op.slot_in), op.g_in, op.layer_in, -1);
+                sp.blk = make_desc(net, slot_ptr(op.slot_in), op.g_in, op.layer_in);
                 sp.rm = rm; sp.nrows = nrows;
                 sp.batch_stride = (int)l.n;
-                bool interval_terms = (op.relax_in != -2) && has_bounds(net, op.layer_in) && op.layer_in != start;
-                sp.lo = interval_terms ? l.d_lo : nullptr;
-                sp.hi = interval_terms ? l.d_hi : nullptr;
-                sp.gam = l.type == T_RELU ? l.d_gam : nullptr;
-                sp.lam = l.type == T_RELU ? l.d_lam : nullptr;
-                sp.del = l.type == T_RELU ? l.d_del : nullptr;
+                const bool interval_terms = !op.consts_only && has_bounds(net, op.layer_in) && op.layer_in != start;
+                sp.cpos = sp.cneg = sp.xlo = sp.xhi = sp.kap = nullptr;
+                sp.xmax_self = nullptr;
+                if (interval_terms) {
+                    if (op.relaxed) {      // coefficients already multiplied by the ReLU slopes: they range over the ReLU's input
+                        const Layer& q = net->L[l.a];
+                        sp.cpos = l.d_rho; sp.cneg = l.d_lo; sp.xlo = q.d_lo; sp.xhi = q.d_hi; sp.xmax_self = q.d_xmax;
+                    } else {
+                        sp.cpos = l.d_hi; sp.cneg = l.d_lo; sp.xlo = l.d_lo; sp.xhi = l.d_hi; sp.xmax_self = l.d_xmax;
+                    }
+                }
+                if (op.relaxed) sp.kap = l.d_kap;
                 sp.beff = l.land.empty() ? nullptr : l.d_beff;
                 sp.e1_a = sp.e1_b = 0.0;
                 sp.xmax_a = sp.xmax_b = nullptr;
@@ -530,16 +589,17 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                 const Layer& a = net->L[op.layer_in];
                 const Layer& p = net->L[op.layer_out];
                 gp::CrossParams cp;
-                cp.in = make_desc(net, slot_ptr(op.slot_in), op.g_in, op.layer_in, op.relax_in);
+                cp.in = make_desc(net, slot_ptr(op.slot_in), op.g_in, op.layer_in);
+                cp.out_grl = op.relaxed ? p.d_grl : nullptr;
                 cp.wt = a.d_wt;
                 cp.kh = a.kh; cp.kw = a.kw; cp.sh = a.sh; cp.sw = a.sw; cp.ph = a.ph; cp.pw = a.pw;
                 cp.out = slot_ptr(op.slot_out);
                 if (a.type == T_DENSE) {   // a dense layer is a 1x1 convolution over the flattened predecessor
                     cp.Ho = 1; cp.Wo = 1; cp.Co = (int)p.n;
                     cp.owy = cp.owx = 1; cp.oSy = cp.oSx = cp.oPy = cp.oPx = 0;
-                    cp.add.data = nullptr; cp.add.gam = cp.add.lam = nullptr;
+                    cp.add.data = nullptr;
                     if (op.slot_add >= 0) {
-                        cp.add = make_desc(net, slot_ptr(op.slot_add), op.g_add, op.layer_out, op.relax_add);
+                        cp.add = make_desc(net, slot_ptr(op.slot_add), op.g_add, op.layer_out);
                         // full-layer addend seen as one pixel with n channels
                         cp.add.H = cp.add.W = 1; cp.add.C = (int)p.n; cp.add.wy = cp.add.wx = 1;
                         cp.add.Sy = cp.add.Sx = cp.add.Py = cp.add.Px = 0;
@@ -548,8 +608,8 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                     cp.Ho = p.H; cp.Wo = p.W; cp.Co = p.C;
                     cp.owy = std::min(op.g_out.Wy, p.H); cp.owx = std::min(op.g_out.Wx, p.W);
                     cp.oSy = op.g_out.Sy; cp.oSx = op.g_out.Sx; cp.oPy = op.g_out.Py; cp.oPx = op.g_out.Px;
-                    cp.add.data = nullptr; cp.add.gam = cp.add.lam = nullptr;
-                    if (op.slot_add >= 0) cp.add = make_desc(net, slot_ptr(op.slot_add), op.g_add, op.layer_out, op.relax_add);
+                    cp.add.data = nullptr;
+                    if (op.slot_add >= 0) cp.add = make_desc(net, slot_ptr(op.slot_add), op.g_add, op.layer_out);
                 }
                 cp.rm = rm; cp.nrows = nrows;
                 prof_mark(net, 0, false);
@@ -601,7 +661,7 @@ gp_status analyze_layers(gp_net* net, int batch) {
         if (l.type == T_RELU) {
             gp::ReluParams rp;
             rp.plo = net->L[l.a].d_lo; rp.phi = net->L[l.a].d_hi;
-            rp.lo = l.d_lo; rp.hi = l.d_hi; rp.gam = l.d_gam; rp.lam = l.d_lam; rp.del = l.d_del;
+            rp.lo = l.d_lo; rp.hi = l.d_hi; rp.grl = l.d_grl; rp.rho = l.d_rho; rp.kap = l.d_kap;
             rp.xmax = l.d_xmax; rp.flag = net->d_flag;
             rp.total = l.n * batch;
             rp.n = l.n;
@@ -672,7 +732,7 @@ void gp_net_destroy(gp_net* net) {
     if (!net) return;
     for (auto& l : net->L) {
         free_layer_bounds(l);
-        dfree(l.d_wt); dfree(l.d_beff);
+        dfree(l.d_wt); dfree(l.d_wti); dfree(l.d_bias); dfree(l.d_beff);
     }
     dfree(net->d_flag); dfree(net->d_labels); dfree(net->d_margins); dfree(net->d_centers);
     dfree(net->ws_own);
@@ -712,16 +772,17 @@ gp_status gp_add_dense(gp_net* net, int32_t in_layer, int32_t out_dim, const flo
     Layer l;
     l.type = T_DENSE; l.a = in_layer; l.C = out_dim; l.H = 1; l.W = 1; l.n = out_dim;
     l.wt_host.resize((size_t)n_in * out_dim);
+    l.wti_host.resize((size_t)n_in * out_dim);
     const long long hw = (long long)p.H * p.W;
     double rowabs = 0;
     for (int o = 0; o < out_dim; ++o) {
         double s = 0;
         const float* src = W + (size_t)o * n_in;
-        float* dst = l.wt_host.data() + (size_t)o * n_in;
         for (long long pix = 0; pix < hw; ++pix)
             for (int c = 0; c < p.C; ++c) {
                 float v = src[c * hw + pix];
-                dst[pix * p.C + c] = v;
+                l.wt_host[(size_t)(pix * p.C + c) * out_dim + o] = v;    // [n_in in H,W,C order][out]
+                l.wti_host[(size_t)o * n_in + (pix * p.C + c)] = v;      // [out][n_in in H,W,C order]
                 s += std::fabs((double)v);
             }
         rowabs = std::max(rowabs, s);
@@ -753,6 +814,7 @@ gp_status gp_add_conv2d(gp_net* net, int32_t in_layer, int32_t c_out, int32_t kh
     l.type = T_CONV; l.a = in_layer; l.C = c_out; l.H = ho; l.W = wo; l.n = (long long)c_out * ho * wo;
     l.kh = kh; l.kw = kw; l.sh = stride_h; l.sw = stride_w; l.ph = pad_h; l.pw = pad_w;
     l.wt_host.resize(nw);
+    l.wti_host.resize(nw);
     double rowabs = 0;
     for (int co = 0; co < c_out; ++co) {
         double s = 0;
@@ -760,7 +822,8 @@ gp_status gp_add_conv2d(gp_net* net, int32_t in_layer, int32_t c_out, int32_t kh
             for (int f = 0; f < kh; ++f)
                 for (int g = 0; g < kw; ++g) {
                     float v = W[(((size_t)co * p.C + ci) * kh + f) * kw + g];
-                    l.wt_host[((size_t)(f * kw + g) * c_out + co) * p.C + ci] = v;
+                    l.wt_host[((size_t)(f * kw + g) * p.C + ci) * c_out + co] = v;
+                    l.wti_host[((size_t)(f * kw + g) * c_out + co) * p.C + ci] = v;
                     s += std::fabs((double)v);
                 }
         rowabs = std::max(rowabs, s);
@@ -957,10 +1020,10 @@ gp_status gp_get_relu_lambda(const gp_net* net, int32_t layer_id, int32_t batch_
     if (batch_index < 0 || batch_index >= net->batch) return fail(net, GP_ERR_ARG, "batch index out of range");
     const Layer& l = net->L[layer_id];
     std::vector<float> v(l.n);
-    HIP_TRY(net, hipMemcpy(v.data(), l.d_lam + (size_t)batch_index * l.n, l.n * sizeof(float), hipMemcpyDeviceToHost));
+    HIP_TRY(net, hipMemcpy(v.data(), l.d_grl + (size_t)batch_index * l.n, l.n * sizeof(float), hipMemcpyDeviceToHost));
     const long long hw = (long long)l.H * l.W;
     for (long long pix = 0; pix < hw; ++pix)
-        for (int c = 0; c < l.C; ++c) lam[c * hw + pix] = v[pix * l.C + c] != 0.f ? 1 : 0;
+        for (int c = 0; c < l.C; ++c) lam[c * hw + pix] = std::signbit(v[pix * l.C + c]) ? 0 : 1;
     return GP_OK;
 }
 

@@ -9,6 +9,8 @@
 #include "kernels.hpp"
 
 #include <math.h>
+#include <stdlib.h>
+#include <string.h>
 
 namespace gp {
 
@@ -44,154 +46,161 @@ __device__ __forceinline__ RowInfo row_info(const RowMap& rm, int r) {
 // to the window in its input (Algorithm 1), written as one implicit GEMM over all rows:
 //   M = rows * out-window pixels, N = input channels, K = taps * output channels.
 // A operand: gathered block values, with a pending ReLU substitution applied on the fly
-//            (a * (a>=0 ? gam : lam), exact in float64).
+//            (a * relax_factor, exact in float64).
 // B operand: filter taps [tap][C_out][C_in].
 // float64 MFMA 16x16x4; accumulators D[i][j]: lane l, register r holds i = 4*r + l/16, j = l%16.
 // ------------------------------------------------------------------------------------------------
-template <int BM, int BN>
+struct F4 {
+    float v[4];
+};
+
+// 4 consecutive floats from base[off..off+3]; elements beyond `nvalid` (and everything when !ok) read as 0.
+// Loads are unconditional from a clamped address so that the compiler emits straight-line code.
+template <bool VEC>
+__device__ __forceinline__ F4 ld4(const float* __restrict__ base, long long off, bool ok, int nvalid) {
+    F4 r;
+    if (VEC) {
+        float4 v = *reinterpret_cast<const float4*>(base + (ok ? off : 0));
+        r.v[0] = ok ? v.x : 0.f; r.v[1] = ok ? v.y : 0.f; r.v[2] = ok ? v.z : 0.f; r.v[3] = ok ? v.w : 0.f;
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            bool okj = ok && j < nvalid;
+            float v = base[okj ? off + j : 0];
+            r.v[j] = okj ? v : 0.f;
+        }
+    }
+    return r;
+}
+
+// ReLU relaxation of one neuron packed in one float: |g| is the slope of the upper line, the sign bit
+// is set when the lower line is 0 (lam = 0) and clear when it is x (lam = 1).
+// A coefficient a over relu(x) becomes a * relax_factor(a, g) over x (Section 2: positive coefficients
+// take the upper line, negative ones the lower line, for an upper bound).
+__device__ __forceinline__ float relax_factor(double a, float g) {
+    return a >= 0.0 ? fabsf(g) : (signbit(g) ? 0.f : 1.f);
+}
+
+// LDS-tiled implicit GEMM on float64 MFMA (16x16x4).
+//   Tile BM x BN per work-group of 4 waves, K step 16.  Both operand tiles are stored [row][k] with the
+//   16 k-values of a row contiguous (row stride 18 doubles): a thread converts the 4 consecutive
+//   channels it loaded (one 16-byte global load) and writes them with two 16-byte LDS stores; an MFMA
+//   lane (row l%16, k-slot l/16) reads ITS 4 consecutive k-values back with two 16-byte LDS loads and
+//   uses value j in MFMA step j, i.e. step j contracts the channel set {j, 4+j, 8+j, 12+j}.  A and B use
+//   the same permutation, so every product pairs the right channels; only the summation order differs,
+//   which the rounding slack covers for any order.
+template <int BM, int BN, bool VEC>
 __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
     constexpr int BK = 16;
-    constexpr int LDA = BM + 4, LDB = BN + 4;
+    constexpr int LDK = 18;                          // doubles per tile row: 144 B, keeps 16-byte alignment, spreads banks
     constexpr int WAVES_N = (BN >= 64) ? 2 : 1;
     constexpr int WAVES_M = 4 / WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
     constexpr int TM = WTM / 16, TN = WTN / 16;
-    constexpr int APT = BM / 64;                    // A pixels per thread
-    constexpr int BPT = (BK * BN / 4 + 255) / 256;  // B float4 per thread
+    constexpr int APT = (BM + 63) / 64;             // A pixels per thread
+    constexpr int BPT = (BN + 63) / 64;             // B columns per thread
     static_assert(TM >= 1 && TN >= 1, "tile");
 
-    __shared__ double As[2][BK][LDA];
-    __shared__ double Bs[2][BK][LDB];
+    __shared__ __attribute__((aligned(16))) double As[2][BM][LDK];
+    __shared__ __attribute__((aligned(16))) double Bs[2][BN][LDK];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int lk = lane >> 4, lm = lane & 15;
     const long long opix = (long long)p.owy * p.owx;
     const long long M = (long long)p.nrows * opix;
     const long long m0 = (long long)blockIdx.x * BM;
     const int n0 = blockIdx.y * BN;
     const int Ck = p.in.C, N = p.Co;
+    const int taps = p.kh * p.kw;
     const int kchunks = (Ck + BK - 1) / BK;
-    const int nIt = p.kh * p.kw * kchunks;
-    const bool vecA = (Ck & 3) == 0;
-    const bool vecB = (N & 3) == 0;
-    const bool relax = p.in.gam != nullptr;
+    const int nIt = taps * kchunks;
 
-    // ---- per-thread pixel bookkeeping for the A gather
-    const int q = tid & 3;
-    const float* a_base[APT];
-    long long a_rbase[APT];
+    // ---- loader bookkeeping: thread -> (tile row ld_row (+64*i), channel quad q4)
+    const int ld_row = tid >> 2, q4 = (tid & 3) * 4;
+    long long a_rowoff[APT];
     int a_A[APT], a_B[APT], a_oiy[APT], a_oix[APT];
     bool a_ok[APT];
 #pragma unroll
     for (int i = 0; i < APT; ++i) {
-        long long m = m0 + (tid >> 2) + 64 * i;
-        a_ok[i] = m < M;
+        long long m = m0 + ld_row + 64 * i;
+        a_ok[i] = (ld_row + 64 * i < BM) && m < M;
         long long mm = a_ok[i] ? m : 0;
         int r = (int)(mm / opix);
         int rem = (int)(mm - (long long)r * opix);
         int a = rem / p.owx, bb = rem - a * p.owx;
         RowInfo ri = row_info(p.rm, r);
-        int ooy = clampi(p.oSy * ri.ys - p.oPy, 0, p.Ho - p.owy);
-        int oox = clampi(p.oSx * ri.xs - p.oPx, 0, p.Wo - p.owx);
-        a_A[i] = ooy + a;
-        a_B[i] = oox + bb;
+        a_A[i] = clampi(p.oSy * ri.ys - p.oPy, 0, p.Ho - p.owy) + a + p.ph;
+        a_B[i] = clampi(p.oSx * ri.xs - p.oPx, 0, p.Wo - p.owx) + bb + p.pw;
         a_oiy[i] = clampi(p.in.Sy * ri.ys - p.in.Py, 0, p.in.H - p.in.wy);
         a_oix[i] = clampi(p.in.Sx * ri.xs - p.in.Px, 0, p.in.W - p.in.wx);
-        a_base[i] = p.in.data + (size_t)r * ((size_t)p.in.wy * p.in.wx * Ck);
-        a_rbase[i] = (long long)ri.b * ((long long)p.in.H * p.in.W * Ck);
+        a_rowoff[i] = (long long)r * ((long long)p.in.wy * p.in.wx * Ck);
     }
-
-    // global -> register staging holds the raw float32 words only, so that nothing depends on the
-    // loads before the MFMA loop of the current tile has been issued; conversion happens at the
-    // register -> LDS copy
-    float4 a_raw[APT], a_gam[APT], a_lam[APT];
-    float4 b_raw[BPT];
-
-    auto load_tiles = [&](int it) {
-        const int t = it / kchunks;
-        const int d0 = (it - t * kchunks) * BK;
+    long long a_src[APT];
+    bool a_tapok[APT];
+    auto set_tap = [&](int t) {
         const int f = t / p.kw, g = t - f * p.kw;
-        // A
 #pragma unroll
         for (int i = 0; i < APT; ++i) {
-            a_raw[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-            a_gam[i] = make_float4(1.f, 1.f, 1.f, 1.f);
-            a_lam[i] = make_float4(1.f, 1.f, 1.f, 1.f);
-            if (!a_ok[i]) continue;
-            int yy = a_A[i] + p.ph - f, xx = a_B[i] + p.pw - g;
-            if (yy < 0 || xx < 0) continue;
+            int yy = a_A[i] - f, xx = a_B[i] - g;
             int y = yy / p.sh, x = xx / p.sw;
-            if (y * p.sh != yy || x * p.sw != xx || y >= p.in.H || x >= p.in.W) continue;
+            bool ok = a_ok[i] && yy >= 0 && xx >= 0 && y * p.sh == yy && x * p.sw == xx && y < p.in.H && x < p.in.W;
             int yi = y - a_oiy[i], xi = x - a_oix[i];
-            if (yi < 0 || yi >= p.in.wy || xi < 0 || xi >= p.in.wx) continue;
-            const int d = d0 + 4 * q;
-            if (d >= Ck) continue;
-            const float* src = a_base[i] + ((size_t)(yi * p.in.wx + xi) * Ck + d);
-            const long long ridx = a_rbase[i] + ((long long)(y * p.in.W + x) * Ck + d);
-            if (vecA) {
-                a_raw[i] = *reinterpret_cast<const float4*>(src);
-                if (relax) {
-                    a_gam[i] = *reinterpret_cast<const float4*>(p.in.gam + ridx);
-                    a_lam[i] = *reinterpret_cast<const float4*>(p.in.lam + ridx);
-                }
-            } else {
-                float v[4] = {0.f, 0.f, 0.f, 0.f}, gm[4] = {1.f, 1.f, 1.f, 1.f}, lm[4] = {1.f, 1.f, 1.f, 1.f};
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (d + j < Ck) {
-                        v[j] = src[j];
-                        if (relax) { gm[j] = p.in.gam[ridx + j]; lm[j] = p.in.lam[ridx + j]; }
-                    }
-                a_raw[i] = make_float4(v[0], v[1], v[2], v[3]);
-                a_gam[i] = make_float4(gm[0], gm[1], gm[2], gm[3]);
-                a_lam[i] = make_float4(lm[0], lm[1], lm[2], lm[3]);
-            }
-        }
-        // B
-#pragma unroll
-        for (int i = 0; i < BPT; ++i) {
-            b_raw[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-            int idx = tid + 256 * i;
-            if (idx >= BK * BN / 4) continue;
-            int kk = idx / (BN / 4), nq = idx - kk * (BN / 4);
-            int d = d0 + kk, n = n0 + 4 * nq;
-            if (d >= Ck || n >= N) continue;
-            const float* src = p.wt + ((size_t)(t * Ck + d) * N + n);
-            if (vecB) {
-                b_raw[i] = *reinterpret_cast<const float4*>(src);
-            } else {
-                float v[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (n + j < N) v[j] = src[j];
-                b_raw[i] = make_float4(v[0], v[1], v[2], v[3]);
-            }
+            ok = ok && yi >= 0 && yi < p.in.wy && xi >= 0 && xi < p.in.wx;
+            a_tapok[i] = ok;
+            a_src[i] = a_rowoff[i] + (long long)(yi * p.in.wx + xi) * Ck;
         }
     };
+    long long b_off[BPT];
+    bool b_ok[BPT];
+#pragma unroll
+    for (int i = 0; i < BPT; ++i) {
+        int n = n0 + ld_row + 64 * i;
+        b_ok[i] = (ld_row + 64 * i < BN) && n < N;
+        b_off[i] = (long long)(b_ok[i] ? n : 0) * Ck;
+    }
 
-    auto relaxed = [&](float v, float gm, float lm) -> double {
-        // coefficient after the pending ReLU substitution; float32 x float32 is exact in float64
-        return relax ? (double)v * (double)(v >= 0.f ? gm : lm) : (double)v;
+    // global -> register staging holds raw float32 words only: nothing depends on the loads until the
+    // MFMA loop of the current tile has been issued; conversion happens at the register -> LDS copy
+    F4 a_raw[APT], b_raw[BPT];
+    int ld_t = 0, ld_d0 = 0;
+    set_tap(0);
+    auto load_tiles = [&]() {
+        const int d = ld_d0 + q4;
+        const bool dok = d < Ck;
+#pragma unroll
+        for (int i = 0; i < APT; ++i) {
+            const bool ok = a_tapok[i] && dok;
+            a_raw[i] = ld4<VEC>(p.in.data, a_src[i] + d, ok, Ck - d);
+        }
+        const long long tbase = (long long)ld_t * N * Ck + d;
+#pragma unroll
+        for (int i = 0; i < BPT; ++i) b_raw[i] = ld4<VEC>(p.wt, tbase + b_off[i], b_ok[i] && dok, Ck - d);
+        ld_d0 += BK;
+        if (ld_d0 >= Ck) {
+            ld_d0 = 0;
+            ++ld_t;
+            if (ld_t < taps) set_tap(ld_t);
+        }
     };
-
     auto store_tiles = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < APT; ++i) {
-            int pm = (tid >> 2) + 64 * i;
-            As[buf][4 * q + 0][pm] = relaxed(a_raw[i].x, a_gam[i].x, a_lam[i].x);
-            As[buf][4 * q + 1][pm] = relaxed(a_raw[i].y, a_gam[i].y, a_lam[i].y);
-            As[buf][4 * q + 2][pm] = relaxed(a_raw[i].z, a_gam[i].z, a_lam[i].z);
-            As[buf][4 * q + 3][pm] = relaxed(a_raw[i].w, a_gam[i].w, a_lam[i].w);
+            const int row = ld_row + 64 * i;
+            if (row < BM) {
+                double2* dst = reinterpret_cast<double2*>(&As[buf][row][q4]);
+                dst[0] = make_double2((double)a_raw[i].v[0], (double)a_raw[i].v[1]);
+                dst[1] = make_double2((double)a_raw[i].v[2], (double)a_raw[i].v[3]);
+            }
         }
 #pragma unroll
         for (int i = 0; i < BPT; ++i) {
-            int idx = tid + 256 * i;
-            if (idx >= BK * BN / 4) continue;
-            int kk = idx / (BN / 4), nq = idx - kk * (BN / 4);
-            Bs[buf][kk][4 * nq + 0] = (double)b_raw[i].x;
-            Bs[buf][kk][4 * nq + 1] = (double)b_raw[i].y;
-            Bs[buf][kk][4 * nq + 2] = (double)b_raw[i].z;
-            Bs[buf][kk][4 * nq + 3] = (double)b_raw[i].w;
+            const int row = ld_row + 64 * i;
+            if (row < BN) {
+                double2* dst = reinterpret_cast<double2*>(&Bs[buf][row][q4]);
+                dst[0] = make_double2((double)b_raw[i].v[0], (double)b_raw[i].v[1]);
+                dst[1] = make_double2((double)b_raw[i].v[2], (double)b_raw[i].v[3]);
+            }
         }
     };
 
@@ -201,33 +210,40 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = double4_t{0.0, 0.0, 0.0, 0.0};
 
-    load_tiles(0);
+    load_tiles();
     store_tiles(0);
     __syncthreads();
-    const int lk = lane >> 4, lm = lane & 15;
     for (int it = 0; it < nIt; ++it) {
         const int buf = it & 1;
-        if (it + 1 < nIt) load_tiles(it + 1);
+        if (it + 1 < nIt) load_tiles();
 #pragma unroll
-        for (int kk = 0; kk < BK; kk += 4) {
-            double av[TM], bv[TN];
+        for (int h = 0; h < 2; ++h) {              // two halves of the lane's 4 k-values: one 16-byte LDS load each
+            double2 av[TM], bv[TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) av[i] = As[buf][kk + lk][wm * WTM + i * 16 + lm];
+            for (int i = 0; i < TM; ++i)
+                av[i] = *reinterpret_cast<const double2*>(&As[buf][wm * WTM + i * 16 + lm][4 * lk + 2 * h]);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) bv[j] = Bs[buf][kk + lk][wn * WTN + j * 16 + lm];
+            for (int j = 0; j < TN; ++j)
+                bv[j] = *reinterpret_cast<const double2*>(&Bs[buf][wn * WTN + j * 16 + lm][4 * lk + 2 * h]);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[i], bv[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[i].x, bv[j].x, acc[i][j], 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[i].y, bv[j].y, acc[i][j], 0, 0, 0);
         }
         if (it + 1 < nIt) store_tiles(buf ^ 1);
         __syncthreads();
     }
 
-    // ---- epilogue: (+ residual addend) -> one rounding to float32 -> store
+    // ---- epilogue: (+ residual addend) (* ReLU substitution of the destination layer) -> one rounding to
+    // float32 -> store.  D[i][j]: register r of lane l holds i = 4*r + l/16, j = l%16.
     const bool has_add = p.add.data != nullptr;
-    const bool add_relax = has_add && p.add.gam != nullptr;
+    const bool need_pos = has_add || p.out_grl != nullptr;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -235,19 +251,20 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
             const long long m = m0 + wm * WTM + i * 16 + 4 * r4 + lk;
             if (m >= M) continue;
             const float* add_src = nullptr;
-            long long add_ridx = 0;
-            if (has_add) {
+            long long ridx = 0;
+            if (need_pos) {
                 int r = (int)(m / opix);
                 int rem = (int)(m - (long long)r * opix);
                 int a = rem / p.owx, bb = rem - a * p.owx;
                 RowInfo ri = row_info(p.rm, r);
                 int A = clampi(p.oSy * ri.ys - p.oPy, 0, p.Ho - p.owy) + a;
                 int B = clampi(p.oSx * ri.xs - p.oPx, 0, p.Wo - p.owx) + bb;
-                int ay = A - clampi(p.add.Sy * ri.ys - p.add.Py, 0, p.add.H - p.add.wy);
-                int ax = B - clampi(p.add.Sx * ri.xs - p.add.Px, 0, p.add.W - p.add.wx);
-                if (ay >= 0 && ay < p.add.wy && ax >= 0 && ax < p.add.wx) {
-                    add_src = p.add.data + ((size_t)r * p.add.wy * p.add.wx + (size_t)(ay * p.add.wx + ax)) * N;
-                    add_ridx = (long long)ri.b * ((long long)p.Ho * p.Wo * N) + (long long)(A * p.Wo + B) * N;
+                ridx = (long long)ri.b * ((long long)p.Ho * p.Wo * N) + (long long)(A * p.Wo + B) * N;
+                if (has_add) {
+                    int ay = A - clampi(p.add.Sy * ri.ys - p.add.Py, 0, p.add.H - p.add.wy);
+                    int ax = B - clampi(p.add.Sx * ri.xs - p.add.Px, 0, p.add.W - p.add.wx);
+                    if (ay >= 0 && ay < p.add.wy && ax >= 0 && ax < p.add.wx)
+                        add_src = p.add.data + ((size_t)r * p.add.wy * p.add.wx + (size_t)(ay * p.add.wx + ax)) * N;
                 }
             }
 #pragma unroll
@@ -255,12 +272,8 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
                 const int n = n0 + wn * WTN + j * 16 + lm;
                 if (n >= N) continue;
                 double v = acc[i][j][r4];
-                if (add_src) {
-                    float av = add_src[n];
-                    double ad = (double)av;
-                    if (add_relax) ad *= (double)(av >= 0.f ? p.add.gam[add_ridx + n] : p.add.lam[add_ridx + n]);
-                    v += ad;
-                }
+                if (add_src) v += (double)add_src[n];
+                if (p.out_grl) v *= (double)relax_factor(v, p.out_grl[ridx + n]);
                 p.out[(size_t)m * N + n] = (float)v;
             }
         }
@@ -271,29 +284,43 @@ template <int BM, int BN>
 static void launch_cross_t(const CrossParams& p, hipStream_t s) {
     long long M = (long long)p.nrows * p.owy * p.owx;
     dim3 grid((unsigned)((M + BM - 1) / BM), (unsigned)((p.Co + BN - 1) / BN));
-    hipLaunchKernelGGL((cross_kernel<BM, BN>), grid, dim3(256), 0, s, p);
+    const bool vec = (p.in.C & 3) == 0;
+    if (vec) hipLaunchKernelGGL((cross_kernel<BM, BN, true>), grid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((cross_kernel<BM, BN, false>), grid, dim3(256), 0, s, p);
 }
 
 void launch_cross(const CrossParams& p, hipStream_t s) {
     long long M = (long long)p.nrows * p.owy * p.owx;
     if (M <= 0 || p.Co <= 0) return;
     const int N = p.Co;
+    static const char* tile_env = getenv("GP_TILE");
+    if (tile_env && N > 32) {
+        if (!strcmp(tile_env, "128x128")) { launch_cross_t<128, 128>(p, s); return; }
+        if (!strcmp(tile_env, "128x64")) { launch_cross_t<128, 64>(p, s); return; }
+        if (!strcmp(tile_env, "64x128")) { launch_cross_t<64, 128>(p, s); return; }
+        if (!strcmp(tile_env, "64x64")) { launch_cross_t<64, 64>(p, s); return; }
+    }
     if (N <= 16) { launch_cross_t<128, 16>(p, s); return; }
     if (N <= 32) { launch_cross_t<128, 32>(p, s); return; }
-    // enough work-groups to fill 256 compute units?
-    long long wg128 = ((M + 127) / 128) * ((N + 127) / 128);
-    if (N > 64 && wg128 >= 512) { launch_cross_t<128, 128>(p, s); return; }
-    long long wg64 = ((M + 127) / 128) * ((N + 63) / 64);
-    if (wg64 >= 512) { launch_cross_t<128, 64>(p, s); return; }
+    // enough work-groups to fill 256 compute units several times over?
+    long long wg = ((M + 127) / 128) * ((N + 63) / 64);
+    if (wg >= 1024) { launch_cross_t<128, 64>(p, s); return; }
     launch_cross_t<64, 64>(p, s);
 }
 
 // ------------------------------------------------------------------------------------------------
-// Per-row reductions over a block (one work-group per row):
-//   candidate  sum_j (m_j >= 0 ? m_j*U_j : m_j*L_j)                         (Section 2, candidate bound)
-//   rounding   sum_j |m_j| * max(|L_j|,|U_j|)                               (slack of the float32 storage)
-//   constants of the next step: sum_j max(m_j,0)*del_j + a_j*bias_c, a_j = m_j*(m_j>=0?gam_j:lam_j)
-//   S1 = sum_j |a_j|                                                        (slack of the next accumulation)
+// Per-row reductions over a block:
+//   candidate  sum_j (m_j >= 0 ? m_j*cpos_j : m_j*cneg_j)                   (Section 2, candidate bound)
+//   rounding   sum_j |m_j| * max(|xlo_j|,|xhi_j|)                           (slack of the float32 storage)
+//   constants of the next step: sum_j max(m_j,0)*kap_j + m_j*bias_c
+//   S1 = sum_j |m_j|                                                        (slack of the next accumulation)
+// For a block over a plain layer cpos/cneg are the layer's upper/lower interval ends.  A block whose
+// coefficients already went through a ReLU substitution holds m = M*slope (M >= 0) or m = M*lam (M < 0)
+// over the ReLU's INPUT; the candidate over the ReLU's OUTPUT interval [L,U] that DeepPoly takes before
+// the substitution is recovered as M*U = m*(U/slope) =: m*rho and M*L = m*L (L = 0 unless the neuron is
+// stably active, where lam = 1), and the intercept term M*del = m*(del/slope) =: m*kap.
+// A work-group handles SCAN_ROWS rows: one wave per row for short rows, all four waves on one row
+// for long ones.
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ double wave_sum(double v) {
 #pragma unroll
@@ -301,67 +328,84 @@ __device__ __forceinline__ double wave_sum(double v) {
     return v;
 }
 
+template <int ROWS_PER_WG>
 __global__ __launch_bounds__(256) void scan_kernel(const ScanParams p) {
-    const int r = blockIdx.x;
+    constexpr int TPR = 256 / ROWS_PER_WG;        // threads per row: 256 or 64
     const int tid = threadIdx.x;
+    const int r = blockIdx.x * ROWS_PER_WG + tid / TPR;
+    const int t = tid % TPR;
+    const bool row_ok = r < p.nrows;
     const BlockDesc& B = p.blk;
-    const RowInfo ri = row_info(p.rm, r);
+    const RowInfo ri = row_info(p.rm, row_ok ? r : 0);
     const int oy = clampi(B.Sy * ri.ys - B.Py, 0, B.H - B.wy);
     const int ox = clampi(B.Sx * ri.xs - B.Px, 0, B.W - B.wx);
     const int nelem = B.wy * B.wx * B.C;
-    const float* src = B.data + (size_t)r * nelem;
+    const float* src = B.data + (size_t)(row_ok ? r : 0) * nelem;
     const long long bbase = (long long)ri.b * p.batch_stride;
+    const bool full_row = (B.wx == B.W);          // window rows are contiguous in the layer
     double cand = 0, absx = 0, cst = 0, cstabs = 0, s1 = 0;
-    for (int e = tid; e < nelem; e += 256) {
-        const float mf = src[e];
-        if (mf == 0.f) continue;
-        const double m = (double)mf;
-        int pix = e / B.C, c = e - pix * B.C;
-        int a = pix / B.wx, bb = pix - a * B.wx;
-        const long long j = bbase + ((long long)((oy + a) * B.W + (ox + bb)) * B.C + c);
-        if (p.lo) {
-            const double L = p.lo[j], U = p.hi[j];
-            cand += (m >= 0.0) ? m * U : m * L;
-            absx += fabs(m) * fmax(fabs(L), fabs(U));
-        }
-        if (p.do_consts) {
-            double av = m;
-            if (p.gam) {
-                av = m * (double)(mf >= 0.f ? p.gam[j] : p.lam[j]);
-                if (mf > 0.f && p.del) {
-                    double t = m * p.del[j];
-                    cst += t;
-                    cstabs += t;
+    if (row_ok) {
+        for (int e = t; e < nelem; e += TPR) {
+            const float mf = src[e];
+            if (mf == 0.f) continue;
+            const double m = (double)mf;
+            int c;
+            long long j;
+            if (full_row) {
+                c = e % B.C;
+                j = bbase + (long long)oy * B.W * B.C + e;
+            } else {
+                int pix = e / B.C;
+                c = e - pix * B.C;
+                int a = pix / B.wx, bb = pix - a * B.wx;
+                j = bbase + ((long long)((oy + a) * B.W + (ox + bb)) * B.C + c);
+            }
+            if (p.cpos) {
+                cand += (m >= 0.0) ? m * p.cpos[j] : m * p.cneg[j];
+                absx += fabs(m) * fmax(fabs(p.xlo[j]), fabs(p.xhi[j]));
+            }
+            if (p.do_consts) {
+                if (p.kap && mf > 0.f) {
+                    double tt = m * p.kap[j];
+                    cst += tt;
+                    cstabs += tt;
+                }
+                s1 += fabs(m);
+                if (p.beff) {
+                    double tt = m * p.beff[c];
+                    cst += tt;
+                    cstabs += fabs(tt);
                 }
             }
-            s1 += fabs(av);
-            if (p.beff) {
-                double t = av * p.beff[c];
-                cst += t;
-                cstabs += fabs(t);
-            }
         }
     }
-    __shared__ double red[5][4];
     cand = wave_sum(cand); absx = wave_sum(absx); cst = wave_sum(cst); cstabs = wave_sum(cstabs); s1 = wave_sum(s1);
-    if ((tid & 63) == 0) {
-        int w = tid >> 6;
-        red[0][w] = cand; red[1][w] = absx; red[2][w] = cst; red[3][w] = cstabs; red[4][w] = s1;
+    if (TPR > 64) {
+        __shared__ double red[5][4];
+        if ((tid & 63) == 0) {
+            int w = tid >> 6;
+            red[0][w] = cand; red[1][w] = absx; red[2][w] = cst; red[3][w] = cstabs; red[4][w] = s1;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            cand = red[0][0] + red[0][1] + red[0][2] + red[0][3];
+            absx = red[1][0] + red[1][1] + red[1][2] + red[1][3];
+            cst = red[2][0] + red[2][1] + red[2][2] + red[2][3];
+            cstabs = red[3][0] + red[3][1] + red[3][2] + red[3][3];
+            s1 = red[4][0] + red[4][1] + red[4][2] + red[4][3];
+        }
     }
-    __syncthreads();
-    if (tid == 0) {
-        cand = red[0][0] + red[0][1] + red[0][2] + red[0][3];
-        absx = red[1][0] + red[1][1] + red[1][2] + red[1][3];
-        cst = red[2][0] + red[2][1] + red[2][2] + red[2][3];
-        cstabs = red[3][0] + red[3][1] + red[3][2] + red[3][3];
-        s1 = red[4][0] + red[4][1] + red[4][2] + red[4][3];
+    if (t == 0 && row_ok) {
         // a sum of n float64 terms in any order is off by at most (n-1)*2^-53*sum|terms|*(1+tiny)
         const double esum = (double)(nelem + 16) * 0x1p-52;
         double c = p.c[r];
         double err = p.err[r];
         // slack of the stored coefficients: |true - stored| <= round_coef*|stored| (+ subnormal floor)
-        err += absx * p.round_coef * (1.0 + esum) + (p.round_coef > 0.0 ? 0x1p-140 * (double)nelem : 0.0);
-        if (p.update_best && p.lo) {
+        err += absx * p.round_coef * (1.0 + esum);
+        // values below the float32 subnormal step vanish; with a substituted ReLU the lost coefficient is
+        // up to 2^20 times larger (slopes are kept >= 2^-20)
+        if (p.round_coef > 0.0 && p.xmax_self) err += 0x1p-128 * (double)nelem * p.xmax_self[ri.b];
+        if (p.update_best && p.cpos) {
             double v = c + cand + err;
             v += (fabs(c) + fabs(cand) + err) * 0x1p-50 + absx * esum;
             p.best[r] = fmin(p.best[r], v);
@@ -382,10 +426,17 @@ __global__ __launch_bounds__(256) void scan_kernel(const ScanParams p) {
 
 void launch_scan(const ScanParams& p, hipStream_t s) {
     if (p.nrows <= 0) return;
-    hipLaunchKernelGGL(scan_kernel, dim3(p.nrows), dim3(256), 0, s, p);
+    const int nelem = p.blk.wy * p.blk.wx * p.blk.C;
+    if (nelem <= 1024) hipLaunchKernelGGL((scan_kernel<4>), dim3((p.nrows + 3) / 4), dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((scan_kernel<1>), dim3(p.nrows), dim3(256), 0, s, p);
 }
 
 // ------------------------------------------------------------------------------------------------
+// Initial expressions (Section 2: the affine layer's own row; Section 4.3: M^{l-1}(x_i) = the filter taps).
+//   mode 0: one-hot +/-1 over the start layer itself (sum layers)
+//   mode 1: e_j - e_label over the whole last layer (certification rows)
+//   mode 2: +/- the row of the start layer's matrix, i.e. its filter placed in the window over the
+//           predecessor; constant = +/- bias.  Exact: no rounding.
 __global__ void init_kernel(const InitParams p) {
     const long long total = (long long)p.nrows * p.nelem;
     for (long long idx = blockIdx.x * (long long)blockDim.x + threadIdx.x; idx < total;
@@ -394,9 +445,10 @@ __global__ void init_kernel(const InitParams p) {
         int e = (int)(idx - (long long)r * p.nelem);
         RowInfo ri = row_info(p.rm, r);
         float v = 0.f;
-        if (!p.certify) {
+        double c0 = 0.0;
+        if (p.mode == 0) {
             v = (e == ri.cs) ? ri.sign : 0.f;
-        } else {
+        } else if (p.mode == 1) {
             // task cs = index among the other classes, block order is H,W,C; classes are numbered C,H,W
             int label = p.labels[ri.b];
             int j = ri.cs + (ri.cs >= label ? 1 : 0);
@@ -404,10 +456,27 @@ __global__ void init_kernel(const InitParams p) {
             int chw = c * (p.H * p.W) + pix;
             if (chw == j) v = 1.f;
             else if (chw == label) v = -1.f;
+        } else {
+            // window over the predecessor (dims H,W,C here), origin from the row's position
+            int pix = e / p.C, c = e - pix * p.C;
+            int a = pix / p.wx, bb = pix - a * p.wx;
+            int A = clampi(p.Sy * ri.ys - p.Py, 0, p.H - p.wy) + a;
+            int B = clampi(p.Sx * ri.xs - p.Px, 0, p.W - p.wx) + bb;
+            int f = A - (ri.ys * p.sh - p.ph), g = B - (ri.xs * p.sw - p.pw);
+            if (p.dense) {
+                v = ri.sign * p.wt[(size_t)ri.cs * p.nelem + e];
+            } else if (f >= 0 && f < p.kh && g >= 0 && g < p.kw) {
+                v = ri.sign * p.wt[((size_t)(f * p.kw + g) * p.Cs + ri.cs) * p.C + c];
+            }
+            c0 = (double)(ri.sign * p.bias[ri.cs]);
+            if (p.out_grl && v != 0.f) {
+                long long j = (long long)ri.b * ((long long)p.H * p.W * p.C) + (long long)(A * p.W + B) * p.C + c;
+                v = (float)((double)v * (double)relax_factor((double)v, p.out_grl[j]));
+            }
         }
         p.out[idx] = v;
         if (e == 0) {
-            p.c[r] = 0.0;
+            p.c[r] = c0;
             p.err[r] = 0.0;
             p.best[r] = INFINITY;
         }
@@ -417,7 +486,7 @@ __global__ void init_kernel(const InitParams p) {
 void launch_init(const InitParams& p, hipStream_t s) {
     long long total = (long long)p.nrows * p.nelem;
     if (total <= 0) return;
-    int blocks = (int)fmin((double)((total + 255) / 256), 65536.0);
+    int blocks = (int)fmin((double)((total + 255) / 256), 262144.0);
     hipLaunchKernelGGL(init_kernel, dim3(blocks), dim3(256), 0, s, p);
 }
 
@@ -454,21 +523,24 @@ __global__ void relu_kernel(const ReluParams p) {
     p.lo[i] = fmax(l, 0.0);
     p.hi[i] = fmax(u, 0.0);
     float g, lam;
-    double d = 0.0;
-    if (l >= 0.0) { g = 1.f; lam = 1.f; }
+    double rho = 0.0, kap = 0.0;
+    if (l >= 0.0) { g = 1.f; lam = 1.f; rho = u; }
     else if (u <= 0.0) { g = 0.f; lam = 0.f; }
     else {
         g = (float)(u / (u - l));
-        g = fminf(fmaxf(g, 0.f), 1.f);
+        g = fminf(fmaxf(g, 0x1p-20f), 1.f);       // a positive coefficient must stay recoverable from its product with g
         double gd = (double)g;
         double d1 = -gd * l, d2 = u - gd * u;     // each off by a few ulps at most
-        d = fmax(d1, d2);
+        double d = fmax(d1, d2);
         d = d + (fabs(d) + fabs(u)) * 0x1p-50 + 0x1p-1000;
         lam = (u > -l) ? 1.f : 0.f;
+        // rounded up, including the float32 rounding of the stored product coefficient*g
+        rho = (u / gd) * (1.0 + 0x1p-22);
+        kap = (d / gd) * (1.0 + 0x1p-22);
     }
-    p.gam[i] = g;
-    p.lam[i] = lam;
-    p.del[i] = d;
+    p.grl[i] = lam != 0.f ? g : -g;      // -0.0f encodes slope 0 with lam = 0
+    p.rho[i] = rho;
+    p.kap[i] = kap;
     double x = fmax(u, 0.0);
     if (isfinite(x)) atomic_max_nonneg(p.xmax + i / p.n, x);
 }

@@ -28,15 +28,16 @@ struct BlockDesc {
     int H, W, C;         // dims of the layer the block ranges over
     int wy, wx;          // window size (already clipped to the layer)
     int Sy, Sx, Py, Px;  // window origin of a row at (ys,xs): clamp(S*ys - P, 0, H - wy)  (eqs. 6-9 with padding)
-    const float* gam;    // pending ReLU substitution: coefficient a stands for a*(a>=0 ? gam : lam);
-    const float* lam;    //   [batch][H*W*C]; null when none
 };
 
 struct CrossParams {       // one back-substitution step through an affine layer (Algorithm 1 per row)
     BlockDesc in;          // block over the layer's OUTPUT neurons
-    const float* wt;       // [kh*kw][C_out_of_layer = in.C][Co]  (Co innermost)
+    const float* wt;       // [kh*kw][Co][in.C]  (the layer's own output channels innermost)
     int kh, kw, sh, sw, ph, pw;
     float* out;            // new block over the layer's INPUT neurons
+    const float* out_grl;  // when the input layer is a ReLU layer and the block is complete: its packed relaxation
+                           //   [batch][Ho*Wo*Co] (|g| = upper slope; sign bit set = lower slope 0, clear = 1), applied to
+                           //   the new coefficients before they are rounded and stored; null: store as is
     int Ho, Wo, Co;        // dims of the input layer
     int owy, owx, oSy, oSx, oPy, oPx;
     BlockDesc add;         // optional block over the same input layer to be summed in (residual join)
@@ -49,15 +50,16 @@ struct ScanParams {        // per-row reductions over a block
     RowMap rm;
     int nrows;
     int batch_stride;      // H*W*C
-    const double* lo;      // intervals of the block's layer [batch][n]; null: no candidate, no rounding term
-    const double* hi;
-    const float* gam;      // relaxation that the NEXT step applies to this block (its layer is a ReLU); null if none
-    const float* lam;
-    const double* del;
+    const double* cpos;    // candidate multiplier of a positive / negative coefficient, [batch][n]; null: no candidate
+    const double* cneg;    //   (a layer's own upper / lower interval ends, or rho / lower end after a ReLU substitution)
+    const double* xlo;     // intervals of the neurons the STORED coefficients multiply (rounding slack); null with cpos
+    const double* xhi;
+    const double* kap;     // constant per unit of positive coefficient (ReLU upper intercept / slope); null if none
     const double* beff;    // [C] bias of the affine layer(s) crossed next; null if none
     double e1_a, e1_b;     // accumulation-error constants of the next crossing(s), times xmax_a[box] / xmax_b[box]
     const double* xmax_a;
     const double* xmax_b;
+    const double* xmax_self; // [batch] largest |bound| of the block's own layer (subnormal floor of the rounding slack)
     double round_coef;     // relative rounding error of the stored coefficients (0 for exact blocks)
     int do_consts;         // add the constants of the next step (relaxation intercepts, bias) to c
     int update_best;       // the expression ranges over this layer only: fold the candidate into best
@@ -67,13 +69,20 @@ struct ScanParams {        // per-row reductions over a block
 };
 
 struct InitParams {
-    float* out;            // identity block over the start layer: [nrows][1][1][Cs]  (or full layer for certify)
+    float* out;            // [nrows][nelem]
     RowMap rm;
     int nrows;
     int nelem;             // elements per row
-    const int* labels;     // certify only: [batch]
-    int certify;           // 0: one-hot +/-1 at the row's own channel; 1: e_j - e_label over the full layer
-    int H, W, C;           // certify: dims of the last layer (to map C,H,W numbering to the block order)
+    int mode;              // 0: one-hot over the start layer; 1: certification rows; 2: the start layer's own matrix row
+    const float* out_grl;  // mode 2: packed relaxation of the predecessor when it is a ReLU layer (applied), else null
+    const int* labels;     // mode 1: [batch]
+    int H, W, C;           // dims of the layer the block ranges over (mode 1: last layer; mode 2: predecessor)
+    // mode 2: window geometry over the predecessor and the start layer's filter
+    int wy, wx, Sy, Sx, Py, Px;
+    int kh, kw, sh, sw, ph, pw, dense;
+    int Cs;                // channels of the start layer
+    const float* wt;       // [tap][Cs][C] (predecessor channels innermost); dense: [Cs][nelem]
+    const float* bias;     // [Cs]
     double* c; double* err; double* best;
 };
 
@@ -88,7 +97,8 @@ struct FinalizeParams {
 struct ReluParams {
     const double* plo; const double* phi;   // predecessor intervals [total]
     double* lo; double* hi;                 // this layer's intervals
-    float* gam; float* lam; double* del;
+    float* grl;                             // packed relaxation (slope, lower choice)
+    double* rho; double* kap;               // u/slope and intercept/slope, rounded up (see scan kernel)
     double* xmax; int* flag;
     long long total;                        // batch * n
     long long n;                            // neurons per box
