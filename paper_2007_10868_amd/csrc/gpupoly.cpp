@@ -502,7 +502,15 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
     gp_status st = get_workspace(net, tb * total + 4096, &ws, &ws_bytes);
     if (st != GP_OK) return st;
     long long Rc_max = (ws_bytes - 4096) / tb;
-    Rc_max = std::min(Rc_max, (long long)(1 << 28) / nsign);
+    if (total >= (1LL << 31)) return fail(net, GP_ERR_SHAPE, "batch * layer size must stay below 2^31");
+    // rows * window pixels of any step must stay below 2^31 (32-bit indexing in the kernels)
+    long long max_pix = 1;
+    for (const PlanOp& op : pl.ops)
+        if (op.kind == PlanOp::CROSS) {
+            const Layer& pp = net->L[op.layer_out];
+            max_pix = std::max(max_pix, (long long)std::min(op.g_out.Wy, pp.H) * std::min(op.g_out.Wx, pp.W));
+        }
+    Rc_max = std::min(Rc_max, ((1LL << 31) - 256) / (nsign * max_pix));
     // keep M = rows * window pixels below 2^31 work-groups' worth and int-safe
     if (Rc_max <= 0) return fail(net, GP_ERR_WORKSPACE, "workspace of %lld bytes cannot hold one row (%lld bytes)", ws_bytes, tb);
     Rc_max = std::min(Rc_max, total);
@@ -520,12 +528,15 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
 
     for (long long row0 = 0; row0 < total; row0 += Rc_max) {
         gp::RowMap rm;
-        rm.row0 = row0;
+        rm.row0 = (int)row0;
         rm.Rc = (int)std::min(Rc_max, total - row0);
         rm.nsign = nsign;
         rm.n_start = (int)n_start;
         if (certify) { rm.Hs = 1; rm.Ws = 1; rm.Cs = (int)n_start; }
         else { rm.Hs = ls.H; rm.Ws = ls.W; rm.Cs = ls.C; }
+        rm.div_n = gp::make_fastdiv((uint32_t)rm.n_start);
+        rm.div_c = gp::make_fastdiv((uint32_t)rm.Cs);
+        rm.div_w = gp::make_fastdiv((uint32_t)rm.Ws);
         const int nrows = rm.Rc * nsign;
         for (const PlanOp& op : pl.ops) {
             if (op.kind == PlanOp::INIT) {
@@ -612,6 +623,10 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                     if (op.slot_add >= 0) cp.add = make_desc(net, slot_ptr(op.slot_add), op.g_add, op.layer_out);
                 }
                 cp.rm = rm; cp.nrows = nrows;
+                cp.div_opix = gp::make_fastdiv((uint32_t)(cp.owy * cp.owx));
+                cp.div_owx = gp::make_fastdiv((uint32_t)cp.owx);
+                cp.div_sh = gp::make_fastdiv((uint32_t)cp.sh);
+                cp.div_sw = gp::make_fastdiv((uint32_t)cp.sw);
                 prof_mark(net, 0, false);
                 gp::launch_cross(cp, net->stream);
                 prof_mark(net, 0, true);

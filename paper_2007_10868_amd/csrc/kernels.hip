@@ -31,13 +31,15 @@ __device__ __forceinline__ RowInfo row_info(const RowMap& rm, int r) {
         rr = r - rm.Rc;
         ri.sign = -1.f;
     }
-    long long g = rm.row0 + rr;
-    ri.b = (int)(g / rm.n_start);
-    int i = (int)(g - (long long)ri.b * rm.n_start);
-    int pos = i / rm.Cs;
-    ri.cs = i - pos * rm.Cs;
-    ri.ys = pos / rm.Ws;
-    ri.xs = pos - ri.ys * rm.Ws;
+    const uint32_t g = (uint32_t)(rm.row0 + rr);
+    const uint32_t b = fast_div(g, rm.div_n);
+    const uint32_t i = g - b * (uint32_t)rm.n_start;
+    const uint32_t pos = fast_div(i, rm.div_c);
+    const uint32_t ys = fast_div(pos, rm.div_w);
+    ri.b = (int)b;
+    ri.cs = (int)(i - pos * (uint32_t)rm.Cs);
+    ri.ys = (int)ys;
+    ri.xs = (int)(pos - ys * (uint32_t)rm.Ws);
     return ri;
 }
 
@@ -50,24 +52,28 @@ __device__ __forceinline__ RowInfo row_info(const RowMap& rm, int r) {
 // B operand: filter taps [tap][C_out][C_in].
 // float64 MFMA 16x16x4; accumulators D[i][j]: lane l, register r holds i = 4*r + l/16, j = l%16.
 // ------------------------------------------------------------------------------------------------
+typedef unsigned int uint4_t __attribute__((ext_vector_type(4)));
+
 struct F4 {
     float v[4];
 };
 
-// 4 consecutive floats from base[off..off+3]; elements beyond `nvalid` (and everything when !ok) read as 0.
-// Loads are unconditional from a clamped address so that the compiler emits straight-line code.
+constexpr uint32_t kOOB = 0x80000000u;   // byte offset beyond every buffer range: the load returns 0
+
+// 4 consecutive floats at byte offset `off` of a buffer resource; offsets beyond the resource's range
+// read as 0 (hardware range check), so invalid taps / rows / channels need no masking instructions.
 template <bool VEC>
-__device__ __forceinline__ F4 ld4(const float* __restrict__ base, long long off, bool ok, int nvalid) {
+__device__ __forceinline__ F4 buf_ld4(__amdgpu_buffer_rsrc_t rsrc, uint32_t off, int nvalid) {
     F4 r;
     if (VEC) {
-        float4 v = *reinterpret_cast<const float4*>(base + (ok ? off : 0));
-        r.v[0] = ok ? v.x : 0.f; r.v[1] = ok ? v.y : 0.f; r.v[2] = ok ? v.z : 0.f; r.v[3] = ok ? v.w : 0.f;
+        uint4_t v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off, 0, 0);
+        r.v[0] = __uint_as_float(v.x); r.v[1] = __uint_as_float(v.y);
+        r.v[2] = __uint_as_float(v.z); r.v[3] = __uint_as_float(v.w);
     } else {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            bool okj = ok && j < nvalid;
-            float v = base[okj ? off + j : 0];
-            r.v[j] = okj ? v : 0.f;
+            uint32_t o = (j < nvalid) ? off + 4u * j : kOOB;
+            r.v[j] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)o, 0, 0));
         }
     }
     return r;
@@ -84,11 +90,14 @@ __device__ __forceinline__ float relax_factor(double a, float g) {
 // LDS-tiled implicit GEMM on float64 MFMA (16x16x4).
 //   Tile BM x BN per work-group of 4 waves, K step 16.  Both operand tiles are stored [row][k] with the
 //   16 k-values of a row contiguous (row stride 18 doubles): a thread converts the 4 consecutive
-//   channels it loaded (one 16-byte global load) and writes them with two 16-byte LDS stores; an MFMA
+//   channels it loaded (one 16-byte buffer load) and writes them with two 16-byte LDS stores; an MFMA
 //   lane (row l%16, k-slot l/16) reads ITS 4 consecutive k-values back with two 16-byte LDS loads and
 //   uses value j in MFMA step j, i.e. step j contracts the channel set {j, 4+j, 8+j, 12+j}.  A and B use
 //   the same permutation, so every product pairs the right channels; only the summation order differs,
 //   which the rounding slack covers for any order.
+//   The MFMA pipe and the vector ALU share the issue port, so everything outside the MFMAs is kept to a
+//   few instructions per K step: 32-bit offsets into per-tile buffer resources, range-checked loads
+//   instead of masks, tap geometry without divisions.
 template <int BM, int BN, bool VEC>
 __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
     constexpr int BK = 16;
@@ -107,97 +116,135 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     const int lk = lane >> 4, lm = lane & 15;
-    const long long opix = (long long)p.owy * p.owx;
-    const long long M = (long long)p.nrows * opix;
-    const long long m0 = (long long)blockIdx.x * BM;
+    const uint32_t opix = (uint32_t)(p.owy * p.owx);
+    const uint32_t M = (uint32_t)p.nrows * opix;            // < 2^31 (host guarantees)
+    const uint32_t m0 = blockIdx.x * (uint32_t)BM;
     const int n0 = blockIdx.y * BN;
     const int Ck = p.in.C, N = p.Co;
     const int taps = p.kh * p.kw;
     const int kchunks = (Ck + BK - 1) / BK;
     const int nIt = taps * kchunks;
+    const uint32_t row_elems = (uint32_t)(p.in.wy * p.in.wx * Ck);
+
+    // ---- buffer resources: A covers the rows of this tile only (32-bit offsets), B the layer's filter
+    const uint32_t r_first = fast_div(m0, p.div_opix);
+    const uint32_t r_last = fast_div(min(m0 + BM - 1, M - 1), p.div_opix);
+    const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(p.in.data + (size_t)r_first * row_elems), 0, (int)((r_last - r_first + 1) * row_elems * 4u), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrcB =
+        __builtin_amdgcn_make_buffer_rsrc((void*)p.wt, 0, (int)((uint32_t)taps * N * Ck * 4u), 0x00020000);
 
     // ---- loader bookkeeping: thread -> (tile row ld_row (+64*i), channel quad q4)
     const int ld_row = tid >> 2, q4 = (tid & 3) * 4;
-    long long a_rowoff[APT];
-    int a_A[APT], a_B[APT], a_oiy[APT], a_oix[APT];
+    uint32_t a_rowoff[APT];                 // byte offset of (row's block, channel q4) inside rsrcA
+    int a_ydiv[APT], a_xdiv[APT], a_ymod[APT], a_xmod[APT], a_oiy[APT], a_oix[APT];
     bool a_ok[APT];
 #pragma unroll
     for (int i = 0; i < APT; ++i) {
-        long long m = m0 + ld_row + 64 * i;
+        const uint32_t m = m0 + ld_row + 64 * i;
         a_ok[i] = (ld_row + 64 * i < BM) && m < M;
-        long long mm = a_ok[i] ? m : 0;
-        int r = (int)(mm / opix);
-        int rem = (int)(mm - (long long)r * opix);
-        int a = rem / p.owx, bb = rem - a * p.owx;
-        RowInfo ri = row_info(p.rm, r);
-        a_A[i] = clampi(p.oSy * ri.ys - p.oPy, 0, p.Ho - p.owy) + a + p.ph;
-        a_B[i] = clampi(p.oSx * ri.xs - p.oPx, 0, p.Wo - p.owx) + bb + p.pw;
+        const uint32_t mm = a_ok[i] ? m : m0;
+        const uint32_t r = fast_div(mm, p.div_opix);
+        const uint32_t rem = mm - r * opix;
+        const uint32_t a = fast_div(rem, p.div_owx), bb = rem - a * (uint32_t)p.owx;
+        const RowInfo ri = row_info(p.rm, (int)r);
+        // output pixel (A,B) of the input layer; tap (f,g) of the filter reads it from layer-output pixel
+        // ((A + ph - f)/sh, (B + pw - g)/sw) when both divisions are exact
+        const uint32_t yy0 = (uint32_t)(clampi(p.oSy * ri.ys - p.oPy, 0, p.Ho - p.owy) + (int)a + p.ph);
+        const uint32_t xx0 = (uint32_t)(clampi(p.oSx * ri.xs - p.oPx, 0, p.Wo - p.owx) + (int)bb + p.pw);
+        const uint32_t yd = fast_div(yy0, p.div_sh), xd = fast_div(xx0, p.div_sw);
+        a_ydiv[i] = (int)yd; a_ymod[i] = (int)(yy0 - yd * (uint32_t)p.sh);
+        a_xdiv[i] = (int)xd; a_xmod[i] = (int)(xx0 - xd * (uint32_t)p.sw);
         a_oiy[i] = clampi(p.in.Sy * ri.ys - p.in.Py, 0, p.in.H - p.in.wy);
         a_oix[i] = clampi(p.in.Sx * ri.xs - p.in.Px, 0, p.in.W - p.in.wx);
-        a_rowoff[i] = (long long)r * ((long long)p.in.wy * p.in.wx * Ck);
+        a_rowoff[i] = ((r - r_first) * row_elems + (uint32_t)q4) * 4u;
     }
-    long long a_src[APT];
-    bool a_tapok[APT];
-    auto set_tap = [&](int t) {
-        const int f = t / p.kw, g = t - f * p.kw;
-#pragma unroll
-        for (int i = 0; i < APT; ++i) {
-            int yy = a_A[i] - f, xx = a_B[i] - g;
-            int y = yy / p.sh, x = xx / p.sw;
-            bool ok = a_ok[i] && yy >= 0 && xx >= 0 && y * p.sh == yy && x * p.sw == xx && y < p.in.H && x < p.in.W;
-            int yi = y - a_oiy[i], xi = x - a_oix[i];
-            ok = ok && yi >= 0 && yi < p.in.wy && xi >= 0 && xi < p.in.wx;
-            a_tapok[i] = ok;
-            a_src[i] = a_rowoff[i] + (long long)(yi * p.in.wx + xi) * Ck;
-        }
-    };
-    long long b_off[BPT];
-    bool b_ok[BPT];
+    // per-thread byte offsets for the current tap: A pixel (kOOB when the tap misses the window), B column
+    uint32_t a_voff[APT], b_voff[BPT];
 #pragma unroll
     for (int i = 0; i < BPT; ++i) {
-        int n = n0 + ld_row + 64 * i;
-        b_ok[i] = (ld_row + 64 * i < BN) && n < N;
-        b_off[i] = (long long)(b_ok[i] ? n : 0) * Ck;
+        const int n = n0 + ld_row + 64 * i;
+        const bool ok = (ld_row + 64 * i < BN) && n < N;
+        b_voff[i] = ok ? ((uint32_t)n * (uint32_t)Ck + (uint32_t)q4) * 4u : kOOB;
     }
-
-    // global -> register staging holds raw float32 words only: nothing depends on the loads until the
-    // MFMA loop of the current tile has been issued; conversion happens at the register -> LDS copy
-    F4 a_raw[APT], b_raw[BPT];
-    int ld_t = 0, ld_d0 = 0;
-    set_tap(0);
-    auto load_tiles = [&]() {
-        const int d = ld_d0 + q4;
-        const bool dok = d < Ck;
+    // tap (f,g) written as f = fdiv*sh + fmod, g = gdiv*sw + gmod (all uniform)
+    auto set_tap = [&](int fdiv, int fmod, int gdiv, int gmod) {
 #pragma unroll
         for (int i = 0; i < APT; ++i) {
-            const bool ok = a_tapok[i] && dok;
-            a_raw[i] = ld4<VEC>(p.in.data, a_src[i] + d, ok, Ck - d);
-        }
-        const long long tbase = (long long)ld_t * N * Ck + d;
-#pragma unroll
-        for (int i = 0; i < BPT; ++i) b_raw[i] = ld4<VEC>(p.wt, tbase + b_off[i], b_ok[i] && dok, Ck - d);
-        ld_d0 += BK;
-        if (ld_d0 >= Ck) {
-            ld_d0 = 0;
-            ++ld_t;
-            if (ld_t < taps) set_tap(ld_t);
+            const int y = a_ydiv[i] - fdiv, x = a_xdiv[i] - gdiv;
+            const int yi = y - a_oiy[i], xi = x - a_oix[i];
+            const bool ok = a_ok[i] && a_ymod[i] == fmod && a_xmod[i] == gmod &&
+                            (unsigned)y < (unsigned)p.in.H && (unsigned)x < (unsigned)p.in.W &&
+                            (unsigned)yi < (unsigned)p.in.wy && (unsigned)xi < (unsigned)p.in.wx;
+            a_voff[i] = ok ? a_rowoff[i] + (uint32_t)(yi * p.in.wx + xi) * (uint32_t)(Ck * 4) : kOOB;
         }
     };
+    int ld_t = 0, ld_d0 = 0, ld_g = 0, ld_fdiv = 0, ld_fmod = 0, ld_gdiv = 0, ld_gmod = 0;
+    set_tap(0, 0, 0, 0);
+
+    // global -> register staging holds raw float32 words only: nothing depends on the loads until the
+    // MFMA loop of the current tile has been issued; conversion happens at the register -> LDS copy.
+    // Per K step the loads cost no vector instruction: per-thread offsets are fixed within a tap and the
+    // channel advance goes through the scalar offset operand of the buffer load.
+    F4 a_raw[APT], b_raw[BPT];
+    auto load_tiles = [&]() {
+        const int rem = Ck - ld_d0;                                 // channels left in this tap (uniform)
+        const uint32_t soffA = (uint32_t)ld_d0 * 4u;
+        const uint32_t soffB = ((uint32_t)ld_t * (uint32_t)N * (uint32_t)Ck + (uint32_t)ld_d0) * 4u;
+        if (VEC && rem >= BK) {
+#pragma unroll
+            for (int i = 0; i < APT; ++i) {
+                uint4_t v = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, (int)a_voff[i], (int)soffA, 0);
+                a_raw[i].v[0] = __uint_as_float(v.x); a_raw[i].v[1] = __uint_as_float(v.y);
+                a_raw[i].v[2] = __uint_as_float(v.z); a_raw[i].v[3] = __uint_as_float(v.w);
+            }
+#pragma unroll
+            for (int i = 0; i < BPT; ++i) {
+                uint4_t v = __builtin_amdgcn_raw_buffer_load_b128(rsrcB, (int)b_voff[i], (int)soffB, 0);
+                b_raw[i].v[0] = __uint_as_float(v.x); b_raw[i].v[1] = __uint_as_float(v.y);
+                b_raw[i].v[2] = __uint_as_float(v.z); b_raw[i].v[3] = __uint_as_float(v.w);
+            }
+        } else {                                                    // ragged last chunk of a tap, or unaligned channels
+            const bool dok = q4 < rem;
+#pragma unroll
+            for (int i = 0; i < APT; ++i)
+                a_raw[i] = buf_ld4<VEC>(rsrcA, (dok && a_voff[i] != kOOB) ? a_voff[i] + soffA : kOOB, rem - q4);
+#pragma unroll
+            for (int i = 0; i < BPT; ++i)
+                b_raw[i] = buf_ld4<VEC>(rsrcB, (dok && b_voff[i] != kOOB) ? b_voff[i] + soffB : kOOB, rem - q4);
+        }
+        ld_d0 += BK;
+        if (ld_d0 >= Ck) {                                          // next tap (uniform, once per kchunks steps)
+            ld_d0 = 0;
+            ++ld_t;
+            ++ld_g; ++ld_gmod;
+            if (ld_gmod == p.sw) { ld_gmod = 0; ++ld_gdiv; }
+            if (ld_g == p.kw) {
+                ld_g = 0; ld_gdiv = 0; ld_gmod = 0;
+                ++ld_fmod;
+                if (ld_fmod == p.sh) { ld_fmod = 0; ++ld_fdiv; }
+            }
+            if (ld_t < taps) set_tap(ld_fdiv, ld_fmod, ld_gdiv, ld_gmod);
+        }
+    };
+    // LDS addresses of this thread's stores and MFMA operand loads (fixed; the buffer index is an immediate)
+    double* const a_st = &As[0][ld_row][q4];
+    double* const b_st = &Bs[0][ld_row][q4];
+    const double* const a_ld = &As[0][wm * WTM + lm][4 * lk];
+    const double* const b_ld = &Bs[0][wn * WTN + lm][4 * lk];
     auto store_tiles = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < APT; ++i) {
-            const int row = ld_row + 64 * i;
-            if (row < BM) {
-                double2* dst = reinterpret_cast<double2*>(&As[buf][row][q4]);
+            if (ld_row + 64 * i < BM) {
+                double2* dst = reinterpret_cast<double2*>(a_st + (buf * BM + 64 * i) * LDK);
                 dst[0] = make_double2((double)a_raw[i].v[0], (double)a_raw[i].v[1]);
                 dst[1] = make_double2((double)a_raw[i].v[2], (double)a_raw[i].v[3]);
             }
         }
 #pragma unroll
         for (int i = 0; i < BPT; ++i) {
-            const int row = ld_row + 64 * i;
-            if (row < BN) {
-                double2* dst = reinterpret_cast<double2*>(&Bs[buf][row][q4]);
+            if (ld_row + 64 * i < BN) {
+                double2* dst = reinterpret_cast<double2*>(b_st + (buf * BN + 64 * i) * LDK);
                 dst[0] = make_double2((double)b_raw[i].v[0], (double)b_raw[i].v[1]);
                 dst[1] = make_double2((double)b_raw[i].v[2], (double)b_raw[i].v[3]);
             }
@@ -210,21 +257,16 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = double4_t{0.0, 0.0, 0.0, 0.0};
 
-    load_tiles();
-    store_tiles(0);
-    __syncthreads();
-    for (int it = 0; it < nIt; ++it) {
-        const int buf = it & 1;
-        if (it + 1 < nIt) load_tiles();
+    auto mfma_tile = [&](int buf) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {              // two halves of the lane's 4 k-values: one 16-byte LDS load each
             double2 av[TM], bv[TN];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                av[i] = *reinterpret_cast<const double2*>(&As[buf][wm * WTM + i * 16 + lm][4 * lk + 2 * h]);
+                av[i] = *reinterpret_cast<const double2*>(a_ld + (buf * BM + i * 16) * LDK + 2 * h);
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                bv[j] = *reinterpret_cast<const double2*>(&Bs[buf][wn * WTN + j * 16 + lm][4 * lk + 2 * h]);
+                bv[j] = *reinterpret_cast<const double2*>(b_ld + (buf * BN + j * 16) * LDK + 2 * h);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -236,9 +278,25 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[i].y, bv[j].y, acc[i][j], 0, 0, 0);
         }
-        if (it + 1 < nIt) store_tiles(buf ^ 1);
+    };
+
+    load_tiles();
+    store_tiles(0);
+    __syncthreads();
+    // two K steps per trip so that the LDS buffer index is a compile-time constant
+    int it = 0;
+    for (; it + 2 <= nIt; it += 2) {
+        load_tiles();                  // tile it+1 (exists)
+        mfma_tile(0);
+        store_tiles(1);
+        __syncthreads();
+        const bool more = it + 2 < nIt;
+        if (more) load_tiles();        // tile it+2
+        mfma_tile(1);
+        if (more) store_tiles(0);
         __syncthreads();
     }
+    if (it < nIt) mfma_tile(0);
 
     // ---- epilogue: (+ residual addend) (* ReLU substitution of the destination layer) -> one rounding to
     // float32 -> store.  D[i][j]: register r of lane l holds i = 4*r + l/16, j = l%16.
@@ -248,25 +306,26 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
         for (int r4 = 0; r4 < 4; ++r4) {
-            const long long m = m0 + wm * WTM + i * 16 + 4 * r4 + lk;
+            const uint32_t m = m0 + wm * WTM + i * 16 + 4 * r4 + lk;
             if (m >= M) continue;
             const float* add_src = nullptr;
-            long long ridx = 0;
+            size_t ridx = 0;
             if (need_pos) {
-                int r = (int)(m / opix);
-                int rem = (int)(m - (long long)r * opix);
-                int a = rem / p.owx, bb = rem - a * p.owx;
-                RowInfo ri = row_info(p.rm, r);
-                int A = clampi(p.oSy * ri.ys - p.oPy, 0, p.Ho - p.owy) + a;
-                int B = clampi(p.oSx * ri.xs - p.oPx, 0, p.Wo - p.owx) + bb;
-                ridx = (long long)ri.b * ((long long)p.Ho * p.Wo * N) + (long long)(A * p.Wo + B) * N;
+                const uint32_t r = fast_div(m, p.div_opix);
+                const uint32_t rem = m - r * opix;
+                const uint32_t a = fast_div(rem, p.div_owx), bb = rem - a * (uint32_t)p.owx;
+                const RowInfo ri = row_info(p.rm, (int)r);
+                const int A = clampi(p.oSy * ri.ys - p.oPy, 0, p.Ho - p.owy) + (int)a;
+                const int B = clampi(p.oSx * ri.xs - p.oPx, 0, p.Wo - p.owx) + (int)bb;
+                ridx = (size_t)ri.b * ((size_t)p.Ho * p.Wo * N) + (size_t)(A * p.Wo + B) * N;
                 if (has_add) {
-                    int ay = A - clampi(p.add.Sy * ri.ys - p.add.Py, 0, p.add.H - p.add.wy);
-                    int ax = B - clampi(p.add.Sx * ri.xs - p.add.Px, 0, p.add.W - p.add.wx);
+                    const int ay = A - clampi(p.add.Sy * ri.ys - p.add.Py, 0, p.add.H - p.add.wy);
+                    const int ax = B - clampi(p.add.Sx * ri.xs - p.add.Px, 0, p.add.W - p.add.wx);
                     if (ay >= 0 && ay < p.add.wy && ax >= 0 && ax < p.add.wx)
                         add_src = p.add.data + ((size_t)r * p.add.wy * p.add.wx + (size_t)(ay * p.add.wx + ax)) * N;
                 }
             }
+            float* out_row = p.out + (size_t)m * N;
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const int n = n0 + wn * WTN + j * 16 + lm;
@@ -274,7 +333,7 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
                 double v = acc[i][j][r4];
                 if (add_src) v += (double)add_src[n];
                 if (p.out_grl) v *= (double)relax_factor(v, p.out_grl[ridx + n]);
-                p.out[(size_t)m * N + n] = (float)v;
+                out_row[n] = (float)v;
             }
         }
     }
@@ -498,7 +557,7 @@ __device__ __forceinline__ void atomic_max_nonneg(double* addr, double v) {
 __global__ void finalize_kernel(const FinalizeParams p) {
     int r = blockIdx.x * blockDim.x + threadIdx.x;
     if (r >= p.rm.Rc) return;
-    long long g = p.rm.row0 + r;
+    long long g = (long long)p.rm.row0 + r;
     double u = p.best[r];
     double l = -p.best[p.rm.Rc + r];
     if (!isfinite(u) || !isfinite(l)) *p.flag = 1;

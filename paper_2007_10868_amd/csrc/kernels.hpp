@@ -14,13 +14,36 @@
 
 namespace gp {
 
+// Unsigned division by a run-time constant without a divide instruction: q = (mulhi(m, x) + x) >> s.
+// Exact for 1 <= d < 2^31 and x < 2^31 (the round-up method with a 33-bit multiplier whose top bit is the "+ x").
+struct FastDiv {
+    uint32_t d, m, s;
+};
+inline FastDiv make_fastdiv(uint32_t d) {
+    FastDiv f;
+    f.d = d;
+    uint32_t s = 0;
+    while ((1ull << s) < d) ++s;
+    f.s = s;
+    f.m = (uint32_t)((((1ull << 32) * ((1ull << s) - d)) / d) + 1);
+    return f;
+}
+__host__ __device__ inline uint32_t fast_div(uint32_t x, const FastDiv& f) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return (__umulhi(f.m, x) + x) >> f.s;
+#else
+    return (uint32_t)(((((uint64_t)f.m * x) >> 32) + x) >> f.s);
+#endif
+}
+
 // which neurons the rows of a launch stand for
 struct RowMap {
-    long long row0;  // first task of this chunk, counted over batch * n_start
+    int row0;        // first task of this chunk, counted over batch * n_start (< 2^31)
     int Rc;          // tasks in the chunk
     int nsign;       // 2: rows [0,Rc) are +x, rows [Rc,2Rc) are -x;  1: one row per task
     int n_start;     // tasks per box of the batch
     int Hs, Ws, Cs;  // start layer dims; task i sits at position ((i/Cs)/Ws, (i/Cs)%Ws), channel i%Cs
+    FastDiv div_n, div_c, div_w;   // n_start, Cs, Ws
 };
 
 struct BlockDesc {
@@ -40,6 +63,7 @@ struct CrossParams {       // one back-substitution step through an affine layer
                            //   the new coefficients before they are rounded and stored; null: store as is
     int Ho, Wo, Co;        // dims of the input layer
     int owy, owx, oSy, oSx, oPy, oPx;
+    FastDiv div_opix, div_owx, div_sh, div_sw;   // owy*owx, owx, sh, sw
     BlockDesc add;         // optional block over the same input layer to be summed in (residual join)
     RowMap rm;
     int nrows;
