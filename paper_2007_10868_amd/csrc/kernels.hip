@@ -381,100 +381,182 @@ void launch_cross(const CrossParams& p, hipStream_t s) {
 // A work-group handles SCAN_ROWS rows: one wave per row for short rows, all four waves on one row
 // for long ones.
 // ------------------------------------------------------------------------------------------------
-__device__ __forceinline__ double wave_sum(double v) {
+// Sum of 8 per-lane values over the 64 lanes of a wave, all 8 at once: every butterfly step halves the
+// number of values a lane carries, so 8 values cost 10 exchanges instead of 48.  On return v[0] of lane l
+// holds the wave total of input value l>>3.
+__device__ __forceinline__ double wave_sum8(double (&v)[8], int lane) {
+    const bool b5 = (lane & 32) != 0, b4 = (lane & 16) != 0, b3 = (lane & 8) != 0;
+    double w[4];
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
-    return v;
+    for (int k = 0; k < 4; ++k) {
+        double keep = b5 ? v[k + 4] : v[k], send = b5 ? v[k] : v[k + 4];
+        w[k] = keep + __shfl_xor(send, 32, 64);
+    }
+    double x[2];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        double keep = b4 ? w[k + 2] : w[k], send = b4 ? w[k] : w[k + 2];
+        x[k] = keep + __shfl_xor(send, 16, 64);
+    }
+    double keep = b3 ? x[1] : x[0], send = b3 ? x[0] : x[1];
+    double y = keep + __shfl_xor(send, 8, 64);
+    y += __shfl_xor(y, 4, 64);
+    y += __shfl_xor(y, 2, 64);
+    y += __shfl_xor(y, 1, 64);
+    return y;
 }
 
-template <int ROWS_PER_WG>
+constexpr int SCAN_G = 8;     // rows per wave
+
+// One wave scans SCAN_G consecutive rows.  Rows of a group normally belong to the same box and sit at the
+// same position (they differ in channel only), so the per-neuron constants are fetched once per element
+// and reused for all rows of the group; otherwise each row fetches its own.  V = elements per lane and
+// step (4 when the channel count allows 16-byte loads).
+template <int V>
 __global__ __launch_bounds__(256) void scan_kernel(const ScanParams p) {
-    constexpr int TPR = 256 / ROWS_PER_WG;        // threads per row: 256 or 64
-    const int tid = threadIdx.x;
-    const int r = blockIdx.x * ROWS_PER_WG + tid / TPR;
-    const int t = tid % TPR;
-    const bool row_ok = r < p.nrows;
+    const int tid = threadIdx.x, lane = tid & 63;
     const BlockDesc& B = p.blk;
-    const RowInfo ri = row_info(p.rm, row_ok ? r : 0);
-    const int oy = clampi(B.Sy * ri.ys - B.Py, 0, B.H - B.wy);
-    const int ox = clampi(B.Sx * ri.xs - B.Px, 0, B.W - B.wx);
+    const int groups_per_half = (p.rm.Rc + SCAN_G - 1) / SCAN_G;
+    const int gidx = blockIdx.x * 4 + (tid >> 6);
+    const int nhalves = p.nrows / p.rm.Rc;                 // 1 or 2
+    if (gidx >= groups_per_half * nhalves) return;          // whole wave leaves; no barrier below
+    const int half = gidx / groups_per_half;
+    const int rr0 = (gidx - half * groups_per_half) * SCAN_G;   // first row of the group inside its half
+    const int nvalid = min(SCAN_G, p.rm.Rc - rr0);
+    const int r0 = half * p.rm.Rc + rr0;
     const int nelem = B.wy * B.wx * B.C;
-    const float* src = B.data + (size_t)(row_ok ? r : 0) * nelem;
-    const long long bbase = (long long)ri.b * p.batch_stride;
-    const bool full_row = (B.wx == B.W);          // window rows are contiguous in the layer
-    double cand = 0, absx = 0, cst = 0, cstabs = 0, s1 = 0;
-    if (row_ok) {
-        for (int e = t; e < nelem; e += TPR) {
-            const float mf = src[e];
-            if (mf == 0.f) continue;
-            const double m = (double)mf;
-            int c;
-            long long j;
-            if (full_row) {
-                c = e % B.C;
-                j = bbase + (long long)oy * B.W * B.C + e;
-            } else {
-                int pix = e / B.C;
-                c = e - pix * B.C;
-                int a = pix / B.wx, bb = pix - a * B.wx;
-                j = bbase + ((long long)((oy + a) * B.W + (ox + bb)) * B.C + c);
-            }
+    const bool full_row = (B.wx == B.W);                   // window rows are contiguous in the layer
+
+    // do all rows share box and window origin?
+    RowInfo ri0 = row_info(p.rm, r0);
+    const int oy0 = clampi(B.Sy * ri0.ys - B.Py, 0, B.H - B.wy);
+    const int ox0 = clampi(B.Sx * ri0.xs - B.Px, 0, B.W - B.wx);
+    bool same = true;
+    for (int k = 1; k < nvalid; ++k) {
+        RowInfo rk = row_info(p.rm, r0 + k);
+        int oy = clampi(B.Sy * rk.ys - B.Py, 0, B.H - B.wy), ox = clampi(B.Sx * rk.xs - B.Px, 0, B.W - B.wx);
+        same = same && rk.b == ri0.b && oy == oy0 && ox == ox0;
+    }
+
+    double cand[SCAN_G], absx[SCAN_G], cst[SCAN_G], cstabs[SCAN_G], s1[SCAN_G];
+#pragma unroll
+    for (int k = 0; k < SCAN_G; ++k) cand[k] = absx[k] = cst[k] = cstabs[k] = s1[k] = 0.0;
+
+    // neuron index of block element e (a multiple of V; the V elements are consecutive channels of one pixel)
+    auto neuron = [&](int e, int oy, int ox, long long bbase, int& c) -> long long {
+        if (full_row) {
+            c = e % B.C;
+            return bbase + (long long)oy * B.W * B.C + e;
+        }
+        int pix = e / B.C;
+        c = e - pix * B.C;
+        int a = pix / B.wx, bb = pix - a * B.wx;
+        return bbase + ((long long)((oy + a) * B.W + (ox + bb)) * B.C + c);
+    };
+    struct Consts {
+        double cp[V], cn[V], X[V], kp[V], be[V];
+    };
+    auto constants = [&](long long j, int c, Consts& q) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            q.cp[v] = q.cn[v] = q.X[v] = q.kp[v] = q.be[v] = 0.0;
             if (p.cpos) {
-                cand += (m >= 0.0) ? m * p.cpos[j] : m * p.cneg[j];
-                absx += fabs(m) * fmax(fabs(p.xlo[j]), fabs(p.xhi[j]));
+                q.cp[v] = p.cpos[j + v];
+                q.cn[v] = p.cneg[j + v];
+                q.X[v] = fmax(fabs(p.xlo[j + v]), fabs(p.xhi[j + v]));
             }
             if (p.do_consts) {
-                if (p.kap && mf > 0.f) {
-                    double tt = m * p.kap[j];
-                    cst += tt;
-                    cstabs += tt;
-                }
-                s1 += fabs(m);
-                if (p.beff) {
-                    double tt = m * p.beff[c];
-                    cst += tt;
-                    cstabs += fabs(tt);
-                }
+                if (p.kap) q.kp[v] = p.kap[j + v];
+                if (p.beff) q.be[v] = p.beff[c + v];
+            }
+        }
+    };
+    auto accumulate = [&](int k, const float (&mf)[V], const Consts& q) {
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const double m = (double)mf[v];
+            if (p.cpos) {
+                cand[k] += (mf[v] >= 0.f) ? m * q.cp[v] : m * q.cn[v];
+                absx[k] += fabs(m) * q.X[v];
+            }
+            if (p.do_consts) {
+                const double tp = fmax(m, 0.0) * q.kp[v];
+                const double tb = m * q.be[v];
+                cst[k] += tp + tb;
+                cstabs[k] += tp + fabs(tb);
+                s1[k] += fabs(m);
+            }
+        }
+    };
+    auto load_m = [&](const float* src, float (&mf)[V]) {
+        if (V == 4) {
+            float4 t = *reinterpret_cast<const float4*>(src);
+            mf[0] = t.x; mf[1 % V] = t.y; mf[2 % V] = t.z; mf[3 % V] = t.w;
+        } else {
+            mf[0] = src[0];
+        }
+    };
+
+    const float* src0 = B.data + (size_t)r0 * nelem;
+    if (same) {
+        const long long bbase = (long long)ri0.b * p.batch_stride;
+        for (int e = lane * V; e < nelem; e += 64 * V) {
+            float mf[SCAN_G][V];
+#pragma unroll
+            for (int k = 0; k < SCAN_G; ++k)
+                if (k < nvalid) load_m(src0 + (size_t)k * nelem + e, mf[k]);
+            int c;
+            const long long j = neuron(e, oy0, ox0, bbase, c);
+            Consts q;
+            constants(j, c, q);
+#pragma unroll
+            for (int k = 0; k < SCAN_G; ++k)
+                if (k < nvalid) accumulate(k, mf[k], q);
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < SCAN_G; ++k) {
+            if (k >= nvalid) continue;
+            RowInfo rk = row_info(p.rm, r0 + k);
+            const int oy = clampi(B.Sy * rk.ys - B.Py, 0, B.H - B.wy), ox = clampi(B.Sx * rk.xs - B.Px, 0, B.W - B.wx);
+            const long long bbase = (long long)rk.b * p.batch_stride;
+            for (int e = lane * V; e < nelem; e += 64 * V) {
+                float mf[V];
+                load_m(src0 + (size_t)k * nelem + e, mf);
+                int c;
+                const long long j = neuron(e, oy, ox, bbase, c);
+                Consts q;
+                constants(j, c, q);
+                accumulate(k, mf, q);
             }
         }
     }
-    cand = wave_sum(cand); absx = wave_sum(absx); cst = wave_sum(cst); cstabs = wave_sum(cstabs); s1 = wave_sum(s1);
-    if (TPR > 64) {
-        __shared__ double red[5][4];
-        if ((tid & 63) == 0) {
-            int w = tid >> 6;
-            red[0][w] = cand; red[1][w] = absx; red[2][w] = cst; red[3][w] = cstabs; red[4][w] = s1;
-        }
-        __syncthreads();
-        if (tid == 0) {
-            cand = red[0][0] + red[0][1] + red[0][2] + red[0][3];
-            absx = red[1][0] + red[1][1] + red[1][2] + red[1][3];
-            cst = red[2][0] + red[2][1] + red[2][2] + red[2][3];
-            cstabs = red[3][0] + red[3][1] + red[3][2] + red[3][3];
-            s1 = red[4][0] + red[4][1] + red[4][2] + red[4][3];
-        }
-    }
-    if (t == 0 && row_ok) {
+    const double t_cand = wave_sum8(cand, lane), t_absx = wave_sum8(absx, lane), t_cst = wave_sum8(cst, lane),
+                 t_cstabs = wave_sum8(cstabs, lane), t_s1 = wave_sum8(s1, lane);
+    const int k = lane >> 3;
+    if ((lane & 7) == 0 && k < nvalid) {
+        const int r = r0 + k;
+        const RowInfo ri = row_info(p.rm, r);
         // a sum of n float64 terms in any order is off by at most (n-1)*2^-53*sum|terms|*(1+tiny)
         const double esum = (double)(nelem + 16) * 0x1p-52;
         double c = p.c[r];
         double err = p.err[r];
         // slack of the stored coefficients: |true - stored| <= round_coef*|stored| (+ subnormal floor)
-        err += absx * p.round_coef * (1.0 + esum);
+        err += t_absx * p.round_coef * (1.0 + esum);
         // values below the float32 subnormal step vanish; with a substituted ReLU the lost coefficient is
         // up to 2^20 times larger (slopes are kept >= 2^-20)
         if (p.round_coef > 0.0 && p.xmax_self) err += 0x1p-128 * (double)nelem * p.xmax_self[ri.b];
         if (p.update_best && p.cpos) {
-            double v = c + cand + err;
-            v += (fabs(c) + fabs(cand) + err) * 0x1p-50 + absx * esum;
+            double v = c + t_cand + err;
+            v += (fabs(c) + fabs(t_cand) + err) * 0x1p-50 + t_absx * esum;
             p.best[r] = fmin(p.best[r], v);
         }
         if (p.do_consts) {
-            double cn = c + cst;
+            double cn = c + t_cst;
             double e1 = 0.0;
             if (p.xmax_a) e1 += p.e1_a * p.xmax_a[ri.b];
             if (p.xmax_b) e1 += p.e1_b * p.xmax_b[ri.b];
-            err += cstabs * esum + (fabs(c) + fabs(cst)) * 0x1p-51 + s1 * e1 * (1.0 + esum);
+            err += t_cstabs * esum + (fabs(c) + fabs(t_cst)) * 0x1p-51 + t_s1 * e1 * (1.0 + esum);
             c = cn;
         }
         err *= (1.0 + 0x1p-48);   // the few float64 operations above
@@ -485,9 +567,10 @@ __global__ __launch_bounds__(256) void scan_kernel(const ScanParams p) {
 
 void launch_scan(const ScanParams& p, hipStream_t s) {
     if (p.nrows <= 0) return;
-    const int nelem = p.blk.wy * p.blk.wx * p.blk.C;
-    if (nelem <= 1024) hipLaunchKernelGGL((scan_kernel<4>), dim3((p.nrows + 3) / 4), dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((scan_kernel<1>), dim3(p.nrows), dim3(256), 0, s, p);
+    const int nhalves = p.nrows / p.rm.Rc;
+    const int groups = ((p.rm.Rc + SCAN_G - 1) / SCAN_G) * nhalves;
+    if ((p.blk.C & 3) == 0) hipLaunchKernelGGL((scan_kernel<4>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((scan_kernel<1>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -496,15 +579,14 @@ void launch_scan(const ScanParams& p, hipStream_t s) {
 //   mode 1: e_j - e_label over the whole last layer (certification rows)
 //   mode 2: +/- the row of the start layer's matrix, i.e. its filter placed in the window over the
 //           predecessor; constant = +/- bias.  Exact: no rounding.
-__global__ void init_kernel(const InitParams p) {
-    const long long total = (long long)p.nrows * p.nelem;
-    for (long long idx = blockIdx.x * (long long)blockDim.x + threadIdx.x; idx < total;
-         idx += (long long)gridDim.x * blockDim.x) {
-        int r = (int)(idx / p.nelem);
-        int e = (int)(idx - (long long)r * p.nelem);
-        RowInfo ri = row_info(p.rm, r);
+__global__ __launch_bounds__(256) void init_kernel(const InitParams p) {
+    // block = 4 rows x 64 elements; grid.x over row quadruples, grid.y over element chunks
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= p.nrows) return;
+    const RowInfo ri = row_info(p.rm, r);
+    float* out = p.out + (size_t)r * p.nelem;
+    for (int e = blockIdx.y * 64 + (threadIdx.x & 63); e < p.nelem; e += gridDim.y * 64) {
         float v = 0.f;
-        double c0 = 0.0;
         if (p.mode == 0) {
             v = (e == ri.cs) ? ri.sign : 0.f;
         } else if (p.mode == 1) {
@@ -515,6 +597,10 @@ __global__ void init_kernel(const InitParams p) {
             int chw = c * (p.H * p.W) + pix;
             if (chw == j) v = 1.f;
             else if (chw == label) v = -1.f;
+        } else if (p.dense) {
+            v = ri.sign * p.wt[(size_t)ri.cs * p.nelem + e];
+            if (p.out_grl && v != 0.f)
+                v = (float)((double)v * (double)relax_factor((double)v, p.out_grl[(size_t)ri.b * p.nelem + e]));
         } else {
             // window over the predecessor (dims H,W,C here), origin from the row's position
             int pix = e / p.C, c = e - pix * p.C;
@@ -522,49 +608,60 @@ __global__ void init_kernel(const InitParams p) {
             int A = clampi(p.Sy * ri.ys - p.Py, 0, p.H - p.wy) + a;
             int B = clampi(p.Sx * ri.xs - p.Px, 0, p.W - p.wx) + bb;
             int f = A - (ri.ys * p.sh - p.ph), g = B - (ri.xs * p.sw - p.pw);
-            if (p.dense) {
-                v = ri.sign * p.wt[(size_t)ri.cs * p.nelem + e];
-            } else if (f >= 0 && f < p.kh && g >= 0 && g < p.kw) {
+            if (f >= 0 && f < p.kh && g >= 0 && g < p.kw)
                 v = ri.sign * p.wt[((size_t)(f * p.kw + g) * p.Cs + ri.cs) * p.C + c];
-            }
-            c0 = (double)(ri.sign * p.bias[ri.cs]);
             if (p.out_grl && v != 0.f) {
-                long long j = (long long)ri.b * ((long long)p.H * p.W * p.C) + (long long)(A * p.W + B) * p.C + c;
+                size_t j = (size_t)ri.b * ((size_t)p.H * p.W * p.C) + (size_t)(A * p.W + B) * p.C + c;
                 v = (float)((double)v * (double)relax_factor((double)v, p.out_grl[j]));
             }
         }
-        p.out[idx] = v;
-        if (e == 0) {
-            p.c[r] = c0;
-            p.err[r] = 0.0;
-            p.best[r] = INFINITY;
-        }
+        out[e] = v;
+    }
+    if (blockIdx.y == 0 && (threadIdx.x & 63) == 0) {
+        p.c[r] = (p.mode == 2) ? (double)(ri.sign * p.bias[ri.cs]) : 0.0;
+        p.err[r] = 0.0;
+        p.best[r] = INFINITY;
     }
 }
 
 void launch_init(const InitParams& p, hipStream_t s) {
-    long long total = (long long)p.nrows * p.nelem;
-    if (total <= 0) return;
-    int blocks = (int)fmin((double)((total + 255) / 256), 262144.0);
-    hipLaunchKernelGGL(init_kernel, dim3(blocks), dim3(256), 0, s, p);
+    if (p.nrows <= 0 || p.nelem <= 0) return;
+    const int ychunks = (int)fmin((double)((p.nelem + 63) / 64), 64.0);
+    hipLaunchKernelGGL(init_kernel, dim3((p.nrows + 3) / 4, ychunks), dim3(256), 0, s, p);
 }
 
-__device__ __forceinline__ void atomic_max_nonneg(double* addr, double v) {
-    // non-negative doubles order like their bit patterns
-    atomicMax(reinterpret_cast<unsigned long long*>(addr), (unsigned long long)__double_as_longlong(v));
+// running maximum of non-negative values, one slot per box; a wave whose lanes all target the same slot
+// combines them first (thousands of atomics on one address serialise).  Must be reached by all 64 lanes.
+__device__ __forceinline__ void atomic_max_nonneg(double* base, int slot, double v, bool valid) {
+    const int first = __builtin_amdgcn_readfirstlane(slot);
+    if (__all(valid && slot == first)) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) v = fmax(v, __shfl_xor(v, off, 64));
+        if ((threadIdx.x & 63) == 0)
+            atomicMax(reinterpret_cast<unsigned long long*>(base + first), (unsigned long long)__double_as_longlong(v));
+    } else if (valid) {
+        // non-negative doubles order like their bit patterns
+        atomicMax(reinterpret_cast<unsigned long long*>(base + slot), (unsigned long long)__double_as_longlong(v));
+    }
 }
 
 __global__ void finalize_kernel(const FinalizeParams p) {
-    int r = blockIdx.x * blockDim.x + threadIdx.x;
-    if (r >= p.rm.Rc) return;
-    long long g = (long long)p.rm.row0 + r;
-    double u = p.best[r];
-    double l = -p.best[p.rm.Rc + r];
-    if (!isfinite(u) || !isfinite(l)) *p.flag = 1;
-    p.hi[g] = u;
-    p.lo[g] = l;
-    double x = fmax(fabs(u), fabs(l));
-    if (isfinite(x)) atomic_max_nonneg(p.xmax + g / p.rm.n_start, x);
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    const bool valid = r < p.rm.Rc;
+    double x = 0.0;
+    int slot = 0;
+    if (valid) {
+        const long long g = (long long)p.rm.row0 + r;
+        const double u = p.best[r];
+        const double l = -p.best[p.rm.Rc + r];
+        if (!isfinite(u) || !isfinite(l)) *p.flag = 1;
+        p.hi[g] = u;
+        p.lo[g] = l;
+        x = fmax(fabs(u), fabs(l));
+        if (!isfinite(x)) x = 0.0;
+        slot = (int)(g / p.rm.n_start);
+    }
+    atomic_max_nonneg(p.xmax, slot, x, valid);
 }
 
 void launch_finalize(const FinalizeParams& p, hipStream_t s) {
@@ -575,33 +672,39 @@ void launch_finalize(const FinalizeParams& p, hipStream_t s) {
 // ReLU layer: intervals [max(l,0), max(u,0)] and the relaxation  lam*x <= relu(x) <= gam*x + del.
 // Any gam in [0,1] is sound when del >= max(-gam*l, u - gam*u); gam is the float32 nearest to u/(u-l).
 __global__ void relu_kernel(const ReluParams p) {
-    long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x;
-    if (i >= p.total) return;
-    double l = p.plo[i], u = p.phi[i];
-    if (!isfinite(l) || !isfinite(u)) *p.flag = 1;
-    p.lo[i] = fmax(l, 0.0);
-    p.hi[i] = fmax(u, 0.0);
-    float g, lam;
-    double rho = 0.0, kap = 0.0;
-    if (l >= 0.0) { g = 1.f; lam = 1.f; rho = u; }
-    else if (u <= 0.0) { g = 0.f; lam = 0.f; }
-    else {
-        g = (float)(u / (u - l));
-        g = fminf(fmaxf(g, 0x1p-20f), 1.f);       // a positive coefficient must stay recoverable from its product with g
-        double gd = (double)g;
-        double d1 = -gd * l, d2 = u - gd * u;     // each off by a few ulps at most
-        double d = fmax(d1, d2);
-        d = d + (fabs(d) + fabs(u)) * 0x1p-50 + 0x1p-1000;
-        lam = (u > -l) ? 1.f : 0.f;
-        // rounded up, including the float32 rounding of the stored product coefficient*g
-        rho = (u / gd) * (1.0 + 0x1p-22);
-        kap = (d / gd) * (1.0 + 0x1p-22);
+    const long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x;
+    const bool valid = i < p.total;
+    double x = 0.0;
+    int slot = 0;
+    if (valid) {
+        const double l = p.plo[i], u = p.phi[i];
+        if (!isfinite(l) || !isfinite(u)) *p.flag = 1;
+        p.lo[i] = fmax(l, 0.0);
+        p.hi[i] = fmax(u, 0.0);
+        float g, lam;
+        double rho = 0.0, kap = 0.0;
+        if (l >= 0.0) { g = 1.f; lam = 1.f; rho = u; }
+        else if (u <= 0.0) { g = 0.f; lam = 0.f; }
+        else {
+            g = (float)(u / (u - l));
+            g = fminf(fmaxf(g, 0x1p-20f), 1.f);       // a positive coefficient must stay recoverable from its product with g
+            const double gd = (double)g;
+            const double d1 = -gd * l, d2 = u - gd * u;     // each off by a few ulps at most
+            double d = fmax(d1, d2);
+            d = d + (fabs(d) + fabs(u)) * 0x1p-50 + 0x1p-1000;
+            lam = (u > -l) ? 1.f : 0.f;
+            // rounded up, including the float32 rounding of the stored product coefficient*g
+            rho = (u / gd) * (1.0 + 0x1p-22);
+            kap = (d / gd) * (1.0 + 0x1p-22);
+        }
+        p.grl[i] = lam != 0.f ? g : -g;      // -0.0f encodes slope 0 with lam = 0
+        p.rho[i] = rho;
+        p.kap[i] = kap;
+        x = fmax(u, 0.0);
+        if (!isfinite(x)) x = 0.0;
+        slot = (int)(i / p.n);
     }
-    p.grl[i] = lam != 0.f ? g : -g;      // -0.0f encodes slope 0 with lam = 0
-    p.rho[i] = rho;
-    p.kap[i] = kap;
-    double x = fmax(u, 0.0);
-    if (isfinite(x)) atomic_max_nonneg(p.xmax + i / p.n, x);
+    atomic_max_nonneg(p.xmax, slot, x, valid);
 }
 
 void launch_relu(const ReluParams& p, hipStream_t s) {
@@ -612,25 +715,30 @@ void launch_relu(const ReluParams& p, hipStream_t s) {
 // Input box [max(c-eps,clip_lo), min(c+eps,clip_hi)], rounded outward in float64, H,W,C order.
 __global__ void box_kernel(const BoxParams p) {
     const long long n = (long long)p.C * p.H * p.W;
-    long long idx = blockIdx.x * (long long)blockDim.x + threadIdx.x;
-    if (idx >= n * p.batch) return;
-    int b = (int)(idx / n);
-    int j = (int)(idx - (long long)b * n);   // H,W,C index
-    int pix = j / p.C, c = j - pix * p.C;
-    double ctr = (double)p.centers[(long long)b * n + (long long)c * (p.H * p.W) + pix];
-    double e = (double)p.eps;
-    double lo = nextafter(ctr - e, -INFINITY), hi = nextafter(ctr + e, INFINITY);
-    lo = fmax(lo, (double)p.clip_lo);
-    hi = fmin(hi, (double)p.clip_hi);
-    if (lo > hi) {
-        if (ctr < (double)p.clip_lo) lo = hi = (double)p.clip_lo;
-        else lo = hi = (double)p.clip_hi;
+    const long long idx = blockIdx.x * (long long)blockDim.x + threadIdx.x;
+    const bool valid = idx < n * p.batch;
+    double x = 0.0;
+    int b = 0;
+    if (valid) {
+        b = (int)(idx / n);
+        const int j = (int)(idx - (long long)b * n);   // H,W,C index
+        const int pix = j / p.C, c = j - pix * p.C;
+        const double ctr = (double)p.centers[(long long)b * n + (long long)c * (p.H * p.W) + pix];
+        const double e = (double)p.eps;
+        double lo = nextafter(ctr - e, -INFINITY), hi = nextafter(ctr + e, INFINITY);
+        lo = fmax(lo, (double)p.clip_lo);
+        hi = fmin(hi, (double)p.clip_hi);
+        if (lo > hi) {
+            if (ctr < (double)p.clip_lo) lo = hi = (double)p.clip_lo;
+            else lo = hi = (double)p.clip_hi;
+        }
+        if (!isfinite(lo) || !isfinite(hi)) *p.flag = 1;
+        p.lo[idx] = lo;
+        p.hi[idx] = hi;
+        x = fmax(fabs(lo), fabs(hi));
+        if (!isfinite(x)) x = 0.0;
     }
-    if (!isfinite(lo) || !isfinite(hi)) *p.flag = 1;
-    p.lo[idx] = lo;
-    p.hi[idx] = hi;
-    double x = fmax(fabs(lo), fabs(hi));
-    if (isfinite(x)) atomic_max_nonneg(p.xmax + b, x);
+    atomic_max_nonneg(p.xmax, b, x, valid);
 }
 
 void launch_box(const BoxParams& p, hipStream_t s) {
