@@ -26,6 +26,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=1, help="index into the five synthetic configurations")
     ap.add_argument("--batch", type=int, default=0, help="inputs per pass (default: all inputs of the configuration)")
+    ap.add_argument("--dump", default="", help="write one CSV line per profiled kernel launch to this file")
     ap.add_argument("--cpu-sample", type=int, default=-1, help="inputs the oracle is timed on (0: skip)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -67,6 +68,8 @@ def main():
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     gpu_ms = e0.elapsed_time(e1)
+    if args.dump:
+        g.profile_dump(args.dump)
     prof = g.profile_read()
     g.profile_enable(False)
     ms_per_step = wall_ms / args.steps

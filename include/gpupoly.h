@@ -123,6 +123,9 @@ gp_status gp_debug_plan(const gp_net* net, int32_t layer_id, int32_t* steps, int
  * steps they carried out, then resets the counters.  All four arrays have 2 entries. */
 gp_status gp_profile_enable(gp_net* net, int32_t on);
 gp_status gp_profile_read(gp_net* net, int64_t* launches, double* total_ms, double* alg_flop, double* alg_bytes);
+/* One CSV line per launch recorded since gp_profile_enable (kernel, start layer, layer, rows, block sizes, N, K,
+ * algorithmic flop, duration in us), written to `path`; call it before gp_profile_read. */
+gp_status gp_profile_dump(gp_net* net, const char* path);
 
 /* Self-check of the matrix instruction the crossing kernel relies on: D[16][16] = A[16][K] * B[K][16]
  * in float64 MFMA (K a multiple of 4; A, B, D row-major in device memory), enqueued on hip_stream.

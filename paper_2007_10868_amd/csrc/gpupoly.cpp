@@ -102,6 +102,8 @@ struct gp_net {
     std::vector<hipEvent_t> prof_ev[2];     // start/stop pairs
     size_t prof_used[2] = {0, 0};
     double prof_flop[2] = {0, 0}, prof_bytes[2] = {0, 0};
+    struct ProfRec { int kind, start, layer, nrows, in_el, out_el, n, k; double flop; };
+    std::vector<ProfRec> prof_recs[2];
 };
 
 namespace {
@@ -595,7 +597,10 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                 prof_mark(net, 1, false);
                 gp::launch_scan(sp, net->stream);
                 prof_mark(net, 1, true);
-                if (net->prof_on) net->prof_bytes[1] += 4.0 * nrows * (double)block_elems(op.g_in, l);
+                if (net->prof_on) {
+                    net->prof_bytes[1] += 4.0 * nrows * (double)block_elems(op.g_in, l);
+                    net->prof_recs[1].push_back({1, start, op.layer_in, nrows, (int)block_elems(op.g_in, l), 0, l.C, 0, 0.0});
+                }
             } else if (op.kind == PlanOp::CROSS) {
                 const Layer& a = net->L[op.layer_in];
                 const Layer& p = net->L[op.layer_out];
@@ -623,10 +628,10 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                     if (op.slot_add >= 0) cp.add = make_desc(net, slot_ptr(op.slot_add), op.g_add, op.layer_out);
                 }
                 cp.rm = rm; cp.nrows = nrows;
-                cp.div_opix = gp::make_fastdiv((uint32_t)(cp.owy * cp.owx));
                 cp.div_owx = gp::make_fastdiv((uint32_t)cp.owx);
                 cp.div_sh = gp::make_fastdiv((uint32_t)cp.sh);
                 cp.div_sw = gp::make_fastdiv((uint32_t)cp.sw);
+                cp.div_kw = gp::make_fastdiv((uint32_t)cp.kw);
                 prof_mark(net, 0, false);
                 gp::launch_cross(cp, net->stream);
                 prof_mark(net, 0, true);
@@ -639,6 +644,8 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                     const double cin = (a.type == T_DENSE) ? (double)p.n : (double)p.C;
                     const bool first = (op.layer_in == start);
                     if (!first) net->prof_flop[0] += 2.0 * nrows * in_el * taps * cin;
+                    net->prof_recs[0].push_back({0, start, op.layer_in, nrows, (int)in_el, (int)out_el, (int)cin, (int)(taps * a.C),
+                                                 first ? 0.0 : 2.0 * nrows * in_el * taps * cin});
                     net->prof_bytes[0] += 4.0 * nrows * (in_el + out_el) + 4.0 * (double)a.wt_host.size();
                 }
             } else if (op.kind == PlanOp::FINALIZE) {
@@ -1108,7 +1115,27 @@ const char* gp_last_error(const gp_net* net) { return net ? net->err.c_str() : "
 gp_status gp_profile_enable(gp_net* net, int32_t on) {
     if (!net) return GP_ERR_ARG;
     net->prof_on = on != 0;
-    for (int k = 0; k < 2; ++k) { net->prof_used[k] = 0; net->prof_flop[k] = net->prof_bytes[k] = 0.0; }
+    for (int k = 0; k < 2; ++k) { net->prof_used[k] = 0; net->prof_flop[k] = net->prof_bytes[k] = 0.0; net->prof_recs[k].clear(); }
+    return GP_OK;
+}
+
+// Writes one CSV line per profiled launch since gp_profile_enable (kernel, start layer, layer, rows, block sizes,
+// N, K, algorithmic flop, duration in us); synchronises.  Call before gp_profile_read, which resets the records.
+gp_status gp_profile_dump(gp_net* net, const char* path) {
+    if (!net || !path) return GP_ERR_ARG;
+    HIP_TRY(net, hipStreamSynchronize(net->stream));
+    FILE* f = fopen(path, "w");
+    if (!f) return fail(net, GP_ERR_ARG, "cannot open %s", path);
+    fprintf(f, "kernel,start_layer,layer,rows,in_elems,out_elems,N,K,alg_flop,us\n");
+    for (int k = 0; k < 2; ++k)
+        for (size_t i = 0; i < net->prof_recs[k].size() && 2 * i + 1 < net->prof_used[k]; ++i) {
+            float t = 0.f;
+            (void)hipEventElapsedTime(&t, net->prof_ev[k][2 * i], net->prof_ev[k][2 * i + 1]);
+            const gp_net::ProfRec& r = net->prof_recs[k][i];
+            fprintf(f, "%s,%d,%d,%d,%d,%d,%d,%d,%.6g,%.2f\n", k == 0 ? "cross" : "scan", r.start, r.layer, r.nrows, r.in_el,
+                    r.out_el, r.n, r.k, r.flop, t * 1e3);
+        }
+    fclose(f);
     return GP_OK;
 }
 
@@ -1128,6 +1155,7 @@ gp_status gp_profile_read(gp_net* net, int64_t* launches, double* total_ms, doub
         alg_bytes[k] = net->prof_bytes[k];
         net->prof_used[k] = 0;
         net->prof_flop[k] = net->prof_bytes[k] = 0.0;
+        net->prof_recs[k].clear();
     }
     return GP_OK;
 }

@@ -98,6 +98,12 @@ __device__ __forceinline__ float relax_factor(double a, float g) {
 //   The MFMA pipe and the vector ALU share the issue port, so everything outside the MFMAs is kept to a
 //   few instructions per K step: 32-bit offsets into per-tile buffer resources, range-checked loads
 //   instead of masks, tap geometry without divisions.
+// Work decomposition: grid.x = tiles of BM rows, grid.y = output pixel of the window, grid.z = tiles of BN
+// input channels.  All rows of a work-group therefore produce the SAME window pixel, so the filter taps
+// that can reach that pixel from inside the rows' windows are (nearly) the same for all of them: the taps
+// that no row of the tile can use are skipped altogether (Algorithm 1 only visits pairs of a window entry
+// and a tap; a gather over all taps of every output pixel would multiply many structural zeros, most of
+// all for small windows and for strided layers).
 template <int BM, int BN, bool VEC>
 __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
     constexpr int BK = 16;
@@ -106,31 +112,31 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
     constexpr int WAVES_M = 4 / WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
     constexpr int TM = WTM / 16, TN = WTN / 16;
-    constexpr int APT = (BM + 63) / 64;             // A pixels per thread
+    constexpr int APT = (BM + 63) / 64;             // A rows per thread
     constexpr int BPT = (BN + 63) / 64;             // B columns per thread
     static_assert(TM >= 1 && TN >= 1, "tile");
 
     __shared__ __attribute__((aligned(16))) double As[2][BM][LDK];
     __shared__ __attribute__((aligned(16))) double Bs[2][BN][LDK];
+    __shared__ unsigned long long s_tapmask;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     const int lk = lane >> 4, lm = lane & 15;
-    const uint32_t opix = (uint32_t)(p.owy * p.owx);
-    const uint32_t M = (uint32_t)p.nrows * opix;            // < 2^31 (host guarantees)
-    const uint32_t m0 = blockIdx.x * (uint32_t)BM;
-    const int n0 = blockIdx.y * BN;
+    const int opix = p.owy * p.owx;
+    const int r_tile = blockIdx.x * BM;                       // first row of the tile
+    const int pix = blockIdx.y;                               // window pixel of the tile (uniform)
+    const int pa = (int)fast_div((uint32_t)pix, p.div_owx), pb = pix - pa * p.owx;
+    const int n0 = blockIdx.z * BN;
     const int Ck = p.in.C, N = p.Co;
     const int taps = p.kh * p.kw;
     const int kchunks = (Ck + BK - 1) / BK;
-    const int nIt = taps * kchunks;
     const uint32_t row_elems = (uint32_t)(p.in.wy * p.in.wx * Ck);
 
     // ---- buffer resources: A covers the rows of this tile only (32-bit offsets), B the layer's filter
-    const uint32_t r_first = fast_div(m0, p.div_opix);
-    const uint32_t r_last = fast_div(min(m0 + BM - 1, M - 1), p.div_opix);
+    const int rows_here = min(BM, p.nrows - r_tile);
     const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)(p.in.data + (size_t)r_first * row_elems), 0, (int)((r_last - r_first + 1) * row_elems * 4u), 0x00020000);
+        (void*)(p.in.data + (size_t)r_tile * row_elems), 0, (int)((uint32_t)rows_here * row_elems * 4u), 0x00020000);
     const __amdgpu_buffer_rsrc_t rsrcB =
         __builtin_amdgcn_make_buffer_rsrc((void*)p.wt, 0, (int)((uint32_t)taps * N * Ck * 4u), 0x00020000);
 
@@ -141,25 +147,21 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
     bool a_ok[APT];
 #pragma unroll
     for (int i = 0; i < APT; ++i) {
-        const uint32_t m = m0 + ld_row + 64 * i;
-        a_ok[i] = (ld_row + 64 * i < BM) && m < M;
-        const uint32_t mm = a_ok[i] ? m : m0;
-        const uint32_t r = fast_div(mm, p.div_opix);
-        const uint32_t rem = mm - r * opix;
-        const uint32_t a = fast_div(rem, p.div_owx), bb = rem - a * (uint32_t)p.owx;
-        const RowInfo ri = row_info(p.rm, (int)r);
-        // output pixel (A,B) of the input layer; tap (f,g) of the filter reads it from layer-output pixel
-        // ((A + ph - f)/sh, (B + pw - g)/sw) when both divisions are exact
-        const uint32_t yy0 = (uint32_t)(clampi(p.oSy * ri.ys - p.oPy, 0, p.Ho - p.owy) + (int)a + p.ph);
-        const uint32_t xx0 = (uint32_t)(clampi(p.oSx * ri.xs - p.oPx, 0, p.Wo - p.owx) + (int)bb + p.pw);
+        const int rl = ld_row + 64 * i;
+        a_ok[i] = rl < rows_here;
+        const RowInfo ri = row_info(p.rm, r_tile + (a_ok[i] ? rl : 0));
+        // window pixel (pa,pb) is pixel (A,B) of the input layer; tap (f,g) of the filter reads it from
+        // layer-output pixel ((A + ph - f)/sh, (B + pw - g)/sw) when both divisions are exact
+        const uint32_t yy0 = (uint32_t)(clampi(p.oSy * ri.ys - p.oPy, 0, p.Ho - p.owy) + pa + p.ph);
+        const uint32_t xx0 = (uint32_t)(clampi(p.oSx * ri.xs - p.oPx, 0, p.Wo - p.owx) + pb + p.pw);
         const uint32_t yd = fast_div(yy0, p.div_sh), xd = fast_div(xx0, p.div_sw);
         a_ydiv[i] = (int)yd; a_ymod[i] = (int)(yy0 - yd * (uint32_t)p.sh);
         a_xdiv[i] = (int)xd; a_xmod[i] = (int)(xx0 - xd * (uint32_t)p.sw);
         a_oiy[i] = clampi(p.in.Sy * ri.ys - p.in.Py, 0, p.in.H - p.in.wy);
         a_oix[i] = clampi(p.in.Sx * ri.xs - p.in.Px, 0, p.in.W - p.in.wx);
-        a_rowoff[i] = ((r - r_first) * row_elems + (uint32_t)q4) * 4u;
+        a_rowoff[i] = ((uint32_t)rl * row_elems + (uint32_t)q4) * 4u;
     }
-    // per-thread byte offsets for the current tap: A pixel (kOOB when the tap misses the window), B column
+    // per-thread byte offsets for the current tap: A row (kOOB when the tap misses the row's window), B column
     uint32_t a_voff[APT], b_voff[BPT];
 #pragma unroll
     for (int i = 0; i < BPT; ++i) {
@@ -167,8 +169,13 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
         const bool ok = (ld_row + 64 * i < BN) && n < N;
         b_voff[i] = ok ? ((uint32_t)n * (uint32_t)Ck + (uint32_t)q4) * 4u : kOOB;
     }
-    // tap (f,g) written as f = fdiv*sh + fmod, g = gdiv*sw + gmod (all uniform)
-    auto set_tap = [&](int fdiv, int fmod, int gdiv, int gmod) {
+    // tap (f,g) written as f = fdiv*sh + fmod, g = gdiv*sw + gmod (all uniform); returns whether any of
+    // this thread's rows uses the tap
+    auto set_tap = [&](int t) -> bool {
+        const int f = (int)fast_div((uint32_t)t, p.div_kw), g = t - f * p.kw;
+        const int fdiv = (int)fast_div((uint32_t)f, p.div_sh), fmod = f - fdiv * p.sh;
+        const int gdiv = (int)fast_div((uint32_t)g, p.div_sw), gmod = g - gdiv * p.sw;
+        bool any = false;
 #pragma unroll
         for (int i = 0; i < APT; ++i) {
             const int y = a_ydiv[i] - fdiv, x = a_xdiv[i] - gdiv;
@@ -177,10 +184,38 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
                             (unsigned)y < (unsigned)p.in.H && (unsigned)x < (unsigned)p.in.W &&
                             (unsigned)yi < (unsigned)p.in.wy && (unsigned)xi < (unsigned)p.in.wx;
             a_voff[i] = ok ? a_rowoff[i] + (uint32_t)(yi * p.in.wx + xi) * (uint32_t)(Ck * 4) : kOOB;
+            any = any || ok;
         }
+        return any;
     };
-    int ld_t = 0, ld_d0 = 0, ld_g = 0, ld_fdiv = 0, ld_fmod = 0, ld_gdiv = 0, ld_gmod = 0;
-    set_tap(0, 0, 0, 0);
+
+    // ---- which taps does this tile need at all?  (bit t of the mask; filters with more than 64 taps keep all)
+    unsigned long long tapmask = ~0ull;
+    if (taps > 1 && taps <= 64) {
+        unsigned long long mine = 0;
+        for (int t = 0; t < taps; ++t)
+            if (set_tap(t)) mine |= 1ull << t;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) mine |= __shfl_xor(mine, off, 64);
+        if (tid == 0) s_tapmask = 0;
+        __syncthreads();
+        if (lane == 0) atomicOr(&s_tapmask, mine);
+        __syncthreads();
+        tapmask = s_tapmask;
+    } else if (taps < 64) {
+        tapmask = (1ull << taps) - 1;
+    }
+    // taps beyond 64 (huge filters) are all visited
+    auto next_tap = [&](int t) -> int {          // first needed tap >= t, or taps
+        while (t < taps && t < 64 && !((tapmask >> t) & 1ull)) ++t;
+        return t;
+    };
+    int n_taps = 0;
+    for (int t = next_tap(0); t < taps; t = next_tap(t + 1)) ++n_taps;
+    const int nIt = n_taps * kchunks;
+
+    int ld_t = next_tap(0), ld_d0 = 0;
+    if (ld_t < taps) set_tap(ld_t);
 
     // global -> register staging holds raw float32 words only: nothing depends on the loads until the
     // MFMA loop of the current tile has been issued; conversion happens at the register -> LDS copy.
@@ -214,17 +249,10 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
                 b_raw[i] = buf_ld4<VEC>(rsrcB, (dok && b_voff[i] != kOOB) ? b_voff[i] + soffB : kOOB, rem - q4);
         }
         ld_d0 += BK;
-        if (ld_d0 >= Ck) {                                          // next tap (uniform, once per kchunks steps)
+        if (ld_d0 >= Ck) {                                          // next needed tap (uniform, once per kchunks steps)
             ld_d0 = 0;
-            ++ld_t;
-            ++ld_g; ++ld_gmod;
-            if (ld_gmod == p.sw) { ld_gmod = 0; ++ld_gdiv; }
-            if (ld_g == p.kw) {
-                ld_g = 0; ld_gdiv = 0; ld_gmod = 0;
-                ++ld_fmod;
-                if (ld_fmod == p.sh) { ld_fmod = 0; ++ld_fdiv; }
-            }
-            if (ld_t < taps) set_tap(ld_fdiv, ld_fmod, ld_gdiv, ld_gmod);
+            ld_t = next_tap(ld_t + 1);
+            if (ld_t < taps) set_tap(ld_t);
         }
     };
     // LDS addresses of this thread's stores and MFMA operand loads (fixed; the buffer index is an immediate)
@@ -280,23 +308,25 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
         }
     };
 
-    load_tiles();
-    store_tiles(0);
-    __syncthreads();
-    // two K steps per trip so that the LDS buffer index is a compile-time constant
-    int it = 0;
-    for (; it + 2 <= nIt; it += 2) {
-        load_tiles();                  // tile it+1 (exists)
-        mfma_tile(0);
-        store_tiles(1);
+    if (nIt > 0) {
+        load_tiles();
+        store_tiles(0);
         __syncthreads();
-        const bool more = it + 2 < nIt;
-        if (more) load_tiles();        // tile it+2
-        mfma_tile(1);
-        if (more) store_tiles(0);
-        __syncthreads();
+        // two K steps per trip so that the LDS buffer index is a compile-time constant
+        int it = 0;
+        for (; it + 2 <= nIt; it += 2) {
+            load_tiles();                  // tile it+1 (exists)
+            mfma_tile(0);
+            store_tiles(1);
+            __syncthreads();
+            const bool more = it + 2 < nIt;
+            if (more) load_tiles();        // tile it+2
+            mfma_tile(1);
+            if (more) store_tiles(0);
+            __syncthreads();
+        }
+        if (it < nIt) mfma_tile(0);
     }
-    if (it < nIt) mfma_tile(0);
 
     // ---- epilogue: (+ residual addend) (* ReLU substitution of the destination layer) -> one rounding to
     // float32 -> store.  D[i][j]: register r of lane l holds i = 4*r + l/16, j = l%16.
@@ -306,17 +336,14 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
         for (int r4 = 0; r4 < 4; ++r4) {
-            const uint32_t m = m0 + wm * WTM + i * 16 + 4 * r4 + lk;
-            if (m >= M) continue;
+            const int r = r_tile + wm * WTM + i * 16 + 4 * r4 + lk;
+            if (r >= p.nrows) continue;
             const float* add_src = nullptr;
             size_t ridx = 0;
             if (need_pos) {
-                const uint32_t r = fast_div(m, p.div_opix);
-                const uint32_t rem = m - r * opix;
-                const uint32_t a = fast_div(rem, p.div_owx), bb = rem - a * (uint32_t)p.owx;
-                const RowInfo ri = row_info(p.rm, (int)r);
-                const int A = clampi(p.oSy * ri.ys - p.oPy, 0, p.Ho - p.owy) + (int)a;
-                const int B = clampi(p.oSx * ri.xs - p.oPx, 0, p.Wo - p.owx) + (int)bb;
+                const RowInfo ri = row_info(p.rm, r);
+                const int A = clampi(p.oSy * ri.ys - p.oPy, 0, p.Ho - p.owy) + pa;
+                const int B = clampi(p.oSx * ri.xs - p.oPx, 0, p.Wo - p.owx) + pb;
                 ridx = (size_t)ri.b * ((size_t)p.Ho * p.Wo * N) + (size_t)(A * p.Wo + B) * N;
                 if (has_add) {
                     const int ay = A - clampi(p.add.Sy * ri.ys - p.add.Py, 0, p.add.H - p.add.wy);
@@ -325,7 +352,7 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
                         add_src = p.add.data + ((size_t)r * p.add.wy * p.add.wx + (size_t)(ay * p.add.wx + ax)) * N;
                 }
             }
-            float* out_row = p.out + (size_t)m * N;
+            float* out_row = p.out + ((size_t)r * opix + pix) * N;
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const int n = n0 + wn * WTN + j * 16 + lm;
@@ -341,16 +368,14 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
 
 template <int BM, int BN>
 static void launch_cross_t(const CrossParams& p, hipStream_t s) {
-    long long M = (long long)p.nrows * p.owy * p.owx;
-    dim3 grid((unsigned)((M + BM - 1) / BM), (unsigned)((p.Co + BN - 1) / BN));
+    dim3 grid((unsigned)((p.nrows + BM - 1) / BM), (unsigned)(p.owy * p.owx), (unsigned)((p.Co + BN - 1) / BN));
     const bool vec = (p.in.C & 3) == 0;
     if (vec) hipLaunchKernelGGL((cross_kernel<BM, BN, true>), grid, dim3(256), 0, s, p);
     else hipLaunchKernelGGL((cross_kernel<BM, BN, false>), grid, dim3(256), 0, s, p);
 }
 
 void launch_cross(const CrossParams& p, hipStream_t s) {
-    long long M = (long long)p.nrows * p.owy * p.owx;
-    if (M <= 0 || p.Co <= 0) return;
+    if (p.nrows <= 0 || p.Co <= 0) return;
     const int N = p.Co;
     static const char* tile_env = getenv("GP_TILE");
     if (tile_env && N > 32) {
@@ -361,9 +386,6 @@ void launch_cross(const CrossParams& p, hipStream_t s) {
     }
     if (N <= 16) { launch_cross_t<128, 16>(p, s); return; }
     if (N <= 32) { launch_cross_t<128, 32>(p, s); return; }
-    // enough work-groups to fill 256 compute units several times over?
-    long long wg = ((M + 127) / 128) * ((N + 63) / 64);
-    if (wg >= 1024) { launch_cross_t<128, 64>(p, s); return; }
     launch_cross_t<64, 64>(p, s);
 }
 

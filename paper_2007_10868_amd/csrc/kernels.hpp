@@ -63,7 +63,7 @@ struct CrossParams {       // one back-substitution step through an affine layer
                            //   the new coefficients before they are rounded and stored; null: store as is
     int Ho, Wo, Co;        // dims of the input layer
     int owy, owx, oSy, oSx, oPy, oPx;
-    FastDiv div_opix, div_owx, div_sh, div_sw;   // owy*owx, owx, sh, sw
+    FastDiv div_owx, div_sh, div_sw, div_kw;     // owx, sh, sw, kw
     BlockDesc add;         // optional block over the same input layer to be summed in (residual join)
     RowMap rm;
     int nrows;
