@@ -99,6 +99,9 @@ gp_status gp_get_bounds_f64(const gp_net* net, int32_t layer_id, int32_t batch_i
                             double* upper);
 /* Lower relaxation slope (0 or 1) chosen for each neuron of a ReLU layer; [n_layer] bytes. */
 gp_status gp_get_relu_lambda(const gp_net* net, int32_t relu_layer_id, int32_t batch_index, int8_t* lam);
+/* Slope of the upper relaxation line used for each neuron of a ReLU layer (1 for stably active, 0 for
+ * stably inactive neurons; any slope in [0,1] is sound with the matching intercept); [n_layer] floats. */
+gp_status gp_get_relu_slopes(const gp_net* net, int32_t relu_layer_id, int32_t batch_index, float* slope);
 
 /* Robustness of `label` over the analysed box: margins[r] = sound lower bound of
  * y_label - y_j over the last layer for the r-th j != label (increasing j), obtained by

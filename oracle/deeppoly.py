@@ -49,7 +49,9 @@ def _load():
     L.dp_layer_size.argtypes = [P, C.c_int]
     L.dp_set_options.argtypes = [P, C.c_int, C.c_int]
     L.dp_request_bounds.argtypes = [P, C.c_int]
+    L.dp_set_collapse.argtypes = [P, C.c_int]
     L.dp_set_lambda_override.argtypes = [P, C.c_int, bp]
+    L.dp_set_gamma_override.argtypes = [P, C.c_int, dp]
     L.dp_set_box.argtypes = [P, dp, dp]
     L.dp_set_ball.argtypes = [P, fp, C.c_float, C.c_float, C.c_float]
     L.dp_set_bounds.argtypes = [P, C.c_int, dp, dp]
@@ -154,6 +156,10 @@ class OracleNet:
     def set_options(self, lambda_policy=0, candidates=0):
         self._chk(self._L.dp_set_options(self._h, lambda_policy, candidates), "set_options")
 
+    def set_collapse(self, on: bool):
+        """False: keep interval coefficients for the whole back-substitution (the literal scheme of Section 4.1)."""
+        self._chk(self._L.dp_set_collapse(self._h, 1 if on else 0), "set_collapse")
+
     def request_bounds(self, lid):
         self._chk(self._L.dp_request_bounds(self._h, lid), "request_bounds")
 
@@ -165,6 +171,14 @@ class OracleNet:
         assert f.size == self.layer_size(lid)
         self._chk(self._L.dp_set_lambda_override(self._h, lid, f.ctypes.data_as(C.POINTER(C.c_byte))),
                   "set_lambda_override")
+
+    def set_gamma_override(self, lid, gam: Optional[np.ndarray]):
+        if gam is None:
+            self._chk(self._L.dp_set_gamma_override(self._h, lid, None), "set_gamma_override")
+            return
+        g, pg = _f64(gam)
+        assert g.size == self.layer_size(lid)
+        self._chk(self._L.dp_set_gamma_override(self._h, lid, pg), "set_gamma_override")
 
     # -- analysis ---------------------------------------------------------------------------
     def set_box(self, lo, hi):

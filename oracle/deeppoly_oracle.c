@@ -32,6 +32,17 @@
  *   - a candidate is evaluated whenever the expression ranges over exactly one layer that has
  *     intervals.
  *   - a label is certified by lower bounds of y_label - y_j.
+ *   - width of the interval coefficients.  Section 4.1 keeps every coefficient as an interval for the
+ *     whole back-substitution.  Pushed through further layers the WIDTHS are multiplied by |F| while the
+ *     coefficients are multiplied by F, so relative to the coefficients they grow by about
+ *     0.4*sqrt(fan-in) per layer; after some 15 convolutional layers a float64 interval is as wide as
+ *     the coefficient itself and the bounds are useless (measured on a 50-layer residual net).  The
+ *     paper's networks are analysed with early termination, which hides this.  Reading taken here
+ *     (option collapse = 1, the default): before a layer of the expression is substituted, every
+ *     interval coefficient [lo,hi] over a neuron with known interval is replaced by a point m in it
+ *     and max(hi-m, m-lo) * max|neuron| is added outward to the constant.  This is sound for the same
+ *     reason concretisation is, keeps float64 and outward rounding, and stops the growth.  collapse = 0
+ *     is the literal scheme.
  *
  * Neuron order inside a layer: C,H,W flattened (channel outermost).
  *
@@ -65,6 +76,7 @@ typedef struct {
     double *gam, *del;       /* ReLU: upper line gam*x+del (unstable neurons)      */
     signed char *lam;        /* ReLU: lower line lam*x                             */
     signed char *lam_force;  /* optional per-neuron override: -1 none, 0, 1        */
+    double *gam_force;       /* optional per-neuron slope of the upper line (NaN: none) */
 } layer_t;
 
 typedef struct {
@@ -72,6 +84,7 @@ typedef struct {
     layer_t *L;
     int lambda_policy;       /* 0: lam=1 iff u>-l   1: always 0   2: always 1      */
     int candidates;          /* 0: every step       1: input layer only            */
+    int collapse;            /* 1: re-centre interval coefficients before each substitution (default) */
     int analyzed;
 } dp_net;
 
@@ -89,6 +102,7 @@ dp_net *dp_create(int c, int h, int w) {
     if (c <= 0 || h <= 0 || w <= 0) return NULL;
     dp_net *N = (dp_net *)calloc(1, sizeof(dp_net));
     N->cap = 16;
+    N->collapse = 1;
     N->L = (layer_t *)calloc(N->cap, sizeof(layer_t));
     N->n_layers = 1;
     layer_t *I = &N->L[0];
@@ -178,7 +192,7 @@ void dp_destroy(dp_net *N) {
     for (int i = 0; i < N->n_layers; ++i) {
         layer_t *l = &N->L[i];
         free(l->wt); free(l->bias); free(l->lo); free(l->hi); free(l->gam); free(l->del);
-        free(l->lam); free(l->lam_force);
+        free(l->lam); free(l->lam_force); free(l->gam_force);
     }
     free(N->L); free(N);
 }
@@ -188,6 +202,11 @@ int dp_layer_size(const dp_net *N, int lid) { return (N && lid >= 0 && lid < N->
 int dp_set_options(dp_net *N, int lambda_policy, int candidates) {
     if (!N || lambda_policy < 0 || lambda_policy > 2 || candidates < 0 || candidates > 1) return DP_ERR_ARG;
     N->lambda_policy = lambda_policy; N->candidates = candidates;
+    return DP_OK;
+}
+int dp_set_collapse(dp_net *N, int on) {
+    if (!N) return DP_ERR_ARG;
+    N->collapse = on ? 1 : 0;
     return DP_OK;
 }
 int dp_request_bounds(dp_net *N, int lid) {
@@ -201,6 +220,16 @@ int dp_set_lambda_override(dp_net *N, int lid, const signed char *force) {
     layer_t *l = &N->L[lid];
     free(l->lam_force); l->lam_force = NULL;
     if (force) { l->lam_force = (signed char *)malloc(l->n); memcpy(l->lam_force, force, l->n); }
+    return DP_OK;
+}
+
+/* gam[i]: slope to use for the upper line of unstable neuron i (any value in [0,1] is sound, see relu_layer);
+   NaN entries and NULL mean "the oracle's own choice".  lid is a ReLU layer. */
+int dp_set_gamma_override(dp_net *N, int lid, const double *gam) {
+    if (!N || lid <= 0 || lid >= N->n_layers || N->L[lid].type != L_RELU) return DP_ERR_ARG;
+    layer_t *l = &N->L[lid];
+    free(l->gam_force); l->gam_force = NULL;
+    if (gam) { l->gam_force = (double *)malloc(sizeof(double) * l->n); memcpy(l->gam_force, gam, sizeof(double) * l->n); }
     return DP_OK;
 }
 
@@ -281,6 +310,7 @@ static void relu_layer(dp_net *N, int lid) {
         else if (u <= 0.0) { r->gam[i] = 0.0; r->del[i] = 0.0; r->lam[i] = 0; }
         else {
             double g = u / sub_up(u, l);           /* any value in [0,1] is sound */
+            if (r->gam_force && r->gam_force[i] == r->gam_force[i]) g = r->gam_force[i];
             if (g > 1.0) g = 1.0;
             if (g < 0.0) g = 0.0;
             double d1 = mul_up(-l, g);             /* -g*l, rounded up            */
@@ -356,6 +386,26 @@ static double concretise(const dp_net *N, const expr_t *e, int k, int sense) {
         }
     }
     return acc;
+}
+
+/* Replace every interval coefficient over layer k by a point inside it; the part given up,
+   |coefficient - point| <= w, can change the expression by at most w * max|x_j|, which goes into the
+   constant on the side that keeps the bound valid. */
+static void collapse_width(const dp_net *N, expr_t *e, int k, int sense) {
+    const layer_t *l = &N->L[k];
+    double *alo = e->lo[k], *ahi = e->hi[k];
+    for (int j = 0; j < l->n; ++j) {
+        double a = alo[j], b = ahi[j];
+        if (a == b) continue;
+        double m = a + (b - a) * 0.5;
+        if (!(m >= a && m <= b)) m = a;
+        double w = dmax(sub_up(b, m), sub_up(m, a));
+        double X = dmax(fabs(l->lo[j]), fabs(l->hi[j]));
+        double slack = mul_up(w, X);
+        if (sense > 0) e->chi = add_up(e->chi, slack);
+        else e->clo = add_dn(e->clo, -slack);
+        alo[j] = ahi[j] = m;
+    }
 }
 
 /* substitute the ReLU layer k: its neurons are replaced by their relaxation over layer a */
@@ -473,6 +523,7 @@ static double backsubstitute(const dp_net *N, expr_t *e, int sense) {
             double v = (sense > 0) ? e->chi : e->clo;
             return (sense > 0) ? dmin(best, v) : dmax(best, v);
         }
+        if (N->collapse && N->L[k].has_bounds) collapse_width(N, e, k, sense);
         if (count == 1 && N->L[k].has_bounds && (k == 0 || N->candidates == 0)) {
             double v = concretise(N, e, k, sense);
             best = (sense > 0) ? dmin(best, v) : dmax(best, v);

@@ -593,6 +593,7 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                 sp.round_coef = op.rounded ? kRoundCoef : 0.0;
                 sp.do_consts = op.do_consts ? 1 : 0;
                 sp.update_best = op.update_best ? 1 : 0;
+                { static const char* dbg = getenv("GP_DEBUG_INPUT_ONLY"); if (dbg && op.layer_in != 0) sp.update_best = 0; }
                 sp.c = d_c; sp.err = d_err; sp.best = d_best;
                 prof_mark(net, 1, false);
                 gp::launch_scan(sp, net->stream);
@@ -1046,6 +1047,22 @@ gp_status gp_get_relu_lambda(const gp_net* net, int32_t layer_id, int32_t batch_
     const long long hw = (long long)l.H * l.W;
     for (long long pix = 0; pix < hw; ++pix)
         for (int c = 0; c < l.C; ++c) lam[c * hw + pix] = std::signbit(v[pix * l.C + c]) ? 0 : 1;
+    return GP_OK;
+}
+
+gp_status gp_get_relu_slopes(const gp_net* net, int32_t layer_id, int32_t batch_index, float* slope) {
+    if (!net) return GP_ERR_ARG;
+    if (!slope) return fail(net, GP_ERR_ARG, "output pointer is null");
+    if (layer_id <= 0 || layer_id >= (int)net->L.size() || net->L[layer_id].type != T_RELU)
+        return fail(net, GP_ERR_ARG, "layer %d is not a ReLU layer", layer_id);
+    if (!net->analyzed) return fail(net, GP_ERR_STATE, "no successful analysis yet");
+    if (batch_index < 0 || batch_index >= net->batch) return fail(net, GP_ERR_ARG, "batch index out of range");
+    const Layer& l = net->L[layer_id];
+    std::vector<float> v(l.n);
+    HIP_TRY(net, hipMemcpy(v.data(), l.d_grl + (size_t)batch_index * l.n, l.n * sizeof(float), hipMemcpyDeviceToHost));
+    const long long hw = (long long)l.H * l.W;
+    for (long long pix = 0; pix < hw; ++pix)
+        for (int c = 0; c < l.C; ++c) slope[c * hw + pix] = std::fabs(v[pix * l.C + c]);
     return GP_OK;
 }
 

@@ -19,7 +19,7 @@ STATUS = {0: "GP_OK", 1: "GP_ERR_ARG", 2: "GP_ERR_SHAPE", 3: "GP_ERR_STATE", 4: 
 EXPORTS = ["gp_net_create", "gp_net_destroy", "gp_add_dense", "gp_add_conv2d", "gp_add_relu", "gp_add_residual",
            "gp_request_bounds", "gp_set_stream", "gp_workspace_size", "gp_set_workspace", "gp_analyze",
            "gp_analyze_box", "gp_analyze_batch", "gp_analyze_batch_dev", "gp_get_bounds", "gp_get_bounds_batch",
-           "gp_get_bounds_f64", "gp_get_relu_lambda", "gp_certify", "gp_certify_batch", "gp_debug_plan",
+           "gp_get_bounds_f64", "gp_get_relu_lambda", "gp_get_relu_slopes", "gp_certify", "gp_certify_batch", "gp_debug_plan",
            "gp_profile_enable", "gp_profile_read", "gp_profile_dump", "gp_debug_mfma_f64", "gp_num_layers", "gp_layer_size", "gp_last_error", "gp_version"]
 
 
@@ -62,6 +62,7 @@ def load_library():
     L.gp_get_bounds_batch.argtypes = [P, i32, i32, fp, fp]
     L.gp_get_bounds_f64.argtypes = [P, i32, i32, dp, dp]
     L.gp_get_relu_lambda.argtypes = [P, i32, i32, C.POINTER(C.c_int8)]
+    L.gp_get_relu_slopes.argtypes = [P, i32, i32, fp]
     L.gp_certify.argtypes = [P, i32, ip, fp]
     L.gp_certify_batch.argtypes = [P, ip, ip, fp]
     L.gp_debug_plan.argtypes = [P, i32, ip, i32, ip]
@@ -208,6 +209,12 @@ class Net:
         lam = np.empty(n, np.int8)
         self._chk(self._L.gp_get_relu_lambda(self._h, lid, batch_index, lam.ctypes.data_as(C.POINTER(C.c_int8))))
         return lam
+
+    def get_relu_slopes(self, lid, batch_index=0):
+        n = self.layer_size(lid)
+        g = np.empty(n, np.float32)
+        self._chk(self._L.gp_get_relu_slopes(self._h, lid, batch_index, g.ctypes.data_as(C.POINTER(C.c_float))))
+        return g
 
     def certify(self, label):
         n = self.layer_size(self.num_layers - 1)

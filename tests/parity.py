@@ -8,7 +8,14 @@ import workloads as wl
 from oracle import OracleNet
 
 REL_TOL = 1e-3          # a GPU bound may be looser than the oracle's by at most REL_TOL * (1 + |b|)
-CONTAIN_TOL = 2e-6      # and must contain it, up to the effect of float32-rounded relaxation slopes
+# ... and must contain it.  With the oracle's own relaxation slopes this holds only up to the effect of the
+# slopes differing slightly (GPU: float32 slope computed from intervals that are wider by the rounding
+# slack, i.e. by up to ~1e-5 relative; every slope in [0,1] is sound, so neither analysis dominates the
+# other).  The difference grows with depth; a tenth of the looseness bar is allowed:
+CONTAIN_TOL = 1e-4
+# When the oracle is told to use the GPU's slopes and lower-line choices, every transformer is monotone
+# in the intervals and the GPU intervals must contain the oracle's up to float64 rounding noise:
+STRICT_CONTAIN_TOL = 1e-9
 
 
 def analysed_layers(net: wl.Net):
@@ -32,7 +39,7 @@ def make_oracle(net: wl.Net, **opts):
     return o
 
 
-def oracle_with_gpu_ties(net: wl.Net, o: OracleNet, g, center, eps, batch_index=0, clip=(0.0, 1.0), tie=1e-6):
+def oracle_with_gpu_ties(net: wl.Net, o: OracleNet, g, center, eps, batch_index=0, clip=(0.0, 1.0), tie=1e-4):
     """Oracle analysis layer by layer.  The choice lam in {0,1} of the lower relaxation is the only
     discontinuity of the analysis: where the oracle's own interval is within `tie` of the switching
     point u = -l, it is told to take the GPU's choice.  Returns the number of such neurons."""
@@ -55,7 +62,29 @@ def oracle_with_gpu_ties(net: wl.Net, o: OracleNet, g, center, eps, batch_index=
     return forced
 
 
-def compare_layer(glo, ghi, olo, ohi, what=""):
+def oracle_with_gpu_relaxation(net: wl.Net, o: OracleNet, g, center, eps, batch_index=0, clip=(0.0, 1.0)):
+    """Oracle analysis layer by layer with the GPU's relaxation parameters (slope of the upper line, choice
+    of the lower line) for every neuron that is unstable for the oracle; intercepts and everything else
+    are the oracle's own, from its own (tighter) intervals."""
+    o.set_ball(center, eps, clip[0], clip[1])
+    for lid in range(1, o.num_layers):
+        L = net.layers[lid - 1]
+        if L["type"] == "relu":
+            o.set_lambda_override(lid, g.get_relu_lambda(lid, batch_index))
+            o.set_gamma_override(lid, g.get_relu_slopes(lid, batch_index).astype(np.float64))
+            o.analyze_layer(lid)
+        elif lid in analysed_layers(net):
+            o.analyze_layer(lid)
+
+
+def clear_overrides(net: wl.Net, o: OracleNet):
+    for lid in range(1, o.num_layers):
+        if net.layers[lid - 1]["type"] == "relu":
+            o.set_lambda_override(lid, None)
+            o.set_gamma_override(lid, None)
+
+
+def compare_layer(glo, ghi, olo, ohi, what="", contain_tol=None):
     """Returns (max looseness / allowed, max containment violation / scale); asserts the bar."""
     glo, ghi = np.asarray(glo, np.float64), np.asarray(ghi, np.float64)
     assert np.all(np.isfinite(glo)) and np.all(np.isfinite(ghi)), what
@@ -63,16 +92,17 @@ def compare_layer(glo, ghi, olo, ohi, what=""):
     loose = max(np.max((olo - glo) / s_lo), np.max((ghi - ohi) / s_hi))
     viol = max(np.max((glo - olo) / s_lo), np.max((ohi - ghi) / s_hi))
     assert loose <= REL_TOL, f"{what}: GPU bound looser than oracle by {loose:.3e} (relative), allowed {REL_TOL}"
-    assert viol <= CONTAIN_TOL, f"{what}: GPU bound inside the oracle bound by {viol:.3e} (relative)"
+    tol = CONTAIN_TOL if contain_tol is None else contain_tol
+    assert viol <= tol, f"{what}: GPU bound inside the oracle bound by {viol:.3e} (relative), allowed {tol}"
     return loose / REL_TOL, viol
 
 
-def compare_all(net, g, o, batch_index=0, what="", f64=True):
+def compare_all(net, g, o, batch_index=0, what="", f64=True, contain_tol=None):
     worst = 0.0
     for lid in analysed_layers(net):
         olo, ohi = o.get_bounds(lid)
         glo, ghi = (g.get_bounds_f64 if f64 else g.get_bounds)(lid, batch_index)
-        r, _ = compare_layer(glo, ghi, olo, ohi, f"{what} layer {lid}")
+        r, _ = compare_layer(glo, ghi, olo, ohi, f"{what} layer {lid}", contain_tol)
         worst = max(worst, r)
     return worst
 

@@ -12,8 +12,8 @@ import torch
 
 import workloads as wl
 from helpers import ball_box, forward
-from parity import (REL_TOL, analysed_layers, check_samples_inside, compare_all, compare_layer, make_gpu,
-                    make_oracle, oracle_with_gpu_ties)
+from parity import (REL_TOL, STRICT_CONTAIN_TOL, analysed_layers, check_samples_inside, clear_overrides, compare_all,
+                    compare_layer, make_gpu, make_oracle, oracle_with_gpu_relaxation, oracle_with_gpu_ties)
 
 pytestmark = pytest.mark.gpu
 
@@ -127,6 +127,9 @@ def test_small_networks_match_oracle_and_contain_samples(maker, eps):
     n_uns = sum(int(np.sum((o.get_bounds(l)[0] < 0) & (o.get_bounds(l)[1] > 0))) for l in analysed_layers(net))
     assert n_uns > 0
     print(net.name, "worst looseness / allowed =", worst)
+    # same relaxation parameters on both sides: the GPU intervals must contain the oracle's, strictly
+    oracle_with_gpu_relaxation(net, o, g, c, eps)
+    compare_all(net, g, o, what=net.name + " (GPU slopes)", contain_tol=STRICT_CONTAIN_TOL)
 
 
 def test_config0_fc6x100_all_inputs_and_certify():
@@ -309,3 +312,71 @@ def test_overflow_is_reported():
     g.analyze(c, 0.1)                       # coefficients overflow float32 on the way down
     lo0, hi0 = ball_box(c, 0.1)
     check_samples_inside(mild, g, lo0, hi0, 2_000, np.random.default_rng(0), what="mild overflow")
+
+
+def test_config3_deep_conv_one_input():
+    """~150k neurons, windows that grow until they cover the image, stride-2 layers, 4096->512 dense head."""
+    net = wl.config(3)
+    g = make_gpu(net)
+    o = make_oracle(net)
+    c = net.center(0)
+    g.analyze(c, net.eps)
+    forced = oracle_with_gpu_ties(net, o, g, c, net.eps)
+    worst = compare_all(net, g, o, what="conv_deep input 0")
+    lo0, hi0 = ball_box(c, net.eps)
+    check_samples_inside(net, g, lo0, hi0, 200, np.random.default_rng(3), what="conv_deep")
+    print("conv_deep worst looseness / allowed =", worst, "lambda ties forced:", forced)
+
+
+def _sampled_rows_against_teacher_forced_oracle(net, g, o, c, eps, rows_per_layer, rng, what):
+    """The oracle gets the GPU's intervals of all earlier layers as data (teacher forcing) and bounds a
+    sample of rows of each analysed layer on its own; the two must agree to the usual bar."""
+    o.set_ball(c, eps)
+    worst = 0.0
+    for lid in range(1, o.num_layers):
+        L = net.layers[lid - 1]
+        if L["type"] == "relu":
+            o.analyze_layer(lid)            # relaxation from the forced intervals of its input
+            continue
+        if lid not in analysed_layers(net):
+            continue
+        glo, ghi = g.get_bounds_f64(lid)
+        n = glo.size
+        rows = np.sort(rng.choice(n, size=min(rows_per_layer, n), replace=False)).astype(np.int32)
+        olo, ohi = o.bound_rows(lid, rows)
+        r, _ = compare_layer(glo[rows], ghi[rows], olo, ohi, f"{what} layer {lid}")
+        worst = max(worst, r)
+        o.set_bounds(lid, glo, ghi)
+    return worst
+
+
+def test_scaled_resnet34_full_parity():
+    """Same depth and topology as the 34-layer residual configuration, channels / 8, 16x16 input:
+    every interval of every analysed layer against the full oracle."""
+    net = wl.scaled_resnet(8, 16)
+    g = make_gpu(net)
+    o = make_oracle(net)
+    c = net.center(0)
+    g.analyze(c, net.eps)
+    forced = oracle_with_gpu_ties(net, o, g, c, net.eps)
+    worst = compare_all(net, g, o, what=net.name)
+    lo0, hi0 = ball_box(c, net.eps)
+    check_samples_inside(net, g, lo0, hi0, 500, np.random.default_rng(4), what=net.name)
+    print(net.name, "worst looseness / allowed =", worst, "ties forced:", forced)
+    oracle_with_gpu_relaxation(net, o, g, c, net.eps)
+    compare_all(net, g, o, what=net.name + " (GPU slopes)", contain_tol=STRICT_CONTAIN_TOL)
+
+
+def test_config4_resnet34_sampled_rows():
+    """The full 1M-neuron configuration: the whole oracle pass would take hours, so rows are sampled
+    per layer with teacher forcing, and every neuron is checked against sampled concrete outputs."""
+    net = wl.config(4)
+    g = make_gpu(net)
+    o = make_oracle(net)
+    c = net.center(0)
+    g.analyze(c, net.eps)
+    rng = np.random.default_rng(5)
+    worst = _sampled_rows_against_teacher_forced_oracle(net, g, o, c, net.eps, 6, rng, "resnet34")
+    lo0, hi0 = ball_box(c, net.eps)
+    check_samples_inside(net, g, lo0, hi0, 64, rng, what="resnet34")
+    print("resnet34 sampled rows: worst looseness / allowed =", worst)

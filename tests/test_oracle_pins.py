@@ -381,3 +381,42 @@ def test_errors():
         o.analyze_box([0, 0, 0, 1], [1, 1, 1, 0])       # lo > hi
     with pytest.raises(Exception):
         o.get_bounds(1)                                  # nothing analysed yet
+
+
+def test_collapsed_and_literal_interval_coefficients():
+    """The literal scheme (interval coefficients kept to the end) and the re-centred one are both sound;
+    on a shallow net they agree to rounding noise, on a deep one the literal intervals blow up."""
+    shallow = tiny_fc(5)
+    rng = np.random.default_rng(3)
+    c = rng.random(shallow.n_in).astype(np.float32)
+    a, b = make_oracle(shallow), make_oracle(shallow)
+    b.set_collapse(False)
+    a.analyze(c, 0.1)
+    b.analyze(c, 0.1)
+    for lid in analysed_layers(shallow):
+        (l1, u1), (l2, u2) = a.get_bounds(lid), b.get_bounds(lid)
+        assert np.max(np.abs(l1 - l2)) < 1e-12 and np.max(np.abs(u1 - u2)) < 1e-12
+    deep = wl.fc_net("deep_fc", [64] * 24, n_in=16, n_out=4, seed=2)
+    c = rng.random(deep.n_in).astype(np.float32)
+    a, b = make_oracle(deep), make_oracle(deep)
+    b.set_collapse(False)
+    a.analyze(c, 1e-4)
+    # same relaxations for the literal run: layer by layer with the collapsed run's intervals
+    b.set_ball(c, 1e-4)
+    X = sample_box(*ball_box(c, 1e-4), 2000, rng)
+    vals = forward(deep, X)
+    widths = []
+    for lid in range(1, b.num_layers):
+        if deep.layers[lid - 1]["type"] == "relu":
+            b.analyze_layer(lid)
+            continue
+        la, ua = a.get_bounds(lid)
+        lb, ub = b.bound_rows(lid, np.arange(la.size, dtype=np.int32))
+        v = vals[lid]
+        assert np.all(v.min(0) >= la - 1e-12) and np.all(v.max(0) <= ua + 1e-12)
+        assert np.all(v.min(0) >= lb - 1e-12) and np.all(v.max(0) <= ub + 1e-12)
+        widths.append((np.mean(ua - la), np.mean(ub - lb)))
+        b.set_bounds(lid, la, ua)
+    # the literal intervals are never tighter (up to noise) and visibly wider at the deep end
+    assert all(wb >= wa * (1 - 1e-9) for wa, wb in widths)
+    assert widths[-1][1] > widths[-1][0] * (1 + 1e-6), widths[-1]
