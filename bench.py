@@ -26,6 +26,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=1, help="index into the five synthetic configurations")
     ap.add_argument("--batch", type=int, default=0, help="inputs per pass (default: all inputs of the configuration)")
+    ap.add_argument("--calib-copy-mb", type=int, default=0, help="run one plain device copy of this many MiB first (scale for HBM counters)")
     ap.add_argument("--dump", default="", help="write one CSV line per profiled kernel launch to this file")
     ap.add_argument("--cpu-sample", type=int, default=-1, help="inputs the oracle is timed on (0: skip)")
     args = ap.parse_args()
@@ -54,6 +55,12 @@ def main():
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     g.set_workspace(ws)
 
+    if args.calib_copy_mb > 0:          # a copy kernel of known size: reads and writes exactly this many bytes
+        src = torch.ones(args.calib_copy_mb << 18, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         g.analyze_batch_dev(t_centers, net.eps)
     torch.cuda.synchronize()
@@ -81,7 +88,7 @@ def main():
     achieved = flop_per_launch / (avg_launch_ms * 1e-3) / 1e12 if avg_launch_ms > 0 else 0.0
     traffic = None
     tfile = os.path.join(ROOT, "profiles", f"cross_kernel_{net.name}_traffic.json")
-    if os.path.exists(tfile):
+    if os.path.exists(tfile) and batch == net.n_inputs:      # counters of a committed rocprofv3 --pmc run of this workload
         traffic = json.load(open(tfile)).get("hbm_bytes_per_launch")
     roofline = dict(bound="mfma", kernel="cross_kernel (float64 MFMA implicit GEMM)", achieved=round(achieved, 3),
                     peak=PEAK_FP64_MFMA_TFLOPS, unit="TFLOP/s", frac=round(achieved / PEAK_FP64_MFMA_TFLOPS, 4),

@@ -98,8 +98,8 @@ __device__ __forceinline__ float relax_factor(double a, float g) {
 //   The MFMA pipe and the vector ALU share the issue port, so everything outside the MFMAs is kept to a
 //   few instructions per K step: 32-bit offsets into per-tile buffer resources, range-checked loads
 //   instead of masks, tap geometry without divisions.
-// Work decomposition: grid.x = tiles of BM rows, grid.y = output pixel of the window, grid.z = tiles of BN
-// input channels.  All rows of a work-group therefore produce the SAME window pixel, so the filter taps
+// Work decomposition: a work-group = (tile of BM rows, output pixel of the window, tile of BN input
+// channels).  All rows of a work-group therefore produce the SAME window pixel, so the filter taps
 // that can reach that pixel from inside the rows' windows are (nearly) the same for all of them: the taps
 // that no row of the tile can use are skipped altogether (Algorithm 1 only visits pairs of a window entry
 // and a tap; a gather over all taps of every output pixel would multiply many structural zeros, most of
@@ -124,10 +124,21 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     const int lk = lane >> 4, lm = lane & 15;
     const int opix = p.owy * p.owx;
-    const int r_tile = blockIdx.x * BM;                       // first row of the tile
-    const int pix = blockIdx.y;                               // window pixel of the tile (uniform)
+    // Work-groups are dealt round-robin to the 8 XCDs, each with its own L2.  The logical tile order is
+    // (row tile, pixel, channel tile) with the channel tile fastest, and XCD x takes the x-th contiguous
+    // eighth of it: the work-groups that re-read the same rows of the block run on the same XCD at about the
+    // same time, so the re-reads hit its L2 instead of HBM.
+    const uint32_t total = (uint32_t)p.ntiles_n * (uint32_t)opix * (uint32_t)p.ntiles_m;
+    const uint32_t per_xcd = (total + 7u) >> 3;
+    const uint32_t logical = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+    if (logical >= total) return;                              // whole work-group leaves before any barrier
+    const uint32_t t2 = fast_div(logical, p.div_ntiles_n);
+    const int nt = (int)(logical - t2 * (uint32_t)p.ntiles_n);
+    const uint32_t rt = fast_div(t2, p.div_opix);
+    const int pix = (int)(t2 - rt * (uint32_t)opix);           // window pixel of the tile (uniform)
+    const int r_tile = (int)rt * BM;                           // first row of the tile
     const int pa = (int)fast_div((uint32_t)pix, p.div_owx), pb = pix - pa * p.owx;
-    const int n0 = blockIdx.z * BN;
+    const int n0 = nt * BN;
     const int Ck = p.in.C, N = p.Co;
     const int taps = p.kh * p.kw;
     const int kchunks = (Ck + BK - 1) / BK;
@@ -367,11 +378,17 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
 }
 
 template <int BM, int BN>
-static void launch_cross_t(const CrossParams& p, hipStream_t s) {
-    dim3 grid((unsigned)((p.nrows + BM - 1) / BM), (unsigned)(p.owy * p.owx), (unsigned)((p.Co + BN - 1) / BN));
+static void launch_cross_t(const CrossParams& p0, hipStream_t s) {
+    CrossParams p = p0;
+    p.ntiles_m = (p.nrows + BM - 1) / BM;
+    p.ntiles_n = (p.Co + BN - 1) / BN;
+    p.div_ntiles_n = make_fastdiv((uint32_t)p.ntiles_n);
+    p.div_opix = make_fastdiv((uint32_t)(p.owy * p.owx));
+    const long long total = (long long)p.ntiles_m * p.ntiles_n * p.owy * p.owx;
+    const unsigned blocks = (unsigned)(((total + 7) / 8) * 8);
     const bool vec = (p.in.C & 3) == 0;
-    if (vec) hipLaunchKernelGGL((cross_kernel<BM, BN, true>), grid, dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((cross_kernel<BM, BN, false>), grid, dim3(256), 0, s, p);
+    if (vec) hipLaunchKernelGGL((cross_kernel<BM, BN, true>), dim3(blocks), dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((cross_kernel<BM, BN, false>), dim3(blocks), dim3(256), 0, s, p);
 }
 
 void launch_cross(const CrossParams& p, hipStream_t s) {

@@ -64,6 +64,8 @@ struct CrossParams {       // one back-substitution step through an affine layer
     int Ho, Wo, Co;        // dims of the input layer
     int owy, owx, oSy, oSx, oPy, oPx;
     FastDiv div_owx, div_sh, div_sw, div_kw;     // owx, sh, sw, kw
+    int ntiles_m, ntiles_n;                      // filled by the launcher: tiles of rows / of input channels
+    FastDiv div_ntiles_n, div_opix;
     BlockDesc add;         // optional block over the same input layer to be summed in (residual join)
     RowMap rm;
     int nrows;
