@@ -50,6 +50,10 @@ def _load():
     L.dp_set_options.argtypes = [P, C.c_int, C.c_int]
     L.dp_request_bounds.argtypes = [P, C.c_int]
     L.dp_set_collapse.argtypes = [P, C.c_int]
+    L.dp_set_early_termination.argtypes = [P, C.c_int]
+    L.dp_set_term_override.argtypes = [P, C.c_int, ip]
+    L.dp_get_term_layer.argtypes = [P, C.c_int, ip]
+    L.dp_get_interval_image.argtypes = [P, C.c_int, dp, dp]
     L.dp_set_lambda_override.argtypes = [P, C.c_int, bp]
     L.dp_set_gamma_override.argtypes = [P, C.c_int, dp]
     L.dp_set_box.argtypes = [P, dp, dp]
@@ -159,6 +163,33 @@ class OracleNet:
     def set_collapse(self, on: bool):
         """False: keep interval coefficients for the whole back-substitution (the literal scheme of Section 4.1)."""
         self._chk(self._L.dp_set_collapse(self._h, 1 if on else 0), "set_collapse")
+
+    def set_early_termination(self, on: bool):
+        """Forward interval pass + termination criterion (Sections 3.2 and 4.2)."""
+        self._chk(self._L.dp_set_early_termination(self._h, 1 if on else 0), "set_early_termination")
+
+    def set_term_override(self, lid, term: Optional[np.ndarray]):
+        """Per neuron of layer lid: where its back-substitution stops (-1: the criterion decides)."""
+        if term is None:
+            self._chk(self._L.dp_set_term_override(self._h, lid, None), "set_term_override")
+            return
+        t = np.ascontiguousarray(term, dtype=np.int32)
+        assert t.size == self.layer_size(lid)
+        self._chk(self._L.dp_set_term_override(self._h, lid, t.ctypes.data_as(C.POINTER(C.c_int))),
+                  "set_term_override")
+
+    def get_term_layer(self, lid) -> np.ndarray:
+        t = np.empty(self.layer_size(lid), np.int32)
+        self._chk(self._L.dp_get_term_layer(self._h, lid, t.ctypes.data_as(C.POINTER(C.c_int))), "get_term_layer")
+        return t
+
+    def get_interval_image(self, lid) -> Tuple[np.ndarray, np.ndarray]:
+        n = self.layer_size(lid)
+        lo = np.empty(n, np.float64)
+        hi = np.empty(n, np.float64)
+        self._chk(self._L.dp_get_interval_image(self._h, lid, lo.ctypes.data_as(C.POINTER(C.c_double)),
+                                                hi.ctypes.data_as(C.POINTER(C.c_double))), "get_interval_image")
+        return lo, hi
 
     def request_bounds(self, lid):
         self._chk(self._L.dp_request_bounds(self._h, lid), "request_bounds")

@@ -15,7 +15,9 @@
  *   - all coefficients are intervals; every operation rounds lower ends towards -inf and upper
  *     ends towards +inf (Section 4.1), in float64.
  *
- * Representation: dense.  No dependence windows, no early termination, no blocking or fusion.
+ * Representation: dense.  No dependence windows, no blocking or fusion.  Early termination
+ * (Section 3.2 "Early termination", Section 4.2 "Implementing early termination") is a separate
+ * mode, off by default; see dp_set_early_termination.
  * A convolution is its defining loop nest with zero padding (the index map of Algorithm 1:
  * output (y,x), tap (f,g) reads input (y*s - p + f, x*s - p + g)).  A residual sum forwards an
  * expression's coefficients to both summands (Section 3.1, "Dependence set and residual
@@ -77,6 +79,13 @@ typedef struct {
     signed char *lam;        /* ReLU: lower line lam*x                             */
     signed char *lam_force;  /* optional per-neuron override: -1 none, 0, 1        */
     double *gam_force;       /* optional per-neuron slope of the upper line (NaN: none) */
+    /* early-termination mode */
+    int feeds_relu, requested;
+    double *ilo, *ihi;       /* interval image of the layer from its predecessors' intervals */
+    int has_ival;
+    int *term;               /* per neuron: layer the expression ranged over when it was dropped; the layer's own
+                                id = never started; 0 = substituted down to the input                 */
+    int *term_force;         /* optional per-neuron override of the decision (-1: none)               */
 } layer_t;
 
 typedef struct {
@@ -85,6 +94,7 @@ typedef struct {
     int lambda_policy;       /* 0: lam=1 iff u>-l   1: always 0   2: always 1      */
     int candidates;          /* 0: every step       1: input layer only            */
     int collapse;            /* 1: re-centre interval coefficients before each substitution (default) */
+    int early_term;          /* 1: forward interval pass + termination criterion (Sections 3.2, 4.2)  */
     int analyzed;
 } dp_net;
 
@@ -127,6 +137,11 @@ static layer_t *new_layer(dp_net *N) {
 static void alloc_bounds(layer_t *l) {
     l->lo = (double *)calloc(l->n, sizeof(double));
     l->hi = (double *)calloc(l->n, sizeof(double));
+    if (l->type != L_RELU) {
+        l->ilo = (double *)calloc(l->n, sizeof(double));
+        l->ihi = (double *)calloc(l->n, sizeof(double));
+        l->term = (int *)calloc(l->n, sizeof(int));
+    }
 }
 
 int dp_add_dense(dp_net *N, int src, int n_out, const float *W, const float *b) {
@@ -167,6 +182,7 @@ int dp_add_relu(dp_net *N, int src) {
     layer_t *p = &N->L[src];
     int C = p->C, H = p->H, W = p->W, n = p->n;
     N->L[src].need_bounds = 1;
+    N->L[src].feeds_relu = 1;
     layer_t *l = new_layer(N);
     l->type = L_RELU; l->a = src; l->C = C; l->H = H; l->W = W; l->n = n;
     alloc_bounds(l);
@@ -193,6 +209,7 @@ void dp_destroy(dp_net *N) {
         layer_t *l = &N->L[i];
         free(l->wt); free(l->bias); free(l->lo); free(l->hi); free(l->gam); free(l->del);
         free(l->lam); free(l->lam_force); free(l->gam_force);
+        free(l->ilo); free(l->ihi); free(l->term); free(l->term_force);
     }
     free(N->L); free(N);
 }
@@ -212,6 +229,41 @@ int dp_set_collapse(dp_net *N, int on) {
 int dp_request_bounds(dp_net *N, int lid) {
     if (!N || lid <= 0 || lid >= N->n_layers) return DP_ERR_ARG;
     N->L[lid].need_bounds = 1;
+    N->L[lid].requested = 1;
+    return DP_OK;
+}
+/* Early termination (Section 3.2: a neuron whose interval does not strictly contain 0 has an exact ReLU
+   relaxation and gains nothing from further back-substitution; Section 4.2: a forward interval pass gives
+   the first intervals, only the other neurons of a ReLU's input layer are back-substituted, and during the
+   back-substitution the criterion is checked again whenever a candidate has been evaluated). */
+int dp_set_early_termination(dp_net *N, int on) {
+    if (!N) return DP_ERR_ARG;
+    N->early_term = on ? 1 : 0;
+    N->analyzed = 0;
+    return DP_OK;
+}
+/* term[i] >= 0 fixes where neuron i of layer lid stops: lid = it is not back-substituted at all, k = right
+   after the candidate over layer k, 0 = at the input; -1 leaves the decision to the criterion.  NULL removes
+   the override.  Only used in early-termination mode. */
+int dp_set_term_override(dp_net *N, int lid, const int *term) {
+    if (!N || lid <= 0 || lid >= N->n_layers || N->L[lid].type == L_RELU) return DP_ERR_ARG;
+    layer_t *l = &N->L[lid];
+    free(l->term_force); l->term_force = NULL;
+    if (term) { l->term_force = (int *)malloc(sizeof(int) * l->n); memcpy(l->term_force, term, sizeof(int) * l->n); }
+    return DP_OK;
+}
+int dp_get_term_layer(const dp_net *N, int lid, int *term) {
+    if (!N || lid <= 0 || lid >= N->n_layers || N->L[lid].type == L_RELU || !term) return DP_ERR_ARG;
+    if (!N->L[lid].has_bounds || !N->early_term) return DP_ERR_STATE;
+    memcpy(term, N->L[lid].term, sizeof(int) * N->L[lid].n);
+    return DP_OK;
+}
+/* the interval image of a layer (early-termination mode; also for layers without back-substituted bounds) */
+int dp_get_interval_image(const dp_net *N, int lid, double *lo, double *hi) {
+    if (!N || lid <= 0 || lid >= N->n_layers || N->L[lid].type == L_RELU) return DP_ERR_ARG;
+    if (!N->L[lid].has_ival) return DP_ERR_STATE;
+    memcpy(lo, N->L[lid].ilo, sizeof(double) * N->L[lid].n);
+    memcpy(hi, N->L[lid].ihi, sizeof(double) * N->L[lid].n);
     return DP_OK;
 }
 /* force[i] in {-1 (no override), 0, 1}; NULL removes the override.  lid is a ReLU layer. */
@@ -243,7 +295,7 @@ int dp_set_box(dp_net *N, const double *lo, const double *hi) {
     memcpy(I->lo, lo, sizeof(double) * I->n);
     memcpy(I->hi, hi, sizeof(double) * I->n);
     I->has_bounds = 1;
-    for (int i = 1; i < N->n_layers; ++i) N->L[i].has_bounds = 0;
+    for (int i = 1; i < N->n_layers; ++i) { N->L[i].has_bounds = 0; N->L[i].has_ival = 0; }
     N->analyzed = 0;
     return DP_OK;
 }
@@ -579,6 +631,133 @@ int dp_bound_rows(dp_net *N, int lid, const int *rows, int n_rows, double *out_l
     return DP_OK;
 }
 
+/* ---- early termination (Sections 3.2 and 4.2) ------------------------------------------------------- */
+/* intervals of layer q as known so far: back-substituted ones if the layer has them, else its interval image */
+static const double *cur_lo(const layer_t *q) { return q->has_bounds ? q->lo : q->ilo; }
+static const double *cur_hi(const layer_t *q) { return q->has_bounds ? q->hi : q->ihi; }
+
+/* forward interval analysis of one layer (Section 4.2, the preliminary / updating step); FE_UPWARD */
+static void interval_image(dp_net *N, int lid) {
+    layer_t *l = &N->L[lid];
+    const layer_t *p = &N->L[l->a];
+    const double *pl = cur_lo(p), *pu = cur_hi(p);
+    if (l->type == L_DENSE) {
+        for (int i = 0; i < l->n; ++i) {
+            const double *w = l->wt + (size_t)i * p->n;
+            double lo = l->bias[i], hi = l->bias[i];
+            for (int j = 0; j < p->n; ++j) {
+                if (w[j] >= 0.0) { lo = add_dn(lo, mul_dn(w[j], pl[j])); hi = add_up(hi, mul_up(w[j], pu[j])); }
+                else             { lo = add_dn(lo, mul_dn(w[j], pu[j])); hi = add_up(hi, mul_up(w[j], pl[j])); }
+            }
+            l->ilo[i] = lo; l->ihi[i] = hi;
+        }
+    } else if (l->type == L_CONV) {
+        for (int d = 0; d < l->C; ++d)
+            for (int y = 0; y < l->H; ++y)
+                for (int x = 0; x < l->W; ++x) {
+                    double lo = l->bias[d], hi = l->bias[d];
+                    for (int ci = 0; ci < p->C; ++ci)
+                        for (int f = 0; f < l->kh; ++f) {
+                            int iy = y * l->sh - l->ph + f;
+                            if (iy < 0 || iy >= p->H) continue;
+                            for (int g = 0; g < l->kw; ++g) {
+                                int ix = x * l->sw - l->pw + g;
+                                if (ix < 0 || ix >= p->W) continue;
+                                double w = l->wt[(((size_t)d * p->C + ci) * l->kh + f) * l->kw + g];
+                                int j = (ci * p->H + iy) * p->W + ix;
+                                if (w >= 0.0) { lo = add_dn(lo, mul_dn(w, pl[j])); hi = add_up(hi, mul_up(w, pu[j])); }
+                                else          { lo = add_dn(lo, mul_dn(w, pu[j])); hi = add_up(hi, mul_up(w, pl[j])); }
+                            }
+                        }
+                    int i = (d * l->H + y) * l->W + x;
+                    l->ilo[i] = lo; l->ihi[i] = hi;
+                }
+    } else if (l->type == L_ADD) {
+        const layer_t *q = &N->L[l->b];
+        const double *ql = cur_lo(q), *qu = cur_hi(q);
+        for (int i = 0; i < l->n; ++i) { l->ilo[i] = add_dn(pl[i], ql[i]); l->ihi[i] = add_up(pu[i], qu[i]); }
+    }
+    l->has_ival = 1;
+}
+
+static void step_any(const dp_net *N, expr_t *e, int k, int sense) {
+    switch (N->L[k].type) {
+        case L_RELU:  step_relu(N, e, k, sense); break;
+        case L_DENSE: step_dense(N, e, k); break;
+        case L_CONV:  step_conv(N, e, k); break;
+        case L_ADD:   step_add(N, e, k); break;
+        default: break;
+    }
+}
+
+/* Upper and lower expression of one neuron substituted in lock step.  *lo,*hi hold the neuron's interval so
+   far and are tightened by every candidate.  After a candidate over a layer k > 0 the termination criterion is
+   checked (may_stop), or the given decision is followed (forced >= 0).  Returns the layer the pair stopped at. */
+static int backsubstitute_pair(const dp_net *N, expr_t *eu, expr_t *el, double *lo, double *hi, int may_stop,
+                               int forced) {
+    for (;;) {
+        int k = -1, count = 0;
+        for (int i = N->n_layers - 1; i >= 0; --i)
+            if (eu->active[i]) { if (k < 0) k = i; ++count; }
+        if (k < 0) {
+            *hi = dmin(*hi, eu->chi); *lo = dmax(*lo, el->clo);
+            return 0;
+        }
+        if (N->collapse && N->L[k].has_bounds) { collapse_width(N, eu, k, +1); collapse_width(N, el, k, -1); }
+        if (count == 1 && N->L[k].has_bounds && (k == 0 || N->candidates == 0)) {
+            *hi = dmin(*hi, concretise(N, eu, k, +1));
+            *lo = dmax(*lo, concretise(N, el, k, -1));
+            if (k > 0) {
+                int stop = (forced >= 0) ? (forced == k) : (may_stop && (*lo >= 0.0 || *hi <= 0.0));
+                if (stop) return k;
+            }
+        }
+        if (k == 0) return 0;
+        step_any(N, eu, k, +1);
+        step_any(N, el, k, -1);
+    }
+}
+
+/* one layer in early-termination mode */
+static int analyze_layer_early(dp_net *N, int lid) {
+    layer_t *l = &N->L[lid];
+    {
+        int old = fegetround();
+        fesetround(FE_UPWARD);
+        interval_image(N, lid);
+        fesetround(old);
+    }
+    const int wants = l->need_bounds || lid == N->n_layers - 1;
+    if (!wants) return DP_OK;
+    /* the criterion speaks about inputs of ReLU layers; rows asked for otherwise are always substituted fully */
+    const int may_stop = l->feeds_relu && !l->requested && lid != N->n_layers - 1;
+    l->has_bounds = 0;
+#pragma omp parallel
+    {
+        int old = fegetround();
+        fesetround(FE_UPWARD);
+        expr_t *eu = expr_new(N), *el = expr_new(N);
+#pragma omp for schedule(dynamic, 1)
+        for (int r = 0; r < l->n; ++r) {
+            double lo = l->ilo[r], hi = l->ihi[r];
+            const int forced = l->term_force ? l->term_force[r] : -1;
+            int skip = (forced >= 0) ? (forced == lid) : (may_stop && !(lo < 0.0 && hi > 0.0));
+            if (skip) { l->lo[r] = lo; l->hi[r] = hi; l->term[r] = lid; continue; }
+            expr_clear(eu, N); expr_clear(el, N);
+            eu->lo[lid][r] = eu->hi[lid][r] = 1.0; eu->active[lid] = 1;
+            el->lo[lid][r] = el->hi[lid][r] = 1.0; el->active[lid] = 1;
+            step_any(N, eu, lid, +1);
+            step_any(N, el, lid, -1);
+            l->term[r] = backsubstitute_pair(N, eu, el, &lo, &hi, may_stop, forced);
+            l->lo[r] = lo; l->hi[r] = hi;
+        }
+        expr_free(eu); expr_free(el);
+        fesetround(old);
+    }
+    l->has_bounds = 1;
+    return DP_OK;
+}
+
 int dp_analyze_layer(dp_net *N, int lid) {
     if (!N || lid <= 0 || lid >= N->n_layers) return DP_ERR_ARG;
     layer_t *l = &N->L[lid];
@@ -590,6 +769,7 @@ int dp_analyze_layer(dp_net *N, int lid) {
         fesetround(old);
         return DP_OK;
     }
+    if (N->early_term) return analyze_layer_early(N, lid);
     int *rows = (int *)malloc(sizeof(int) * l->n);
     for (int i = 0; i < l->n; ++i) rows[i] = i;
     l->has_bounds = 0;
@@ -603,7 +783,7 @@ int dp_analyze(dp_net *N) {
     if (!N || !N->L[0].has_bounds) return DP_ERR_STATE;
     for (int i = 1; i < N->n_layers; ++i) {
         layer_t *l = &N->L[i];
-        if (l->type == L_RELU || l->need_bounds || i == N->n_layers - 1) {
+        if (l->type == L_RELU || l->need_bounds || i == N->n_layers - 1 || N->early_term) {
             int rc = dp_analyze_layer(N, i);
             if (rc != DP_OK) return rc;
         }

@@ -144,3 +144,98 @@ def np_deeppoly(net: wl.Net, lo0, hi0, lambda_policy=0, candidates=0, extra_rows
         s, c0 = first_step(nL, np.asarray(extra_rows, np.float64))
         bounds["extra"] = _np_backsub(net, mats, bounds, relax, s, c0, False, candidates)
     return bounds
+
+
+def np_deeppoly_early(net: wl.Net, lo0, hi0):
+    """The early-termination procedure (Sections 3.2 and 4.2) written a second time, in matrix form with
+    round-to-nearest float64: interval image of every layer first, only the neurons of a ReLU's input layer
+    whose interval strictly contains 0 are back-substituted, upper and lower expression side by side, and a
+    neuron's rows are removed from the matrices as soon as a candidate shows l >= 0 or u <= 0.
+
+    Returns (bounds, term, ival): {layer: (l, u)}, {layer: int array}, {layer: (l, u)}."""
+    nL = len(net.layers)
+    mats = {i: affine_matrix(net, i) for i, L in enumerate(net.layers, start=1) if L["type"] in ("dense", "conv")}
+    feeds_relu = {L["src"] for L in net.layers if L["type"] == "relu"}
+    bounds = {0: (np.asarray(lo0, np.float64), np.asarray(hi0, np.float64))}
+    ival, relax, term = {}, {}, {}
+
+    def known(q):
+        return bounds[q] if q in bounds else ival[q]
+
+    def substitute(expr, c, k, upper):
+        M = expr.pop(k)
+        L = net.layers[k - 1]
+        if L["type"] in ("dense", "conv"):
+            A, b = mats[k]
+            expr[L["src"]] = expr.get(L["src"], 0) + M @ A
+            c = c + M @ b
+        elif L["type"] == "add":
+            expr[L["a"]] = expr.get(L["a"], 0) + M
+            expr[L["b"]] = expr.get(L["b"], 0) + M
+        else:
+            g, d, lam = relax[k]
+            Mp, Mn = np.maximum(M, 0), np.minimum(M, 0)
+            if upper:
+                expr[L["src"]] = expr.get(L["src"], 0) + Mp * g + Mn * lam
+                c = c + Mp @ d
+            else:
+                expr[L["src"]] = expr.get(L["src"], 0) + Mp * lam + Mn * g
+                c = c + Mn @ d
+        return c
+
+    for i, L in enumerate(net.layers, start=1):
+        t = L["type"]
+        if t == "relu":
+            l, u = bounds[L["src"]]
+            uns = (l < 0) & (u > 0)
+            den = np.where(uns, u - l, 1.0)
+            g = np.where(l >= 0, 1.0, np.where(u <= 0, 0.0, u / den))
+            d = np.where(uns, -l * u / den, 0.0)
+            lam = np.where(l >= 0, 1.0, np.where(u <= 0, 0.0, (u > -l).astype(np.float64)))
+            relax[i] = (g, d, lam)
+            bounds[i] = (np.maximum(l, 0), np.maximum(u, 0))
+            continue
+        if t == "add":
+            (la, ua), (lb, ub) = known(L["a"]), known(L["b"])
+            ival[i] = (la + lb, ua + ub)
+        else:
+            A, b = mats[i]
+            pl, pu = known(L["src"])
+            Ap, An = np.maximum(A, 0), np.minimum(A, 0)
+            ival[i] = (Ap @ pl + An @ pu + b, Ap @ pu + An @ pl + b)
+        if not (i in feeds_relu or i == nL):
+            continue
+        may_stop = i in feeds_relu and i != nL
+        lo, hi = ival[i][0].copy(), ival[i][1].copy()
+        n = lo.size
+        tm = np.zeros(n, np.int64)
+        idx = np.arange(n)
+        if may_stop:
+            act = (lo < 0) & (hi > 0)
+            tm[~act] = i
+            idx = idx[act]
+        R = np.eye(n)[idx]
+        eu, el = {i: R.copy()}, {i: R.copy()}
+        cu, cl = np.zeros(idx.size), np.zeros(idx.size)
+        cu = substitute(eu, cu, i, True)
+        cl = substitute(el, cl, i, False)
+        while idx.size:
+            k = max(eu)
+            if len(eu) == 1 and k in bounds:
+                l, u = bounds[k]
+                hi[idx] = np.minimum(hi[idx], np.maximum(eu[k], 0) @ u + np.minimum(eu[k], 0) @ l + cu)
+                lo[idx] = np.maximum(lo[idx], np.maximum(el[k], 0) @ l + np.minimum(el[k], 0) @ u + cl)
+                if k > 0 and may_stop:
+                    done = (lo[idx] >= 0) | (hi[idx] <= 0)
+                    tm[idx[done]] = k
+                    keep = ~done
+                    idx, cu, cl = idx[keep], cu[keep], cl[keep]
+                    eu = {q: M[keep] for q, M in eu.items()}
+                    el = {q: M[keep] for q, M in el.items()}
+            if k == 0:
+                break
+            cu = substitute(eu, cu, k, True)
+            cl = substitute(el, cl, k, False)
+        bounds[i] = (lo, hi)
+        term[i] = tm
+    return bounds, term, ival
