@@ -28,6 +28,8 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="inputs per pass (default: all inputs of the configuration)")
     ap.add_argument("--calib-copy-mb", type=int, default=0, help="run one plain device copy of this many MiB first (scale for HBM counters)")
     ap.add_argument("--dump", default="", help="write one CSV line per profiled kernel launch to this file")
+    ap.add_argument("--early-term", action="store_true",
+                    help="analyse with early termination (forward interval pass, stable neurons are not back-substituted)")
     ap.add_argument("--cpu-sample", type=int, default=-1, help="inputs the oracle is timed on (0: skip)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -45,6 +47,8 @@ def main():
     batch = args.batch or net.n_inputs
     g = Net(*net.input_shape)
     wl.build_into(net, g)
+    if args.early_term:
+        g.set_early_termination(True)
     centers = np.stack([net.center(j % net.n_inputs) for j in range(batch)])
     t_centers = torch.tensor(centers, device="cuda")
     stream = torch.cuda.current_stream()
@@ -79,6 +83,11 @@ def main():
         g.profile_dump(args.dump)
     prof = g.profile_read()
     g.profile_enable(False)
+    early = None
+    if args.early_term:
+        done, full_flop = g.early_termination_stats()
+        early = dict(crossing_flop_done=done, crossing_flop_without_removal=full_flop,
+                     fraction=round(done / full_flop, 4) if full_flop > 0 else None)
     ms_per_step = wall_ms / args.steps
     ms_per_input = ms_per_step / batch
 
@@ -107,6 +116,8 @@ def main():
         wl.build_into(net, o)
         t0 = time.perf_counter()
         for j in range(n_cpu):
+            if args.early_term:
+                o.set_early_termination(True)
             o.analyze(net.center(j), net.eps)
         cpu_ms = (time.perf_counter() - t0) * 1e3 / n_cpu
         cpu = dict(value=round(cpu_ms, 3), unit="ms/input", cores=oracle_threads(), kind="oracle",
@@ -117,8 +128,11 @@ def main():
                gpu_ms_per_step=round(gpu_ms / args.steps, 4),
                higher_is_better=False, scaling="weak", vs_baseline=None, dtype="f64", data="synthetic",
                config=dict(workload=net.name, inputs_per_step=batch, eps=net.eps, neurons=int(sum(net.n_neurons(i) for i in range(1, net.out_layer + 1) if net.layers[i - 1]["type"] != "relu")),
-                           coefficient_storage="f32", accumulate="f64 MFMA", workspace_bytes=ws_bytes),
+                           coefficient_storage="f32", accumulate="f64 MFMA", workspace_bytes=ws_bytes,
+                           early_termination=bool(args.early_term)),
                roofline=roofline, cpu_baseline=cpu)
+    if early is not None:
+        out["early_termination"] = early
     print(json.dumps(out))
 
 

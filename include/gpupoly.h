@@ -66,6 +66,23 @@ gp_status gp_add_residual(gp_net* net, int32_t layer_a, int32_t layer_b, int32_t
 /* Also compute bounds for this (affine or sum) layer although no ReLU reads it. */
 gp_status gp_request_bounds(gp_net* net, int32_t layer_id);
 
+/* Early termination (paper Section 3.2 "Early termination", Section 4.2 "Implementing early termination"); off by
+ * default.  When on, every layer first gets its interval image from its predecessors' intervals (forward interval
+ * analysis); of a layer that feeds a ReLU only the neurons whose interval strictly contains 0 are back-substituted,
+ * and a neuron stops as soon as a candidate shows lower >= 0 or upper <= 0 (checked after every candidate over a
+ * hidden layer); it keeps the bounds it has then.  Rows of stopped neurons are removed from the coefficient blocks.
+ * Reported bounds are the intersection of the interval image and the candidates.  The last layer, layers marked with
+ * gp_request_bounds and certification rows are always substituted down to the input.  Takes effect at the next
+ * analysis; bounds of stopped neurons are sound but in general looser than without early termination. */
+gp_status gp_set_early_termination(gp_net* net, int32_t on);
+/* After an analysis with early termination: for each neuron of a layer that has bounds, the id of the layer its
+ * expression ranged over when it stopped; layer_id itself = never back-substituted, 0 = substituted down to the
+ * input.  term: [n_layer]. */
+gp_status gp_get_term_layer(const gp_net* net, int32_t layer_id, int32_t batch_index, int32_t* term);
+/* Work of the affine crossings in the last analysis with early termination: floating-point operations carried out,
+ * and what the same analysis costs when no row is ever removed. */
+gp_status gp_get_early_termination_stats(const gp_net* net, double* flop_done, double* flop_full);
+
 /* HIP stream (hipStream_t) all work of this net is enqueued on; NULL = the default stream. */
 gp_status gp_set_stream(gp_net* net, void* hip_stream);
 /* Scratch memory for the coefficient blocks of the rows in flight (Section 4.2 "Memory

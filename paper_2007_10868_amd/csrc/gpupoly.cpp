@@ -40,6 +40,7 @@ struct Layer {
     double rowabs = 0.0;           // max_i sum_j |F_ij|
     bool need_bounds = false;      // intervals are computed for this layer (derived from the topology)
     bool req_bounds = false;       // asked for through gp_request_bounds
+    bool feeds_relu = false;       // some ReLU layer reads this layer (the termination criterion applies to it)
     // topology-derived
     std::vector<int> land;         // affine layers a block over this layer is crossed through next
     std::vector<double> beff_host; // [C] summed bias of those layers (float64: the sum of two float32 is kept exact)
@@ -51,6 +52,7 @@ struct Layer {
     double *d_lo = nullptr, *d_hi = nullptr, *d_xmax = nullptr;
     double *d_rho = nullptr, *d_kap = nullptr;   // ReLU layers: candidate and intercept multipliers after substitution
     float* d_grl = nullptr;        // packed ReLU relaxation (see relax_factor in kernels.hip)
+    int* d_term = nullptr;         // early termination: per task the layer at which it met the criterion
 };
 
 struct PlanOp {
@@ -97,6 +99,12 @@ struct gp_net {
     float* d_centers = nullptr;
     long long d_centers_cap = 0;
     int device = -1;
+    // early termination (Sections 3.2, 4.2)
+    bool early = false;
+    int* d_count = nullptr;
+    int* h_count = nullptr;        // pinned: task counts read back while the GPU keeps working
+    hipEvent_t count_ev = nullptr;
+    double early_flop_done = 0.0, early_flop_full = 0.0;   // crossing work carried out / work without any removal
     // optional per-kernel timing (gp_profile_*): index 0 = affine crossing, 1 = row scan
     bool prof_on = false;
     std::vector<hipEvent_t> prof_ev[2];     // start/stop pairs
@@ -192,12 +200,12 @@ void land_of(const gp_net* net, int q, std::vector<int>& out) {   // where a coe
 gp_status prepare_topology(gp_net* net) {
     if (net->topo_ready) return GP_OK;
     int nl = (int)net->L.size();
-    for (int i = 0; i < nl; ++i) net->L[i].need_bounds = net->L[i].req_bounds;
+    for (int i = 0; i < nl; ++i) { net->L[i].need_bounds = net->L[i].req_bounds; net->L[i].feeds_relu = false; }
     for (int i = 1; i < nl; ++i) {
         Layer& l = net->L[i];
         // every crossing must land on a layer with intervals (they bound the rounding slack)
         if (is_affine(l)) net->L[l.a].need_bounds = true;
-        if (l.type == T_RELU) net->L[l.a].need_bounds = true;
+        if (l.type == T_RELU) { net->L[l.a].need_bounds = true; net->L[l.a].feeds_relu = true; }
     }
     net->L[nl - 1].need_bounds = true;
     for (int i = 0; i < nl; ++i) {
@@ -387,9 +395,10 @@ gp_status get_plan(gp_net* net, int lid, Plan** out) {
 
 // ---- device state ------------------------------------------------------------------------------
 void free_layer_bounds(Layer& l) {
-    dfree(l.d_lo); dfree(l.d_hi); dfree(l.d_rho); dfree(l.d_kap); dfree(l.d_xmax); dfree(l.d_grl);
+    dfree(l.d_lo); dfree(l.d_hi); dfree(l.d_rho); dfree(l.d_kap); dfree(l.d_xmax); dfree(l.d_grl); dfree(l.d_term);
     l.d_lo = l.d_hi = l.d_rho = l.d_kap = l.d_xmax = nullptr;
     l.d_grl = nullptr;
+    l.d_term = nullptr;
 }
 
 bool has_bounds(const gp_net* net, int lid) {
@@ -402,6 +411,9 @@ gp_status ensure_device(gp_net* net, int batch) {
     if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) return fail(net, GP_ERR_DEVICE, "no HIP device");
     if (net->device < 0) HIP_TRY(net, hipGetDevice(&net->device));
     if (!net->d_flag) HIP_TRY(net, hipMalloc((void**)&net->d_flag, sizeof(int)));
+    if (!net->d_count) HIP_TRY(net, hipMalloc((void**)&net->d_count, sizeof(int)));
+    if (!net->h_count) HIP_TRY(net, hipHostMalloc((void**)&net->h_count, 2 * sizeof(int), hipHostMallocDefault));
+    if (!net->count_ev) HIP_TRY(net, hipEventCreateWithFlags(&net->count_ev, hipEventDisableTiming));
     if (!net->weights_uploaded) {
         for (auto& l : net->L) {
             if (!l.wt_host.empty() && !l.d_wt) {
@@ -428,11 +440,14 @@ gp_status ensure_device(gp_net* net, int batch) {
         for (size_t i = 0; i < net->L.size(); ++i) {
             Layer& l = net->L[i];
             size_t cnt = (size_t)l.n * batch;
-            if (has_bounds(net, (int)i)) {
+            // with early termination every layer carries intervals (its interval image at least)
+            if (has_bounds(net, (int)i) || net->early) {
                 HIP_TRY(net, hipMalloc((void**)&l.d_lo, cnt * sizeof(double)));
                 HIP_TRY(net, hipMalloc((void**)&l.d_hi, cnt * sizeof(double)));
                 HIP_TRY(net, hipMalloc((void**)&l.d_xmax, sizeof(double) * batch));
             }
+            if (net->early && l.need_bounds && l.type != T_RELU && i > 0)
+                HIP_TRY(net, hipMalloc((void**)&l.d_term, cnt * sizeof(int)));
             if (l.type == T_RELU) {
                 HIP_TRY(net, hipMalloc((void**)&l.d_grl, cnt * sizeof(float)));
                 HIP_TRY(net, hipMalloc((void**)&l.d_rho, cnt * sizeof(double)));
@@ -451,7 +466,8 @@ long long align_up(long long v, long long a) { return (v + a - 1) / a * a; }
 
 // bytes one task (both signs) needs for this plan
 long long task_bytes(const Plan& pl, int nsign) {
-    return (long long)nsign * (pl.n_slots * align_up(pl.slot_elems * 4, 16) + 3 * 8);
+    // blocks; constant, slack (twice: rows are moved when tasks are removed), best; row lists and flags
+    return (long long)nsign * (pl.n_slots * align_up(pl.slot_elems * 4, 16) + 5 * 8) + 16;
 }
 
 gp_status get_workspace(gp_net* net, long long want, char** ws, long long* bytes) {
@@ -492,18 +508,24 @@ void prof_mark(gp_net* net, int kind, bool stop) {
     (void)hipEventRecord(ev[used++], net->stream);
 }
 
-// run one plan over all its tasks, chunk by chunk (Section 4.2 "Memory management")
+// run one plan over all its tasks, chunk by chunk (Section 4.2 "Memory management").
+// With early termination (Sections 3.2, 4.2) the rows' best bounds start from the layer's interval image, tasks
+// whose interval does not strictly contain 0 never start, and after every candidate the tasks that have come to
+// meet the criterion are flagged; flagged tasks keep their bounds, and once enough of them have gathered their
+// rows are removed from the block (prefix sum over the flags, rows copied to a free block).
 gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int batch) {
     const Layer& ls = net->L[start];
     const int nsign = certify ? 1 : 2;
     const long long n_start = certify ? (ls.n - 1) : ls.n;
     const long long total = n_start * batch;
     if (total <= 0) return GP_OK;
+    const bool early = net->early && !certify;
+    const bool may_stop = early && ls.feeds_relu && !ls.req_bounds && start != (int)net->L.size() - 1;
     const long long tb = task_bytes(pl, nsign);
     char* ws; long long ws_bytes;
-    gp_status st = get_workspace(net, tb * total + 4096, &ws, &ws_bytes);
+    gp_status st = get_workspace(net, tb * total + 8192, &ws, &ws_bytes);
     if (st != GP_OK) return st;
-    long long Rc_max = (ws_bytes - 4096) / tb;
+    long long Rc_max = (ws_bytes - 8192) / tb;
     if (total >= (1LL << 31)) return fail(net, GP_ERR_SHAPE, "batch * layer size must stay below 2^31");
     // rows * window pixels of any step must stay below 2^31 (32-bit indexing in the kernels)
     long long max_pix = 1;
@@ -513,20 +535,35 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
             max_pix = std::max(max_pix, (long long)std::min(op.g_out.Wy, pp.H) * std::min(op.g_out.Wx, pp.W));
         }
     Rc_max = std::min(Rc_max, ((1LL << 31) - 256) / (nsign * max_pix));
-    // keep M = rows * window pixels below 2^31 work-groups' worth and int-safe
     if (Rc_max <= 0) return fail(net, GP_ERR_WORKSPACE, "workspace of %lld bytes cannot hold one row (%lld bytes)", ws_bytes, tb);
     Rc_max = std::min(Rc_max, total);
     const long long nrows_max = Rc_max * nsign;
-    double* d_c = (double*)ws;
-    double* d_err = d_c + nrows_max;
-    double* d_best = d_err + nrows_max;
-    char* slots0 = ws + align_up(3 * nrows_max * 8, 256);
+    // header: per-row scalars (two copies of constant and slack), then the task lists of early termination
+    double* d_cbuf[2] = {(double*)ws, (double*)ws + nrows_max};
+    double* d_ebuf[2] = {(double*)ws + 2 * nrows_max, (double*)ws + 3 * nrows_max};
+    double* d_best = (double*)ws + 4 * nrows_max;
+    int* d_rowid[2] = {(int*)(d_best + nrows_max), (int*)(d_best + nrows_max) + Rc_max};
+    int* d_sel = d_rowid[1] + Rc_max;
+    int* d_wg = d_sel + Rc_max;
+    const long long nwg_max = (Rc_max + 255) / 256 + 1;
+    unsigned char* d_done[2] = {(unsigned char*)(d_wg + nwg_max), (unsigned char*)(d_wg + nwg_max) + Rc_max};
+    char* slots0 = ws + align_up((d_done[1] + Rc_max) - (unsigned char*)ws, 256);
     const long long slot_bytes = align_up(nrows_max * pl.slot_elems * 4, 256);
-    if (slots0 + slot_bytes * pl.n_slots > ws + ws_bytes) {   // alignment slack: shrink
-        Rc_max = std::max<long long>(1, Rc_max - 64);
-        return fail(net, GP_ERR_WORKSPACE, "workspace layout overflow");
+    if (slots0 + slot_bytes * pl.n_slots > ws + ws_bytes) return fail(net, GP_ERR_WORKSPACE, "workspace layout overflow");
+
+    // per row: arithmetic of the crossings that follow each op of the plan
+    std::vector<double> rem_flop(pl.ops.size() + 1, 0.0);
+    for (size_t i = pl.ops.size(); i-- > 0;) {
+        rem_flop[i] = rem_flop[i + 1];
+        const PlanOp& op = pl.ops[i];
+        if (op.kind == PlanOp::CROSS) {
+            const Layer& a = net->L[op.layer_in];
+            const Layer& p = net->L[op.layer_out];
+            const double taps = (a.type == T_DENSE) ? 1.0 : (double)a.kh * a.kw;
+            const double cin = (a.type == T_DENSE) ? (double)p.n : (double)p.C;
+            rem_flop[i] += 2.0 * (double)block_elems(op.g_in, a) * taps * cin;
+        }
     }
-    auto slot_ptr = [&](int s) { return (float*)(slots0 + slot_bytes * s); };
 
     for (long long row0 = 0; row0 < total; row0 += Rc_max) {
         gp::RowMap rm;
@@ -539,8 +576,92 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
         rm.div_n = gp::make_fastdiv((uint32_t)rm.n_start);
         rm.div_c = gp::make_fastdiv((uint32_t)rm.Cs);
         rm.div_w = gp::make_fastdiv((uint32_t)rm.Ws);
-        const int nrows = rm.Rc * nsign;
-        for (const PlanOp& op : pl.ops) {
+        rm.rowid = nullptr;
+        rm.Rc0 = rm.Rc;
+        const gp::RowMap rm0 = rm;            // the chunk before any removal (layout of `best`)
+        int phys[kMaxSlots];
+        for (int i = 0; i < kMaxSlots; ++i) phys[i] = i;
+        auto slot_ptr = [&](int s) { return (float*)(slots0 + slot_bytes * phys[s]); };
+        int cur = 0;                          // which copy of constant / slack / task list / flags is current
+        double *d_c = d_cbuf[0], *d_err = d_ebuf[0];
+        bool have_rows = false;               // constants and slack exist (an INIT has run)
+        bool stop_all = false;                // every task met the criterion: skip to FINALIZE
+
+        // Flag the tasks that meet the criterion and count the ones kept.  The count of one check is read at the
+        // next one (the GPU works on the step in between, so the host does not make it wait); only when that
+        // count says that removing rows pays is the stream drained for the exact count, and the rows removed.
+        bool pending = false;
+        auto check_termination = [&](int key, bool first, int slot, long long nelem, double rem_flop) -> gp_status {
+            gp::TermParams tp;
+            tp.best = d_best; tp.Rc0 = rm.Rc0; tp.rowid = rm.rowid; tp.Ra = rm.Rc;
+            tp.done = d_done[cur]; tp.term_layer = ls.d_term;
+            tp.row0 = rm.row0; tp.key = key; tp.first = first ? 1 : 0; tp.may_stop = may_stop ? 1 : 0;
+            tp.wgcount = d_wg;
+            gp::launch_term(tp, net->d_count, net->stream);
+            // removing rows costs a copy of the rows kept (and an idle moment of the GPU); the rows removed would
+            // have cost their share of the crossings still to come
+            auto pays = [&](int kept) {
+                if (first) return kept < rm.Rc;                  // nothing to copy yet
+                const double gone = (double)(rm.Rc - kept) * nsign, stay = (double)kept * nsign;
+                return gone * rem_flop / 30e12 > 1.5 * (stay * (double)nelem * 8.0 / 2.5e12 + 30e-6);
+            };
+            bool exact = first;
+            if (!first && pending) {
+                HIP_TRY(net, hipEventSynchronize(net->count_ev));
+                pending = false;
+                const int before = net->h_count[0];
+                if (before == 0) { stop_all = true; return GP_OK; }   // flags only ever grow
+                exact = before > 0 && before <= rm.Rc && pays(before);
+            }
+            if (!exact) {
+                HIP_TRY(net, hipMemcpyAsync(net->h_count, net->d_count, sizeof(int), hipMemcpyDeviceToHost, net->stream));
+                HIP_TRY(net, hipEventRecord(net->count_ev, net->stream));
+                pending = true;
+                return GP_OK;
+            }
+            HIP_TRY(net, hipMemcpyAsync(net->h_count + 1, net->d_count, sizeof(int), hipMemcpyDeviceToHost, net->stream));
+            HIP_TRY(net, hipStreamSynchronize(net->stream));
+            const int kept = net->h_count[1];
+            if (kept < 0 || kept > rm.Rc) return fail(net, GP_ERR_DEVICE, "task count out of range");
+            if (kept == 0) { stop_all = true; return GP_OK; }
+            if (!pays(kept)) return GP_OK;
+            gp::CompactParams cp;
+            cp.done = d_done[cur]; cp.wgoffset = d_wg; cp.Ra = rm.Rc;
+            cp.rowid_old = rm.rowid; cp.rowid_new = d_rowid[cur ^ 1]; cp.sel = d_sel;
+            cp.c_old = have_rows ? d_c : nullptr; cp.err_old = have_rows ? d_err : nullptr;
+            cp.c_new = d_cbuf[cur ^ 1]; cp.err_new = d_ebuf[cur ^ 1];
+            cp.count = net->d_count; cp.nsign = nsign; cp.done_new = d_done[cur ^ 1];
+            gp::launch_compact(cp, net->stream);
+            if (slot >= 0) {
+                const int other = (slot + 1) % pl.n_slots;      // every other block is dead at a candidate
+                gp::CopyRowsParams cr;
+                cr.src = slot_ptr(slot); cr.dst = slot_ptr(other); cr.sel = d_sel;
+                cr.Ra_old = rm.Rc; cr.Ra_new = kept; cr.nsign = nsign; cr.nelem = (int)nelem;
+                gp::launch_copy_rows(cr, net->stream);
+                std::swap(phys[slot], phys[other]);
+            }
+            cur ^= 1;
+            d_c = d_cbuf[cur]; d_err = d_ebuf[cur];
+            rm.rowid = d_rowid[cur];
+            rm.Rc = kept;
+            return GP_OK;
+        };
+
+        if (early) {
+            gp::SeedParams sd;
+            sd.lo = ls.d_lo; sd.hi = ls.d_hi; sd.best = d_best; sd.row0 = rm.row0; sd.Rc0 = rm.Rc0;
+            gp::launch_seed(sd, net->stream);
+            if (may_stop) {
+                st = check_termination(start, true, -1, 0, 0.0);
+                if (st != GP_OK) return st;
+            } else if (ls.d_term) {
+                gp::launch_fill_i32(ls.d_term + row0, 0, rm.Rc, net->stream);
+            }
+        }
+        for (size_t oi = 0; oi < pl.ops.size(); ++oi) {
+            const PlanOp& op = pl.ops[oi];
+            const int nrows = rm.Rc * nsign;
+            if (stop_all && op.kind != PlanOp::FINALIZE) continue;
             if (op.kind == PlanOp::INIT) {
                 const Layer& lo = net->L[op.layer_out];
                 gp::InitParams ip;
@@ -561,7 +682,9 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                     ip.out_grl = op.relaxed ? lo.d_grl : nullptr;
                 }
                 ip.c = d_c; ip.err = d_err; ip.best = d_best;
+                ip.seeded = early ? 1 : 0;
                 gp::launch_init(ip, net->stream);
+                have_rows = true;
             } else if (op.kind == PlanOp::SCAN) {
                 const Layer& l = net->L[op.layer_in];
                 gp::ScanParams sp;
@@ -593,14 +716,19 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                 sp.round_coef = op.rounded ? kRoundCoef : 0.0;
                 sp.do_consts = op.do_consts ? 1 : 0;
                 sp.update_best = op.update_best ? 1 : 0;
-                { static const char* dbg = getenv("GP_DEBUG_INPUT_ONLY"); if (dbg && op.layer_in != 0) sp.update_best = 0; }
                 sp.c = d_c; sp.err = d_err; sp.best = d_best;
+                sp.done = may_stop ? d_done[cur] : nullptr;
                 prof_mark(net, 1, false);
                 gp::launch_scan(sp, net->stream);
                 prof_mark(net, 1, true);
                 if (net->prof_on) {
                     net->prof_bytes[1] += 4.0 * nrows * (double)block_elems(op.g_in, l);
                     net->prof_recs[1].push_back({1, start, op.layer_in, nrows, (int)block_elems(op.g_in, l), 0, l.C, 0, 0.0});
+                }
+                // a candidate over a hidden layer has just been folded into best: re-evaluate the criterion
+                if (may_stop && op.update_best && interval_terms && op.layer_in != 0) {
+                    st = check_termination(op.layer_in, false, op.slot_in, block_elems(op.g_in, l), rem_flop[oi]);
+                    if (st != GP_OK) return st;
                 }
             } else if (op.kind == PlanOp::CROSS) {
                 const Layer& a = net->L[op.layer_in];
@@ -636,25 +764,30 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                 prof_mark(net, 0, false);
                 gp::launch_cross(cp, net->stream);
                 prof_mark(net, 0, true);
+                // algorithmic work of the step (Section 2: one product M^k * F^k): every coefficient of the
+                // row's block meets every filter tap and every input channel once; the one-hot start block
+                // of a row is bookkeeping, not part of the method, and counts as zero
+                const double in_el = (double)block_elems(op.g_in, a), out_el = (double)block_elems(op.g_out, p);
+                const double taps = (a.type == T_DENSE) ? 1.0 : (double)a.kh * a.kw;
+                const double cin = (a.type == T_DENSE) ? (double)p.n : (double)p.C;
+                const bool first = (op.layer_in == start);
+                const double per_row = first ? 0.0 : 2.0 * in_el * taps * cin;
+                if (early) {
+                    net->early_flop_done += per_row * nrows;
+                    net->early_flop_full += per_row * rm0.Rc * nsign;
+                }
                 if (net->prof_on) {
-                    // algorithmic work of the step (Section 2: one product M^k * F^k): every coefficient of the
-                    // row's block meets every filter tap and every input channel once; the one-hot start block
-                    // of a row is bookkeeping, not part of the method, and counts as zero
-                    const double in_el = (double)block_elems(op.g_in, a), out_el = (double)block_elems(op.g_out, p);
-                    const double taps = (a.type == T_DENSE) ? 1.0 : (double)a.kh * a.kw;
-                    const double cin = (a.type == T_DENSE) ? (double)p.n : (double)p.C;
-                    const bool first = (op.layer_in == start);
-                    if (!first) net->prof_flop[0] += 2.0 * nrows * in_el * taps * cin;
+                    net->prof_flop[0] += per_row * nrows;
                     net->prof_recs[0].push_back({0, start, op.layer_in, nrows, (int)in_el, (int)out_el, (int)cin, (int)(taps * a.C),
-                                                 first ? 0.0 : 2.0 * nrows * in_el * taps * cin});
+                                                 per_row * nrows});
                     net->prof_bytes[0] += 4.0 * nrows * (in_el + out_el) + 4.0 * (double)a.wt_host.size();
                 }
             } else if (op.kind == PlanOp::FINALIZE) {
                 if (certify) {
-                    gp::launch_margins(d_best, net->d_margins + row0, rm.Rc, net->d_flag, net->stream);
+                    gp::launch_margins(d_best, net->d_margins + row0, rm0.Rc, net->d_flag, net->stream);
                 } else {
                     gp::FinalizeParams fp;
-                    fp.rm = rm; fp.best = d_best;
+                    fp.rm = rm0; fp.best = d_best;
                     fp.lo = net->L[start].d_lo; fp.hi = net->L[start].d_hi;
                     fp.xmax = net->L[start].d_xmax; fp.flag = net->d_flag;
                     gp::launch_finalize(fp, net->stream);
@@ -689,12 +822,35 @@ gp_status analyze_layers(gp_net* net, int batch) {
             rp.total = l.n * batch;
             rp.n = l.n;
             gp::launch_relu(rp, net->stream);
-        } else if (l.need_bounds) {
-            Plan* pl;
-            gp_status st = get_plan(net, i, &pl);
-            if (st != GP_OK) return st;
-            st = run_plan(net, *pl, i, false, batch);
-            if (st != GP_OK) return st;
+        } else {
+            if (net->early) {
+                // forward interval analysis of this layer from what is known of its predecessors (Section 4.2)
+                if (l.type == T_ADD) {
+                    gp::AddIvalParams ap;
+                    ap.alo = net->L[l.a].d_lo; ap.ahi = net->L[l.a].d_hi;
+                    ap.blo = net->L[l.b].d_lo; ap.bhi = net->L[l.b].d_hi;
+                    ap.lo = l.d_lo; ap.hi = l.d_hi; ap.total = l.n * batch; ap.flag = net->d_flag;
+                    gp::launch_add_ival(ap, net->stream);
+                } else {
+                    const Layer& p = net->L[l.a];
+                    gp::IvalParams ip;
+                    ip.plo = p.d_lo; ip.phi = p.d_hi; ip.wt = l.d_wti; ip.bias = l.d_bias;
+                    ip.lo = l.d_lo; ip.hi = l.d_hi; ip.flag = net->d_flag;
+                    if (l.type == T_DENSE) { ip.Hi = ip.Wi = 1; ip.Ci = (int)p.n; }
+                    else { ip.Hi = p.H; ip.Wi = p.W; ip.Ci = p.C; }
+                    ip.H = l.H; ip.W = l.W; ip.C = l.C;
+                    ip.kh = l.kh; ip.kw = l.kw; ip.sh = l.sh; ip.sw = l.sw; ip.ph = l.ph; ip.pw = l.pw;
+                    ip.batch = batch;
+                    gp::launch_ival(ip, net->stream);
+                }
+            }
+            if (l.need_bounds) {
+                Plan* pl;
+                gp_status st = get_plan(net, i, &pl);
+                if (st != GP_OK) return st;
+                st = run_plan(net, *pl, i, false, batch);
+                if (st != GP_OK) return st;
+            }
         }
     }
     gp_status st = check_flag(net);
@@ -721,6 +877,7 @@ gp_status begin_analysis(gp_net* net, int batch) {
     if (st != GP_OK) return st;
     gp::launch_fill_i32(net->d_flag, 0, 1, net->stream);
     gp::launch_fill_f64(net->L[0].d_xmax, 0.0, batch, net->stream);
+    net->early_flop_done = net->early_flop_full = 0.0;
     return GP_OK;
 }
 
@@ -757,6 +914,9 @@ void gp_net_destroy(gp_net* net) {
         free_layer_bounds(l);
         dfree(l.d_wt); dfree(l.d_wti); dfree(l.d_bias); dfree(l.d_beff);
     }
+    dfree(net->d_count);
+    if (net->h_count) (void)hipHostFree(net->h_count);
+    if (net->count_ev) (void)hipEventDestroy(net->count_ev);
     dfree(net->d_flag); dfree(net->d_labels); dfree(net->d_margins); dfree(net->d_centers);
     dfree(net->ws_own);
     for (int k = 0; k < 2; ++k)
@@ -892,6 +1052,45 @@ gp_status gp_request_bounds(gp_net* net, int32_t layer_id) {
     if (net->L[layer_id].type == T_RELU) return GP_OK;
     net->L[layer_id].req_bounds = true;
     topology_changed(net);
+    return GP_OK;
+}
+
+gp_status gp_set_early_termination(gp_net* net, int32_t on) {
+    if (!net) return GP_ERR_ARG;
+    const bool want = on != 0;
+    if (want != net->early) {
+        net->early = want;
+        net->analyzed = false;
+        if (net->batch) {           // the set of layers that carry intervals changes
+            for (auto& l : net->L) free_layer_bounds(l);
+            net->batch = 0;
+        }
+    }
+    return GP_OK;
+}
+
+gp_status gp_get_term_layer(const gp_net* net, int32_t layer_id, int32_t batch_index, int32_t* term) {
+    if (!net) return GP_ERR_ARG;
+    if (!term) return fail(net, GP_ERR_ARG, "output pointer is null");
+    if (layer_id <= 0 || layer_id >= (int)net->L.size() || net->L[layer_id].type == T_RELU)
+        return fail(net, GP_ERR_ARG, "layer %d starts no back-substitution", layer_id);
+    if (!net->analyzed || !net->early) return fail(net, GP_ERR_STATE, "no successful analysis with early termination yet");
+    if (batch_index < 0 || batch_index >= net->batch) return fail(net, GP_ERR_ARG, "batch index out of range");
+    const Layer& l = net->L[layer_id];
+    if (!l.d_term) return fail(net, GP_ERR_STATE, "layer %d has no bounds (see gp_request_bounds)", layer_id);
+    std::vector<int> t(l.n);
+    HIP_TRY(net, hipMemcpy(t.data(), l.d_term + (size_t)batch_index * l.n, l.n * sizeof(int), hipMemcpyDeviceToHost));
+    const long long hw = (long long)l.H * l.W;
+    for (long long pix = 0; pix < hw; ++pix)
+        for (int c = 0; c < l.C; ++c) term[c * hw + pix] = t[pix * l.C + c];
+    return GP_OK;
+}
+
+gp_status gp_get_early_termination_stats(const gp_net* net, double* flop_done, double* flop_full) {
+    if (!net || !flop_done || !flop_full) return GP_ERR_ARG;
+    if (!net->analyzed || !net->early) return fail(net, GP_ERR_STATE, "no successful analysis with early termination yet");
+    *flop_done = net->early_flop_done;
+    *flop_full = net->early_flop_full;
     return GP_OK;
 }
 

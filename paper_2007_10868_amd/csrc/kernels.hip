@@ -31,6 +31,7 @@ __device__ __forceinline__ RowInfo row_info(const RowMap& rm, int r) {
         rr = r - rm.Rc;
         ri.sign = -1.f;
     }
+    if (rm.rowid) rr = rm.rowid[rr];
     const uint32_t g = (uint32_t)(rm.row0 + rr);
     const uint32_t b = fast_div(g, rm.div_n);
     const uint32_t i = g - b * (uint32_t)rm.n_start;
@@ -41,6 +42,14 @@ __device__ __forceinline__ RowInfo row_info(const RowMap& rm, int r) {
     ri.ys = (int)ys;
     ri.xs = (int)(pos - ys * (uint32_t)rm.Ws);
     return ri;
+}
+
+// where row r keeps its best candidate: the layout of the chunk before any row was removed
+__device__ __forceinline__ int best_index(const RowMap& rm, int r) {
+    const int half = r >= rm.Rc ? 1 : 0;
+    int rr = r - half * rm.Rc;
+    if (rm.rowid) rr = rm.rowid[rr];
+    return half * rm.Rc0 + rr;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -466,15 +475,14 @@ __global__ __launch_bounds__(256) void scan_kernel(const ScanParams p) {
     const int nelem = B.wy * B.wx * B.C;
     const bool full_row = (B.wx == B.W);                   // window rows are contiguous in the layer
 
-    // do all rows share box and window origin?
-    RowInfo ri0 = row_info(p.rm, r0);
-    const int oy0 = clampi(B.Sy * ri0.ys - B.Py, 0, B.H - B.wy);
-    const int ox0 = clampi(B.Sx * ri0.xs - B.Px, 0, B.W - B.wx);
-    bool same = true;
-    for (int k = 1; k < nvalid; ++k) {
-        RowInfo rk = row_info(p.rm, r0 + k);
-        int oy = clampi(B.Sy * rk.ys - B.Py, 0, B.H - B.wy), ox = clampi(B.Sx * rk.xs - B.Px, 0, B.W - B.wx);
-        same = same && rk.b == ri0.b && oy == oy0 && ox == ox0;
+    // box and window origin of every row of the group; consecutive rows that agree in all three form a run
+    int rb[SCAN_G], roy[SCAN_G], rox[SCAN_G];
+#pragma unroll
+    for (int k = 0; k < SCAN_G; ++k) {
+        const RowInfo rk = row_info(p.rm, r0 + (k < nvalid ? k : 0));
+        rb[k] = rk.b;
+        roy[k] = clampi(B.Sy * rk.ys - B.Py, 0, B.H - B.wy);
+        rox[k] = clampi(B.Sx * rk.xs - B.Px, 0, B.W - B.wx);
     }
 
     double cand[SCAN_G], absx[SCAN_G], cst[SCAN_G], cstabs[SCAN_G], s1[SCAN_G];
@@ -537,38 +545,33 @@ __global__ __launch_bounds__(256) void scan_kernel(const ScanParams p) {
     };
 
     const float* src0 = B.data + (size_t)r0 * nelem;
-    if (same) {
-        const long long bbase = (long long)ri0.b * p.batch_stride;
+    // one pass over the block per run: the constants are fetched once per element and serve all rows of the run
+    // (normally the whole group is one run; after rows have been removed a group can straddle positions)
+    int k0 = 0;
+    while (k0 < nvalid) {
+        int k1 = k0 + 1;
+#pragma unroll
+        for (int k = 1; k < SCAN_G; ++k)
+            if (k == k1 && k < nvalid && rb[k] == rb[k - 1] && roy[k] == roy[k - 1] && rox[k] == rox[k - 1]) ++k1;
+        int b0 = 0, oy0 = 0, ox0 = 0;
+#pragma unroll
+        for (int k = 0; k < SCAN_G; ++k)
+            if (k == k0) { b0 = rb[k]; oy0 = roy[k]; ox0 = rox[k]; }
+        const long long bbase = (long long)b0 * p.batch_stride;
         for (int e = lane * V; e < nelem; e += 64 * V) {
             float mf[SCAN_G][V];
 #pragma unroll
             for (int k = 0; k < SCAN_G; ++k)
-                if (k < nvalid) load_m(src0 + (size_t)k * nelem + e, mf[k]);
+                if (k >= k0 && k < k1) load_m(src0 + (size_t)k * nelem + e, mf[k]);
             int c;
             const long long j = neuron(e, oy0, ox0, bbase, c);
             Consts q;
             constants(j, c, q);
 #pragma unroll
             for (int k = 0; k < SCAN_G; ++k)
-                if (k < nvalid) accumulate(k, mf[k], q);
+                if (k >= k0 && k < k1) accumulate(k, mf[k], q);
         }
-    } else {
-#pragma unroll
-        for (int k = 0; k < SCAN_G; ++k) {
-            if (k >= nvalid) continue;
-            RowInfo rk = row_info(p.rm, r0 + k);
-            const int oy = clampi(B.Sy * rk.ys - B.Py, 0, B.H - B.wy), ox = clampi(B.Sx * rk.xs - B.Px, 0, B.W - B.wx);
-            const long long bbase = (long long)rk.b * p.batch_stride;
-            for (int e = lane * V; e < nelem; e += 64 * V) {
-                float mf[V];
-                load_m(src0 + (size_t)k * nelem + e, mf);
-                int c;
-                const long long j = neuron(e, oy, ox, bbase, c);
-                Consts q;
-                constants(j, c, q);
-                accumulate(k, mf, q);
-            }
-        }
+        k0 = k1;
     }
     const double t_cand = wave_sum8(cand, lane), t_absx = wave_sum8(absx, lane), t_cst = wave_sum8(cst, lane),
                  t_cstabs = wave_sum8(cstabs, lane), t_s1 = wave_sum8(s1, lane);
@@ -588,7 +591,12 @@ __global__ __launch_bounds__(256) void scan_kernel(const ScanParams p) {
         if (p.update_best && p.cpos) {
             double v = c + t_cand + err;
             v += (fabs(c) + fabs(t_cand) + err) * 0x1p-50 + t_absx * esum;
-            p.best[r] = fmin(p.best[r], v);
+            // a task that met the termination criterion keeps the bounds it had at that moment
+            const bool frozen = p.done && p.done[r >= p.rm.Rc ? r - p.rm.Rc : r];
+            if (!frozen) {
+                const int bi = best_index(p.rm, r);
+                p.best[bi] = fmin(p.best[bi], v);
+            }
         }
         if (p.do_consts) {
             double cn = c + t_cst;
@@ -659,7 +667,7 @@ __global__ __launch_bounds__(256) void init_kernel(const InitParams p) {
     if (blockIdx.y == 0 && (threadIdx.x & 63) == 0) {
         p.c[r] = (p.mode == 2) ? (double)(ri.sign * p.bias[ri.cs]) : 0.0;
         p.err[r] = 0.0;
-        p.best[r] = INFINITY;
+        if (!p.seeded) p.best[r] = INFINITY;
     }
 }
 
@@ -813,6 +821,201 @@ __global__ void margins_kernel(const double* best, float* margins, long long n, 
 }
 void launch_margins(const double* best, float* margins, long long n, int* flag, hipStream_t s) {
     if (n > 0) hipLaunchKernelGGL(margins_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, best, margins, n, flag);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Early termination (Section 3.2: a ReLU input whose interval does not contain 0 strictly gains nothing from
+// back-substitution; Section 4.2: forward interval analysis first, only the other rows are back-substituted,
+// rows that come to meet the criterion are removed with a prefix sum over the row flags).
+// ------------------------------------------------------------------------------------------------
+// Interval image of an affine layer: one wave per neuron, float64.  The float32 weight times a float64 bound is
+// rounded once (fused multiply-add); a sum of n such terms in any order is off by less than
+// (n + 16) * 2^-52 * sum|terms|, which is added outward.
+__global__ __launch_bounds__(256) void ival_kernel(const IvalParams p) {
+    const int lane = threadIdx.x & 63;
+    const long long n = (long long)p.H * p.W * p.C;
+    const long long idx = blockIdx.x * 4LL + (threadIdx.x >> 6);
+    if (idx >= n * p.batch) return;                         // whole wave leaves
+    const int b = (int)(idx / n);
+    const int j = (int)(idx - (long long)b * n);
+    const int pix = j / p.C, c = j - pix * p.C;
+    const int y = pix / p.W, x = pix - y * p.W;
+    const long long n_in = (long long)p.Hi * p.Wi * p.Ci;
+    const double* plo = p.plo + (long long)b * n_in;
+    const double* phi = p.phi + (long long)b * n_in;
+    const int taps = p.kh * p.kw;
+    double lo = 0.0, hi = 0.0, mag = 0.0;
+    for (int t = 0; t < taps; ++t) {
+        const int f = t / p.kw, g = t - f * p.kw;
+        const int iy = y * p.sh - p.ph + f, ix = x * p.sw - p.pw + g;
+        if (iy < 0 || iy >= p.Hi || ix < 0 || ix >= p.Wi) continue;          // uniform per wave
+        const float* w = p.wt + ((size_t)t * p.C + c) * p.Ci;
+        const double* l = plo + (size_t)(iy * p.Wi + ix) * p.Ci;
+        const double* u = phi + (size_t)(iy * p.Wi + ix) * p.Ci;
+        for (int ci = lane; ci < p.Ci; ci += 64) {
+            const double wv = (double)w[ci], L = l[ci], U = u[ci];
+            lo = fma(wv, wv >= 0.0 ? L : U, lo);
+            hi = fma(wv, wv >= 0.0 ? U : L, hi);
+            mag = fma(fabs(wv), fmax(fabs(L), fabs(U)), mag);
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        lo += __shfl_xor(lo, off, 64);
+        hi += __shfl_xor(hi, off, 64);
+        mag += __shfl_xor(mag, off, 64);
+    }
+    if (lane == 0) {
+        const double bias = (double)p.bias[c];
+        const double terms = (double)taps * p.Ci + 1.0;
+        const double slack = (terms + 16.0) * 0x1p-52 * (mag + fabs(bias)) * (1.0 + 0x1p-30);
+        double l2 = lo + bias - slack, u2 = hi + bias + slack;
+        l2 -= fabs(l2) * 0x1p-51 + 0x1p-1000;
+        u2 += fabs(u2) * 0x1p-51 + 0x1p-1000;
+        if (!isfinite(l2) || !isfinite(u2)) *p.flag = 1;
+        p.lo[idx] = l2;
+        p.hi[idx] = u2;
+    }
+}
+void launch_ival(const IvalParams& p, hipStream_t s) {
+    const long long total = (long long)p.H * p.W * p.C * p.batch;
+    if (total <= 0) return;
+    hipLaunchKernelGGL(ival_kernel, dim3((unsigned)((total + 3) / 4)), dim3(256), 0, s, p);
+}
+
+__global__ void add_ival_kernel(const AddIvalParams p) {
+    const long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x;
+    if (i >= p.total) return;
+    double l = p.alo[i] + p.blo[i], u = p.ahi[i] + p.bhi[i];
+    l -= fabs(l) * 0x1p-52 + 0x1p-1000;
+    u += fabs(u) * 0x1p-52 + 0x1p-1000;
+    if (!isfinite(l) || !isfinite(u)) *p.flag = 1;
+    p.lo[i] = l;
+    p.hi[i] = u;
+}
+void launch_add_ival(const AddIvalParams& p, hipStream_t s) {
+    if (p.total <= 0) return;
+    hipLaunchKernelGGL(add_ival_kernel, dim3((unsigned)((p.total + 255) / 256)), dim3(256), 0, s, p);
+}
+
+__global__ void seed_kernel(const SeedParams p) {
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= p.Rc0) return;
+    p.best[r] = p.hi[(long long)p.row0 + r];
+    p.best[p.Rc0 + r] = -p.lo[(long long)p.row0 + r];
+}
+void launch_seed(const SeedParams& p, hipStream_t s) {
+    if (p.Rc0 <= 0) return;
+    hipLaunchKernelGGL(seed_kernel, dim3((p.Rc0 + 255) / 256), dim3(256), 0, s, p);
+}
+
+// criterion per task: upper bound <= 0 or lower bound >= 0 (best[Rc0 + .] holds minus the lower bound)
+__global__ __launch_bounds__(256) void term_flag_kernel(const TermParams p) {
+    __shared__ int s_cnt[4];
+    const int rr = blockIdx.x * 256 + threadIdx.x;
+    int keep = 0;
+    if (rr < p.Ra) {
+        const int orig = p.rowid ? p.rowid[rr] : rr;
+        const bool was = !p.first && p.done[rr];
+        const bool crit = p.may_stop && (p.best[orig] <= 0.0 || p.best[p.Rc0 + orig] <= 0.0);
+        const bool now = was || crit;
+        p.done[rr] = now ? 1 : 0;
+        if (p.term_layer) {
+            if (p.first) p.term_layer[(long long)p.row0 + orig] = now ? p.key : 0;
+            else if (now && !was) p.term_layer[(long long)p.row0 + orig] = p.key;
+        }
+        keep = now ? 0 : 1;
+    }
+    const unsigned long long m = __ballot(keep);
+    if ((threadIdx.x & 63) == 0) s_cnt[threadIdx.x >> 6] = __popcll(m);
+    __syncthreads();
+    if (threadIdx.x == 0) p.wgcount[blockIdx.x] = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+}
+// exclusive prefix sum of the per-work-group counts in place (one work-group walks the array), total to *count
+__global__ __launch_bounds__(1024) void term_scan_kernel(int* wgcount, int nwg, int* count) {
+    __shared__ int s_wave[16];
+    __shared__ int s_carry;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) s_carry = 0;
+    __syncthreads();
+    for (int base = 0; base < nwg; base += 1024) {
+        const int i = base + tid;
+        const int v = i < nwg ? wgcount[i] : 0;
+        int incl = v;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int t = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += t;
+        }
+        if (lane == 63) s_wave[wave] = incl;
+        __syncthreads();
+        int wave_off = 0;
+        for (int w = 0; w < wave; ++w) wave_off += s_wave[w];
+        const int carry = s_carry;
+        if (i < nwg) wgcount[i] = carry + wave_off + incl - v;
+        __syncthreads();
+        if (tid == 1023) s_carry = carry + wave_off + incl;
+        __syncthreads();
+    }
+    if (tid == 0) *count = s_carry;
+}
+void launch_term(const TermParams& p, int* count, hipStream_t s) {
+    if (p.Ra <= 0) return;
+    const int nwg = (p.Ra + 255) / 256;
+    hipLaunchKernelGGL(term_flag_kernel, dim3(nwg), dim3(256), 0, s, p);
+    hipLaunchKernelGGL(term_scan_kernel, dim3(1), dim3(1024), 0, s, p.wgcount, nwg, count);
+}
+
+__global__ __launch_bounds__(256) void compact_kernel(const CompactParams p) {
+    __shared__ int s_cnt[4];
+    const int rr = blockIdx.x * 256 + threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int keep = (rr < p.Ra && !p.done[rr]) ? 1 : 0;
+    const unsigned long long m = __ballot(keep);
+    if (lane == 0) s_cnt[wave] = __popcll(m);
+    __syncthreads();
+    if (!keep) return;
+    int pos = p.wgoffset[blockIdx.x] + __popcll(m & ((1ull << lane) - 1ull));
+    for (int w = 0; w < wave; ++w) pos += s_cnt[w];
+    const int Ra_new = *p.count;
+    p.sel[pos] = rr;
+    p.rowid_new[pos] = p.rowid_old ? p.rowid_old[rr] : rr;
+    p.done_new[pos] = 0;
+    if (p.c_old) {
+        for (int h = 0; h < p.nsign; ++h) {
+            p.c_new[h * Ra_new + pos] = p.c_old[h * p.Ra + rr];
+            p.err_new[h * Ra_new + pos] = p.err_old[h * p.Ra + rr];
+        }
+    }
+}
+void launch_compact(const CompactParams& p, hipStream_t s) {
+    if (p.Ra <= 0) return;
+    hipLaunchKernelGGL(compact_kernel, dim3((p.Ra + 255) / 256), dim3(256), 0, s, p);
+}
+
+// block rows of the tasks kept, moved to their new places in another buffer (4 rows per work-group)
+__global__ __launch_bounds__(256) void copy_rows_kernel(const CopyRowsParams p) {
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= p.Ra_new * p.nsign) return;
+    const int half = r >= p.Ra_new ? 1 : 0;
+    const int i = r - half * p.Ra_new;
+    const float* src = p.src + ((size_t)half * p.Ra_old + p.sel[i]) * p.nelem;
+    float* dst = p.dst + (size_t)r * p.nelem;
+    const int lane = threadIdx.x & 63;
+    if ((p.nelem & 3) == 0) {
+        const int n4 = p.nelem >> 2;
+        for (int e = blockIdx.y * 64 + lane; e < n4; e += gridDim.y * 64)
+            reinterpret_cast<float4*>(dst)[e] = reinterpret_cast<const float4*>(src)[e];
+    } else {
+        for (int e = blockIdx.y * 64 + lane; e < p.nelem; e += gridDim.y * 64) dst[e] = src[e];
+    }
+}
+void launch_copy_rows(const CopyRowsParams& p, hipStream_t s) {
+    const long long rows = (long long)p.Ra_new * p.nsign;
+    if (rows <= 0 || p.nelem <= 0) return;
+    const int per = (p.nelem & 3) == 0 ? p.nelem / 4 : p.nelem;
+    const int ychunks = (int)fmin((double)((per + 63) / 64), 32.0);
+    hipLaunchKernelGGL(copy_rows_kernel, dim3((unsigned)((rows + 3) / 4), ychunks), dim3(256), 0, s, p);
 }
 
 __global__ void mfma_check_kernel(const double* A, const double* B, double* D, int K) {

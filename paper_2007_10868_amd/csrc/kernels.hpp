@@ -44,6 +44,10 @@ struct RowMap {
     int n_start;     // tasks per box of the batch
     int Hs, Ws, Cs;  // start layer dims; task i sits at position ((i/Cs)/Ws, (i/Cs)%Ws), channel i%Cs
     FastDiv div_n, div_c, div_w;   // n_start, Cs, Ws
+    // early termination (Section 4.2): after rows have been removed, row rr of a half stands for task
+    // row0 + rowid[rr] (null: rr itself); Rc0 = tasks of the chunk before any removal (`best` keeps that layout)
+    const int* rowid;
+    int Rc0;
 };
 
 struct BlockDesc {
@@ -91,7 +95,8 @@ struct ScanParams {        // per-row reductions over a block
     int update_best;       // the expression ranges over this layer only: fold the candidate into best
     double* c;             // per-row constant
     double* err;           // per-row accumulated slack (>= 0)
-    double* best;          // per-row best candidate so far
+    double* best;          // per-row best candidate so far (indexed by the row's place before any removal)
+    const unsigned char* done;   // per task of the chunk (compact): 1 = termination criterion met, best is final; null: none
 };
 
 struct InitParams {
@@ -110,6 +115,7 @@ struct InitParams {
     const float* wt;       // [tap][Cs][C] (predecessor channels innermost); dense: [Cs][nelem]
     const float* bias;     // [Cs]
     double* c; double* err; double* best;
+    int seeded;            // best already holds the rows' interval image: leave it
 };
 
 struct FinalizeParams {
@@ -138,6 +144,47 @@ struct BoxParams {
     int C, H, W, batch;
 };
 
+// ---- early termination (Sections 3.2 and 4.2) ---------------------------------------------------------
+struct IvalParams {          // forward interval analysis of an affine layer
+    const double* plo; const double* phi;   // predecessor intervals [batch][Hi*Wi*Ci], H,W,C order
+    const float* wt;         // [tap][C][Ci] (dense: [C][n_in], seen as one tap over a 1x1 layer with n_in channels)
+    const float* bias;       // [C]
+    double* lo; double* hi;  // [batch][H*W*C]
+    int* flag;
+    int Hi, Wi, Ci, H, W, C, kh, kw, sh, sw, ph, pw, batch;
+};
+struct AddIvalParams {       // sum layer: interval sum, rounded outward
+    const double *alo, *ahi, *blo, *bhi;
+    double *lo, *hi;
+    long long total;
+    int* flag;
+};
+struct SeedParams {          // best[r] = upper end, best[Rc0 + r] = -(lower end) of task row0 + r
+    const double* lo; const double* hi;
+    double* best;
+    int row0, Rc0;
+};
+struct TermParams {          // termination criterion per task of the chunk, and the number of tasks kept per 256
+    const double* best; int Rc0;
+    const int* rowid; int Ra;            // current compact list (null: identity) and its length
+    unsigned char* done;                 // [Ra] in/out
+    int* term_layer;                     // [batch * n_start]: layer at which a task met the criterion
+    int row0, key, first, may_stop;      // first: before any step (done has no previous value; tasks kept get 0)
+    int* wgcount;                        // [ceil(Ra/256)] tasks kept per work-group
+};
+struct CompactParams {       // order-preserving removal of the tasks that are done
+    const unsigned char* done; const int* wgoffset; int Ra;
+    const int* rowid_old; int* rowid_new; int* sel;      // sel[new] = old compact position
+    const double *c_old, *err_old; double *c_new, *err_new;   // both halves ([2*Ra] -> [2*Ra_new]); null before the first step
+    const int* count;        // device: Ra_new
+    int nsign;
+    unsigned char* done_new; // [Ra_new] cleared
+};
+struct CopyRowsParams {      // dst row (h*Ra_new + i) = src row (h*Ra_old + sel[i])
+    const float* src; float* dst; const int* sel;
+    int Ra_old, Ra_new, nsign, nelem;
+};
+
 void launch_cross(const CrossParams& p, hipStream_t s);
 void launch_scan(const ScanParams& p, hipStream_t s);
 void launch_init(const InitParams& p, hipStream_t s);
@@ -146,6 +193,12 @@ void launch_relu(const ReluParams& p, hipStream_t s);
 void launch_box(const BoxParams& p, hipStream_t s);
 void launch_fill_f64(double* p, double v, long long n, hipStream_t s);
 void launch_fill_i32(int* p, int v, long long n, hipStream_t s);
+void launch_ival(const IvalParams& p, hipStream_t s);
+void launch_add_ival(const AddIvalParams& p, hipStream_t s);
+void launch_seed(const SeedParams& p, hipStream_t s);
+void launch_term(const TermParams& p, int* count, hipStream_t s);      // flags, counts, scan; *count (device) = tasks kept
+void launch_compact(const CompactParams& p, hipStream_t s);
+void launch_copy_rows(const CopyRowsParams& p, hipStream_t s);
 void launch_margins(const double* best, float* margins, long long n, int* flag, hipStream_t s);
 // float64 MFMA self-check: D[16][16] = A[16][K] * B[K][16], same instruction and layout as the crossing kernel
 void launch_mfma_check(const double* A, const double* B, double* D, int K, hipStream_t s);

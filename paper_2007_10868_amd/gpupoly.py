@@ -17,7 +17,8 @@ STATUS = {0: "GP_OK", 1: "GP_ERR_ARG", 2: "GP_ERR_SHAPE", 3: "GP_ERR_STATE", 4: 
 
 # every symbol include/gpupoly.h declares
 EXPORTS = ["gp_net_create", "gp_net_destroy", "gp_add_dense", "gp_add_conv2d", "gp_add_relu", "gp_add_residual",
-           "gp_request_bounds", "gp_set_stream", "gp_workspace_size", "gp_set_workspace", "gp_analyze",
+           "gp_request_bounds", "gp_set_early_termination", "gp_get_term_layer", "gp_get_early_termination_stats",
+           "gp_set_stream", "gp_workspace_size", "gp_set_workspace", "gp_analyze",
            "gp_analyze_box", "gp_analyze_batch", "gp_analyze_batch_dev", "gp_get_bounds", "gp_get_bounds_batch",
            "gp_get_bounds_f64", "gp_get_relu_lambda", "gp_get_relu_slopes", "gp_certify", "gp_certify_batch", "gp_debug_plan",
            "gp_profile_enable", "gp_profile_read", "gp_profile_dump", "gp_debug_mfma_f64", "gp_num_layers", "gp_layer_size", "gp_last_error", "gp_version"]
@@ -52,6 +53,9 @@ def load_library():
     L.gp_add_residual.argtypes = [P, i32, i32, ip]
     L.gp_request_bounds.argtypes = [P, i32]
     L.gp_set_stream.argtypes = [P, P]
+    L.gp_set_early_termination.argtypes = [P, i32]
+    L.gp_get_term_layer.argtypes = [P, i32, i32, ip]
+    L.gp_get_early_termination_stats.argtypes = [P, dp, dp]
     L.gp_workspace_size.argtypes = [P, i32, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
     L.gp_set_workspace.argtypes = [P, P, C.c_int64]
     L.gp_analyze.argtypes = [P, fp, f32, f32, f32]
@@ -147,6 +151,20 @@ class Net:
         return self._L.gp_layer_size(self._h, lid)
 
     # ---- device plumbing (torch is used for memory and streams only)
+    def set_early_termination(self, on=True):
+        self._chk(self._L.gp_set_early_termination(self._h, 1 if on else 0))
+
+    def get_term_layer(self, lid, batch_index=0):
+        t = np.empty(self.layer_size(lid), np.int32)
+        self._chk(self._L.gp_get_term_layer(self._h, lid, batch_index, t.ctypes.data_as(C.POINTER(C.c_int32))))
+        return t
+
+    def early_termination_stats(self):
+        """(flop carried out by the crossings, flop of the same analysis with no row removed)"""
+        a, b = C.c_double(0), C.c_double(0)
+        self._chk(self._L.gp_get_early_termination_stats(self._h, C.byref(a), C.byref(b)))
+        return a.value, b.value
+
     def set_stream(self, stream=None):
         """stream: a torch.cuda.Stream (or None for the default stream)."""
         self._chk(self._L.gp_set_stream(self._h, C.c_void_p(stream.cuda_stream if stream is not None else 0)))

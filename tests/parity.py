@@ -116,3 +116,34 @@ def check_samples_inside(net, g, lo0, hi0, n, rng, batch_index=0, what=""):
         v = vals[lid]
         assert np.all(v.min(0) >= glo.astype(np.float64)), f"{what} layer {lid}: sampled output below the lower bound"
         assert np.all(v.max(0) <= ghi.astype(np.float64)), f"{what} layer {lid}: sampled output above the upper bound"
+
+
+def bounded_affine_layers(net: wl.Net):
+    """Layers that start back-substitutions (they have bounds and are no ReLU layers)."""
+    return [i for i in analysed_layers(net) if net.layers[i - 1]["type"] != "relu"]
+
+
+def oracle_early_with_gpu_decisions(net: wl.Net, o: OracleNet, g, center, eps, batch_index=0, clip=(0.0, 1.0),
+                                    tie=1e-4):
+    """Oracle in early-termination mode, layer by layer, stopping every neuron where the GPU stopped it (a
+    neuron whose candidate is within rounding of 0 can be stopped by one side and not by the other, and what it
+    keeps then differs by more than rounding), and taking the GPU's lower-line choice at near-ties as in
+    oracle_with_gpu_ties.  Returns the number of forced lower-line choices."""
+    o.set_early_termination(True)
+    o.set_ball(center, eps, clip[0], clip[1])
+    for lid in bounded_affine_layers(net):
+        o.set_term_override(lid, g.get_term_layer(lid, batch_index))
+    forced = 0
+    for lid in range(1, o.num_layers):
+        L = net.layers[lid - 1]
+        if L["type"] == "relu":
+            lo, hi = o.get_bounds(L["src"])
+            near = (lo < 0) & (hi > 0) & (np.abs(hi + lo) <= tie * (hi - lo))
+            if near.any():
+                lam = g.get_relu_lambda(lid, batch_index)
+                o.set_lambda_override(lid, np.where(near, lam, -1).astype(np.int8))
+                forced += int(near.sum())
+            else:
+                o.set_lambda_override(lid, None)
+        o.analyze_layer(lid)        # in this mode every layer is visited (interval image at least)
+    return forced
