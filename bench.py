@@ -30,6 +30,7 @@ def main():
     ap.add_argument("--dump", default="", help="write one CSV line per profiled kernel launch to this file")
     ap.add_argument("--early-term", action="store_true",
                     help="analyse with early termination (forward interval pass, stable neurons are not back-substituted)")
+    ap.add_argument("--eps", type=float, default=0.0, help="override the configuration's perturbation radius")
     ap.add_argument("--cpu-sample", type=int, default=-1, help="inputs the oracle is timed on (0: skip)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -44,6 +45,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     net = wl.config(args.config)
+    if args.eps > 0:
+        net.eps = args.eps
     batch = args.batch or net.n_inputs
     g = Net(*net.input_shape)
     wl.build_into(net, g)
