@@ -403,13 +403,8 @@ static void launch_cross_t(const CrossParams& p0, hipStream_t s) {
 void launch_cross(const CrossParams& p, hipStream_t s) {
     if (p.nrows <= 0 || p.Co <= 0) return;
     const int N = p.Co;
-    static const char* tile_env = getenv("GP_TILE");
-    if (tile_env && N > 32) {
-        if (!strcmp(tile_env, "128x128")) { launch_cross_t<128, 128>(p, s); return; }
-        if (!strcmp(tile_env, "128x64")) { launch_cross_t<128, 64>(p, s); return; }
-        if (!strcmp(tile_env, "64x128")) { launch_cross_t<64, 128>(p, s); return; }
-        if (!strcmp(tile_env, "64x64")) { launch_cross_t<64, 64>(p, s); return; }
-    }
+    // tile shapes measured on MI355X: 64x64 beats the larger tiles (their lower occupancy costs more than their
+    // higher arithmetic intensity gains); narrow layers take a tall tile so that fewer MFMA columns are padding
     if (N <= 16) { launch_cross_t<128, 16>(p, s); return; }
     if (N <= 32) { launch_cross_t<128, 32>(p, s); return; }
     launch_cross_t<64, 64>(p, s);
@@ -452,6 +447,43 @@ __device__ __forceinline__ double wave_sum8(double (&v)[8], int lane) {
     y += __shfl_xor(y, 2, 64);
     y += __shfl_xor(y, 1, 64);
     return y;
+}
+
+// Per-row bookkeeping after the reductions: rounding slack of the stored coefficients, candidate folded into best,
+// constants of the next step added to c, slack of the next accumulation.
+__device__ __forceinline__ void scan_finish(const ScanParams& p, int r, int nelem, double t_cand, double t_absx, double t_cst,
+                                            double t_cstabs, double t_s1) {
+    const RowInfo ri = row_info(p.rm, r);
+    // a sum of n float64 terms in any order is off by at most (n-1)*2^-53*sum|terms|*(1+tiny)
+    const double esum = (double)(nelem + 16) * 0x1p-52;
+    double c = p.c[r];
+    double err = p.err[r];
+    // slack of the stored coefficients: |true - stored| <= round_coef*|stored| (+ subnormal floor)
+    err += t_absx * p.round_coef * (1.0 + esum);
+    // values below the float32 subnormal step vanish; with a substituted ReLU the lost coefficient is
+    // up to 2^20 times larger (slopes are kept >= 2^-20)
+    if (p.round_coef > 0.0 && p.xmax_self) err += 0x1p-128 * (double)nelem * p.xmax_self[ri.b];
+    if (p.update_best && p.cpos) {
+        double v = c + t_cand + err;
+        v += (fabs(c) + fabs(t_cand) + err) * 0x1p-50 + t_absx * esum;
+        // a task that met the termination criterion keeps the bounds it had at that moment
+        const bool frozen = p.done && p.done[r >= p.rm.Rc ? r - p.rm.Rc : r];
+        if (!frozen) {
+            const int bi = best_index(p.rm, r);
+            p.best[bi] = fmin(p.best[bi], v);
+        }
+    }
+    if (p.do_consts) {
+        double cn = c + t_cst;
+        double e1 = 0.0;
+        if (p.xmax_a) e1 += p.e1_a * p.xmax_a[ri.b];
+        if (p.xmax_b) e1 += p.e1_b * p.xmax_b[ri.b];
+        err += t_cstabs * esum + (fabs(c) + fabs(t_cst)) * 0x1p-51 + t_s1 * e1 * (1.0 + esum);
+        c = cn;
+    }
+    err *= (1.0 + 0x1p-48);   // the few float64 operations above
+    p.c[r] = c;
+    p.err[r] = err;
 }
 
 constexpr int SCAN_G = 8;     // rows per wave
@@ -578,46 +610,96 @@ __global__ __launch_bounds__(256) void scan_kernel(const ScanParams p) {
     const int k = lane >> 3;
     if ((lane & 7) == 0 && k < nvalid) {
         const int r = r0 + k;
-        const RowInfo ri = row_info(p.rm, r);
-        // a sum of n float64 terms in any order is off by at most (n-1)*2^-53*sum|terms|*(1+tiny)
-        const double esum = (double)(nelem + 16) * 0x1p-52;
-        double c = p.c[r];
-        double err = p.err[r];
-        // slack of the stored coefficients: |true - stored| <= round_coef*|stored| (+ subnormal floor)
-        err += t_absx * p.round_coef * (1.0 + esum);
-        // values below the float32 subnormal step vanish; with a substituted ReLU the lost coefficient is
-        // up to 2^20 times larger (slopes are kept >= 2^-20)
-        if (p.round_coef > 0.0 && p.xmax_self) err += 0x1p-128 * (double)nelem * p.xmax_self[ri.b];
-        if (p.update_best && p.cpos) {
-            double v = c + t_cand + err;
-            v += (fabs(c) + fabs(t_cand) + err) * 0x1p-50 + t_absx * esum;
-            // a task that met the termination criterion keeps the bounds it had at that moment
-            const bool frozen = p.done && p.done[r >= p.rm.Rc ? r - p.rm.Rc : r];
-            if (!frozen) {
-                const int bi = best_index(p.rm, r);
-                p.best[bi] = fmin(p.best[bi], v);
+        scan_finish(p, r, nelem, t_cand, t_absx, t_cst, t_cstabs, t_s1);
+    }
+}
+
+// Short rows: the same reductions with 8 lanes per row and 8 rows per wave.  Every lane accumulates for its own row
+// (no per-row register arrays, so many more waves are resident), and fetches the constants of its own elements;
+// lanes of different rows that meet the same neuron read the same addresses.
+template <int V>
+__global__ __launch_bounds__(256) void scan_tall_kernel(const ScanParams p) {
+    const int tid = threadIdx.x, lane = tid & 63;
+    const BlockDesc& B = p.blk;
+    const int groups_per_half = (p.rm.Rc + SCAN_G - 1) / SCAN_G;
+    const int gidx = blockIdx.x * 4 + (tid >> 6);
+    const int nhalves = p.nrows / p.rm.Rc;
+    if (gidx >= groups_per_half * nhalves) return;          // whole wave leaves
+    const int half = gidx / groups_per_half;
+    const int rr0 = (gidx - half * groups_per_half) * SCAN_G;
+    const int nvalid = min(SCAN_G, p.rm.Rc - rr0);
+    const int k = lane >> 3, sub = lane & 7;
+    const bool valid = k < nvalid;
+    const int r = half * p.rm.Rc + rr0 + (valid ? k : 0);
+    const int nelem = B.wy * B.wx * B.C;
+    const bool full_row = (B.wx == B.W);
+    const RowInfo ri = row_info(p.rm, r);
+    const int oy = clampi(B.Sy * ri.ys - B.Py, 0, B.H - B.wy), ox = clampi(B.Sx * ri.xs - B.Px, 0, B.W - B.wx);
+    const long long bbase = (long long)ri.b * p.batch_stride;
+    const float* src = B.data + (size_t)r * nelem;
+    double cand = 0.0, absx = 0.0, cst = 0.0, cstabs = 0.0, s1 = 0.0;
+    if (valid) {
+        for (int e = sub * V; e < nelem; e += 8 * V) {
+            float mf[V];
+            if (V == 4) {
+                const float4 t = *reinterpret_cast<const float4*>(src + e);
+                mf[0] = t.x; mf[1 % V] = t.y; mf[2 % V] = t.z; mf[3 % V] = t.w;
+            } else {
+                mf[0] = src[e];
+            }
+            int c;
+            long long j;
+            if (full_row) {
+                c = e % B.C;
+                j = bbase + (long long)oy * B.W * B.C + e;
+            } else {
+                const int pix = e / B.C;
+                c = e - pix * B.C;
+                const int a = pix / B.wx, bb = pix - a * B.wx;
+                j = bbase + ((long long)((oy + a) * B.W + (ox + bb)) * B.C + c);
+            }
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                const double m = (double)mf[v];
+                if (p.cpos) {
+                    cand += (mf[v] >= 0.f) ? m * p.cpos[j + v] : m * p.cneg[j + v];
+                    absx += fabs(m) * fmax(fabs(p.xlo[j + v]), fabs(p.xhi[j + v]));
+                }
+                if (p.do_consts) {
+                    const double tp = p.kap ? fmax(m, 0.0) * p.kap[j + v] : 0.0;
+                    const double tb = p.beff ? m * p.beff[c + v] : 0.0;
+                    cst += tp + tb;
+                    cstabs += tp + fabs(tb);
+                    s1 += fabs(m);
+                }
             }
         }
-        if (p.do_consts) {
-            double cn = c + t_cst;
-            double e1 = 0.0;
-            if (p.xmax_a) e1 += p.e1_a * p.xmax_a[ri.b];
-            if (p.xmax_b) e1 += p.e1_b * p.xmax_b[ri.b];
-            err += t_cstabs * esum + (fabs(c) + fabs(t_cst)) * 0x1p-51 + t_s1 * e1 * (1.0 + esum);
-            c = cn;
-        }
-        err *= (1.0 + 0x1p-48);   // the few float64 operations above
-        p.c[r] = c;
-        p.err[r] = err;
     }
+#pragma unroll
+    for (int off = 4; off > 0; off >>= 1) {
+        cand += __shfl_xor(cand, off, 64);
+        absx += __shfl_xor(absx, off, 64);
+        cst += __shfl_xor(cst, off, 64);
+        cstabs += __shfl_xor(cstabs, off, 64);
+        s1 += __shfl_xor(s1, off, 64);
+    }
+    if (valid && sub == 0) scan_finish(p, r, nelem, cand, absx, cst, cstabs, s1);
 }
 
 void launch_scan(const ScanParams& p, hipStream_t s) {
     if (p.nrows <= 0) return;
     const int nhalves = p.nrows / p.rm.Rc;
     const int groups = ((p.rm.Rc + SCAN_G - 1) / SCAN_G) * nhalves;
-    if ((p.blk.C & 3) == 0) hipLaunchKernelGGL((scan_kernel<4>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((scan_kernel<1>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
+    const int nelem = p.blk.wy * p.blk.wx * p.blk.C;
+    const bool vec = (p.blk.C & 3) == 0;
+    if (nelem <= 256) {      // measured cross-over of the two layouts on MI355X
+        if (vec) hipLaunchKernelGGL((scan_tall_kernel<4>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((scan_tall_kernel<1>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
+    } else if (vec) {
+        hipLaunchKernelGGL((scan_kernel<4>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
+    } else {
+        hipLaunchKernelGGL((scan_kernel<1>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
