@@ -151,6 +151,9 @@ gp_status gp_profile_dump(gp_net* net, const char* path);
  * in float64 MFMA (K a multiple of 4; A, B, D row-major in device memory), enqueued on hip_stream.
  * The rounding slack of a crossing assumes |D - exact| <= (K+8) * 2^-50 * sum|terms|; tests check it. */
 gp_status gp_debug_mfma_f64(const double* A_dev, const double* B_dev, double* D_dev, int32_t K, void* hip_stream);
+/* The same check for the 4-column instruction that crosses layers with at most 4 input channels (the image):
+ * D[16][4] = A[16][K] * B[K][4]. */
+gp_status gp_debug_mfma_f64_4col(const double* A_dev, const double* B_dev, double* D_dev, int32_t K, void* hip_stream);
 
 int32_t gp_num_layers(const gp_net* net);
 int32_t gp_layer_size(const gp_net* net, int32_t layer_id);

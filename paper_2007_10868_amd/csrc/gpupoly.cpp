@@ -1383,4 +1383,11 @@ gp_status gp_debug_mfma_f64(const double* A_dev, const double* B_dev, double* D_
     return hipGetLastError() == hipSuccess ? GP_OK : GP_ERR_DEVICE;
 }
 
+// test hook: D[16][4] = A[16][K] * B[K][4] with the 4-column float64 MFMA instruction (device pointers)
+gp_status gp_debug_mfma_f64_4col(const double* A_dev, const double* B_dev, double* D_dev, int32_t K, void* hip_stream) {
+    if (!A_dev || !B_dev || !D_dev || K <= 0 || (K & 3)) return GP_ERR_ARG;
+    gp::launch_mfma4_check(A_dev, B_dev, D_dev, K, (hipStream_t)hip_stream);
+    return hipGetLastError() == hipSuccess ? GP_OK : GP_ERR_DEVICE;
+}
+
 }  // extern "C"

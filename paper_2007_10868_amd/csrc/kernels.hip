@@ -120,7 +120,12 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
     constexpr int WAVES_N = (BN >= 64) ? 2 : 1;
     constexpr int WAVES_M = 4 / WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
-    constexpr int TM = WTM / 16, TN = WTN / 16;
+    // BN == 4: layers with at most 4 input channels (the image).  A 16-column MFMA tile would be 13/16 padding
+    // there; the 4x4x4 instruction (4 independent 4x4 blocks) keeps 16 rows per instruction with 4 columns.  Its
+    // operand layout: lane l holds A[row l%16][k l/16] (as for 16x16x4), B[k l/16][column l%4] (the same B for
+    // every block), and receives D[row 4*((l%16)/4) + l/16][column l%4].
+    constexpr bool SMALLN = (BN == 4);
+    constexpr int TM = WTM / 16, TN = SMALLN ? 1 : WTN / 16;
     constexpr int APT = (BM + 63) / 64;             // A rows per thread
     constexpr int BPT = (BN + 63) / 64;             // B columns per thread
     static_assert(TM >= 1 && TN >= 1, "tile");
@@ -279,7 +284,7 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
     double* const a_st = &As[0][ld_row][q4];
     double* const b_st = &Bs[0][ld_row][q4];
     const double* const a_ld = &As[0][wm * WTM + lm][4 * lk];
-    const double* const b_ld = &Bs[0][wn * WTN + lm][4 * lk];
+    const double* const b_ld = &Bs[0][SMALLN ? (lm & 3) : (wn * WTN + lm)][4 * lk];
     auto store_tiles = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < APT; ++i) {
@@ -318,13 +323,17 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[i].x, bv[j].x, acc[i][j], 0, 0, 0);
+                for (int j = 0; j < TN; ++j) {
+                    if constexpr (SMALLN) acc[i][j][0] = __builtin_amdgcn_mfma_f64_4x4x4f64(av[i].x, bv[j].x, acc[i][j][0], 0, 0, 0);
+                    else acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[i].x, bv[j].x, acc[i][j], 0, 0, 0);
+                }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[i].y, bv[j].y, acc[i][j], 0, 0, 0);
+                for (int j = 0; j < TN; ++j) {
+                    if constexpr (SMALLN) acc[i][j][0] = __builtin_amdgcn_mfma_f64_4x4x4f64(av[i].y, bv[j].y, acc[i][j][0], 0, 0, 0);
+                    else acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[i].y, bv[j].y, acc[i][j], 0, 0, 0);
+                }
         }
     };
 
@@ -355,8 +364,9 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-            const int r = r_tile + wm * WTM + i * 16 + 4 * r4 + lk;
+        for (int r4 = 0; r4 < (SMALLN ? 1 : 4); ++r4) {
+            // 16x16x4: register r4 of the lane is row 4*r4 + l/16; 4x4x4: the lane's one value is row 4*((l%16)/4) + l/16
+            const int r = r_tile + wm * WTM + i * 16 + (SMALLN ? 4 * (lm >> 2) : 4 * r4) + lk;
             if (r >= p.nrows) continue;
             const float* add_src = nullptr;
             size_t ridx = 0;
@@ -375,7 +385,7 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
             float* out_row = p.out + ((size_t)r * opix + pix) * N;
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                const int n = n0 + wn * WTN + j * 16 + lm;
+                const int n = SMALLN ? n0 + (lm & 3) : n0 + wn * WTN + j * 16 + lm;
                 if (n >= N) continue;
                 double v = acc[i][j][r4];
                 if (add_src) v += (double)add_src[n];
@@ -405,6 +415,7 @@ void launch_cross(const CrossParams& p, hipStream_t s) {
     const int N = p.Co;
     // tile shapes measured on MI355X: 64x64 beats the larger tiles (their lower occupancy costs more than their
     // higher arithmetic intensity gains); narrow layers take a tall tile so that fewer MFMA columns are padding
+    if (N <= 4) { launch_cross_t<128, 4>(p, s); return; }
     if (N <= 16) { launch_cross_t<128, 16>(p, s); return; }
     if (N <= 32) { launch_cross_t<128, 32>(p, s); return; }
     launch_cross_t<64, 64>(p, s);
@@ -1112,6 +1123,20 @@ __global__ void mfma_check_kernel(const double* A, const double* B, double* D, i
 }
 void launch_mfma_check(const double* A, const double* B, double* D, int K, hipStream_t s) {
     hipLaunchKernelGGL(mfma_check_kernel, dim3(1), dim3(64), 0, s, A, B, D, K);
+}
+// the 4-column form used for layers with at most 4 input channels: D[16][4] = A[16][K] * B[K][4]
+__global__ void mfma4_check_kernel(const double* A, const double* B, double* D, int K) {
+    const int l = threadIdx.x;
+    double c = 0.0;
+    for (int k0 = 0; k0 < K; k0 += 4) {
+        const double a = A[(l & 15) * K + k0 + (l >> 4)];
+        const double b = B[(k0 + (l >> 4)) * 4 + (l & 3)];
+        c = __builtin_amdgcn_mfma_f64_4x4x4f64(a, b, c, 0, 0, 0);
+    }
+    D[(4 * ((l & 15) >> 2) + (l >> 4)) * 4 + (l & 3)] = c;
+}
+void launch_mfma4_check(const double* A, const double* B, double* D, int K, hipStream_t s) {
+    hipLaunchKernelGGL(mfma4_check_kernel, dim3(1), dim3(64), 0, s, A, B, D, K);
 }
 
 }  // namespace gp

@@ -202,5 +202,7 @@ void launch_copy_rows(const CopyRowsParams& p, hipStream_t s);
 void launch_margins(const double* best, float* margins, long long n, int* flag, hipStream_t s);
 // float64 MFMA self-check: D[16][16] = A[16][K] * B[K][16], same instruction and layout as the crossing kernel
 void launch_mfma_check(const double* A, const double* B, double* D, int K, hipStream_t s);
+// the same for the 4-column instruction (4x4x4, four blocks): D[16][4] = A[16][K] * B[K][4]
+void launch_mfma4_check(const double* A, const double* B, double* D, int K, hipStream_t s);
 
 }  // namespace gp

@@ -21,7 +21,7 @@ EXPORTS = ["gp_net_create", "gp_net_destroy", "gp_add_dense", "gp_add_conv2d", "
            "gp_set_stream", "gp_workspace_size", "gp_set_workspace", "gp_analyze",
            "gp_analyze_box", "gp_analyze_batch", "gp_analyze_batch_dev", "gp_get_bounds", "gp_get_bounds_batch",
            "gp_get_bounds_f64", "gp_get_relu_lambda", "gp_get_relu_slopes", "gp_certify", "gp_certify_batch", "gp_debug_plan",
-           "gp_profile_enable", "gp_profile_read", "gp_profile_dump", "gp_debug_mfma_f64", "gp_num_layers", "gp_layer_size", "gp_last_error", "gp_version"]
+           "gp_profile_enable", "gp_profile_read", "gp_profile_dump", "gp_debug_mfma_f64", "gp_debug_mfma_f64_4col", "gp_num_layers", "gp_layer_size", "gp_last_error", "gp_version"]
 
 
 class GpuPolyError(RuntimeError):
@@ -79,6 +79,7 @@ def load_library():
     L.gp_profile_read.argtypes = [P, C.POINTER(C.c_int64), dp, dp, dp]
     L.gp_profile_dump.argtypes = [P, C.c_char_p]
     L.gp_debug_mfma_f64.argtypes = [P, P, P, i32, P]
+    L.gp_debug_mfma_f64_4col.argtypes = [P, P, P, i32, P]
     _lib = L
     return L
 

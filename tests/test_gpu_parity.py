@@ -80,28 +80,31 @@ def run_pair(net, center, eps, clip=(0.0, 1.0)):
 
 
 # ------------------------------------------------------------------------------------------------
-def test_mfma_f64_error_model():
-    """The crossing kernel's slack assumes |MFMA sum - exact sum| <= (K+8) * 2^-50 * sum|terms|.
-    Checked against exact rational arithmetic on float32-valued operands with heavy cancellation."""
+@pytest.mark.parametrize("cols", [16, 4])
+def test_mfma_f64_error_model(cols):
+    """The crossing kernel's slack assumes |MFMA sum - exact sum| <= (K+8) * 2^-50 * sum|terms|, for the 16-column
+    instruction and for the 4-column one.  Checked against exact rational arithmetic on float32-valued operands with
+    heavy cancellation."""
     from paper_2007_10868_amd import load_library
     lib = load_library()
     rng = np.random.default_rng(0)
     K = 512
     A = (rng.standard_normal((16, K)) * np.exp2(rng.integers(-20, 20, (16, K)))).astype(np.float32).astype(np.float64)
-    B = rng.standard_normal((K, 16)).astype(np.float32).astype(np.float64)
+    B = rng.standard_normal((K, cols)).astype(np.float32).astype(np.float64)
     A[:, 1::2] = -A[:, 0::2]           # cancellation
     B[1::2, :] = B[0::2, :] * (1 + 2.0 ** -20)
     B = B.astype(np.float32).astype(np.float64)
     tA, tB = torch.tensor(A, device="cuda"), torch.tensor(B, device="cuda")
-    tD = torch.zeros(16, 16, dtype=torch.float64, device="cuda")
-    st = lib.gp_debug_mfma_f64(C.c_void_p(tA.data_ptr()), C.c_void_p(tB.data_ptr()), C.c_void_p(tD.data_ptr()), K,
+    tD = torch.zeros(16, cols, dtype=torch.float64, device="cuda")
+    fn = lib.gp_debug_mfma_f64 if cols == 16 else lib.gp_debug_mfma_f64_4col
+    st = fn(C.c_void_p(tA.data_ptr()), C.c_void_p(tB.data_ptr()), C.c_void_p(tD.data_ptr()), K,
                                C.c_void_p(torch.cuda.current_stream().cuda_stream))
     assert st == 0
     torch.cuda.synchronize()
     D = tD.cpu().numpy()
     worst = 0.0
     for i in range(16):
-        for j in range(0, 16, 5):
+        for j in range(0, cols, 5 if cols == 16 else 1):
             terms = [Fraction(float(A[i, k])) * Fraction(float(B[k, j])) for k in range(K)]
             exact = sum(terms)
             mag = sum(abs(t) for t in terms)
