@@ -460,6 +460,25 @@ __device__ __forceinline__ double wave_sum8(double (&v)[8], int lane) {
     return y;
 }
 
+// One coefficient's contribution to the five per-row sums.  Written with explicit fused multiply-adds only, so that
+// every scan kernel performs exactly the same operations in the same order per lane and a row's result does not
+// depend on which kernel (i.e. on how many rows share the launch) handled it.
+__device__ __forceinline__ void scan_term(bool has_cand, bool do_consts, float mf, double cp, double cn, double X, double kp,
+                                          double be, double& cand, double& absx, double& cst, double& cstabs, double& s1) {
+    const double m = (double)mf;
+    const double am = fabs(m);
+    if (has_cand) {
+        cand = fma(m, mf >= 0.f ? cp : cn, cand);
+        absx = fma(am, X, absx);
+    }
+    if (do_consts) {
+        const double mp = fmax(m, 0.0);
+        cst = fma(m, be, fma(mp, kp, cst));
+        cstabs = fma(am, fabs(be), fma(mp, kp, cstabs));
+        s1 += am;
+    }
+}
+
 // Per-row bookkeeping after the reductions: rounding slack of the stored coefficients, candidate folded into best,
 // constants of the next step added to c, slack of the next accumulation.
 __device__ __forceinline__ void scan_finish(const ScanParams& p, int r, int nelem, double t_cand, double t_absx, double t_cst,
@@ -563,20 +582,9 @@ __global__ __launch_bounds__(256) void scan_kernel(const ScanParams p) {
     };
     auto accumulate = [&](int k, const float (&mf)[V], const Consts& q) {
 #pragma unroll
-        for (int v = 0; v < V; ++v) {
-            const double m = (double)mf[v];
-            if (p.cpos) {
-                cand[k] += (mf[v] >= 0.f) ? m * q.cp[v] : m * q.cn[v];
-                absx[k] += fabs(m) * q.X[v];
-            }
-            if (p.do_consts) {
-                const double tp = fmax(m, 0.0) * q.kp[v];
-                const double tb = m * q.be[v];
-                cst[k] += tp + tb;
-                cstabs[k] += tp + fabs(tb);
-                s1[k] += fabs(m);
-            }
-        }
+        for (int v = 0; v < V; ++v)
+            scan_term(p.cpos != nullptr, p.do_consts != 0, mf[v], q.cp[v], q.cn[v], q.X[v], q.kp[v], q.be[v], cand[k], absx[k],
+                      cst[k], cstabs[k], s1[k]);
     };
     auto load_m = [&](const float* src, float (&mf)[V]) {
         if (V == 4) {
@@ -625,21 +633,23 @@ __global__ __launch_bounds__(256) void scan_kernel(const ScanParams p) {
     }
 }
 
-// Short rows: the same reductions with 8 lanes per row and 8 rows per wave.  Every lane accumulates for its own row
-// (no per-row register arrays, so many more waves are resident), and fetches the constants of its own elements;
-// lanes of different rows that meet the same neuron read the same addresses.
-template <int V>
+// The same reductions with LPR lanes per row and 64/LPR rows per wave: every lane accumulates for its own row (no
+// per-row register arrays, so many more waves are resident) and fetches the constants of its own elements.
+//   LPR = 8  : short rows (8 rows per wave; lanes of different rows that meet the same neuron read the same addresses);
+//   LPR = 64 : one row per wave, for launches with so few rows that 8 rows per wave would leave most of the chip idle.
+template <int V, int LPR>
 __global__ __launch_bounds__(256) void scan_tall_kernel(const ScanParams p) {
+    constexpr int RPW = 64 / LPR;                            // rows per wave
     const int tid = threadIdx.x, lane = tid & 63;
     const BlockDesc& B = p.blk;
-    const int groups_per_half = (p.rm.Rc + SCAN_G - 1) / SCAN_G;
+    const int groups_per_half = (p.rm.Rc + RPW - 1) / RPW;
     const int gidx = blockIdx.x * 4 + (tid >> 6);
     const int nhalves = p.nrows / p.rm.Rc;
     if (gidx >= groups_per_half * nhalves) return;          // whole wave leaves
     const int half = gidx / groups_per_half;
-    const int rr0 = (gidx - half * groups_per_half) * SCAN_G;
-    const int nvalid = min(SCAN_G, p.rm.Rc - rr0);
-    const int k = lane >> 3, sub = lane & 7;
+    const int rr0 = (gidx - half * groups_per_half) * RPW;
+    const int nvalid = min(RPW, p.rm.Rc - rr0);
+    const int k = lane / LPR, sub = lane % LPR;
     const bool valid = k < nvalid;
     const int r = half * p.rm.Rc + rr0 + (valid ? k : 0);
     const int nelem = B.wy * B.wx * B.C;
@@ -650,7 +660,7 @@ __global__ __launch_bounds__(256) void scan_tall_kernel(const ScanParams p) {
     const float* src = B.data + (size_t)r * nelem;
     double cand = 0.0, absx = 0.0, cst = 0.0, cstabs = 0.0, s1 = 0.0;
     if (valid) {
-        for (int e = sub * V; e < nelem; e += 8 * V) {
+        for (int e = sub * V; e < nelem; e += LPR * V) {
             float mf[V];
             if (V == 4) {
                 const float4 t = *reinterpret_cast<const float4*>(src + e);
@@ -671,23 +681,22 @@ __global__ __launch_bounds__(256) void scan_tall_kernel(const ScanParams p) {
             }
 #pragma unroll
             for (int v = 0; v < V; ++v) {
-                const double m = (double)mf[v];
+                double cp = 0.0, cn = 0.0, X = 0.0, kp = 0.0, be = 0.0;
                 if (p.cpos) {
-                    cand += (mf[v] >= 0.f) ? m * p.cpos[j + v] : m * p.cneg[j + v];
-                    absx += fabs(m) * fmax(fabs(p.xlo[j + v]), fabs(p.xhi[j + v]));
+                    cp = p.cpos[j + v];
+                    cn = p.cneg[j + v];
+                    X = fmax(fabs(p.xlo[j + v]), fabs(p.xhi[j + v]));
                 }
                 if (p.do_consts) {
-                    const double tp = p.kap ? fmax(m, 0.0) * p.kap[j + v] : 0.0;
-                    const double tb = p.beff ? m * p.beff[c + v] : 0.0;
-                    cst += tp + tb;
-                    cstabs += tp + fabs(tb);
-                    s1 += fabs(m);
+                    if (p.kap) kp = p.kap[j + v];
+                    if (p.beff) be = p.beff[c + v];
                 }
+                scan_term(p.cpos != nullptr, p.do_consts != 0, mf[v], cp, cn, X, kp, be, cand, absx, cst, cstabs, s1);
             }
         }
     }
 #pragma unroll
-    for (int off = 4; off > 0; off >>= 1) {
+    for (int off = LPR / 2; off > 0; off >>= 1) {
         cand += __shfl_xor(cand, off, 64);
         absx += __shfl_xor(absx, off, 64);
         cst += __shfl_xor(cst, off, 64);
@@ -704,8 +713,12 @@ void launch_scan(const ScanParams& p, hipStream_t s) {
     const int nelem = p.blk.wy * p.blk.wx * p.blk.C;
     const bool vec = (p.blk.C & 3) == 0;
     if (nelem <= 256) {      // measured cross-over of the two layouts on MI355X
-        if (vec) hipLaunchKernelGGL((scan_tall_kernel<4>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
-        else hipLaunchKernelGGL((scan_tall_kernel<1>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
+        if (vec) hipLaunchKernelGGL((scan_tall_kernel<4, 8>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((scan_tall_kernel<1, 8>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
+    } else if (groups < 2048) {   // fewer waves than the chip holds at once: one row per wave
+        const int waves = p.nrows;
+        if (vec) hipLaunchKernelGGL((scan_tall_kernel<4, 64>), dim3((waves + 3) / 4), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((scan_tall_kernel<1, 64>), dim3((waves + 3) / 4), dim3(256), 0, s, p);
     } else if (vec) {
         hipLaunchKernelGGL((scan_kernel<4>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
     } else {
