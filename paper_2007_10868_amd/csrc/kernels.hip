@@ -117,7 +117,7 @@ template <int BM, int BN, bool VEC>
 __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
     constexpr int BK = 16;
     constexpr int LDK = 18;                          // doubles per tile row: 144 B, keeps 16-byte alignment, spreads banks
-    constexpr int WAVES_N = (BN >= 64) ? 2 : 1;
+    constexpr int WAVES_N = (BN >= 64 || BM < 64) ? 2 : 1;
     constexpr int WAVES_M = 4 / WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
     // BN == 4: layers with at most 4 input channels (the image).  A 16-column MFMA tile would be 13/16 padding
@@ -418,6 +418,10 @@ void launch_cross(const CrossParams& p, hipStream_t s) {
     if (N <= 4) { launch_cross_t<128, 4>(p, s); return; }
     if (N <= 16) { launch_cross_t<128, 16>(p, s); return; }
     if (N <= 32) { launch_cross_t<128, 32>(p, s); return; }
+    // few rows (one input at a time): smaller tiles so that the launch still covers the chip
+    const long long wg64 = (long long)((p.nrows + 63) / 64) * ((N + 63) / 64) * p.owy * p.owx;
+    if (wg64 < 256) { launch_cross_t<32, 32>(p, s); return; }
+    if (wg64 < 512) { launch_cross_t<64, 32>(p, s); return; }
     launch_cross_t<64, 64>(p, s);
 }
 
