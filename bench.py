@@ -102,7 +102,7 @@ def main():
     tfile = os.path.join(ROOT, "profiles", f"cross_kernel_{net.name}_traffic.json")
     if os.path.exists(tfile) and batch == net.n_inputs:      # counters of a committed rocprofv3 --pmc run of this workload
         traffic = json.load(open(tfile)).get("hbm_bytes_per_launch")
-    roofline = dict(bound="mfma", kernel="cross_kernel (float64 MFMA implicit GEMM)", achieved=round(achieved, 3),
+    roofline = dict(bound="mfma", kernel="cross_kernel (float64 MFMA implicit GEMM; all crossing launches of a pass)", achieved=round(achieved, 3),
                     peak=PEAK_FP64_MFMA_TFLOPS, unit="TFLOP/s", frac=round(achieved / PEAK_FP64_MFMA_TFLOPS, 4),
                     traffic=traffic, launches_per_step=cross["launches"] // args.steps,
                     avg_launch_us=round(avg_launch_ms * 1e3, 2), alg_flop_per_launch=flop_per_launch,
