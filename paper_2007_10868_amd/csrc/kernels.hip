@@ -483,35 +483,52 @@ __device__ __forceinline__ void scan_term(bool has_cand, bool do_consts, float m
     }
 }
 
+// The scalars of a row that its bookkeeping reads.  Fetched early (scan_row_fetch) by the kernels that want the
+// round trip to overlap with the row's own loads.
+struct ScanRow {
+    double c, err, best, xmax_self, xmax_a, xmax_b;
+    int bi;
+    bool frozen;
+};
+__device__ __forceinline__ ScanRow scan_row_fetch(const ScanParams& p, int r, const RowInfo& ri) {
+    ScanRow s;
+    s.c = p.c[r];
+    s.err = p.err[r];
+    s.xmax_self = (p.round_coef > 0.0 && p.xmax_self) ? p.xmax_self[ri.b] : 0.0;
+    s.bi = 0; s.best = 0.0; s.frozen = true;
+    if (p.update_best && p.cpos) {
+        // a task that met the termination criterion keeps the bounds it had at that moment
+        s.frozen = p.done && p.done[r >= p.rm.Rc ? r - p.rm.Rc : r];
+        s.bi = best_index(p.rm, r);
+        s.best = p.best[s.bi];
+    }
+    s.xmax_a = (p.do_consts && p.xmax_a) ? p.xmax_a[ri.b] : 0.0;
+    s.xmax_b = (p.do_consts && p.xmax_b) ? p.xmax_b[ri.b] : 0.0;
+    return s;
+}
 // Per-row bookkeeping after the reductions: rounding slack of the stored coefficients, candidate folded into best,
 // constants of the next step added to c, slack of the next accumulation.
-__device__ __forceinline__ void scan_finish(const ScanParams& p, int r, int nelem, double t_cand, double t_absx, double t_cst,
-                                            double t_cstabs, double t_s1) {
-    const RowInfo ri = row_info(p.rm, r);
+__device__ __forceinline__ void scan_finish(const ScanParams& p, int r, int nelem, const ScanRow& s, double t_cand,
+                                            double t_absx, double t_cst, double t_cstabs, double t_s1) {
     // a sum of n float64 terms in any order is off by at most (n-1)*2^-53*sum|terms|*(1+tiny)
     const double esum = (double)(nelem + 16) * 0x1p-52;
-    double c = p.c[r];
-    double err = p.err[r];
+    double c = s.c;
+    double err = s.err;
     // slack of the stored coefficients: |true - stored| <= round_coef*|stored| (+ subnormal floor)
     err += t_absx * p.round_coef * (1.0 + esum);
     // values below the float32 subnormal step vanish; with a substituted ReLU the lost coefficient is
     // up to 2^20 times larger (slopes are kept >= 2^-20)
-    if (p.round_coef > 0.0 && p.xmax_self) err += 0x1p-128 * (double)nelem * p.xmax_self[ri.b];
+    if (p.round_coef > 0.0 && p.xmax_self) err += 0x1p-128 * (double)nelem * s.xmax_self;
     if (p.update_best && p.cpos) {
         double v = c + t_cand + err;
         v += (fabs(c) + fabs(t_cand) + err) * 0x1p-50 + t_absx * esum;
-        // a task that met the termination criterion keeps the bounds it had at that moment
-        const bool frozen = p.done && p.done[r >= p.rm.Rc ? r - p.rm.Rc : r];
-        if (!frozen) {
-            const int bi = best_index(p.rm, r);
-            p.best[bi] = fmin(p.best[bi], v);
-        }
+        if (!s.frozen) p.best[s.bi] = fmin(s.best, v);
     }
     if (p.do_consts) {
         double cn = c + t_cst;
         double e1 = 0.0;
-        if (p.xmax_a) e1 += p.e1_a * p.xmax_a[ri.b];
-        if (p.xmax_b) e1 += p.e1_b * p.xmax_b[ri.b];
+        if (p.xmax_a) e1 += p.e1_a * s.xmax_a;
+        if (p.xmax_b) e1 += p.e1_b * s.xmax_b;
         err += t_cstabs * esum + (fabs(c) + fabs(t_cst)) * 0x1p-51 + t_s1 * e1 * (1.0 + esum);
         c = cn;
     }
@@ -633,7 +650,8 @@ __global__ __launch_bounds__(256) void scan_kernel(const ScanParams p) {
     const int k = lane >> 3;
     if ((lane & 7) == 0 && k < nvalid) {
         const int r = r0 + k;
-        scan_finish(p, r, nelem, t_cand, t_absx, t_cst, t_cstabs, t_s1);
+        const RowInfo ri = row_info(p.rm, r);
+        scan_finish(p, r, nelem, scan_row_fetch(p, r, ri), t_cand, t_absx, t_cst, t_cstabs, t_s1);
     }
 }
 
@@ -707,7 +725,126 @@ __global__ __launch_bounds__(256) void scan_tall_kernel(const ScanParams p) {
         cstabs += __shfl_xor(cstabs, off, 64);
         s1 += __shfl_xor(s1, off, 64);
     }
-    if (valid && sub == 0) scan_finish(p, r, nelem, cand, absx, cst, cstabs, s1);
+    if (valid && sub == 0) scan_finish(p, r, nelem, scan_row_fetch(p, r, ri), cand, absx, cst, cstabs, s1);
+}
+
+// Rows of a few hundred coefficients (dense layers, small windows): 32 rows per work-group, 8 lanes per row.  The
+// per-neuron constants of the rows' window are staged ONCE per work-group in LDS (5 doubles per element) instead of
+// being fetched by every wave, every lane accumulates for its own row (few registers, many resident waves), and
+// lanes of different rows read the same LDS words (broadcast).  Rows of a work-group that do not share box and
+// window origin are handled run by run.
+constexpr int SCAN_LDS_MAX = 1024;      // elements per row this kernel takes (40 KB of LDS at most)
+// ROWS per work-group (8 lanes each): 32, or 8 when a launch has so few rows that more, smaller work-groups finish
+// sooner; the grouping does not touch a row's arithmetic.
+// U: row slices (8 lanes x V elements each) whose loads are in flight together.
+template <int V, int ROWS, int U>
+__global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) {
+    constexpr int SCAN_LDS_ROWS = ROWS;
+    constexpr int NT = ROWS * 8;
+    extern __shared__ __attribute__((aligned(16))) double s_const[];     // [5][nelem_pad]
+    __shared__ int s_b[SCAN_LDS_ROWS], s_oy[SCAN_LDS_ROWS], s_ox[SCAN_LDS_ROWS];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const BlockDesc& B = p.blk;
+    const int nelem = B.wy * B.wx * B.C;
+    const int npad = (nelem + 3) & ~3;
+    double* const s_cp = s_const;
+    double* const s_cn = s_const + npad;
+    double* const s_X = s_const + 2 * npad;
+    double* const s_kp = s_const + 3 * npad;
+    double* const s_be = s_const + 4 * npad;
+    const int gph = (p.rm.Rc + SCAN_LDS_ROWS - 1) / SCAN_LDS_ROWS;      // work-groups per half
+    const int half = blockIdx.x / gph;
+    const int rr0 = (blockIdx.x - half * gph) * SCAN_LDS_ROWS;
+    const int nvalid = min(SCAN_LDS_ROWS, p.rm.Rc - rr0);
+    const int kk = wave * 8 + (lane >> 3), sub = lane & 7;
+    const bool valid = kk < nvalid;
+    const int r = half * p.rm.Rc + rr0 + (valid ? kk : 0);
+    const bool full_row = (B.wx == B.W);
+    const RowInfo ri = row_info(p.rm, r);
+    if (sub == 0 && valid) {
+        s_b[kk] = ri.b;
+        s_oy[kk] = clampi(B.Sy * ri.ys - B.Py, 0, B.H - B.wy);
+        s_ox[kk] = clampi(B.Sx * ri.xs - B.Px, 0, B.W - B.wx);
+    }
+    __syncthreads();
+    const float* src = B.data + (size_t)r * nelem;
+    double cand = 0.0, absx = 0.0, cst = 0.0, cstabs = 0.0, s1 = 0.0;
+    auto load_slices = [&](int e0, float (&mf)[U][V]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int e = e0 + u * 8 * V;
+            if (e < nelem) {
+                if (V == 4) {
+                    const float4 t = *reinterpret_cast<const float4*>(src + e);
+                    mf[u][0] = t.x; mf[u][1 % V] = t.y; mf[u][2 % V] = t.z; mf[u][3 % V] = t.w;
+                } else {
+                    mf[u][0] = src[e];
+                }
+            }
+        }
+    };
+    auto add_slices = [&](int e0, const float (&mf)[U][V]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int e = e0 + u * 8 * V;
+            if (e < nelem) {
+#pragma unroll
+                for (int v = 0; v < V; ++v)
+                    scan_term(p.cpos != nullptr, p.do_consts != 0, mf[u][v], s_cp[e + v], s_cn[e + v], s_X[e + v],
+                              s_kp[e + v], s_be[e + v], cand, absx, cst, cstabs, s1);
+            }
+        }
+    };
+    int k0 = 0;
+    while (k0 < nvalid) {                                   // uniform over the work-group
+        const int b0 = s_b[k0], oy0 = s_oy[k0], ox0 = s_ox[k0];
+        int k1 = k0 + 1;
+        while (k1 < nvalid && s_b[k1] == b0 && s_oy[k1] == oy0 && s_ox[k1] == ox0) ++k1;
+        const long long bbase = (long long)b0 * p.batch_stride;
+        for (int e = tid; e < nelem; e += NT) {
+            int c;
+            long long j;
+            if (full_row) {
+                c = e % B.C;
+                j = bbase + (long long)oy0 * B.W * B.C + e;
+            } else {
+                const int pix = e / B.C;
+                c = e - pix * B.C;
+                const int a = pix / B.wx, bb = pix - a * B.wx;
+                j = bbase + ((long long)((oy0 + a) * B.W + (ox0 + bb)) * B.C + c);
+            }
+            double cp = 0.0, cn = 0.0, X = 0.0, kp = 0.0, be = 0.0;
+            if (p.cpos) {
+                cp = p.cpos[j];
+                cn = p.cneg[j];
+                X = fmax(fabs(p.xlo[j]), fabs(p.xhi[j]));
+            }
+            if (p.do_consts) {
+                if (p.kap) kp = p.kap[j];
+                if (p.beff) be = p.beff[c];
+            }
+            s_cp[e] = cp; s_cn[e] = cn; s_X[e] = X; s_kp[e] = kp; s_be[e] = be;
+        }
+        __syncthreads();
+        if (valid && kk >= k0 && kk < k1) {
+            for (int e0 = sub * V; e0 < nelem; e0 += U * 8 * V) {
+                float mf[U][V];
+                load_slices(e0, mf);
+                add_slices(e0, mf);
+            }
+        }
+        __syncthreads();                                    // the next run overwrites the constants
+        k0 = k1;
+    }
+#pragma unroll
+    for (int off = 4; off > 0; off >>= 1) {
+        cand += __shfl_xor(cand, off, 64);
+        absx += __shfl_xor(absx, off, 64);
+        cst += __shfl_xor(cst, off, 64);
+        cstabs += __shfl_xor(cstabs, off, 64);
+        s1 += __shfl_xor(s1, off, 64);
+    }
+    if (valid && sub == 0) scan_finish(p, r, nelem, scan_row_fetch(p, r, ri), cand, absx, cst, cstabs, s1);
 }
 
 void launch_scan(const ScanParams& p, hipStream_t s) {
@@ -719,6 +856,17 @@ void launch_scan(const ScanParams& p, hipStream_t s) {
     if (nelem <= 256) {      // measured cross-over of the two layouts on MI355X
         if (vec) hipLaunchKernelGGL((scan_tall_kernel<4, 8>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
         else hipLaunchKernelGGL((scan_tall_kernel<1, 8>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
+    } else if (nelem <= SCAN_LDS_MAX) {
+        const size_t lds = (size_t)5 * ((nelem + 3) & ~3) * sizeof(double);
+        if (p.nrows >= 4096) {
+            const int wgs = ((p.rm.Rc + 31) / 32) * nhalves;
+            if (vec) hipLaunchKernelGGL((scan_lds_kernel<4, 32, 4>), dim3(wgs), dim3(256), lds, s, p);
+            else hipLaunchKernelGGL((scan_lds_kernel<1, 32, 4>), dim3(wgs), dim3(256), lds, s, p);
+        } else {
+            const int wgs = ((p.rm.Rc + 7) / 8) * nhalves;
+            if (vec) hipLaunchKernelGGL((scan_lds_kernel<4, 8, 4>), dim3(wgs), dim3(64), lds, s, p);
+            else hipLaunchKernelGGL((scan_lds_kernel<1, 8, 4>), dim3(wgs), dim3(64), lds, s, p);
+        }
     } else if (groups < 2048) {   // fewer waves than the chip holds at once: one row per wave
         const int waves = p.nrows;
         if (vec) hipLaunchKernelGGL((scan_tall_kernel<4, 64>), dim3((waves + 3) / 4), dim3(256), 0, s, p);

@@ -133,3 +133,25 @@ def test_no_gpu_is_an_error_not_a_fallback():
     with pytest.raises(GpuPolyError) as e:
         n.analyze(np.zeros(4, np.float32), 0.1)
     assert e.value.status == 5
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: asking the benchmark for more must end with a message, not with a number."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_early_termination_calls_without_analysis():
+    g = Net(4)
+    g.add_dense(0, np.ones((3, 4), np.float32))
+    g.set_early_termination(True)
+    with pytest.raises(GpuPolyError) as e:
+        g.get_term_layer(1)
+    assert e.value.status == 3          # GP_ERR_STATE: nothing analysed yet
+    with pytest.raises(GpuPolyError):
+        g.early_termination_stats()
+    g.set_early_termination(False)
