@@ -127,6 +127,13 @@ gp_status gp_certify(gp_net* net, int32_t label, int32_t* verified, float* margi
 /* labels: [batch]; verified: [batch]; margins: [batch][n_out-1]. */
 gp_status gp_certify_batch(gp_net* net, const int32_t* labels, int32_t* verified, float* margins);
 
+/* Sound lower bounds of arbitrary linear forms of the last layer over the analysed box(es):
+ *   lower[b][r] <= sum_j coef[r][j] * y_j + offset[r]   for every input of box b
+ * by back-substituting the form (the certification rows y_label - y_j of gp_certify are the special case; the paper's
+ * introduction names properties other than robustness that reduce to such forms).  coef: [n_forms][n_out] with the
+ * outputs numbered C,H,W; offset: [n_forms] or NULL; lower: [batch][n_forms], rounded down to float32. */
+gp_status gp_bound_outputs(gp_net* net, int32_t n_forms, const float* coef, const float* offset, float* lower);
+
 /* Introspection (host only, no GPU needed): the sequence of back-substitution steps planned for
  * the rows of `layer_id`.  Each step is 8 int32: {kind, layer, window_h, window_w, channels,
  * acc_stride_h, acc_pad_h, merged}; kind 0 = initial block, 1 = affine crossing, 2 = ReLU,

@@ -65,6 +65,7 @@ def _load():
     L.dp_analyze_layer.argtypes = [P, C.c_int]
     L.dp_analyze.argtypes = [P]
     L.dp_certify.argtypes = [P, C.c_int, ip, dp]
+    L.dp_bound_forms.argtypes = [P, C.c_int, dp, dp, dp]
     L.dp_selftest_rounding.argtypes = [C.c_double] * 3
     L.dp_num_threads.restype = C.c_int
     bad = L.dp_selftest_rounding(1.0, 1e-30, 1.0 / 3.0)
@@ -275,3 +276,18 @@ class OracleNet:
         self._chk(self._L.dp_certify(self._h, int(label), C.byref(v), m.ctypes.data_as(C.POINTER(C.c_double))),
                   "certify")
         return bool(v.value), m
+
+    def bound_outputs(self, coef, offset=None) -> np.ndarray:
+        """Lower bounds of the linear forms coef @ y + offset of the last layer (rows of coef)."""
+        n = self.layer_size(self.num_layers - 1)
+        cf, pc = _f64(np.atleast_2d(coef))
+        assert cf.shape[1] == n
+        if offset is not None:
+            off, po = _f64(offset)
+            assert off.size == cf.shape[0]
+        else:
+            po = None
+        out = np.empty(cf.shape[0], np.float64)
+        self._chk(self._L.dp_bound_forms(self._h, cf.shape[0], pc, po, out.ctypes.data_as(C.POINTER(C.c_double))),
+                  "bound_forms")
+        return out

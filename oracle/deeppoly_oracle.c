@@ -829,6 +829,39 @@ int dp_certify(dp_net *N, int label, int *verified, double *margins) {
     return DP_OK;
 }
 
+/* Lower bounds of arbitrary linear forms of the last layer, sum_j coef[r][j]*y_j + offset[r] (the certification
+   rows y_label - y_j are the special case dp_certify computes): other output specifications than robustness. */
+int dp_bound_forms(dp_net *N, int n_forms, const double *coef, const double *offset, double *lower) {
+    if (!N || n_forms < 0 || !coef || !lower) return DP_ERR_ARG;
+    int lid = N->n_layers - 1;
+    layer_t *l = &N->L[lid];
+    if (!l->has_bounds) return DP_ERR_STATE;
+    if (l->type == L_RELU) return DP_ERR_ARG;
+#pragma omp parallel
+    {
+        int old = fegetround();
+        fesetround(FE_UPWARD);
+        expr_t *e = expr_new(N);
+#pragma omp for schedule(dynamic, 1)
+        for (int r = 0; r < n_forms; ++r) {
+            expr_clear(e, N);
+            for (int j = 0; j < l->n; ++j) e->lo[lid][j] = e->hi[lid][j] = coef[(size_t)r * l->n + j];
+            e->active[lid] = 1;
+            e->clo = e->chi = offset ? offset[r] : 0.0;
+            switch (l->type) {
+                case L_DENSE: step_dense(N, e, lid); break;
+                case L_CONV:  step_conv(N, e, lid); break;
+                case L_ADD:   step_add(N, e, lid); break;
+                default: break;
+            }
+            lower[r] = backsubstitute(N, e, -1);
+        }
+        expr_free(e);
+        fesetround(old);
+    }
+    return DP_OK;
+}
+
 /* Self-check that the compiler kept the directed-rounding idioms intact (returns 0 when fine).
    The inputs come from the caller so that nothing can be folded at compile time. */
 int dp_selftest_rounding(double one, double tiny, double third) {

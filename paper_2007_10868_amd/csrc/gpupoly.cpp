@@ -96,6 +96,11 @@ struct gp_net {
     int* d_flag = nullptr;
     int* d_labels = nullptr;
     float* d_margins = nullptr;
+    // arbitrary linear forms of the outputs (gp_bound_outputs)
+    float *d_forms = nullptr, *d_form_off = nullptr, *d_form_out = nullptr;
+    long long d_forms_cap = 0, d_form_out_cap = 0;
+    int n_forms = 0;               // > 0 while run_plan works on caller-given forms instead of certification rows
+    bool forms_have_offset = false;
     float* d_centers = nullptr;
     long long d_centers_cap = 0;
     int device = -1;
@@ -516,7 +521,8 @@ void prof_mark(gp_net* net, int kind, bool stop) {
 gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int batch) {
     const Layer& ls = net->L[start];
     const int nsign = certify ? 1 : 2;
-    const long long n_start = certify ? (ls.n - 1) : ls.n;
+    const bool forms = certify && net->n_forms > 0;
+    const long long n_start = forms ? net->n_forms : certify ? (ls.n - 1) : ls.n;
     const long long total = n_start * batch;
     if (total <= 0) return GP_OK;
     const bool early = net->early && !certify;
@@ -669,8 +675,10 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                 ip.out = slot_ptr(op.slot_out);
                 ip.rm = rm; ip.nrows = nrows;
                 ip.nelem = (int)block_elems(op.g_out, lo);
-                ip.mode = op.init_mode;
+                ip.mode = (forms && op.init_mode == 1) ? 3 : op.init_mode;
                 ip.labels = net->d_labels;
+                ip.forms = net->d_forms;
+                ip.offsets = net->forms_have_offset ? net->d_form_off : nullptr;
                 ip.H = lo.H; ip.W = lo.W; ip.C = lo.C;
                 if (op.init_mode == 2) {
                     ip.wy = std::min(op.g_out.Wy, lo.H); ip.wx = std::min(op.g_out.Wx, lo.W);
@@ -784,7 +792,7 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                 }
             } else if (op.kind == PlanOp::FINALIZE) {
                 if (certify) {
-                    gp::launch_margins(d_best, net->d_margins + row0, rm0.Rc, net->d_flag, net->stream);
+                    gp::launch_margins(d_best, (forms ? net->d_form_out : net->d_margins) + row0, rm0.Rc, net->d_flag, net->stream);
                 } else {
                     gp::FinalizeParams fp;
                     fp.rm = rm0; fp.best = d_best;
@@ -917,6 +925,7 @@ void gp_net_destroy(gp_net* net) {
     dfree(net->d_count);
     if (net->h_count) (void)hipHostFree(net->h_count);
     if (net->count_ev) (void)hipEventDestroy(net->count_ev);
+    dfree(net->d_forms); dfree(net->d_form_off); dfree(net->d_form_out);
     dfree(net->d_flag); dfree(net->d_labels); dfree(net->d_margins); dfree(net->d_centers);
     dfree(net->ws_own);
     for (int k = 0; k < 2; ++k)
@@ -1295,6 +1304,48 @@ gp_status gp_certify_batch(gp_net* net, const int32_t* labels, int32_t* verified
                 if (!(margins[b * (lo.n - 1) + j] > 0.f)) ok = 0;
             verified[b] = ok;
         }
+    return GP_OK;
+}
+
+gp_status gp_bound_outputs(gp_net* net, int32_t n_forms, const float* coef, const float* offset, float* lower) {
+    if (!net) return GP_ERR_ARG;
+    if (n_forms <= 0 || !coef || !lower) return fail(net, GP_ERR_ARG, "n_forms must be positive, coef and lower non-null");
+    if (!net->analyzed) return fail(net, GP_ERR_STATE, "no successful analysis yet");
+    const int last = (int)net->L.size() - 1;
+    const Layer& lo = net->L[last];
+    if (lo.type == T_RELU) return fail(net, GP_ERR_UNSUPPORTED, "the last layer must be affine or a sum");
+    if (!all_finite(coef, (size_t)n_forms * lo.n) || (offset && !all_finite(offset, n_forms)))
+        return fail(net, GP_ERR_NONFINITE, "NaN/Inf in the forms");
+    if (!net->cert_plan.valid) {
+        gp_status st = build_plan(net, last, true, net->cert_plan);
+        if (st != GP_OK) return st;
+    }
+    const long long ncoef = (long long)n_forms * lo.n, nout = (long long)n_forms * net->batch;
+    if (net->d_forms_cap < ncoef) {
+        dfree(net->d_forms); dfree(net->d_form_off);
+        net->d_forms = net->d_form_off = nullptr; net->d_forms_cap = 0;
+        HIP_TRY(net, hipMalloc((void**)&net->d_forms, ncoef * sizeof(float)));
+        HIP_TRY(net, hipMalloc((void**)&net->d_form_off, (size_t)n_forms * sizeof(float)));
+        net->d_forms_cap = ncoef;
+    }
+    if (net->d_form_out_cap < nout) {
+        dfree(net->d_form_out); net->d_form_out = nullptr; net->d_form_out_cap = 0;
+        HIP_TRY(net, hipMalloc((void**)&net->d_form_out, nout * sizeof(float)));
+        net->d_form_out_cap = nout;
+    }
+    HIP_TRY(net, hipMemcpyAsync(net->d_forms, coef, ncoef * sizeof(float), hipMemcpyHostToDevice, net->stream));
+    if (offset)
+        HIP_TRY(net, hipMemcpyAsync(net->d_form_off, offset, (size_t)n_forms * sizeof(float), hipMemcpyHostToDevice, net->stream));
+    HIP_TRY(net, hipStreamSynchronize(net->stream));
+    gp::launch_fill_i32(net->d_flag, 0, 1, net->stream);
+    net->n_forms = n_forms;
+    net->forms_have_offset = offset != nullptr;
+    gp_status st = run_plan(net, net->cert_plan, last, true, net->batch);
+    net->n_forms = 0;
+    if (st != GP_OK) return st;
+    st = check_flag(net);
+    if (st != GP_OK) return st;
+    HIP_TRY(net, hipMemcpy(lower, net->d_form_out, nout * sizeof(float), hipMemcpyDeviceToHost));
     return GP_OK;
 }
 

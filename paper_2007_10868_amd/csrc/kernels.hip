@@ -884,6 +884,7 @@ void launch_scan(const ScanParams& p, hipStream_t s) {
 //   mode 1: e_j - e_label over the whole last layer (certification rows)
 //   mode 2: +/- the row of the start layer's matrix, i.e. its filter placed in the window over the
 //           predecessor; constant = +/- bias.  Exact: no rounding.
+//   mode 3: minus a caller-given linear form over the whole last layer; constant = minus its offset
 __global__ __launch_bounds__(256) void init_kernel(const InitParams p) {
     // block = 4 rows x 64 elements; grid.x over row quadruples, grid.y over element chunks
     const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -902,6 +903,10 @@ __global__ __launch_bounds__(256) void init_kernel(const InitParams p) {
             int chw = c * (p.H * p.W) + pix;
             if (chw == j) v = 1.f;
             else if (chw == label) v = -1.f;
+        } else if (p.mode == 3) {
+            // upper bound of minus the form: block order is H,W,C, the form's coefficients are numbered C,H,W
+            int pix = e / p.C, c = e - pix * p.C;
+            v = -p.forms[(size_t)ri.cs * p.nelem + (size_t)c * (p.H * p.W) + pix];
         } else if (p.dense) {
             v = ri.sign * p.wt[(size_t)ri.cs * p.nelem + e];
             if (p.out_grl && v != 0.f)
@@ -923,7 +928,7 @@ __global__ __launch_bounds__(256) void init_kernel(const InitParams p) {
         out[e] = v;
     }
     if (blockIdx.y == 0 && (threadIdx.x & 63) == 0) {
-        p.c[r] = (p.mode == 2) ? (double)(ri.sign * p.bias[ri.cs]) : 0.0;
+        p.c[r] = (p.mode == 2) ? (double)(ri.sign * p.bias[ri.cs]) : (p.mode == 3 && p.offsets) ? -(double)p.offsets[ri.cs] : 0.0;
         p.err[r] = 0.0;
         if (!p.seeded) p.best[r] = INFINITY;
     }

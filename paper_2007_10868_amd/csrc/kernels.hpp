@@ -104,9 +104,12 @@ struct InitParams {
     RowMap rm;
     int nrows;
     int nelem;             // elements per row
-    int mode;              // 0: one-hot over the start layer; 1: certification rows; 2: the start layer's own matrix row
+    int mode;              // 0: one-hot over the start layer; 1: certification rows; 2: the start layer's own matrix row;
+                           // 3: minus a caller-given linear form of the last layer (rows of `forms`, C,H,W order)
     const float* out_grl;  // mode 2: packed relaxation of the predecessor when it is a ReLU layer (applied), else null
     const int* labels;     // mode 1: [batch]
+    const float* forms;    // mode 3: [n_forms][nelem]
+    const float* offsets;  // mode 3: [n_forms] or null
     int H, W, C;           // dims of the layer the block ranges over (mode 1: last layer; mode 2: predecessor)
     // mode 2: window geometry over the predecessor and the start layer's filter
     int wy, wx, Sy, Sx, Py, Px;

@@ -20,7 +20,7 @@ EXPORTS = ["gp_net_create", "gp_net_destroy", "gp_add_dense", "gp_add_conv2d", "
            "gp_request_bounds", "gp_set_early_termination", "gp_get_term_layer", "gp_get_early_termination_stats",
            "gp_set_stream", "gp_workspace_size", "gp_set_workspace", "gp_analyze",
            "gp_analyze_box", "gp_analyze_batch", "gp_analyze_batch_dev", "gp_get_bounds", "gp_get_bounds_batch",
-           "gp_get_bounds_f64", "gp_get_relu_lambda", "gp_get_relu_slopes", "gp_certify", "gp_certify_batch", "gp_debug_plan",
+           "gp_get_bounds_f64", "gp_get_relu_lambda", "gp_get_relu_slopes", "gp_certify", "gp_certify_batch", "gp_bound_outputs", "gp_debug_plan",
            "gp_profile_enable", "gp_profile_read", "gp_profile_dump", "gp_debug_mfma_f64", "gp_debug_mfma_f64_4col", "gp_num_layers", "gp_layer_size", "gp_last_error", "gp_version"]
 
 
@@ -69,6 +69,7 @@ def load_library():
     L.gp_get_relu_slopes.argtypes = [P, i32, i32, fp]
     L.gp_certify.argtypes = [P, i32, ip, fp]
     L.gp_certify_batch.argtypes = [P, ip, ip, fp]
+    L.gp_bound_outputs.argtypes = [P, i32, fp, fp, fp]
     L.gp_debug_plan.argtypes = [P, i32, ip, i32, ip]
     L.gp_num_layers.argtypes = [P]
     L.gp_layer_size.argtypes = [P, i32]
@@ -251,6 +252,20 @@ class Net:
                                            v.ctypes.data_as(C.POINTER(C.c_int32)),
                                            m.ctypes.data_as(C.POINTER(C.c_float))))
         return v.astype(bool), m
+
+    def bound_outputs(self, coef, offset=None, batch=1):
+        """Lower bounds of coef @ y + offset over each analysed box; returns [batch, n_forms] float32."""
+        cf = np.ascontiguousarray(np.atleast_2d(coef), dtype=np.float32)
+        assert cf.shape[1] == self.layer_size(self.num_layers - 1)
+        po = None
+        if offset is not None:
+            off = np.ascontiguousarray(offset, dtype=np.float32)
+            assert off.size == cf.shape[0]
+            po = off.ctypes.data_as(C.POINTER(C.c_float))
+        out = np.empty((batch, cf.shape[0]), np.float32)
+        self._chk(self._L.gp_bound_outputs(self._h, cf.shape[0], cf.ctypes.data_as(C.POINTER(C.c_float)), po,
+                                           out.ctypes.data_as(C.POINTER(C.c_float))))
+        return out
 
     def profile_enable(self, on=True):
         self._chk(self._L.gp_profile_enable(self._h, 1 if on else 0))

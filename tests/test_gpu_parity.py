@@ -383,3 +383,33 @@ def test_config4_resnet34_sampled_rows():
     lo0, hi0 = ball_box(c, net.eps)
     check_samples_inside(net, g, lo0, hi0, 64, rng, what="resnet34")
     print("resnet34 sampled rows: worst looseness / allowed =", worst)
+
+
+@pytest.mark.parametrize("maker,eps", [(odd_fc, 0.02), (tiny_conv, 0.05), (mid_resnet, 0.005)])
+def test_linear_output_forms(maker, eps):
+    """gp_bound_outputs: lower bounds of arbitrary linear forms of the outputs against the oracle's (never above it
+    beyond rounding, looser by at most the usual bar), below sampled values, and equal to gp_certify on its rows."""
+    net = maker(5)
+    rng = np.random.default_rng(31)
+    X = rng.random((2, net.n_in)).astype(np.float32)
+    g = make_gpu(net)
+    g.analyze_batch(X, eps)
+    n_out = net.n_neurons(net.out_layer)
+    coef = rng.standard_normal((6, n_out)).astype(np.float32)
+    coef[1] = 0.0
+    off = rng.standard_normal(6).astype(np.float32)
+    lb = g.bound_outputs(coef, off, batch=2).astype(np.float64)
+    for b in range(2):
+        o = make_oracle(net)
+        oracle_with_gpu_ties(net, o, g, X[b], eps, batch_index=b)
+        ref = o.bound_outputs(coef.astype(np.float64), off.astype(np.float64))
+        assert np.all(lb[b] <= ref + 2e-6 * (1 + np.abs(ref))), (b, lb[b], ref)
+        assert np.all(ref - lb[b] <= REL_TOL * (1 + np.abs(ref))), (b, lb[b], ref)
+        lo0, hi0 = ball_box(X[b], eps)
+        from helpers import sample_box
+        Y = forward(net, sample_box(lo0, hi0, 500, rng))[net.out_layer]
+        assert np.all(Y @ coef.T.astype(np.float64) + off >= lb[b])
+    label = 2
+    rows = np.array([np.eye(n_out)[label] - np.eye(n_out)[j] for j in range(n_out) if j != label], np.float32)
+    _, margins = g.certify_batch([label, label])
+    assert np.array_equal(g.bound_outputs(rows, batch=2), margins)

@@ -420,3 +420,30 @@ def test_collapsed_and_literal_interval_coefficients():
     # the literal intervals are never tighter (up to noise) and visibly wider at the deep end
     assert all(wb >= wa * (1 - 1e-9) for wa, wb in widths)
     assert widths[-1][1] > widths[-1][0] * (1 + 1e-6), widths[-1]
+
+
+@pytest.mark.parametrize("maker,eps", [(tiny_fc, 0.1), (tiny_conv, 0.05), (tiny_resnet, 0.02)])
+def test_linear_output_forms_against_second_implementation_and_samples(maker, eps):
+    """Lower bounds of arbitrary linear forms of the outputs: equal to the NumPy DeepPoly's to 1e-9, below every
+    sampled value of the form, and equal to the certification margins when the forms are y_label - y_j."""
+    net = maker(17)
+    rng = np.random.default_rng(23)
+    c = rng.random(net.n_in).astype(np.float32)
+    o = make_oracle(net)
+    o.analyze(c, eps)
+    n_out = net.n_neurons(net.out_layer)
+    coef = rng.standard_normal((5, n_out))
+    coef[1] = 0.0
+    coef[2, 1:] = 0.0
+    off = rng.standard_normal(5)
+    lb = o.bound_outputs(coef, off)
+    lo0, hi0 = o.get_bounds(0)
+    ref = np_deeppoly(net, lo0, hi0, extra_rows=coef)["extra"] + off
+    assert np.max(np.abs(lb - ref) / (1 + np.abs(ref))) < 1e-9
+    assert abs(lb[1] - off[1]) < 1e-12                       # the zero form is its offset
+    Y = forward(net, sample_box(lo0, hi0, 2000, rng))[net.out_layer]
+    assert np.all(Y @ coef.T + off >= lb - 1e-12)
+    label = 1
+    rows = np.array([np.eye(n_out)[label] - np.eye(n_out)[j] for j in range(n_out) if j != label])
+    _, margins = o.certify(label)
+    assert np.array_equal(o.bound_outputs(rows), margins)
