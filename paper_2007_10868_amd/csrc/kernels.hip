@@ -734,8 +734,7 @@ __global__ __launch_bounds__(256) void scan_tall_kernel(const ScanParams p) {
 // lanes of different rows read the same LDS words (broadcast).  Rows of a work-group that do not share box and
 // window origin are handled run by run.
 constexpr int SCAN_LDS_MAX = 1024;      // elements per row this kernel takes (40 KB of LDS at most)
-// ROWS per work-group (8 lanes each): 32, or 8 when a launch has so few rows that more, smaller work-groups finish
-// sooner; the grouping does not touch a row's arithmetic.
+// ROWS per work-group (8 lanes each); the grouping does not touch a row's arithmetic.
 // U: row slices (8 lanes x V elements each) whose loads are in flight together.
 template <int V, int ROWS, int U>
 __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) {
@@ -858,15 +857,9 @@ void launch_scan(const ScanParams& p, hipStream_t s) {
         else hipLaunchKernelGGL((scan_tall_kernel<1, 8>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
     } else if (nelem <= SCAN_LDS_MAX) {
         const size_t lds = (size_t)5 * ((nelem + 3) & ~3) * sizeof(double);
-        if (p.nrows >= 4096) {
-            const int wgs = ((p.rm.Rc + 31) / 32) * nhalves;
-            if (vec) hipLaunchKernelGGL((scan_lds_kernel<4, 32, 4>), dim3(wgs), dim3(256), lds, s, p);
-            else hipLaunchKernelGGL((scan_lds_kernel<1, 32, 4>), dim3(wgs), dim3(256), lds, s, p);
-        } else {
-            const int wgs = ((p.rm.Rc + 7) / 8) * nhalves;
-            if (vec) hipLaunchKernelGGL((scan_lds_kernel<4, 8, 4>), dim3(wgs), dim3(64), lds, s, p);
-            else hipLaunchKernelGGL((scan_lds_kernel<1, 8, 4>), dim3(wgs), dim3(64), lds, s, p);
-        }
+        const int wgs = ((p.rm.Rc + 31) / 32) * nhalves;
+        if (vec) hipLaunchKernelGGL((scan_lds_kernel<4, 32, 4>), dim3(wgs), dim3(256), lds, s, p);
+        else hipLaunchKernelGGL((scan_lds_kernel<1, 32, 4>), dim3(wgs), dim3(256), lds, s, p);
     } else if (groups < 2048) {   // fewer waves than the chip holds at once: one row per wave
         const int waves = p.nrows;
         if (vec) hipLaunchKernelGGL((scan_tall_kernel<4, 64>), dim3((waves + 3) / 4), dim3(256), 0, s, p);
