@@ -9,6 +9,7 @@
 #include "kernels.hpp"
 
 #include <math.h>
+#include <type_traits>
 #include <stdlib.h>
 #include <string.h>
 
@@ -113,8 +114,11 @@ __device__ __forceinline__ float relax_factor(double a, float g) {
 // that no row of the tile can use are skipped altogether (Algorithm 1 only visits pairs of a window entry
 // and a tap; a gather over all taps of every output pixel would multiply many structural zeros, most of
 // all for small windows and for strided layers).
-template <int BM, int BN, bool VEC>
-__global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
+// DENSE: the layer is a plain matrix (one tap, 1x1 windows): no tap geometry is kept, which leaves the registers for
+// the software-pipelined K loop at 4 waves per SIMD without spilling.  The general 64x64 kernel is held to 4 waves per
+// SIMD as well (a few values of the tap bookkeeping spill; measured: +3.4 % on the residual net against 3 waves).
+template <int BM, int BN, bool VEC, bool DENSE>
+__global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_kernel(const CrossParams p) {
     constexpr int BK = 16;
     constexpr int LDK = 18;                          // doubles per tile row: 144 B, keeps 16-byte alignment, spreads banks
     constexpr int WAVES_N = (BN >= 64 || BM < 64) ? 2 : 1;
@@ -154,7 +158,7 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
     const int pa = (int)fast_div((uint32_t)pix, p.div_owx), pb = pix - pa * p.owx;
     const int n0 = nt * BN;
     const int Ck = p.in.C, N = p.Co;
-    const int taps = p.kh * p.kw;
+    const int taps = DENSE ? 1 : p.kh * p.kw;
     const int kchunks = (Ck + BK - 1) / BK;
     const uint32_t row_elems = (uint32_t)(p.in.wy * p.in.wx * Ck);
 
@@ -197,6 +201,11 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
     // tap (f,g) written as f = fdiv*sh + fmod, g = gdiv*sw + gmod (all uniform); returns whether any of
     // this thread's rows uses the tap
     auto set_tap = [&](int t) -> bool {
+        if constexpr (DENSE) {
+#pragma unroll
+            for (int i = 0; i < APT; ++i) a_voff[i] = a_ok[i] ? a_rowoff[i] : kOOB;
+            return true;
+        }
         const int f = (int)fast_div((uint32_t)t, p.div_kw), g = t - f * p.kw;
         const int fdiv = (int)fast_div((uint32_t)f, p.div_sh), fmod = f - fdiv * p.sh;
         const int gdiv = (int)fast_div((uint32_t)g, p.div_sw), gmod = g - gdiv * p.sw;
@@ -216,7 +225,7 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
 
     // ---- which taps does this tile need at all?  (bit t of the mask; filters with more than 64 taps keep all)
     unsigned long long tapmask = ~0ull;
-    if (taps > 1 && taps <= 64) {
+    if (!DENSE && taps > 1 && taps <= 64) {
         unsigned long long mine = 0;
         for (int t = 0; t < taps; ++t)
             if (set_tap(t)) mine |= 1ull << t;
@@ -310,51 +319,133 @@ __global__ __launch_bounds__(256) void cross_kernel(const CrossParams p) {
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = double4_t{0.0, 0.0, 0.0, 0.0};
 
-    auto mfma_tile = [&](int buf) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {              // two halves of the lane's 4 k-values: one 16-byte LDS load each
-            double2 av[TM], bv[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-                av[i] = *reinterpret_cast<const double2*>(a_ld + (buf * BM + i * 16) * LDK + 2 * h);
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                bv[j] = *reinterpret_cast<const double2*>(b_ld + (buf * BN + j * 16) * LDK + 2 * h);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    if constexpr (SMALLN) acc[i][j][0] = __builtin_amdgcn_mfma_f64_4x4x4f64(av[i].x, bv[j].x, acc[i][j][0], 0, 0, 0);
-                    else acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[i].x, bv[j].x, acc[i][j], 0, 0, 0);
-                }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    if constexpr (SMALLN) acc[i][j][0] = __builtin_amdgcn_mfma_f64_4x4x4f64(av[i].y, bv[j].y, acc[i][j][0], 0, 0, 0);
-                    else acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[i].y, bv[j].y, acc[i][j], 0, 0, 0);
-                }
-        }
-    };
+    if constexpr (SMALLN) {
+        auto mfma_tile = [&](int buf) {
+    #pragma unroll
+            for (int h = 0; h < 2; ++h) {              // two halves of the lane's 4 k-values: one 16-byte LDS load each
+                double2 av[TM], bv[TN];
+    #pragma unroll
+                for (int i = 0; i < TM; ++i)
+                    av[i] = *reinterpret_cast<const double2*>(a_ld + (buf * BM + i * 16) * LDK + 2 * h);
+    #pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    bv[j] = *reinterpret_cast<const double2*>(b_ld + (buf * BN + j * 16) * LDK + 2 * h);
+    #pragma unroll
+                for (int i = 0; i < TM; ++i)
+    #pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        if constexpr (SMALLN) acc[i][j][0] = __builtin_amdgcn_mfma_f64_4x4x4f64(av[i].x, bv[j].x, acc[i][j][0], 0, 0, 0);
+                        else acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[i].x, bv[j].x, acc[i][j], 0, 0, 0);
+                    }
+    #pragma unroll
+                for (int i = 0; i < TM; ++i)
+    #pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        if constexpr (SMALLN) acc[i][j][0] = __builtin_amdgcn_mfma_f64_4x4x4f64(av[i].y, bv[j].y, acc[i][j][0], 0, 0, 0);
+                        else acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[i].y, bv[j].y, acc[i][j], 0, 0, 0);
+                    }
+            }
+        };
 
-    if (nIt > 0) {
-        load_tiles();
-        store_tiles(0);
-        __syncthreads();
-        // two K steps per trip so that the LDS buffer index is a compile-time constant
-        int it = 0;
-        for (; it + 2 <= nIt; it += 2) {
-            load_tiles();                  // tile it+1 (exists)
-            mfma_tile(0);
-            store_tiles(1);
+        if (nIt > 0) {
+            load_tiles();
+            store_tiles(0);
             __syncthreads();
-            const bool more = it + 2 < nIt;
-            if (more) load_tiles();        // tile it+2
-            mfma_tile(1);
-            if (more) store_tiles(0);
-            __syncthreads();
+            // two K steps per trip so that the LDS buffer index is a compile-time constant
+            int it = 0;
+            for (; it + 2 <= nIt; it += 2) {
+                load_tiles();                  // tile it+1 (exists)
+                mfma_tile(0);
+                store_tiles(1);
+                __syncthreads();
+                const bool more = it + 2 < nIt;
+                if (more) load_tiles();        // tile it+2
+                mfma_tile(1);
+                if (more) store_tiles(0);
+                __syncthreads();
+            }
+            if (it < nIt) mfma_tile(0);
         }
-        if (it < nIt) mfma_tile(0);
+    } else {
+        // MFMA operand fragments of one K step: [half of the lane's 4 k-values][16-row tile], two sets so that the next
+        // step's fragments are fetched from LDS while the MFMAs of the current step run
+        double2 av[2][2][TM], bv[2][2][TN];
+        auto read_frags = [&](auto set_c, int buf) {
+            constexpr int set = decltype(set_c)::value;
+    #pragma unroll
+            for (int h = 0; h < 2; ++h) {
+    #pragma unroll
+                for (int i = 0; i < TM; ++i)
+                    av[set][h][i] = *reinterpret_cast<const double2*>(a_ld + (buf * BM + i * 16) * LDK + 2 * h);
+    #pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    bv[set][h][j] = *reinterpret_cast<const double2*>(b_ld + (buf * BN + j * 16) * LDK + 2 * h);
+            }
+        };
+        // quarter q of a step's 16 MFMAs: k-value q of each lane's four (halves h = q/2, component q%2)
+        auto mfma_q = [&](auto set_c, auto q_c) {
+            constexpr int set = decltype(set_c)::value, q = decltype(q_c)::value, h = q >> 1;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const double a = (q & 1) ? av[set][h][i].y : av[set][h][i].x;
+                    const double b = (q & 1) ? bv[set][h][j].y : bv[set][h][j].x;
+                    acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc[i][j], 0, 0, 0);
+                }
+        };
+        using Q0 = std::integral_constant<int, 0>;
+        using Q1 = std::integral_constant<int, 1>;
+        using Q2 = std::integral_constant<int, 2>;
+        using Q3 = std::integral_constant<int, 3>;
+        auto mfma_head = [&](auto set_c) {       // the MFMAs issued before the LDS write of the step (the split point
+            mfma_q(set_c, Q0{});                 // makes no measurable difference: 4, 8 or 12 of the 16)
+            mfma_q(set_c, Q1{});
+        };
+        auto mfma_tail = [&](auto set_c) {
+            mfma_q(set_c, Q2{});
+            mfma_q(set_c, Q3{});
+        };
+        using C0 = std::integral_constant<int, 0>;
+        using C1 = std::integral_constant<int, 1>;
+
+        // Software pipeline over the K steps (tiles t = 0..nIt-1).  Per step, in program order: convert and write tile
+        // t+2 into the LDS buffer whose tile was turned into fragments one step ago; fetch the fragments of tile t+1;
+        // issue the global loads of tile t+3; then the MFMAs of tile t; one barrier.  The LDS and global latencies of
+        // the coming tiles pass while the MFMAs of the current one run, and nothing but the barrier stands between the
+        // MFMA phases of consecutive steps.
+        if (nIt > 0) {
+            load_tiles();                          // tile 0
+            store_tiles(0);
+            if (nIt > 1) load_tiles();             // tile 1
+            __syncthreads();
+            read_frags(C0{}, 0);
+            if (nIt > 1) store_tiles(1);
+            if (nIt > 2) load_tiles();             // tile 2
+            __syncthreads();
+            int t = 0;
+            for (; t + 2 <= nIt; t += 2) {
+                read_frags(C1{}, 1);                       // tile t+1
+                mfma_head(C0{});                           // tile t, first part
+                __builtin_amdgcn_sched_barrier(0);
+                if (t + 2 < nIt) store_tiles(0);           // tile t+2 (its loads were issued a step ago)
+                if (t + 3 < nIt) load_tiles();             // tile t+3
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_tail(C0{});                           // tile t, the rest
+                __builtin_amdgcn_sched_barrier(0);         // keep the barrier (and its wait for the LDS traffic) behind the MFMAs
+                __syncthreads();
+                if (t + 2 < nIt) read_frags(C0{}, 0);      // tile t+2
+                mfma_head(C1{});                           // tile t+1
+                __builtin_amdgcn_sched_barrier(0);
+                if (t + 3 < nIt) store_tiles(1);           // tile t+3
+                if (t + 4 < nIt) load_tiles();             // tile t+4
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_tail(C1{});
+                __builtin_amdgcn_sched_barrier(0);
+                __syncthreads();
+            }
+            if (t < nIt) { mfma_head(C0{}); mfma_tail(C0{}); }   // odd number of tiles: the last one
+        }
     }
 
     // ---- epilogue: (+ residual addend) (* ReLU substitution of the destination layer) -> one rounding to
@@ -406,8 +497,17 @@ static void launch_cross_t(const CrossParams& p0, hipStream_t s) {
     const long long total = (long long)p.ntiles_m * p.ntiles_n * p.owy * p.owx;
     const unsigned blocks = (unsigned)(((total + 7) / 8) * 8);
     const bool vec = (p.in.C & 3) == 0;
-    if (vec) hipLaunchKernelGGL((cross_kernel<BM, BN, true>), dim3(blocks), dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((cross_kernel<BM, BN, false>), dim3(blocks), dim3(256), 0, s, p);
+    if constexpr (BN >= 32 && BM <= 64) {
+        const bool dense = p.kh * p.kw == 1 && p.in.wy * p.in.wx == 1 && p.owy * p.owx == 1 && p.sh == 1 && p.sw == 1 &&
+                           p.ph == 0 && p.pw == 0;
+        if (dense) {
+            if (vec) hipLaunchKernelGGL((cross_kernel<BM, BN, true, true>), dim3(blocks), dim3(256), 0, s, p);
+            else hipLaunchKernelGGL((cross_kernel<BM, BN, false, true>), dim3(blocks), dim3(256), 0, s, p);
+            return;
+        }
+    }
+    if (vec) hipLaunchKernelGGL((cross_kernel<BM, BN, true, false>), dim3(blocks), dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((cross_kernel<BM, BN, false, false>), dim3(blocks), dim3(256), 0, s, p);
 }
 
 void launch_cross(const CrossParams& p, hipStream_t s) {
