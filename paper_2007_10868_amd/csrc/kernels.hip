@@ -984,6 +984,23 @@ __global__ __launch_bounds__(256) void init_kernel(const InitParams p) {
     if (r >= p.nrows) return;
     const RowInfo ri = row_info(p.rm, r);
     float* out = p.out + (size_t)r * p.nelem;
+    if (p.mode == 2 && p.dense && (p.nelem & 3) == 0) {
+        // rows of a dense layer's matrix: four coefficients per lane (16-byte loads and stores)
+        const float* w = p.wt + (size_t)ri.cs * p.nelem;
+        const float* g = p.out_grl ? p.out_grl + (size_t)ri.b * p.nelem : nullptr;
+        for (int e = (blockIdx.y * 64 + (threadIdx.x & 63)) * 4; e < p.nelem; e += gridDim.y * 256) {
+            const float4 wv = *reinterpret_cast<const float4*>(w + e);
+            float v[4] = {ri.sign * wv.x, ri.sign * wv.y, ri.sign * wv.z, ri.sign * wv.w};
+            if (g) {
+                const float4 gv = *reinterpret_cast<const float4*>(g + e);
+                const float gg[4] = {gv.x, gv.y, gv.z, gv.w};
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    if (v[k] != 0.f) v[k] = (float)((double)v[k] * (double)relax_factor((double)v[k], gg[k]));
+            }
+            *reinterpret_cast<float4*>(out + e) = make_float4(v[0], v[1], v[2], v[3]);
+        }
+    } else
     for (int e = blockIdx.y * 64 + (threadIdx.x & 63); e < p.nelem; e += gridDim.y * 64) {
         float v = 0.f;
         if (p.mode == 0) {
@@ -1029,7 +1046,8 @@ __global__ __launch_bounds__(256) void init_kernel(const InitParams p) {
 
 void launch_init(const InitParams& p, hipStream_t s) {
     if (p.nrows <= 0 || p.nelem <= 0) return;
-    const int ychunks = (int)fmin((double)((p.nelem + 63) / 64), 64.0);
+    const int per = (p.mode == 2 && p.dense && (p.nelem & 3) == 0) ? p.nelem / 4 : p.nelem;   // items per row
+    const int ychunks = (int)fmin((double)((per + 63) / 64), 64.0);
     hipLaunchKernelGGL(init_kernel, dim3((p.nrows + 3) / 4, ychunks), dim3(256), 0, s, p);
 }
 
