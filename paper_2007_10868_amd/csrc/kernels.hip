@@ -294,7 +294,34 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
     double* const b_st = &Bs[0][ld_row][q4];
     const double* const a_ld = &As[0][wm * WTM + lm][4 * lk];
     const double* const b_ld = &Bs[0][SMALLN ? (lm & 3) : (wn * WTN + lm)][4 * lk];
-    auto store_tiles = [&](int buf) {
+    // Last K step of a dense layer whose channel count is no multiple of 16 (e.g. 500 = 31*16 + 4): only tail_q of
+    // the 4 channel quads exist.  Stored as usual they would sit in k-positions 0..4*tail_q-1, one in each of the 4
+    // MFMA steps of the tile; stored transposed (channel j of quad q at k-position 4*j + q, for A and B alike) quad q
+    // falls entirely into MFMA step q, and the steps >= tail_q, which would multiply zeros, are left out.
+    const int tail_q = (DENSE && VEC && !SMALLN && (Ck & 15)) ? ((Ck & 15) >> 2) : 0;
+    auto store_tiles = [&](int buf, bool tail = false) {
+        if (tail) {                                                 // uniform
+            const int q = tid & 3;
+            if (q < tail_q) {
+#pragma unroll
+                for (int i = 0; i < APT; ++i) {
+                    if (ld_row + 64 * i < BM) {
+                        double* dst = &As[0][ld_row][0] + (buf * BM + 64 * i) * LDK + q;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) dst[4 * j] = (double)a_raw[i].v[j];
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < BPT; ++i) {
+                    if (ld_row + 64 * i < BN) {
+                        double* dst = &Bs[0][ld_row][0] + (buf * BN + 64 * i) * LDK + q;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) dst[4 * j] = (double)b_raw[i].v[j];
+                    }
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < APT; ++i) {
             if (ld_row + 64 * i < BM) {
@@ -398,53 +425,57 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
         using Q1 = std::integral_constant<int, 1>;
         using Q2 = std::integral_constant<int, 2>;
         using Q3 = std::integral_constant<int, 3>;
-        auto mfma_head = [&](auto set_c) {       // the MFMAs issued before the LDS write of the step (the split point
-            mfma_q(set_c, Q0{});                 // makes no measurable difference: 4, 8 or 12 of the 16)
-            mfma_q(set_c, Q1{});
+        // qlim: MFMA steps of the tile that hold data (4, or tail_q for the transposed last tile)
+        auto mfma_head = [&](auto set_c, int qlim) {   // the MFMAs issued before the LDS write of the step (the split
+            mfma_q(set_c, Q0{});                       // point makes no measurable difference: 4, 8 or 12 of the 16)
+            if (qlim > 1) mfma_q(set_c, Q1{});
         };
-        auto mfma_tail = [&](auto set_c) {
-            mfma_q(set_c, Q2{});
-            mfma_q(set_c, Q3{});
+        auto mfma_tail = [&](auto set_c, int qlim) {
+            if (qlim > 2) mfma_q(set_c, Q2{});
+            if (qlim > 3) mfma_q(set_c, Q3{});
         };
         using C0 = std::integral_constant<int, 0>;
         using C1 = std::integral_constant<int, 1>;
+        const int last = nIt - 1;
+        const int qlast = tail_q ? tail_q : 4;
 
-        // Software pipeline over the K steps (tiles t = 0..nIt-1).  Per step, in program order: convert and write tile
-        // t+2 into the LDS buffer whose tile was turned into fragments one step ago; fetch the fragments of tile t+1;
-        // issue the global loads of tile t+3; then the MFMAs of tile t; one barrier.  The LDS and global latencies of
-        // the coming tiles pass while the MFMAs of the current one run, and nothing but the barrier stands between the
-        // MFMA phases of consecutive steps.
+        // Software pipeline over the K steps (tiles t = 0..nIt-1).  Per step, in program order: fetch the fragments
+        // of tile t+1 from LDS; half of the MFMAs of tile t; convert and write tile t+2 into the LDS buffer whose
+        // tile was turned into fragments one step ago; issue the global loads of tile t+3; the other MFMAs of tile
+        // t; one barrier.  The LDS and global latencies of the coming tiles pass while the MFMAs of the current one
+        // run, and nothing but the barrier stands between the MFMA phases of consecutive steps.
         if (nIt > 0) {
             load_tiles();                          // tile 0
-            store_tiles(0);
+            store_tiles(0, tail_q && last == 0);
             if (nIt > 1) load_tiles();             // tile 1
             __syncthreads();
             read_frags(C0{}, 0);
-            if (nIt > 1) store_tiles(1);
+            if (nIt > 1) store_tiles(1, tail_q && last == 1);
             if (nIt > 2) load_tiles();             // tile 2
             __syncthreads();
             int t = 0;
             for (; t + 2 <= nIt; t += 2) {
                 read_frags(C1{}, 1);                       // tile t+1
-                mfma_head(C0{});                           // tile t, first part
+                mfma_head(C0{}, 4);                        // tile t (never the last one here), first part
                 __builtin_amdgcn_sched_barrier(0);
-                if (t + 2 < nIt) store_tiles(0);           // tile t+2 (its loads were issued a step ago)
+                if (t + 2 < nIt) store_tiles(0, tail_q && t + 2 == last);   // tile t+2 (its loads were issued a step ago)
                 if (t + 3 < nIt) load_tiles();             // tile t+3
                 __builtin_amdgcn_sched_barrier(0);
-                mfma_tail(C0{});                           // tile t, the rest
+                mfma_tail(C0{}, 4);                        // tile t, the rest
                 __builtin_amdgcn_sched_barrier(0);         // keep the barrier (and its wait for the LDS traffic) behind the MFMAs
                 __syncthreads();
+                const int q1 = (t + 1 == last) ? qlast : 4;
                 if (t + 2 < nIt) read_frags(C0{}, 0);      // tile t+2
-                mfma_head(C1{});                           // tile t+1
+                mfma_head(C1{}, q1);                       // tile t+1
                 __builtin_amdgcn_sched_barrier(0);
-                if (t + 3 < nIt) store_tiles(1);           // tile t+3
+                if (t + 3 < nIt) store_tiles(1, tail_q && t + 3 == last);   // tile t+3
                 if (t + 4 < nIt) load_tiles();             // tile t+4
                 __builtin_amdgcn_sched_barrier(0);
-                mfma_tail(C1{});
+                mfma_tail(C1{}, q1);
                 __builtin_amdgcn_sched_barrier(0);
                 __syncthreads();
             }
-            if (t < nIt) { mfma_head(C0{}); mfma_tail(C0{}); }   // odd number of tiles: the last one
+            if (t < nIt) { mfma_head(C0{}, qlast); mfma_tail(C0{}, qlast); }   // odd number of tiles: the last one
         }
     }
 

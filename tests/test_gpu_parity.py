@@ -33,6 +33,10 @@ def odd_fc(seed=0):          # widths that are no multiple of 4: scalar load pat
     return wl.fc_net("odd_fc", [37, 101, 19], n_in=23, n_out=7, seed=seed)
 
 
+def quad_fc(seed=0):         # widths = 4, 8, 12 (mod 16): every length of the transposed last K tile of dense layers
+    return wl.fc_net("quad_fc", [24, 28, 40, 20, 52], n_in=36, n_out=8, seed=seed)
+
+
 def tiny_conv(seed=0):       # channel counts 2,3,4: unaligned paths; stride 2 with an even kernel
     return wl.conv_net("tiny_conv", (2, 6, 6), [(3, 3, 1, 1), (4, 4, 2, 1)], [8], n_out=3, seed=seed)
 
@@ -116,7 +120,7 @@ def test_mfma_f64_error_model(cols):
     print("worst |err|/sum|terms| =", worst)
 
 
-@pytest.mark.parametrize("maker,eps", [(tiny_fc, 0.1), (odd_fc, 0.05), (tiny_conv, 0.05), (pad0_conv, 0.03),
+@pytest.mark.parametrize("maker,eps", [(tiny_fc, 0.1), (odd_fc, 0.05), (quad_fc, 0.03), (tiny_conv, 0.05), (pad0_conv, 0.03),
                                        (tiny_resnet, 0.02), (mid_resnet, 0.01), (rect_conv, 0.04)])
 def test_small_networks_match_oracle_and_contain_samples(maker, eps):
     net = maker(1)
