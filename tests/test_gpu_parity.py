@@ -188,6 +188,37 @@ def test_config1_fc9x500_single_and_batched():
     compare_layer(lo, hi, olo, ohi, "fc9x500 device centres")
 
 
+def test_config1_in_the_benchmark_launch_configuration():
+    """The workload exactly as bench.py times it: all 100 inputs of FC 9x500 in one batched pass, centres resident on
+    the device, workspace from a torch tensor sized the way bench.py sizes it.  Full oracle parity on three of the
+    inputs, bit-equality with a single-input pass, sampled outputs for every tenth input."""
+    net = wl.config(1)
+    batch = net.n_inputs
+    g = make_gpu(net)
+    centers = np.stack([net.center(j) for j in range(batch)])
+    t = torch.tensor(centers, device="cuda")
+    g.set_stream(torch.cuda.current_stream())
+    _, full = g.workspace_size(batch)
+    free, _ = torch.cuda.mem_get_info()
+    ws = torch.empty(int(min(full, free * 0.6)), dtype=torch.uint8, device="cuda")
+    g.set_workspace(ws)
+    g.analyze_batch_dev(t, net.eps)
+    o = make_oracle(net)
+    for b in (0, 57, 99):
+        oracle_with_gpu_ties(net, o, g, centers[b], net.eps, batch_index=b)
+        compare_all(net, g, o, batch_index=b, what=f"fc9x500 x100, input {b}")
+    rng = np.random.default_rng(3)
+    for b in range(0, batch, 10):
+        lo0, hi0 = ball_box(centers[b], net.eps)
+        check_samples_inside(net, g, lo0, hi0, 200, rng, batch_index=b, what=f"fc9x500 x100, input {b}")
+    batched = {l: g.get_bounds_f64(l, 57) for l in analysed_layers(net)}
+    g1 = make_gpu(net)
+    g1.analyze(centers[57], net.eps)
+    for l in analysed_layers(net):
+        lo, hi = g1.get_bounds_f64(l)
+        assert np.array_equal(lo, batched[l][0]) and np.array_equal(hi, batched[l][1]), l
+
+
 def test_config2_small_conv():
     net = wl.config(2)
     g = make_gpu(net)
