@@ -32,8 +32,17 @@ def make_gpu(net: wl.Net):
 
 
 def make_oracle(net: wl.Net, **opts):
+    """The oracle with the same set of bounded layers as the GPU library: the paper bounds the inputs of ReLU layers
+    and the last layer; the library also bounds every layer that an affine layer reads (it needs their intervals for
+    its rounding slack), which matters only where two affine layers follow each other without a ReLU.  Those layers
+    are marked in the oracle as explicitly requested, so that both sides take the same candidates."""
     o = OracleNet(*net.input_shape)
     wl.build_into(net, o)
+    for L in net.layers:
+        if L["type"] in ("dense", "conv"):
+            src = L["src"]
+            if src > 0 and net.layers[src - 1]["type"] != "relu":
+                o.request_bounds(src)
     if opts:
         o.set_options(**opts)
     return o
