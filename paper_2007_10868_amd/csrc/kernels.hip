@@ -105,9 +105,10 @@ __device__ __forceinline__ float relax_factor(double a, float g) {
 //   uses value j in MFMA step j, i.e. step j contracts the channel set {j, 4+j, 8+j, 12+j}.  A and B use
 //   the same permutation, so every product pairs the right channels; only the summation order differs,
 //   which the rounding slack covers for any order.
-//   The MFMA pipe and the vector ALU share the issue port, so everything outside the MFMAs is kept to a
-//   few instructions per K step: 32-bit offsets into per-tile buffer resources, range-checked loads
-//   instead of masks, tap geometry without divisions.
+//   Vector instructions do not overlap float64 MFMAs on this chip (each costs 4-6 cycles of MFMA time), so
+//   everything outside the MFMAs is kept to a few instructions per K step: 32-bit offsets into per-tile buffer
+//   resources, range-checked loads instead of masks, tap geometry without divisions.
+//   The K loop is software-pipelined (see the loop itself); tiles of 4 columns use the 4x4x4 instruction.
 // Work decomposition: a work-group = (tile of BM rows, output pixel of the window, tile of BN input
 // channels).  All rows of a work-group therefore produce the SAME window pixel, so the filter taps
 // that can reach that pixel from inside the rows' windows are (nearly) the same for all of them: the taps
@@ -347,33 +348,24 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
         for (int j = 0; j < TN; ++j) acc[i][j] = double4_t{0.0, 0.0, 0.0, 0.0};
 
     if constexpr (SMALLN) {
+        // 4-column tiles: the step onto the image is bound by how fast the L2 delivers the re-read window entries, not
+        // by the matrix pipe, so the plain order is kept: load the next tile, MFMAs of the current one, write, barrier
         auto mfma_tile = [&](int buf) {
-    #pragma unroll
-            for (int h = 0; h < 2; ++h) {              // two halves of the lane's 4 k-values: one 16-byte LDS load each
-                double2 av[TM], bv[TN];
-    #pragma unroll
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {          // two halves of the lane's 4 k-values: one 16-byte LDS load each
+                double2 av[TM], bv;
+#pragma unroll
                 for (int i = 0; i < TM; ++i)
                     av[i] = *reinterpret_cast<const double2*>(a_ld + (buf * BM + i * 16) * LDK + 2 * h);
-    #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    bv[j] = *reinterpret_cast<const double2*>(b_ld + (buf * BN + j * 16) * LDK + 2 * h);
-    #pragma unroll
+                bv = *reinterpret_cast<const double2*>(b_ld + (buf * BN) * LDK + 2 * h);
+#pragma unroll
                 for (int i = 0; i < TM; ++i)
-    #pragma unroll
-                    for (int j = 0; j < TN; ++j) {
-                        if constexpr (SMALLN) acc[i][j][0] = __builtin_amdgcn_mfma_f64_4x4x4f64(av[i].x, bv[j].x, acc[i][j][0], 0, 0, 0);
-                        else acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[i].x, bv[j].x, acc[i][j], 0, 0, 0);
-                    }
-    #pragma unroll
+                    acc[i][0][0] = __builtin_amdgcn_mfma_f64_4x4x4f64(av[i].x, bv.x, acc[i][0][0], 0, 0, 0);
+#pragma unroll
                 for (int i = 0; i < TM; ++i)
-    #pragma unroll
-                    for (int j = 0; j < TN; ++j) {
-                        if constexpr (SMALLN) acc[i][j][0] = __builtin_amdgcn_mfma_f64_4x4x4f64(av[i].y, bv[j].y, acc[i][j][0], 0, 0, 0);
-                        else acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[i].y, bv[j].y, acc[i][j], 0, 0, 0);
-                    }
+                    acc[i][0][0] = __builtin_amdgcn_mfma_f64_4x4x4f64(av[i].y, bv.y, acc[i][0][0], 0, 0, 0);
             }
         };
-
         if (nIt > 0) {
             load_tiles();
             store_tiles(0);
@@ -567,8 +559,8 @@ void launch_cross(const CrossParams& p, hipStream_t s) {
 // over the ReLU's INPUT; the candidate over the ReLU's OUTPUT interval [L,U] that DeepPoly takes before
 // the substitution is recovered as M*U = m*(U/slope) =: m*rho and M*L = m*L (L = 0 unless the neuron is
 // stably active, where lam = 1), and the intercept term M*del = m*(del/slope) =: m*kap.
-// A work-group handles SCAN_ROWS rows: one wave per row for short rows, all four waves on one row
-// for long ones.
+// Three kernels share this arithmetic (scan_term, scan_finish) and differ in how rows and lanes are laid out; which
+// one runs is decided by the row length (and, for long rows, by the size of the launch), see launch_scan.
 // ------------------------------------------------------------------------------------------------
 // Sum of 8 per-lane values over the 64 lanes of a wave, all 8 at once: every butterfly step halves the
 // number of values a lane carries, so 8 values cost 10 exchanges instead of 48.  On return v[0] of lane l
