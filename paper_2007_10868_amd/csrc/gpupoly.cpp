@@ -471,8 +471,10 @@ long long align_up(long long v, long long a) { return (v + a - 1) / a * a; }
 
 // bytes one task (both signs) needs for this plan
 long long task_bytes(const Plan& pl, int nsign) {
-    // blocks; constant, slack (twice: rows are moved when tasks are removed), best; row lists and flags
-    return (long long)nsign * (pl.n_slots * align_up(pl.slot_elems * 4, 16) + 5 * 8) + 16;
+    // blocks; constant, slack (twice: rows are moved when tasks are removed), best; row lists and flags; chunk sums of
+    // the scan of long rows (5 doubles per 512 coefficients)
+    const long long chunks = pl.slot_elems > 1024 ? (pl.slot_elems + 511) / 512 : 0;
+    return (long long)nsign * (pl.n_slots * align_up(pl.slot_elems * 4, 16) + 5 * 8 + chunks * 40) + 16;
 }
 
 gp_status get_workspace(gp_net* net, long long want, char** ws, long long* bytes) {
@@ -529,9 +531,9 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
     const bool may_stop = early && ls.feeds_relu && !ls.req_bounds && start != (int)net->L.size() - 1;
     const long long tb = task_bytes(pl, nsign);
     char* ws; long long ws_bytes;
-    gp_status st = get_workspace(net, tb * total + 8192, &ws, &ws_bytes);
+    gp_status st = get_workspace(net, tb * total + 16384, &ws, &ws_bytes);
     if (st != GP_OK) return st;
-    long long Rc_max = (ws_bytes - 8192) / tb;
+    long long Rc_max = (ws_bytes - 16384) / tb;
     if (total >= (1LL << 31)) return fail(net, GP_ERR_SHAPE, "batch * layer size must stay below 2^31");
     // rows * window pixels of any step must stay below 2^31 (32-bit indexing in the kernels)
     long long max_pix = 1;
@@ -553,7 +555,9 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
     int* d_wg = d_sel + Rc_max;
     const long long nwg_max = (Rc_max + 255) / 256 + 1;
     unsigned char* d_done[2] = {(unsigned char*)(d_wg + nwg_max), (unsigned char*)(d_wg + nwg_max) + Rc_max};
-    char* slots0 = ws + align_up((d_done[1] + Rc_max) - (unsigned char*)ws, 256);
+    const long long chunks_max = pl.slot_elems > 1024 ? (pl.slot_elems + 511) / 512 : 0;
+    double* d_partial = (double*)(ws + align_up((d_done[1] + Rc_max) - (unsigned char*)ws, 256));
+    char* slots0 = (char*)d_partial + align_up(nrows_max * chunks_max * 40, 256);
     const long long slot_bytes = align_up(nrows_max * pl.slot_elems * 4, 256);
     if (slots0 + slot_bytes * pl.n_slots > ws + ws_bytes) return fail(net, GP_ERR_WORKSPACE, "workspace layout overflow");
 
@@ -726,6 +730,7 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                 sp.update_best = op.update_best ? 1 : 0;
                 sp.c = d_c; sp.err = d_err; sp.best = d_best;
                 sp.done = may_stop ? d_done[cur] : nullptr;
+                sp.partial = chunks_max ? d_partial : nullptr;
                 prof_mark(net, 1, false);
                 gp::launch_scan(sp, net->stream);
                 prof_mark(net, 1, true);
@@ -1121,8 +1126,8 @@ gp_status gp_workspace_size(const gp_net* cnet, int32_t batch, int64_t* min_byte
         st = get_plan(net, (int)i, &pl);
         if (st != GP_OK) return st;
         long long tb = task_bytes(*pl, 2);
-        mn = std::max(mn, tb + 8192);
-        full = std::max(full, tb * net->L[i].n * batch + 8192);
+        mn = std::max(mn, tb + 16384);
+        full = std::max(full, tb * net->L[i].n * batch + 16384);
     }
     *min_bytes = mn;
     *full_bytes = full;

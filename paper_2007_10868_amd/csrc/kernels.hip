@@ -559,34 +559,9 @@ void launch_cross(const CrossParams& p, hipStream_t s) {
 // over the ReLU's INPUT; the candidate over the ReLU's OUTPUT interval [L,U] that DeepPoly takes before
 // the substitution is recovered as M*U = m*(U/slope) =: m*rho and M*L = m*L (L = 0 unless the neuron is
 // stably active, where lam = 1), and the intercept term M*del = m*(del/slope) =: m*kap.
-// Three kernels share this arithmetic (scan_term, scan_finish) and differ in how rows and lanes are laid out; which
-// one runs is decided by the row length (and, for long rows, by the size of the launch), see launch_scan.
+// The kernels share this arithmetic (scan_term, scan_finish) and differ in how rows and lanes are laid out; which one
+// runs is decided by the row length alone, see launch_scan.
 // ------------------------------------------------------------------------------------------------
-// Sum of 8 per-lane values over the 64 lanes of a wave, all 8 at once: every butterfly step halves the
-// number of values a lane carries, so 8 values cost 10 exchanges instead of 48.  On return v[0] of lane l
-// holds the wave total of input value l>>3.
-__device__ __forceinline__ double wave_sum8(double (&v)[8], int lane) {
-    const bool b5 = (lane & 32) != 0, b4 = (lane & 16) != 0, b3 = (lane & 8) != 0;
-    double w[4];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        double keep = b5 ? v[k + 4] : v[k], send = b5 ? v[k] : v[k + 4];
-        w[k] = keep + __shfl_xor(send, 32, 64);
-    }
-    double x[2];
-#pragma unroll
-    for (int k = 0; k < 2; ++k) {
-        double keep = b4 ? w[k + 2] : w[k], send = b4 ? w[k] : w[k + 2];
-        x[k] = keep + __shfl_xor(send, 16, 64);
-    }
-    double keep = b3 ? x[1] : x[0], send = b3 ? x[0] : x[1];
-    double y = keep + __shfl_xor(send, 8, 64);
-    y += __shfl_xor(y, 4, 64);
-    y += __shfl_xor(y, 2, 64);
-    y += __shfl_xor(y, 1, 64);
-    return y;
-}
-
 // One coefficient's contribution to the five per-row sums.  Written with explicit fused multiply-adds only, so that
 // every scan kernel performs exactly the same operations in the same order per lane and a row's result does not
 // depend on which kernel (i.e. on how many rows share the launch) handled it.
@@ -660,128 +635,11 @@ __device__ __forceinline__ void scan_finish(const ScanParams& p, int r, int nele
     p.err[r] = err;
 }
 
-constexpr int SCAN_G = 8;     // rows per wave
+constexpr int SCAN_G = 8;     // rows per wave of the 8-lanes-per-row layout
 
-// One wave scans SCAN_G consecutive rows.  Rows of a group normally belong to the same box and sit at the
-// same position (they differ in channel only), so the per-neuron constants are fetched once per element
-// and reused for all rows of the group; otherwise each row fetches its own.  V = elements per lane and
-// step (4 when the channel count allows 16-byte loads).
-template <int V>
-__global__ __launch_bounds__(256) void scan_kernel(const ScanParams p) {
-    const int tid = threadIdx.x, lane = tid & 63;
-    const BlockDesc& B = p.blk;
-    const int groups_per_half = (p.rm.Rc + SCAN_G - 1) / SCAN_G;
-    const int gidx = blockIdx.x * 4 + (tid >> 6);
-    const int nhalves = p.nrows / p.rm.Rc;                 // 1 or 2
-    if (gidx >= groups_per_half * nhalves) return;          // whole wave leaves; no barrier below
-    const int half = gidx / groups_per_half;
-    const int rr0 = (gidx - half * groups_per_half) * SCAN_G;   // first row of the group inside its half
-    const int nvalid = min(SCAN_G, p.rm.Rc - rr0);
-    const int r0 = half * p.rm.Rc + rr0;
-    const int nelem = B.wy * B.wx * B.C;
-    const bool full_row = (B.wx == B.W);                   // window rows are contiguous in the layer
-
-    // box and window origin of every row of the group; consecutive rows that agree in all three form a run
-    int rb[SCAN_G], roy[SCAN_G], rox[SCAN_G];
-#pragma unroll
-    for (int k = 0; k < SCAN_G; ++k) {
-        const RowInfo rk = row_info(p.rm, r0 + (k < nvalid ? k : 0));
-        rb[k] = rk.b;
-        roy[k] = clampi(B.Sy * rk.ys - B.Py, 0, B.H - B.wy);
-        rox[k] = clampi(B.Sx * rk.xs - B.Px, 0, B.W - B.wx);
-    }
-
-    double cand[SCAN_G], absx[SCAN_G], cst[SCAN_G], cstabs[SCAN_G], s1[SCAN_G];
-#pragma unroll
-    for (int k = 0; k < SCAN_G; ++k) cand[k] = absx[k] = cst[k] = cstabs[k] = s1[k] = 0.0;
-
-    // neuron index of block element e (a multiple of V; the V elements are consecutive channels of one pixel)
-    auto neuron = [&](int e, int oy, int ox, long long bbase, int& c) -> long long {
-        if (full_row) {
-            c = e % B.C;
-            return bbase + (long long)oy * B.W * B.C + e;
-        }
-        int pix = e / B.C;
-        c = e - pix * B.C;
-        int a = pix / B.wx, bb = pix - a * B.wx;
-        return bbase + ((long long)((oy + a) * B.W + (ox + bb)) * B.C + c);
-    };
-    struct Consts {
-        double cp[V], cn[V], X[V], kp[V], be[V];
-    };
-    auto constants = [&](long long j, int c, Consts& q) {
-#pragma unroll
-        for (int v = 0; v < V; ++v) {
-            q.cp[v] = q.cn[v] = q.X[v] = q.kp[v] = q.be[v] = 0.0;
-            if (p.cpos) {
-                q.cp[v] = p.cpos[j + v];
-                q.cn[v] = p.cneg[j + v];
-                q.X[v] = fmax(fabs(p.xlo[j + v]), fabs(p.xhi[j + v]));
-            }
-            if (p.do_consts) {
-                if (p.kap) q.kp[v] = p.kap[j + v];
-                if (p.beff) q.be[v] = p.beff[c + v];
-            }
-        }
-    };
-    auto accumulate = [&](int k, const float (&mf)[V], const Consts& q) {
-#pragma unroll
-        for (int v = 0; v < V; ++v)
-            scan_term(p.cpos != nullptr, p.do_consts != 0, mf[v], q.cp[v], q.cn[v], q.X[v], q.kp[v], q.be[v], cand[k], absx[k],
-                      cst[k], cstabs[k], s1[k]);
-    };
-    auto load_m = [&](const float* src, float (&mf)[V]) {
-        if (V == 4) {
-            float4 t = *reinterpret_cast<const float4*>(src);
-            mf[0] = t.x; mf[1 % V] = t.y; mf[2 % V] = t.z; mf[3 % V] = t.w;
-        } else {
-            mf[0] = src[0];
-        }
-    };
-
-    const float* src0 = B.data + (size_t)r0 * nelem;
-    // one pass over the block per run: the constants are fetched once per element and serve all rows of the run
-    // (normally the whole group is one run; after rows have been removed a group can straddle positions)
-    int k0 = 0;
-    while (k0 < nvalid) {
-        int k1 = k0 + 1;
-#pragma unroll
-        for (int k = 1; k < SCAN_G; ++k)
-            if (k == k1 && k < nvalid && rb[k] == rb[k - 1] && roy[k] == roy[k - 1] && rox[k] == rox[k - 1]) ++k1;
-        int b0 = 0, oy0 = 0, ox0 = 0;
-#pragma unroll
-        for (int k = 0; k < SCAN_G; ++k)
-            if (k == k0) { b0 = rb[k]; oy0 = roy[k]; ox0 = rox[k]; }
-        const long long bbase = (long long)b0 * p.batch_stride;
-        for (int e = lane * V; e < nelem; e += 64 * V) {
-            float mf[SCAN_G][V];
-#pragma unroll
-            for (int k = 0; k < SCAN_G; ++k)
-                if (k >= k0 && k < k1) load_m(src0 + (size_t)k * nelem + e, mf[k]);
-            int c;
-            const long long j = neuron(e, oy0, ox0, bbase, c);
-            Consts q;
-            constants(j, c, q);
-#pragma unroll
-            for (int k = 0; k < SCAN_G; ++k)
-                if (k >= k0 && k < k1) accumulate(k, mf[k], q);
-        }
-        k0 = k1;
-    }
-    const double t_cand = wave_sum8(cand, lane), t_absx = wave_sum8(absx, lane), t_cst = wave_sum8(cst, lane),
-                 t_cstabs = wave_sum8(cstabs, lane), t_s1 = wave_sum8(s1, lane);
-    const int k = lane >> 3;
-    if ((lane & 7) == 0 && k < nvalid) {
-        const int r = r0 + k;
-        const RowInfo ri = row_info(p.rm, r);
-        scan_finish(p, r, nelem, scan_row_fetch(p, r, ri), t_cand, t_absx, t_cst, t_cstabs, t_s1);
-    }
-}
-
-// The same reductions with LPR lanes per row and 64/LPR rows per wave: every lane accumulates for its own row (no
-// per-row register arrays, so many more waves are resident) and fetches the constants of its own elements.
-//   LPR = 8  : short rows (8 rows per wave; lanes of different rows that meet the same neuron read the same addresses);
-//   LPR = 64 : one row per wave, for launches with so few rows that 8 rows per wave would leave most of the chip idle.
+// Short rows: LPR = 8 lanes per row, 8 rows per wave.  Every lane accumulates for its own row (few registers, many
+// resident waves) and fetches the constants of its own elements; lanes of different rows that meet the same neuron
+// read the same addresses.
 template <int V, int LPR>
 __global__ __launch_bounds__(256) void scan_tall_kernel(const ScanParams p) {
     constexpr int RPW = 64 / LPR;                            // rows per wave
@@ -856,10 +714,13 @@ __global__ __launch_bounds__(256) void scan_tall_kernel(const ScanParams p) {
 // being fetched by every wave, every lane accumulates for its own row (few registers, many resident waves), and
 // lanes of different rows read the same LDS words (broadcast).  Rows of a work-group that do not share box and
 // window origin are handled run by run.
-constexpr int SCAN_LDS_MAX = 1024;      // elements per row this kernel takes (40 KB of LDS at most)
+constexpr int SCAN_LDS_MAX = 1024;      // longest row whose constants are staged whole (40 KB of LDS)
+constexpr int SCAN_CHUNK = 512;         // chunk of longer rows (20 KB of LDS: 8 work-groups per CU)
 // ROWS per work-group (8 lanes each); the grouping does not touch a row's arithmetic.
 // U: row slices (8 lanes x V elements each) whose loads are in flight together.
-template <int V, int ROWS, int U>
+// CHUNKED: rows longer than SCAN_LDS_MAX are cut into chunks of SCAN_CHUNK coefficients, one work-group per (32 rows,
+// chunk); the five sums of a (row, chunk) go to p.partial and scan_combine_kernel adds a row's chunks in order.
+template <int V, int ROWS, int U, bool CHUNKED>
 __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) {
     constexpr int SCAN_LDS_ROWS = ROWS;
     constexpr int NT = ROWS * 8;
@@ -868,7 +729,9 @@ __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const BlockDesc& B = p.blk;
     const int nelem = B.wy * B.wx * B.C;
-    const int npad = (nelem + 3) & ~3;
+    const int c0 = CHUNKED ? (int)blockIdx.y * SCAN_CHUNK : 0;             // this work-group's element range
+    const int c1 = CHUNKED ? min(nelem, c0 + SCAN_CHUNK) : nelem;
+    const int npad = CHUNKED ? SCAN_CHUNK : ((nelem + 3) & ~3);
     double* const s_cp = s_const;
     double* const s_cn = s_const + npad;
     double* const s_X = s_const + 2 * npad;
@@ -895,7 +758,7 @@ __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) 
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int e = e0 + u * 8 * V;
-            if (e < nelem) {
+            if (e < c1) {
                 if (V == 4) {
                     const float4 t = *reinterpret_cast<const float4*>(src + e);
                     mf[u][0] = t.x; mf[u][1 % V] = t.y; mf[u][2 % V] = t.z; mf[u][3 % V] = t.w;
@@ -909,11 +772,12 @@ __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) 
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int e = e0 + u * 8 * V;
-            if (e < nelem) {
+            if (e < c1) {
+                const int k = e - c0;
 #pragma unroll
                 for (int v = 0; v < V; ++v)
-                    scan_term(p.cpos != nullptr, p.do_consts != 0, mf[u][v], s_cp[e + v], s_cn[e + v], s_X[e + v],
-                              s_kp[e + v], s_be[e + v], cand, absx, cst, cstabs, s1);
+                    scan_term(p.cpos != nullptr, p.do_consts != 0, mf[u][v], s_cp[k + v], s_cn[k + v], s_X[k + v],
+                              s_kp[k + v], s_be[k + v], cand, absx, cst, cstabs, s1);
             }
         }
     };
@@ -923,7 +787,7 @@ __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) 
         int k1 = k0 + 1;
         while (k1 < nvalid && s_b[k1] == b0 && s_oy[k1] == oy0 && s_ox[k1] == ox0) ++k1;
         const long long bbase = (long long)b0 * p.batch_stride;
-        for (int e = tid; e < nelem; e += NT) {
+        for (int e = c0 + tid; e < c1; e += NT) {
             int c;
             long long j;
             if (full_row) {
@@ -945,11 +809,12 @@ __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) 
                 if (p.kap) kp = p.kap[j];
                 if (p.beff) be = p.beff[c];
             }
-            s_cp[e] = cp; s_cn[e] = cn; s_X[e] = X; s_kp[e] = kp; s_be[e] = be;
+            const int k = e - c0;
+            s_cp[k] = cp; s_cn[k] = cn; s_X[k] = X; s_kp[k] = kp; s_be[k] = be;
         }
         __syncthreads();
         if (valid && kk >= k0 && kk < k1) {
-            for (int e0 = sub * V; e0 < nelem; e0 += U * 8 * V) {
+            for (int e0 = c0 + sub * V; e0 < c1; e0 += U * 8 * V) {
                 float mf[U][V];
                 load_slices(e0, mf);
                 add_slices(e0, mf);
@@ -966,31 +831,53 @@ __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) 
         cstabs += __shfl_xor(cstabs, off, 64);
         s1 += __shfl_xor(s1, off, 64);
     }
-    if (valid && sub == 0) scan_finish(p, r, nelem, scan_row_fetch(p, r, ri), cand, absx, cst, cstabs, s1);
+    if (valid && sub == 0) {
+        if constexpr (CHUNKED) {
+            double* out = p.partial + ((size_t)r * gridDim.y + blockIdx.y) * 5;
+            out[0] = cand; out[1] = absx; out[2] = cst; out[3] = cstabs; out[4] = s1;
+        } else {
+            scan_finish(p, r, nelem, scan_row_fetch(p, r, ri), cand, absx, cst, cstabs, s1);
+        }
+    }
 }
+
+// a row's chunk sums added in chunk order, then the row's bookkeeping
+__global__ __launch_bounds__(256) void scan_combine_kernel(const ScanParams p, int nchunks) {
+    const int r = blockIdx.x * 256 + threadIdx.x;
+    if (r >= p.nrows) return;
+    const double* in = p.partial + (size_t)r * nchunks * 5;
+    double t[5] = {0.0, 0.0, 0.0, 0.0, 0.0};
+    for (int c = 0; c < nchunks; ++c)
+#pragma unroll
+        for (int q = 0; q < 5; ++q) t[q] += in[c * 5 + q];
+    const RowInfo ri = row_info(p.rm, r);
+    scan_finish(p, r, p.blk.wy * p.blk.wx * p.blk.C, scan_row_fetch(p, r, ri), t[0], t[1], t[2], t[3], t[4]);
+}
+
 
 void launch_scan(const ScanParams& p, hipStream_t s) {
     if (p.nrows <= 0) return;
     const int nhalves = p.nrows / p.rm.Rc;
-    const int groups = ((p.rm.Rc + SCAN_G - 1) / SCAN_G) * nhalves;
     const int nelem = p.blk.wy * p.blk.wx * p.blk.C;
     const bool vec = (p.blk.C & 3) == 0;
-    if (nelem <= 256) {      // measured cross-over of the two layouts on MI355X
+    // the layout depends on the row length only, never on how many rows the launch has: a row's sums are formed in
+    // the same order whether its box is analysed alone, in a batch, or in a chunk of a batch
+    if (nelem <= 256 || (nelem > SCAN_LDS_MAX && !p.partial)) {      // cross-over of the two layouts measured on MI355X
+        const int groups = ((p.rm.Rc + SCAN_G - 1) / SCAN_G) * nhalves;
         if (vec) hipLaunchKernelGGL((scan_tall_kernel<4, 8>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
         else hipLaunchKernelGGL((scan_tall_kernel<1, 8>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
     } else if (nelem <= SCAN_LDS_MAX) {
         const size_t lds = (size_t)5 * ((nelem + 3) & ~3) * sizeof(double);
         const int wgs = ((p.rm.Rc + 31) / 32) * nhalves;
-        if (vec) hipLaunchKernelGGL((scan_lds_kernel<4, 32, 4>), dim3(wgs), dim3(256), lds, s, p);
-        else hipLaunchKernelGGL((scan_lds_kernel<1, 32, 4>), dim3(wgs), dim3(256), lds, s, p);
-    } else if (groups < 2048) {   // fewer waves than the chip holds at once: one row per wave
-        const int waves = p.nrows;
-        if (vec) hipLaunchKernelGGL((scan_tall_kernel<4, 64>), dim3((waves + 3) / 4), dim3(256), 0, s, p);
-        else hipLaunchKernelGGL((scan_tall_kernel<1, 64>), dim3((waves + 3) / 4), dim3(256), 0, s, p);
-    } else if (vec) {
-        hipLaunchKernelGGL((scan_kernel<4>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
+        if (vec) hipLaunchKernelGGL((scan_lds_kernel<4, 32, 4, false>), dim3(wgs), dim3(256), lds, s, p);
+        else hipLaunchKernelGGL((scan_lds_kernel<1, 32, 4, false>), dim3(wgs), dim3(256), lds, s, p);
     } else {
-        hipLaunchKernelGGL((scan_kernel<1>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
+        const int nchunks = (nelem + SCAN_CHUNK - 1) / SCAN_CHUNK;
+        const dim3 grid(((p.rm.Rc + 31) / 32) * nhalves, nchunks);
+        const size_t lds = (size_t)5 * SCAN_CHUNK * sizeof(double);
+        if (vec) hipLaunchKernelGGL((scan_lds_kernel<4, 32, 4, true>), grid, dim3(256), lds, s, p);
+        else hipLaunchKernelGGL((scan_lds_kernel<1, 32, 4, true>), grid, dim3(256), lds, s, p);
+        hipLaunchKernelGGL(scan_combine_kernel, dim3((p.nrows + 255) / 256), dim3(256), 0, s, p, nchunks);
     }
 }
 

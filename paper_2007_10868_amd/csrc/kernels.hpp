@@ -97,6 +97,7 @@ struct ScanParams {        // per-row reductions over a block
     double* err;           // per-row accumulated slack (>= 0)
     double* best;          // per-row best candidate so far (indexed by the row's place before any removal)
     const unsigned char* done;   // per task of the chunk (compact): 1 = termination criterion met, best is final; null: none
+    double* partial;       // scratch for rows longer than 1024 coefficients: [nrows][ceil(nelem/512)][5]; null: not available
 };
 
 struct InitParams {
