@@ -608,6 +608,9 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
             tp.row0 = rm.row0; tp.key = key; tp.first = first ? 1 : 0; tp.may_stop = may_stop ? 1 : 0;
             tp.wgcount = d_wg;
             gp::launch_term(tp, net->d_count, net->stream);
+            // When all crossings still to come for this chunk take less than a few host round trips, removing rows
+            // cannot pay: the flags are kept up to date (they decide what a task keeps), nothing is read back.
+            if ((double)rm.Rc * nsign * rem_flop / 30e12 < 200e-6) return GP_OK;
             // removing rows costs a copy of the rows kept (and an idle moment of the GPU); the rows removed would
             // have cost their share of the crossings still to come
             auto pays = [&](int kept) {
@@ -662,7 +665,7 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
             sd.lo = ls.d_lo; sd.hi = ls.d_hi; sd.best = d_best; sd.row0 = rm.row0; sd.Rc0 = rm.Rc0;
             gp::launch_seed(sd, net->stream);
             if (may_stop) {
-                st = check_termination(start, true, -1, 0, 0.0);
+                st = check_termination(start, true, -1, 0, rem_flop[0]);
                 if (st != GP_OK) return st;
             } else if (ls.d_term) {
                 gp::launch_fill_i32(ls.d_term + row0, 0, rm.Rc, net->stream);
