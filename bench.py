@@ -94,6 +94,20 @@ def main():
     ms_per_step = wall_ms / args.steps
     ms_per_input = ms_per_step / batch
 
+    # one input at a time (what a caller without a batch sees); not the metric, reported beside it
+    single_ms = None
+    if batch > 1:
+        one = t_centers[:1].contiguous()
+        for _ in range(3):
+            g.analyze_batch_dev(one, net.eps)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        reps = 10
+        for _ in range(reps):
+            g.analyze_batch_dev(one, net.eps)
+        torch.cuda.synchronize()
+        single_ms = (time.perf_counter() - t0) * 1e3 / reps
+
     cross = prof["cross"]
     avg_launch_ms = cross["ms"] / max(cross["launches"], 1)
     flop_per_launch = cross["flop"] / max(cross["launches"], 1)
@@ -134,6 +148,8 @@ def main():
                            coefficient_storage="f32", accumulate="f64 MFMA", workspace_bytes=ws_bytes,
                            early_termination=bool(args.early_term)),
                roofline=roofline, cpu_baseline=cpu)
+    if single_ms is not None:
+        out["single_input_latency_ms"] = round(single_ms, 4)
     if early is not None:
         out["early_termination"] = early
     print(json.dumps(out))
