@@ -59,6 +59,7 @@ struct PlanOp {
     enum Kind { INIT = 0, SCAN = 1, CROSS = 2, FINALIZE = 3 } kind = INIT;
     int slot_in = -1, slot_out = -1, slot_add = -1;
     Geom g_in, g_out, g_add;
+    Geom t_in;             // CROSS: the rows' exact dependence window over layer_in (never clipped or widened)
     int layer_in = -1, layer_out = -1;
     bool relaxed = false;  // CROSS/INIT: apply the ReLU substitution of layer_out to the new block; SCAN: block holds such coefficients
     bool consts_only = false;
@@ -191,6 +192,34 @@ bool hull(const Geom& a, const Geom& b, const Layer& l, Geom& o) {
     return true;
 }
 
+// The exact dependence window of a row (Section 4.3), carried beside the stored one.  The stored window is clipped
+// to the layer and shifted inside it at the borders, and it is widened to the whole layer once it is as large; the
+// entries it holds outside the exact window are structural zeros, which the crossing kernel skips.
+const int kEverywhere = 1 << 20;
+Geom everywhere() {
+    Geom g;
+    g.Sy = g.Sx = 0; g.Py = g.Px = kEverywhere; g.Wy = g.Wx = 2 * kEverywhere;
+    return g;
+}
+bool is_everywhere(const Geom& g) { return g.Wy >= 2 * kEverywhere || g.Wx >= 2 * kEverywhere; }
+
+Geom cross_exact(const Geom& t, const Layer& a) {
+    if (a.type == T_DENSE || is_everywhere(t)) return everywhere();
+    Geom o;
+    o.Sy = t.Sy * a.sh; o.Py = t.Py * a.sh + a.ph; o.Wy = (t.Wy - 1) * a.sh + a.kh;
+    o.Sx = t.Sx * a.sw; o.Px = t.Px * a.sw + a.pw; o.Wx = (t.Wx - 1) * a.sw + a.kw;
+    if (o.Wy >= kEverywhere / 4 || o.Wx >= kEverywhere / 4 || o.Py >= kEverywhere / 4 || o.Px >= kEverywhere / 4) return everywhere();
+    return o;
+}
+
+Geom hull_exact(const Geom& a, const Geom& b) {
+    if (is_everywhere(a) || is_everywhere(b) || a.Sy != b.Sy || a.Sx != b.Sx) return everywhere();
+    Geom o;
+    o.Sy = a.Sy; o.Py = std::max(a.Py, b.Py); o.Wy = std::max(a.Wy - a.Py, b.Wy - b.Py) + o.Py;
+    o.Sx = a.Sx; o.Px = std::max(a.Px, b.Px); o.Wx = std::max(a.Wx - a.Px, b.Wx - b.Px) + o.Px;
+    return o;
+}
+
 long long block_elems(const Geom& g, const Layer& l) {
     return (long long)std::min(g.Wy, l.H) * std::min(g.Wx, l.W) * l.C;
 }
@@ -234,6 +263,7 @@ gp_status prepare_topology(gp_net* net) {
 struct Desc {
     int slot = -1;
     Geom g;
+    Geom t;                  // exact dependence window (see cross_exact)
     bool consumed = false;   // the constants of the next step have been added to the rows' constant
 };
 
@@ -255,6 +285,7 @@ gp_status build_plan(gp_net* net, int start, bool certify, Plan& pl) {
     Geom g0;
     if (certify) { g0.Sy = g0.Sx = g0.Py = g0.Px = 0; g0.Wy = L[start].H; g0.Wx = L[start].W; }
     else { g0.Sy = g0.Sx = 1; g0.Py = g0.Px = 0; g0.Wy = g0.Wx = 1; }
+    const Geom t0 = certify ? everywhere() : g0;
     normalise(g0, L[start]);
     if (!certify && is_affine(L[start])) {
         // the neuron's own affine expression (Section 2): the filter placed in the window over the predecessor
@@ -276,7 +307,7 @@ gp_status build_plan(gp_net* net, int start, bool certify, Plan& pl) {
         sc.slot_in = op.slot_out; sc.g_in = g1; sc.layer_in = pr;
         sc.do_consts = true; sc.update_best = true; sc.rounded = relu_pred; sc.relaxed = relu_pred;
         pl.ops.push_back(sc);
-        Desc d; d.slot = op.slot_out; d.g = g1; d.consumed = true;
+        Desc d; d.slot = op.slot_out; d.g = g1; d.t = cross_exact(t0, L[start]); d.consumed = true;
         expr[relu_pred ? L[pr].a : pr] = d;
         push_step(pl, 0, start, g0, L[start], 0);
         push_step(pl, 1, start, g1, L[pr], 0);
@@ -295,7 +326,7 @@ gp_status build_plan(gp_net* net, int start, bool certify, Plan& pl) {
         sc.slot_in = op.slot_out; sc.g_in = g0; sc.layer_in = start;
         sc.do_consts = true; sc.update_best = false; sc.rounded = false;
         pl.ops.push_back(sc);
-        Desc d; d.slot = op.slot_out; d.g = g0; d.consumed = true;
+        Desc d; d.slot = op.slot_out; d.g = g0; d.t = t0; d.consumed = true;
         expr[start] = d;
         push_step(pl, 0, start, g0, L[start], 0);
     }
@@ -332,9 +363,10 @@ gp_status build_plan(gp_net* net, int start, bool certify, Plan& pl) {
         } else if (is_affine(l)) {
             const int p = l.a;
             Geom g = cross_geom(d.g, l, L[p]);
+            Geom t = cross_exact(d.t, l);
             PlanOp op;
             op.kind = PlanOp::CROSS;
-            op.slot_in = d.slot; op.g_in = d.g; op.layer_in = k; op.layer_out = p;
+            op.slot_in = d.slot; op.g_in = d.g; op.t_in = d.t; op.layer_in = k; op.layer_out = p;
             Desc ad;
             bool has_add = expr.count(p) > 0;
             if (has_add) {
@@ -344,6 +376,7 @@ gp_status build_plan(gp_net* net, int start, bool certify, Plan& pl) {
                 if (!hull(g, ad.g, L[p], h))
                     return fail(net, GP_ERR_UNSUPPORTED, "layer %d: branches with different accumulated strides", p);
                 g = h;
+                t = hull_exact(t, ad.t);
                 if (l.type == T_DENSE && block_elems(ad.g, L[p]) != L[p].n)
                     return fail(net, GP_ERR_UNSUPPORTED, "layer %d: windowed block joins a dense branch", p);
                 op.slot_add = ad.slot; op.g_add = ad.g;
@@ -370,7 +403,7 @@ gp_status build_plan(gp_net* net, int start, bool certify, Plan& pl) {
             sc.slot_in = op.slot_out; sc.g_in = g; sc.layer_in = p;
             sc.do_consts = complete; sc.update_best = expr.empty(); sc.rounded = true; sc.relaxed = relaxed;
             pl.ops.push_back(sc);
-            Desc nd; nd.slot = op.slot_out; nd.g = g; nd.consumed = complete;
+            Desc nd; nd.slot = op.slot_out; nd.g = g; nd.t = t; nd.consumed = complete;
             expr[key] = nd;
             push_step(pl, 1, k, g, L[p], has_add ? 1 : 0);
             if (relaxed) push_step(pl, 2, p, g, L[p], 0);
@@ -492,13 +525,15 @@ gp_status get_workspace(gp_net* net, long long want, char** ws, long long* bytes
     return GP_OK;
 }
 
-gp::BlockDesc make_desc(const gp_net* net, const float* data, const Geom& g, int layer) {
+gp::BlockDesc make_desc(const gp_net* net, const float* data, const Geom& g, int layer, const Geom* exact = nullptr) {
     const Layer& l = net->L[layer];
     gp::BlockDesc b;
     b.data = data;
     b.H = l.H; b.W = l.W; b.C = l.C;
     b.wy = std::min(g.Wy, l.H); b.wx = std::min(g.Wx, l.W);
     b.Sy = g.Sy; b.Sx = g.Sx; b.Py = g.Py; b.Px = g.Px;
+    const Geom t = (exact && l.H < 32768 && l.W < 32768) ? *exact : everywhere();
+    b.tSy = t.Sy; b.tSx = t.Sx; b.tPy = t.Py; b.tPx = t.Px; b.tWy = t.Wy; b.tWx = t.Wx;
     return b;
 }
 
@@ -750,7 +785,7 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                 const Layer& a = net->L[op.layer_in];
                 const Layer& p = net->L[op.layer_out];
                 gp::CrossParams cp;
-                cp.in = make_desc(net, slot_ptr(op.slot_in), op.g_in, op.layer_in);
+                cp.in = make_desc(net, slot_ptr(op.slot_in), op.g_in, op.layer_in, &op.t_in);
                 cp.out_grl = op.relaxed ? p.d_grl : nullptr;
                 cp.wt = a.d_wt;
                 cp.kh = a.kh; cp.kw = a.kw; cp.sh = a.sh; cp.sw = a.sw; cp.ph = a.ph; cp.pw = a.pw;

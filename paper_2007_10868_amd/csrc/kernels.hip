@@ -174,6 +174,7 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
     const int ld_row = tid >> 2, q4 = (tid & 3) * 4;
     uint32_t a_rowoff[APT];                 // byte offset of (row's block, channel q4) inside rsrcA
     int a_ydiv[APT], a_xdiv[APT], a_ymod[APT], a_xmod[APT], a_oiy[APT], a_oix[APT];
+    uint32_t a_ty[APT], a_tx[APT];          // the row's exact window inside the stored one: first index | size << 16
     bool a_ok[APT];
 #pragma unroll
     for (int i = 0; i < APT; ++i) {
@@ -189,6 +190,15 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
         a_xdiv[i] = (int)xd; a_xmod[i] = (int)(xx0 - xd * (uint32_t)p.sw);
         a_oiy[i] = clampi(p.in.Sy * ri.ys - p.in.Py, 0, p.in.H - p.in.wy);
         a_oix[i] = clampi(p.in.Sx * ri.xs - p.in.Px, 0, p.in.W - p.in.wx);
+        if constexpr (!DENSE) {
+            // entries of the stored window outside the exact dependence window are structural zeros (border rows
+            // keep a full-size window shifted inside the layer): taps that only reach those are not visited
+            const int ty = p.in.tSy * ri.ys - p.in.tPy, tx = p.in.tSx * ri.xs - p.in.tPx;
+            const int ylo = max(ty, a_oiy[i]), yhi = min(ty + p.in.tWy, a_oiy[i] + p.in.wy);
+            const int xlo = max(tx, a_oix[i]), xhi = min(tx + p.in.tWx, a_oix[i] + p.in.wx);
+            a_ty[i] = (uint32_t)(ylo - a_oiy[i]) | ((uint32_t)max(yhi - ylo, 0) << 16);
+            a_tx[i] = (uint32_t)(xlo - a_oix[i]) | ((uint32_t)max(xhi - xlo, 0) << 16);
+        }
         a_rowoff[i] = ((uint32_t)rl * row_elems + (uint32_t)q4) * 4u;
     }
     // per-thread byte offsets for the current tap: A row (kOOB when the tap misses the row's window), B column
@@ -217,7 +227,8 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
             const int yi = y - a_oiy[i], xi = x - a_oix[i];
             const bool ok = a_ok[i] && a_ymod[i] == fmod && a_xmod[i] == gmod &&
                             (unsigned)y < (unsigned)p.in.H && (unsigned)x < (unsigned)p.in.W &&
-                            (unsigned)yi < (unsigned)p.in.wy && (unsigned)xi < (unsigned)p.in.wx;
+                            (unsigned)(yi - (int)(a_ty[i] & 0xffffu)) < (a_ty[i] >> 16) &&
+                            (unsigned)(xi - (int)(a_tx[i] & 0xffffu)) < (a_tx[i] >> 16);
             a_voff[i] = ok ? a_rowoff[i] + (uint32_t)(yi * p.in.wx + xi) * (uint32_t)(Ck * 4) : kOOB;
             any = any || ok;
         }

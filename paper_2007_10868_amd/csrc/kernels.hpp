@@ -55,6 +55,10 @@ struct BlockDesc {
     int H, W, C;         // dims of the layer the block ranges over
     int wy, wx;          // window size (already clipped to the layer)
     int Sy, Sx, Py, Px;  // window origin of a row at (ys,xs): clamp(S*ys - P, 0, H - wy)  (eqs. 6-9 with padding)
+    // the row's exact dependence window: origin tS*pos - tP (may be negative), size tW (may exceed the layer); the
+    // stored window contains its part inside the layer, and every stored entry outside it is a structural zero
+    // (read by the crossing kernel only; H, W < 32768 there)
+    int tSy, tSx, tPy, tPx, tWy, tWx;
 };
 
 struct CrossParams {       // one back-substitution step through an affine layer (Algorithm 1 per row)
