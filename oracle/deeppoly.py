@@ -51,6 +51,8 @@ def _load():
     L.dp_request_bounds.argtypes = [P, C.c_int]
     L.dp_set_collapse.argtypes = [P, C.c_int]
     L.dp_set_early_termination.argtypes = [P, C.c_int]
+    L.dp_set_float_inference.argtypes = [P, C.c_int]
+    L.dp_get_inference_error.argtypes = [P, C.c_int, dp]
     L.dp_set_term_override.argtypes = [P, C.c_int, ip]
     L.dp_get_term_layer.argtypes = [P, C.c_int, ip]
     L.dp_get_interval_image.argtypes = [P, C.c_int, dp, dp]
@@ -168,6 +170,17 @@ class OracleNet:
     def set_early_termination(self, on: bool):
         """Forward interval pass + termination criterion (Sections 3.2 and 4.2)."""
         self._chk(self._L.dp_set_early_termination(self._h, 1 if on else 0), "set_early_termination")
+
+    def set_float_inference(self, on: bool):
+        """Bounds that also hold for every float32 evaluation order of the network (Section 4.1, last paragraph)."""
+        self._chk(self._L.dp_set_float_inference(self._h, 1 if on else 0), "set_float_inference")
+
+    def get_inference_error(self, lid) -> np.ndarray:
+        """Per neuron of an affine or sum layer: the bound on |float32 evaluation - exact value| the last analysis used."""
+        eta = np.empty(self.layer_size(lid), np.float64)
+        self._chk(self._L.dp_get_inference_error(self._h, lid, eta.ctypes.data_as(C.POINTER(C.c_double))),
+                  "get_inference_error")
+        return eta
 
     def set_term_override(self, lid, term: Optional[np.ndarray]):
         """Per neuron of layer lid: where its back-substitution stops (-1: the criterion decides)."""

@@ -46,6 +46,19 @@
  *     reason concretisation is, keeps float64 and outward rounding, and stops the growth.  collapse = 0
  *     is the literal scheme.
  *
+ *   - rounding of the inference itself (Section 4.1, last paragraph; the paper names the goal and defers the
+ *     technique to a citation).  Reading taken here, a separate mode that is off by default
+ *     (dp_set_float_inference): the network is evaluated in float32, every affine neuron as a sum of float32
+ *     products and its bias in ANY order, fused or not, a residual sum as one rounded addition, ReLU exactly.
+ *     The classical bound for such a sum of K products and a bias is
+ *         |computed - exact| <= gamma(K+1) * (sum_j |w_j|*|x_j| + |b|) + (K+1)*2^-149,   gamma(k) = k*u/(1-k*u),
+ *     u = 2^-24 (the last term covers products that underflow).  With |x_j| <= max(|l_j|,|u_j|) this is a constant
+ *     eta_i per neuron, and the neuron's relation becomes x_i in sum_j w_ij x_j + b_i + [-eta_i, eta_i]: substituting
+ *     a coefficient a over x_i adds |a|*eta_i to the constant, outward.  A rounded addition is monotone, so the
+ *     interval of a residual sum is the interval of the exact sum moved outward by u*|end|, and a coefficient a
+ *     over it adds |a|*u*max|end| when it is substituted.  The analysis then bounds every such float32 evaluation
+ *     (and the real-valued one).
+ *
  * Neuron order inside a layer: C,H,W flattened (channel outermost).
  *
  * Pins: see tests/test_oracle_*.py (closed forms, eps=0, all-stable composition, hand example,
@@ -86,6 +99,9 @@ typedef struct {
     int *term;               /* per neuron: layer the expression ranged over when it was dropped; the layer's own
                                 id = never started; 0 = substituted down to the input                 */
     int *term_force;         /* optional per-neuron override of the decision (-1: none)               */
+    /* float32-inference mode */
+    double *eta;             /* per neuron: bound on |float32 evaluation - exact value| given the predecessors     */
+    int has_eta;
 } layer_t;
 
 typedef struct {
@@ -95,6 +111,7 @@ typedef struct {
     int candidates;          /* 0: every step       1: input layer only            */
     int collapse;            /* 1: re-centre interval coefficients before each substitution (default) */
     int early_term;          /* 1: forward interval pass + termination criterion (Sections 3.2, 4.2)  */
+    int float_inference;     /* 1: bounds also hold for every float32 evaluation order (Section 4.1)  */
     int analyzed;
 } dp_net;
 
@@ -141,6 +158,7 @@ static void alloc_bounds(layer_t *l) {
         l->ilo = (double *)calloc(l->n, sizeof(double));
         l->ihi = (double *)calloc(l->n, sizeof(double));
         l->term = (int *)calloc(l->n, sizeof(int));
+        l->eta = (double *)calloc(l->n, sizeof(double));
     }
 }
 
@@ -209,7 +227,7 @@ void dp_destroy(dp_net *N) {
         layer_t *l = &N->L[i];
         free(l->wt); free(l->bias); free(l->lo); free(l->hi); free(l->gam); free(l->del);
         free(l->lam); free(l->lam_force); free(l->gam_force);
-        free(l->ilo); free(l->ihi); free(l->term); free(l->term_force);
+        free(l->ilo); free(l->ihi); free(l->term); free(l->term_force); free(l->eta);
     }
     free(N->L); free(N);
 }
@@ -240,6 +258,20 @@ int dp_set_early_termination(dp_net *N, int on) {
     if (!N) return DP_ERR_ARG;
     N->early_term = on ? 1 : 0;
     N->analyzed = 0;
+    return DP_OK;
+}
+/* Bounds that also hold for every float32 evaluation of the network (any summation order, fused or unfused
+   multiply-add; Section 4.1, last paragraph).  See the header for the error model. */
+int dp_set_float_inference(dp_net *N, int on) {
+    if (!N) return DP_ERR_ARG;
+    N->float_inference = on ? 1 : 0;
+    for (int i = 0; i < N->n_layers; ++i) N->L[i].has_eta = 0;
+    N->analyzed = 0;
+    return DP_OK;
+}
+int dp_get_inference_error(const dp_net *N, int lid, double *eta) {
+    if (!N || lid <= 0 || lid >= N->n_layers || !N->L[lid].has_eta) return DP_ERR_STATE;
+    memcpy(eta, N->L[lid].eta, sizeof(double) * N->L[lid].n);
     return DP_OK;
 }
 /* term[i] >= 0 fixes where neuron i of layer lid stops: lid = it is not back-substituted at all, k = right
@@ -420,6 +452,14 @@ static inline void acc_scaled(double *lo, double *hi, double alo, double ahi, do
     else          { *lo = add_dn(*lo, mul_dn(ahi, w)); *hi = add_up(*hi, mul_up(alo, w)); }
 }
 
+/* float32-inference mode: the neuron the coefficient [a,b] stood over is its exact expression plus an error in
+   [-eta, eta] */
+static inline void acc_error(expr_t *e, double a, double b, double eta) {
+    double s = mul_up(dmax(fabs(a), fabs(b)), eta);
+    e->chi = add_up(e->chi, s);
+    e->clo = add_dn(e->clo, -s);
+}
+
 /* candidate bound of the expression part that ranges over layer k (sense +1: upper, -1: lower) */
 static double concretise(const dp_net *N, const expr_t *e, int k, int sense) {
     const layer_t *l = &N->L[k];
@@ -513,6 +553,7 @@ static void step_dense(const dp_net *N, expr_t *e, int k) {
         const double *w = d->wt + (size_t)i * n_in;
         for (int j = 0; j < n_in; ++j) acc_scaled(&dlo[j], &dhi[j], a, b, w[j]);
         acc_scaled(&e->clo, &e->chi, a, b, d->bias[i]);
+        if (d->has_eta) acc_error(e, a, b, d->eta[i]);
         slo[i] = shi[i] = 0.0;
     }
     e->active[k] = 0;
@@ -543,6 +584,7 @@ static void step_conv(const dp_net *N, expr_t *e, int k) {
                         }
                     }
                 acc_scaled(&e->clo, &e->chi, a, b, c->bias[d]);
+                if (c->has_eta) acc_error(e, a, b, c->eta[i]);
                 slo[i] = shi[i] = 0.0;
             }
     e->active[k] = 0;
@@ -557,6 +599,7 @@ static void step_add(const dp_net *N, expr_t *e, int k) {
         if (a == 0.0 && b == 0.0) continue;
         e->lo[s->a][j] = add_dn(e->lo[s->a][j], a); e->hi[s->a][j] = add_up(e->hi[s->a][j], b);
         e->lo[s->b][j] = add_dn(e->lo[s->b][j], a); e->hi[s->b][j] = add_up(e->hi[s->b][j], b);
+        if (s->has_eta) acc_error(e, a, b, s->eta[j]);
         slo[j] = shi[j] = 0.0;
     }
     e->active[k] = 0;
@@ -589,6 +632,74 @@ static double backsubstitute(const dp_net *N, expr_t *e, int sense) {
             default: return NAN;
         }
     }
+}
+
+/* ---- float32-inference mode (Section 4.1, last paragraph) ------------------------------------------- */
+static const double kU32 = 0x1p-24;           /* unit roundoff of float32 */
+
+/* eta of an affine layer from the intervals of its predecessor (pl, pu); FE_UPWARD */
+static void affine_inference_error(layer_t *l, const layer_t *p, const double *pl, const double *pu) {
+    const double K = (l->type == L_DENSE) ? (double)p->n : (double)l->kh * l->kw * p->C;
+    const double ku = (K + 1.0) * kU32;
+    const double gamma = ku / (-(ku - 1.0));                     /* k*u/(1-k*u): the denominator rounds down */
+    const double floor_ = (K + 1.0) * 0x1p-149;
+    if (l->type == L_DENSE) {
+        for (int i = 0; i < l->n; ++i) {
+            const double *w = l->wt + (size_t)i * p->n;
+            double s = fabs(l->bias[i]);
+            for (int j = 0; j < p->n; ++j) s = add_up(s, mul_up(fabs(w[j]), dmax(fabs(pl[j]), fabs(pu[j]))));
+            l->eta[i] = add_up(mul_up(s, gamma), floor_);
+        }
+    } else {
+        for (int d = 0; d < l->C; ++d)
+            for (int y = 0; y < l->H; ++y)
+                for (int x = 0; x < l->W; ++x) {
+                    double s = fabs(l->bias[d]);
+                    for (int ci = 0; ci < p->C; ++ci)
+                        for (int f = 0; f < l->kh; ++f) {
+                            int iy = y * l->sh - l->ph + f;
+                            if (iy < 0 || iy >= p->H) continue;
+                            for (int g = 0; g < l->kw; ++g) {
+                                int ix = x * l->sw - l->pw + g;
+                                if (ix < 0 || ix >= p->W) continue;
+                                double w = l->wt[(((size_t)d * p->C + ci) * l->kh + f) * l->kw + g];
+                                int j = (ci * p->H + iy) * p->W + ix;
+                                s = add_up(s, mul_up(fabs(w), dmax(fabs(pl[j]), fabs(pu[j]))));
+                            }
+                        }
+                    l->eta[(d * l->H + y) * l->W + x] = add_up(mul_up(s, gamma), floor_);
+                }
+    }
+    l->has_eta = 1;
+}
+
+/* a rounded float32 addition is monotone: the interval of the exact sum moves outward by u*|end|; FE_UPWARD */
+static inline void widen_rounded_sum(double *lo, double *hi) {
+    *lo = add_dn(*lo, -mul_up(fabs(*lo), kU32));
+    *hi = add_up(*hi, mul_up(fabs(*hi), kU32));
+}
+
+/* eta of a residual sum from its own (already widened) interval */
+static void sum_inference_error(layer_t *l) {
+    int old = fegetround();
+    fesetround(FE_UPWARD);
+    for (int i = 0; i < l->n; ++i) l->eta[i] = mul_up(dmax(fabs(l->lo[i]), fabs(l->hi[i])), kU32);
+    fesetround(old);
+    l->has_eta = 1;
+}
+
+/* before the rows of layer lid are bounded: the layer's own eta (affine) or none yet (sum) */
+static int prepare_inference_error(dp_net *N, int lid, int early) {
+    layer_t *l = &N->L[lid];
+    l->has_eta = 0;
+    if (!N->float_inference || (l->type != L_DENSE && l->type != L_CONV)) return DP_OK;
+    const layer_t *p = &N->L[l->a];
+    if (!p->has_bounds && !(early && p->has_ival)) return DP_ERR_STATE;
+    int old = fegetround();
+    fesetround(FE_UPWARD);
+    affine_inference_error(l, p, p->has_bounds ? p->lo : p->ilo, p->has_bounds ? p->hi : p->ihi);
+    fesetround(old);
+    return DP_OK;
 }
 
 /* bounds of rows[0..n_rows) of layer lid, from the intervals already stored for earlier layers */
@@ -624,6 +735,7 @@ int dp_bound_rows(dp_net *N, int lid, const int *rows, int n_rows, double *out_l
                 }
                 if (sense > 0) out_hi[r] = v; else out_lo[r] = v;
             }
+            if (N->float_inference && l->type == L_ADD) widen_rounded_sum(&out_lo[r], &out_hi[r]);
         }
         expr_free(e);
         fesetround(old);
@@ -649,6 +761,7 @@ static void interval_image(dp_net *N, int lid) {
                 if (w[j] >= 0.0) { lo = add_dn(lo, mul_dn(w[j], pl[j])); hi = add_up(hi, mul_up(w[j], pu[j])); }
                 else             { lo = add_dn(lo, mul_dn(w[j], pu[j])); hi = add_up(hi, mul_up(w[j], pl[j])); }
             }
+            if (l->has_eta) { lo = add_dn(lo, -l->eta[i]); hi = add_up(hi, l->eta[i]); }
             l->ilo[i] = lo; l->ihi[i] = hi;
         }
     } else if (l->type == L_CONV) {
@@ -670,12 +783,16 @@ static void interval_image(dp_net *N, int lid) {
                             }
                         }
                     int i = (d * l->H + y) * l->W + x;
+                    if (l->has_eta) { lo = add_dn(lo, -l->eta[i]); hi = add_up(hi, l->eta[i]); }
                     l->ilo[i] = lo; l->ihi[i] = hi;
                 }
     } else if (l->type == L_ADD) {
         const layer_t *q = &N->L[l->b];
         const double *ql = cur_lo(q), *qu = cur_hi(q);
-        for (int i = 0; i < l->n; ++i) { l->ilo[i] = add_dn(pl[i], ql[i]); l->ihi[i] = add_up(pu[i], qu[i]); }
+        for (int i = 0; i < l->n; ++i) {
+            l->ilo[i] = add_dn(pl[i], ql[i]); l->ihi[i] = add_up(pu[i], qu[i]);
+            if (N->float_inference) widen_rounded_sum(&l->ilo[i], &l->ihi[i]);
+        }
     }
     l->has_ival = 1;
 }
@@ -722,6 +839,8 @@ static int backsubstitute_pair(const dp_net *N, expr_t *eu, expr_t *el, double *
 static int analyze_layer_early(dp_net *N, int lid) {
     layer_t *l = &N->L[lid];
     {
+        int rc = prepare_inference_error(N, lid, 1);
+        if (rc != DP_OK) return rc;
         int old = fegetround();
         fesetround(FE_UPWARD);
         interval_image(N, lid);
@@ -749,12 +868,18 @@ static int analyze_layer_early(dp_net *N, int lid) {
             step_any(N, eu, lid, +1);
             step_any(N, el, lid, -1);
             l->term[r] = backsubstitute_pair(N, eu, el, &lo, &hi, may_stop, forced);
+            if (N->float_inference && l->type == L_ADD) {
+                /* candidates bound the exact sum, the interval image already the rounded one */
+                widen_rounded_sum(&lo, &hi);
+                lo = dmax(lo, l->ilo[r]); hi = dmin(hi, l->ihi[r]);
+            }
             l->lo[r] = lo; l->hi[r] = hi;
         }
         expr_free(eu); expr_free(el);
         fesetround(old);
     }
     l->has_bounds = 1;
+    if (N->float_inference && l->type == L_ADD) sum_inference_error(l);
     return DP_OK;
 }
 
@@ -770,12 +895,17 @@ int dp_analyze_layer(dp_net *N, int lid) {
         return DP_OK;
     }
     if (N->early_term) return analyze_layer_early(N, lid);
+    int rc = prepare_inference_error(N, lid, 0);
+    if (rc != DP_OK) return rc;
     int *rows = (int *)malloc(sizeof(int) * l->n);
     for (int i = 0; i < l->n; ++i) rows[i] = i;
     l->has_bounds = 0;
-    int rc = dp_bound_rows(N, lid, rows, l->n, l->lo, l->hi);
+    rc = dp_bound_rows(N, lid, rows, l->n, l->lo, l->hi);
     free(rows);
-    if (rc == DP_OK) l->has_bounds = 1;
+    if (rc == DP_OK) {
+        l->has_bounds = 1;
+        if (N->float_inference && l->type == L_ADD) sum_inference_error(l);
+    }
     return rc;
 }
 
@@ -783,8 +913,13 @@ int dp_analyze(dp_net *N) {
     if (!N || !N->L[0].has_bounds) return DP_ERR_STATE;
     for (int i = 1; i < N->n_layers; ++i) {
         layer_t *l = &N->L[i];
-        if (l->type == L_RELU || l->need_bounds || i == N->n_layers - 1 || N->early_term) {
+        /* in float32-inference mode a residual sum needs its own interval (its rounding error is relative to it) */
+        if (l->type == L_RELU || l->need_bounds || i == N->n_layers - 1 || N->early_term ||
+            (N->float_inference && l->type == L_ADD)) {
             int rc = dp_analyze_layer(N, i);
+            if (rc != DP_OK) return rc;
+        } else {
+            int rc = prepare_inference_error(N, i, 0);      /* crossed by later expressions all the same */
             if (rc != DP_OK) return rc;
         }
     }

@@ -239,3 +239,62 @@ def np_deeppoly_early(net: wl.Net, lo0, hi0):
         bounds[i] = (lo, hi)
         term[i] = tm
     return bounds, term, ival
+
+
+# ---- float32 inference in a chosen summation order ------------------------------------------------------
+def _sum_f32(terms: np.ndarray, order: str, rng) -> np.ndarray:
+    """Row-wise float32 sum of terms [rows, n] taken in the given order (every partial sum is rounded to float32)."""
+    t = np.ascontiguousarray(terms, dtype=np.float32)
+    n = t.shape[1]
+    if order == "forward":
+        idx = np.arange(n)
+    elif order == "reverse":
+        idx = np.arange(n)[::-1]
+    elif order == "random":
+        idx = rng.permutation(n)
+    elif order in ("ascending", "descending"):       # by magnitude, per row
+        key = np.abs(t) if order == "ascending" else -np.abs(t)
+        t = np.take_along_axis(t, np.argsort(key, axis=1, kind="stable"), axis=1)
+        idx = np.arange(n)
+    elif order == "pairwise":                        # balanced tree
+        cur = t
+        while cur.shape[1] > 1:
+            if cur.shape[1] % 2:
+                cur = np.concatenate([cur, np.zeros((cur.shape[0], 1), np.float32)], axis=1)
+            cur = (cur[:, 0::2] + cur[:, 1::2]).astype(np.float32)
+        return cur[:, 0]
+    else:
+        raise ValueError(order)
+    t = t[:, idx]
+    acc = np.zeros(t.shape[0], np.float32)
+    for k in range(n):                               # strictly sequential float32 accumulation
+        acc = (acc + t[:, k]).astype(np.float32)
+    return acc
+
+
+def forward_float32(net: wl.Net, x: np.ndarray, order: str, rng) -> dict:
+    """One float32 inference of the network at the float32 point x: every affine neuron is the float32 sum, in
+    the given order, of its float32 products and its bias; a residual sum is one float32 addition; ReLU is exact.
+    Returns {layer id: float32 [n]} (CHW order).  Test-side code: the order models what an inference engine may do."""
+    vals = {0: np.asarray(x, np.float32).reshape(-1)}
+    for i, L in enumerate(net.layers, start=1):
+        t = L["type"]
+        if t in ("dense", "conv"):
+            A, b = affine_matrix(net, i)             # exact float32 values held in float64
+            A32, b32 = A.astype(np.float32), b.astype(np.float32)
+            assert np.array_equal(A32.astype(np.float64), A) and np.array_equal(b32.astype(np.float64), b)
+            prod = (A32 * vals[L["src"]][None, :]).astype(np.float32)      # rounded products
+            terms = np.concatenate([prod, b32[:, None]], axis=1)
+            if t == "conv":                          # taps that fall into the padding are not terms of the sum
+                terms = np.where(np.concatenate([A32 != 0, np.ones((A32.shape[0], 1), bool)], axis=1), terms, np.float32(0))
+            vals[i] = _sum_f32(terms, order, rng)
+        elif t == "relu":
+            vals[i] = np.maximum(vals[L["src"]], np.float32(0))
+        elif t == "add":
+            vals[i] = (vals[L["a"]] + vals[L["b"]]).astype(np.float32)
+        else:
+            raise ValueError(t)
+    return vals
+
+
+FLOAT32_ORDERS = ("forward", "reverse", "random", "ascending", "descending", "pairwise")
