@@ -232,3 +232,43 @@ def test_certification_margins_cover_float32_outputs():
         for order in FLOAT32_ORDERS:
             out = forward_float32(net, x, order, rng)[net.out_layer].astype(np.float64)
             assert np.all(out[label] - out[others] >= margins)
+
+
+def rounded_sum_net():
+    """x -> add(x, relu(D x)) -> first component, with D = 2^-25 * identity.  At x = (1, 1) every affine neuron is exact
+    in float32 (one non-zero product, zero bias), the residual sum 1 + 2^-25 is not: it rounds to 1."""
+    net = wl.Net("rounded_sum", (2, 1, 1))
+    d = net.dense(0, np.array([[2.0 ** -25, 0.0], [0.0, 2.0 ** -25]], np.float32), np.zeros(2, np.float32))
+    r = net.relu(d)
+    s = net.add(0, r)
+    net.dense(s, np.array([[1.0, 0.0]], np.float32), np.zeros(1, np.float32))
+    return net, s
+
+
+def test_rounded_sum_hand_example():
+    net, s = rounded_sum_net()
+    x = np.array([1.0, 1.0], np.float32)
+    vals = forward_float32(net, x, "forward", np.random.default_rng(0))
+    assert vals[s][0] == np.float32(1.0) and vals[net.out_layer][0] == np.float32(1.0)
+    exact = 1.0 + 2.0 ** -25
+    on = build(net)
+    on.set_box(x.astype(np.float64), x.astype(np.float64))
+    on.analyze()
+    # the sum layer's own interval: the exact sum moved outward by one float32 rounding (and the summands' tiny errors)
+    lo, hi = on.get_bounds(s)
+    assert lo[0] <= 1.0 and hi[0] >= exact
+    assert lo[0] >= exact - 2.0 ** -24 * exact * (1 + 1e-6) and hi[0] <= exact + 2.0 ** -24 * exact * (1 + 1e-6)
+    # an expression substituted THROUGH the sum layer is charged the same rounding
+    ylo, yhi = on.get_bounds(net.out_layer)
+    assert ylo[0] <= 1.0 and yhi[0] >= exact
+    # (one rounding of the sum, gamma(3) for the output neuron of two inputs: 4 * 2^-24 relative in all)
+    assert ylo[0] >= exact - 4.001 * 2.0 ** -24 * exact and yhi[0] <= exact + 4.001 * 2.0 ** -24 * exact
+    # ... on top of the output neuron's own error: both constants (each pinned above) add up along the path, so the
+    # bound may not be tighter than their sum allows
+    eta_s, eta_y = on.get_inference_error(s)[0], on.get_inference_error(net.out_layer)[0]
+    assert ylo[0] <= exact - (eta_y + eta_s) * (1 - 1e-9) and yhi[0] >= exact + (eta_y + eta_s) * (1 - 1e-9)
+    # the real-valued analysis excludes the float32 result
+    off = build(net, float_inference=False, request=[s])
+    off.set_box(x.astype(np.float64), x.astype(np.float64))
+    off.analyze()
+    assert off.get_bounds(s)[0][0] > 1.0 and off.get_bounds(net.out_layer)[0][0] > 1.0
