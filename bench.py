@@ -30,6 +30,8 @@ def main():
     ap.add_argument("--dump", default="", help="write one CSV line per profiled kernel launch to this file")
     ap.add_argument("--early-term", action="store_true",
                     help="analyse with early termination (forward interval pass, stable neurons are not back-substituted)")
+    ap.add_argument("--float-inference", action="store_true",
+                    help="bounds that also cover every float32 evaluation order of the network (inference rounding)")
     ap.add_argument("--eps", type=float, default=0.0, help="override the configuration's perturbation radius")
     ap.add_argument("--cpu-sample", type=int, default=-1, help="inputs the oracle is timed on (0: skip)")
     args = ap.parse_args()
@@ -52,6 +54,8 @@ def main():
     wl.build_into(net, g)
     if args.early_term:
         g.set_early_termination(True)
+    if args.float_inference:
+        g.set_float_inference(True)
     centers = np.stack([net.center(j % net.n_inputs) for j in range(batch)])
     t_centers = torch.tensor(centers, device="cuda")
     stream = torch.cuda.current_stream()
@@ -135,6 +139,8 @@ def main():
         for j in range(n_cpu):
             if args.early_term:
                 o.set_early_termination(True)
+            if args.float_inference:
+                o.set_float_inference(True)
             o.analyze(net.center(j), net.eps)
         cpu_ms = (time.perf_counter() - t0) * 1e3 / n_cpu
         cpu = dict(value=round(cpu_ms, 3), unit="ms/input", cores=oracle_threads(), kind="oracle",
@@ -146,7 +152,7 @@ def main():
                higher_is_better=False, scaling="weak", vs_baseline=None, dtype="f64", data="synthetic",
                config=dict(workload=net.name, inputs_per_step=batch, eps=net.eps, neurons=int(sum(net.n_neurons(i) for i in range(1, net.out_layer + 1) if net.layers[i - 1]["type"] != "relu")),
                            coefficient_storage="f32", accumulate="f64 MFMA", workspace_bytes=ws_bytes,
-                           early_termination=bool(args.early_term)),
+                           early_termination=bool(args.early_term), float_inference=bool(args.float_inference)),
                roofline=roofline, cpu_baseline=cpu)
     if single_ms is not None:
         out["single_input_latency_ms"] = round(single_ms, 4)

@@ -75,6 +75,17 @@ gp_status gp_request_bounds(gp_net* net, int32_t layer_id);
  * gp_request_bounds and certification rows are always substituted down to the input.  Takes effect at the next
  * analysis; bounds of stopped neurons are sound but in general looser than without early termination. */
 gp_status gp_set_early_termination(gp_net* net, int32_t on);
+/* Rounding of the inference itself (paper Section 4.1, last paragraph: the analysis should also cover the error a
+ * floating-point evaluation of the network makes, whatever the order of its sums); off by default.  When on, every
+ * bound holds for the real-valued network AND for every float32 evaluation of it in which an affine neuron is a sum
+ * of float32 products and its bias taken in any order, with or without fused multiply-add, a residual sum is one
+ * rounded addition and ReLU is exact (round to nearest, gradual underflow, no overflow).  Mechanism: an affine neuron
+ * of K inputs is its exact expression plus an error of at most gamma(K+1)*(sum|w_j||x_j| + |b|) + (K+1)*2^-149,
+ * gamma(k) = k*2^-24/(1 - k*2^-24), evaluated with the predecessors' bounds; that constant is added, times the
+ * magnitude of the coefficient, whenever an expression is substituted through the neuron.  A residual sum layer's
+ * interval is moved outward by 2^-24*|end| (so sum layers always get bounds in this mode).  Takes effect at the
+ * next analysis.  The bounds of gp_certify and gp_bound_outputs then speak about the float32 outputs. */
+gp_status gp_set_float_inference(gp_net* net, int32_t on);
 /* After an analysis with early termination: for each neuron of a layer that has bounds, the id of the layer its
  * expression ranged over when it stopped; layer_id itself = never back-substituted, 0 = substituted down to the
  * input.  term: [n_layer]. */

@@ -53,6 +53,11 @@ struct Layer {
     double *d_rho = nullptr, *d_kap = nullptr;   // ReLU layers: candidate and intercept multipliers after substitution
     float* d_grl = nullptr;        // packed ReLU relaxation (see relax_factor in kernels.hip)
     int* d_term = nullptr;         // early termination: per task the layer at which it met the criterion
+    // inference rounding (Section 4.1): per neuron, how far a float32 evaluation can be from the exact expression over
+    // the predecessors.  d_eta: affine layers their own error; sum layers their own rounding plus what their summands
+    // pass on (a coefficient over the sum crosses all of them at once).  d_eta_thru: sum layers, the summands' part alone.
+    double* d_eta = nullptr;
+    double* d_eta_thru = nullptr;
 };
 
 struct PlanOp {
@@ -107,6 +112,7 @@ struct gp_net {
     int device = -1;
     // early termination (Sections 3.2, 4.2)
     bool early = false;
+    bool float_inference = false;  // bounds also hold for every float32 evaluation order of the network (Section 4.1)
     int* d_count = nullptr;
     int* h_count = nullptr;        // pinned: task counts read back while the GPU keeps working
     hipEvent_t count_ev = nullptr;
@@ -240,6 +246,8 @@ gp_status prepare_topology(gp_net* net) {
         // every crossing must land on a layer with intervals (they bound the rounding slack)
         if (is_affine(l)) net->L[l.a].need_bounds = true;
         if (l.type == T_RELU) { net->L[l.a].need_bounds = true; net->L[l.a].feeds_relu = true; }
+        // the rounding error of a float32 addition is relative to the sum: a sum layer needs its own interval
+        if (l.type == T_ADD && net->float_inference) l.need_bounds = true;
     }
     net->L[nl - 1].need_bounds = true;
     for (int i = 0; i < nl; ++i) {
@@ -434,9 +442,24 @@ gp_status get_plan(gp_net* net, int lid, Plan** out) {
 // ---- device state ------------------------------------------------------------------------------
 void free_layer_bounds(Layer& l) {
     dfree(l.d_lo); dfree(l.d_hi); dfree(l.d_rho); dfree(l.d_kap); dfree(l.d_xmax); dfree(l.d_grl); dfree(l.d_term);
-    l.d_lo = l.d_hi = l.d_rho = l.d_kap = l.d_xmax = nullptr;
+    dfree(l.d_eta); dfree(l.d_eta_thru);
+    l.d_lo = l.d_hi = l.d_rho = l.d_kap = l.d_xmax = l.d_eta = l.d_eta_thru = nullptr;
     l.d_grl = nullptr;
     l.d_term = nullptr;
+}
+
+// what a coefficient over layer lid picks up per unit of magnitude when it is substituted (inference rounding), or null
+const double* eta_of(const gp_net* net, int lid) {
+    const Layer& l = net->L[lid];
+    if (!net->float_inference) return nullptr;
+    if (is_affine(l) || l.type == T_ADD) return l.d_eta;
+    if (l.type == T_RELU) return eta_of(net, l.a);
+    return nullptr;
+}
+// a coefficient over a sum layer is handed to both summands unchanged: it crosses a summand that is an affine or a sum
+// layer in the same step (like land_of), while a ReLU summand is substituted later, as a block of its own
+bool summand_passes_eta(const gp_net* net, int lid) {
+    return is_affine(net->L[lid]) || net->L[lid].type == T_ADD;
 }
 
 bool has_bounds(const gp_net* net, int lid) {
@@ -486,6 +509,10 @@ gp_status ensure_device(gp_net* net, int batch) {
             }
             if (net->early && l.need_bounds && l.type != T_RELU && i > 0)
                 HIP_TRY(net, hipMalloc((void**)&l.d_term, cnt * sizeof(int)));
+            if (net->float_inference && (is_affine(l) || l.type == T_ADD))
+                HIP_TRY(net, hipMalloc((void**)&l.d_eta, cnt * sizeof(double)));
+            if (net->float_inference && l.type == T_ADD && (summand_passes_eta(net, l.a) || summand_passes_eta(net, l.b)))
+                HIP_TRY(net, hipMalloc((void**)&l.d_eta_thru, cnt * sizeof(double)));
             if (l.type == T_RELU) {
                 HIP_TRY(net, hipMalloc((void**)&l.d_grl, cnt * sizeof(float)));
                 HIP_TRY(net, hipMalloc((void**)&l.d_rho, cnt * sizeof(double)));
@@ -730,6 +757,7 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                     ip.Cs = ls.C;
                     ip.wt = ls.d_wti; ip.bias = ls.d_bias;
                     ip.out_grl = op.relaxed ? lo.d_grl : nullptr;
+                    ip.eta = net->float_inference ? ls.d_eta : nullptr;
                 }
                 ip.c = d_c; ip.err = d_err; ip.best = d_best;
                 ip.seeded = early ? 1 : 0;
@@ -754,6 +782,8 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                 }
                 if (op.relaxed) sp.kap = l.d_kap;
                 sp.beff = l.land.empty() ? nullptr : l.d_beff;
+                // a sum layer's own rows bound the exact sum of its summands; its one rounding is added when they are stored
+                sp.eta = (!certify && op.layer_in == start && l.type == T_ADD) ? l.d_eta_thru : eta_of(net, op.layer_in);
                 sp.e1_a = sp.e1_b = 0.0;
                 sp.xmax_a = sp.xmax_b = nullptr;
                 for (size_t i = 0; i < l.land.size(); ++i) {
@@ -841,6 +871,7 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                     fp.rm = rm0; fp.best = d_best;
                     fp.lo = net->L[start].d_lo; fp.hi = net->L[start].d_hi;
                     fp.xmax = net->L[start].d_xmax; fp.flag = net->d_flag;
+                    fp.widen = (net->float_inference && net->L[start].type == T_ADD) ? 0x1p-24 * (1.0 + 0x1p-20) : 0.0;
                     gp::launch_finalize(fp, net->stream);
                 }
             }
@@ -874,10 +905,20 @@ gp_status analyze_layers(gp_net* net, int batch) {
             rp.n = l.n;
             gp::launch_relu(rp, net->stream);
         } else {
-            if (net->early) {
-                // forward interval analysis of this layer from what is known of its predecessors (Section 4.2)
+            if (net->float_inference && l.type == T_ADD && l.d_eta_thru) {
+                gp::SumEtaParams ep;
+                ep.lo = ep.hi = nullptr; ep.u = 0.0;
+                ep.ea = summand_passes_eta(net, l.a) ? net->L[l.a].d_eta : nullptr;
+                ep.eb = summand_passes_eta(net, l.b) ? net->L[l.b].d_eta : nullptr;
+                ep.out = l.d_eta_thru; ep.total = l.n * batch;
+                gp::launch_sum_eta(ep, net->stream);
+            }
+            if (net->early || (net->float_inference && is_affine(l))) {
+                // forward interval analysis of this layer from what is known of its predecessors (Section 4.2), and/or
+                // the error of its float32 evaluation given those intervals (Section 4.1)
                 if (l.type == T_ADD) {
                     gp::AddIvalParams ap;
+                    ap.widen = net->float_inference ? 0x1p-24 * (1.0 + 0x1p-20) : 0.0;
                     ap.alo = net->L[l.a].d_lo; ap.ahi = net->L[l.a].d_hi;
                     ap.blo = net->L[l.b].d_lo; ap.bhi = net->L[l.b].d_hi;
                     ap.lo = l.d_lo; ap.hi = l.d_hi; ap.total = l.n * batch; ap.flag = net->d_flag;
@@ -886,7 +927,8 @@ gp_status analyze_layers(gp_net* net, int batch) {
                     const Layer& p = net->L[l.a];
                     gp::IvalParams ip;
                     ip.plo = p.d_lo; ip.phi = p.d_hi; ip.wt = l.d_wti; ip.bias = l.d_bias;
-                    ip.lo = l.d_lo; ip.hi = l.d_hi; ip.flag = net->d_flag;
+                    ip.lo = net->early ? l.d_lo : nullptr; ip.hi = net->early ? l.d_hi : nullptr; ip.flag = net->d_flag;
+                    ip.eta = net->float_inference ? l.d_eta : nullptr;
                     if (l.type == T_DENSE) { ip.Hi = ip.Wi = 1; ip.Ci = (int)p.n; }
                     else { ip.Hi = p.H; ip.Wi = p.W; ip.Ci = p.C; }
                     ip.H = l.H; ip.W = l.W; ip.C = l.C;
@@ -901,6 +943,13 @@ gp_status analyze_layers(gp_net* net, int batch) {
                 if (st != GP_OK) return st;
                 st = run_plan(net, *pl, i, false, batch);
                 if (st != GP_OK) return st;
+            }
+            if (net->float_inference && l.type == T_ADD) {
+                gp::SumEtaParams ep;
+                ep.lo = l.d_lo; ep.hi = l.d_hi; ep.u = 0x1p-24;
+                ep.ea = l.d_eta_thru; ep.eb = nullptr;
+                ep.out = l.d_eta; ep.total = l.n * batch;
+                gp::launch_sum_eta(ep, net->stream);
             }
         }
     }
@@ -1114,6 +1163,21 @@ gp_status gp_set_early_termination(gp_net* net, int32_t on) {
         net->early = want;
         net->analyzed = false;
         if (net->batch) {           // the set of layers that carry intervals changes
+            for (auto& l : net->L) free_layer_bounds(l);
+            net->batch = 0;
+        }
+    }
+    return GP_OK;
+}
+
+gp_status gp_set_float_inference(gp_net* net, int32_t on) {
+    if (!net) return GP_ERR_ARG;
+    const bool want = on != 0;
+    if (want != net->float_inference) {
+        net->float_inference = want;
+        net->analyzed = false;
+        net->topo_ready = false;    // sum layers carry intervals in this mode
+        if (net->batch) {
             for (auto& l : net->L) free_layer_bounds(l);
             net->batch = 0;
         }

@@ -565,6 +565,8 @@ void launch_cross(const CrossParams& p, hipStream_t s) {
 //   rounding   sum_j |m_j| * max(|xlo_j|,|xhi_j|)                           (slack of the float32 storage)
 //   constants of the next step: sum_j max(m_j,0)*kap_j + m_j*bias_c
 //   S1 = sum_j |m_j|                                                        (slack of the next accumulation)
+// With inference rounding (p.eta) the constants also take sum_j |m_j|*eta_j.  Since |m| = 2*max(m,0) - m this needs no
+// sum of its own: eta_j is folded into the two constants of the neuron, kap_j + 2*eta_j and bias_c - eta_j.
 // For a block over a plain layer cpos/cneg are the layer's upper/lower interval ends.  A block whose
 // coefficients already went through a ReLU substitution holds m = M*slope (M >= 0) or m = M*lam (M < 0)
 // over the ReLU's INPUT; the candidate over the ReLU's OUTPUT interval [L,U] that DeepPoly takes before
@@ -704,6 +706,7 @@ __global__ __launch_bounds__(256) void scan_tall_kernel(const ScanParams p) {
                 if (p.do_consts) {
                     if (p.kap) kp = p.kap[j + v];
                     if (p.beff) be = p.beff[c + v];
+                    if (p.eta) { const double et = p.eta[j + v]; kp += 2.0 * et; be -= et; }
                 }
                 scan_term(p.cpos != nullptr, p.do_consts != 0, mf[v], cp, cn, X, kp, be, cand, absx, cst, cstabs, s1);
             }
@@ -819,6 +822,7 @@ __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) 
             if (p.do_consts) {
                 if (p.kap) kp = p.kap[j];
                 if (p.beff) be = p.beff[c];
+                if (p.eta) { const double et = p.eta[j]; kp += 2.0 * et; be -= et; }
             }
             const int k = e - c0;
             s_cp[k] = cp; s_cn[k] = cn; s_X[k] = X; s_kp[k] = kp; s_be[k] = be;
@@ -959,7 +963,11 @@ __global__ __launch_bounds__(256) void init_kernel(const InitParams p) {
         out[e] = v;
     }
     if (blockIdx.y == 0 && (threadIdx.x & 63) == 0) {
-        p.c[r] = (p.mode == 2) ? (double)(ri.sign * p.bias[ri.cs]) : (p.mode == 3 && p.offsets) ? -(double)p.offsets[ri.cs] : 0.0;
+        double c = (p.mode == 2) ? (double)(ri.sign * p.bias[ri.cs]) : (p.mode == 3 && p.offsets) ? -(double)p.offsets[ri.cs] : 0.0;
+        // the start neuron's float32 evaluation may exceed its exact expression by eta, in either direction
+        if (p.mode == 2 && p.eta)
+            c += p.eta[(long long)ri.b * p.rm.n_start + (long long)(ri.ys * p.rm.Ws + ri.xs) * p.rm.Cs + ri.cs] * (1.0 + 0x1p-50);
+        p.c[r] = c;
         p.err[r] = 0.0;
         if (!p.seeded) p.best[r] = INFINITY;
     }
@@ -994,8 +1002,12 @@ __global__ void finalize_kernel(const FinalizeParams p) {
     int slot = 0;
     if (valid) {
         const long long g = (long long)p.rm.row0 + r;
-        const double u = p.best[r];
-        const double l = -p.best[p.rm.Rc + r];
+        double u = p.best[r];
+        double l = -p.best[p.rm.Rc + r];
+        if (p.widen > 0.0) {        // the neuron is one rounded float32 addition of the bounded exact sum (monotone)
+            u += fabs(u) * p.widen + 0x1p-1000;
+            l -= fabs(l) * p.widen + 0x1p-1000;
+        }
         if (!isfinite(u) || !isfinite(l)) *p.flag = 1;
         p.hi[g] = u;
         p.lo[g] = l;
@@ -1164,12 +1176,25 @@ __global__ __launch_bounds__(256) void ival_kernel(const IvalParams p) {
         const double bias = (double)p.bias[c];
         const double terms = (double)taps * p.Ci + 1.0;
         const double slack = (terms + 16.0) * 0x1p-52 * (mag + fabs(bias)) * (1.0 + 0x1p-30);
-        double l2 = lo + bias - slack, u2 = hi + bias + slack;
-        l2 -= fabs(l2) * 0x1p-51 + 0x1p-1000;
-        u2 += fabs(u2) * 0x1p-51 + 0x1p-1000;
-        if (!isfinite(l2) || !isfinite(u2)) *p.flag = 1;
-        p.lo[idx] = l2;
-        p.hi[idx] = u2;
+        double eta = 0.0;
+        if (p.eta) {
+            // float32 evaluation of sum_j w_j*x_j + bias in any order, fused or not: every term passes through at most
+            // `terms` roundings, so |computed - exact| <= gamma(terms)*(sum|w_j||x_j| + |bias|), gamma(k) = k*u/(1-k*u),
+            // u = 2^-24, plus half a subnormal step per product that underflows
+            const double ku = terms * 0x1p-24;
+            const double gamma = ku / (1.0 - ku) * (1.0 + 0x1p-50);
+            eta = gamma * (mag * (1.0 + (terms + 16.0) * 0x1p-52) + fabs(bias)) * (1.0 + 0x1p-50) + terms * 0x1p-149;
+            if (!isfinite(eta) || ku >= 0.5) *p.flag = 1;
+            p.eta[idx] = eta;
+        }
+        if (p.lo) {
+            double l2 = lo + bias - slack - eta, u2 = hi + bias + slack + eta;
+            l2 -= fabs(l2) * 0x1p-51 + 0x1p-1000;
+            u2 += fabs(u2) * 0x1p-51 + 0x1p-1000;
+            if (!isfinite(l2) || !isfinite(u2)) *p.flag = 1;
+            p.lo[idx] = l2;
+            p.hi[idx] = u2;
+        }
     }
 }
 void launch_ival(const IvalParams& p, hipStream_t s) {
@@ -1182,8 +1207,8 @@ __global__ void add_ival_kernel(const AddIvalParams p) {
     const long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x;
     if (i >= p.total) return;
     double l = p.alo[i] + p.blo[i], u = p.ahi[i] + p.bhi[i];
-    l -= fabs(l) * 0x1p-52 + 0x1p-1000;
-    u += fabs(u) * 0x1p-52 + 0x1p-1000;
+    l -= fabs(l) * (0x1p-52 + p.widen) + 0x1p-1000;
+    u += fabs(u) * (0x1p-52 + p.widen) + 0x1p-1000;
     if (!isfinite(l) || !isfinite(u)) *p.flag = 1;
     p.lo[i] = l;
     p.hi[i] = u;
@@ -1191,6 +1216,20 @@ __global__ void add_ival_kernel(const AddIvalParams p) {
 void launch_add_ival(const AddIvalParams& p, hipStream_t s) {
     if (p.total <= 0) return;
     hipLaunchKernelGGL(add_ival_kernel, dim3((unsigned)((p.total + 255) / 256)), dim3(256), 0, s, p);
+}
+
+__global__ void sum_eta_kernel(const SumEtaParams p) {
+    const long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x;
+    if (i >= p.total) return;
+    double e = 0.0;
+    if (p.lo) e = fmax(fabs(p.lo[i]), fabs(p.hi[i])) * p.u;
+    if (p.ea) e += p.ea[i];
+    if (p.eb) e += p.eb[i];
+    p.out[i] = e * (1.0 + 0x1p-50);
+}
+void launch_sum_eta(const SumEtaParams& p, hipStream_t s) {
+    if (p.total <= 0) return;
+    hipLaunchKernelGGL(sum_eta_kernel, dim3((unsigned)((p.total + 255) / 256)), dim3(256), 0, s, p);
 }
 
 __global__ void seed_kernel(const SeedParams p) {

@@ -90,6 +90,8 @@ struct ScanParams {        // per-row reductions over a block
     const double* xhi;
     const double* kap;     // constant per unit of positive coefficient (ReLU upper intercept / slope); null if none
     const double* beff;    // [C] bias of the affine layer(s) crossed next; null if none
+    const double* eta;     // [batch][n] constant per unit of |coefficient|: how far a float32 evaluation of the neuron
+                           //   can be from its exact affine expression (Section 4.1, inference rounding); null: none
     double e1_a, e1_b;     // accumulation-error constants of the next crossing(s), times xmax_a[box] / xmax_b[box]
     const double* xmax_a;
     const double* xmax_b;
@@ -122,6 +124,7 @@ struct InitParams {
     int Cs;                // channels of the start layer
     const float* wt;       // [tap][Cs][C] (predecessor channels innermost); dense: [Cs][nelem]
     const float* bias;     // [Cs]
+    const double* eta;     // mode 2: [batch][n_start] float32 evaluation error of the start neurons (added to c); null: none
     double* c; double* err; double* best;
     int seeded;            // best already holds the rows' interval image: leave it
 };
@@ -132,6 +135,7 @@ struct FinalizeParams {
     double* lo; double* hi;   // [batch][n_start] of the start layer
     double* xmax;             // [batch] running max of |bounds| of that layer, per box
     int* flag;                // set to 1 on NaN/Inf
+    double widen;             // each end moves outward by widen*|end| (a sum layer's one float32 rounding); 0: none
 };
 
 struct ReluParams {
@@ -157,15 +161,23 @@ struct IvalParams {          // forward interval analysis of an affine layer
     const double* plo; const double* phi;   // predecessor intervals [batch][Hi*Wi*Ci], H,W,C order
     const float* wt;         // [tap][C][Ci] (dense: [C][n_in], seen as one tap over a 1x1 layer with n_in channels)
     const float* bias;       // [C]
-    double* lo; double* hi;  // [batch][H*W*C]
+    double* lo; double* hi;  // [batch][H*W*C]; null: intervals not wanted
+    double* eta;             // [batch][H*W*C] out: float32 evaluation error of each neuron (also widens lo, hi); null: none
     int* flag;
     int Hi, Wi, Ci, H, W, C, kh, kw, sh, sw, ph, pw, batch;
+};
+struct SumEtaParams {        // out = u*max(|lo|,|hi|) + ea + eb (each part optional), rounded up
+    const double *lo, *hi; double u;
+    const double *ea, *eb;
+    double* out;
+    long long total;
 };
 struct AddIvalParams {       // sum layer: interval sum, rounded outward
     const double *alo, *ahi, *blo, *bhi;
     double *lo, *hi;
     long long total;
     int* flag;
+    double widen;            // relative outward widening of each end (one float32 rounding); 0: none
 };
 struct SeedParams {          // best[r] = upper end, best[Rc0 + r] = -(lower end) of task row0 + r
     const double* lo; const double* hi;
@@ -203,6 +215,7 @@ void launch_fill_f64(double* p, double v, long long n, hipStream_t s);
 void launch_fill_i32(int* p, int v, long long n, hipStream_t s);
 void launch_ival(const IvalParams& p, hipStream_t s);
 void launch_add_ival(const AddIvalParams& p, hipStream_t s);
+void launch_sum_eta(const SumEtaParams& p, hipStream_t s);
 void launch_seed(const SeedParams& p, hipStream_t s);
 void launch_term(const TermParams& p, int* count, hipStream_t s);      // flags, counts, scan; *count (device) = tasks kept
 void launch_compact(const CompactParams& p, hipStream_t s);

@@ -48,10 +48,12 @@ def make_oracle(net: wl.Net, **opts):
     return o
 
 
-def oracle_with_gpu_ties(net: wl.Net, o: OracleNet, g, center, eps, batch_index=0, clip=(0.0, 1.0), tie=1e-4):
+def oracle_with_gpu_ties(net: wl.Net, o: OracleNet, g, center, eps, batch_index=0, clip=(0.0, 1.0), tie=1e-4,
+                         extra_layers=()):
     """Oracle analysis layer by layer.  The choice lam in {0,1} of the lower relaxation is the only
     discontinuity of the analysis: where the oracle's own interval is within `tie` of the switching
-    point u = -l, it is told to take the GPU's choice.  Returns the number of such neurons."""
+    point u = -l, it is told to take the GPU's choice.  Returns the number of such neurons.
+    extra_layers: layers to bound besides the inputs of ReLU layers and the last layer."""
     o.set_ball(center, eps, clip[0], clip[1])
     forced = 0
     for lid in range(1, o.num_layers):
@@ -66,7 +68,7 @@ def oracle_with_gpu_ties(net: wl.Net, o: OracleNet, g, center, eps, batch_index=
             else:
                 o.set_lambda_override(lid, None)
             o.analyze_layer(lid)
-        elif lid in analysed_layers(net):
+        elif lid in analysed_layers(net) or lid in extra_layers:
             o.analyze_layer(lid)
     return forced
 
@@ -125,6 +127,18 @@ def check_samples_inside(net, g, lo0, hi0, n, rng, batch_index=0, what=""):
         v = vals[lid]
         assert np.all(v.min(0) >= glo.astype(np.float64)), f"{what} layer {lid}: sampled output below the lower bound"
         assert np.all(v.max(0) <= ghi.astype(np.float64)), f"{what} layer {lid}: sampled output above the upper bound"
+
+
+def float_inference_layers(net: wl.Net):
+    """Layers that carry bounds in float32-inference mode besides the usual ones: every layer an affine layer reads
+    (its intervals enter the reader's error constant) and every sum layer (its rounding is relative to its interval)."""
+    out = set()
+    for i, L in enumerate(net.layers, start=1):
+        if L["type"] in ("dense", "conv") and L["src"] > 0 and net.layers[L["src"] - 1]["type"] != "relu":
+            out.add(L["src"])
+        if L["type"] == "add":
+            out.add(i)
+    return sorted(out)
 
 
 def bounded_affine_layers(net: wl.Net):

@@ -7,8 +7,9 @@ import pytest
 import torch
 
 import workloads as wl
-from helpers import ball_box
-from parity import check_samples_inside, compare_all, make_gpu, make_oracle, oracle_with_gpu_ties
+from helpers import ball_box, forward_float32
+from parity import (analysed_layers, check_samples_inside, compare_all, compare_layer, float_inference_layers, make_gpu,
+                    make_oracle, oracle_with_gpu_ties)
 from test_gpu_early_term import check_early
 
 pytestmark = pytest.mark.gpu
@@ -81,3 +82,35 @@ def test_random_topology(seed):
     g.set_early_termination(True)
     g.analyze(c, net.eps)
     check_early(net, g, c, net.eps, what=net.name + " early", samples=100, seed=seed)
+
+
+@pytest.mark.parametrize("seed", range(0, 40, 2))
+def test_random_topology_float_inference(seed):
+    """Section 4.1, rounding of the inference: same comparison in float32-inference mode, plus float32 evaluations of
+    the network in several summation orders at corners of the box."""
+    net = random_net(seed)
+    rng = np.random.default_rng(20_000 + seed)
+    c = np.random.default_rng(10_000 + seed).random(net.n_in).astype(np.float32)
+    g = make_gpu(net)
+    g.set_float_inference(True)
+    if seed % 4 == 2:
+        g.set_early_termination(True)
+    g.analyze(c, net.eps)
+    layers = sorted(set(analysed_layers(net)) | set(float_inference_layers(net)))
+    if seed % 4 == 0:
+        o = make_oracle(net)
+        o.set_float_inference(True)
+        oracle_with_gpu_ties(net, o, g, c, net.eps, extra_layers=float_inference_layers(net))
+        for lid in layers:
+            olo, ohi = o.get_bounds(lid)
+            glo, ghi = g.get_bounds_f64(lid)
+            compare_layer(glo, ghi, olo, ohi, f"{net.name} layer {lid}")
+    lo0, hi0 = ball_box(c, net.eps)
+    for k in range(3):
+        x = c if k == 0 else np.clip(c.astype(np.float64) + net.eps * 0.999 * rng.choice([-1.0, 1.0], c.size), lo0, hi0).astype(np.float32)
+        for order in ("forward", "random", "descending", "pairwise"):
+            vals = forward_float32(net, x, order, rng)
+            for lid in layers:
+                glo, ghi = g.get_bounds_f64(lid)
+                v = vals[lid].astype(np.float64)
+                assert np.all(v >= glo) and np.all(v <= ghi), (net.name, order, lid)

@@ -235,12 +235,14 @@ def test_certification_margins_cover_float32_outputs():
 
 
 def rounded_sum_net():
-    """x -> add(x, relu(D x)) -> first component, with D = 2^-25 * identity.  At x = (1, 1) every affine neuron is exact
-    in float32 (one non-zero product, zero bias), the residual sum 1 + 2^-25 is not: it rounds to 1."""
+    """x -> add(E relu(D x), x) -> first component, with D = 2^-25 * identity and E = identity.  At x = (1, 1) every
+    affine neuron is exact in float32 (one non-zero product, zero bias), the residual sum 1 + 2^-25 is not: it rounds
+    to 1."""
     net = wl.Net("rounded_sum", (2, 1, 1))
     d = net.dense(0, np.array([[2.0 ** -25, 0.0], [0.0, 2.0 ** -25]], np.float32), np.zeros(2, np.float32))
     r = net.relu(d)
-    s = net.add(0, r)
+    e = net.dense(r, np.eye(2, dtype=np.float32), np.zeros(2, np.float32))
+    s = net.add(e, 0)
     net.dense(s, np.array([[1.0, 0.0]], np.float32), np.zeros(1, np.float32))
     return net, s
 
