@@ -68,6 +68,15 @@ struct F4 {
     float v[4];
 };
 
+// a value every lane of the wave holds alike, moved to scalar registers: what is derived from it (loop bounds, tap
+// numbers, scalar offsets and resource descriptors of buffer loads) then stays scalar; left in vector registers the
+// compiler would wrap every such load into a loop over the distinct values
+__device__ __forceinline__ unsigned long long wave_uniform(unsigned long long v) {
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+    return ((unsigned long long)hi << 32) | lo;
+}
+
 constexpr uint32_t kOOB = 0x80000000u;   // byte offset beyond every buffer range: the load returns 0
 
 // 4 consecutive floats at byte offset `off` of a buffer resource; offsets beyond the resource's range
@@ -95,6 +104,23 @@ __device__ __forceinline__ F4 buf_ld4(__amdgpu_buffer_rsrc_t rsrc, uint32_t off,
 // take the upper line, negative ones the lower line, for an upper bound).
 __device__ __forceinline__ float relax_factor(double a, float g) {
     return a >= 0.0 ? fabsf(g) : (signbit(g) ? 0.f : 1.f);
+}
+
+// Epilogue bookkeeping of one row: offset of the row's output pixel (window pixel (pa,pb)) in the packed relaxation
+// of the input layer, [batch][Ho*Wo*Co], and in the addend block (-1 when the pixel lies outside the addend's window).
+__device__ __forceinline__ void epilogue_row_info(const CrossParams& p, const RowInfo& ri, int r, int pa, int pb,
+                                                  long long& ridx, long long& aoff) {
+    const int N = p.Co;
+    const int A = clampi(p.oSy * ri.ys - p.oPy, 0, p.Ho - p.owy) + pa;
+    const int B = clampi(p.oSx * ri.xs - p.oPx, 0, p.Wo - p.owx) + pb;
+    ridx = (long long)ri.b * ((long long)p.Ho * p.Wo * N) + (long long)(A * p.Wo + B) * N;
+    aoff = -1;
+    if (p.add.data) {
+        const int ay = A - clampi(p.add.Sy * ri.ys - p.add.Py, 0, p.add.H - p.add.wy);
+        const int ax = B - clampi(p.add.Sx * ri.xs - p.add.Px, 0, p.add.W - p.add.wx);
+        if (ay >= 0 && ay < p.add.wy && ax >= 0 && ax < p.add.wx)
+            aoff = ((long long)r * p.add.wy * p.add.wx + (long long)(ay * p.add.wx + ax)) * N;
+    }
 }
 
 // LDS-tiled implicit GEMM on float64 MFMA (16x16x4).
@@ -138,6 +164,10 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
     __shared__ __attribute__((aligned(16))) double As[2][BM][LDK];
     __shared__ __attribute__((aligned(16))) double Bs[2][BN][LDK];
     __shared__ unsigned long long s_tapmask;
+    // per tile row, for the epilogue: where the row's output pixel sits in the relaxation array of the input layer and
+    // in the addend block (-1: outside its window).  Worked out once per row by the thread that sets up the row's
+    // loads; the 8 rows of an epilogue lane would otherwise each repeat the row's index arithmetic.
+    __shared__ long long s_ridx[BM], s_aoff[BM];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
@@ -200,6 +230,7 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
             a_tx[i] = (uint32_t)(xlo - a_oix[i]) | ((uint32_t)max(xhi - xlo, 0) << 16);
         }
         a_rowoff[i] = ((uint32_t)rl * row_elems + (uint32_t)q4) * 4u;
+        if ((tid & 3) == 0 && a_ok[i]) epilogue_row_info(p, ri, r_tile + rl, pa, pb, s_ridx[rl], s_aoff[rl]);
     }
     // per-thread byte offsets for the current tap: A row (kOOB when the tap misses the row's window), B column
     uint32_t a_voff[APT], b_voff[BPT];
@@ -247,7 +278,7 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
         __syncthreads();
         if (lane == 0) atomicOr(&s_tapmask, mine);
         __syncthreads();
-        tapmask = s_tapmask;
+        tapmask = wave_uniform(s_tapmask);
     } else if (taps < 64) {
         tapmask = (1ull << taps) - 1;
     }
@@ -484,33 +515,234 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
 
     // ---- epilogue: (+ residual addend) (* ReLU substitution of the destination layer) -> one rounding to
     // float32 -> store.  D[i][j]: register r of lane l holds i = 4*r + l/16, j = l%16.
+    __syncthreads();                                   // s_ridx, s_aoff (a tile without any tap has met no barrier yet)
     const bool has_add = p.add.data != nullptr;
-    const bool need_pos = has_add || p.out_grl != nullptr;
+    // a dense layer's relaxation entry depends on the row's box only: when the whole tile lies in one box (within the
+    // +x half and within the -x half rows are ordered by box) the lane's columns need one load each instead of one per row
+    float g_same[TN];
+    bool same_box = false;
+    if constexpr (DENSE) {
+        same_box = p.out_grl != nullptr && s_ridx[0] == s_ridx[rows_here - 1] &&
+                   (r_tile + rows_here <= p.rm.Rc || r_tile >= p.rm.Rc);
+        if (same_box) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int n = n0 + wn * WTN + j * 16 + lm;
+                g_same[j] = n < N ? p.out_grl[s_ridx[0] + n] : 0.f;
+            }
+        }
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
         for (int r4 = 0; r4 < (SMALLN ? 1 : 4); ++r4) {
             // 16x16x4: register r4 of the lane is row 4*r4 + l/16; 4x4x4: the lane's one value is row 4*((l%16)/4) + l/16
-            const int r = r_tile + wm * WTM + i * 16 + (SMALLN ? 4 * (lm >> 2) : 4 * r4) + lk;
+            const int rl = wm * WTM + i * 16 + (SMALLN ? 4 * (lm >> 2) : 4 * r4) + lk;
+            const int r = r_tile + rl;
             if (r >= p.nrows) continue;
-            const float* add_src = nullptr;
-            size_t ridx = 0;
-            if (need_pos) {
-                const RowInfo ri = row_info(p.rm, r);
-                const int A = clampi(p.oSy * ri.ys - p.oPy, 0, p.Ho - p.owy) + pa;
-                const int B = clampi(p.oSx * ri.xs - p.oPx, 0, p.Wo - p.owx) + pb;
-                ridx = (size_t)ri.b * ((size_t)p.Ho * p.Wo * N) + (size_t)(A * p.Wo + B) * N;
-                if (has_add) {
-                    const int ay = A - clampi(p.add.Sy * ri.ys - p.add.Py, 0, p.add.H - p.add.wy);
-                    const int ax = B - clampi(p.add.Sx * ri.xs - p.add.Px, 0, p.add.W - p.add.wx);
-                    if (ay >= 0 && ay < p.add.wy && ax >= 0 && ax < p.add.wx)
-                        add_src = p.add.data + ((size_t)r * p.add.wy * p.add.wx + (size_t)(ay * p.add.wx + ax)) * N;
-                }
-            }
+            const long long ridx = s_ridx[rl];
+            const long long aoff = has_add ? s_aoff[rl] : -1;
+            const float* add_src = aoff >= 0 ? p.add.data + aoff : nullptr;
             float* out_row = p.out + ((size_t)r * opix + pix) * N;
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const int n = SMALLN ? n0 + (lm & 3) : n0 + wn * WTN + j * 16 + lm;
+                if (n >= N) continue;
+                double v = acc[i][j][r4];
+                if (add_src) v += (double)add_src[n];
+                if (p.out_grl) v *= (double)relax_factor(v, (DENSE && same_box) ? g_same[j] : p.out_grl[ridx + n]);
+                out_row[n] = (float)v;
+            }
+        }
+    }
+}
+
+template <int TM, int TN_, bool VEC>
+__global__ __launch_bounds__(256) void cross_direct_kernel(const CrossParams p) {
+    constexpr bool SMALLN = (TN_ == 0);
+    constexpr int TN = SMALLN ? 1 : TN_;
+    constexpr int BK = 16;
+    constexpr int BM = 64 * TM;                      // rows per work-group (4 waves of 16*TM rows)
+    constexpr int BN = SMALLN ? 4 : 16 * TN;
+    // epilogue bookkeeping per row (see cross_kernel); written and read by the same wave, so program order suffices
+    __shared__ long long s_ridx[BM], s_aoff[BM];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lk = lane >> 4, lm = lane & 15;
+    const int opix = p.owy * p.owx;
+    const uint32_t total = (uint32_t)p.ntiles_n * (uint32_t)opix * (uint32_t)p.ntiles_m;
+    const uint32_t per_xcd = (total + 7u) >> 3;
+    const uint32_t logical = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);     // see cross_kernel
+    if (logical >= total) return;
+    const uint32_t t2 = fast_div(logical, p.div_ntiles_n);
+    const int nt = (int)(logical - t2 * (uint32_t)p.ntiles_n);
+    const uint32_t rt = fast_div(t2, p.div_opix);
+    const int pix = (int)(t2 - rt * (uint32_t)opix);
+    const int r_wave = (int)rt * BM + wave * 16 * TM;          // first row of this wave
+    if (r_wave >= p.nrows) return;                             // no barrier anywhere below
+    const int pa = (int)fast_div((uint32_t)pix, p.div_owx), pb = pix - pa * p.owx;
+    const int n0 = nt * BN;
+    const int Ck = p.in.C, N = p.Co;
+    const int taps = p.kh * p.kw;
+    const int kchunks = (Ck + BK - 1) / BK;
+    const uint32_t row_elems = (uint32_t)(p.in.wy * p.in.wx * Ck);
+    const int rows_here = min(16 * TM, p.nrows - r_wave);
+    const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(p.in.data + (size_t)r_wave * row_elems), 0, (int)((uint32_t)rows_here * row_elems * 4u), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrcB =
+        __builtin_amdgcn_make_buffer_rsrc((void*)p.wt, 0, (int)((uint32_t)taps * N * Ck * 4u), 0x00020000);
+
+    const int q4 = 4 * lk;                       // this lane's channel quad inside a K step
+    uint32_t a_rowoff[TM];
+    int a_ydiv[TM], a_xdiv[TM], a_ymod[TM], a_xmod[TM], a_oiy[TM], a_oix[TM];
+    uint32_t a_ty[TM], a_tx[TM];
+    bool a_ok[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int rl = i * 16 + lm;
+        a_ok[i] = rl < rows_here;
+        const RowInfo ri = row_info(p.rm, r_wave + (a_ok[i] ? rl : 0));
+        const uint32_t yy0 = (uint32_t)(clampi(p.oSy * ri.ys - p.oPy, 0, p.Ho - p.owy) + pa + p.ph);
+        const uint32_t xx0 = (uint32_t)(clampi(p.oSx * ri.xs - p.oPx, 0, p.Wo - p.owx) + pb + p.pw);
+        const uint32_t yd = fast_div(yy0, p.div_sh), xd = fast_div(xx0, p.div_sw);
+        a_ydiv[i] = (int)yd; a_ymod[i] = (int)(yy0 - yd * (uint32_t)p.sh);
+        a_xdiv[i] = (int)xd; a_xmod[i] = (int)(xx0 - xd * (uint32_t)p.sw);
+        a_oiy[i] = clampi(p.in.Sy * ri.ys - p.in.Py, 0, p.in.H - p.in.wy);
+        a_oix[i] = clampi(p.in.Sx * ri.xs - p.in.Px, 0, p.in.W - p.in.wx);
+        const int ty = p.in.tSy * ri.ys - p.in.tPy, tx = p.in.tSx * ri.xs - p.in.tPx;     // exact window, see cross_kernel
+        const int ylo = max(ty, a_oiy[i]), yhi = min(ty + p.in.tWy, a_oiy[i] + p.in.wy);
+        const int xlo = max(tx, a_oix[i]), xhi = min(tx + p.in.tWx, a_oix[i] + p.in.wx);
+        a_ty[i] = (uint32_t)(ylo - a_oiy[i]) | ((uint32_t)max(yhi - ylo, 0) << 16);
+        a_tx[i] = (uint32_t)(xlo - a_oix[i]) | ((uint32_t)max(xhi - xlo, 0) << 16);
+        a_rowoff[i] = ((uint32_t)rl * row_elems + (uint32_t)q4) * 4u;
+        if (lk == 0 && a_ok[i])
+            epilogue_row_info(p, ri, r_wave + rl, pa, pb, s_ridx[wave * 16 * TM + rl], s_aoff[wave * 16 * TM + rl]);
+    }
+    uint32_t a_voff[TM], b_voff[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = SMALLN ? n0 + (lm & 3) : n0 + j * 16 + lm;
+        b_voff[j] = n < N ? ((uint32_t)n * (uint32_t)Ck + (uint32_t)q4) * 4u : kOOB;
+    }
+    auto set_tap = [&](int t) -> bool {
+        const int f = (int)fast_div((uint32_t)t, p.div_kw), g = t - f * p.kw;
+        const int fdiv = (int)fast_div((uint32_t)f, p.div_sh), fmod = f - fdiv * p.sh;
+        const int gdiv = (int)fast_div((uint32_t)g, p.div_sw), gmod = g - gdiv * p.sw;
+        bool any = false;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int y = a_ydiv[i] - fdiv, x = a_xdiv[i] - gdiv;
+            const int yi = y - a_oiy[i], xi = x - a_oix[i];
+            const bool ok = a_ok[i] && a_ymod[i] == fmod && a_xmod[i] == gmod &&
+                            (unsigned)y < (unsigned)p.in.H && (unsigned)x < (unsigned)p.in.W &&
+                            (unsigned)(yi - (int)(a_ty[i] & 0xffffu)) < (a_ty[i] >> 16) &&
+                            (unsigned)(xi - (int)(a_tx[i] & 0xffffu)) < (a_tx[i] >> 16);
+            a_voff[i] = ok ? a_rowoff[i] + (uint32_t)(yi * p.in.wx + xi) * (uint32_t)(Ck * 4) : kOOB;
+            any = any || ok;
+        }
+        return any;
+    };
+    // taps some row of this wave can use (bit t; filters with more than 64 taps keep all)
+    unsigned long long tapmask = ~0ull;
+    if (taps <= 64) {
+        unsigned long long mine = 0;
+        for (int t = 0; t < taps; ++t)
+            if (set_tap(t)) mine |= 1ull << t;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) mine |= __shfl_xor(mine, off, 64);
+        tapmask = wave_uniform(mine);
+    }
+    auto next_tap = [&](int t) -> int {
+        while (t < taps && t < 64 && !((tapmask >> t) & 1ull)) ++t;
+        return t;
+    };
+    int n_taps = 0;
+    for (int t = next_tap(0); t < taps; t = next_tap(t + 1)) ++n_taps;
+    const int nIt = n_taps * kchunks;
+
+    int ld_t = next_tap(0), ld_d0 = 0;
+    if (ld_t < taps) set_tap(ld_t);
+    F4 a_raw[TM], b_raw[TN];
+    auto load_step = [&]() {
+        const int rem = Ck - ld_d0;
+        const uint32_t soffA = (uint32_t)ld_d0 * 4u;
+        const uint32_t soffB = ((uint32_t)ld_t * (uint32_t)N * (uint32_t)Ck + (uint32_t)ld_d0) * 4u;
+        if (VEC && rem >= BK) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                uint4_t v = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, (int)a_voff[i], (int)soffA, 0);
+                a_raw[i].v[0] = __uint_as_float(v.x); a_raw[i].v[1] = __uint_as_float(v.y);
+                a_raw[i].v[2] = __uint_as_float(v.z); a_raw[i].v[3] = __uint_as_float(v.w);
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                uint4_t v = __builtin_amdgcn_raw_buffer_load_b128(rsrcB, (int)b_voff[j], (int)soffB, 0);
+                b_raw[j].v[0] = __uint_as_float(v.x); b_raw[j].v[1] = __uint_as_float(v.y);
+                b_raw[j].v[2] = __uint_as_float(v.z); b_raw[j].v[3] = __uint_as_float(v.w);
+            }
+        } else {
+            const bool dok = q4 < rem;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                a_raw[i] = buf_ld4<VEC>(rsrcA, (dok && a_voff[i] != kOOB) ? a_voff[i] + soffA : kOOB, rem - q4);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                b_raw[j] = buf_ld4<VEC>(rsrcB, (dok && b_voff[j] != kOOB) ? b_voff[j] + soffB : kOOB, rem - q4);
+        }
+        ld_d0 += BK;
+        if (ld_d0 >= Ck) {
+            ld_d0 = 0;
+            ld_t = next_tap(ld_t + 1);
+            if (ld_t < taps) set_tap(ld_t);
+        }
+    };
+
+    double4_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = double4_t{0.0, 0.0, 0.0, 0.0};
+
+    if (nIt > 0) load_step();
+    for (int it = 0; it < nIt; ++it) {
+        double av[TM][4], bv[TN][4];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) av[i][k] = (double)a_raw[i].v[k];
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) bv[j][k] = (double)b_raw[j].v[k];
+        if (it + 1 < nIt) load_step();             // in flight while the MFMAs below run
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    if constexpr (SMALLN)
+                        acc[i][0][0] = __builtin_amdgcn_mfma_f64_4x4x4f64(av[i][k], bv[0][k], acc[i][0][0], 0, 0, 0);
+                    else
+                        acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[i][k], bv[j][k], acc[i][j], 0, 0, 0);
+                }
+    }
+
+    // ---- epilogue, as in cross_kernel
+    const bool has_add = p.add.data != nullptr;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int r4 = 0; r4 < (SMALLN ? 1 : 4); ++r4) {
+            const int rl = i * 16 + (SMALLN ? 4 * (lm >> 2) : 4 * r4) + lk;
+            const int r = r_wave + rl;
+            if (r >= p.nrows) continue;
+            const long long ridx = s_ridx[wave * 16 * TM + rl];
+            const long long aoff = has_add ? s_aoff[wave * 16 * TM + rl] : -1;
+            const float* add_src = aoff >= 0 ? p.add.data + aoff : nullptr;
+            float* out_row = p.out + ((size_t)r * opix + pix) * N;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int n = SMALLN ? n0 + (lm & 3) : n0 + j * 16 + lm;
                 if (n >= N) continue;
                 double v = acc[i][j][r4];
                 if (add_src) v += (double)add_src[n];
@@ -519,6 +751,20 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
             }
         }
     }
+}
+
+template <int TM, int TN>
+static void launch_cross_direct(const CrossParams& p0, hipStream_t s) {
+    constexpr int BM = 64 * TM, BN = TN == 0 ? 4 : 16 * TN;
+    CrossParams p = p0;
+    p.ntiles_m = (p.nrows + BM - 1) / BM;
+    p.ntiles_n = (p.Co + BN - 1) / BN;
+    p.div_ntiles_n = make_fastdiv((uint32_t)p.ntiles_n);
+    p.div_opix = make_fastdiv((uint32_t)(p.owy * p.owx));
+    const long long total = (long long)p.ntiles_m * p.ntiles_n * p.owy * p.owx;
+    const unsigned blocks = (unsigned)(((total + 7) / 8) * 8);
+    if ((p.in.C & 3) == 0) hipLaunchKernelGGL((cross_direct_kernel<TM, TN, true>), dim3(blocks), dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((cross_direct_kernel<TM, TN, false>), dim3(blocks), dim3(256), 0, s, p);
 }
 
 template <int BM, int BN>
@@ -544,14 +790,29 @@ static void launch_cross_t(const CrossParams& p0, hipStream_t s) {
     else hipLaunchKernelGGL((cross_kernel<BM, BN, false, false>), dim3(blocks), dim3(256), 0, s, p);
 }
 
+#ifndef CROSS_TM4
+#define CROSS_TM4 2
+#endif
+#ifndef CROSS_TM16
+#define CROSS_TM16 2
+#endif
+#ifndef CROSS_TM32
+#define CROSS_TM32 2
+#endif
 void launch_cross(const CrossParams& p, hipStream_t s) {
     if (p.nrows <= 0 || p.Co <= 0) return;
     const int N = p.Co;
     // tile shapes measured on MI355X: 64x64 beats the larger tiles (their lower occupancy costs more than their
     // higher arithmetic intensity gains); narrow layers take a tall tile so that fewer MFMA columns are padding
+#ifdef CROSS_OLD_TALL
     if (N <= 4) { launch_cross_t<128, 4>(p, s); return; }
     if (N <= 16) { launch_cross_t<128, 16>(p, s); return; }
     if (N <= 32) { launch_cross_t<128, 32>(p, s); return; }
+#else
+    if (N <= 4) { launch_cross_direct<CROSS_TM4, 0>(p, s); return; }
+    if (N <= 16) { launch_cross_direct<CROSS_TM16, 1>(p, s); return; }
+    if (N <= 32) { launch_cross_direct<CROSS_TM32, 2>(p, s); return; }
+#endif
     // few rows (one input at a time): smaller tiles so that the launch still covers the chip
     const long long wg64 = (long long)((p.nrows + 63) / 64) * ((N + 63) / 64) * p.owy * p.owx;
     if (wg64 < 256) { launch_cross_t<32, 32>(p, s); return; }
