@@ -702,9 +702,7 @@ __global__ __launch_bounds__(256) void cross_direct_kernel(const CrossParams p) 
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = double4_t{0.0, 0.0, 0.0, 0.0};
 
-    if (nIt > 0) load_step();
-    for (int it = 0; it < nIt; ++it) {
-        double av[TM][4], bv[TN][4];
+    auto convert = [&](double (&av)[TM][4], double (&bv)[TN][4]) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -713,7 +711,8 @@ __global__ __launch_bounds__(256) void cross_direct_kernel(const CrossParams p) 
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int k = 0; k < 4; ++k) bv[j][k] = (double)b_raw[j].v[k];
-        if (it + 1 < nIt) load_step();             // in flight while the MFMAs below run
+    };
+    auto mfmas = [&](const double (&av)[TM][4], const double (&bv)[TN][4]) {
 #pragma unroll
         for (int k = 0; k < 4; ++k)
 #pragma unroll
@@ -725,6 +724,55 @@ __global__ __launch_bounds__(256) void cross_direct_kernel(const CrossParams p) 
                     else
                         acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[i][k], bv[j][k], acc[i][j], 0, 0, 0);
                 }
+    };
+    if (VEC && (Ck & (BK - 1)) == 0) {
+        // Whole K steps only.  One step is ONE basic block - convert the step's raw values, issue the next step's loads,
+        // then the MFMAs - with the order pinned: the loads stay in flight while the MFMAs run.  (With branches between
+        // them the compiler moves the MFMAs ahead of the loads and every step waits for its own loads.)  The loads are
+        // unconditional: behind the last step they re-read the current rows (A) and run off the filter's range (B, zeros).
+        auto issue = [&]() {
+            const uint32_t soffA = (uint32_t)ld_d0 * 4u;
+            const uint32_t soffB = ((uint32_t)ld_t * (uint32_t)N * (uint32_t)Ck + (uint32_t)ld_d0) * 4u;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                uint4_t v = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, (int)a_voff[i], (int)soffA, 0);
+                a_raw[i].v[0] = __uint_as_float(v.x); a_raw[i].v[1] = __uint_as_float(v.y);
+                a_raw[i].v[2] = __uint_as_float(v.z); a_raw[i].v[3] = __uint_as_float(v.w);
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                uint4_t v = __builtin_amdgcn_raw_buffer_load_b128(rsrcB, (int)b_voff[j], (int)soffB, 0);
+                b_raw[j].v[0] = __uint_as_float(v.x); b_raw[j].v[1] = __uint_as_float(v.y);
+                b_raw[j].v[2] = __uint_as_float(v.z); b_raw[j].v[3] = __uint_as_float(v.w);
+            }
+        };
+        auto advance = [&]() {                      // the step the next loads are for (uniform)
+            ld_d0 += BK;
+            if (ld_d0 >= Ck) {
+                ld_d0 = 0;
+                ld_t = next_tap(ld_t + 1);
+                if (ld_t < taps) set_tap(ld_t);
+            }
+        };
+        if (nIt > 0) { issue(); advance(); }
+        for (int it = 0; it < nIt; ++it) {
+            double av[TM][4], bv[TN][4];
+            convert(av, bv);
+            __builtin_amdgcn_sched_barrier(0);
+            issue();
+            __builtin_amdgcn_sched_barrier(0);
+            mfmas(av, bv);
+            __builtin_amdgcn_sched_barrier(0);
+            advance();
+        }
+    } else {
+        if (nIt > 0) load_step();
+        for (int it = 0; it < nIt; ++it) {
+            double av[TM][4], bv[TN][4];
+            convert(av, bv);
+            if (it + 1 < nIt) load_step();
+            mfmas(av, bv);
+        }
     }
 
     // ---- epilogue, as in cross_kernel
