@@ -131,10 +131,12 @@ __device__ __forceinline__ void epilogue_row_info(const CrossParams& p, const Ro
 //   uses value j in MFMA step j, i.e. step j contracts the channel set {j, 4+j, 8+j, 12+j}.  A and B use
 //   the same permutation, so every product pairs the right channels; only the summation order differs,
 //   which the rounding slack covers for any order.
-//   Vector instructions do not overlap float64 MFMAs on this chip (each costs 4-6 cycles of MFMA time), so
-//   everything outside the MFMAs is kept to a few instructions per K step: 32-bit offsets into per-tile buffer
-//   resources, range-checked loads instead of masks, tap geometry without divisions.
-//   The K loop is software-pipelined (see the loop itself); tiles of 4 columns use the 4x4x4 instruction.
+//   Vector instructions do not overlap float64 MFMAs on this chip (each costs 4-6 cycles of MFMA time; the chip's
+//   float64 vector and matrix peaks are the same number), so everything outside the MFMAs is kept to a few
+//   instructions per K step: 32-bit offsets into per-tile buffer resources, range-checked loads instead of masks,
+//   tap geometry without divisions, per-row index arithmetic done once per row.
+//   The K loop is software-pipelined (see the loop itself).  Layers with at most 32 input channels take
+//   cross_direct_kernel below.
 // Work decomposition: a work-group = (tile of BM rows, output pixel of the window, tile of BN input
 // channels).  All rows of a work-group therefore produce the SAME window pixel, so the filter taps
 // that can reach that pixel from inside the rows' windows are (nearly) the same for all of them: the taps
@@ -151,12 +153,7 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
     constexpr int WAVES_N = (BN >= 64 || BM < 64) ? 2 : 1;
     constexpr int WAVES_M = 4 / WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
-    // BN == 4: layers with at most 4 input channels (the image).  A 16-column MFMA tile would be 13/16 padding
-    // there; the 4x4x4 instruction (4 independent 4x4 blocks) keeps 16 rows per instruction with 4 columns.  Its
-    // operand layout: lane l holds A[row l%16][k l/16] (as for 16x16x4), B[k l/16][column l%4] (the same B for
-    // every block), and receives D[row 4*((l%16)/4) + l/16][column l%4].
-    constexpr bool SMALLN = (BN == 4);
-    constexpr int TM = WTM / 16, TN = SMALLN ? 1 : WTN / 16;
+    constexpr int TM = WTM / 16, TN = WTN / 16;
     constexpr int APT = (BM + 63) / 64;             // A rows per thread
     constexpr int BPT = (BN + 63) / 64;             // B columns per thread
     static_assert(TM >= 1 && TN >= 1, "tile");
@@ -336,12 +333,12 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
     double* const a_st = &As[0][ld_row][q4];
     double* const b_st = &Bs[0][ld_row][q4];
     const double* const a_ld = &As[0][wm * WTM + lm][4 * lk];
-    const double* const b_ld = &Bs[0][SMALLN ? (lm & 3) : (wn * WTN + lm)][4 * lk];
+    const double* const b_ld = &Bs[0][wn * WTN + lm][4 * lk];
     // Last K step of a dense layer whose channel count is no multiple of 16 (e.g. 500 = 31*16 + 4): only tail_q of
     // the 4 channel quads exist.  Stored as usual they would sit in k-positions 0..4*tail_q-1, one in each of the 4
     // MFMA steps of the tile; stored transposed (channel j of quad q at k-position 4*j + q, for A and B alike) quad q
     // falls entirely into MFMA step q, and the steps >= tail_q, which would multiply zeros, are left out.
-    const int tail_q = (DENSE && VEC && !SMALLN && (Ck & 15)) ? ((Ck & 15) >> 2) : 0;
+    const int tail_q = (DENSE && VEC && (Ck & 15)) ? ((Ck & 15) >> 2) : 0;
     auto store_tiles = [&](int buf, bool tail = false) {
         if (tail) {                                                 // uniform
             const int q = tid & 3;
@@ -389,45 +386,7 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = double4_t{0.0, 0.0, 0.0, 0.0};
 
-    if constexpr (SMALLN) {
-        // 4-column tiles: the step onto the image is bound by how fast the L2 delivers the re-read window entries, not
-        // by the matrix pipe, so the plain order is kept: load the next tile, MFMAs of the current one, write, barrier
-        auto mfma_tile = [&](int buf) {
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {          // two halves of the lane's 4 k-values: one 16-byte LDS load each
-                double2 av[TM], bv;
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-                    av[i] = *reinterpret_cast<const double2*>(a_ld + (buf * BM + i * 16) * LDK + 2 * h);
-                bv = *reinterpret_cast<const double2*>(b_ld + (buf * BN) * LDK + 2 * h);
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-                    acc[i][0][0] = __builtin_amdgcn_mfma_f64_4x4x4f64(av[i].x, bv.x, acc[i][0][0], 0, 0, 0);
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-                    acc[i][0][0] = __builtin_amdgcn_mfma_f64_4x4x4f64(av[i].y, bv.y, acc[i][0][0], 0, 0, 0);
-            }
-        };
-        if (nIt > 0) {
-            load_tiles();
-            store_tiles(0);
-            __syncthreads();
-            // two K steps per trip so that the LDS buffer index is a compile-time constant
-            int it = 0;
-            for (; it + 2 <= nIt; it += 2) {
-                load_tiles();                  // tile it+1 (exists)
-                mfma_tile(0);
-                store_tiles(1);
-                __syncthreads();
-                const bool more = it + 2 < nIt;
-                if (more) load_tiles();        // tile it+2
-                mfma_tile(1);
-                if (more) store_tiles(0);
-                __syncthreads();
-            }
-            if (it < nIt) mfma_tile(0);
-        }
-    } else {
+    {
         // MFMA operand fragments of one K step: [half of the lane's 4 k-values][16-row tile], two sets so that the next
         // step's fragments are fetched from LDS while the MFMAs of the current step run
         double2 av[2][2][TM], bv[2][2][TN];
@@ -535,9 +494,8 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
-        for (int r4 = 0; r4 < (SMALLN ? 1 : 4); ++r4) {
-            // 16x16x4: register r4 of the lane is row 4*r4 + l/16; 4x4x4: the lane's one value is row 4*((l%16)/4) + l/16
-            const int rl = wm * WTM + i * 16 + (SMALLN ? 4 * (lm >> 2) : 4 * r4) + lk;
+        for (int r4 = 0; r4 < 4; ++r4) {
+            const int rl = wm * WTM + i * 16 + 4 * r4 + lk;              // register r4 of the lane is row 4*r4 + l/16
             const int r = r_tile + rl;
             if (r >= p.nrows) continue;
             const long long ridx = s_ridx[rl];
@@ -546,7 +504,7 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
             float* out_row = p.out + ((size_t)r * opix + pix) * N;
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                const int n = SMALLN ? n0 + (lm & 3) : n0 + wn * WTN + j * 16 + lm;
+                const int n = n0 + wn * WTN + j * 16 + lm;
                 if (n >= N) continue;
                 double v = acc[i][j][r4];
                 if (add_src) v += (double)add_src[n];
@@ -781,6 +739,7 @@ __global__ __launch_bounds__(256) void cross_direct_kernel(const CrossParams p) 
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
         for (int r4 = 0; r4 < (SMALLN ? 1 : 4); ++r4) {
+            // 16x16x4: register r4 of the lane is row 4*r4 + l/16; 4x4x4: the lane's one value is row 4*((l%16)/4) + l/16
             const int rl = i * 16 + (SMALLN ? 4 * (lm >> 2) : 4 * r4) + lk;
             const int r = r_wave + rl;
             if (r >= p.nrows) continue;
@@ -838,29 +797,15 @@ static void launch_cross_t(const CrossParams& p0, hipStream_t s) {
     else hipLaunchKernelGGL((cross_kernel<BM, BN, false, false>), dim3(blocks), dim3(256), 0, s, p);
 }
 
-#ifndef CROSS_TM4
-#define CROSS_TM4 2
-#endif
-#ifndef CROSS_TM16
-#define CROSS_TM16 2
-#endif
-#ifndef CROSS_TM32
-#define CROSS_TM32 2
-#endif
 void launch_cross(const CrossParams& p, hipStream_t s) {
     if (p.nrows <= 0 || p.Co <= 0) return;
     const int N = p.Co;
     // tile shapes measured on MI355X: 64x64 beats the larger tiles (their lower occupancy costs more than their
     // higher arithmetic intensity gains); narrow layers take a tall tile so that fewer MFMA columns are padding
-#ifdef CROSS_OLD_TALL
-    if (N <= 4) { launch_cross_t<128, 4>(p, s); return; }
-    if (N <= 16) { launch_cross_t<128, 16>(p, s); return; }
-    if (N <= 32) { launch_cross_t<128, 32>(p, s); return; }
-#else
-    if (N <= 4) { launch_cross_direct<CROSS_TM4, 0>(p, s); return; }
-    if (N <= 16) { launch_cross_direct<CROSS_TM16, 1>(p, s); return; }
-    if (N <= 32) { launch_cross_direct<CROSS_TM32, 2>(p, s); return; }
-#endif
+    // narrow layers: no LDS staging, fewer MFMA columns of padding (4-column instruction for the image layers)
+    if (N <= 4) { launch_cross_direct<2, 0>(p, s); return; }
+    if (N <= 16) { launch_cross_direct<2, 1>(p, s); return; }
+    if (N <= 32) { launch_cross_direct<2, 2>(p, s); return; }
     // few rows (one input at a time): smaller tiles so that the launch still covers the chip
     const long long wg64 = (long long)((p.nrows + 63) / 64) * ((N + 63) / 64) * p.owy * p.owx;
     if (wg64 < 256) { launch_cross_t<32, 32>(p, s); return; }
