@@ -46,6 +46,7 @@ struct Layer {
     std::vector<double> beff_host; // [C] summed bias of those layers (float64: the sum of two float32 is kept exact)
     // device
     float* d_wt = nullptr;
+    double* d_wt64 = nullptr;      // the same in float64, only for layers with at most 4 input channels (see cross_image_kernel)
     float* d_wti = nullptr;
     float* d_bias = nullptr;
     double* d_beff = nullptr;
@@ -480,6 +481,12 @@ gp_status ensure_device(gp_net* net, int batch) {
             if (!l.wt_host.empty() && !l.d_wt) {
                 HIP_TRY(net, hipMalloc((void**)&l.d_wt, l.wt_host.size() * sizeof(float)));
                 HIP_TRY(net, hipMemcpy(l.d_wt, l.wt_host.data(), l.wt_host.size() * sizeof(float), hipMemcpyHostToDevice));
+                const Layer& pr = net->L[l.a];
+                if ((l.type == T_DENSE ? pr.n : (long long)pr.C) <= 4) {
+                    std::vector<double> w64(l.wt_host.begin(), l.wt_host.end());
+                    HIP_TRY(net, hipMalloc((void**)&l.d_wt64, w64.size() * sizeof(double)));
+                    HIP_TRY(net, hipMemcpy(l.d_wt64, w64.data(), w64.size() * sizeof(double), hipMemcpyHostToDevice));
+                }
             }
             if (!l.wti_host.empty() && !l.d_wti) {
                 HIP_TRY(net, hipMalloc((void**)&l.d_wti, l.wti_host.size() * sizeof(float)));
@@ -818,6 +825,7 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                 cp.in = make_desc(net, slot_ptr(op.slot_in), op.g_in, op.layer_in, &op.t_in);
                 cp.out_grl = op.relaxed ? p.d_grl : nullptr;
                 cp.wt = a.d_wt;
+                cp.wt64 = a.d_wt64;
                 cp.kh = a.kh; cp.kw = a.kw; cp.sh = a.sh; cp.sw = a.sw; cp.ph = a.ph; cp.pw = a.pw;
                 cp.out = slot_ptr(op.slot_out);
                 if (a.type == T_DENSE) {   // a dense layer is a 1x1 convolution over the flattened predecessor
@@ -1012,7 +1020,7 @@ void gp_net_destroy(gp_net* net) {
     if (!net) return;
     for (auto& l : net->L) {
         free_layer_bounds(l);
-        dfree(l.d_wt); dfree(l.d_wti); dfree(l.d_bias); dfree(l.d_beff);
+        dfree(l.d_wt); dfree(l.d_wt64); dfree(l.d_wti); dfree(l.d_bias); dfree(l.d_beff);
     }
     dfree(net->d_count);
     if (net->h_count) (void)hipHostFree(net->h_count);

@@ -774,6 +774,99 @@ static void launch_cross_direct(const CrossParams& p0, hipStream_t s) {
     else hipLaunchKernelGGL((cross_direct_kernel<TM, TN, false>), dim3(blocks), dim3(256), 0, s, p);
 }
 
+// Layers with at most 4 input channels (the image): no matrix instruction.  An output pixel of such a step has N <= 4
+// values and, behind a strided layer, K = (taps that reach it) * channels of a few dozen: a work-group per pixel
+// would spend its time on bookkeeping.  Here ONE LANE computes one (row, output pixel): it walks the taps that can
+// reach its pixel and the channels under each tap and accumulates N float64 sums with fused multiply-adds (whose
+// peak on this chip equals the float64 MFMA peak).  Lanes are grouped by the pixel's PARITY CLASS, i.e. by
+// ((A + ph) mod sh, (B + pw) mod sw) of its absolute position (A, B): within a class every lane uses the same taps
+// f = cy + t*sh, g = cx + u*sw, so tap and channel loops are uniform and the (float64) filter values come through
+// scalar loads.  Consecutive lanes are consecutive pixels of the class in a row's window: their block reads are
+// consecutive window entries (64 contiguous bytes per 16 channels each).
+// grid: x over (row, pixel of the class) / 256, y over the sh*sw classes.
+template <bool VEC>
+__global__ __launch_bounds__(256) void cross_image_kernel(const CrossParams p) {
+    const int N = p.Co, Ck = p.in.C;
+    const long long gid = blockIdx.x * 256LL + threadIdx.x;
+    const uint32_t ppc = (uint32_t)(p.cls_ny * p.cls_nx);
+    if (gid >= (long long)p.nrows * ppc) return;
+    const uint32_t r = fast_div((uint32_t)gid, p.div_cls);
+    const uint32_t k = (uint32_t)gid - r * ppc;
+    const uint32_t ky = fast_div(k, p.div_cls_nx), kx = k - ky * (uint32_t)p.cls_nx;
+    const int cy = (int)fast_div(blockIdx.y, p.div_sw), cx = (int)blockIdx.y - cy * p.sw;      // the class (uniform)
+    const RowInfo ri = row_info(p.rm, (int)r);
+    const int oy = clampi(p.oSy * ri.ys - p.oPy, 0, p.Ho - p.owy), ox = clampi(p.oSx * ri.xs - p.oPx, 0, p.Wo - p.owx);
+    // first window pixel of the class: pa = cy - (oy + ph) (mod sh)
+    const uint32_t my = (uint32_t)(oy + p.ph), mx = (uint32_t)(ox + p.pw);
+    int pa = cy - (int)(my - fast_div(my, p.div_sh) * (uint32_t)p.sh);
+    int pb = cx - (int)(mx - fast_div(mx, p.div_sw) * (uint32_t)p.sw);
+    pa += (pa < 0 ? p.sh : 0) + (int)ky * p.sh;
+    pb += (pb < 0 ? p.sw : 0) + (int)kx * p.sw;
+    if (pa >= p.owy || pb >= p.owx) return;
+    const int A = oy + pa, B = ox + pb;
+    // tap (f, g) = (cy + t*sh, cx + u*sw) reads layer-output pixel (y0 - t, x0 - u)
+    const int y0 = (int)fast_div((uint32_t)(A + p.ph - cy), p.div_sh), x0 = (int)fast_div((uint32_t)(B + p.pw - cx), p.div_sw);
+    // the part of the row's stored window that lies in its exact dependence window (see cross_kernel)
+    const int oiy = clampi(p.in.Sy * ri.ys - p.in.Py, 0, p.in.H - p.in.wy), oix = clampi(p.in.Sx * ri.xs - p.in.Px, 0, p.in.W - p.in.wx);
+    const int ty = p.in.tSy * ri.ys - p.in.tPy, tx = p.in.tSx * ri.xs - p.in.tPx;
+    const int ylo = max(ty, oiy), yhi = min(ty + p.in.tWy, oiy + p.in.wy);
+    const int xlo = max(tx, oix), xhi = min(tx + p.in.tWx, oix + p.in.wx);
+    const float* const row = p.in.data + (size_t)r * (size_t)(p.in.wy * p.in.wx * Ck);
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int t = 0, f = cy; f < p.kh; ++t, f += p.sh) {                  // uniform loops
+        const int y = y0 - t;
+        const bool yok = y >= ylo && y < yhi;
+        for (int u = 0, g = cx; g < p.kw; ++u, g += p.sw) {
+            const int x = x0 - u;
+            if (!(yok && x >= xlo && x < xhi)) continue;
+            const float* a = row + (size_t)((y - oiy) * p.in.wx + (x - oix)) * Ck;
+            const double* w = p.wt64 + (size_t)(f * p.kw + g) * N * Ck;     // [n][c], uniform
+            if (VEC) {
+                for (int c = 0; c < Ck; c += 4) {
+                    const float4 v = *reinterpret_cast<const float4*>(a + c);
+                    const double av[4] = {(double)v.x, (double)v.y, (double)v.z, (double)v.w};
+#pragma unroll
+                    for (int n = 0; n < 4; ++n)
+                        if (n < N) {
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) acc[n] = fma(av[j], w[n * Ck + c + j], acc[n]);
+                        }
+                }
+            } else {
+                for (int c = 0; c < Ck; ++c) {
+                    const double av = (double)a[c];
+#pragma unroll
+                    for (int n = 0; n < 4; ++n)
+                        if (n < N) acc[n] = fma(av, w[n * Ck + c], acc[n]);
+                }
+            }
+        }
+    }
+    long long ridx, aoff;
+    epilogue_row_info(p, ri, (int)r, pa, pb, ridx, aoff);
+    float* out = p.out + ((size_t)r * (size_t)(p.owy * p.owx) + (size_t)(pa * p.owx + pb)) * N;
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+        if (n < N) {
+            double v = acc[n];
+            if (aoff >= 0) v += (double)p.add.data[aoff + n];
+            if (p.out_grl) v *= (double)relax_factor(v, p.out_grl[ridx + n]);
+            out[n] = (float)v;
+        }
+}
+
+static void launch_cross_image(const CrossParams& p0, hipStream_t s) {
+    CrossParams p = p0;
+    p.cls_ny = (p.owy + p.sh - 1) / p.sh;
+    p.cls_nx = (p.owx + p.sw - 1) / p.sw;
+    p.div_cls = make_fastdiv((uint32_t)(p.cls_ny * p.cls_nx));
+    p.div_cls_nx = make_fastdiv((uint32_t)p.cls_nx);
+    const long long items = (long long)p.nrows * p.cls_ny * p.cls_nx;      // < 2^31: rows * window pixels is
+    const dim3 grid((unsigned)((items + 255) / 256), (unsigned)(p.sh * p.sw));
+    if ((p.in.C & 3) == 0) hipLaunchKernelGGL((cross_image_kernel<true>), grid, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((cross_image_kernel<false>), grid, dim3(256), 0, s, p);
+}
+
 template <int BM, int BN>
 static void launch_cross_t(const CrossParams& p0, hipStream_t s) {
     CrossParams p = p0;
@@ -803,6 +896,11 @@ void launch_cross(const CrossParams& p, hipStream_t s) {
     // tile shapes measured on MI355X: 64x64 beats the larger tiles (their lower occupancy costs more than their
     // higher arithmetic intensity gains); narrow layers take a tall tile so that fewer MFMA columns are padding
     // narrow layers: no LDS staging, fewer MFMA columns of padding (4-column instruction for the image layers)
+    // image layers: one lane per output pixel while the pixel's K (taps of its parity class x channels) is short; a
+    // lane's loads are 16 bytes out of a 128-byte line, which the L1 no longer absorbs for longer K (measured: 1.6x
+    // faster than the MFMA kernel at K = 64, 0.75x at K = 288)
+    const int k_pixel = ((p.kh + p.sh - 1) / p.sh) * ((p.kw + p.sw - 1) / p.sw) * p.in.C;
+    if (N <= 4 && p.wt64 && k_pixel <= 128) { launch_cross_image(p, s); return; }
     if (N <= 4) { launch_cross_direct<2, 0>(p, s); return; }
     if (N <= 16) { launch_cross_direct<2, 1>(p, s); return; }
     if (N <= 32) { launch_cross_direct<2, 2>(p, s); return; }

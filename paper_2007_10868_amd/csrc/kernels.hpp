@@ -64,6 +64,7 @@ struct BlockDesc {
 struct CrossParams {       // one back-substitution step through an affine layer (Algorithm 1 per row)
     BlockDesc in;          // block over the layer's OUTPUT neurons
     const float* wt;       // [kh*kw][Co][in.C]  (the layer's own output channels innermost)
+    const double* wt64;    // the same values in float64; present (non-null) when Co <= 4
     int kh, kw, sh, sw, ph, pw;
     float* out;            // new block over the layer's INPUT neurons
     const float* out_grl;  // when the input layer is a ReLU layer and the block is complete: its packed relaxation
@@ -74,6 +75,8 @@ struct CrossParams {       // one back-substitution step through an affine layer
     FastDiv div_owx, div_sh, div_sw, div_kw;     // owx, sh, sw, kw
     int ntiles_m, ntiles_n;                      // filled by the launcher: tiles of rows / of input channels
     FastDiv div_ntiles_n, div_opix;
+    int cls_ny, cls_nx;                          // filled by the launcher (cross_image_kernel): pixels per parity class
+    FastDiv div_cls, div_cls_nx;
     BlockDesc add;         // optional block over the same input layer to be summed in (residual join)
     RowMap rm;
     int nrows;
