@@ -32,6 +32,7 @@ def main():
                     help="analyse with early termination (forward interval pass, stable neurons are not back-substituted)")
     ap.add_argument("--float-inference", action="store_true",
                     help="bounds that also cover every float32 evaluation order of the network (inference rounding)")
+    ap.add_argument("--graph", action="store_true", help="replay the pass as a captured HIP graph")
     ap.add_argument("--eps", type=float, default=0.0, help="override the configuration's perturbation radius")
     ap.add_argument("--cpu-sample", type=int, default=-1, help="inputs the oracle is timed on (0: skip)")
     args = ap.parse_args()
@@ -56,6 +57,8 @@ def main():
         g.set_early_termination(True)
     if args.float_inference:
         g.set_float_inference(True)
+    if args.graph:
+        g.set_graph_replay(True)
     centers = np.stack([net.center(j % net.n_inputs) for j in range(batch)])
     t_centers = torch.tensor(centers, device="cuda")
     stream = torch.cuda.current_stream()
@@ -75,7 +78,8 @@ def main():
     for _ in range(args.warmup):
         g.analyze_batch_dev(t_centers, net.eps)
     torch.cuda.synchronize()
-    g.profile_enable(True)
+    if not args.graph:                  # per-kernel events are recorded on eager launches only
+        g.profile_enable(True)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -111,6 +115,21 @@ def main():
             g.analyze_batch_dev(one, net.eps)
         torch.cuda.synchronize()
         single_ms = (time.perf_counter() - t0) * 1e3 / reps
+
+    # the same K steps replayed as one captured HIP graph per pass (no per-kernel events there, so this is reported
+    # beside the metric, which stays the eager, event-instrumented region above)
+    graph_ms = None
+    if not args.graph and not args.early_term:
+        g.set_graph_replay(True)
+        for _ in range(2):
+            g.analyze_batch_dev(t_centers, net.eps)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            g.analyze_batch_dev(t_centers, net.eps)
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        g.set_graph_replay(False)
 
     cross = prof["cross"]
     avg_launch_ms = cross["ms"] / max(cross["launches"], 1)
@@ -152,10 +171,13 @@ def main():
                higher_is_better=False, scaling="weak", vs_baseline=None, dtype="f64", data="synthetic",
                config=dict(workload=net.name, inputs_per_step=batch, eps=net.eps, neurons=int(sum(net.n_neurons(i) for i in range(1, net.out_layer + 1) if net.layers[i - 1]["type"] != "relu")),
                            coefficient_storage="f32", accumulate="f64 MFMA", workspace_bytes=ws_bytes,
-                           early_termination=bool(args.early_term), float_inference=bool(args.float_inference)),
+                           early_termination=bool(args.early_term), float_inference=bool(args.float_inference),
+                           graph_replay=bool(args.graph)),
                roofline=roofline, cpu_baseline=cpu)
     if single_ms is not None:
         out["single_input_latency_ms"] = round(single_ms, 4)
+    if graph_ms is not None:
+        out["graph_replay"] = dict(ms_per_step=round(graph_ms, 4), ms_per_input=round(graph_ms / batch, 5))
     if early is not None:
         out["early_termination"] = early
     print(json.dumps(out))

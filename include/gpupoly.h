@@ -75,6 +75,14 @@ gp_status gp_request_bounds(gp_net* net, int32_t layer_id);
  * gp_request_bounds and certification rows are always substituted down to the input.  Takes effect at the next
  * analysis; bounds of stopped neurons are sound but in general looser than without early termination. */
 gp_status gp_set_early_termination(gp_net* net, int32_t on);
+/* Plumbing; off by default.  When on, gp_analyze, gp_analyze_batch and gp_analyze_batch_dev capture their kernel launches
+ * into a HIP graph the first time and replay it afterwards: one pass over a small batch is a chain of some 150 dependent
+ * launches of a few microseconds each, and the replay removes their per-launch dispatch cost.  The graph is rebuilt
+ * whenever batch, centres pointer (the library's own staging buffer for host centres), eps, clip range, workspace or
+ * stream differ from the captured ones or the network or a mode changes; with early termination (the host reads
+ * counts between steps) and while profiling the calls run as usual.  Results are bit-identical either way.  The
+ * capture itself runs with the stream idle (the call synchronises it first). */
+gp_status gp_set_graph_replay(gp_net* net, int32_t on);
 /* Rounding of the inference itself (paper Section 4.1, last paragraph: the analysis should also cover the error a
  * floating-point evaluation of the network makes, whatever the order of its sums); off by default.  When on, every
  * bound holds for the real-valued network AND for every float32 evaluation of it in which an affine neuron is a sum

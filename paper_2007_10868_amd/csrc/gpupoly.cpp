@@ -113,6 +113,15 @@ struct gp_net {
     int device = -1;
     // early termination (Sections 3.2, 4.2)
     bool early = false;
+    // Graph replay (gp_set_graph_replay): the launches of one box analysis, captured once and replayed.  A pass over a
+    // small batch is a chain of ~150 dependent launches of a few microseconds each; replayed as one graph the
+    // per-launch dispatch cost goes away.  Valid for one (batch, centres pointer, eps, clip, workspace, stream).
+    bool graph_on = false;
+    hipGraphExec_t graph_exec = nullptr;
+    hipStream_t cap_stream = nullptr;      // launches are captured on a stream of the library's own (the legacy default
+                                           // stream cannot be captured), the graph then runs on the caller's stream
+    struct GraphKey { int batch; const float* centers; float eps, clo, chi; void* ws; long long ws_bytes; hipStream_t stream; };
+    GraphKey graph_key = {};
     bool float_inference = false;  // bounds also hold for every float32 evaluation order of the network (Section 4.1)
     int* d_count = nullptr;
     int* h_count = nullptr;        // pinned: task counts read back while the GPU keeps working
@@ -151,6 +160,11 @@ gp_status fail(const gp_net* net, gp_status st, const char* fmt, ...) {
 
 void dfree(void* p) {
     if (p) (void)hipFree(p);
+}
+
+// a captured graph holds device addresses: whatever frees or moves device memory drops it
+void drop_graph(gp_net* net) {
+    if (net->graph_exec) { (void)hipGraphExecDestroy(net->graph_exec); net->graph_exec = nullptr; }
 }
 
 bool all_finite(const float* p, size_t n) {
@@ -441,7 +455,7 @@ gp_status get_plan(gp_net* net, int lid, Plan** out) {
 }
 
 // ---- device state ------------------------------------------------------------------------------
-void free_layer_bounds(Layer& l) {
+void free_layer_bounds(Layer& l) {   // callers drop the captured graph
     dfree(l.d_lo); dfree(l.d_hi); dfree(l.d_rho); dfree(l.d_kap); dfree(l.d_xmax); dfree(l.d_grl); dfree(l.d_term);
     dfree(l.d_eta); dfree(l.d_eta_thru);
     l.d_lo = l.d_hi = l.d_rho = l.d_kap = l.d_xmax = l.d_eta = l.d_eta_thru = nullptr;
@@ -502,6 +516,7 @@ gp_status ensure_device(gp_net* net, int batch) {
         net->weights_uploaded = true;
     }
     if (net->batch != batch) {
+        drop_graph(net);
         for (auto& l : net->L) free_layer_bounds(l);
         dfree(net->d_labels); net->d_labels = nullptr;
         dfree(net->d_margins); net->d_margins = nullptr;
@@ -550,6 +565,7 @@ gp_status get_workspace(gp_net* net, long long want, char** ws, long long* bytes
     long long need = std::min(want, cap);
     need = align_up(std::max(need, 1LL << 20), 1 << 20);
     if (net->ws_own_bytes < need) {
+        drop_graph(net);
         dfree(net->ws_own);
         net->ws_own = nullptr; net->ws_own_bytes = 0;
         HIP_TRY(net, hipMalloc(&net->ws_own, need));
@@ -961,6 +977,10 @@ gp_status analyze_layers(gp_net* net, int batch) {
             }
         }
     }
+    return GP_OK;
+}
+
+gp_status finish_analysis(gp_net* net) {
     gp_status st = check_flag(net);
     if (st != GP_OK) return st;
     net->analyzed = true;
@@ -983,10 +1003,32 @@ gp_status begin_analysis(gp_net* net, int batch) {
         }
     st = ensure_device(net, batch);
     if (st != GP_OK) return st;
-    gp::launch_fill_i32(net->d_flag, 0, 1, net->stream);
-    gp::launch_fill_f64(net->L[0].d_xmax, 0.0, batch, net->stream);
     net->early_flop_done = net->early_flop_full = 0.0;
     return GP_OK;
+}
+
+void enqueue_reset(gp_net* net, int batch) {
+    gp::launch_fill_i32(net->d_flag, 0, 1, net->stream);
+    gp::launch_fill_f64(net->L[0].d_xmax, 0.0, batch, net->stream);
+}
+
+bool same_key(const gp_net::GraphKey& a, const gp_net::GraphKey& b) {
+    return a.batch == b.batch && a.centers == b.centers && a.eps == b.eps && a.clo == b.clo && a.chi == b.chi &&
+           a.ws == b.ws && a.ws_bytes == b.ws_bytes && a.stream == b.stream;
+}
+
+// the library's own workspace sized for the largest plan, so that nothing allocates while launches are captured
+gp_status reserve_workspace(gp_net* net, int batch) {
+    if (net->ws_user) return GP_OK;
+    long long want = 0;
+    for (size_t i = 1; i < net->L.size(); ++i) {
+        const Layer& l = net->L[i];
+        if (l.type == T_RELU || !l.need_bounds) continue;
+        const Plan& pl = net->plans[i];
+        if (pl.valid) want = std::max(want, task_bytes(pl, 2) * l.n * batch + 16384);
+    }
+    char* ws; long long bytes;
+    return get_workspace(net, want, &ws, &bytes);
 }
 
 void hwc_from_chw(const Layer& l, const float* src, double* dst) {
@@ -1025,6 +1067,8 @@ void gp_net_destroy(gp_net* net) {
     dfree(net->d_count);
     if (net->h_count) (void)hipHostFree(net->h_count);
     if (net->count_ev) (void)hipEventDestroy(net->count_ev);
+    if (net->graph_exec) (void)hipGraphExecDestroy(net->graph_exec);
+    if (net->cap_stream) (void)hipStreamDestroy(net->cap_stream);
     dfree(net->d_forms); dfree(net->d_form_off); dfree(net->d_form_out);
     dfree(net->d_flag); dfree(net->d_labels); dfree(net->d_margins); dfree(net->d_centers);
     dfree(net->ws_own);
@@ -1041,6 +1085,7 @@ static gp_status check_new_layer(gp_net* net, int32_t in_layer, int32_t* layer_i
 }
 
 static void topology_changed(gp_net* net) {
+    drop_graph(net);
     net->topo_ready = false;
     net->analyzed = false;
     net->weights_uploaded = false;
@@ -1178,8 +1223,16 @@ gp_status gp_set_early_termination(gp_net* net, int32_t on) {
     return GP_OK;
 }
 
+gp_status gp_set_graph_replay(gp_net* net, int32_t on) {
+    if (!net) return GP_ERR_ARG;
+    net->graph_on = on != 0;
+    if (!net->graph_on) drop_graph(net);
+    return GP_OK;
+}
+
 gp_status gp_set_float_inference(gp_net* net, int32_t on) {
     if (!net) return GP_ERR_ARG;
+    drop_graph(net);
     const bool want = on != 0;
     if (want != net->float_inference) {
         net->float_inference = want;
@@ -1265,8 +1318,40 @@ gp_status gp_analyze_batch_dev(gp_net* net, int32_t batch, const float* centers_
     bp.centers = centers_dev; bp.eps = eps; bp.clip_lo = clip_lo; bp.clip_hi = clip_hi;
     bp.lo = in.d_lo; bp.hi = in.d_hi; bp.xmax = in.d_xmax; bp.flag = net->d_flag;
     bp.C = in.C; bp.H = in.H; bp.W = in.W; bp.batch = batch;
-    gp::launch_box(bp, net->stream);
-    return analyze_layers(net, batch);
+    auto enqueue = [&]() -> gp_status {
+        enqueue_reset(net, batch);
+        gp::launch_box(bp, net->stream);
+        return analyze_layers(net, batch);
+    };
+    // early termination reads counts back between the steps and profiling records events: both stay eager
+    if (!net->graph_on || net->early || net->prof_on) {
+        st = enqueue();
+        if (st != GP_OK) return st;
+        return finish_analysis(net);
+    }
+    const gp_net::GraphKey key = {batch, centers_dev, eps, clip_lo, clip_hi, net->ws_user, net->ws_user_bytes, net->stream};
+    if (!net->graph_exec || !same_key(key, net->graph_key)) {
+        drop_graph(net);
+        st = reserve_workspace(net, batch);
+        if (st != GP_OK) return st;
+        HIP_TRY(net, hipStreamSynchronize(net->stream));
+        if (!net->cap_stream) HIP_TRY(net, hipStreamCreateWithFlags(&net->cap_stream, hipStreamNonBlocking));
+        hipStream_t const user = net->stream;
+        HIP_TRY(net, hipStreamBeginCapture(net->cap_stream, hipStreamCaptureModeThreadLocal));
+        net->stream = net->cap_stream;
+        st = enqueue();
+        net->stream = user;
+        hipGraph_t graph = nullptr;
+        const hipError_t ec = hipStreamEndCapture(net->cap_stream, &graph);
+        if (st != GP_OK) { if (graph) (void)hipGraphDestroy(graph); return st; }
+        if (ec != hipSuccess || !graph) return fail(net, GP_ERR_DEVICE, "graph capture: %s", hipGetErrorString(ec));
+        const hipError_t ei = hipGraphInstantiate(&net->graph_exec, graph, nullptr, nullptr, 0);
+        (void)hipGraphDestroy(graph);
+        if (ei != hipSuccess) { net->graph_exec = nullptr; return fail(net, GP_ERR_DEVICE, "graph instantiate: %s", hipGetErrorString(ei)); }
+        net->graph_key = key;
+    }
+    HIP_TRY(net, hipGraphLaunch(net->graph_exec, net->stream));
+    return finish_analysis(net);
 }
 
 gp_status gp_analyze_batch(gp_net* net, int32_t batch, const float* centers, float eps, float clip_lo, float clip_hi) {
@@ -1310,9 +1395,12 @@ gp_status gp_analyze_box(gp_net* net, const float* lo, const float* hi) {
     for (long long i = 0; i < in.n; ++i) xmax = std::max(xmax, std::max(std::fabs(l[i]), std::fabs(h[i])));
     HIP_TRY(net, hipMemcpyAsync(in.d_lo, l.data(), in.n * sizeof(double), hipMemcpyHostToDevice, net->stream));
     HIP_TRY(net, hipMemcpyAsync(in.d_hi, h.data(), in.n * sizeof(double), hipMemcpyHostToDevice, net->stream));
+    gp::launch_fill_i32(net->d_flag, 0, 1, net->stream);
     HIP_TRY(net, hipMemcpyAsync(in.d_xmax, &xmax, sizeof(double), hipMemcpyHostToDevice, net->stream));
     HIP_TRY(net, hipStreamSynchronize(net->stream));
-    return analyze_layers(net, 1);
+    st = analyze_layers(net, 1);
+    if (st != GP_OK) return st;
+    return finish_analysis(net);
 }
 
 gp_status gp_get_bounds_f64(const gp_net* net, int32_t layer_id, int32_t batch_index, double* lower, double* upper) {
