@@ -946,6 +946,25 @@ __device__ __forceinline__ void scan_term(bool has_cand, bool do_consts, float m
     }
 }
 
+// The same for the kernels that stage the neurons' constants in LDS, with fewer vector instructions per coefficient
+// (every one of them is paid in time here): the staged multiplier pair is (cpos - cneg, cneg), so that the candidate
+// term needs no select, m*c(m) = max(m,0)*(cpos - cneg) + m*cneg; and the magnitude of the constant terms, which only
+// scales a rounding slack, is not summed per coefficient but bounded per row by S1 * max_j(|bias_j| + kap_j).
+__device__ __forceinline__ void scan_term_staged(bool has_cand, bool do_consts, float mf, double dcp, double cn, double X,
+                                                 double kp, double be, double& cand, double& absx, double& cst, double& s1) {
+    const double m = (double)mf;
+    const double am = fabs(m);
+    const double mp = fmax(m, 0.0);
+    if (has_cand) {
+        cand = fma(mp, dcp, fma(m, cn, cand));
+        absx = fma(am, X, absx);
+    }
+    if (do_consts) {
+        cst = fma(m, be, fma(mp, kp, cst));
+        s1 += am;
+    }
+}
+
 // The scalars of a row that its bookkeeping reads.  Fetched early (scan_row_fetch) by the kernels that want the
 // round trip to overlap with the row's own loads.
 struct ScanRow {
@@ -984,7 +1003,9 @@ __device__ __forceinline__ void scan_finish(const ScanParams& p, int r, int nele
     if (p.round_coef > 0.0 && p.xmax_self) err += 0x1p-128 * (double)nelem * s.xmax_self;
     if (p.update_best && p.cpos) {
         double v = c + t_cand + err;
-        v += (fabs(c) + fabs(t_cand) + err) * 0x1p-50 + t_absx * esum;
+        // (the candidate's terms are at most 3*|m|*X in magnitude when the multiplier comes as a difference, see
+        // scan_term_staged)
+        v += (fabs(c) + fabs(t_cand) + err) * 0x1p-50 + 3.0 * t_absx * esum;
         if (!s.frozen) p.best[s.bi] = fmin(s.best, v);
     }
     if (p.do_consts) {
@@ -1092,6 +1113,9 @@ __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) 
     constexpr int NT = ROWS * 8;
     extern __shared__ __attribute__((aligned(16))) double s_const[];     // [5][nelem_pad]
     __shared__ int s_b[SCAN_LDS_ROWS], s_oy[SCAN_LDS_ROWS], s_ox[SCAN_LDS_ROWS];
+    // bits of max_j(|bias_j| + kap_j) over the staged constants (non-negative), one slot per parity of the run: a slot
+    // is cleared during the following run, two barriers away from both its readers and its next writers
+    __shared__ unsigned long long s_qmax[2];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const BlockDesc& B = p.blk;
     const int nelem = B.wy * B.wx * B.C;
@@ -1117,6 +1141,7 @@ __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) 
         s_oy[kk] = clampi(B.Sy * ri.ys - B.Py, 0, B.H - B.wy);
         s_ox[kk] = clampi(B.Sx * ri.xs - B.Px, 0, B.W - B.wx);
     }
+    if (tid == 0) s_qmax[0] = s_qmax[1] = 0ull;
     __syncthreads();
     const float* src = B.data + (size_t)r * nelem;
     double cand = 0.0, absx = 0.0, cst = 0.0, cstabs = 0.0, s1 = 0.0;
@@ -1142,17 +1167,19 @@ __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) 
                 const int k = e - c0;
 #pragma unroll
                 for (int v = 0; v < V; ++v)
-                    scan_term(p.cpos != nullptr, p.do_consts != 0, mf[u][v], s_cp[k + v], s_cn[k + v], s_X[k + v],
-                              s_kp[k + v], s_be[k + v], cand, absx, cst, cstabs, s1);
+                    scan_term_staged(p.cpos != nullptr, p.do_consts != 0, mf[u][v], s_cp[k + v], s_cn[k + v], s_X[k + v],
+                                     s_kp[k + v], s_be[k + v], cand, absx, cst, s1);
             }
         }
     };
-    int k0 = 0;
+    int k0 = 0, run = 0;
     while (k0 < nvalid) {                                   // uniform over the work-group
+        if (tid == 0) s_qmax[(run & 1) ^ 1] = 0ull;
         const int b0 = s_b[k0], oy0 = s_oy[k0], ox0 = s_ox[k0];
         int k1 = k0 + 1;
         while (k1 < nvalid && s_b[k1] == b0 && s_oy[k1] == oy0 && s_ox[k1] == ox0) ++k1;
         const long long bbase = (long long)b0 * p.batch_stride;
+        double qmax = 0.0;
         for (int e = c0 + tid; e < c1; e += NT) {
             int c;
             long long j;
@@ -1177,18 +1204,29 @@ __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) 
                 if (p.eta) { const double et = p.eta[j]; kp += 2.0 * et; be -= et; }
             }
             const int k = e - c0;
-            s_cp[k] = cp; s_cn[k] = cn; s_X[k] = X; s_kp[k] = kp; s_be[k] = be;
+            s_cp[k] = cp - cn; s_cn[k] = cn; s_X[k] = X; s_kp[k] = kp; s_be[k] = be;
+            qmax = fmax(qmax, fabs(be) + kp);
+        }
+        if (p.do_consts) {
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) qmax = fmax(qmax, __shfl_xor(qmax, off, 64));
+            // non-negative doubles order like their bit patterns
+            if (lane == 0) atomicMax(&s_qmax[run & 1], (unsigned long long)__double_as_longlong(qmax));
         }
         __syncthreads();
         if (valid && kk >= k0 && kk < k1) {
+            const double s1_before = s1;
             for (int e0 = c0 + sub * V; e0 < c1; e0 += U * 8 * V) {
                 float mf[U][V];
                 load_slices(e0, mf);
                 add_slices(e0, mf);
             }
+            // magnitude of the row's constant terms (scales a rounding slack only): a row lies in exactly one run
+            cstabs = (s1 - s1_before) * __longlong_as_double((long long)s_qmax[run & 1]) * (1.0 + 0x1p-50);
         }
         __syncthreads();                                    // the next run overwrites the constants
         k0 = k1;
+        ++run;
     }
 #pragma unroll
     for (int off = 4; off > 0; off >>= 1) {
