@@ -550,6 +550,31 @@ __global__ __launch_bounds__(256) void cross_direct_kernel(const CrossParams p) 
         __builtin_amdgcn_make_buffer_rsrc((void*)p.wt, 0, (int)((uint32_t)taps * N * Ck * 4u), 0x00020000);
 
     const int q4 = 4 * lk;                       // this lane's channel quad inside a K step
+    // The rows of a wave are consecutive tasks, i.e. mostly the channels of ONE position of the start layer in one box:
+    // then every row has the same window origins and can use the same taps, and the whole tap geometry is computed
+    // once, in scalar registers (r_wave is uniform), instead of per lane in vector instructions that cost matrix time.
+    const RowInfo u0 = row_info(p.rm, r_wave), u1 = row_info(p.rm, r_wave + rows_here - 1);
+    const bool uni = p.rm.rowid == nullptr && u0.b == u1.b && u0.ys == u1.ys && u0.xs == u1.xs &&
+                     (r_wave + rows_here <= p.rm.Rc || r_wave >= p.rm.Rc);
+    // uniform form of the geometry below (same formulas on the wave's common position)
+    const int u_oiy = clampi(p.in.Sy * u0.ys - p.in.Py, 0, p.in.H - p.in.wy);
+    const int u_oix = clampi(p.in.Sx * u0.xs - p.in.Px, 0, p.in.W - p.in.wx);
+    const int u_A = clampi(p.oSy * u0.ys - p.oPy, 0, p.Ho - p.owy) + pa, u_B = clampi(p.oSx * u0.xs - p.oPx, 0, p.Wo - p.owx) + pb;
+    const uint32_t u_yy0 = (uint32_t)(u_A + p.ph), u_xx0 = (uint32_t)(u_B + p.pw);
+    const int u_ydiv = (int)fast_div(u_yy0, p.div_sh), u_xdiv = (int)fast_div(u_xx0, p.div_sw);
+    const int u_ymod = (int)(u_yy0 - (uint32_t)u_ydiv * (uint32_t)p.sh), u_xmod = (int)(u_xx0 - (uint32_t)u_xdiv * (uint32_t)p.sw);
+    const int u_ty = p.in.tSy * u0.ys - p.in.tPy, u_tx = p.in.tSx * u0.xs - p.in.tPx;
+    const int u_ylo = max(max(u_ty, u_oiy), 0), u_yhi = min(min(u_ty + p.in.tWy, u_oiy + p.in.wy), p.in.H);
+    const int u_xlo = max(max(u_tx, u_oix), 0), u_xhi = min(min(u_tx + p.in.tWx, u_oix + p.in.wx), p.in.W);
+    // tap t reaches this pixel from inside the common window?  poff = element offset of the window entry it reads
+    auto tap_uniform = [&](int t, int& poff) -> bool {
+        const int f = (int)fast_div((uint32_t)t, p.div_kw), g = t - f * p.kw;
+        const int fdiv = (int)fast_div((uint32_t)f, p.div_sh), fmod = f - fdiv * p.sh;
+        const int gdiv = (int)fast_div((uint32_t)g, p.div_sw), gmod = g - gdiv * p.sw;
+        const int y = u_ydiv - fdiv, x = u_xdiv - gdiv;
+        poff = ((y - u_oiy) * p.in.wx + (x - u_oix)) * Ck;
+        return u_ymod == fmod && u_xmod == gmod && y >= u_ylo && y < u_yhi && x >= u_xlo && x < u_xhi;
+    };
     uint32_t a_rowoff[TM];
     int a_ydiv[TM], a_xdiv[TM], a_ymod[TM], a_xmod[TM], a_oiy[TM], a_oix[TM];
     uint32_t a_ty[TM], a_tx[TM];
@@ -558,6 +583,10 @@ __global__ __launch_bounds__(256) void cross_direct_kernel(const CrossParams p) 
     for (int i = 0; i < TM; ++i) {
         const int rl = i * 16 + lm;
         a_ok[i] = rl < rows_here;
+        a_rowoff[i] = ((uint32_t)rl * row_elems + (uint32_t)q4) * 4u;
+        a_ydiv[i] = a_xdiv[i] = a_ymod[i] = a_xmod[i] = a_oiy[i] = a_oix[i] = 0;
+        a_ty[i] = a_tx[i] = 0;
+        if (uni) continue;
         const RowInfo ri = row_info(p.rm, r_wave + (a_ok[i] ? rl : 0));
         const uint32_t yy0 = (uint32_t)(clampi(p.oSy * ri.ys - p.oPy, 0, p.Ho - p.owy) + pa + p.ph);
         const uint32_t xx0 = (uint32_t)(clampi(p.oSx * ri.xs - p.oPx, 0, p.Wo - p.owx) + pb + p.pw);
@@ -571,7 +600,6 @@ __global__ __launch_bounds__(256) void cross_direct_kernel(const CrossParams p) 
         const int xlo = max(tx, a_oix[i]), xhi = min(tx + p.in.tWx, a_oix[i] + p.in.wx);
         a_ty[i] = (uint32_t)(ylo - a_oiy[i]) | ((uint32_t)max(yhi - ylo, 0) << 16);
         a_tx[i] = (uint32_t)(xlo - a_oix[i]) | ((uint32_t)max(xhi - xlo, 0) << 16);
-        a_rowoff[i] = ((uint32_t)rl * row_elems + (uint32_t)q4) * 4u;
         if (lk == 0 && a_ok[i])
             epilogue_row_info(p, ri, r_wave + rl, pa, pb, s_ridx[wave * 16 * TM + rl], s_aoff[wave * 16 * TM + rl]);
     }
@@ -601,7 +629,19 @@ __global__ __launch_bounds__(256) void cross_direct_kernel(const CrossParams p) 
     };
     // taps some row of this wave can use (bit t; filters with more than 64 taps keep all)
     unsigned long long tapmask = ~0ull;
-    if (taps <= 64) {
+    uint32_t s_tapoff = 0;                       // uniform path: byte offset of the current tap's window entry (scalar)
+    if (uni) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a_voff[i] = a_ok[i] ? a_rowoff[i] : kOOB;
+        if (taps <= 64) {
+            unsigned long long m = 0;
+            for (int t = 0; t < taps; ++t) {
+                int poff;
+                if (tap_uniform(t, poff)) m |= 1ull << t;
+            }
+            tapmask = m;
+        }
+    } else if (taps <= 64) {
         unsigned long long mine = 0;
         for (int t = 0; t < taps; ++t)
             if (set_tap(t)) mine |= 1ull << t;
@@ -617,12 +657,30 @@ __global__ __launch_bounds__(256) void cross_direct_kernel(const CrossParams p) 
     for (int t = next_tap(0); t < taps; t = next_tap(t + 1)) ++n_taps;
     const int nIt = n_taps * kchunks;
 
+    // the step the next loads are for moves on to tap t (uniform)
+    auto enter_tap = [&](int t) {
+        if (uni) {
+            int poff;
+            // (filters with more than 64 taps visit all of them: a tap that misses the window reads nothing)
+            if (tap_uniform(t, poff)) {
+                s_tapoff = (uint32_t)poff * 4u;
+#pragma unroll
+                for (int i = 0; i < TM; ++i) a_voff[i] = a_ok[i] ? a_rowoff[i] : kOOB;
+            } else {
+                s_tapoff = 0;
+#pragma unroll
+                for (int i = 0; i < TM; ++i) a_voff[i] = kOOB;
+            }
+        } else {
+            set_tap(t);
+        }
+    };
     int ld_t = next_tap(0), ld_d0 = 0;
-    if (ld_t < taps) set_tap(ld_t);
+    if (ld_t < taps) enter_tap(ld_t);
     F4 a_raw[TM], b_raw[TN];
     auto load_step = [&]() {
         const int rem = Ck - ld_d0;
-        const uint32_t soffA = (uint32_t)ld_d0 * 4u;
+        const uint32_t soffA = s_tapoff + (uint32_t)ld_d0 * 4u;
         const uint32_t soffB = ((uint32_t)ld_t * (uint32_t)N * (uint32_t)Ck + (uint32_t)ld_d0) * 4u;
         if (VEC && rem >= BK) {
 #pragma unroll
@@ -650,7 +708,7 @@ __global__ __launch_bounds__(256) void cross_direct_kernel(const CrossParams p) 
         if (ld_d0 >= Ck) {
             ld_d0 = 0;
             ld_t = next_tap(ld_t + 1);
-            if (ld_t < taps) set_tap(ld_t);
+            if (ld_t < taps) enter_tap(ld_t);
         }
     };
 
@@ -689,7 +747,7 @@ __global__ __launch_bounds__(256) void cross_direct_kernel(const CrossParams p) 
         // them the compiler moves the MFMAs ahead of the loads and every step waits for its own loads.)  The loads are
         // unconditional: behind the last step they re-read the current rows (A) and run off the filter's range (B, zeros).
         auto issue = [&]() {
-            const uint32_t soffA = (uint32_t)ld_d0 * 4u;
+            const uint32_t soffA = s_tapoff + (uint32_t)ld_d0 * 4u;
             const uint32_t soffB = ((uint32_t)ld_t * (uint32_t)N * (uint32_t)Ck + (uint32_t)ld_d0) * 4u;
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
@@ -709,7 +767,7 @@ __global__ __launch_bounds__(256) void cross_direct_kernel(const CrossParams p) 
             if (ld_d0 >= Ck) {
                 ld_d0 = 0;
                 ld_t = next_tap(ld_t + 1);
-                if (ld_t < taps) set_tap(ld_t);
+                if (ld_t < taps) enter_tap(ld_t);
             }
         };
         if (nIt > 0) { issue(); advance(); }
@@ -733,8 +791,33 @@ __global__ __launch_bounds__(256) void cross_direct_kernel(const CrossParams p) 
         }
     }
 
-    // ---- epilogue, as in cross_kernel
+    // ---- epilogue, as in cross_kernel; on the uniform path the pixel's place in the relaxation array and in the
+    // addend's window is the same for all rows (the addend block itself is per row)
     const bool has_add = p.add.data != nullptr;
+    const long long u_ridx = (long long)u0.b * ((long long)p.Ho * p.Wo * N) + (long long)(u_A * p.Wo + u_B) * N;
+    long long u_aoff = -1;
+    const long long u_astride = (long long)p.add.wy * p.add.wx * N;
+    if (uni && has_add) {
+        const int ay = u_A - clampi(p.add.Sy * u0.ys - p.add.Py, 0, p.add.H - p.add.wy);
+        const int ax = u_B - clampi(p.add.Sx * u0.xs - p.add.Px, 0, p.add.W - p.add.wx);
+        if (ay >= 0 && ay < p.add.wy && ax >= 0 && ax < p.add.wx) u_aoff = (long long)(ay * p.add.wx + ax) * N;
+    }
+    // uniform path: the lane's columns have ONE relaxation entry each, whatever the row: the two multipliers a
+    // coefficient can take (upper slope for a >= 0, lower slope 0 or 1 for a < 0) are formed once per column
+    double g_pos[TN], g_neg[TN];
+    if (uni && p.out_grl) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = SMALLN ? n0 + (lm & 3) : n0 + j * 16 + lm;
+            const float g = n < N ? p.out_grl[u_ridx + n] : 0.f;
+            g_pos[j] = (double)fabsf(g);
+            g_neg[j] = signbit(g) ? 0.0 : 1.0;
+        }
+    }
+    // stores through a buffer resource over the wave's rows: 32-bit offsets
+    const uint32_t out_row_bytes = (uint32_t)opix * (uint32_t)N * 4u;
+    const __amdgpu_buffer_rsrc_t rsrcO = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(p.out + (size_t)r_wave * opix * N), 0, (int)((uint32_t)rows_here * out_row_bytes), 0x00020000);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -743,18 +826,21 @@ __global__ __launch_bounds__(256) void cross_direct_kernel(const CrossParams p) 
             const int rl = i * 16 + (SMALLN ? 4 * (lm >> 2) : 4 * r4) + lk;
             const int r = r_wave + rl;
             if (r >= p.nrows) continue;
-            const long long ridx = s_ridx[wave * 16 * TM + rl];
-            const long long aoff = has_add ? s_aoff[wave * 16 * TM + rl] : -1;
+            const long long ridx = uni ? u_ridx : s_ridx[wave * 16 * TM + rl];
+            const long long aoff = !has_add ? -1 : !uni ? s_aoff[wave * 16 * TM + rl] : u_aoff < 0 ? -1 : (long long)r * u_astride + u_aoff;
             const float* add_src = aoff >= 0 ? p.add.data + aoff : nullptr;
-            float* out_row = p.out + ((size_t)r * opix + pix) * N;
+            const uint32_t out_off = (uint32_t)rl * out_row_bytes + (uint32_t)pix * (uint32_t)N * 4u;
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const int n = SMALLN ? n0 + (lm & 3) : n0 + j * 16 + lm;
                 if (n >= N) continue;
                 double v = acc[i][j][r4];
                 if (add_src) v += (double)add_src[n];
-                if (p.out_grl) v *= (double)relax_factor(v, p.out_grl[ridx + n]);
-                out_row[n] = (float)v;
+                if (p.out_grl) {
+                    if (uni) v *= (v >= 0.0 ? g_pos[j] : g_neg[j]);
+                    else v *= (double)relax_factor(v, p.out_grl[ridx + n]);
+                }
+                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint((float)v), rsrcO, (int)(out_off + (uint32_t)n * 4u), 0, 0);
             }
         }
     }
