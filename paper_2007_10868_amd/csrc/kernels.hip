@@ -199,6 +199,30 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
 
     // ---- loader bookkeeping: thread -> (tile row ld_row (+64*i), channel quad q4)
     const int ld_row = tid >> 2, q4 = (tid & 3) * 4;
+    // The rows of a tile are consecutive tasks, i.e. mostly the channels of ONE position of the start layer in one box:
+    // then every row has the same window origins and can use the same taps, and the tap geometry is computed once, in
+    // scalar registers (r_tile is uniform), instead of per thread in vector instructions that cost matrix time.
+    const RowInfo u0 = row_info(p.rm, r_tile), u1 = row_info(p.rm, r_tile + rows_here - 1);
+    const bool uni = !DENSE && p.rm.rowid == nullptr && u0.b == u1.b && u0.ys == u1.ys && u0.xs == u1.xs &&
+                     (r_tile + rows_here <= p.rm.Rc || r_tile >= p.rm.Rc);
+    const int u_oiy = clampi(p.in.Sy * u0.ys - p.in.Py, 0, p.in.H - p.in.wy);
+    const int u_oix = clampi(p.in.Sx * u0.xs - p.in.Px, 0, p.in.W - p.in.wx);
+    const int u_A = clampi(p.oSy * u0.ys - p.oPy, 0, p.Ho - p.owy) + pa, u_B = clampi(p.oSx * u0.xs - p.oPx, 0, p.Wo - p.owx) + pb;
+    const uint32_t u_yy0 = (uint32_t)(u_A + p.ph), u_xx0 = (uint32_t)(u_B + p.pw);
+    const int u_ydiv = (int)fast_div(u_yy0, p.div_sh), u_xdiv = (int)fast_div(u_xx0, p.div_sw);
+    const int u_ymod = (int)(u_yy0 - (uint32_t)u_ydiv * (uint32_t)p.sh), u_xmod = (int)(u_xx0 - (uint32_t)u_xdiv * (uint32_t)p.sw);
+    const int u_ty = p.in.tSy * u0.ys - p.in.tPy, u_tx = p.in.tSx * u0.xs - p.in.tPx;
+    const int u_ylo = max(max(u_ty, u_oiy), 0), u_yhi = min(min(u_ty + p.in.tWy, u_oiy + p.in.wy), p.in.H);
+    const int u_xlo = max(max(u_tx, u_oix), 0), u_xhi = min(min(u_tx + p.in.tWx, u_oix + p.in.wx), p.in.W);
+    // tap t reaches this pixel from inside the common window?  poff = element offset of the window entry it reads
+    auto tap_uniform = [&](int t, int& poff) -> bool {
+        const int f = (int)fast_div((uint32_t)t, p.div_kw), g = t - f * p.kw;
+        const int fdiv = (int)fast_div((uint32_t)f, p.div_sh), fmod = f - fdiv * p.sh;
+        const int gdiv = (int)fast_div((uint32_t)g, p.div_sw), gmod = g - gdiv * p.sw;
+        const int y = u_ydiv - fdiv, x = u_xdiv - gdiv;
+        poff = ((y - u_oiy) * p.in.wx + (x - u_oix)) * Ck;
+        return u_ymod == fmod && u_xmod == gmod && y >= u_ylo && y < u_yhi && x >= u_xlo && x < u_xhi;
+    };
     uint32_t a_rowoff[APT];                 // byte offset of (row's block, channel q4) inside rsrcA
     int a_ydiv[APT], a_xdiv[APT], a_ymod[APT], a_xmod[APT], a_oiy[APT], a_oix[APT];
     uint32_t a_ty[APT], a_tx[APT];          // the row's exact window inside the stored one: first index | size << 16
@@ -207,6 +231,10 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
     for (int i = 0; i < APT; ++i) {
         const int rl = ld_row + 64 * i;
         a_ok[i] = rl < rows_here;
+        a_rowoff[i] = ((uint32_t)rl * row_elems + (uint32_t)q4) * 4u;
+        a_ydiv[i] = a_xdiv[i] = a_ymod[i] = a_xmod[i] = a_oiy[i] = a_oix[i] = 0;
+        a_ty[i] = a_tx[i] = 0;
+        if (uni) continue;
         const RowInfo ri = row_info(p.rm, r_tile + (a_ok[i] ? rl : 0));
         // window pixel (pa,pb) is pixel (A,B) of the input layer; tap (f,g) of the filter reads it from
         // layer-output pixel ((A + ph - f)/sh, (B + pw - g)/sw) when both divisions are exact
@@ -226,7 +254,6 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
             a_ty[i] = (uint32_t)(ylo - a_oiy[i]) | ((uint32_t)max(yhi - ylo, 0) << 16);
             a_tx[i] = (uint32_t)(xlo - a_oix[i]) | ((uint32_t)max(xhi - xlo, 0) << 16);
         }
-        a_rowoff[i] = ((uint32_t)rl * row_elems + (uint32_t)q4) * 4u;
         if ((tid & 3) == 0 && a_ok[i]) epilogue_row_info(p, ri, r_tile + rl, pa, pb, s_ridx[rl], s_aoff[rl]);
     }
     // per-thread byte offsets for the current tap: A row (kOOB when the tap misses the row's window), B column
@@ -265,7 +292,19 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
 
     // ---- which taps does this tile need at all?  (bit t of the mask; filters with more than 64 taps keep all)
     unsigned long long tapmask = ~0ull;
-    if (!DENSE && taps > 1 && taps <= 64) {
+    uint32_t s_tapoff = 0;                       // uniform path: byte offset of the current tap's window entry (scalar)
+    if (uni) {
+#pragma unroll
+        for (int i = 0; i < APT; ++i) a_voff[i] = a_ok[i] ? a_rowoff[i] : kOOB;
+        if (taps <= 64) {
+            unsigned long long m = 0;
+            for (int t = 0; t < taps; ++t) {
+                int poff;
+                if (tap_uniform(t, poff)) m |= 1ull << t;
+            }
+            tapmask = m;
+        }
+    } else if (!DENSE && taps > 1 && taps <= 64) {
         unsigned long long mine = 0;
         for (int t = 0; t < taps; ++t)
             if (set_tap(t)) mine |= 1ull << t;
@@ -288,8 +327,25 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
     for (int t = next_tap(0); t < taps; t = next_tap(t + 1)) ++n_taps;
     const int nIt = n_taps * kchunks;
 
+    // the step the next loads are for moves on to tap t (uniform)
+    auto enter_tap = [&](int t) {
+        if (uni) {
+            int poff;
+            if (tap_uniform(t, poff)) {      // (filters with more than 64 taps visit all: a tap that misses reads nothing)
+                s_tapoff = (uint32_t)poff * 4u;
+#pragma unroll
+                for (int i = 0; i < APT; ++i) a_voff[i] = a_ok[i] ? a_rowoff[i] : kOOB;
+            } else {
+                s_tapoff = 0;
+#pragma unroll
+                for (int i = 0; i < APT; ++i) a_voff[i] = kOOB;
+            }
+        } else {
+            set_tap(t);
+        }
+    };
     int ld_t = next_tap(0), ld_d0 = 0;
-    if (ld_t < taps) set_tap(ld_t);
+    if (ld_t < taps) enter_tap(ld_t);
 
     // global -> register staging holds raw float32 words only: nothing depends on the loads until the
     // MFMA loop of the current tile has been issued; conversion happens at the register -> LDS copy.
@@ -298,7 +354,7 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
     F4 a_raw[APT], b_raw[BPT];
     auto load_tiles = [&]() {
         const int rem = Ck - ld_d0;                                 // channels left in this tap (uniform)
-        const uint32_t soffA = (uint32_t)ld_d0 * 4u;
+        const uint32_t soffA = s_tapoff + (uint32_t)ld_d0 * 4u;
         const uint32_t soffB = ((uint32_t)ld_t * (uint32_t)N * (uint32_t)Ck + (uint32_t)ld_d0) * 4u;
         if (VEC && rem >= BK) {
 #pragma unroll
@@ -326,7 +382,7 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
         if (ld_d0 >= Ck) {                                          // next needed tap (uniform, once per kchunks steps)
             ld_d0 = 0;
             ld_t = next_tap(ld_t + 1);
-            if (ld_t < taps) set_tap(ld_t);
+            if (ld_t < taps) enter_tap(ld_t);
         }
     };
     // LDS addresses of this thread's stores and MFMA operand loads (fixed; the buffer index is an immediate)
@@ -491,6 +547,23 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
             }
         }
     }
+    // uniform path: the pixel's place in the relaxation array and in the addend's window is the same for all rows
+    const long long u_ridx = (long long)u0.b * ((long long)p.Ho * p.Wo * N) + (long long)(u_A * p.Wo + u_B) * N;
+    long long u_aoff = -1;
+    const long long u_astride = (long long)p.add.wy * p.add.wx * N;
+    if (uni && has_add) {
+        const int ay = u_A - clampi(p.add.Sy * u0.ys - p.add.Py, 0, p.add.H - p.add.wy);
+        const int ax = u_B - clampi(p.add.Sx * u0.xs - p.add.Px, 0, p.add.W - p.add.wx);
+        if (ay >= 0 && ay < p.add.wy && ax >= 0 && ax < p.add.wx) u_aoff = (long long)(ay * p.add.wx + ax) * N;
+    }
+    if (uni && p.out_grl) {
+        same_box = true;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = n0 + wn * WTN + j * 16 + lm;
+            g_same[j] = n < N ? p.out_grl[u_ridx + n] : 0.f;
+        }
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -498,8 +571,8 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
             const int rl = wm * WTM + i * 16 + 4 * r4 + lk;              // register r4 of the lane is row 4*r4 + l/16
             const int r = r_tile + rl;
             if (r >= p.nrows) continue;
-            const long long ridx = s_ridx[rl];
-            const long long aoff = has_add ? s_aoff[rl] : -1;
+            const long long ridx = uni ? u_ridx : s_ridx[rl];
+            const long long aoff = !has_add ? -1 : !uni ? s_aoff[rl] : u_aoff < 0 ? -1 : (long long)r * u_astride + u_aoff;
             const float* add_src = aoff >= 0 ? p.add.data + aoff : nullptr;
             float* out_row = p.out + ((size_t)r * opix + pix) * N;
 #pragma unroll
@@ -508,13 +581,25 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
                 if (n >= N) continue;
                 double v = acc[i][j][r4];
                 if (add_src) v += (double)add_src[n];
-                if (p.out_grl) v *= (double)relax_factor(v, (DENSE && same_box) ? g_same[j] : p.out_grl[ridx + n]);
+                if (p.out_grl) v *= (double)relax_factor(v, same_box ? g_same[j] : p.out_grl[ridx + n]);
                 out_row[n] = (float)v;
             }
         }
     }
 }
 
+// Narrow layers (at most 32 input channels): the same implicit GEMM without LDS and without barriers.
+//   With one wave across the N tile, an A value is needed by exactly one wave, in exactly the place the MFMA wants
+//   it: lane l supplies A[row l%16][k l/16], so a lane that loads the 4 consecutive channels 4*(l/16)..+3 of row l%16
+//   (one 16-byte buffer load; the four lanes of a row cover 64 contiguous bytes) holds its operand for the four MFMA
+//   steps of a 16-channel K step, in the k-permutation described at cross_kernel.  The filter values are fetched the
+//   same way (lane l: column l%16, the same 4 channels; they stay in the vector L1).  Every wave works on its own
+//   16*TM rows and skips the taps that none of ITS rows can use; the next step's loads are issued before the MFMAs of
+//   the current one and other waves' MFMAs cover what latency is left.
+//   TN_ = 0 stands for layers with at most 4 input channels (the image).  A 16-column MFMA tile would be 13/16 padding
+//   there; the 4x4x4 instruction (4 independent 4x4 blocks) keeps 16 rows per instruction with 4 columns.  Its operand
+//   layout: lane l holds A[row l%16][k l/16] (as for 16x16x4), B[k l/16][column l%4] (the same B for every block), and
+//   receives D[row 4*((l%16)/4) + l/16][column l%4].
 template <int TM, int TN_, bool VEC>
 __global__ __launch_bounds__(256) void cross_direct_kernel(const CrossParams p) {
     constexpr bool SMALLN = (TN_ == 0);
