@@ -33,6 +33,8 @@ def main():
     ap.add_argument("--float-inference", action="store_true",
                     help="bounds that also cover every float32 evaluation order of the network (inference rounding)")
     ap.add_argument("--graph", action="store_true", help="replay the pass as a captured HIP graph")
+    ap.add_argument("--weight-scale", type=float, default=1.0,
+                    help="multiply every weight by this factor (well below 1: most ReLUs stable, as in robustly trained nets)")
     ap.add_argument("--eps", type=float, default=0.0, help="override the configuration's perturbation radius")
     ap.add_argument("--cpu-sample", type=int, default=-1, help="inputs the oracle is timed on (0: skip)")
     args = ap.parse_args()
@@ -48,6 +50,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     net = wl.config(args.config)
+    if args.weight_scale != 1.0:
+        net = wl.contracted(net, args.weight_scale)
     if args.eps > 0:
         net.eps = args.eps
     batch = args.batch or net.n_inputs

@@ -210,6 +210,21 @@ def config(i: int) -> Net:
     raise ValueError(i)
 
 
+def contracted(net: Net, weight_scale: float) -> Net:
+    """The same network with every weight matrix / filter multiplied by `weight_scale` (biases kept).  With random
+    He-normal weights the interval widths grow from layer to layer and every ReLU is unstable after the first few;
+    a factor well below 1 stops that growth and leaves most ReLUs stable, which is the regime of the paper's robustly
+    trained networks (Section 5), where early termination removes most of the work."""
+    out = Net(f"{net.name}_w{weight_scale:g}", net.input_shape, eps=net.eps, n_inputs=net.n_inputs,
+              input_seed_base=net.input_seed_base)
+    for L in net.layers:
+        d = dict(L)
+        if d["type"] in ("dense", "conv"):
+            d["W"] = (d["W"] * np.float32(weight_scale)).astype(np.float32)
+        out.layers.append(d)
+    return out
+
+
 def scaled_resnet(div: int, spatial: int = 32, blocks=(3, 4, 6, 3), seed: int = 1004, eps=0.5 / 255.0) -> Net:
     """Same depth and topology as configuration 4 with channels divided by `div`."""
     ch = tuple(max(1, c // div) for c in (64, 128, 256, 512))
