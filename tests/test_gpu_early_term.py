@@ -118,6 +118,32 @@ def test_config1_rows_are_removed():
     assert stopped > 0 and done <= full
 
 
+def test_contracted_config1_most_work_is_removed():
+    """The regime early termination is for (most ReLUs stable): the benchmark network with its weights scaled by 0.3,
+    in the benchmark's launch configuration (all rows of a batch in the same launches, rows physically removed)."""
+    net = wl.contracted(wl.config(1), 0.3)
+    eps = net.eps
+    X = np.stack([net.center(j) for j in range(8)])
+    g = make_gpu(net)
+    g.set_early_termination(True)
+    g.analyze_batch(X, eps)
+    done, full = g.early_termination_stats()
+    print(f"contracted config1: crossing work {done / full:.3f} of full")
+    assert done < 0.6 * full
+    for b in (0, 7):
+        stopped = check_early(net, g, X[b], eps, batch_index=b, what=f"contracted config1[{b}]", samples=50)
+        assert stopped > 1000
+    # batched == one by one, bit for bit, also when rows are removed
+    g1 = make_gpu(net)
+    g1.set_early_termination(True)
+    g1.analyze(X[7], eps)
+    for lid in bounded_affine_layers(net):
+        a, b = g.get_bounds_f64(lid, 7)
+        c, d = g1.get_bounds_f64(lid)
+        assert np.array_equal(a, c) and np.array_equal(b, d)
+        assert np.array_equal(g.get_term_layer(lid, 7), g1.get_term_layer(lid))
+
+
 def test_chunked_batched_conv():
     """Small workspace: many chunks, each with its own task list."""
     net = wl.config(2)
