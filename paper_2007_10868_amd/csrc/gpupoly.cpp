@@ -245,6 +245,25 @@ long long block_elems(const Geom& g, const Layer& l) {
     return (long long)std::min(g.Wy, l.H) * std::min(g.Wx, l.W) * l.C;
 }
 
+// Average, over the positions of the start layer, of the share of a stored window that lies inside the exact
+// dependence window: the stored block of a border row is a full-size window shifted inside the layer (or the whole
+// layer), and what it holds outside the exact window are structural zeros that no step multiplies.  The algorithmic
+// work of a step counts the exact part only.
+double exact_share(const Geom& g, const Geom& t, const Layer& l, int Hs, int Ws) {
+    if (is_everywhere(t)) return 1.0;
+    auto axis = [](int S, int P, int W, int tS, int tP, int tW, int H, int n_pos) {
+        const int w = std::min(W, H);
+        double sum = 0.0;
+        for (int pos = 0; pos < n_pos; ++pos) {
+            const int o = std::min(std::max(S * pos - P, 0), H - w);
+            const int lo = std::max(std::max(tS * pos - tP, o), 0), hi = std::min(std::min(tS * pos - tP + tW, o + w), H);
+            sum += std::max(hi - lo, 0);
+        }
+        return sum / ((double)n_pos * w);
+    };
+    return axis(g.Sy, g.Py, g.Wy, t.Sy, t.Py, t.Wy, l.H, Hs) * axis(g.Sx, g.Px, g.Wx, t.Sx, t.Px, t.Wx, l.W, Ws);
+}
+
 // ---- topology-derived data ---------------------------------------------------------------------
 void land_of(const gp_net* net, int q, std::vector<int>& out) {   // where a coefficient over layer q goes next
     const Layer& l = net->L[q];
@@ -656,7 +675,8 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
             const Layer& p = net->L[op.layer_out];
             const double taps = (a.type == T_DENSE) ? 1.0 : (double)a.kh * a.kw;
             const double cin = (a.type == T_DENSE) ? (double)p.n : (double)p.C;
-            rem_flop[i] += 2.0 * (double)block_elems(op.g_in, a) * taps * cin;
+            rem_flop[i] += 2.0 * (double)block_elems(op.g_in, a) * taps * cin *
+                           (certify ? 1.0 : exact_share(op.g_in, op.t_in, a, ls.H, ls.W));
         }
     }
 
@@ -876,7 +896,9 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                 const double taps = (a.type == T_DENSE) ? 1.0 : (double)a.kh * a.kw;
                 const double cin = (a.type == T_DENSE) ? (double)p.n : (double)p.C;
                 const bool first = (op.layer_in == start);
-                const double per_row = first ? 0.0 : 2.0 * in_el * taps * cin;
+                // (averaged over the start layer's positions, the part of the stored block inside the exact window)
+                const double share = certify ? 1.0 : exact_share(op.g_in, op.t_in, a, ls.H, ls.W);
+                const double per_row = first ? 0.0 : 2.0 * in_el * taps * cin * share;
                 if (early) {
                     net->early_flop_done += per_row * nrows;
                     net->early_flop_full += per_row * rm0.Rc * nsign;
