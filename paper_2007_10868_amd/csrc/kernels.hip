@@ -620,6 +620,20 @@ __global__ __launch_bounds__(256) void cross_direct_kernel(const CrossParams p) 
     const int nt = (int)(logical - t2 * (uint32_t)p.ntiles_n);
     const uint32_t rt = fast_div(t2, p.div_opix);
     const int pix = (int)(t2 - rt * (uint32_t)opix);
+    // Image layers: the filter (float64, 4 columns, the missing ones zero) is staged in LDS once per work-group.  With
+    // 4 output columns a K step moves 1 KB of filter values per wave through the vector L1 next to 2 KB of block values,
+    // and the L1 (64 B/clk) is what bounds these steps; from LDS the filter costs neither L1 traffic nor conversions.
+    extern __shared__ __attribute__((aligned(16))) double s_w[];          // [tap][4][Ck + 2]
+    const int ldw = p.in.C + 2;
+    const bool lds_wt = SMALLN && p.lds_wt != 0;
+    if (lds_wt) {
+        const int Ck_ = p.in.C, cnt = p.kh * p.kw * 4 * Ck_;
+        for (int idx = tid; idx < cnt; idx += 256) {
+            const int c = idx % Ck_, tn = idx / Ck_, n = tn & 3, t = tn >> 2;
+            s_w[tn * ldw + c] = n < p.Co ? p.wt64[((size_t)t * p.Co + n) * Ck_ + c] : 0.0;
+        }
+        __syncthreads();                                       // the only barrier; no wave has left yet
+    }
     const int r_wave = (int)rt * BM + wave * 16 * TM;          // first row of this wave
     if (r_wave >= p.nrows) return;                             // no barrier anywhere below
     const int pa = (int)fast_div((uint32_t)pix, p.div_owx), pb = pix - pa * p.owx;
@@ -855,16 +869,57 @@ __global__ __launch_bounds__(256) void cross_direct_kernel(const CrossParams p) 
                 if (ld_t < taps) enter_tap(ld_t);
             }
         };
-        if (nIt > 0) { issue(); advance(); }
-        for (int it = 0; it < nIt; ++it) {
-            double av[TM][4], bv[TN][4];
-            convert(av, bv);
-            __builtin_amdgcn_sched_barrier(0);
-            issue();
-            __builtin_amdgcn_sched_barrier(0);
-            mfmas(av, bv);
-            __builtin_amdgcn_sched_barrier(0);
-            advance();
+        if (lds_wt) {
+            // block values as above (the filter loads of issue() are dead here and drop out); the filter fragment of
+            // the NEXT step is fetched from LDS while the MFMAs of this one run
+            auto issue_a = [&]() {
+                const uint32_t soffA = s_tapoff + (uint32_t)ld_d0 * 4u;
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    uint4_t v = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, (int)a_voff[i], (int)soffA, 0);
+                    a_raw[i].v[0] = __uint_as_float(v.x); a_raw[i].v[1] = __uint_as_float(v.y);
+                    a_raw[i].v[2] = __uint_as_float(v.z); a_raw[i].v[3] = __uint_as_float(v.w);
+                }
+            };
+            const double* const w_lane = s_w + (lm & 3) * ldw + q4;
+            auto filter_frag = [&](int t, int d0, double (&b)[4]) {
+                const int tt = min(t, taps - 1);                // behind the last step: any valid address
+                const double2* src = reinterpret_cast<const double2*>(w_lane + tt * 4 * ldw + d0);
+                const double2 x = src[0], y = src[1];
+                b[0] = x.x; b[1] = x.y; b[2] = y.x; b[3] = y.y;
+            };
+            double bcur[4] = {0.0, 0.0, 0.0, 0.0}, bnext[4];
+            if (nIt > 0) { filter_frag(ld_t, ld_d0, bcur); issue_a(); advance(); }
+            for (int it = 0; it < nIt; ++it) {
+                double av[TM][4], bv[TN][4];
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) av[i][k] = (double)a_raw[i].v[k];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) bv[0][k] = bcur[k];
+                __builtin_amdgcn_sched_barrier(0);
+                issue_a();
+                filter_frag(ld_t, ld_d0, bnext);
+                __builtin_amdgcn_sched_barrier(0);
+                mfmas(av, bv);
+                __builtin_amdgcn_sched_barrier(0);
+                advance();
+#pragma unroll
+                for (int k = 0; k < 4; ++k) bcur[k] = bnext[k];
+            }
+        } else {
+            if (nIt > 0) { issue(); advance(); }
+            for (int it = 0; it < nIt; ++it) {
+                double av[TM][4], bv[TN][4];
+                convert(av, bv);
+                __builtin_amdgcn_sched_barrier(0);
+                issue();
+                __builtin_amdgcn_sched_barrier(0);
+                mfmas(av, bv);
+                __builtin_amdgcn_sched_barrier(0);
+                advance();
+            }
         }
     } else {
         if (nIt > 0) load_step();
@@ -941,8 +996,12 @@ static void launch_cross_direct(const CrossParams& p0, hipStream_t s) {
     p.div_opix = make_fastdiv((uint32_t)(p.owy * p.owx));
     const long long total = (long long)p.ntiles_m * p.ntiles_n * p.owy * p.owx;
     const unsigned blocks = (unsigned)(((total + 7) / 8) * 8);
-    if ((p.in.C & 3) == 0) hipLaunchKernelGGL((cross_direct_kernel<TM, TN, true>), dim3(blocks), dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((cross_direct_kernel<TM, TN, false>), dim3(blocks), dim3(256), 0, s, p);
+    // image layers: filter in LDS when its float64 copy exists, the K steps are whole and it fits beside 8 work-groups
+    const size_t w_bytes = (size_t)p.kh * p.kw * 4 * (p.in.C + 2) * sizeof(double);
+    p.lds_wt = (TN == 0 && p.wt64 && (p.in.C & 15) == 0 && w_bytes <= 24576) ? 1 : 0;
+    const size_t lds = p.lds_wt ? w_bytes : 0;
+    if ((p.in.C & 3) == 0) hipLaunchKernelGGL((cross_direct_kernel<TM, TN, true>), dim3(blocks), dim3(256), lds, s, p);
+    else hipLaunchKernelGGL((cross_direct_kernel<TM, TN, false>), dim3(blocks), dim3(256), lds, s, p);
 }
 
 // Layers with at most 4 input channels (the image): no matrix instruction.  An output pixel of such a step has N <= 4
