@@ -123,7 +123,7 @@ def main():
     # the same K steps replayed as one captured HIP graph per pass (no per-kernel events there, so this is reported
     # beside the metric, which stays the eager, event-instrumented region above)
     graph_ms = None
-    if not args.graph and not args.early_term:
+    if not args.graph and not args.early_term and ms_per_step < 2000.0:
         g.set_graph_replay(True)
         for _ in range(2):
             g.analyze_batch_dev(t_centers, net.eps)
