@@ -1545,6 +1545,32 @@ __global__ __launch_bounds__(256) void init_kernel(const InitParams p) {
             }
             *reinterpret_cast<float4*>(out + e) = make_float4(v[0], v[1], v[2], v[3]);
         }
+    } else if (p.mode == 2 && !p.dense && (p.C & 3) == 0) {
+        // the start layer's filter placed in the row's window over the predecessor: four channels of a window pixel per
+        // lane (16-byte loads and stores), pixel coordinates without divisions
+        const int oy = clampi(p.Sy * ri.ys - p.Py, 0, p.H - p.wy), ox = clampi(p.Sx * ri.xs - p.Px, 0, p.W - p.wx);
+        const int fy = ri.ys * p.sh - p.ph, fx = ri.xs * p.sw - p.pw;
+        for (int e = (blockIdx.y * 64 + (threadIdx.x & 63)) * 4; e < p.nelem; e += gridDim.y * 256) {
+            const uint32_t pix = fast_div((uint32_t)e, p.div_C);
+            const int c = e - (int)pix * p.C;
+            const uint32_t a = fast_div(pix, p.div_wx);
+            const int A = oy + (int)a, B = ox + (int)(pix - a * (uint32_t)p.wx);
+            const int f = A - fy, g = B - fx;
+            float v[4] = {0.f, 0.f, 0.f, 0.f};
+            if (f >= 0 && f < p.kh && g >= 0 && g < p.kw) {
+                const float4 wv = *reinterpret_cast<const float4*>(p.wt + ((size_t)(f * p.kw + g) * p.Cs + ri.cs) * p.C + c);
+                v[0] = ri.sign * wv.x; v[1] = ri.sign * wv.y; v[2] = ri.sign * wv.z; v[3] = ri.sign * wv.w;
+                if (p.out_grl) {
+                    const size_t j = (size_t)ri.b * ((size_t)p.H * p.W * p.C) + (size_t)(A * p.W + B) * p.C + c;
+                    const float4 gv = *reinterpret_cast<const float4*>(p.out_grl + j);
+                    const float gg[4] = {gv.x, gv.y, gv.z, gv.w};
+#pragma unroll
+                    for (int k = 0; k < 4; ++k)
+                        if (v[k] != 0.f) v[k] = (float)((double)v[k] * (double)relax_factor((double)v[k], gg[k]));
+                }
+            }
+            *reinterpret_cast<float4*>(out + e) = make_float4(v[0], v[1], v[2], v[3]);
+        }
     } else
     for (int e = blockIdx.y * 64 + (threadIdx.x & 63); e < p.nelem; e += gridDim.y * 64) {
         float v = 0.f;
@@ -1568,8 +1594,8 @@ __global__ __launch_bounds__(256) void init_kernel(const InitParams p) {
                 v = (float)((double)v * (double)relax_factor((double)v, p.out_grl[(size_t)ri.b * p.nelem + e]));
         } else {
             // window over the predecessor (dims H,W,C here), origin from the row's position
-            int pix = e / p.C, c = e - pix * p.C;
-            int a = pix / p.wx, bb = pix - a * p.wx;
+            int pix = (int)fast_div((uint32_t)e, p.div_C), c = e - pix * p.C;
+            int a = (int)fast_div((uint32_t)pix, p.div_wx), bb = pix - a * p.wx;
             int A = clampi(p.Sy * ri.ys - p.Py, 0, p.H - p.wy) + a;
             int B = clampi(p.Sx * ri.xs - p.Px, 0, p.W - p.wx) + bb;
             int f = A - (ri.ys * p.sh - p.ph), g = B - (ri.xs * p.sw - p.pw);
@@ -1593,9 +1619,13 @@ __global__ __launch_bounds__(256) void init_kernel(const InitParams p) {
     }
 }
 
-void launch_init(const InitParams& p, hipStream_t s) {
-    if (p.nrows <= 0 || p.nelem <= 0) return;
-    const int per = (p.mode == 2 && p.dense && (p.nelem & 3) == 0) ? p.nelem / 4 : p.nelem;   // items per row
+void launch_init(const InitParams& p0, hipStream_t s) {
+    if (p0.nrows <= 0 || p0.nelem <= 0) return;
+    InitParams p = p0;
+    p.div_C = make_fastdiv((uint32_t)std::max(p.C, 1));
+    p.div_wx = make_fastdiv((uint32_t)std::max(p.wx, 1));
+    const bool vec4 = p.mode == 2 && (p.dense ? (p.nelem & 3) == 0 : (p.C & 3) == 0);
+    const int per = vec4 ? p.nelem / 4 : p.nelem;   // items per row
     const int ychunks = (int)fmin((double)((per + 63) / 64), 64.0);
     hipLaunchKernelGGL(init_kernel, dim3((p.nrows + 3) / 4, ychunks), dim3(256), 0, s, p);
 }

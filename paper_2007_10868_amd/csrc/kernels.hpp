@@ -131,6 +131,7 @@ struct InitParams {
     const double* eta;     // mode 2: [batch][n_start] float32 evaluation error of the start neurons (added to c); null: none
     double* c; double* err; double* best;
     int seeded;            // best already holds the rows' interval image: leave it
+    FastDiv div_C, div_wx; // filled by the launcher
 };
 
 struct FinalizeParams {
