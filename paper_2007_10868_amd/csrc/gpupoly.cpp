@@ -101,6 +101,7 @@ struct gp_net {
     bool analyzed = false;
     bool weights_uploaded = false;
     int* d_flag = nullptr;
+    double* d_xmax_all = nullptr;  // [layers][batch] running max of |bounds| per layer and box (one array: one clear per pass)
     int* d_labels = nullptr;
     float* d_margins = nullptr;
     // arbitrary linear forms of the outputs (gp_bound_outputs)
@@ -475,7 +476,7 @@ gp_status get_plan(gp_net* net, int lid, Plan** out) {
 
 // ---- device state ------------------------------------------------------------------------------
 void free_layer_bounds(Layer& l) {   // callers drop the captured graph
-    dfree(l.d_lo); dfree(l.d_hi); dfree(l.d_rho); dfree(l.d_kap); dfree(l.d_xmax); dfree(l.d_grl); dfree(l.d_term);
+    dfree(l.d_lo); dfree(l.d_hi); dfree(l.d_rho); dfree(l.d_kap); dfree(l.d_grl); dfree(l.d_term);   // d_xmax: part of d_xmax_all
     dfree(l.d_eta); dfree(l.d_eta_thru);
     l.d_lo = l.d_hi = l.d_rho = l.d_kap = l.d_xmax = l.d_eta = l.d_eta_thru = nullptr;
     l.d_grl = nullptr;
@@ -539,6 +540,8 @@ gp_status ensure_device(gp_net* net, int batch) {
         for (auto& l : net->L) free_layer_bounds(l);
         dfree(net->d_labels); net->d_labels = nullptr;
         dfree(net->d_margins); net->d_margins = nullptr;
+        dfree(net->d_xmax_all); net->d_xmax_all = nullptr;
+        HIP_TRY(net, hipMalloc((void**)&net->d_xmax_all, sizeof(double) * batch * net->L.size()));
         for (size_t i = 0; i < net->L.size(); ++i) {
             Layer& l = net->L[i];
             size_t cnt = (size_t)l.n * batch;
@@ -546,7 +549,7 @@ gp_status ensure_device(gp_net* net, int batch) {
             if (has_bounds(net, (int)i) || net->early) {
                 HIP_TRY(net, hipMalloc((void**)&l.d_lo, cnt * sizeof(double)));
                 HIP_TRY(net, hipMalloc((void**)&l.d_hi, cnt * sizeof(double)));
-                HIP_TRY(net, hipMalloc((void**)&l.d_xmax, sizeof(double) * batch));
+                l.d_xmax = net->d_xmax_all + i * (size_t)batch;
             }
             if (net->early && l.need_bounds && l.type != T_RELU && i > 0)
                 HIP_TRY(net, hipMalloc((void**)&l.d_term, cnt * sizeof(int)));
@@ -941,7 +944,6 @@ gp_status analyze_layers(gp_net* net, int batch) {
     int nl = (int)net->L.size();
     for (int i = 1; i < nl; ++i) {
         Layer& l = net->L[i];
-        if (l.d_xmax) gp::launch_fill_f64(l.d_xmax, 0.0, batch, net->stream);
         if (l.type == T_RELU) {
             gp::ReluParams rp;
             rp.plo = net->L[l.a].d_lo; rp.phi = net->L[l.a].d_hi;
@@ -1031,7 +1033,7 @@ gp_status begin_analysis(gp_net* net, int batch) {
 
 void enqueue_reset(gp_net* net, int batch) {
     gp::launch_fill_i32(net->d_flag, 0, 1, net->stream);
-    gp::launch_fill_f64(net->L[0].d_xmax, 0.0, batch, net->stream);
+    gp::launch_fill_f64(net->d_xmax_all, 0.0, (long long)batch * (long long)net->L.size(), net->stream);
 }
 
 bool same_key(const gp_net::GraphKey& a, const gp_net::GraphKey& b) {
@@ -1092,6 +1094,7 @@ void gp_net_destroy(gp_net* net) {
     if (net->graph_exec) (void)hipGraphExecDestroy(net->graph_exec);
     if (net->cap_stream) (void)hipStreamDestroy(net->cap_stream);
     dfree(net->d_forms); dfree(net->d_form_off); dfree(net->d_form_out);
+    dfree(net->d_xmax_all);
     dfree(net->d_flag); dfree(net->d_labels); dfree(net->d_margins); dfree(net->d_centers);
     dfree(net->ws_own);
     for (int k = 0; k < 2; ++k)
@@ -1417,7 +1420,7 @@ gp_status gp_analyze_box(gp_net* net, const float* lo, const float* hi) {
     for (long long i = 0; i < in.n; ++i) xmax = std::max(xmax, std::max(std::fabs(l[i]), std::fabs(h[i])));
     HIP_TRY(net, hipMemcpyAsync(in.d_lo, l.data(), in.n * sizeof(double), hipMemcpyHostToDevice, net->stream));
     HIP_TRY(net, hipMemcpyAsync(in.d_hi, h.data(), in.n * sizeof(double), hipMemcpyHostToDevice, net->stream));
-    gp::launch_fill_i32(net->d_flag, 0, 1, net->stream);
+    enqueue_reset(net, 1);
     HIP_TRY(net, hipMemcpyAsync(in.d_xmax, &xmax, sizeof(double), hipMemcpyHostToDevice, net->stream));
     HIP_TRY(net, hipStreamSynchronize(net->stream));
     st = analyze_layers(net, 1);
