@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgpupoly_hip.so")
-SOURCES = ["gpupoly.cpp", "kernels.hip"]
+SOURCES = ["gpupoly.cpp", "cross.hip", "scan.hip", "layers.hip"]
 # packed-fp32 instructions are switched off for every kernel of this library
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-mllvm", "-amdgpu-mfma-vgpr-form", "-Wno-unused-command-line-argument"]
@@ -15,7 +15,7 @@ FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-x",
 
 def build(force: bool = True, verbose: bool = False) -> str:
     srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    deps = srcs + [os.path.join(CSRC, "kernels.hpp"), os.path.join(HERE, "..", "include", "gpupoly.h")]
+    deps = srcs + [os.path.join(CSRC, "kernels.hpp"), os.path.join(CSRC, "device_common.hpp"), os.path.join(HERE, "..", "include", "gpupoly.h")]
     if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(d) for d in deps):
         return LIB
     cmd = ["hipcc", *FLAGS, "-o", LIB, *srcs]

@@ -6,52 +6,10 @@
 // is rounded once to float32.  Every rounding is bounded and the bound, multiplied by the largest
 // magnitude the neuron can take, is added to a per-row slack `err` that is part of every
 // candidate bound.  All rows are upper-bound expressions (lower bounds are taken on -x).
-#include "kernels.hpp"
-
-#include <math.h>
-#include <type_traits>
-#include <stdlib.h>
-#include <string.h>
+// This file: crossing an affine layer (Algorithm 1 as an implicit GEMM), in three forms chosen by the layer's width.
+#include "device_common.hpp"
 
 namespace gp {
-
-typedef double double4_t __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ int clampi(int v, int lo, int hi) { return min(max(v, lo), hi); }
-
-struct RowInfo {
-    int b, ys, xs, cs;
-    float sign;
-};
-
-__device__ __forceinline__ RowInfo row_info(const RowMap& rm, int r) {
-    RowInfo ri;
-    int rr = r;
-    ri.sign = 1.f;
-    if (r >= rm.Rc) {
-        rr = r - rm.Rc;
-        ri.sign = -1.f;
-    }
-    if (rm.rowid) rr = rm.rowid[rr];
-    const uint32_t g = (uint32_t)(rm.row0 + rr);
-    const uint32_t b = fast_div(g, rm.div_n);
-    const uint32_t i = g - b * (uint32_t)rm.n_start;
-    const uint32_t pos = fast_div(i, rm.div_c);
-    const uint32_t ys = fast_div(pos, rm.div_w);
-    ri.b = (int)b;
-    ri.cs = (int)(i - pos * (uint32_t)rm.Cs);
-    ri.ys = (int)ys;
-    ri.xs = (int)(pos - ys * (uint32_t)rm.Ws);
-    return ri;
-}
-
-// where row r keeps its best candidate: the layout of the chunk before any row was removed
-__device__ __forceinline__ int best_index(const RowMap& rm, int r) {
-    const int half = r >= rm.Rc ? 1 : 0;
-    int rr = r - half * rm.Rc;
-    if (rm.rowid) rr = rm.rowid[rr];
-    return half * rm.Rc0 + rr;
-}
 
 // ------------------------------------------------------------------------------------------------
 // Crossing an affine layer: per row a transposed convolution from the window in the layer's output
@@ -62,50 +20,6 @@ __device__ __forceinline__ int best_index(const RowMap& rm, int r) {
 // B operand: filter taps [tap][C_out][C_in].
 // float64 MFMA 16x16x4; accumulators D[i][j]: lane l, register r holds i = 4*r + l/16, j = l%16.
 // ------------------------------------------------------------------------------------------------
-typedef unsigned int uint4_t __attribute__((ext_vector_type(4)));
-
-struct F4 {
-    float v[4];
-};
-
-// a value every lane of the wave holds alike, moved to scalar registers: what is derived from it (loop bounds, tap
-// numbers, scalar offsets and resource descriptors of buffer loads) then stays scalar; left in vector registers the
-// compiler would wrap every such load into a loop over the distinct values
-__device__ __forceinline__ unsigned long long wave_uniform(unsigned long long v) {
-    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
-    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
-    return ((unsigned long long)hi << 32) | lo;
-}
-
-constexpr uint32_t kOOB = 0x80000000u;   // byte offset beyond every buffer range: the load returns 0
-
-// 4 consecutive floats at byte offset `off` of a buffer resource; offsets beyond the resource's range
-// read as 0 (hardware range check), so invalid taps / rows / channels need no masking instructions.
-template <bool VEC>
-__device__ __forceinline__ F4 buf_ld4(__amdgpu_buffer_rsrc_t rsrc, uint32_t off, int nvalid) {
-    F4 r;
-    if (VEC) {
-        uint4_t v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off, 0, 0);
-        r.v[0] = __uint_as_float(v.x); r.v[1] = __uint_as_float(v.y);
-        r.v[2] = __uint_as_float(v.z); r.v[3] = __uint_as_float(v.w);
-    } else {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            uint32_t o = (j < nvalid) ? off + 4u * j : kOOB;
-            r.v[j] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)o, 0, 0));
-        }
-    }
-    return r;
-}
-
-// ReLU relaxation of one neuron packed in one float: |g| is the slope of the upper line, the sign bit
-// is set when the lower line is 0 (lam = 0) and clear when it is x (lam = 1).
-// A coefficient a over relu(x) becomes a * relax_factor(a, g) over x (Section 2: positive coefficients
-// take the upper line, negative ones the lower line, for an upper bound).
-__device__ __forceinline__ float relax_factor(double a, float g) {
-    return a >= 0.0 ? fabsf(g) : (signbit(g) ? 0.f : 1.f);
-}
-
 // Epilogue bookkeeping of one row: offset of the row's output pixel (window pixel (pa,pb)) in the packed relaxation
 // of the input layer, [batch][Ho*Wo*Co], and in the addend block (-1 when the pixel lies outside the addend's window).
 __device__ __forceinline__ void epilogue_row_info(const CrossParams& p, const RowInfo& ri, int r, int pa, int pb,
@@ -1139,895 +1053,6 @@ void launch_cross(const CrossParams& p, hipStream_t s) {
     if (wg64 < 256) { launch_cross_t<32, 32>(p, s); return; }
     if (wg64 < 512) { launch_cross_t<64, 32>(p, s); return; }
     launch_cross_t<64, 64>(p, s);
-}
-
-// ------------------------------------------------------------------------------------------------
-// Per-row reductions over a block:
-//   candidate  sum_j (m_j >= 0 ? m_j*cpos_j : m_j*cneg_j)                   (Section 2, candidate bound)
-//   rounding   sum_j |m_j| * max(|xlo_j|,|xhi_j|)                           (slack of the float32 storage)
-//   constants of the next step: sum_j max(m_j,0)*kap_j + m_j*bias_c
-//   S1 = sum_j |m_j|                                                        (slack of the next accumulation)
-// With inference rounding (p.eta) the constants also take sum_j |m_j|*eta_j.  Since |m| = 2*max(m,0) - m this needs no
-// sum of its own: eta_j is folded into the two constants of the neuron, kap_j + 2*eta_j and bias_c - eta_j.
-// For a block over a plain layer cpos/cneg are the layer's upper/lower interval ends.  A block whose
-// coefficients already went through a ReLU substitution holds m = M*slope (M >= 0) or m = M*lam (M < 0)
-// over the ReLU's INPUT; the candidate over the ReLU's OUTPUT interval [L,U] that DeepPoly takes before
-// the substitution is recovered as M*U = m*(U/slope) =: m*rho and M*L = m*L (L = 0 unless the neuron is
-// stably active, where lam = 1), and the intercept term M*del = m*(del/slope) =: m*kap.
-// The kernels share this arithmetic (scan_term, scan_finish) and differ in how rows and lanes are laid out; which one
-// runs is decided by the row length alone, see launch_scan.
-// ------------------------------------------------------------------------------------------------
-// One coefficient's contribution to the five per-row sums.  Written with explicit fused multiply-adds only, so that
-// every scan kernel performs exactly the same operations in the same order per lane and a row's result does not
-// depend on which kernel (i.e. on how many rows share the launch) handled it.
-__device__ __forceinline__ void scan_term(bool has_cand, bool do_consts, float mf, double cp, double cn, double X, double kp,
-                                          double be, double& cand, double& absx, double& cst, double& cstabs, double& s1) {
-    const double m = (double)mf;
-    const double am = fabs(m);
-    if (has_cand) {
-        cand = fma(m, mf >= 0.f ? cp : cn, cand);
-        absx = fma(am, X, absx);
-    }
-    if (do_consts) {
-        const double mp = fmax(m, 0.0);
-        cst = fma(m, be, fma(mp, kp, cst));
-        cstabs = fma(am, fabs(be), fma(mp, kp, cstabs));
-        s1 += am;
-    }
-}
-
-// The same for the kernels that stage the neurons' constants in LDS, with fewer vector instructions per coefficient
-// (every one of them is paid in time here): the staged multiplier pair is (cpos - cneg, cneg), so that the candidate
-// term needs no select, m*c(m) = max(m,0)*(cpos - cneg) + m*cneg; and the magnitude of the constant terms, which only
-// scales a rounding slack, is not summed per coefficient but bounded per row by S1 * max_j(|bias_j| + kap_j).
-__device__ __forceinline__ void scan_term_staged(bool has_cand, bool do_consts, float mf, double dcp, double cn, double X,
-                                                 double kp, double be, double& cand, double& absx, double& cst, double& s1) {
-    const double m = (double)mf;
-    const double am = fabs(m);
-    const double mp = fmax(m, 0.0);
-    if (has_cand) {
-        cand = fma(mp, dcp, fma(m, cn, cand));
-        absx = fma(am, X, absx);
-    }
-    if (do_consts) {
-        cst = fma(m, be, fma(mp, kp, cst));
-        s1 += am;
-    }
-}
-
-// The scalars of a row that its bookkeeping reads.  Fetched early (scan_row_fetch) by the kernels that want the
-// round trip to overlap with the row's own loads.
-struct ScanRow {
-    double c, err, best, xmax_self, xmax_a, xmax_b;
-    int bi;
-    bool frozen;
-};
-__device__ __forceinline__ ScanRow scan_row_fetch(const ScanParams& p, int r, const RowInfo& ri) {
-    ScanRow s;
-    s.c = p.c[r];
-    s.err = p.err[r];
-    s.xmax_self = (p.round_coef > 0.0 && p.xmax_self) ? p.xmax_self[ri.b] : 0.0;
-    s.bi = 0; s.best = 0.0; s.frozen = true;
-    if (p.update_best && p.cpos) {
-        // a task that met the termination criterion keeps the bounds it had at that moment
-        s.frozen = p.done && p.done[r >= p.rm.Rc ? r - p.rm.Rc : r];
-        s.bi = best_index(p.rm, r);
-        s.best = p.best[s.bi];
-    }
-    s.xmax_a = (p.do_consts && p.xmax_a) ? p.xmax_a[ri.b] : 0.0;
-    s.xmax_b = (p.do_consts && p.xmax_b) ? p.xmax_b[ri.b] : 0.0;
-    return s;
-}
-// Per-row bookkeeping after the reductions: rounding slack of the stored coefficients, candidate folded into best,
-// constants of the next step added to c, slack of the next accumulation.
-__device__ __forceinline__ void scan_finish(const ScanParams& p, int r, int nelem, const ScanRow& s, double t_cand,
-                                            double t_absx, double t_cst, double t_cstabs, double t_s1) {
-    // a sum of n float64 terms in any order is off by at most (n-1)*2^-53*sum|terms|*(1+tiny)
-    const double esum = (double)(nelem + 16) * 0x1p-52;
-    double c = s.c;
-    double err = s.err;
-    // slack of the stored coefficients: |true - stored| <= round_coef*|stored| (+ subnormal floor)
-    err += t_absx * p.round_coef * (1.0 + esum);
-    // values below the float32 subnormal step vanish; with a substituted ReLU the lost coefficient is
-    // up to 2^20 times larger (slopes are kept >= 2^-20)
-    if (p.round_coef > 0.0 && p.xmax_self) err += 0x1p-128 * (double)nelem * s.xmax_self;
-    if (p.update_best && p.cpos) {
-        double v = c + t_cand + err;
-        // (the candidate's terms are at most 3*|m|*X in magnitude when the multiplier comes as a difference, see
-        // scan_term_staged)
-        v += (fabs(c) + fabs(t_cand) + err) * 0x1p-50 + 3.0 * t_absx * esum;
-        if (!s.frozen) p.best[s.bi] = fmin(s.best, v);
-    }
-    if (p.do_consts) {
-        double cn = c + t_cst;
-        double e1 = 0.0;
-        if (p.xmax_a) e1 += p.e1_a * s.xmax_a;
-        if (p.xmax_b) e1 += p.e1_b * s.xmax_b;
-        err += t_cstabs * esum + (fabs(c) + fabs(t_cst)) * 0x1p-51 + t_s1 * e1 * (1.0 + esum);
-        c = cn;
-    }
-    err *= (1.0 + 0x1p-48);   // the few float64 operations above
-    p.c[r] = c;
-    p.err[r] = err;
-}
-
-constexpr int SCAN_G = 8;     // rows per wave of the 8-lanes-per-row layout
-
-// Short rows: LPR = 8 lanes per row, 8 rows per wave.  Every lane accumulates for its own row (few registers, many
-// resident waves) and fetches the constants of its own elements; lanes of different rows that meet the same neuron
-// read the same addresses.
-template <int V, int LPR>
-__global__ __launch_bounds__(256) void scan_tall_kernel(const ScanParams p) {
-    constexpr int RPW = 64 / LPR;                            // rows per wave
-    const int tid = threadIdx.x, lane = tid & 63;
-    const BlockDesc& B = p.blk;
-    const int groups_per_half = (p.rm.Rc + RPW - 1) / RPW;
-    const int gidx = blockIdx.x * 4 + (tid >> 6);
-    const int nhalves = p.nrows / p.rm.Rc;
-    if (gidx >= groups_per_half * nhalves) return;          // whole wave leaves
-    const int half = gidx / groups_per_half;
-    const int rr0 = (gidx - half * groups_per_half) * RPW;
-    const int nvalid = min(RPW, p.rm.Rc - rr0);
-    const int k = lane / LPR, sub = lane % LPR;
-    const bool valid = k < nvalid;
-    const int r = half * p.rm.Rc + rr0 + (valid ? k : 0);
-    const int nelem = B.wy * B.wx * B.C;
-    const bool full_row = (B.wx == B.W);
-    const RowInfo ri = row_info(p.rm, r);
-    const int oy = clampi(B.Sy * ri.ys - B.Py, 0, B.H - B.wy), ox = clampi(B.Sx * ri.xs - B.Px, 0, B.W - B.wx);
-    const long long bbase = (long long)ri.b * p.batch_stride;
-    const float* src = B.data + (size_t)r * nelem;
-    double cand = 0.0, absx = 0.0, cst = 0.0, cstabs = 0.0, s1 = 0.0;
-    if (valid) {
-        for (int e = sub * V; e < nelem; e += LPR * V) {
-            float mf[V];
-            if (V == 4) {
-                const float4 t = *reinterpret_cast<const float4*>(src + e);
-                mf[0] = t.x; mf[1 % V] = t.y; mf[2 % V] = t.z; mf[3 % V] = t.w;
-            } else {
-                mf[0] = src[e];
-            }
-            int c;
-            long long j;
-            if (full_row) {
-                c = e % B.C;
-                j = bbase + (long long)oy * B.W * B.C + e;
-            } else {
-                const int pix = e / B.C;
-                c = e - pix * B.C;
-                const int a = pix / B.wx, bb = pix - a * B.wx;
-                j = bbase + ((long long)((oy + a) * B.W + (ox + bb)) * B.C + c);
-            }
-#pragma unroll
-            for (int v = 0; v < V; ++v) {
-                double cp = 0.0, cn = 0.0, X = 0.0, kp = 0.0, be = 0.0;
-                if (p.cpos) {
-                    cp = p.cpos[j + v];
-                    cn = p.cneg[j + v];
-                    X = fmax(fabs(p.xlo[j + v]), fabs(p.xhi[j + v]));
-                }
-                if (p.do_consts) {
-                    if (p.kap) kp = p.kap[j + v];
-                    if (p.beff) be = p.beff[c + v];
-                    if (p.eta) { const double et = p.eta[j + v]; kp += 2.0 * et; be -= et; }
-                }
-                scan_term(p.cpos != nullptr, p.do_consts != 0, mf[v], cp, cn, X, kp, be, cand, absx, cst, cstabs, s1);
-            }
-        }
-    }
-#pragma unroll
-    for (int off = LPR / 2; off > 0; off >>= 1) {
-        cand += __shfl_xor(cand, off, 64);
-        absx += __shfl_xor(absx, off, 64);
-        cst += __shfl_xor(cst, off, 64);
-        cstabs += __shfl_xor(cstabs, off, 64);
-        s1 += __shfl_xor(s1, off, 64);
-    }
-    if (valid && sub == 0) scan_finish(p, r, nelem, scan_row_fetch(p, r, ri), cand, absx, cst, cstabs, s1);
-}
-
-// Rows of a few hundred coefficients (dense layers, small windows): 32 rows per work-group, 8 lanes per row.  The
-// per-neuron constants of the rows' window are staged ONCE per work-group in LDS (5 doubles per element) instead of
-// being fetched by every wave, every lane accumulates for its own row (few registers, many resident waves), and
-// lanes of different rows read the same LDS words (broadcast).  Rows of a work-group that do not share box and
-// window origin are handled run by run.
-constexpr int SCAN_LDS_MAX = 1024;      // longest row whose constants are staged whole (40 KB of LDS)
-constexpr int SCAN_CHUNK = 512;         // chunk of longer rows (20 KB of LDS: 8 work-groups per CU)
-// ROWS per work-group (8 lanes each); the grouping does not touch a row's arithmetic.
-// U: row slices (8 lanes x V elements each) whose loads are in flight together.
-// CHUNKED: rows longer than SCAN_LDS_MAX are cut into chunks of SCAN_CHUNK coefficients, one work-group per (32 rows,
-// chunk); the five sums of a (row, chunk) go to p.partial and scan_combine_kernel adds a row's chunks in order.
-template <int V, int ROWS, int U, bool CHUNKED>
-__global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) {
-    constexpr int SCAN_LDS_ROWS = ROWS;
-    constexpr int NT = ROWS * 8;
-    extern __shared__ __attribute__((aligned(16))) double s_const[];     // [5][nelem_pad]
-    __shared__ int s_b[SCAN_LDS_ROWS], s_oy[SCAN_LDS_ROWS], s_ox[SCAN_LDS_ROWS];
-    // bits of max_j(|bias_j| + kap_j) over the staged constants (non-negative), one slot per parity of the run: a slot
-    // is cleared during the following run, two barriers away from both its readers and its next writers
-    __shared__ unsigned long long s_qmax[2];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const BlockDesc& B = p.blk;
-    const int nelem = B.wy * B.wx * B.C;
-    const int c0 = CHUNKED ? (int)blockIdx.y * SCAN_CHUNK : 0;             // this work-group's element range
-    const int c1 = CHUNKED ? min(nelem, c0 + SCAN_CHUNK) : nelem;
-    const int npad = CHUNKED ? SCAN_CHUNK : ((nelem + 3) & ~3);
-    double* const s_cp = s_const;
-    double* const s_cn = s_const + npad;
-    double* const s_X = s_const + 2 * npad;
-    double* const s_kp = s_const + 3 * npad;
-    double* const s_be = s_const + 4 * npad;
-    const int gph = (p.rm.Rc + SCAN_LDS_ROWS - 1) / SCAN_LDS_ROWS;      // work-groups per half
-    const int half = blockIdx.x / gph;
-    const int rr0 = (blockIdx.x - half * gph) * SCAN_LDS_ROWS;
-    const int nvalid = min(SCAN_LDS_ROWS, p.rm.Rc - rr0);
-    const int kk = wave * 8 + (lane >> 3), sub = lane & 7;
-    const bool valid = kk < nvalid;
-    const int r = half * p.rm.Rc + rr0 + (valid ? kk : 0);
-    const bool full_row = (B.wx == B.W);
-    const RowInfo ri = row_info(p.rm, r);
-    if (sub == 0 && valid) {
-        s_b[kk] = ri.b;
-        s_oy[kk] = clampi(B.Sy * ri.ys - B.Py, 0, B.H - B.wy);
-        s_ox[kk] = clampi(B.Sx * ri.xs - B.Px, 0, B.W - B.wx);
-    }
-    if (tid == 0) s_qmax[0] = s_qmax[1] = 0ull;
-    __syncthreads();
-    const float* src = B.data + (size_t)r * nelem;
-    double cand = 0.0, absx = 0.0, cst = 0.0, cstabs = 0.0, s1 = 0.0;
-    auto load_slices = [&](int e0, float (&mf)[U][V]) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int e = e0 + u * 8 * V;
-            if (e < c1) {
-                if (V == 4) {
-                    const float4 t = *reinterpret_cast<const float4*>(src + e);
-                    mf[u][0] = t.x; mf[u][1 % V] = t.y; mf[u][2 % V] = t.z; mf[u][3 % V] = t.w;
-                } else {
-                    mf[u][0] = src[e];
-                }
-            }
-        }
-    };
-    auto add_slices = [&](int e0, const float (&mf)[U][V]) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int e = e0 + u * 8 * V;
-            if (e < c1) {
-                const int k = e - c0;
-#pragma unroll
-                for (int v = 0; v < V; ++v)
-                    scan_term_staged(p.cpos != nullptr, p.do_consts != 0, mf[u][v], s_cp[k + v], s_cn[k + v], s_X[k + v],
-                                     s_kp[k + v], s_be[k + v], cand, absx, cst, s1);
-            }
-        }
-    };
-    int k0 = 0, run = 0;
-    while (k0 < nvalid) {                                   // uniform over the work-group
-        if (tid == 0) s_qmax[(run & 1) ^ 1] = 0ull;
-        const int b0 = s_b[k0], oy0 = s_oy[k0], ox0 = s_ox[k0];
-        int k1 = k0 + 1;
-        while (k1 < nvalid && s_b[k1] == b0 && s_oy[k1] == oy0 && s_ox[k1] == ox0) ++k1;
-        const long long bbase = (long long)b0 * p.batch_stride;
-        double qmax = 0.0;
-        for (int e = c0 + tid; e < c1; e += NT) {
-            int c;
-            long long j;
-            if (full_row) {
-                c = e % B.C;
-                j = bbase + (long long)oy0 * B.W * B.C + e;
-            } else {
-                const int pix = e / B.C;
-                c = e - pix * B.C;
-                const int a = pix / B.wx, bb = pix - a * B.wx;
-                j = bbase + ((long long)((oy0 + a) * B.W + (ox0 + bb)) * B.C + c);
-            }
-            double cp = 0.0, cn = 0.0, X = 0.0, kp = 0.0, be = 0.0;
-            if (p.cpos) {
-                cp = p.cpos[j];
-                cn = p.cneg[j];
-                X = fmax(fabs(p.xlo[j]), fabs(p.xhi[j]));
-            }
-            if (p.do_consts) {
-                if (p.kap) kp = p.kap[j];
-                if (p.beff) be = p.beff[c];
-                if (p.eta) { const double et = p.eta[j]; kp += 2.0 * et; be -= et; }
-            }
-            const int k = e - c0;
-            s_cp[k] = cp - cn; s_cn[k] = cn; s_X[k] = X; s_kp[k] = kp; s_be[k] = be;
-            qmax = fmax(qmax, fabs(be) + kp);
-        }
-        if (p.do_consts) {
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) qmax = fmax(qmax, __shfl_xor(qmax, off, 64));
-            // non-negative doubles order like their bit patterns
-            if (lane == 0) atomicMax(&s_qmax[run & 1], (unsigned long long)__double_as_longlong(qmax));
-        }
-        __syncthreads();
-        if (valid && kk >= k0 && kk < k1) {
-            const double s1_before = s1;
-            for (int e0 = c0 + sub * V; e0 < c1; e0 += U * 8 * V) {
-                float mf[U][V];
-                load_slices(e0, mf);
-                add_slices(e0, mf);
-            }
-            // magnitude of the row's constant terms (scales a rounding slack only): a row lies in exactly one run
-            cstabs = (s1 - s1_before) * __longlong_as_double((long long)s_qmax[run & 1]) * (1.0 + 0x1p-50);
-        }
-        __syncthreads();                                    // the next run overwrites the constants
-        k0 = k1;
-        ++run;
-    }
-#pragma unroll
-    for (int off = 4; off > 0; off >>= 1) {
-        cand += __shfl_xor(cand, off, 64);
-        absx += __shfl_xor(absx, off, 64);
-        cst += __shfl_xor(cst, off, 64);
-        cstabs += __shfl_xor(cstabs, off, 64);
-        s1 += __shfl_xor(s1, off, 64);
-    }
-    if (valid && sub == 0) {
-        if constexpr (CHUNKED) {
-            double* out = p.partial + ((size_t)r * gridDim.y + blockIdx.y) * 5;
-            out[0] = cand; out[1] = absx; out[2] = cst; out[3] = cstabs; out[4] = s1;
-        } else {
-            scan_finish(p, r, nelem, scan_row_fetch(p, r, ri), cand, absx, cst, cstabs, s1);
-        }
-    }
-}
-
-// a row's chunk sums added in chunk order, then the row's bookkeeping
-__global__ __launch_bounds__(256) void scan_combine_kernel(const ScanParams p, int nchunks) {
-    const int r = blockIdx.x * 256 + threadIdx.x;
-    if (r >= p.nrows) return;
-    const double* in = p.partial + (size_t)r * nchunks * 5;
-    double t[5] = {0.0, 0.0, 0.0, 0.0, 0.0};
-    for (int c = 0; c < nchunks; ++c)
-#pragma unroll
-        for (int q = 0; q < 5; ++q) t[q] += in[c * 5 + q];
-    const RowInfo ri = row_info(p.rm, r);
-    scan_finish(p, r, p.blk.wy * p.blk.wx * p.blk.C, scan_row_fetch(p, r, ri), t[0], t[1], t[2], t[3], t[4]);
-}
-
-
-void launch_scan(const ScanParams& p, hipStream_t s) {
-    if (p.nrows <= 0) return;
-    const int nhalves = p.nrows / p.rm.Rc;
-    const int nelem = p.blk.wy * p.blk.wx * p.blk.C;
-    const bool vec = (p.blk.C & 3) == 0;
-    // the layout depends on the row length only, never on how many rows the launch has: a row's sums are formed in
-    // the same order whether its box is analysed alone, in a batch, or in a chunk of a batch
-    if (nelem <= 256 || (nelem > SCAN_LDS_MAX && !p.partial)) {      // cross-over of the two layouts measured on MI355X
-        const int groups = ((p.rm.Rc + SCAN_G - 1) / SCAN_G) * nhalves;
-        if (vec) hipLaunchKernelGGL((scan_tall_kernel<4, 8>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
-        else hipLaunchKernelGGL((scan_tall_kernel<1, 8>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
-    } else if (nelem <= SCAN_LDS_MAX) {
-        const size_t lds = (size_t)5 * ((nelem + 3) & ~3) * sizeof(double);
-        const int wgs = ((p.rm.Rc + 31) / 32) * nhalves;
-        if (vec) hipLaunchKernelGGL((scan_lds_kernel<4, 32, 4, false>), dim3(wgs), dim3(256), lds, s, p);
-        else hipLaunchKernelGGL((scan_lds_kernel<1, 32, 4, false>), dim3(wgs), dim3(256), lds, s, p);
-    } else {
-        const int nchunks = (nelem + SCAN_CHUNK - 1) / SCAN_CHUNK;
-        const dim3 grid(((p.rm.Rc + 31) / 32) * nhalves, nchunks);
-        const size_t lds = (size_t)5 * SCAN_CHUNK * sizeof(double);
-        if (vec) hipLaunchKernelGGL((scan_lds_kernel<4, 32, 4, true>), grid, dim3(256), lds, s, p);
-        else hipLaunchKernelGGL((scan_lds_kernel<1, 32, 4, true>), grid, dim3(256), lds, s, p);
-        hipLaunchKernelGGL(scan_combine_kernel, dim3((p.nrows + 255) / 256), dim3(256), 0, s, p, nchunks);
-    }
-}
-
-// ------------------------------------------------------------------------------------------------
-// Initial expressions (Section 2: the affine layer's own row; Section 4.3: M^{l-1}(x_i) = the filter taps).
-//   mode 0: one-hot +/-1 over the start layer itself (sum layers)
-//   mode 1: e_j - e_label over the whole last layer (certification rows)
-//   mode 2: +/- the row of the start layer's matrix, i.e. its filter placed in the window over the
-//           predecessor; constant = +/- bias.  Exact: no rounding.
-//   mode 3: minus a caller-given linear form over the whole last layer; constant = minus its offset
-__global__ __launch_bounds__(256) void init_kernel(const InitParams p) {
-    // block = 4 rows x 64 elements; grid.x over row quadruples, grid.y over element chunks
-    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (r >= p.nrows) return;
-    const RowInfo ri = row_info(p.rm, r);
-    float* out = p.out + (size_t)r * p.nelem;
-    if (p.mode == 2 && p.dense && (p.nelem & 3) == 0) {
-        // rows of a dense layer's matrix: four coefficients per lane (16-byte loads and stores)
-        const float* w = p.wt + (size_t)ri.cs * p.nelem;
-        const float* g = p.out_grl ? p.out_grl + (size_t)ri.b * p.nelem : nullptr;
-        for (int e = (blockIdx.y * 64 + (threadIdx.x & 63)) * 4; e < p.nelem; e += gridDim.y * 256) {
-            const float4 wv = *reinterpret_cast<const float4*>(w + e);
-            float v[4] = {ri.sign * wv.x, ri.sign * wv.y, ri.sign * wv.z, ri.sign * wv.w};
-            if (g) {
-                const float4 gv = *reinterpret_cast<const float4*>(g + e);
-                const float gg[4] = {gv.x, gv.y, gv.z, gv.w};
-#pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    if (v[k] != 0.f) v[k] = (float)((double)v[k] * (double)relax_factor((double)v[k], gg[k]));
-            }
-            *reinterpret_cast<float4*>(out + e) = make_float4(v[0], v[1], v[2], v[3]);
-        }
-    } else if (p.mode == 2 && !p.dense && (p.C & 3) == 0) {
-        // the start layer's filter placed in the row's window over the predecessor: four channels of a window pixel per
-        // lane (16-byte loads and stores), pixel coordinates without divisions
-        const int oy = clampi(p.Sy * ri.ys - p.Py, 0, p.H - p.wy), ox = clampi(p.Sx * ri.xs - p.Px, 0, p.W - p.wx);
-        const int fy = ri.ys * p.sh - p.ph, fx = ri.xs * p.sw - p.pw;
-        for (int e = (blockIdx.y * 64 + (threadIdx.x & 63)) * 4; e < p.nelem; e += gridDim.y * 256) {
-            const uint32_t pix = fast_div((uint32_t)e, p.div_C);
-            const int c = e - (int)pix * p.C;
-            const uint32_t a = fast_div(pix, p.div_wx);
-            const int A = oy + (int)a, B = ox + (int)(pix - a * (uint32_t)p.wx);
-            const int f = A - fy, g = B - fx;
-            float v[4] = {0.f, 0.f, 0.f, 0.f};
-            if (f >= 0 && f < p.kh && g >= 0 && g < p.kw) {
-                const float4 wv = *reinterpret_cast<const float4*>(p.wt + ((size_t)(f * p.kw + g) * p.Cs + ri.cs) * p.C + c);
-                v[0] = ri.sign * wv.x; v[1] = ri.sign * wv.y; v[2] = ri.sign * wv.z; v[3] = ri.sign * wv.w;
-                if (p.out_grl) {
-                    const size_t j = (size_t)ri.b * ((size_t)p.H * p.W * p.C) + (size_t)(A * p.W + B) * p.C + c;
-                    const float4 gv = *reinterpret_cast<const float4*>(p.out_grl + j);
-                    const float gg[4] = {gv.x, gv.y, gv.z, gv.w};
-#pragma unroll
-                    for (int k = 0; k < 4; ++k)
-                        if (v[k] != 0.f) v[k] = (float)((double)v[k] * (double)relax_factor((double)v[k], gg[k]));
-                }
-            }
-            *reinterpret_cast<float4*>(out + e) = make_float4(v[0], v[1], v[2], v[3]);
-        }
-    } else
-    for (int e = blockIdx.y * 64 + (threadIdx.x & 63); e < p.nelem; e += gridDim.y * 64) {
-        float v = 0.f;
-        if (p.mode == 0) {
-            v = (e == ri.cs) ? ri.sign : 0.f;
-        } else if (p.mode == 1) {
-            // task cs = index among the other classes, block order is H,W,C; classes are numbered C,H,W
-            int label = p.labels[ri.b];
-            int j = ri.cs + (ri.cs >= label ? 1 : 0);
-            int pix = e / p.C, c = e - pix * p.C;
-            int chw = c * (p.H * p.W) + pix;
-            if (chw == j) v = 1.f;
-            else if (chw == label) v = -1.f;
-        } else if (p.mode == 3) {
-            // upper bound of minus the form: block order is H,W,C, the form's coefficients are numbered C,H,W
-            int pix = e / p.C, c = e - pix * p.C;
-            v = -p.forms[(size_t)ri.cs * p.nelem + (size_t)c * (p.H * p.W) + pix];
-        } else if (p.dense) {
-            v = ri.sign * p.wt[(size_t)ri.cs * p.nelem + e];
-            if (p.out_grl && v != 0.f)
-                v = (float)((double)v * (double)relax_factor((double)v, p.out_grl[(size_t)ri.b * p.nelem + e]));
-        } else {
-            // window over the predecessor (dims H,W,C here), origin from the row's position
-            int pix = (int)fast_div((uint32_t)e, p.div_C), c = e - pix * p.C;
-            int a = (int)fast_div((uint32_t)pix, p.div_wx), bb = pix - a * p.wx;
-            int A = clampi(p.Sy * ri.ys - p.Py, 0, p.H - p.wy) + a;
-            int B = clampi(p.Sx * ri.xs - p.Px, 0, p.W - p.wx) + bb;
-            int f = A - (ri.ys * p.sh - p.ph), g = B - (ri.xs * p.sw - p.pw);
-            if (f >= 0 && f < p.kh && g >= 0 && g < p.kw)
-                v = ri.sign * p.wt[((size_t)(f * p.kw + g) * p.Cs + ri.cs) * p.C + c];
-            if (p.out_grl && v != 0.f) {
-                size_t j = (size_t)ri.b * ((size_t)p.H * p.W * p.C) + (size_t)(A * p.W + B) * p.C + c;
-                v = (float)((double)v * (double)relax_factor((double)v, p.out_grl[j]));
-            }
-        }
-        out[e] = v;
-    }
-    if (blockIdx.y == 0 && (threadIdx.x & 63) == 0) {
-        double c = (p.mode == 2) ? (double)(ri.sign * p.bias[ri.cs]) : (p.mode == 3 && p.offsets) ? -(double)p.offsets[ri.cs] : 0.0;
-        // the start neuron's float32 evaluation may exceed its exact expression by eta, in either direction
-        if (p.mode == 2 && p.eta)
-            c += p.eta[(long long)ri.b * p.rm.n_start + (long long)(ri.ys * p.rm.Ws + ri.xs) * p.rm.Cs + ri.cs] * (1.0 + 0x1p-50);
-        p.c[r] = c;
-        p.err[r] = 0.0;
-        if (!p.seeded) p.best[r] = INFINITY;
-    }
-}
-
-void launch_init(const InitParams& p0, hipStream_t s) {
-    if (p0.nrows <= 0 || p0.nelem <= 0) return;
-    InitParams p = p0;
-    p.div_C = make_fastdiv((uint32_t)std::max(p.C, 1));
-    p.div_wx = make_fastdiv((uint32_t)std::max(p.wx, 1));
-    const bool vec4 = p.mode == 2 && (p.dense ? (p.nelem & 3) == 0 : (p.C & 3) == 0);
-    const int per = vec4 ? p.nelem / 4 : p.nelem;   // items per row
-    const int ychunks = (int)fmin((double)((per + 63) / 64), 64.0);
-    hipLaunchKernelGGL(init_kernel, dim3((p.nrows + 3) / 4, ychunks), dim3(256), 0, s, p);
-}
-
-// running maximum of non-negative values, one slot per box; a wave whose lanes all target the same slot
-// combines them first (thousands of atomics on one address serialise).  Must be reached by all 64 lanes.
-__device__ __forceinline__ void atomic_max_nonneg(double* base, int slot, double v, bool valid) {
-    const int first = __builtin_amdgcn_readfirstlane(slot);
-    if (__all(valid && slot == first)) {
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) v = fmax(v, __shfl_xor(v, off, 64));
-        if ((threadIdx.x & 63) == 0)
-            atomicMax(reinterpret_cast<unsigned long long*>(base + first), (unsigned long long)__double_as_longlong(v));
-    } else if (valid) {
-        // non-negative doubles order like their bit patterns
-        atomicMax(reinterpret_cast<unsigned long long*>(base + slot), (unsigned long long)__double_as_longlong(v));
-    }
-}
-
-__global__ void finalize_kernel(const FinalizeParams p) {
-    const int r = blockIdx.x * blockDim.x + threadIdx.x;
-    const bool valid = r < p.rm.Rc;
-    double x = 0.0;
-    int slot = 0;
-    if (valid) {
-        const long long g = (long long)p.rm.row0 + r;
-        double u = p.best[r];
-        double l = -p.best[p.rm.Rc + r];
-        if (p.widen > 0.0) {        // the neuron is one rounded float32 addition of the bounded exact sum (monotone)
-            u += fabs(u) * p.widen + 0x1p-1000;
-            l -= fabs(l) * p.widen + 0x1p-1000;
-        }
-        if (!isfinite(u) || !isfinite(l)) *p.flag = 1;
-        p.hi[g] = u;
-        p.lo[g] = l;
-        x = fmax(fabs(u), fabs(l));
-        if (!isfinite(x)) x = 0.0;
-        slot = (int)(g / p.rm.n_start);
-    }
-    atomic_max_nonneg(p.xmax, slot, x, valid);
-}
-
-void launch_finalize(const FinalizeParams& p, hipStream_t s) {
-    if (p.rm.Rc <= 0) return;
-    hipLaunchKernelGGL(finalize_kernel, dim3((p.rm.Rc + 255) / 256), dim3(256), 0, s, p);
-}
-
-// ReLU layer: intervals [max(l,0), max(u,0)] and the relaxation  lam*x <= relu(x) <= gam*x + del.
-// Any gam in [0,1] is sound when del >= max(-gam*l, u - gam*u); gam is the float32 nearest to u/(u-l).
-__global__ void relu_kernel(const ReluParams p) {
-    const long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x;
-    const bool valid = i < p.total;
-    double x = 0.0;
-    int slot = 0;
-    if (valid) {
-        const double l = p.plo[i], u = p.phi[i];
-        if (!isfinite(l) || !isfinite(u)) *p.flag = 1;
-        p.lo[i] = fmax(l, 0.0);
-        p.hi[i] = fmax(u, 0.0);
-        float g, lam;
-        double rho = 0.0, kap = 0.0;
-        if (l >= 0.0) { g = 1.f; lam = 1.f; rho = u; }
-        else if (u <= 0.0) { g = 0.f; lam = 0.f; }
-        else {
-            g = (float)(u / (u - l));
-            g = fminf(fmaxf(g, 0x1p-20f), 1.f);       // a positive coefficient must stay recoverable from its product with g
-            const double gd = (double)g;
-            const double d1 = -gd * l, d2 = u - gd * u;     // each off by a few ulps at most
-            double d = fmax(d1, d2);
-            d = d + (fabs(d) + fabs(u)) * 0x1p-50 + 0x1p-1000;
-            lam = (u > -l) ? 1.f : 0.f;
-            // rounded up, including the float32 rounding of the stored product coefficient*g
-            rho = (u / gd) * (1.0 + 0x1p-22);
-            kap = (d / gd) * (1.0 + 0x1p-22);
-        }
-        p.grl[i] = lam != 0.f ? g : -g;      // -0.0f encodes slope 0 with lam = 0
-        p.rho[i] = rho;
-        p.kap[i] = kap;
-        x = fmax(u, 0.0);
-        if (!isfinite(x)) x = 0.0;
-        slot = (int)(i / p.n);
-    }
-    atomic_max_nonneg(p.xmax, slot, x, valid);
-}
-
-void launch_relu(const ReluParams& p, hipStream_t s) {
-    if (p.total <= 0) return;
-    hipLaunchKernelGGL(relu_kernel, dim3((unsigned)((p.total + 255) / 256)), dim3(256), 0, s, p);
-}
-
-// Input box [max(c-eps,clip_lo), min(c+eps,clip_hi)], rounded outward in float64, H,W,C order.
-__global__ void box_kernel(const BoxParams p) {
-    const long long n = (long long)p.C * p.H * p.W;
-    const long long idx = blockIdx.x * (long long)blockDim.x + threadIdx.x;
-    const bool valid = idx < n * p.batch;
-    double x = 0.0;
-    int b = 0;
-    if (valid) {
-        b = (int)(idx / n);
-        const int j = (int)(idx - (long long)b * n);   // H,W,C index
-        const int pix = j / p.C, c = j - pix * p.C;
-        const double ctr = (double)p.centers[(long long)b * n + (long long)c * (p.H * p.W) + pix];
-        const double e = (double)p.eps;
-        double lo = nextafter(ctr - e, -INFINITY), hi = nextafter(ctr + e, INFINITY);
-        lo = fmax(lo, (double)p.clip_lo);
-        hi = fmin(hi, (double)p.clip_hi);
-        if (lo > hi) {
-            if (ctr < (double)p.clip_lo) lo = hi = (double)p.clip_lo;
-            else lo = hi = (double)p.clip_hi;
-        }
-        if (!isfinite(lo) || !isfinite(hi)) *p.flag = 1;
-        p.lo[idx] = lo;
-        p.hi[idx] = hi;
-        x = fmax(fabs(lo), fabs(hi));
-        if (!isfinite(x)) x = 0.0;
-    }
-    atomic_max_nonneg(p.xmax, b, x, valid);
-}
-
-void launch_box(const BoxParams& p, hipStream_t s) {
-    long long total = (long long)p.C * p.H * p.W * p.batch;
-    if (total <= 0) return;
-    hipLaunchKernelGGL(box_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, p);
-}
-
-__global__ void fill_f64_kernel(double* p, double v, long long n) {
-    long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x;
-    if (i < n) p[i] = v;
-}
-__global__ void fill_i32_kernel(int* p, int v, long long n) {
-    long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x;
-    if (i < n) p[i] = v;
-}
-void launch_fill_f64(double* p, double v, long long n, hipStream_t s) {
-    if (n > 0) hipLaunchKernelGGL(fill_f64_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, v, n);
-}
-void launch_fill_i32(int* p, int v, long long n, hipStream_t s) {
-    if (n > 0) hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, v, n);
-}
-
-// margins = -(upper bound of y_j - y_label), rounded down to float32
-__global__ void margins_kernel(const double* best, float* margins, long long n, int* flag) {
-    long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    double m = -best[i];
-    if (!isfinite(m)) *flag = 1;
-    float f = (float)m;
-    if ((double)f > m) f = nextafterf(f, -INFINITY);
-    margins[i] = f;
-}
-void launch_margins(const double* best, float* margins, long long n, int* flag, hipStream_t s) {
-    if (n > 0) hipLaunchKernelGGL(margins_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, best, margins, n, flag);
-}
-
-// ------------------------------------------------------------------------------------------------
-// Early termination (Section 3.2: a ReLU input whose interval does not contain 0 strictly gains nothing from
-// back-substitution; Section 4.2: forward interval analysis first, only the other rows are back-substituted,
-// rows that come to meet the criterion are removed with a prefix sum over the row flags).
-// ------------------------------------------------------------------------------------------------
-// Interval image of an affine layer: one wave per neuron, float64.  The float32 weight times a float64 bound is
-// rounded once (fused multiply-add); a sum of n such terms in any order is off by less than
-// (n + 16) * 2^-52 * sum|terms|, which is added outward.
-__global__ __launch_bounds__(256) void ival_kernel(const IvalParams p) {
-    const int lane = threadIdx.x & 63;
-    const long long n = (long long)p.H * p.W * p.C;
-    const long long idx = blockIdx.x * 4LL + (threadIdx.x >> 6);
-    if (idx >= n * p.batch) return;                         // whole wave leaves
-    const int b = (int)(idx / n);
-    const int j = (int)(idx - (long long)b * n);
-    const int pix = j / p.C, c = j - pix * p.C;
-    const int y = pix / p.W, x = pix - y * p.W;
-    const long long n_in = (long long)p.Hi * p.Wi * p.Ci;
-    const double* plo = p.plo + (long long)b * n_in;
-    const double* phi = p.phi + (long long)b * n_in;
-    const int taps = p.kh * p.kw;
-    double lo = 0.0, hi = 0.0, mag = 0.0;
-    for (int t = 0; t < taps; ++t) {
-        const int f = t / p.kw, g = t - f * p.kw;
-        const int iy = y * p.sh - p.ph + f, ix = x * p.sw - p.pw + g;
-        if (iy < 0 || iy >= p.Hi || ix < 0 || ix >= p.Wi) continue;          // uniform per wave
-        const float* w = p.wt + ((size_t)t * p.C + c) * p.Ci;
-        const double* l = plo + (size_t)(iy * p.Wi + ix) * p.Ci;
-        const double* u = phi + (size_t)(iy * p.Wi + ix) * p.Ci;
-        for (int ci = lane; ci < p.Ci; ci += 64) {
-            const double wv = (double)w[ci], L = l[ci], U = u[ci];
-            lo = fma(wv, wv >= 0.0 ? L : U, lo);
-            hi = fma(wv, wv >= 0.0 ? U : L, hi);
-            mag = fma(fabs(wv), fmax(fabs(L), fabs(U)), mag);
-        }
-    }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        lo += __shfl_xor(lo, off, 64);
-        hi += __shfl_xor(hi, off, 64);
-        mag += __shfl_xor(mag, off, 64);
-    }
-    if (lane == 0) {
-        const double bias = (double)p.bias[c];
-        const double terms = (double)taps * p.Ci + 1.0;
-        const double slack = (terms + 16.0) * 0x1p-52 * (mag + fabs(bias)) * (1.0 + 0x1p-30);
-        double eta = 0.0;
-        if (p.eta) {
-            // float32 evaluation of sum_j w_j*x_j + bias in any order, fused or not: every term passes through at most
-            // `terms` roundings, so |computed - exact| <= gamma(terms)*(sum|w_j||x_j| + |bias|), gamma(k) = k*u/(1-k*u),
-            // u = 2^-24, plus half a subnormal step per product that underflows
-            const double ku = terms * 0x1p-24;
-            const double gamma = ku / (1.0 - ku) * (1.0 + 0x1p-50);
-            eta = gamma * (mag * (1.0 + (terms + 16.0) * 0x1p-52) + fabs(bias)) * (1.0 + 0x1p-50) + terms * 0x1p-149;
-            if (!isfinite(eta) || ku >= 0.5) *p.flag = 1;
-            p.eta[idx] = eta;
-        }
-        if (p.lo) {
-            double l2 = lo + bias - slack - eta, u2 = hi + bias + slack + eta;
-            l2 -= fabs(l2) * 0x1p-51 + 0x1p-1000;
-            u2 += fabs(u2) * 0x1p-51 + 0x1p-1000;
-            if (!isfinite(l2) || !isfinite(u2)) *p.flag = 1;
-            p.lo[idx] = l2;
-            p.hi[idx] = u2;
-        }
-    }
-}
-void launch_ival(const IvalParams& p, hipStream_t s) {
-    const long long total = (long long)p.H * p.W * p.C * p.batch;
-    if (total <= 0) return;
-    hipLaunchKernelGGL(ival_kernel, dim3((unsigned)((total + 3) / 4)), dim3(256), 0, s, p);
-}
-
-__global__ void add_ival_kernel(const AddIvalParams p) {
-    const long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x;
-    if (i >= p.total) return;
-    double l = p.alo[i] + p.blo[i], u = p.ahi[i] + p.bhi[i];
-    l -= fabs(l) * (0x1p-52 + p.widen) + 0x1p-1000;
-    u += fabs(u) * (0x1p-52 + p.widen) + 0x1p-1000;
-    if (!isfinite(l) || !isfinite(u)) *p.flag = 1;
-    p.lo[i] = l;
-    p.hi[i] = u;
-}
-void launch_add_ival(const AddIvalParams& p, hipStream_t s) {
-    if (p.total <= 0) return;
-    hipLaunchKernelGGL(add_ival_kernel, dim3((unsigned)((p.total + 255) / 256)), dim3(256), 0, s, p);
-}
-
-__global__ void sum_eta_kernel(const SumEtaParams p) {
-    const long long i = blockIdx.x * (long long)blockDim.x + threadIdx.x;
-    if (i >= p.total) return;
-    double e = 0.0;
-    if (p.lo) e = fmax(fabs(p.lo[i]), fabs(p.hi[i])) * p.u;
-    if (p.ea) e += p.ea[i];
-    if (p.eb) e += p.eb[i];
-    p.out[i] = e * (1.0 + 0x1p-50);
-}
-void launch_sum_eta(const SumEtaParams& p, hipStream_t s) {
-    if (p.total <= 0) return;
-    hipLaunchKernelGGL(sum_eta_kernel, dim3((unsigned)((p.total + 255) / 256)), dim3(256), 0, s, p);
-}
-
-__global__ void seed_kernel(const SeedParams p) {
-    const int r = blockIdx.x * blockDim.x + threadIdx.x;
-    if (r >= p.Rc0) return;
-    p.best[r] = p.hi[(long long)p.row0 + r];
-    p.best[p.Rc0 + r] = -p.lo[(long long)p.row0 + r];
-}
-void launch_seed(const SeedParams& p, hipStream_t s) {
-    if (p.Rc0 <= 0) return;
-    hipLaunchKernelGGL(seed_kernel, dim3((p.Rc0 + 255) / 256), dim3(256), 0, s, p);
-}
-
-// criterion per task: upper bound <= 0 or lower bound >= 0 (best[Rc0 + .] holds minus the lower bound)
-__global__ __launch_bounds__(256) void term_flag_kernel(const TermParams p) {
-    __shared__ int s_cnt[4];
-    const int rr = blockIdx.x * 256 + threadIdx.x;
-    int keep = 0;
-    if (rr < p.Ra) {
-        const int orig = p.rowid ? p.rowid[rr] : rr;
-        const bool was = !p.first && p.done[rr];
-        const bool crit = p.may_stop && (p.best[orig] <= 0.0 || p.best[p.Rc0 + orig] <= 0.0);
-        const bool now = was || crit;
-        p.done[rr] = now ? 1 : 0;
-        if (p.term_layer) {
-            if (p.first) p.term_layer[(long long)p.row0 + orig] = now ? p.key : 0;
-            else if (now && !was) p.term_layer[(long long)p.row0 + orig] = p.key;
-        }
-        keep = now ? 0 : 1;
-    }
-    const unsigned long long m = __ballot(keep);
-    if ((threadIdx.x & 63) == 0) s_cnt[threadIdx.x >> 6] = __popcll(m);
-    __syncthreads();
-    if (threadIdx.x == 0) p.wgcount[blockIdx.x] = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
-}
-// exclusive prefix sum of the per-work-group counts in place (one work-group walks the array), total to *count
-__global__ __launch_bounds__(1024) void term_scan_kernel(int* wgcount, int nwg, int* count) {
-    __shared__ int s_wave[16];
-    __shared__ int s_carry;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid == 0) s_carry = 0;
-    __syncthreads();
-    for (int base = 0; base < nwg; base += 1024) {
-        const int i = base + tid;
-        const int v = i < nwg ? wgcount[i] : 0;
-        int incl = v;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const int t = __shfl_up(incl, off, 64);
-            if (lane >= off) incl += t;
-        }
-        if (lane == 63) s_wave[wave] = incl;
-        __syncthreads();
-        int wave_off = 0;
-        for (int w = 0; w < wave; ++w) wave_off += s_wave[w];
-        const int carry = s_carry;
-        if (i < nwg) wgcount[i] = carry + wave_off + incl - v;
-        __syncthreads();
-        if (tid == 1023) s_carry = carry + wave_off + incl;
-        __syncthreads();
-    }
-    if (tid == 0) *count = s_carry;
-}
-void launch_term(const TermParams& p, int* count, hipStream_t s) {
-    if (p.Ra <= 0) return;
-    const int nwg = (p.Ra + 255) / 256;
-    hipLaunchKernelGGL(term_flag_kernel, dim3(nwg), dim3(256), 0, s, p);
-    hipLaunchKernelGGL(term_scan_kernel, dim3(1), dim3(1024), 0, s, p.wgcount, nwg, count);
-}
-
-__global__ __launch_bounds__(256) void compact_kernel(const CompactParams p) {
-    __shared__ int s_cnt[4];
-    const int rr = blockIdx.x * 256 + threadIdx.x;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int keep = (rr < p.Ra && !p.done[rr]) ? 1 : 0;
-    const unsigned long long m = __ballot(keep);
-    if (lane == 0) s_cnt[wave] = __popcll(m);
-    __syncthreads();
-    if (!keep) return;
-    int pos = p.wgoffset[blockIdx.x] + __popcll(m & ((1ull << lane) - 1ull));
-    for (int w = 0; w < wave; ++w) pos += s_cnt[w];
-    const int Ra_new = *p.count;
-    p.sel[pos] = rr;
-    p.rowid_new[pos] = p.rowid_old ? p.rowid_old[rr] : rr;
-    p.done_new[pos] = 0;
-    if (p.c_old) {
-        for (int h = 0; h < p.nsign; ++h) {
-            p.c_new[h * Ra_new + pos] = p.c_old[h * p.Ra + rr];
-            p.err_new[h * Ra_new + pos] = p.err_old[h * p.Ra + rr];
-        }
-    }
-}
-void launch_compact(const CompactParams& p, hipStream_t s) {
-    if (p.Ra <= 0) return;
-    hipLaunchKernelGGL(compact_kernel, dim3((p.Ra + 255) / 256), dim3(256), 0, s, p);
-}
-
-// block rows of the tasks kept, moved to their new places in another buffer (4 rows per work-group)
-__global__ __launch_bounds__(256) void copy_rows_kernel(const CopyRowsParams p) {
-    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (r >= p.Ra_new * p.nsign) return;
-    const int half = r >= p.Ra_new ? 1 : 0;
-    const int i = r - half * p.Ra_new;
-    const float* src = p.src + ((size_t)half * p.Ra_old + p.sel[i]) * p.nelem;
-    float* dst = p.dst + (size_t)r * p.nelem;
-    const int lane = threadIdx.x & 63;
-    if ((p.nelem & 3) == 0) {
-        const int n4 = p.nelem >> 2;
-        for (int e = blockIdx.y * 64 + lane; e < n4; e += gridDim.y * 64)
-            reinterpret_cast<float4*>(dst)[e] = reinterpret_cast<const float4*>(src)[e];
-    } else {
-        for (int e = blockIdx.y * 64 + lane; e < p.nelem; e += gridDim.y * 64) dst[e] = src[e];
-    }
-}
-void launch_copy_rows(const CopyRowsParams& p, hipStream_t s) {
-    const long long rows = (long long)p.Ra_new * p.nsign;
-    if (rows <= 0 || p.nelem <= 0) return;
-    const int per = (p.nelem & 3) == 0 ? p.nelem / 4 : p.nelem;
-    const int ychunks = (int)fmin((double)((per + 63) / 64), 32.0);
-    hipLaunchKernelGGL(copy_rows_kernel, dim3((unsigned)((rows + 3) / 4), ychunks), dim3(256), 0, s, p);
-}
-
-__global__ void mfma_check_kernel(const double* A, const double* B, double* D, int K) {
-    int l = threadIdx.x;
-    double4_t c = {0.0, 0.0, 0.0, 0.0};
-    for (int k0 = 0; k0 < K; k0 += 4) {
-        double a = A[(l & 15) * K + k0 + (l >> 4)];
-        double b = B[(k0 + (l >> 4)) * 16 + (l & 15)];
-        c = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
-    }
-    for (int r = 0; r < 4; ++r) D[(4 * r + (l >> 4)) * 16 + (l & 15)] = c[r];
-}
-void launch_mfma_check(const double* A, const double* B, double* D, int K, hipStream_t s) {
-    hipLaunchKernelGGL(mfma_check_kernel, dim3(1), dim3(64), 0, s, A, B, D, K);
-}
-// the 4-column form used for layers with at most 4 input channels: D[16][4] = A[16][K] * B[K][4]
-__global__ void mfma4_check_kernel(const double* A, const double* B, double* D, int K) {
-    const int l = threadIdx.x;
-    double c = 0.0;
-    for (int k0 = 0; k0 < K; k0 += 4) {
-        const double a = A[(l & 15) * K + k0 + (l >> 4)];
-        const double b = B[(k0 + (l >> 4)) * 4 + (l & 3)];
-        c = __builtin_amdgcn_mfma_f64_4x4x4f64(a, b, c, 0, 0, 0);
-    }
-    D[(4 * ((l & 15) >> 2) + (l >> 4)) * 4 + (l & 3)] = c;
-}
-void launch_mfma4_check(const double* A, const double* B, double* D, int K, hipStream_t s) {
-    hipLaunchKernelGGL(mfma4_check_kernel, dim3(1), dim3(64), 0, s, A, B, D, K);
 }
 
 }  // namespace gp

@@ -1,0 +1,95 @@
+// Device-side helpers shared by the kernel files: how a row of a launch maps to its neuron, range-checked buffer
+// loads, the packed ReLU relaxation.
+#pragma once
+#include "kernels.hpp"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+#include <type_traits>
+
+namespace gp {
+
+typedef double double4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ int clampi(int v, int lo, int hi) { return min(max(v, lo), hi); }
+
+struct RowInfo {
+    int b, ys, xs, cs;
+    float sign;
+};
+
+__device__ __forceinline__ RowInfo row_info(const RowMap& rm, int r) {
+    RowInfo ri;
+    int rr = r;
+    ri.sign = 1.f;
+    if (r >= rm.Rc) {
+        rr = r - rm.Rc;
+        ri.sign = -1.f;
+    }
+    if (rm.rowid) rr = rm.rowid[rr];
+    const uint32_t g = (uint32_t)(rm.row0 + rr);
+    const uint32_t b = fast_div(g, rm.div_n);
+    const uint32_t i = g - b * (uint32_t)rm.n_start;
+    const uint32_t pos = fast_div(i, rm.div_c);
+    const uint32_t ys = fast_div(pos, rm.div_w);
+    ri.b = (int)b;
+    ri.cs = (int)(i - pos * (uint32_t)rm.Cs);
+    ri.ys = (int)ys;
+    ri.xs = (int)(pos - ys * (uint32_t)rm.Ws);
+    return ri;
+}
+
+// where row r keeps its best candidate: the layout of the chunk before any row was removed
+__device__ __forceinline__ int best_index(const RowMap& rm, int r) {
+    const int half = r >= rm.Rc ? 1 : 0;
+    int rr = r - half * rm.Rc;
+    if (rm.rowid) rr = rm.rowid[rr];
+    return half * rm.Rc0 + rr;
+}
+
+typedef unsigned int uint4_t __attribute__((ext_vector_type(4)));
+
+struct F4 {
+    float v[4];
+};
+
+// a value every lane of the wave holds alike, moved to scalar registers: what is derived from it (loop bounds, tap
+// numbers, scalar offsets and resource descriptors of buffer loads) then stays scalar; left in vector registers the
+// compiler would wrap every such load into a loop over the distinct values
+__device__ __forceinline__ unsigned long long wave_uniform(unsigned long long v) {
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+    return ((unsigned long long)hi << 32) | lo;
+}
+
+constexpr uint32_t kOOB = 0x80000000u;   // byte offset beyond every buffer range: the load returns 0
+
+// 4 consecutive floats at byte offset `off` of a buffer resource; offsets beyond the resource's range
+// read as 0 (hardware range check), so invalid taps / rows / channels need no masking instructions.
+template <bool VEC>
+__device__ __forceinline__ F4 buf_ld4(__amdgpu_buffer_rsrc_t rsrc, uint32_t off, int nvalid) {
+    F4 r;
+    if (VEC) {
+        uint4_t v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off, 0, 0);
+        r.v[0] = __uint_as_float(v.x); r.v[1] = __uint_as_float(v.y);
+        r.v[2] = __uint_as_float(v.z); r.v[3] = __uint_as_float(v.w);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t o = (j < nvalid) ? off + 4u * j : kOOB;
+            r.v[j] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, (int)o, 0, 0));
+        }
+    }
+    return r;
+}
+
+// ReLU relaxation of one neuron packed in one float: |g| is the slope of the upper line, the sign bit
+// is set when the lower line is 0 (lam = 0) and clear when it is x (lam = 1).
+// A coefficient a over relu(x) becomes a * relax_factor(a, g) over x (Section 2: positive coefficients
+// take the upper line, negative ones the lower line, for an upper bound).
+__device__ __forceinline__ float relax_factor(double a, float g) {
+    return a >= 0.0 ? fabsf(g) : (signbit(g) ? 0.f : 1.f);
+}
+
+}  // namespace gp

@@ -1,5 +1,5 @@
 // Host side of the gpupoly C ABI: network description, dependence-window planning, and the
-// back-substitution driver that enqueues the kernels of kernels.hip.
+// back-substitution driver that enqueues the kernels of cross.hip, scan.hip and layers.hip.
 //
 // Driver (paper Section 2 "Bottleneck Backsubstitution", Section 4.2 for the order of layers):
 // layers are visited in id order; every layer that needs intervals is the start layer of a batch
@@ -52,7 +52,7 @@ struct Layer {
     double* d_beff = nullptr;
     double *d_lo = nullptr, *d_hi = nullptr, *d_xmax = nullptr;
     double *d_rho = nullptr, *d_kap = nullptr;   // ReLU layers: candidate and intercept multipliers after substitution
-    float* d_grl = nullptr;        // packed ReLU relaxation (see relax_factor in kernels.hip)
+    float* d_grl = nullptr;        // packed ReLU relaxation (see relax_factor in device_common.hpp)
     int* d_term = nullptr;         // early termination: per task the layer at which it met the criterion
     // inference rounding (Section 4.1): per neuron, how far a float32 evaluation can be from the exact expression over
     // the predecessors.  d_eta: affine layers their own error; sum layers their own rounding plus what their summands

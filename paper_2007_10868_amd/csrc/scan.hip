@@ -1,0 +1,382 @@
+// Per-row reductions over a coefficient block: candidate bounds, rounding slack, constants of the next step
+// (paper Section 2, candidate bounds; Section 4.1 for the slack).
+#include "device_common.hpp"
+
+namespace gp {
+
+// ------------------------------------------------------------------------------------------------
+// Per-row reductions over a block:
+//   candidate  sum_j (m_j >= 0 ? m_j*cpos_j : m_j*cneg_j)                   (Section 2, candidate bound)
+//   rounding   sum_j |m_j| * max(|xlo_j|,|xhi_j|)                           (slack of the float32 storage)
+//   constants of the next step: sum_j max(m_j,0)*kap_j + m_j*bias_c
+//   S1 = sum_j |m_j|                                                        (slack of the next accumulation)
+// With inference rounding (p.eta) the constants also take sum_j |m_j|*eta_j.  Since |m| = 2*max(m,0) - m this needs no
+// sum of its own: eta_j is folded into the two constants of the neuron, kap_j + 2*eta_j and bias_c - eta_j.
+// For a block over a plain layer cpos/cneg are the layer's upper/lower interval ends.  A block whose
+// coefficients already went through a ReLU substitution holds m = M*slope (M >= 0) or m = M*lam (M < 0)
+// over the ReLU's INPUT; the candidate over the ReLU's OUTPUT interval [L,U] that DeepPoly takes before
+// the substitution is recovered as M*U = m*(U/slope) =: m*rho and M*L = m*L (L = 0 unless the neuron is
+// stably active, where lam = 1), and the intercept term M*del = m*(del/slope) =: m*kap.
+// The kernels share this arithmetic (scan_term, scan_finish) and differ in how rows and lanes are laid out; which one
+// runs is decided by the row length alone, see launch_scan.
+// ------------------------------------------------------------------------------------------------
+// One coefficient's contribution to the five per-row sums.  Written with explicit fused multiply-adds only, so that
+// every scan kernel performs exactly the same operations in the same order per lane and a row's result does not
+// depend on which kernel (i.e. on how many rows share the launch) handled it.
+__device__ __forceinline__ void scan_term(bool has_cand, bool do_consts, float mf, double cp, double cn, double X, double kp,
+                                          double be, double& cand, double& absx, double& cst, double& cstabs, double& s1) {
+    const double m = (double)mf;
+    const double am = fabs(m);
+    if (has_cand) {
+        cand = fma(m, mf >= 0.f ? cp : cn, cand);
+        absx = fma(am, X, absx);
+    }
+    if (do_consts) {
+        const double mp = fmax(m, 0.0);
+        cst = fma(m, be, fma(mp, kp, cst));
+        cstabs = fma(am, fabs(be), fma(mp, kp, cstabs));
+        s1 += am;
+    }
+}
+
+// The same for the kernels that stage the neurons' constants in LDS, with fewer vector instructions per coefficient
+// (every one of them is paid in time here): the staged multiplier pair is (cpos - cneg, cneg), so that the candidate
+// term needs no select, m*c(m) = max(m,0)*(cpos - cneg) + m*cneg; and the magnitude of the constant terms, which only
+// scales a rounding slack, is not summed per coefficient but bounded per row by S1 * max_j(|bias_j| + kap_j).
+__device__ __forceinline__ void scan_term_staged(bool has_cand, bool do_consts, float mf, double dcp, double cn, double X,
+                                                 double kp, double be, double& cand, double& absx, double& cst, double& s1) {
+    const double m = (double)mf;
+    const double am = fabs(m);
+    const double mp = fmax(m, 0.0);
+    if (has_cand) {
+        cand = fma(mp, dcp, fma(m, cn, cand));
+        absx = fma(am, X, absx);
+    }
+    if (do_consts) {
+        cst = fma(m, be, fma(mp, kp, cst));
+        s1 += am;
+    }
+}
+
+// The scalars of a row that its bookkeeping reads.  Fetched early (scan_row_fetch) by the kernels that want the
+// round trip to overlap with the row's own loads.
+struct ScanRow {
+    double c, err, best, xmax_self, xmax_a, xmax_b;
+    int bi;
+    bool frozen;
+};
+__device__ __forceinline__ ScanRow scan_row_fetch(const ScanParams& p, int r, const RowInfo& ri) {
+    ScanRow s;
+    s.c = p.c[r];
+    s.err = p.err[r];
+    s.xmax_self = (p.round_coef > 0.0 && p.xmax_self) ? p.xmax_self[ri.b] : 0.0;
+    s.bi = 0; s.best = 0.0; s.frozen = true;
+    if (p.update_best && p.cpos) {
+        // a task that met the termination criterion keeps the bounds it had at that moment
+        s.frozen = p.done && p.done[r >= p.rm.Rc ? r - p.rm.Rc : r];
+        s.bi = best_index(p.rm, r);
+        s.best = p.best[s.bi];
+    }
+    s.xmax_a = (p.do_consts && p.xmax_a) ? p.xmax_a[ri.b] : 0.0;
+    s.xmax_b = (p.do_consts && p.xmax_b) ? p.xmax_b[ri.b] : 0.0;
+    return s;
+}
+// Per-row bookkeeping after the reductions: rounding slack of the stored coefficients, candidate folded into best,
+// constants of the next step added to c, slack of the next accumulation.
+__device__ __forceinline__ void scan_finish(const ScanParams& p, int r, int nelem, const ScanRow& s, double t_cand,
+                                            double t_absx, double t_cst, double t_cstabs, double t_s1) {
+    // a sum of n float64 terms in any order is off by at most (n-1)*2^-53*sum|terms|*(1+tiny)
+    const double esum = (double)(nelem + 16) * 0x1p-52;
+    double c = s.c;
+    double err = s.err;
+    // slack of the stored coefficients: |true - stored| <= round_coef*|stored| (+ subnormal floor)
+    err += t_absx * p.round_coef * (1.0 + esum);
+    // values below the float32 subnormal step vanish; with a substituted ReLU the lost coefficient is
+    // up to 2^20 times larger (slopes are kept >= 2^-20)
+    if (p.round_coef > 0.0 && p.xmax_self) err += 0x1p-128 * (double)nelem * s.xmax_self;
+    if (p.update_best && p.cpos) {
+        double v = c + t_cand + err;
+        // (the candidate's terms are at most 3*|m|*X in magnitude when the multiplier comes as a difference, see
+        // scan_term_staged)
+        v += (fabs(c) + fabs(t_cand) + err) * 0x1p-50 + 3.0 * t_absx * esum;
+        if (!s.frozen) p.best[s.bi] = fmin(s.best, v);
+    }
+    if (p.do_consts) {
+        double cn = c + t_cst;
+        double e1 = 0.0;
+        if (p.xmax_a) e1 += p.e1_a * s.xmax_a;
+        if (p.xmax_b) e1 += p.e1_b * s.xmax_b;
+        err += t_cstabs * esum + (fabs(c) + fabs(t_cst)) * 0x1p-51 + t_s1 * e1 * (1.0 + esum);
+        c = cn;
+    }
+    err *= (1.0 + 0x1p-48);   // the few float64 operations above
+    p.c[r] = c;
+    p.err[r] = err;
+}
+
+constexpr int SCAN_G = 8;     // rows per wave of the 8-lanes-per-row layout
+
+// Short rows: LPR = 8 lanes per row, 8 rows per wave.  Every lane accumulates for its own row (few registers, many
+// resident waves) and fetches the constants of its own elements; lanes of different rows that meet the same neuron
+// read the same addresses.
+template <int V, int LPR>
+__global__ __launch_bounds__(256) void scan_tall_kernel(const ScanParams p) {
+    constexpr int RPW = 64 / LPR;                            // rows per wave
+    const int tid = threadIdx.x, lane = tid & 63;
+    const BlockDesc& B = p.blk;
+    const int groups_per_half = (p.rm.Rc + RPW - 1) / RPW;
+    const int gidx = blockIdx.x * 4 + (tid >> 6);
+    const int nhalves = p.nrows / p.rm.Rc;
+    if (gidx >= groups_per_half * nhalves) return;          // whole wave leaves
+    const int half = gidx / groups_per_half;
+    const int rr0 = (gidx - half * groups_per_half) * RPW;
+    const int nvalid = min(RPW, p.rm.Rc - rr0);
+    const int k = lane / LPR, sub = lane % LPR;
+    const bool valid = k < nvalid;
+    const int r = half * p.rm.Rc + rr0 + (valid ? k : 0);
+    const int nelem = B.wy * B.wx * B.C;
+    const bool full_row = (B.wx == B.W);
+    const RowInfo ri = row_info(p.rm, r);
+    const int oy = clampi(B.Sy * ri.ys - B.Py, 0, B.H - B.wy), ox = clampi(B.Sx * ri.xs - B.Px, 0, B.W - B.wx);
+    const long long bbase = (long long)ri.b * p.batch_stride;
+    const float* src = B.data + (size_t)r * nelem;
+    double cand = 0.0, absx = 0.0, cst = 0.0, cstabs = 0.0, s1 = 0.0;
+    if (valid) {
+        for (int e = sub * V; e < nelem; e += LPR * V) {
+            float mf[V];
+            if (V == 4) {
+                const float4 t = *reinterpret_cast<const float4*>(src + e);
+                mf[0] = t.x; mf[1 % V] = t.y; mf[2 % V] = t.z; mf[3 % V] = t.w;
+            } else {
+                mf[0] = src[e];
+            }
+            int c;
+            long long j;
+            if (full_row) {
+                c = e % B.C;
+                j = bbase + (long long)oy * B.W * B.C + e;
+            } else {
+                const int pix = e / B.C;
+                c = e - pix * B.C;
+                const int a = pix / B.wx, bb = pix - a * B.wx;
+                j = bbase + ((long long)((oy + a) * B.W + (ox + bb)) * B.C + c);
+            }
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                double cp = 0.0, cn = 0.0, X = 0.0, kp = 0.0, be = 0.0;
+                if (p.cpos) {
+                    cp = p.cpos[j + v];
+                    cn = p.cneg[j + v];
+                    X = fmax(fabs(p.xlo[j + v]), fabs(p.xhi[j + v]));
+                }
+                if (p.do_consts) {
+                    if (p.kap) kp = p.kap[j + v];
+                    if (p.beff) be = p.beff[c + v];
+                    if (p.eta) { const double et = p.eta[j + v]; kp += 2.0 * et; be -= et; }
+                }
+                scan_term(p.cpos != nullptr, p.do_consts != 0, mf[v], cp, cn, X, kp, be, cand, absx, cst, cstabs, s1);
+            }
+        }
+    }
+#pragma unroll
+    for (int off = LPR / 2; off > 0; off >>= 1) {
+        cand += __shfl_xor(cand, off, 64);
+        absx += __shfl_xor(absx, off, 64);
+        cst += __shfl_xor(cst, off, 64);
+        cstabs += __shfl_xor(cstabs, off, 64);
+        s1 += __shfl_xor(s1, off, 64);
+    }
+    if (valid && sub == 0) scan_finish(p, r, nelem, scan_row_fetch(p, r, ri), cand, absx, cst, cstabs, s1);
+}
+
+// Rows of a few hundred coefficients (dense layers, small windows): 32 rows per work-group, 8 lanes per row.  The
+// per-neuron constants of the rows' window are staged ONCE per work-group in LDS (5 doubles per element) instead of
+// being fetched by every wave, every lane accumulates for its own row (few registers, many resident waves), and
+// lanes of different rows read the same LDS words (broadcast).  Rows of a work-group that do not share box and
+// window origin are handled run by run.
+constexpr int SCAN_LDS_MAX = 1024;      // longest row whose constants are staged whole (40 KB of LDS)
+constexpr int SCAN_CHUNK = 512;         // chunk of longer rows (20 KB of LDS: 8 work-groups per CU)
+// ROWS per work-group (8 lanes each); the grouping does not touch a row's arithmetic.
+// U: row slices (8 lanes x V elements each) whose loads are in flight together.
+// CHUNKED: rows longer than SCAN_LDS_MAX are cut into chunks of SCAN_CHUNK coefficients, one work-group per (32 rows,
+// chunk); the five sums of a (row, chunk) go to p.partial and scan_combine_kernel adds a row's chunks in order.
+template <int V, int ROWS, int U, bool CHUNKED>
+__global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) {
+    constexpr int SCAN_LDS_ROWS = ROWS;
+    constexpr int NT = ROWS * 8;
+    extern __shared__ __attribute__((aligned(16))) double s_const[];     // [5][nelem_pad]
+    __shared__ int s_b[SCAN_LDS_ROWS], s_oy[SCAN_LDS_ROWS], s_ox[SCAN_LDS_ROWS];
+    // bits of max_j(|bias_j| + kap_j) over the staged constants (non-negative), one slot per parity of the run: a slot
+    // is cleared during the following run, two barriers away from both its readers and its next writers
+    __shared__ unsigned long long s_qmax[2];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const BlockDesc& B = p.blk;
+    const int nelem = B.wy * B.wx * B.C;
+    const int c0 = CHUNKED ? (int)blockIdx.y * SCAN_CHUNK : 0;             // this work-group's element range
+    const int c1 = CHUNKED ? min(nelem, c0 + SCAN_CHUNK) : nelem;
+    const int npad = CHUNKED ? SCAN_CHUNK : ((nelem + 3) & ~3);
+    double* const s_cp = s_const;
+    double* const s_cn = s_const + npad;
+    double* const s_X = s_const + 2 * npad;
+    double* const s_kp = s_const + 3 * npad;
+    double* const s_be = s_const + 4 * npad;
+    const int gph = (p.rm.Rc + SCAN_LDS_ROWS - 1) / SCAN_LDS_ROWS;      // work-groups per half
+    const int half = blockIdx.x / gph;
+    const int rr0 = (blockIdx.x - half * gph) * SCAN_LDS_ROWS;
+    const int nvalid = min(SCAN_LDS_ROWS, p.rm.Rc - rr0);
+    const int kk = wave * 8 + (lane >> 3), sub = lane & 7;
+    const bool valid = kk < nvalid;
+    const int r = half * p.rm.Rc + rr0 + (valid ? kk : 0);
+    const bool full_row = (B.wx == B.W);
+    const RowInfo ri = row_info(p.rm, r);
+    if (sub == 0 && valid) {
+        s_b[kk] = ri.b;
+        s_oy[kk] = clampi(B.Sy * ri.ys - B.Py, 0, B.H - B.wy);
+        s_ox[kk] = clampi(B.Sx * ri.xs - B.Px, 0, B.W - B.wx);
+    }
+    if (tid == 0) s_qmax[0] = s_qmax[1] = 0ull;
+    __syncthreads();
+    const float* src = B.data + (size_t)r * nelem;
+    double cand = 0.0, absx = 0.0, cst = 0.0, cstabs = 0.0, s1 = 0.0;
+    auto load_slices = [&](int e0, float (&mf)[U][V]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int e = e0 + u * 8 * V;
+            if (e < c1) {
+                if (V == 4) {
+                    const float4 t = *reinterpret_cast<const float4*>(src + e);
+                    mf[u][0] = t.x; mf[u][1 % V] = t.y; mf[u][2 % V] = t.z; mf[u][3 % V] = t.w;
+                } else {
+                    mf[u][0] = src[e];
+                }
+            }
+        }
+    };
+    auto add_slices = [&](int e0, const float (&mf)[U][V]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int e = e0 + u * 8 * V;
+            if (e < c1) {
+                const int k = e - c0;
+#pragma unroll
+                for (int v = 0; v < V; ++v)
+                    scan_term_staged(p.cpos != nullptr, p.do_consts != 0, mf[u][v], s_cp[k + v], s_cn[k + v], s_X[k + v],
+                                     s_kp[k + v], s_be[k + v], cand, absx, cst, s1);
+            }
+        }
+    };
+    int k0 = 0, run = 0;
+    while (k0 < nvalid) {                                   // uniform over the work-group
+        if (tid == 0) s_qmax[(run & 1) ^ 1] = 0ull;
+        const int b0 = s_b[k0], oy0 = s_oy[k0], ox0 = s_ox[k0];
+        int k1 = k0 + 1;
+        while (k1 < nvalid && s_b[k1] == b0 && s_oy[k1] == oy0 && s_ox[k1] == ox0) ++k1;
+        const long long bbase = (long long)b0 * p.batch_stride;
+        double qmax = 0.0;
+        for (int e = c0 + tid; e < c1; e += NT) {
+            int c;
+            long long j;
+            if (full_row) {
+                c = e % B.C;
+                j = bbase + (long long)oy0 * B.W * B.C + e;
+            } else {
+                const int pix = e / B.C;
+                c = e - pix * B.C;
+                const int a = pix / B.wx, bb = pix - a * B.wx;
+                j = bbase + ((long long)((oy0 + a) * B.W + (ox0 + bb)) * B.C + c);
+            }
+            double cp = 0.0, cn = 0.0, X = 0.0, kp = 0.0, be = 0.0;
+            if (p.cpos) {
+                cp = p.cpos[j];
+                cn = p.cneg[j];
+                X = fmax(fabs(p.xlo[j]), fabs(p.xhi[j]));
+            }
+            if (p.do_consts) {
+                if (p.kap) kp = p.kap[j];
+                if (p.beff) be = p.beff[c];
+                if (p.eta) { const double et = p.eta[j]; kp += 2.0 * et; be -= et; }
+            }
+            const int k = e - c0;
+            s_cp[k] = cp - cn; s_cn[k] = cn; s_X[k] = X; s_kp[k] = kp; s_be[k] = be;
+            qmax = fmax(qmax, fabs(be) + kp);
+        }
+        if (p.do_consts) {
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) qmax = fmax(qmax, __shfl_xor(qmax, off, 64));
+            // non-negative doubles order like their bit patterns
+            if (lane == 0) atomicMax(&s_qmax[run & 1], (unsigned long long)__double_as_longlong(qmax));
+        }
+        __syncthreads();
+        if (valid && kk >= k0 && kk < k1) {
+            const double s1_before = s1;
+            for (int e0 = c0 + sub * V; e0 < c1; e0 += U * 8 * V) {
+                float mf[U][V];
+                load_slices(e0, mf);
+                add_slices(e0, mf);
+            }
+            // magnitude of the row's constant terms (scales a rounding slack only): a row lies in exactly one run
+            cstabs = (s1 - s1_before) * __longlong_as_double((long long)s_qmax[run & 1]) * (1.0 + 0x1p-50);
+        }
+        __syncthreads();                                    // the next run overwrites the constants
+        k0 = k1;
+        ++run;
+    }
+#pragma unroll
+    for (int off = 4; off > 0; off >>= 1) {
+        cand += __shfl_xor(cand, off, 64);
+        absx += __shfl_xor(absx, off, 64);
+        cst += __shfl_xor(cst, off, 64);
+        cstabs += __shfl_xor(cstabs, off, 64);
+        s1 += __shfl_xor(s1, off, 64);
+    }
+    if (valid && sub == 0) {
+        if constexpr (CHUNKED) {
+            double* out = p.partial + ((size_t)r * gridDim.y + blockIdx.y) * 5;
+            out[0] = cand; out[1] = absx; out[2] = cst; out[3] = cstabs; out[4] = s1;
+        } else {
+            scan_finish(p, r, nelem, scan_row_fetch(p, r, ri), cand, absx, cst, cstabs, s1);
+        }
+    }
+}
+
+// a row's chunk sums added in chunk order, then the row's bookkeeping
+__global__ __launch_bounds__(256) void scan_combine_kernel(const ScanParams p, int nchunks) {
+    const int r = blockIdx.x * 256 + threadIdx.x;
+    if (r >= p.nrows) return;
+    const double* in = p.partial + (size_t)r * nchunks * 5;
+    double t[5] = {0.0, 0.0, 0.0, 0.0, 0.0};
+    for (int c = 0; c < nchunks; ++c)
+#pragma unroll
+        for (int q = 0; q < 5; ++q) t[q] += in[c * 5 + q];
+    const RowInfo ri = row_info(p.rm, r);
+    scan_finish(p, r, p.blk.wy * p.blk.wx * p.blk.C, scan_row_fetch(p, r, ri), t[0], t[1], t[2], t[3], t[4]);
+}
+
+
+void launch_scan(const ScanParams& p, hipStream_t s) {
+    if (p.nrows <= 0) return;
+    const int nhalves = p.nrows / p.rm.Rc;
+    const int nelem = p.blk.wy * p.blk.wx * p.blk.C;
+    const bool vec = (p.blk.C & 3) == 0;
+    // the layout depends on the row length only, never on how many rows the launch has: a row's sums are formed in
+    // the same order whether its box is analysed alone, in a batch, or in a chunk of a batch
+    if (nelem <= 256 || (nelem > SCAN_LDS_MAX && !p.partial)) {      // cross-over of the two layouts measured on MI355X
+        const int groups = ((p.rm.Rc + SCAN_G - 1) / SCAN_G) * nhalves;
+        if (vec) hipLaunchKernelGGL((scan_tall_kernel<4, 8>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((scan_tall_kernel<1, 8>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
+    } else if (nelem <= SCAN_LDS_MAX) {
+        const size_t lds = (size_t)5 * ((nelem + 3) & ~3) * sizeof(double);
+        const int wgs = ((p.rm.Rc + 31) / 32) * nhalves;
+        if (vec) hipLaunchKernelGGL((scan_lds_kernel<4, 32, 4, false>), dim3(wgs), dim3(256), lds, s, p);
+        else hipLaunchKernelGGL((scan_lds_kernel<1, 32, 4, false>), dim3(wgs), dim3(256), lds, s, p);
+    } else {
+        const int nchunks = (nelem + SCAN_CHUNK - 1) / SCAN_CHUNK;
+        const dim3 grid(((p.rm.Rc + 31) / 32) * nhalves, nchunks);
+        const size_t lds = (size_t)5 * SCAN_CHUNK * sizeof(double);
+        if (vec) hipLaunchKernelGGL((scan_lds_kernel<4, 32, 4, true>), grid, dim3(256), lds, s, p);
+        else hipLaunchKernelGGL((scan_lds_kernel<1, 32, 4, true>), grid, dim3(256), lds, s, p);
+        hipLaunchKernelGGL(scan_combine_kernel, dim3((p.nrows + 255) / 256), dim3(256), 0, s, p, nchunks);
+    }
+}
+
+}  // namespace gp
