@@ -1011,6 +1011,157 @@ static void launch_cross_image(const CrossParams& p0, hipStream_t s) {
     else hipLaunchKernelGGL((cross_image_kernel<false>), grid, dim3(256), 0, s, p);
 }
 
+// Image layers behind a stride-1 layer with a long K per pixel (3x3 filters over 32 or 64 channels).  With 4 output
+// columns a block value feeds only 4 multiply-adds per use, and in the kernels above every output pixel re-loads the
+// values under its taps: those steps run at the speed of the vector L1 (64 B/clk), not of the matrix pipe.  Here one
+// wave computes a STRIP of P horizontally adjacent output pixels for its 32 rows: a block value (one 16-byte load per
+// lane and 16-channel step, as in cross_direct_kernel) is loaded and converted once and used for every output pixel of
+// the strip it reaches (up to kw of them), which cuts the L1 traffic and the conversions by that factor.  The filter
+// (float64, 4 columns) sits in LDS; its fragments for the kw taps of a filter row are fetched once per (filter row,
+// channel step).  Accumulators: one double per lane, 16-row tile and strip pixel (4x4x4 MFMA).
+// Requires what the launcher checks: stride 1, every group of 32 consecutive rows at one position of the start layer
+// in one box (so the whole geometry is scalar), whole 16-channel steps.
+// grid: (row tile of 128 rows, output row, strip) in the XCD-aware order of cross_kernel.
+template <int P>
+__global__ __launch_bounds__(256) void cross_strip_kernel(const CrossParams p) {
+    constexpr int TM = 2, KW_MAX = 4;
+    extern __shared__ __attribute__((aligned(16))) double s_w[];          // [tap][4][Ck + 2]
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lk = lane >> 4, lm = lane & 15;
+    const int Ck = p.in.C, N = p.Co, ldw = Ck + 2;
+    const int nstrips = (p.owx + P - 1) / P;
+    const uint32_t per_tile = (uint32_t)(p.owy * nstrips);
+    const uint32_t total = per_tile * (uint32_t)p.ntiles_m;
+    const uint32_t per_xcd = (total + 7u) >> 3;
+    const uint32_t logical = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+    if (logical >= total) return;
+    {   // filter -> LDS (all waves, before any of them leaves)
+        const int cnt = p.kh * p.kw * 4 * Ck;
+        for (int idx = tid; idx < cnt; idx += 256) {
+            const int c = idx % Ck, tn = idx / Ck, n = tn & 3, t = tn >> 2;
+            s_w[tn * ldw + c] = n < N ? p.wt64[((size_t)t * N + n) * Ck + c] : 0.0;
+        }
+        __syncthreads();
+    }
+    const uint32_t rt = fast_div(logical, p.div_opix);                     // div_opix divides by per_tile here
+    const int rem = (int)(logical - rt * per_tile);
+    const int pa = rem / nstrips, pb0 = (rem - pa * nstrips) * P;
+    const int Pv = min(P, p.owx - pb0);
+    const int r_wave = (int)rt * 128 + wave * 32;
+    if (r_wave >= p.nrows) return;
+    const int rows_here = min(32, p.nrows - r_wave);
+    const RowInfo u0 = row_info(p.rm, r_wave), u1 = row_info(p.rm, r_wave + rows_here - 1);
+    if (!(u0.b == u1.b && u0.ys == u1.ys && u0.xs == u1.xs)) return;       // excluded by the launcher's conditions
+    const int opix = p.owy * p.owx;
+    const uint32_t row_elems = (uint32_t)(p.in.wy * p.in.wx * Ck);
+    const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(p.in.data + (size_t)r_wave * row_elems), 0, (int)((uint32_t)rows_here * row_elems * 4u), 0x00020000);
+    // geometry of the wave's common position (scalar)
+    const int oiy = clampi(p.in.Sy * u0.ys - p.in.Py, 0, p.in.H - p.in.wy), oix = clampi(p.in.Sx * u0.xs - p.in.Px, 0, p.in.W - p.in.wx);
+    const int A = clampi(p.oSy * u0.ys - p.oPy, 0, p.Ho - p.owy) + pa, B0 = clampi(p.oSx * u0.xs - p.oPx, 0, p.Wo - p.owx) + pb0;
+    const int ty = p.in.tSy * u0.ys - p.in.tPy, tx = p.in.tSx * u0.xs - p.in.tPx;
+    const int ylo = max(max(ty, oiy), 0), yhi = min(min(ty + p.in.tWy, oiy + p.in.wy), p.in.H);
+    const int xlo = max(max(tx, oix), 0), xhi = min(min(tx + p.in.tWx, oix + p.in.wx), p.in.W);
+    uint32_t a_voff[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int rl = i * 16 + lm;
+        a_voff[i] = rl < rows_here ? ((uint32_t)rl * row_elems + 4u * (uint32_t)lk) * 4u : kOOB;
+    }
+    const double* const w_lane = s_w + (lm & 3) * ldw + 4 * lk;
+    double acc[TM][P];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int q = 0; q < P; ++q) acc[i][q] = 0.0;
+
+    // tap (f, g) of a stride-1 layer reads, for output pixel (A, B), the layer-output pixel (A + ph - f, B + pw - g);
+    // so the block value at (y, x) reaches output pixel B = x - pw + g, i.e. strip pixel q = x - pw + g - B0
+    const int x_first = max(xlo, B0 + p.pw - (p.kw - 1)), x_last = min(xhi, B0 + Pv + p.pw);      // [x_first, x_last)
+    for (int f = 0; f < p.kh; ++f) {
+        const int y = A + p.ph - f;
+        if (y < ylo || y >= yhi) continue;
+        for (int d0 = 0; d0 < Ck; d0 += 16) {
+            double bf[KW_MAX][4];
+#pragma unroll
+            for (int g = 0; g < KW_MAX; ++g) {
+                const int gg = min(g, p.kw - 1);
+                const double2* src = reinterpret_cast<const double2*>(w_lane + (f * p.kw + gg) * 4 * ldw + d0);
+                const double2 v0 = src[0], v1 = src[1];
+                bf[g][0] = v0.x; bf[g][1] = v0.y; bf[g][2] = v1.x; bf[g][3] = v1.y;
+            }
+            for (int x = x_first; x < x_last; ++x) {
+                const uint32_t soff = (uint32_t)(((y - oiy) * p.in.wx + (x - oix)) * Ck + d0) * 4u;
+                double av[TM][4];
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    const uint4_t v = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, (int)a_voff[i], (int)soff, 0);
+                    av[i][0] = (double)__uint_as_float(v.x); av[i][1] = (double)__uint_as_float(v.y);
+                    av[i][2] = (double)__uint_as_float(v.z); av[i][3] = (double)__uint_as_float(v.w);
+                }
+                const int q0 = x - p.pw - B0;                   // strip pixel reached through tap g = 0
+#pragma unroll
+                for (int g = 0; g < KW_MAX; ++g) {
+                    const int q = q0 + g;
+                    if (g >= p.kw || q < 0 || q >= Pv) continue;            // uniform
+#pragma unroll
+                    for (int qq = 0; qq < P; ++qq) {
+                        if (q != qq) continue;                              // uniform: picks the accumulator
+#pragma unroll
+                        for (int k = 0; k < 4; ++k)
+#pragma unroll
+                            for (int i = 0; i < TM; ++i)
+                                acc[i][qq] = __builtin_amdgcn_mfma_f64_4x4x4f64(av[i][k], bf[g][k], acc[i][qq], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+
+    // ---- epilogue: the lane's value of tile i is row 4*((l%16)/4) + l/16, column l%4
+    const int n = lm & 3;
+    const bool has_add = p.add.data != nullptr;
+    const int add_oy = has_add ? clampi(p.add.Sy * u0.ys - p.add.Py, 0, p.add.H - p.add.wy) : 0;
+    const int add_ox = has_add ? clampi(p.add.Sx * u0.xs - p.add.Px, 0, p.add.W - p.add.wx) : 0;
+#pragma unroll
+    for (int q = 0; q < P; ++q) {
+        if (q >= Pv) continue;
+        const int B = B0 + q, pix = pa * p.owx + pb0 + q;
+        const long long ridx = (long long)u0.b * ((long long)p.Ho * p.Wo * N) + (long long)(A * p.Wo + B) * N;
+        const int ay = A - add_oy, ax = B - add_ox;
+        const bool add_in = has_add && ay >= 0 && ay < p.add.wy && ax >= 0 && ax < p.add.wx;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int rl = i * 16 + 4 * (lm >> 2) + lk;
+            const int r = r_wave + rl;
+            if (r >= p.nrows || n >= N) continue;
+            double v = acc[i][q];
+            if (add_in) v += (double)p.add.data[((size_t)r * p.add.wy * p.add.wx + (size_t)(ay * p.add.wx + ax)) * N + n];
+            if (p.out_grl) v *= (double)relax_factor(v, p.out_grl[ridx + n]);
+            p.out[((size_t)r * opix + pix) * N + n] = (float)v;
+        }
+    }
+}
+
+// does the strip kernel apply?  (stride 1, short filter rows, whole channel steps, filter fits in LDS, and every group
+// of 32 consecutive rows is one position of the start layer in one box)
+static bool strip_applies(const CrossParams& p, size_t& lds) {
+    lds = (size_t)p.kh * p.kw * 4 * (p.in.C + 2) * sizeof(double);
+    return p.Co <= 4 && p.wt64 && p.sh == 1 && p.sw == 1 && p.kw <= 4 && (p.in.C & 15) == 0 && lds <= 24576 &&
+           p.rm.rowid == nullptr && (p.rm.Cs & 31) == 0 && (p.rm.row0 & 31) == 0 && (p.rm.Rc & 31) == 0 && p.owx >= 4;
+}
+
+static void launch_cross_strip(const CrossParams& p0, size_t lds, hipStream_t s) {
+    constexpr int P = 8;
+    CrossParams p = p0;
+    p.ntiles_m = (p.nrows + 127) / 128;
+    const int nstrips = (p.owx + P - 1) / P;
+    p.div_opix = make_fastdiv((uint32_t)(p.owy * nstrips));
+    const long long total = (long long)p.ntiles_m * p.owy * nstrips;
+    const unsigned blocks = (unsigned)(((total + 7) / 8) * 8);
+    hipLaunchKernelGGL((cross_strip_kernel<P>), dim3(blocks), dim3(256), lds, s, p);
+}
+
 template <int BM, int BN>
 static void launch_cross_t(const CrossParams& p0, hipStream_t s) {
     CrossParams p = p0;
@@ -1045,6 +1196,8 @@ void launch_cross(const CrossParams& p, hipStream_t s) {
     // faster than the MFMA kernel at K = 64, 0.75x at K = 288)
     const int k_pixel = ((p.kh + p.sh - 1) / p.sh) * ((p.kw + p.sw - 1) / p.sw) * p.in.C;
     if (N <= 4 && p.wt64 && k_pixel <= 128) { launch_cross_image(p, s); return; }
+    size_t strip_lds = 0;
+    if (N <= 4 && strip_applies(p, strip_lds)) { launch_cross_strip(p, strip_lds, s); return; }
     if (N <= 4) { launch_cross_direct<2, 0>(p, s); return; }
     if (N <= 16) { launch_cross_direct<2, 1>(p, s); return; }
     if (N <= 32) { launch_cross_direct<2, 2>(p, s); return; }

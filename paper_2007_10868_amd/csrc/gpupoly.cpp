@@ -651,6 +651,8 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
         }
     Rc_max = std::min(Rc_max, ((1LL << 31) - 256) / (nsign * max_pix));
     if (Rc_max <= 0) return fail(net, GP_ERR_WORKSPACE, "workspace of %lld bytes cannot hold one row (%lld bytes)", ws_bytes, tb);
+    // when the rows do not fit at once, chunks start at multiples of 64 tasks (kernels that want rows grouped by position)
+    if (Rc_max < total && Rc_max > 64) Rc_max -= Rc_max % 64;
     Rc_max = std::min(Rc_max, total);
     const long long nrows_max = Rc_max * nsign;
     // header: per-row scalars (two copies of constant and slack), then the task lists of early termination
