@@ -1022,9 +1022,9 @@ static void launch_cross_image(const CrossParams& p0, hipStream_t s) {
 // Requires what the launcher checks: stride 1, every group of 32 consecutive rows at one position of the start layer
 // in one box (so the whole geometry is scalar), whole 16-channel steps.
 // grid: (row tile of 128 rows, output row, strip) in the XCD-aware order of cross_kernel.
-template <int P>
+template <int P, int KW>
 __global__ __launch_bounds__(256) void cross_strip_kernel(const CrossParams p) {
-    constexpr int TM = 2, KW_MAX = 4;
+    constexpr int TM = 2;
     extern __shared__ __attribute__((aligned(16))) double s_w[];          // [tap][4][Ck + 2]
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lk = lane >> 4, lm = lane & 15;
@@ -1077,42 +1077,58 @@ __global__ __launch_bounds__(256) void cross_strip_kernel(const CrossParams p) {
 
     // tap (f, g) of a stride-1 layer reads, for output pixel (A, B), the layer-output pixel (A + ph - f, B + pw - g);
     // so the block value at (y, x) reaches output pixel B = x - pw + g, i.e. strip pixel q = x - pw + g - B0
-    const int x_first = max(xlo, B0 + p.pw - (p.kw - 1)), x_last = min(xhi, B0 + Pv + p.pw);      // [x_first, x_last)
+    // The strip's block pixels of one filter row are x_j = B0 + pw - (KW-1) + j, j = 0 .. P+KW-2, and x_j reaches strip
+    // pixel q = j - (KW-1) + g through tap g: with j and g unrolled every accumulator index is a compile-time constant
+    // and a step costs a handful of scalar instructions (the scalar unit is shared by the CU's four SIMDs; with MFMAs
+    // of 16 cycles a loop that picks accumulators at run time is bound by it).  Strip pixels beyond the window's edge
+    // (last strip) are computed from whatever valid block pixels reach them and not stored.
+    constexpr int NJ = P + KW - 1;
+    const int xj0 = B0 + p.pw - (KW - 1);
     for (int f = 0; f < p.kh; ++f) {
         const int y = A + p.ph - f;
         if (y < ylo || y >= yhi) continue;
+        const uint32_t row_off = (uint32_t)((y - oiy) * p.in.wx - oix) * (uint32_t)Ck;    // + x*Ck + d0: wraps harmlessly when x < oix is never used
         for (int d0 = 0; d0 < Ck; d0 += 16) {
-            double bf[KW_MAX][4];
+            double bf[KW][4];
 #pragma unroll
-            for (int g = 0; g < KW_MAX; ++g) {
-                const int gg = min(g, p.kw - 1);
-                const double2* src = reinterpret_cast<const double2*>(w_lane + (f * p.kw + gg) * 4 * ldw + d0);
+            for (int g = 0; g < KW; ++g) {
+                const double2* src = reinterpret_cast<const double2*>(w_lane + (f * KW + g) * 4 * ldw + d0);
                 const double2 v0 = src[0], v1 = src[1];
                 bf[g][0] = v0.x; bf[g][1] = v0.y; bf[g][2] = v1.x; bf[g][3] = v1.y;
             }
-            for (int x = x_first; x < x_last; ++x) {
-                const uint32_t soff = (uint32_t)(((y - oiy) * p.in.wx + (x - oix)) * Ck + d0) * 4u;
+            uint4_t raw[2][TM];
+            auto valid = [&](int j) { const int x = xj0 + j; return x >= xlo && x < xhi; };
+            auto issue = [&](int j, uint4_t (&dst)[TM]) {
+                const uint32_t soff = (row_off + (uint32_t)(xj0 + j) * (uint32_t)Ck + (uint32_t)d0) * 4u;
+#pragma unroll
+                for (int i = 0; i < TM; ++i) dst[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, (int)a_voff[i], (int)soff, 0);
+            };
+            if (valid(0)) issue(0, raw[0]);
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                const bool vj = valid(j);
                 double av[TM][4];
+                if (vj) {
 #pragma unroll
-                for (int i = 0; i < TM; ++i) {
-                    const uint4_t v = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, (int)a_voff[i], (int)soff, 0);
-                    av[i][0] = (double)__uint_as_float(v.x); av[i][1] = (double)__uint_as_float(v.y);
-                    av[i][2] = (double)__uint_as_float(v.z); av[i][3] = (double)__uint_as_float(v.w);
+                    for (int i = 0; i < TM; ++i) {
+                        av[i][0] = (double)__uint_as_float(raw[j & 1][i].x); av[i][1] = (double)__uint_as_float(raw[j & 1][i].y);
+                        av[i][2] = (double)__uint_as_float(raw[j & 1][i].z); av[i][3] = (double)__uint_as_float(raw[j & 1][i].w);
+                    }
                 }
-                const int q0 = x - p.pw - B0;                   // strip pixel reached through tap g = 0
+                if (j + 1 < NJ && valid(j + 1)) issue(j + 1, raw[(j + 1) & 1]);     // in flight during the MFMAs below
+                if (vj) {
+                    // k outermost: consecutive MFMAs go to up to KW*TM different accumulators, so none waits for the
+                    // result of the one before it
 #pragma unroll
-                for (int g = 0; g < KW_MAX; ++g) {
-                    const int q = q0 + g;
-                    if (g >= p.kw || q < 0 || q >= Pv) continue;            // uniform
+                    for (int k = 0; k < 4; ++k)
 #pragma unroll
-                    for (int qq = 0; qq < P; ++qq) {
-                        if (q != qq) continue;                              // uniform: picks the accumulator
-#pragma unroll
-                        for (int k = 0; k < 4; ++k)
+                        for (int g = 0; g < KW; ++g) {
+                            const int q = j - (KW - 1) + g;
+                            if (q < 0 || q >= P) continue;                          // compile time
 #pragma unroll
                             for (int i = 0; i < TM; ++i)
-                                acc[i][qq] = __builtin_amdgcn_mfma_f64_4x4x4f64(av[i][k], bf[g][k], acc[i][qq], 0, 0, 0);
-                    }
+                                acc[i][q] = __builtin_amdgcn_mfma_f64_4x4x4f64(av[i][k], bf[g][k], acc[i][q], 0, 0, 0);
+                        }
                 }
             }
         }
@@ -1143,11 +1159,11 @@ __global__ __launch_bounds__(256) void cross_strip_kernel(const CrossParams p) {
     }
 }
 
-// does the strip kernel apply?  (stride 1, short filter rows, whole channel steps, filter fits in LDS, and every group
+// does the strip kernel apply?  (stride 1, filter rows of 3 taps, whole channel steps, filter fits in LDS, and every group
 // of 32 consecutive rows is one position of the start layer in one box)
 static bool strip_applies(const CrossParams& p, size_t& lds) {
     lds = (size_t)p.kh * p.kw * 4 * (p.in.C + 2) * sizeof(double);
-    return p.Co <= 4 && p.wt64 && p.sh == 1 && p.sw == 1 && p.kw <= 4 && (p.in.C & 15) == 0 && lds <= 24576 &&
+    return p.Co <= 4 && p.wt64 && p.sh == 1 && p.sw == 1 && p.kw == 3 && (p.in.C & 15) == 0 && lds <= 24576 &&
            p.rm.rowid == nullptr && (p.rm.Cs & 31) == 0 && (p.rm.row0 & 31) == 0 && (p.rm.Rc & 31) == 0 && p.owx >= 4;
 }
 
@@ -1159,7 +1175,7 @@ static void launch_cross_strip(const CrossParams& p0, size_t lds, hipStream_t s)
     p.div_opix = make_fastdiv((uint32_t)(p.owy * nstrips));
     const long long total = (long long)p.ntiles_m * p.owy * nstrips;
     const unsigned blocks = (unsigned)(((total + 7) / 8) * 8);
-    hipLaunchKernelGGL((cross_strip_kernel<P>), dim3(blocks), dim3(256), lds, s, p);
+    hipLaunchKernelGGL((cross_strip_kernel<P, 3>), dim3(blocks), dim3(256), lds, s, p);
 }
 
 template <int BM, int BN>
