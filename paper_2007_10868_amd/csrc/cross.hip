@@ -6,7 +6,7 @@
 // is rounded once to float32.  Every rounding is bounded and the bound, multiplied by the largest
 // magnitude the neuron can take, is added to a per-row slack `err` that is part of every
 // candidate bound.  All rows are upper-bound expressions (lower bounds are taken on -x).
-// This file: crossing an affine layer (Algorithm 1 as an implicit GEMM), in three forms chosen by the layer's width.
+// This file: crossing an affine layer (Algorithm 1 as an implicit GEMM), in several forms chosen by the width of the layer.
 #include "device_common.hpp"
 
 namespace gp {
