@@ -1082,54 +1082,53 @@ __global__ __launch_bounds__(256) void cross_strip_kernel(const CrossParams p) {
     // and a step costs a handful of scalar instructions (the scalar unit is shared by the CU's four SIMDs; with MFMAs
     // of 16 cycles a loop that picks accumulators at run time is bound by it).  Strip pixels beyond the window's edge
     // (last strip) are computed from whatever valid block pixels reach them and not stored.
+    // Order of the contributions to one output pixel: filter row, then tap of the row, then channel step - the order
+    // cross_direct_kernel uses (its taps ascend, i.e. the block pixels DEscend), with the same instruction on the same
+    // operands: a row gets the same bits from either kernel, so results do not depend on which of the two a chunk of
+    // rows happens to qualify for.
     constexpr int NJ = P + KW - 1;
     const int xj0 = B0 + p.pw - (KW - 1);
     for (int f = 0; f < p.kh; ++f) {
         const int y = A + p.ph - f;
         if (y < ylo || y >= yhi) continue;
-        const uint32_t row_off = (uint32_t)((y - oiy) * p.in.wx - oix) * (uint32_t)Ck;    // + x*Ck + d0: wraps harmlessly when x < oix is never used
-        for (int d0 = 0; d0 < Ck; d0 += 16) {
-            double bf[KW][4];
+        const uint32_t row_off = (uint32_t)((y - oiy) * p.in.wx - oix) * (uint32_t)Ck;    // + x*Ck + d0 (x >= oix whenever it is used)
+        const double* const w_row = w_lane + f * KW * 4 * ldw;
 #pragma unroll
-            for (int g = 0; g < KW; ++g) {
-                const double2* src = reinterpret_cast<const double2*>(w_lane + (f * KW + g) * 4 * ldw + d0);
-                const double2 v0 = src[0], v1 = src[1];
-                bf[g][0] = v0.x; bf[g][1] = v0.y; bf[g][2] = v1.x; bf[g][3] = v1.y;
-            }
-            uint4_t raw[2][TM];
-            auto valid = [&](int j) { const int x = xj0 + j; return x >= xlo && x < xhi; };
-            auto issue = [&](int j, uint4_t (&dst)[TM]) {
-                const uint32_t soff = (row_off + (uint32_t)(xj0 + j) * (uint32_t)Ck + (uint32_t)d0) * 4u;
+        for (int jj = 0; jj < NJ; ++jj) {
+            const int j = NJ - 1 - jj;
+            const int x = xj0 + j;
+            if (x < xlo || x >= xhi) continue;                                      // uniform
+            for (int d0 = 0; d0 < Ck; d0 += 16) {
+                const uint32_t soff = (row_off + (uint32_t)x * (uint32_t)Ck + (uint32_t)d0) * 4u;
+                uint4_t raw[TM];
 #pragma unroll
-                for (int i = 0; i < TM; ++i) dst[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, (int)a_voff[i], (int)soff, 0);
-            };
-            if (valid(0)) issue(0, raw[0]);
+                for (int i = 0; i < TM; ++i) raw[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, (int)a_voff[i], (int)soff, 0);
+                double bf[KW][4];
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) {
-                const bool vj = valid(j);
+                for (int g = 0; g < KW; ++g) {
+                    const int q = j - (KW - 1) + g;
+                    if (q < 0 || q >= P) continue;                                  // compile time
+                    const double2* src = reinterpret_cast<const double2*>(w_row + g * 4 * ldw + d0);
+                    const double2 v0 = src[0], v1 = src[1];
+                    bf[g][0] = v0.x; bf[g][1] = v0.y; bf[g][2] = v1.x; bf[g][3] = v1.y;
+                }
                 double av[TM][4];
-                if (vj) {
 #pragma unroll
-                    for (int i = 0; i < TM; ++i) {
-                        av[i][0] = (double)__uint_as_float(raw[j & 1][i].x); av[i][1] = (double)__uint_as_float(raw[j & 1][i].y);
-                        av[i][2] = (double)__uint_as_float(raw[j & 1][i].z); av[i][3] = (double)__uint_as_float(raw[j & 1][i].w);
+                for (int i = 0; i < TM; ++i) {
+                    av[i][0] = (double)__uint_as_float(raw[i].x); av[i][1] = (double)__uint_as_float(raw[i].y);
+                    av[i][2] = (double)__uint_as_float(raw[i].z); av[i][3] = (double)__uint_as_float(raw[i].w);
+                }
+                // k outermost: consecutive MFMAs go to up to KW*TM different accumulators, none waits for the one before
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+#pragma unroll
+                    for (int g = 0; g < KW; ++g) {
+                        const int q = j - (KW - 1) + g;
+                        if (q < 0 || q >= P) continue;                              // compile time
+#pragma unroll
+                        for (int i = 0; i < TM; ++i)
+                            acc[i][q] = __builtin_amdgcn_mfma_f64_4x4x4f64(av[i][k], bf[g][k], acc[i][q], 0, 0, 0);
                     }
-                }
-                if (j + 1 < NJ && valid(j + 1)) issue(j + 1, raw[(j + 1) & 1]);     // in flight during the MFMAs below
-                if (vj) {
-                    // k outermost: consecutive MFMAs go to up to KW*TM different accumulators, so none waits for the
-                    // result of the one before it
-#pragma unroll
-                    for (int k = 0; k < 4; ++k)
-#pragma unroll
-                        for (int g = 0; g < KW; ++g) {
-                            const int q = j - (KW - 1) + g;
-                            if (q < 0 || q >= P) continue;                          // compile time
-#pragma unroll
-                            for (int i = 0; i < TM; ++i)
-                                acc[i][q] = __builtin_amdgcn_mfma_f64_4x4x4f64(av[i][k], bf[g][k], acc[i][q], 0, 0, 0);
-                        }
-                }
             }
         }
     }
