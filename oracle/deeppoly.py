@@ -43,6 +43,7 @@ def _load():
     L.dp_destroy.argtypes = [P]
     L.dp_add_dense.argtypes = [P, C.c_int, C.c_int, fp, fp]
     L.dp_add_conv2d.argtypes = [P] + [C.c_int] * 8 + [fp, fp]
+    L.dp_add_avgpool2d.argtypes = [P] + [C.c_int] * 7
     L.dp_add_relu.argtypes = [P, C.c_int]
     L.dp_add_residual.argtypes = [P, C.c_int, C.c_int]
     L.dp_num_layers.argtypes = [P]
@@ -139,6 +140,17 @@ class OracleNet:
         lid = self._L.dp_add_conv2d(self._h, src, W.shape[0], W.shape[2], W.shape[3], sh, sw, ph, pw, pW, pb)
         if lid < 0:
             raise OracleError("add_conv2d")
+        return lid
+
+    def add_avgpool2d(self, src, kernel, stride=None, pad=0) -> int:
+        kh, kw = (kernel, kernel) if np.isscalar(kernel) else kernel
+        if stride is None:
+            stride = (kh, kw)
+        sh, sw = (stride, stride) if np.isscalar(stride) else stride
+        ph, pw = (pad, pad) if np.isscalar(pad) else pad
+        lid = self._L.dp_add_avgpool2d(self._h, src, kh, kw, sh, sw, ph, pw)
+        if lid < 0:
+            raise OracleError("add_avgpool2d")
         return lid
 
     def add_relu(self, src) -> int:

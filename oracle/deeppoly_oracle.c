@@ -77,7 +77,7 @@
 
 #pragma STDC FENV_ACCESS ON
 
-enum { L_INPUT = 0, L_DENSE = 1, L_CONV = 2, L_RELU = 3, L_ADD = 4 };
+enum { L_INPUT = 0, L_DENSE = 1, L_CONV = 2, L_RELU = 3, L_ADD = 4, L_POOL = 5 };
 enum { DP_OK = 0, DP_ERR_ARG = 1, DP_ERR_STATE = 3, DP_ERR_NOMEM = 4 };
 
 typedef struct {
@@ -86,6 +86,7 @@ typedef struct {
     double *wt;              /* dense [n][n_in]; conv [C][Cin][kh][kw]             */
     double *bias;            /* [n] dense, [C] conv                                */
     int kh, kw, sh, sw, ph, pw;
+    double w_dn, w_up;       /* average pooling: 1/(kh*kw) rounded down / up               */
     double *lo, *hi;         /* intervals of this layer's neurons                  */
     int has_bounds, need_bounds;
     double *gam, *del;       /* ReLU: upper line gam*x+del (unstable neurons)      */
@@ -191,6 +192,28 @@ int dp_add_conv2d(dp_net *N, int src, int c_out, int kh, int kw, int sh, int sw,
     l->bias = (double *)calloc(c_out, sizeof(double));
     for (size_t i = 0; i < nw; ++i) l->wt[i] = (double)W[i];
     if (b) for (int i = 0; i < c_out; ++i) l->bias[i] = (double)b[i];
+    alloc_bounds(l);
+    return N->n_layers - 1;
+}
+
+/* Average pooling: every channel on its own, out(c,y,x) = (1/(kh*kw)) * sum of the window of in(c,.,.) at
+   (y*sh - ph + f, x*sw - pw + g); positions in the zero padding add nothing and the divisor stays kh*kw.  An affine
+   layer like a convolution (Section 2: the affine transformer is exact), with no stored filter. */
+int dp_add_avgpool2d(dp_net *N, int src, int kh, int kw, int sh, int sw, int ph, int pw) {
+    if (!N || src < 0 || src >= N->n_layers || kh <= 0 || kw <= 0 || sh <= 0 || sw <= 0 || ph < 0 || pw < 0) return -1;
+    layer_t *p = &N->L[src];
+    if (p->H + 2 * ph < kh || p->W + 2 * pw < kw) return -1;
+    int ho = (p->H + 2 * ph - kh) / sh + 1, wo = (p->W + 2 * pw - kw) / sw + 1;
+    int C = p->C;
+    layer_t *l = new_layer(N);
+    l->type = L_POOL; l->a = src; l->C = C; l->H = ho; l->W = wo; l->n = C * ho * wo;
+    l->kh = kh; l->kw = kw; l->sh = sh; l->sw = sw; l->ph = ph; l->pw = pw;
+    int old = fegetround();
+    fesetround(FE_UPWARD);
+    volatile double k = (double)kh * kw, one = 1.0;
+    l->w_up = one / k;
+    l->w_dn = -((-one) / k);
+    fesetround(old);
     alloc_bounds(l);
     return N->n_layers - 1;
 }
@@ -591,6 +614,40 @@ static void step_conv(const dp_net *N, expr_t *e, int k) {
     e->active[c->a] = 1;
 }
 
+/* coefficient interval [alo,ahi] times the pooling weight, known only as w_dn <= 1/(kh*kw) <= w_up (both > 0) */
+static inline void acc_pooled(double *lo, double *hi, double alo, double ahi, double w_dn, double w_up) {
+    *lo = add_dn(*lo, alo >= 0.0 ? mul_dn(alo, w_dn) : mul_dn(alo, w_up));
+    *hi = add_up(*hi, ahi >= 0.0 ? mul_up(ahi, w_up) : mul_up(ahi, w_dn));
+}
+
+static void step_pool(const dp_net *N, expr_t *e, int k) {
+    const layer_t *c = &N->L[k];
+    const layer_t *p = &N->L[c->a];
+    double *slo = e->lo[k], *shi = e->hi[k];
+    double *dlo = e->lo[c->a], *dhi = e->hi[c->a];
+    for (int d = 0; d < c->C; ++d)
+        for (int y = 0; y < c->H; ++y)
+            for (int x = 0; x < c->W; ++x) {
+                int i = (d * c->H + y) * c->W + x;
+                double a = slo[i], b = shi[i];
+                if (a == 0.0 && b == 0.0) continue;
+                for (int f = 0; f < c->kh; ++f) {
+                    int iy = y * c->sh - c->ph + f;
+                    if (iy < 0 || iy >= p->H) continue;
+                    for (int g = 0; g < c->kw; ++g) {
+                        int ix = x * c->sw - c->pw + g;
+                        if (ix < 0 || ix >= p->W) continue;
+                        int j = (d * p->H + iy) * p->W + ix;
+                        acc_pooled(&dlo[j], &dhi[j], a, b, c->w_dn, c->w_up);
+                    }
+                }
+                if (c->has_eta) acc_error(e, a, b, c->eta[i]);
+                slo[i] = shi[i] = 0.0;
+            }
+    e->active[k] = 0;
+    e->active[c->a] = 1;
+}
+
 static void step_add(const dp_net *N, expr_t *e, int k) {
     const layer_t *s = &N->L[k];
     double *slo = e->lo[k], *shi = e->hi[k];
@@ -628,6 +685,7 @@ static double backsubstitute(const dp_net *N, expr_t *e, int sense) {
             case L_RELU:  step_relu(N, e, k, sense); break;
             case L_DENSE: step_dense(N, e, k); break;
             case L_CONV:  step_conv(N, e, k); break;
+            case L_POOL:  step_pool(N, e, k); break;
             case L_ADD:   step_add(N, e, k); break;
             default: return NAN;
         }
@@ -639,7 +697,10 @@ static const double kU32 = 0x1p-24;           /* unit roundoff of float32 */
 
 /* eta of an affine layer from the intervals of its predecessor (pl, pu); FE_UPWARD */
 static void affine_inference_error(layer_t *l, const layer_t *p, const double *pl, const double *pu) {
-    const double K = (l->type == L_DENSE) ? (double)p->n : (double)l->kh * l->kw * p->C;
+    /* summands of one neuron; an average is the float32 sum of its kh*kw window values in any order followed by one
+       rounded multiplication by a rounded 1/(kh*kw) or one rounded division: K + 1 roundings at most, like a sum of K
+       products and a bias */
+    const double K = (l->type == L_DENSE) ? (double)p->n : (l->type == L_POOL) ? (double)l->kh * l->kw : (double)l->kh * l->kw * p->C;
     const double ku = (K + 1.0) * kU32;
     const double gamma = ku / (-(ku - 1.0));                     /* k*u/(1-k*u): the denominator rounds down */
     const double floor_ = (K + 1.0) * 0x1p-149;
@@ -650,6 +711,23 @@ static void affine_inference_error(layer_t *l, const layer_t *p, const double *p
             for (int j = 0; j < p->n; ++j) s = add_up(s, mul_up(fabs(w[j]), dmax(fabs(pl[j]), fabs(pu[j]))));
             l->eta[i] = add_up(mul_up(s, gamma), floor_);
         }
+    } else if (l->type == L_POOL) {
+        for (int d = 0; d < l->C; ++d)
+            for (int y = 0; y < l->H; ++y)
+                for (int x = 0; x < l->W; ++x) {
+                    double s = 0.0;
+                    for (int f = 0; f < l->kh; ++f) {
+                        int iy = y * l->sh - l->ph + f;
+                        if (iy < 0 || iy >= p->H) continue;
+                        for (int g = 0; g < l->kw; ++g) {
+                            int ix = x * l->sw - l->pw + g;
+                            if (ix < 0 || ix >= p->W) continue;
+                            int j = (d * p->H + iy) * p->W + ix;
+                            s = add_up(s, dmax(fabs(pl[j]), fabs(pu[j])));
+                        }
+                    }
+                    l->eta[(d * l->H + y) * l->W + x] = add_up(mul_up(mul_up(s, l->w_up), gamma), floor_);
+                }
     } else {
         for (int d = 0; d < l->C; ++d)
             for (int y = 0; y < l->H; ++y)
@@ -692,7 +770,7 @@ static void sum_inference_error(layer_t *l) {
 static int prepare_inference_error(dp_net *N, int lid, int early) {
     layer_t *l = &N->L[lid];
     l->has_eta = 0;
-    if (!N->float_inference || (l->type != L_DENSE && l->type != L_CONV)) return DP_OK;
+    if (!N->float_inference || (l->type != L_DENSE && l->type != L_CONV && l->type != L_POOL)) return DP_OK;
     const layer_t *p = &N->L[l->a];
     if (!p->has_bounds && !(early && p->has_ival)) return DP_ERR_STATE;
     int old = fegetround();
@@ -728,6 +806,7 @@ int dp_bound_rows(dp_net *N, int lid, const int *rows, int n_rows, double *out_l
                     switch (l->type) {
                         case L_DENSE: step_dense(N, e, lid); break;
                         case L_CONV:  step_conv(N, e, lid); break;
+                        case L_POOL:  step_pool(N, e, lid); break;
                         case L_ADD:   step_add(N, e, lid); break;
                         default: break;
                     }
@@ -786,6 +865,27 @@ static void interval_image(dp_net *N, int lid) {
                     if (l->has_eta) { lo = add_dn(lo, -l->eta[i]); hi = add_up(hi, l->eta[i]); }
                     l->ilo[i] = lo; l->ihi[i] = hi;
                 }
+    } else if (l->type == L_POOL) {
+        for (int d = 0; d < l->C; ++d)
+            for (int y = 0; y < l->H; ++y)
+                for (int x = 0; x < l->W; ++x) {
+                    double lo = 0.0, hi = 0.0;
+                    for (int f = 0; f < l->kh; ++f) {
+                        int iy = y * l->sh - l->ph + f;
+                        if (iy < 0 || iy >= p->H) continue;
+                        for (int g = 0; g < l->kw; ++g) {
+                            int ix = x * l->sw - l->pw + g;
+                            if (ix < 0 || ix >= p->W) continue;
+                            int j = (d * p->H + iy) * p->W + ix;
+                            lo = add_dn(lo, pl[j]); hi = add_up(hi, pu[j]);
+                        }
+                    }
+                    lo = lo >= 0.0 ? mul_dn(lo, l->w_dn) : mul_dn(lo, l->w_up);
+                    hi = hi >= 0.0 ? mul_up(hi, l->w_up) : mul_up(hi, l->w_dn);
+                    int i = (d * l->H + y) * l->W + x;
+                    if (l->has_eta) { lo = add_dn(lo, -l->eta[i]); hi = add_up(hi, l->eta[i]); }
+                    l->ilo[i] = lo; l->ihi[i] = hi;
+                }
     } else if (l->type == L_ADD) {
         const layer_t *q = &N->L[l->b];
         const double *ql = cur_lo(q), *qu = cur_hi(q);
@@ -802,6 +902,7 @@ static void step_any(const dp_net *N, expr_t *e, int k, int sense) {
         case L_RELU:  step_relu(N, e, k, sense); break;
         case L_DENSE: step_dense(N, e, k); break;
         case L_CONV:  step_conv(N, e, k); break;
+        case L_POOL:  step_pool(N, e, k); break;
         case L_ADD:   step_add(N, e, k); break;
         default: break;
     }
@@ -950,6 +1051,7 @@ int dp_certify(dp_net *N, int label, int *verified, double *margins) {
             switch (l->type) {
                 case L_DENSE: step_dense(N, e, lid); break;
                 case L_CONV:  step_conv(N, e, lid); break;
+                case L_POOL:  step_pool(N, e, lid); break;
                 case L_ADD:   step_add(N, e, lid); break;
                 default: break;
             }
@@ -986,6 +1088,7 @@ int dp_bound_forms(dp_net *N, int n_forms, const double *coef, const double *off
             switch (l->type) {
                 case L_DENSE: step_dense(N, e, lid); break;
                 case L_CONV:  step_conv(N, e, lid); break;
+                case L_POOL:  step_pool(N, e, lid); break;
                 case L_ADD:   step_add(N, e, lid); break;
                 default: break;
             }

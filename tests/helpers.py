@@ -25,6 +25,8 @@ def forward(net: wl.Net, X: np.ndarray):
         elif t == "conv":
             v = F.conv2d(vals[L["src"]], torch.as_tensor(L["W"].astype(np.float64)),
                          torch.as_tensor(L["b"].astype(np.float64)), stride=L["stride"], padding=L["pad"])
+        elif t == "avgpool":
+            v = F.avg_pool2d(vals[L["src"]], L["kernel"], stride=L["stride"], padding=L["pad"], count_include_pad=True)
         elif t == "relu":
             v = torch.clamp(vals[L["src"]], min=0.0)
         elif t == "add":
@@ -45,6 +47,9 @@ def affine_matrix(net: wl.Net, lid: int):
     zero = torch.zeros(1, *shp, dtype=torch.float64)
     if L["type"] == "dense":
         return L["W"].astype(np.float64), L["b"].astype(np.float64)
+    if L["type"] == "avgpool":
+        cols = F.avg_pool2d(eye, L["kernel"], stride=L["stride"], padding=L["pad"], count_include_pad=True)
+        return cols.reshape(n, -1).T.numpy().copy(), np.zeros(cols[0].numel())
     W = torch.as_tensor(L["W"].astype(np.float64))
     bvec = F.conv2d(zero, W, torch.as_tensor(L["b"].astype(np.float64)), stride=L["stride"], padding=L["pad"])
     cols = F.conv2d(eye, W, None, stride=L["stride"], padding=L["pad"])
@@ -85,7 +90,7 @@ def _np_backsub(net, mats, bounds, relax, start, c0, upper, candidates):
             return best
         M = expr.pop(k)
         L = net.layers[k - 1]
-        if L["type"] in ("dense", "conv"):
+        if L["type"] in ("dense", "conv", "avgpool"):
             A, b = mats[k]
             expr[L["src"]] = expr.get(L["src"], 0) + M @ A
             c = c + M @ b
@@ -109,14 +114,14 @@ def np_deeppoly(net: wl.Net, lo0, hi0, lambda_policy=0, candidates=0, extra_rows
     Returns {layer id: (l, u)} for the input, ReLU inputs, ReLU layers and the last layer.
     extra_rows: optional matrix over the last layer; its lower bounds are returned under key "extra"."""
     nL = len(net.layers)
-    mats = {i: affine_matrix(net, i) for i, L in enumerate(net.layers, start=1) if L["type"] in ("dense", "conv")}
+    mats = {i: affine_matrix(net, i) for i, L in enumerate(net.layers, start=1) if L["type"] in ("dense", "conv", "avgpool")}
     feeds_relu = {L["src"] for L in net.layers if L["type"] == "relu"}
     bounds = {0: (np.asarray(lo0, np.float64), np.asarray(hi0, np.float64))}
     relax = {}
 
     def first_step(i, R):
         L = net.layers[i - 1]
-        if L["type"] in ("dense", "conv"):
+        if L["type"] in ("dense", "conv", "avgpool"):
             A, b = mats[i]
             return {L["src"]: R @ A}, R @ b
         s = {}
@@ -154,7 +159,7 @@ def np_deeppoly_early(net: wl.Net, lo0, hi0):
 
     Returns (bounds, term, ival): {layer: (l, u)}, {layer: int array}, {layer: (l, u)}."""
     nL = len(net.layers)
-    mats = {i: affine_matrix(net, i) for i, L in enumerate(net.layers, start=1) if L["type"] in ("dense", "conv")}
+    mats = {i: affine_matrix(net, i) for i, L in enumerate(net.layers, start=1) if L["type"] in ("dense", "conv", "avgpool")}
     feeds_relu = {L["src"] for L in net.layers if L["type"] == "relu"}
     bounds = {0: (np.asarray(lo0, np.float64), np.asarray(hi0, np.float64))}
     ival, relax, term = {}, {}, {}
@@ -165,7 +170,7 @@ def np_deeppoly_early(net: wl.Net, lo0, hi0):
     def substitute(expr, c, k, upper):
         M = expr.pop(k)
         L = net.layers[k - 1]
-        if L["type"] in ("dense", "conv"):
+        if L["type"] in ("dense", "conv", "avgpool"):
             A, b = mats[k]
             expr[L["src"]] = expr.get(L["src"], 0) + M @ A
             c = c + M @ b
@@ -274,12 +279,19 @@ def _sum_f32(terms: np.ndarray, order: str, rng) -> np.ndarray:
 
 def forward_float32(net: wl.Net, x: np.ndarray, order: str, rng) -> dict:
     """One float32 inference of the network at the float32 point x: every affine neuron is the float32 sum, in
-    the given order, of its float32 products and its bias; a residual sum is one float32 addition; ReLU is exact.
+    the given order, of its float32 products and its bias; an average is the float32 sum of its window, divided by
+    the window size or multiplied by its rounded reciprocal; a residual sum is one float32 addition; ReLU is exact.
     Returns {layer id: float32 [n]} (CHW order).  Test-side code: the order models what an inference engine may do."""
     vals = {0: np.asarray(x, np.float32).reshape(-1)}
     for i, L in enumerate(net.layers, start=1):
         t = L["type"]
-        if t in ("dense", "conv"):
+        if t == "avgpool":                           # float32 sum of the window in the given order, then one scaling
+            A, _ = affine_matrix(net, i)
+            K = np.float32(L["kernel"] * L["kernel"])
+            terms = np.where(A != 0, vals[L["src"]][None, :], np.float32(0)).astype(np.float32)
+            s_ = _sum_f32(terms, order, rng)
+            vals[i] = (s_ / K).astype(np.float32) if rng.random() < 0.5 else (s_ * (np.float32(1) / K)).astype(np.float32)
+        elif t in ("dense", "conv"):
             A, b = affine_matrix(net, i)             # exact float32 values held in float64
             A32, b32 = A.astype(np.float32), b.astype(np.float32)
             assert np.array_equal(A32.astype(np.float64), A) and np.array_equal(b32.astype(np.float64), b)

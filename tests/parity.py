@@ -39,7 +39,7 @@ def make_oracle(net: wl.Net, **opts):
     o = OracleNet(*net.input_shape)
     wl.build_into(net, o)
     for L in net.layers:
-        if L["type"] in ("dense", "conv"):
+        if L["type"] in ("dense", "conv", "avgpool"):
             src = L["src"]
             if src > 0 and net.layers[src - 1]["type"] != "relu":
                 o.request_bounds(src)
@@ -134,7 +134,7 @@ def float_inference_layers(net: wl.Net):
     (its intervals enter the reader's error constant) and every sum layer (its rounding is relative to its interval)."""
     out = set()
     for i, L in enumerate(net.layers, start=1):
-        if L["type"] in ("dense", "conv") and L["src"] > 0 and net.layers[L["src"] - 1]["type"] != "relu":
+        if L["type"] in ("dense", "conv", "avgpool") and L["src"] > 0 and net.layers[L["src"] - 1]["type"] != "relu":
             out.add(L["src"])
         if L["type"] == "add":
             out.add(i)

@@ -82,7 +82,7 @@ def _shift_biases(net, shift):
     feeds = {L["src"] for L in net.layers if L["type"] == "relu"}
     feeds |= {L[k] for L in net.layers if L["type"] == "add" for k in ("a", "b")}
     for i, L in enumerate(net.layers, start=1):
-        if i in feeds and L["type"] in ("dense", "conv"):
+        if i in feeds and L["type"] in ("dense", "conv", "avgpool"):
             L["W"] = (L["W"] * np.float32(0.02)).astype(np.float32)
             L["b"] = (L["b"] + np.float32(shift)).astype(np.float32)
 

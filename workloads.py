@@ -53,6 +53,13 @@ class Net:
         return self._push(dict(type="conv", src=src, W=W, b=b, stride=stride, pad=pad,
                                shape=(co, ho, wo)))
 
+    def avgpool(self, src: int, kernel: int, stride: int = 0, pad: int = 0) -> int:
+        c, h, w = self.shape_of(src)
+        stride = stride or kernel
+        ho = (h + 2 * pad - kernel) // stride + 1
+        wo = (w + 2 * pad - kernel) // stride + 1
+        return self._push(dict(type="avgpool", src=src, kernel=kernel, stride=stride, pad=pad, shape=(c, ho, wo)))
+
     def relu(self, src: int) -> int:
         return self._push(dict(type="relu", src=src, shape=self.shape_of(src)))
 
@@ -81,7 +88,7 @@ class Net:
 
 
 def build_into(net: Net, target) -> List[int]:
-    """Replays the topology on any object with add_dense/add_conv2d/add_relu/add_residual.
+    """Replays the topology on any object with add_dense/add_conv2d/add_avgpool2d/add_relu/add_residual.
 
     Returns the ids the target handed back (they must equal 1..len(layers))."""
     ids = []
@@ -91,6 +98,8 @@ def build_into(net: Net, target) -> List[int]:
             ids.append(target.add_dense(L["src"], L["W"], L["b"]))
         elif t == "conv":
             ids.append(target.add_conv2d(L["src"], L["W"], L["b"], L["stride"], L["pad"]))
+        elif t == "avgpool":
+            ids.append(target.add_avgpool2d(L["src"], L["kernel"], L["stride"], L["pad"]))
         elif t == "relu":
             ids.append(target.add_relu(L["src"]))
         elif t == "add":
@@ -151,14 +160,38 @@ def conv_net(name, input_shape, convs, denses, n_out=10, seed=0, eps=0.0, n_inpu
     return net
 
 
+def pool_net(name, input_shape, stages, denses, n_out=10, seed=0, eps=0.0, n_inputs=1, input_seed_base=0) -> Net:
+    """stages: ("conv", c_out, k, stride, pad) (followed by ReLU) or ("pool", k, stride, pad) (average pooling);
+    denses: hidden widths (+ReLU).  The LeNet family: convolutions with sub-sampling by averages in between."""
+    rng = np.random.default_rng(seed)
+    net = Net(name, input_shape, eps=eps, n_inputs=n_inputs, input_seed_base=input_seed_base)
+    cur = 0
+    for st in stages:
+        if st[0] == "conv":
+            _, co, k, s, p = st
+            W, b = _conv_params(rng, co, net.shape_of(cur)[0], k)
+            cur = net.relu(net.conv(cur, W, b, s, p))
+        else:
+            _, k, s, p = st
+            cur = net.avgpool(cur, k, s, p)
+    fan = net.n_neurons(cur)
+    for wd in denses:
+        W, b = _dense_params(rng, wd, fan)
+        cur = net.relu(net.dense(cur, W, b))
+        fan = wd
+    W, b = _dense_params(rng, n_out, fan)
+    net.dense(cur, W, b)
+    return net
+
+
 def resnet(name, input_shape=(3, 32, 32), channels=(64, 128, 256, 512), blocks=(3, 4, 6, 3),
-           n_out=10, seed=0, eps=0.0, n_inputs=1, input_seed_base=0, second_conv_scale=0.2) -> Net:
+           n_out=10, seed=0, eps=0.0, n_inputs=1, input_seed_base=0, second_conv_scale=0.2, pool_head=False) -> Net:
     """Basic-block residual net: stem conv3x3+ReLU; per block conv3x3-ReLU-conv3x3, sum with the
     shortcut (identity, or a 1x1 stride-2 conv when the stage halves the resolution), ReLU.
     Batch-norm is taken as folded into the conv weights.  The head is global average pooling
     followed by a dense layer; average pooling is linear, so the two are handed over as ONE dense
     layer whose weight is W[o][c] / (H*W) replicated over the H*W positions of channel c
-    (exact when H*W is a power of two)."""
+    (exact when H*W is a power of two).  pool_head: the same network with the pooling as a layer of its own."""
     rng = np.random.default_rng(seed)
     net = Net(name, input_shape, eps=eps, n_inputs=n_inputs, input_seed_base=input_seed_base)
     W, b = _conv_params(rng, channels[0], input_shape[0], 3)
@@ -183,6 +216,10 @@ def resnet(name, input_shape=(3, 32, 32), channels=(64, 128, 256, 512), blocks=(
             c_prev = ch
     c, hh, ww = net.shape_of(cur)
     Wh, bh = _dense_params(rng, n_out, c)
+    if pool_head:
+        assert hh == ww
+        net.dense(net.avgpool(cur, hh), Wh, bh)
+        return net
     Wfold = np.repeat(Wh / np.float32(hh * ww), hh * ww, axis=1).astype(np.float32)  # CHW order
     net.dense(cur, Wfold, bh)
     return net
