@@ -58,6 +58,13 @@ gp_status gp_add_dense(gp_net* net, int32_t in_layer, int32_t out_dim, const flo
 gp_status gp_add_conv2d(gp_net* net, int32_t in_layer, int32_t c_out, int32_t kh, int32_t kw,
                         int32_t stride_h, int32_t stride_w, int32_t pad_h, int32_t pad_w,
                         const float* W, const float* b, int32_t* layer_id);
+/* Average pooling, every channel on its own: output (c,y,x) = (1/(kh*kw)) * sum over the window taps (f,g) of input
+ * (c, y*stride_h - pad_h + f, x*stride_w - pad_w + g); taps in the zero padding add nothing and the divisor stays kh*kw.
+ * An affine layer (Section 2, affine transformer; Section 3.1: its dependence sets are those of a convolution with the
+ * same window) without a stored filter: crossing it costs window-size operations per coefficient instead of a
+ * contraction over channels.  pad < window in both dimensions. */
+gp_status gp_add_avgpool2d(gp_net* net, int32_t in_layer, int32_t kh, int32_t kw, int32_t stride_h, int32_t stride_w,
+                           int32_t pad_h, int32_t pad_w, int32_t* layer_id);
 /* Element-wise max(x,0) of in_layer. */
 gp_status gp_add_relu(gp_net* net, int32_t in_layer, int32_t* layer_id);
 /* Element-wise sum of two layers of equal shape: the exit of a residual block (Section 3.1,
@@ -86,8 +93,10 @@ gp_status gp_set_graph_replay(gp_net* net, int32_t on);
 /* Rounding of the inference itself (paper Section 4.1, last paragraph: the analysis should also cover the error a
  * floating-point evaluation of the network makes, whatever the order of its sums); off by default.  When on, every
  * bound holds for the real-valued network AND for every float32 evaluation of it in which an affine neuron is a sum
- * of float32 products and its bias taken in any order, with or without fused multiply-add, a residual sum is one
- * rounded addition and ReLU is exact (round to nearest, gradual underflow, no overflow).  Mechanism: an affine neuron
+ * of float32 products and its bias taken in any order, with or without fused multiply-add, an average is the float32
+ * sum of its window in any order followed by one rounded division or one multiplication by the rounded reciprocal
+ * (the affine formula below with K = window size, |w_j| = 1/K, b = 0), a residual sum is one rounded addition and
+ * ReLU is exact (round to nearest, gradual underflow, no overflow).  Mechanism: an affine neuron
  * of K inputs is its exact expression plus an error of at most gamma(K+1)*(sum|w_j||x_j| + |b|) + (K+1)*2^-149,
  * gamma(k) = k*2^-24/(1 - k*2^-24), evaluated with the predecessors' bounds; that constant is added, times the
  * magnitude of the coefficient, whenever an expression is substituted through the neuron.  A residual sum layer's

@@ -1200,8 +1200,97 @@ static void launch_cross_t(const CrossParams& p0, hipStream_t s) {
     else hipLaunchKernelGGL((cross_kernel<BM, BN, false, false>), dim3(blocks), dim3(256), 0, s, p);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Crossing an average-pooling layer: every channel on its own, the filter is the constant 1/(kh*kw).  Per row the same
+// transposed convolution as above (Algorithm 1) without the contraction over channels: a gather of at most
+// ceil(kh/sh)*ceil(kw/sw) block entries per new coefficient, so the step is bound by memory, not by arithmetic, and runs
+// on plain float64 vector adds.  One lane per (row, window pixel, 4 channels); the lanes of a pixel read consecutive
+// channels (16 bytes each).  The sum of the gathered entries is exact in float64 up to (taps - 1) roundings, the scaling
+// by the rounded reciprocal adds two more: the caller's slack constant for the step covers taps + 8 of them.
+// Epilogue (addend, ReLU substitution, one rounding to float32) as in the other forms.
+// grid: x over (row, pixel) items, 256 >> lg per work-group; y over chunks of 4 << lg channels.
+template <bool VEC>
+__global__ __launch_bounds__(256) void cross_pool_kernel(const CrossParams p, int lg) {
+    const int C = p.Co;                                     // channels pass through: p.in.C == p.Co
+    const uint32_t opix = (uint32_t)(p.owy * p.owx);
+    const uint32_t item = blockIdx.x * (256u >> lg) + (threadIdx.x >> lg);
+    const int c0 = (int)((blockIdx.y << lg) + (threadIdx.x & ((1u << lg) - 1u))) * 4;
+    if (item >= (uint32_t)p.nrows * opix || c0 >= C) return;
+    const uint32_t r = fast_div(item, p.div_opix);
+    const uint32_t pix = item - r * opix;
+    const int pa = (int)fast_div(pix, p.div_owx), pb = (int)pix - pa * p.owx;
+    const RowInfo ri = row_info(p.rm, (int)r);
+    const int A = clampi(p.oSy * ri.ys - p.oPy, 0, p.Ho - p.owy) + pa;
+    const int B = clampi(p.oSx * ri.xs - p.oPx, 0, p.Wo - p.owx) + pb;
+    // the part of the row's stored window that lies in its exact dependence window (see cross_kernel)
+    const int oiy = clampi(p.in.Sy * ri.ys - p.in.Py, 0, p.in.H - p.in.wy), oix = clampi(p.in.Sx * ri.xs - p.in.Px, 0, p.in.W - p.in.wx);
+    const int ty = p.in.tSy * ri.ys - p.in.tPy, tx = p.in.tSx * ri.xs - p.in.tPx;
+    const int ylo = max(ty, oiy), yhi = min(ty + p.in.tWy, oiy + p.in.wy);
+    const int xlo = max(tx, oix), xhi = min(tx + p.in.tWx, oix + p.in.wx);
+    const float* const row = p.in.data + (size_t)r * (size_t)(p.in.wy * p.in.wx * C) + c0;
+    const int nv = min(4, C - c0);
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    // tap (f, g) reads the layer-output pixel ((A + ph - f) / sh, (B + pw - g) / sw) when both divisions are exact
+    for (int f = 0; f < p.kh; ++f) {
+        const int ny = A + p.ph - f;
+        if (ny < 0) break;
+        const int y = (int)fast_div((uint32_t)ny, p.div_sh);
+        if (y * p.sh != ny || y < ylo || y >= yhi) continue;
+        for (int g = 0; g < p.kw; ++g) {
+            const int nx = B + p.pw - g;
+            if (nx < 0) break;
+            const int x = (int)fast_div((uint32_t)nx, p.div_sw);
+            if (x * p.sw != nx || x < xlo || x >= xhi) continue;
+            const float* a = row + (size_t)((y - oiy) * p.in.wx + (x - oix)) * C;
+            if (VEC) {
+                const float4 v = *reinterpret_cast<const float4*>(a);
+                acc[0] += (double)v.x; acc[1] += (double)v.y; acc[2] += (double)v.z; acc[3] += (double)v.w;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (j < nv) acc[j] += (double)a[j];
+            }
+        }
+    }
+    long long ridx, aoff;
+    epilogue_row_info(p, ri, (int)r, pa, pb, ridx, aoff);
+    float* out = p.out + ((size_t)r * (size_t)opix + (size_t)pix) * C + c0;
+    float res[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        res[j] = 0.f;
+        if (j < nv) {
+            double v = acc[j] * p.pool_scale;
+            if (aoff >= 0) v += (double)p.add.data[aoff + c0 + j];
+            if (p.out_grl) v *= (double)relax_factor(v, p.out_grl[ridx + c0 + j]);
+            res[j] = (float)v;
+        }
+    }
+    if (VEC) {
+        *reinterpret_cast<float4*>(out) = make_float4(res[0], res[1], res[2], res[3]);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (j < nv) out[j] = res[j];
+    }
+}
+
+static void launch_cross_pool(const CrossParams& p0, hipStream_t s) {
+    CrossParams p = p0;
+    const int cg = (p.Co + 3) / 4;                          // groups of 4 channels
+    int lg = 0;
+    while ((1 << lg) < cg && lg < 6) ++lg;
+    p.div_opix = make_fastdiv((uint32_t)(p.owy * p.owx));
+    const long long items = (long long)p.nrows * p.owy * p.owx;            // < 2^31 (checked by the caller)
+    const int per_wg = 256 >> lg;
+    const dim3 grid((unsigned)((items + per_wg - 1) / per_wg), (unsigned)((cg + (1 << lg) - 1) >> lg));
+    if ((p.Co & 3) == 0) hipLaunchKernelGGL((cross_pool_kernel<true>), grid, dim3(256), 0, s, p, lg);
+    else hipLaunchKernelGGL((cross_pool_kernel<false>), grid, dim3(256), 0, s, p, lg);
+}
+
 void launch_cross(const CrossParams& p, hipStream_t s) {
     if (p.nrows <= 0 || p.Co <= 0) return;
+    if (p.pool_scale != 0.0) { launch_cross_pool(p, s); return; }
     const int N = p.Co;
     // tile shapes measured on MI355X: 64x64 beats the larger tiles (their lower occupancy costs more than their
     // higher arithmetic intensity gains); narrow layers take a tall tile so that fewer MFMA columns are padding

@@ -21,7 +21,7 @@
 
 namespace {
 
-enum LType { T_INPUT = 0, T_DENSE = 1, T_CONV = 2, T_RELU = 3, T_ADD = 4 };
+enum LType { T_INPUT = 0, T_DENSE = 1, T_CONV = 2, T_RELU = 3, T_ADD = 4, T_POOL = 5 };   // T_POOL: average pooling
 
 // Dependence window of a row in some layer, before clipping to the layer (Section 4.3):
 // origin = S*pos - P (accumulated stride S, eq. 9; P accumulates padding), size W (eq. 4).
@@ -174,7 +174,10 @@ bool all_finite(const float* p, size_t n) {
     return true;
 }
 
-bool is_affine(const Layer& l) { return l.type == T_DENSE || l.type == T_CONV; }
+bool is_affine(const Layer& l) { return l.type == T_DENSE || l.type == T_CONV || l.type == T_POOL; }
+// an average-pooling layer is a convolution whose filter is the constant 1/(kh*kw) on the channel diagonal: same window
+// geometry, no stored filter, no contraction over channels
+double pool_scale(const Layer& l) { return l.type == T_POOL ? 1.0 / ((double)l.kh * l.kw) : 0.0; }
 
 // ---- window geometry -------------------------------------------------------------------------
 void normalise(Geom& g, const Layer& l) {
@@ -330,7 +333,7 @@ gp_status build_plan(gp_net* net, int start, bool certify, Plan& pl) {
     else { g0.Sy = g0.Sx = 1; g0.Py = g0.Px = 0; g0.Wy = g0.Wx = 1; }
     const Geom t0 = certify ? everywhere() : g0;
     normalise(g0, L[start]);
-    if (!certify && is_affine(L[start])) {
+    if (!certify && is_affine(L[start]) && L[start].type != T_POOL) {
         // the neuron's own affine expression (Section 2): the filter placed in the window over the predecessor
         const int pr = L[start].a;
         Geom g1 = cross_geom(g0, L[start], L[pr]);
@@ -679,7 +682,7 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
             const Layer& a = net->L[op.layer_in];
             const Layer& p = net->L[op.layer_out];
             const double taps = (a.type == T_DENSE) ? 1.0 : (double)a.kh * a.kw;
-            const double cin = (a.type == T_DENSE) ? (double)p.n : (double)p.C;
+            const double cin = (a.type == T_DENSE) ? (double)p.n : (a.type == T_POOL) ? 1.0 : (double)p.C;
             rem_flop[i] += 2.0 * (double)block_elems(op.g_in, a) * taps * cin *
                            (certify ? 1.0 : exact_share(op.g_in, op.t_in, a, ls.H, ls.W));
         }
@@ -836,7 +839,7 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                 sp.xmax_a = sp.xmax_b = nullptr;
                 for (size_t i = 0; i < l.land.size(); ++i) {
                     const Layer& q = net->L[l.land[i]];
-                    double K = (double)q.kh * q.kw * q.C;
+                    double K = (double)q.kh * q.kw * (q.type == T_POOL ? 1.0 : (double)q.C);   // terms of one new coefficient
                     double e1 = (K + 8.0) * 0x1p-50 * q.rowabs;
                     if (i == 0) { sp.e1_a = e1; sp.xmax_a = net->L[q.a].d_xmax; }
                     else { sp.e1_b = e1; sp.xmax_b = net->L[q.a].d_xmax; }
@@ -867,6 +870,7 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                 cp.out_grl = op.relaxed ? p.d_grl : nullptr;
                 cp.wt = a.d_wt;
                 cp.wt64 = a.d_wt64;
+                cp.pool_scale = pool_scale(a);
                 cp.kh = a.kh; cp.kw = a.kw; cp.sh = a.sh; cp.sw = a.sw; cp.ph = a.ph; cp.pw = a.pw;
                 cp.out = slot_ptr(op.slot_out);
                 if (a.type == T_DENSE) {   // a dense layer is a 1x1 convolution over the flattened predecessor
@@ -899,7 +903,7 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                 // of a row is bookkeeping, not part of the method, and counts as zero
                 const double in_el = (double)block_elems(op.g_in, a), out_el = (double)block_elems(op.g_out, p);
                 const double taps = (a.type == T_DENSE) ? 1.0 : (double)a.kh * a.kw;
-                const double cin = (a.type == T_DENSE) ? (double)p.n : (double)p.C;
+                const double cin = (a.type == T_DENSE) ? (double)p.n : (a.type == T_POOL) ? 1.0 : (double)p.C;
                 const bool first = (op.layer_in == start);
                 // (averaged over the start layer's positions, the part of the stored block inside the exact window)
                 const double share = certify ? 1.0 : exact_share(op.g_in, op.t_in, a, ls.H, ls.W);
@@ -977,6 +981,7 @@ gp_status analyze_layers(gp_net* net, int batch) {
                     const Layer& p = net->L[l.a];
                     gp::IvalParams ip;
                     ip.plo = p.d_lo; ip.phi = p.d_hi; ip.wt = l.d_wti; ip.bias = l.d_bias;
+                    ip.pool_scale = pool_scale(l);
                     ip.lo = net->early ? l.d_lo : nullptr; ip.hi = net->early ? l.d_hi : nullptr; ip.flag = net->d_flag;
                     ip.eta = net->float_inference ? l.d_eta : nullptr;
                     if (l.type == T_DENSE) { ip.Hi = ip.Wi = 1; ip.Ci = (int)p.n; }
@@ -1195,6 +1200,28 @@ gp_status gp_add_conv2d(gp_net* net, int32_t in_layer, int32_t c_out, int32_t kh
     l.rowabs = rowabs * (1.0 + 1e-9);
     l.bias_host.assign(c_out, 0.f);
     if (b) std::copy(b, b + c_out, l.bias_host.begin());
+    net->L.push_back(std::move(l));
+    topology_changed(net);
+    *layer_id = (int)net->L.size() - 1;
+    return GP_OK;
+}
+
+gp_status gp_add_avgpool2d(gp_net* net, int32_t in_layer, int32_t kh, int32_t kw, int32_t stride_h, int32_t stride_w,
+                           int32_t pad_h, int32_t pad_w, int32_t* layer_id) {
+    gp_status st = check_new_layer(net, in_layer, layer_id);
+    if (st != GP_OK) return st;
+    if (kh <= 0 || kw <= 0 || stride_h <= 0 || stride_w <= 0 || pad_h < 0 || pad_w < 0)
+        return fail(net, GP_ERR_ARG, "avgpool2d: bad argument");
+    const Layer& p = net->L[in_layer];
+    if (p.H + 2 * pad_h < kh || p.W + 2 * pad_w < kw) return fail(net, GP_ERR_SHAPE, "avgpool2d: window larger than padded input");
+    if (pad_h >= kh || pad_w >= kw) return fail(net, GP_ERR_SHAPE, "avgpool2d: padding must be smaller than the window");
+    if ((long long)kh * kw > (1 << 20)) return fail(net, GP_ERR_SHAPE, "avgpool2d: window too large");
+    const int ho = (p.H + 2 * pad_h - kh) / stride_h + 1, wo = (p.W + 2 * pad_w - kw) / stride_w + 1;
+    Layer l;
+    l.type = T_POOL; l.a = in_layer; l.C = p.C; l.H = ho; l.W = wo; l.n = (long long)p.C * ho * wo;
+    l.kh = kh; l.kw = kw; l.sh = stride_h; l.sw = stride_w; l.ph = pad_h; l.pw = pad_w;
+    l.rowabs = 1.0 + 1e-9;             // kh*kw weights of 1/(kh*kw) each
+    l.bias_host.assign(l.C, 0.f);
     net->L.push_back(std::move(l));
     topology_changed(net);
     *layer_id = (int)net->L.size() - 1;

@@ -65,6 +65,8 @@ struct CrossParams {       // one back-substitution step through an affine layer
     BlockDesc in;          // block over the layer's OUTPUT neurons
     const float* wt;       // [kh*kw][Co][in.C]  (the layer's own output channels innermost)
     const double* wt64;    // the same values in float64; present (non-null) when Co <= 4
+    double pool_scale;     // 0: a layer with a filter; else the layer is average pooling (channels pass through,
+                           //   Co == in.C, wt unused) and this is 1/(kh*kw)
     int kh, kw, sh, sw, ph, pw;
     float* out;            // new block over the layer's INPUT neurons
     const float* out_grl;  // when the input layer is a ReLU layer and the block is complete: its packed relaxation
@@ -166,6 +168,7 @@ struct IvalParams {          // forward interval analysis of an affine layer
     const double* plo; const double* phi;   // predecessor intervals [batch][Hi*Wi*Ci], H,W,C order
     const float* wt;         // [tap][C][Ci] (dense: [C][n_in], seen as one tap over a 1x1 layer with n_in channels)
     const float* bias;       // [C]
+    double pool_scale;       // 0: a layer with weights; else average pooling (C == Ci, wt and bias unused): 1/(kh*kw)
     double* lo; double* hi;  // [batch][H*W*C]; null: intervals not wanted
     double* eta;             // [batch][H*W*C] out: float32 evaluation error of each neuron (also widens lo, hi); null: none
     int* flag;

@@ -335,9 +335,60 @@ __global__ __launch_bounds__(256) void ival_kernel(const IvalParams p) {
         }
     }
 }
+// the same for an average-pooling layer: one lane per neuron, consecutive lanes are consecutive channels
+__global__ __launch_bounds__(256) void pool_ival_kernel(const IvalParams p) {
+    const long long n = (long long)p.H * p.W * p.C;
+    const long long idx = blockIdx.x * 256LL + threadIdx.x;
+    if (idx >= n * p.batch) return;
+    const int b = (int)(idx / n);
+    const int j = (int)(idx - (long long)b * n);
+    const int pix = j / p.C, c = j - pix * p.C;
+    const int y = pix / p.W, x = pix - y * p.W;
+    const long long n_in = (long long)p.Hi * p.Wi * p.C;
+    const double* plo = p.plo + (long long)b * n_in + c;
+    const double* phi = p.phi + (long long)b * n_in + c;
+    double lo = 0.0, hi = 0.0, mag = 0.0, alo = 0.0, ahi = 0.0;
+    for (int f = 0; f < p.kh; ++f) {
+        const int iy = y * p.sh - p.ph + f;
+        if (iy < 0 || iy >= p.Hi) continue;
+        for (int g = 0; g < p.kw; ++g) {
+            const int ix = x * p.sw - p.pw + g;
+            if (ix < 0 || ix >= p.Wi) continue;
+            const double L = plo[(size_t)(iy * p.Wi + ix) * p.C], U = phi[(size_t)(iy * p.Wi + ix) * p.C];
+            lo += L; hi += U; alo += fabs(L); ahi += fabs(U); mag += fmax(fabs(L), fabs(U));
+        }
+    }
+    // the scale is 1/(kh*kw) rounded once; the sums carry at most kh*kw - 1 roundings, each relative to the magnitudes
+    // summed: a window whose lower ends are all 0 (outputs of ReLUs) keeps the lower end 0 exactly
+    const double terms = (double)(p.kh * p.kw) + 1.0;
+    const double rel = (terms + 16.0) * 0x1p-52 * p.pool_scale * (1.0 + 0x1p-30);
+    mag *= p.pool_scale * (1.0 + 0x1p-50);
+    double eta = 0.0;
+    if (p.eta) {
+        // float32 average: the window summed in any order, then one rounded multiplication by a rounded reciprocal or
+        // one rounded division: at most kh*kw + 1 roundings on every term (see ival_kernel)
+        const double ku = terms * 0x1p-24;
+        const double gamma = ku / (1.0 - ku) * (1.0 + 0x1p-50);
+        eta = gamma * mag * (1.0 + (terms + 16.0) * 0x1p-52) * (1.0 + 0x1p-50) + terms * 0x1p-149;
+        if (!isfinite(eta) || ku >= 0.5) *p.flag = 1;
+        p.eta[idx] = eta;
+    }
+    if (p.lo) {
+        double l2 = lo * p.pool_scale - rel * alo - eta, u2 = hi * p.pool_scale + rel * ahi + eta;
+        l2 -= fabs(l2) * 0x1p-51 + (alo > 0.0 ? 0x1p-1000 : 0.0);
+        u2 += fabs(u2) * 0x1p-51 + (ahi > 0.0 ? 0x1p-1000 : 0.0);
+        if (!isfinite(l2) || !isfinite(u2)) *p.flag = 1;
+        p.lo[idx] = l2;
+        p.hi[idx] = u2;
+    }
+}
 void launch_ival(const IvalParams& p, hipStream_t s) {
     const long long total = (long long)p.H * p.W * p.C * p.batch;
     if (total <= 0) return;
+    if (p.pool_scale != 0.0) {
+        hipLaunchKernelGGL(pool_ival_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, p);
+        return;
+    }
     hipLaunchKernelGGL(ival_kernel, dim3((unsigned)((total + 3) / 4)), dim3(256), 0, s, p);
 }
 

@@ -16,7 +16,7 @@ STATUS = {0: "GP_OK", 1: "GP_ERR_ARG", 2: "GP_ERR_SHAPE", 3: "GP_ERR_STATE", 4: 
           6: "GP_ERR_NONFINITE", 7: "GP_ERR_WORKSPACE", 8: "GP_ERR_UNSUPPORTED"}
 
 # every symbol include/gpupoly.h declares
-EXPORTS = ["gp_net_create", "gp_net_destroy", "gp_add_dense", "gp_add_conv2d", "gp_add_relu", "gp_add_residual",
+EXPORTS = ["gp_net_create", "gp_net_destroy", "gp_add_dense", "gp_add_conv2d", "gp_add_avgpool2d", "gp_add_relu", "gp_add_residual",
            "gp_request_bounds", "gp_set_early_termination", "gp_set_float_inference", "gp_set_graph_replay", "gp_get_term_layer", "gp_get_early_termination_stats",
            "gp_set_stream", "gp_workspace_size", "gp_set_workspace", "gp_analyze",
            "gp_analyze_box", "gp_analyze_batch", "gp_analyze_batch_dev", "gp_get_bounds", "gp_get_bounds_batch",
@@ -49,6 +49,7 @@ def load_library():
     L.gp_net_destroy.restype = None
     L.gp_add_dense.argtypes = [P, i32, i32, fp, fp, ip]
     L.gp_add_conv2d.argtypes = [P] + [i32] * 8 + [fp, fp, ip]
+    L.gp_add_avgpool2d.argtypes = [P] + [i32] * 7 + [ip]
     L.gp_add_relu.argtypes = [P, i32, ip]
     L.gp_add_residual.argtypes = [P, i32, i32, ip]
     L.gp_request_bounds.argtypes = [P, i32]
@@ -132,6 +133,16 @@ class Net:
         lid = C.c_int32(-1)
         self._chk(self._L.gp_add_conv2d(self._h, src, W.shape[0], W.shape[2], W.shape[3], sh, sw, ph, pw, pW, pb,
                                         C.byref(lid)))
+        return lid.value
+
+    def add_avgpool2d(self, src, kernel, stride=None, pad=0) -> int:
+        kh, kw = (kernel, kernel) if np.isscalar(kernel) else kernel
+        if stride is None:
+            stride = (kh, kw)
+        sh, sw = (stride, stride) if np.isscalar(stride) else stride
+        ph, pw = (pad, pad) if np.isscalar(pad) else pad
+        lid = C.c_int32(-1)
+        self._chk(self._L.gp_add_avgpool2d(self._h, src, kh, kw, sh, sw, ph, pw, C.byref(lid)))
         return lid.value
 
     def add_relu(self, src) -> int:

@@ -11,6 +11,12 @@ import torch.nn.functional as F
 import workloads as wl
 
 
+def _avgpool(v, L):
+    """Average pooling with zero padding and the divisor always kh*kw (padding of any size below the window)."""
+    ph, pw = (L["pad"], L["pad"]) if np.isscalar(L["pad"]) else L["pad"]
+    return F.avg_pool2d(F.pad(v, (pw, pw, ph, ph)), L["kernel"], stride=L["stride"], padding=0)
+
+
 def forward(net: wl.Net, X: np.ndarray):
     """Concrete float64 forward pass.  X: [batch, n_in] (CHW-flattened).  Returns {layer id: [batch, n]}."""
     X = torch.as_tensor(np.asarray(X, dtype=np.float64))
@@ -26,7 +32,7 @@ def forward(net: wl.Net, X: np.ndarray):
             v = F.conv2d(vals[L["src"]], torch.as_tensor(L["W"].astype(np.float64)),
                          torch.as_tensor(L["b"].astype(np.float64)), stride=L["stride"], padding=L["pad"])
         elif t == "avgpool":
-            v = F.avg_pool2d(vals[L["src"]], L["kernel"], stride=L["stride"], padding=L["pad"], count_include_pad=True)
+            v = _avgpool(vals[L["src"]], L)
         elif t == "relu":
             v = torch.clamp(vals[L["src"]], min=0.0)
         elif t == "add":
@@ -48,7 +54,7 @@ def affine_matrix(net: wl.Net, lid: int):
     if L["type"] == "dense":
         return L["W"].astype(np.float64), L["b"].astype(np.float64)
     if L["type"] == "avgpool":
-        cols = F.avg_pool2d(eye, L["kernel"], stride=L["stride"], padding=L["pad"], count_include_pad=True)
+        cols = _avgpool(eye, L)
         return cols.reshape(n, -1).T.numpy().copy(), np.zeros(cols[0].numel())
     W = torch.as_tensor(L["W"].astype(np.float64))
     bvec = F.conv2d(zero, W, torch.as_tensor(L["b"].astype(np.float64)), stride=L["stride"], padding=L["pad"])
@@ -287,7 +293,8 @@ def forward_float32(net: wl.Net, x: np.ndarray, order: str, rng) -> dict:
         t = L["type"]
         if t == "avgpool":                           # float32 sum of the window in the given order, then one scaling
             A, _ = affine_matrix(net, i)
-            K = np.float32(L["kernel"] * L["kernel"])
+            k = L["kernel"]
+            K = np.float32(k * k if np.isscalar(k) else k[0] * k[1])
             terms = np.where(A != 0, vals[L["src"]][None, :], np.float32(0)).astype(np.float32)
             s_ = _sum_f32(terms, order, rng)
             vals[i] = (s_ / K).astype(np.float32) if rng.random() < 0.5 else (s_ * (np.float32(1) / K)).astype(np.float32)

@@ -24,6 +24,13 @@ def analysed_layers(net: wl.Net):
             if L["type"] == "relu" or i in feeds or i == len(net.layers)]
 
 
+def affine_read_layers(net: wl.Net):
+    """Layers that an affine layer reads directly (no ReLU in between): the library bounds them too (their intervals
+    enter its rounding slack) and takes candidates there."""
+    return sorted({L["src"] for L in net.layers if L["type"] in ("dense", "conv", "avgpool") and L["src"] > 0
+                   and net.layers[L["src"] - 1]["type"] != "relu"})
+
+
 def make_gpu(net: wl.Net):
     from paper_2007_10868_amd import Net
     g = Net(*net.input_shape)
@@ -56,6 +63,7 @@ def oracle_with_gpu_ties(net: wl.Net, o: OracleNet, g, center, eps, batch_index=
     extra_layers: layers to bound besides the inputs of ReLU layers and the last layer."""
     o.set_ball(center, eps, clip[0], clip[1])
     forced = 0
+    also = affine_read_layers(net)      # marked as requested by make_oracle: candidates are taken there on both sides
     for lid in range(1, o.num_layers):
         L = net.layers[lid - 1]
         if L["type"] == "relu":
@@ -68,7 +76,7 @@ def oracle_with_gpu_ties(net: wl.Net, o: OracleNet, g, center, eps, batch_index=
             else:
                 o.set_lambda_override(lid, None)
             o.analyze_layer(lid)
-        elif lid in analysed_layers(net) or lid in extra_layers:
+        elif lid in analysed_layers(net) or lid in extra_layers or lid in also:
             o.analyze_layer(lid)
     return forced
 
@@ -84,7 +92,7 @@ def oracle_with_gpu_relaxation(net: wl.Net, o: OracleNet, g, center, eps, batch_
             o.set_lambda_override(lid, g.get_relu_lambda(lid, batch_index))
             o.set_gamma_override(lid, g.get_relu_slopes(lid, batch_index).astype(np.float64))
             o.analyze_layer(lid)
-        elif lid in analysed_layers(net):
+        elif lid in analysed_layers(net) or lid in affine_read_layers(net):
             o.analyze_layer(lid)
 
 
@@ -110,7 +118,7 @@ def compare_layer(glo, ghi, olo, ohi, what="", contain_tol=None):
 
 def compare_all(net, g, o, batch_index=0, what="", f64=True, contain_tol=None):
     worst = 0.0
-    for lid in analysed_layers(net):
+    for lid in sorted(set(analysed_layers(net)) | set(affine_read_layers(net))):
         olo, ohi = o.get_bounds(lid)
         glo, ghi = (g.get_bounds_f64 if f64 else g.get_bounds)(lid, batch_index)
         r, _ = compare_layer(glo, ghi, olo, ohi, f"{what} layer {lid}", contain_tol)
@@ -122,7 +130,7 @@ def check_samples_inside(net, g, lo0, hi0, n, rng, batch_index=0, what=""):
     from helpers import forward, sample_box
     X = sample_box(lo0, hi0, n, rng)
     vals = forward(net, X)
-    for lid in analysed_layers(net):
+    for lid in sorted(set(analysed_layers(net)) | set(affine_read_layers(net))):
         glo, ghi = g.get_bounds(lid, batch_index)
         v = vals[lid]
         assert np.all(v.min(0) >= glo.astype(np.float64)), f"{what} layer {lid}: sampled output below the lower bound"
