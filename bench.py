@@ -25,6 +25,7 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=1, help="index into the five synthetic configurations")
+    ap.add_argument("--workload", default="", help="a named workload outside the five configurations (lenet_pool) instead of --config")
     ap.add_argument("--batch", type=int, default=0, help="inputs per pass (default: all inputs of the configuration)")
     ap.add_argument("--calib-copy-mb", type=int, default=0, help="run one plain device copy of this many MiB first (scale for HBM counters)")
     ap.add_argument("--dump", default="", help="write one CSV line per profiled kernel launch to this file")
@@ -49,7 +50,10 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    net = wl.config(args.config)
+    if args.workload:
+        net = {"lenet_pool": wl.lenet_pool}[args.workload]()
+    else:
+        net = wl.config(args.config)
     if args.weight_scale != 1.0:
         net = wl.contracted(net, args.weight_scale)
     if args.eps > 0:
@@ -153,7 +157,7 @@ def main():
 
     # ---- the oracle, as it stands, on the host cores of this machine, on a bounded sample of the workload
     cpu = None
-    n_cpu = args.cpu_sample if args.cpu_sample >= 0 else {0: 10, 1: 10, 2: 10, 3: 1, 4: 0}[args.config]
+    n_cpu = args.cpu_sample if args.cpu_sample >= 0 else (1 if args.workload else {0: 10, 1: 10, 2: 10, 3: 1, 4: 0}[args.config])
     if n_cpu > 0:
         from oracle import OracleNet, oracle_threads
         o = OracleNet(*net.input_shape)

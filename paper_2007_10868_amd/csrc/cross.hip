@@ -1208,20 +1208,24 @@ static void launch_cross_t(const CrossParams& p0, hipStream_t s) {
 // channels (16 bytes each).  The sum of the gathered entries is exact in float64 up to (taps - 1) roundings, the scaling
 // by the rounded reciprocal adds two more: the caller's slack constant for the step covers taps + 8 of them.
 // Epilogue (addend, ReLU substitution, one rounding to float32) as in the other forms.
-// grid: x over (row, pixel) items, 256 >> lg per work-group; y over chunks of 4 << lg channels.
+// A lane works on PX horizontally adjacent window pixels: what depends on the row alone (its position, the window
+// origins, the exact window) is worked out once for them (that integer arithmetic, not the memory system, bounds a
+// lane-per-pixel version).
+// grid: x over (row, window line, group of PX pixels) items, 256 >> lg per work-group; y over chunks of 4 << lg channels.
 template <bool VEC>
-__global__ __launch_bounds__(256) void cross_pool_kernel(const CrossParams p, int lg) {
+__global__ __launch_bounds__(256) void cross_pool_kernel(const CrossParams p, int lg, FastDiv div_nq, FastDiv div_line) {
+    constexpr int PX = 4;
     const int C = p.Co;                                     // channels pass through: p.in.C == p.Co
-    const uint32_t opix = (uint32_t)(p.owy * p.owx);
+    const uint32_t nq = div_nq.d, per_row = div_line.d;     // pixel groups per window line, per row (= owy * nq)
     const uint32_t item = blockIdx.x * (256u >> lg) + (threadIdx.x >> lg);
     const int c0 = (int)((blockIdx.y << lg) + (threadIdx.x & ((1u << lg) - 1u))) * 4;
-    if (item >= (uint32_t)p.nrows * opix || c0 >= C) return;
-    const uint32_t r = fast_div(item, p.div_opix);
-    const uint32_t pix = item - r * opix;
-    const int pa = (int)fast_div(pix, p.div_owx), pb = (int)pix - pa * p.owx;
+    if (item >= (uint32_t)p.nrows * per_row || c0 >= C) return;
+    const uint32_t r = fast_div(item, div_line);
+    const uint32_t rem = item - r * per_row;
+    const int pa = (int)fast_div(rem, div_nq), pb0 = (int)(rem - (uint32_t)pa * nq) * PX;
     const RowInfo ri = row_info(p.rm, (int)r);
     const int A = clampi(p.oSy * ri.ys - p.oPy, 0, p.Ho - p.owy) + pa;
-    const int B = clampi(p.oSx * ri.xs - p.oPx, 0, p.Wo - p.owx) + pb;
+    const int B0 = clampi(p.oSx * ri.xs - p.oPx, 0, p.Wo - p.owx) + pb0;
     // the part of the row's stored window that lies in its exact dependence window (see cross_kernel)
     const int oiy = clampi(p.in.Sy * ri.ys - p.in.Py, 0, p.in.H - p.in.wy), oix = clampi(p.in.Sx * ri.xs - p.in.Px, 0, p.in.W - p.in.wx);
     const int ty = p.in.tSy * ri.ys - p.in.tPy, tx = p.in.tSx * ri.xs - p.in.tPx;
@@ -1229,63 +1233,77 @@ __global__ __launch_bounds__(256) void cross_pool_kernel(const CrossParams p, in
     const int xlo = max(tx, oix), xhi = min(tx + p.in.tWx, oix + p.in.wx);
     const float* const row = p.in.data + (size_t)r * (size_t)(p.in.wy * p.in.wx * C) + c0;
     const int nv = min(4, C - c0);
-    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    const int npx = min(PX, p.owx - pb0);
+    double acc[PX][4];
+#pragma unroll
+    for (int q = 0; q < PX; ++q)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[q][j] = 0.0;
     // tap (f, g) reads the layer-output pixel ((A + ph - f) / sh, (B + pw - g) / sw) when both divisions are exact
     for (int f = 0; f < p.kh; ++f) {
         const int ny = A + p.ph - f;
         if (ny < 0) break;
         const int y = (int)fast_div((uint32_t)ny, p.div_sh);
         if (y * p.sh != ny || y < ylo || y >= yhi) continue;
-        for (int g = 0; g < p.kw; ++g) {
-            const int nx = B + p.pw - g;
-            if (nx < 0) break;
-            const int x = (int)fast_div((uint32_t)nx, p.div_sw);
-            if (x * p.sw != nx || x < xlo || x >= xhi) continue;
-            const float* a = row + (size_t)((y - oiy) * p.in.wx + (x - oix)) * C;
-            if (VEC) {
-                const float4 v = *reinterpret_cast<const float4*>(a);
-                acc[0] += (double)v.x; acc[1] += (double)v.y; acc[2] += (double)v.z; acc[3] += (double)v.w;
-            } else {
+        const float* const line = row + (long long)((y - oiy) * p.in.wx - oix) * C;       // + x * C, x >= oix
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (j < nv) acc[j] += (double)a[j];
+        for (int q = 0; q < PX; ++q) {
+            if (q >= npx) break;
+            for (int g = 0; g < p.kw; ++g) {
+                const int nx = B0 + q + p.pw - g;
+                if (nx < 0) break;
+                const int x = (int)fast_div((uint32_t)nx, p.div_sw);
+                if (x * p.sw != nx || x < xlo || x >= xhi) continue;
+                const float* a = line + (long long)x * C;
+                if (VEC) {
+                    const float4 v = *reinterpret_cast<const float4*>(a);
+                    acc[q][0] += (double)v.x; acc[q][1] += (double)v.y; acc[q][2] += (double)v.z; acc[q][3] += (double)v.w;
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (j < nv) acc[q][j] += (double)a[j];
+                }
             }
         }
     }
-    long long ridx, aoff;
-    epilogue_row_info(p, ri, (int)r, pa, pb, ridx, aoff);
-    float* out = p.out + ((size_t)r * (size_t)opix + (size_t)pix) * C + c0;
-    float res[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        res[j] = 0.f;
-        if (j < nv) {
-            double v = acc[j] * p.pool_scale;
-            if (aoff >= 0) v += (double)p.add.data[aoff + c0 + j];
-            if (p.out_grl) v *= (double)relax_factor(v, p.out_grl[ridx + c0 + j]);
-            res[j] = (float)v;
+    for (int q = 0; q < PX; ++q) {
+        if (q >= npx) break;
+        long long ridx, aoff;
+        epilogue_row_info(p, ri, (int)r, pa, pb0 + q, ridx, aoff);
+        float* out = p.out + ((size_t)r * (size_t)(p.owy * p.owx) + (size_t)(pa * p.owx + pb0 + q)) * C + c0;
+        float res[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            res[j] = 0.f;
+            if (j < nv) {
+                double v = acc[q][j] * p.pool_scale;
+                if (aoff >= 0) v += (double)p.add.data[aoff + c0 + j];
+                if (p.out_grl) v *= (double)relax_factor(v, p.out_grl[ridx + c0 + j]);
+                res[j] = (float)v;
+            }
         }
-    }
-    if (VEC) {
-        *reinterpret_cast<float4*>(out) = make_float4(res[0], res[1], res[2], res[3]);
-    } else {
+        if (VEC) {
+            *reinterpret_cast<float4*>(out) = make_float4(res[0], res[1], res[2], res[3]);
+        } else {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (j < nv) out[j] = res[j];
+            for (int j = 0; j < 4; ++j)
+                if (j < nv) out[j] = res[j];
+        }
     }
 }
 
-static void launch_cross_pool(const CrossParams& p0, hipStream_t s) {
-    CrossParams p = p0;
+static void launch_cross_pool(const CrossParams& p, hipStream_t s) {
     const int cg = (p.Co + 3) / 4;                          // groups of 4 channels
     int lg = 0;
     while ((1 << lg) < cg && lg < 6) ++lg;
-    p.div_opix = make_fastdiv((uint32_t)(p.owy * p.owx));
-    const long long items = (long long)p.nrows * p.owy * p.owx;            // < 2^31 (checked by the caller)
+    const int nq = (p.owx + 3) / 4;
+    const long long items = (long long)p.nrows * p.owy * nq;               // < 2^31: rows * window pixels is
     const int per_wg = 256 >> lg;
     const dim3 grid((unsigned)((items + per_wg - 1) / per_wg), (unsigned)((cg + (1 << lg) - 1) >> lg));
-    if ((p.Co & 3) == 0) hipLaunchKernelGGL((cross_pool_kernel<true>), grid, dim3(256), 0, s, p, lg);
-    else hipLaunchKernelGGL((cross_pool_kernel<false>), grid, dim3(256), 0, s, p, lg);
+    const FastDiv div_nq = make_fastdiv((uint32_t)nq), div_line = make_fastdiv((uint32_t)(p.owy * nq));
+    if ((p.Co & 3) == 0) hipLaunchKernelGGL((cross_pool_kernel<true>), grid, dim3(256), 0, s, p, lg, div_nq, div_line);
+    else hipLaunchKernelGGL((cross_pool_kernel<false>), grid, dim3(256), 0, s, p, lg, div_nq, div_line);
 }
 
 void launch_cross(const CrossParams& p, hipStream_t s) {

@@ -247,6 +247,14 @@ def config(i: int) -> Net:
     raise ValueError(i)
 
 
+def lenet_pool() -> Net:
+    """Not one of the five configurations: a CIFAR-sized LeNet-family network with average pooling as sub-sampling
+    (conv5x5-32, ReLU, 2x2 average, conv5x5-64, ReLU, 2x2 average, dense 512, ReLU, dense 10), the workload the
+    pooling step of the library is measured on."""
+    return pool_net("lenet_pool", (3, 32, 32), [("conv", 32, 5, 1, 2), ("pool", 2, 2, 0), ("conv", 64, 5, 1, 2), ("pool", 2, 2, 0)],
+                    [512], n_out=10, seed=1100, eps=1.0 / 255.0, n_inputs=20, input_seed_base=2900)
+
+
 def contracted(net: Net, weight_scale: float) -> Net:
     """The same network with every weight matrix / filter multiplied by `weight_scale` (biases kept).  With random
     He-normal weights the interval widths grow from layer to layer and every ReLU is unstable after the first few;
