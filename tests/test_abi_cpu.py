@@ -67,6 +67,36 @@ def test_window_recurrence_with_stride_and_padding():
     assert plan[-1]["channels"] == 3
 
 
+def test_average_pooling_plans_like_a_convolution_with_the_same_window():
+    """The dependence window of a row grows through a pooling layer as through a convolution (eq. 4: W' = (W-1)*s + f;
+    eq. 9: S' = s*S), channels pass through, and rows of a pooling layer itself start from a one-hot block."""
+    net = wl.pool_net("p", (3, 32, 32), [("conv", 8, 3, 1, 1), ("pool", 2, 2, 0), ("conv", 16, 3, 1, 0), ("pool", 3, 2, 1)],
+                      [20], n_out=5, seed=0)
+    g = Net(*net.input_shape)
+    wl.build_into(net, g)
+    assert [g.layer_size(i) for i in (3, 6)] == [8 * 16 * 16, 16 * 7 * 7]
+    plan = [p for p in g.debug_plan(6) if p["kind"] in (0, 1)]           # rows of the second pooling layer
+    assert (plan[0]["layer"], plan[0]["window_h"], plan[0]["channels"]) == (6, 1, 16)
+    W, S = 1, 1
+    expect = []
+    for lid in (6, 4, 3, 1):
+        L = net.layers[lid - 1]
+        k = L["kernel"] if L["type"] == "avgpool" else L["W"].shape[2]
+        W, S = (W - 1) * L["stride"] + k, S * L["stride"]
+        expect.append((lid, W, S, net.shape_of(L["src"])[0]))
+    got = [(p["layer"], p["window_h"], p["acc_stride_h"], p["channels"]) for p in plan[1:]]
+    assert got == expect == [(6, 3, 2, 16), (4, 5, 2, 8), (3, 10, 4, 8), (1, 12, 4, 3)]
+    with pytest.raises(GpuPolyError) as e:
+        g.add_avgpool2d(7, 2)                               # layer 7 is 20x1x1: window larger than the input
+    assert e.value.status == 2
+    with pytest.raises(GpuPolyError) as e:
+        g.add_avgpool2d(2, 2, 1, 2)                         # padding as large as the window
+    assert e.value.status == 2
+    with pytest.raises(GpuPolyError) as e:
+        g.add_avgpool2d(2, 0)
+    assert e.value.status == 1
+
+
 def test_residual_plan_merges_branches():
     net = wl.scaled_resnet(8, 16)
     g = Net(*net.input_shape)
