@@ -1011,7 +1011,7 @@ static void launch_cross_image(const CrossParams& p0, hipStream_t s) {
     else hipLaunchKernelGGL((cross_image_kernel<false>), grid, dim3(256), 0, s, p);
 }
 
-// Image layers behind a stride-1 layer with a long K per pixel (3x3 filters over 32 or 64 channels).  With 4 output
+// Image layers behind a stride-1 layer with a long K per pixel (3x3 or 5x5 filters over 32 or 64 channels).  With 4 output
 // columns a block value feeds only 4 multiply-adds per use, and in the kernels above every output pixel re-loads the
 // values under its taps: those steps run at the speed of the vector L1 (64 B/clk), not of the matrix pipe.  Here one
 // wave computes a STRIP of P horizontally adjacent output pixels for its 32 rows: a block value (one 16-byte load per
@@ -1162,7 +1162,8 @@ __global__ __launch_bounds__(256) void cross_strip_kernel(const CrossParams p) {
 // of 32 consecutive rows is one position of the start layer in one box)
 static bool strip_applies(const CrossParams& p, size_t& lds) {
     lds = (size_t)p.kh * p.kw * 4 * (p.in.C + 2) * sizeof(double);
-    return p.Co <= 4 && p.wt64 && p.sh == 1 && p.sw == 1 && p.kw == 3 && (p.in.C & 15) == 0 && lds <= 24576 &&
+    const bool fits = (p.kw == 3 && lds <= 24576) || (p.kw == 5 && lds <= 32768);     // filter rows of 3 or 5 taps
+    return p.Co <= 4 && p.wt64 && p.sh == 1 && p.sw == 1 && fits && (p.in.C & 15) == 0 &&
            p.rm.rowid == nullptr && (p.rm.Cs & 31) == 0 && (p.rm.row0 & 31) == 0 && (p.rm.Rc & 31) == 0 && p.owx >= 4;
 }
 
@@ -1174,7 +1175,8 @@ static void launch_cross_strip(const CrossParams& p0, size_t lds, hipStream_t s)
     p.div_opix = make_fastdiv((uint32_t)(p.owy * nstrips));
     const long long total = (long long)p.ntiles_m * p.owy * nstrips;
     const unsigned blocks = (unsigned)(((total + 7) / 8) * 8);
-    hipLaunchKernelGGL((cross_strip_kernel<P, 3>), dim3(blocks), dim3(256), lds, s, p);
+    if (p.kw == 3) hipLaunchKernelGGL((cross_strip_kernel<P, 3>), dim3(blocks), dim3(256), lds, s, p);
+    else hipLaunchKernelGGL((cross_strip_kernel<P, 5>), dim3(blocks), dim3(256), lds, s, p);
 }
 
 template <int BM, int BN>

@@ -59,6 +59,11 @@ def strip_conv(seed=0):
     return wl.conv_net("strip_conv", (3, 7, 11), [(32, 3, 1, 1), (16, 3, 1, 1), (32, 3, 1, 0)], [12], n_out=4, seed=seed)
 
 
+def strip5_conv(seed=0):
+    """The same with 5x5 filters (the other filter width the strip kernel is built for)."""
+    return wl.conv_net("strip5_conv", (3, 9, 13), [(32, 5, 1, 2), (16, 5, 1, 2), (32, 5, 1, 0)], [12], n_out=4, seed=seed)
+
+
 def rect_conv(seed=0):
     """Rectangular image, kh != kw, stride_h != stride_w, pad_h != pad_w."""
     rng = np.random.default_rng(seed)
@@ -127,7 +132,7 @@ def test_mfma_f64_error_model(cols):
 
 
 @pytest.mark.parametrize("maker,eps", [(tiny_fc, 0.1), (odd_fc, 0.05), (quad_fc, 0.03), (tiny_conv, 0.05), (pad0_conv, 0.03),
-                                       (tiny_resnet, 0.02), (mid_resnet, 0.01), (rect_conv, 0.04), (strip_conv, 0.004)])
+                                       (tiny_resnet, 0.02), (mid_resnet, 0.01), (rect_conv, 0.04), (strip_conv, 0.004), (strip5_conv, 0.002)])
 def test_small_networks_match_oracle_and_contain_samples(maker, eps):
     net = maker(1)
     rng = np.random.default_rng(5)
@@ -240,7 +245,7 @@ def test_config2_small_conv():
     print("conv_small worst looseness / allowed =", worst)
 
 
-@pytest.mark.parametrize("make, rows", [(mid_resnet, 37), (strip_conv, 37), (strip_conv, 200)])
+@pytest.mark.parametrize("make, rows", [(mid_resnet, 37), (strip_conv, 37), (strip_conv, 200), (strip5_conv, 37), (strip5_conv, 200)])
 def test_row_chunking_gives_identical_bounds(make, rows):
     """A workspace that holds only a few rows forces the chunked path (Section 4.2, memory management).  Which
     crossing kernel a chunk gets may depend on how its rows are aligned; the bounds may not."""
