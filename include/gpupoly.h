@@ -103,6 +103,13 @@ gp_status gp_set_graph_replay(gp_net* net, int32_t on);
  * interval is moved outward by 2^-24*|end| (so sum layers always get bounds in this mode).  Takes effect at the
  * next analysis.  The bounds of gp_certify and gp_bound_outputs then speak about the float32 outputs. */
 gp_status gp_set_float_inference(gp_net* net, int32_t on);
+/* Precision of the stored coefficients (the paper evaluates a single and a double precision build, Section 5); 32
+ * (default) or 64.  With 32 every new coefficient of a row's block is rounded once to float32 and the rounding is
+ * paid into the row's slack; with 64 the blocks hold float64 values: twice the memory and traffic, only the general
+ * crossing kernel, and bounds whose distance to exact arithmetic is of the order 1e-12 relative instead of 1e-6 (the
+ * weights stay the float32 values handed over; the relaxation slopes stay float32 values, any slope is sound).
+ * Takes effect at the next analysis. */
+gp_status gp_set_coefficient_storage(gp_net* net, int32_t bits);
 /* After an analysis with early termination: for each neuron of a layer that has bounds, the id of the layer its
  * expression ranged over when it stopped; layer_id itself = never back-substituted, 0 = substituted down to the
  * input.  term: [n_layer]. */

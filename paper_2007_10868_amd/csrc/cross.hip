@@ -60,8 +60,12 @@ __device__ __forceinline__ void epilogue_row_info(const CrossParams& p, const Ro
 // DENSE: the layer is a plain matrix (one tap, 1x1 windows): no tap geometry is kept, which leaves the registers for
 // the software-pipelined K loop at 4 waves per SIMD without spilling.  The general 64x64 kernel is held to 4 waves per
 // SIMD as well (a few values of the tap bookkeeping spill; measured: +3.4 % on the residual net against 3 waves).
-template <int BM, int BN, bool VEC, bool DENSE>
+// CT: storage type of the coefficient blocks (float; double for the float64 storage mode, which only this form and
+// cross_pool_kernel serve: 32 bytes per 4 channels, no conversion, no rounding but the final one to float64).
+template <int BM, int BN, bool VEC, bool DENSE, typename CT = float>
 __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_kernel(const CrossParams p) {
+    constexpr bool A64 = std::is_same<CT, double>::value;
+    constexpr uint32_t CS = sizeof(CT);
     constexpr int BK = 16;
     constexpr int LDK = 18;                          // doubles per tile row: 144 B, keeps 16-byte alignment, spreads banks
     constexpr int WAVES_N = (BN >= 64 || BM < 64) ? 2 : 1;
@@ -107,7 +111,7 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
     // ---- buffer resources: A covers the rows of this tile only (32-bit offsets), B the layer's filter
     const int rows_here = min(BM, p.nrows - r_tile);
     const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)(p.in.data + (size_t)r_tile * row_elems), 0, (int)((uint32_t)rows_here * row_elems * 4u), 0x00020000);
+        (void*)(reinterpret_cast<const CT*>(p.in.data) + (size_t)r_tile * row_elems), 0, (int)((uint32_t)rows_here * row_elems * CS), 0x00020000);
     const __amdgpu_buffer_rsrc_t rsrcB =
         __builtin_amdgcn_make_buffer_rsrc((void*)p.wt, 0, (int)((uint32_t)taps * N * Ck * 4u), 0x00020000);
 
@@ -145,7 +149,7 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
     for (int i = 0; i < APT; ++i) {
         const int rl = ld_row + 64 * i;
         a_ok[i] = rl < rows_here;
-        a_rowoff[i] = ((uint32_t)rl * row_elems + (uint32_t)q4) * 4u;
+        a_rowoff[i] = ((uint32_t)rl * row_elems + (uint32_t)q4) * CS;
         a_ydiv[i] = a_xdiv[i] = a_ymod[i] = a_xmod[i] = a_oiy[i] = a_oix[i] = 0;
         a_ty[i] = a_tx[i] = 0;
         if (uni) continue;
@@ -198,7 +202,7 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
                             (unsigned)y < (unsigned)p.in.H && (unsigned)x < (unsigned)p.in.W &&
                             (unsigned)(yi - (int)(a_ty[i] & 0xffffu)) < (a_ty[i] >> 16) &&
                             (unsigned)(xi - (int)(a_tx[i] & 0xffffu)) < (a_tx[i] >> 16);
-            a_voff[i] = ok ? a_rowoff[i] + (uint32_t)(yi * p.in.wx + xi) * (uint32_t)(Ck * 4) : kOOB;
+            a_voff[i] = ok ? a_rowoff[i] + (uint32_t)(yi * p.in.wx + xi) * ((uint32_t)Ck * CS) : kOOB;
             any = any || ok;
         }
         return any;
@@ -246,7 +250,7 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
         if (uni) {
             int poff;
             if (tap_uniform(t, poff)) {      // (filters with more than 64 taps visit all: a tap that misses reads nothing)
-                s_tapoff = (uint32_t)poff * 4u;
+                s_tapoff = (uint32_t)poff * CS;
 #pragma unroll
                 for (int i = 0; i < APT; ++i) a_voff[i] = a_ok[i] ? a_rowoff[i] : kOOB;
             } else {
@@ -266,16 +270,28 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
     // Per K step the loads cost no vector instruction: per-thread offsets are fixed within a tap and the
     // channel advance goes through the scalar offset operand of the buffer load.
     F4 a_raw[APT], b_raw[BPT];
+    double a_raw64[A64 ? APT : 1][4];
+    auto a_val = [&](int i, int j) -> double {
+        if constexpr (A64) return a_raw64[i][j];
+        else return (double)a_raw[i].v[j];
+    };
     auto load_tiles = [&]() {
         const int rem = Ck - ld_d0;                                 // channels left in this tap (uniform)
-        const uint32_t soffA = s_tapoff + (uint32_t)ld_d0 * 4u;
+        const uint32_t soffA = s_tapoff + (uint32_t)ld_d0 * CS;
         const uint32_t soffB = ((uint32_t)ld_t * (uint32_t)N * (uint32_t)Ck + (uint32_t)ld_d0) * 4u;
         if (VEC && rem >= BK) {
 #pragma unroll
             for (int i = 0; i < APT; ++i) {
-                uint4_t v = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, (int)a_voff[i], (int)soffA, 0);
-                a_raw[i].v[0] = __uint_as_float(v.x); a_raw[i].v[1] = __uint_as_float(v.y);
-                a_raw[i].v[2] = __uint_as_float(v.z); a_raw[i].v[3] = __uint_as_float(v.w);
+                if constexpr (A64) {        // (kOOB + 16 is still beyond every range)
+                    const uint4_t v0 = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, (int)a_voff[i], (int)soffA, 0);
+                    const uint4_t v1 = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, (int)(a_voff[i] + 16u), (int)soffA, 0);
+                    a_raw64[i][0] = __hiloint2double((int)v0.y, (int)v0.x); a_raw64[i][1] = __hiloint2double((int)v0.w, (int)v0.z);
+                    a_raw64[i][2] = __hiloint2double((int)v1.y, (int)v1.x); a_raw64[i][3] = __hiloint2double((int)v1.w, (int)v1.z);
+                } else {
+                    uint4_t v = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, (int)a_voff[i], (int)soffA, 0);
+                    a_raw[i].v[0] = __uint_as_float(v.x); a_raw[i].v[1] = __uint_as_float(v.y);
+                    a_raw[i].v[2] = __uint_as_float(v.z); a_raw[i].v[3] = __uint_as_float(v.w);
+                }
             }
 #pragma unroll
             for (int i = 0; i < BPT; ++i) {
@@ -286,8 +302,11 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
         } else {                                                    // ragged last chunk of a tap, or unaligned channels
             const bool dok = q4 < rem;
 #pragma unroll
-            for (int i = 0; i < APT; ++i)
-                a_raw[i] = buf_ld4<VEC>(rsrcA, (dok && a_voff[i] != kOOB) ? a_voff[i] + soffA : kOOB, rem - q4);
+            for (int i = 0; i < APT; ++i) {
+                const uint32_t off = (dok && a_voff[i] != kOOB) ? a_voff[i] + soffA : kOOB;
+                if constexpr (A64) buf_ld4_f64<VEC>(rsrcA, off, rem - q4, a_raw64[i]);
+                else a_raw[i] = buf_ld4<VEC>(rsrcA, off, rem - q4);
+            }
 #pragma unroll
             for (int i = 0; i < BPT; ++i)
                 b_raw[i] = buf_ld4<VEC>(rsrcB, (dok && b_voff[i] != kOOB) ? b_voff[i] + soffB : kOOB, rem - q4);
@@ -318,7 +337,7 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
                     if (ld_row + 64 * i < BM) {
                         double* dst = &As[0][ld_row][0] + (buf * BM + 64 * i) * LDK + q;
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) dst[4 * j] = (double)a_raw[i].v[j];
+                        for (int j = 0; j < 4; ++j) dst[4 * j] = a_val(i, j);
                     }
                 }
 #pragma unroll
@@ -336,8 +355,8 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
         for (int i = 0; i < APT; ++i) {
             if (ld_row + 64 * i < BM) {
                 double2* dst = reinterpret_cast<double2*>(a_st + (buf * BM + 64 * i) * LDK);
-                dst[0] = make_double2((double)a_raw[i].v[0], (double)a_raw[i].v[1]);
-                dst[1] = make_double2((double)a_raw[i].v[2], (double)a_raw[i].v[3]);
+                dst[0] = make_double2(a_val(i, 0), a_val(i, 1));
+                dst[1] = make_double2(a_val(i, 2), a_val(i, 3));
             }
         }
 #pragma unroll
@@ -487,8 +506,8 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
             if (r >= p.nrows) continue;
             const long long ridx = uni ? u_ridx : s_ridx[rl];
             const long long aoff = !has_add ? -1 : !uni ? s_aoff[rl] : u_aoff < 0 ? -1 : (long long)r * u_astride + u_aoff;
-            const float* add_src = aoff >= 0 ? p.add.data + aoff : nullptr;
-            float* out_row = p.out + ((size_t)r * opix + pix) * N;
+            const CT* add_src = aoff >= 0 ? reinterpret_cast<const CT*>(p.add.data) + aoff : nullptr;
+            CT* out_row = reinterpret_cast<CT*>(p.out) + ((size_t)r * opix + pix) * N;
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const int n = n0 + wn * WTN + j * 16 + lm;
@@ -496,7 +515,7 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
                 double v = acc[i][j][r4];
                 if (add_src) v += (double)add_src[n];
                 if (p.out_grl) v *= (double)relax_factor(v, same_box ? g_same[j] : p.out_grl[ridx + n]);
-                out_row[n] = (float)v;
+                out_row[n] = (CT)v;
             }
         }
     }
@@ -1214,7 +1233,7 @@ static void launch_cross_t(const CrossParams& p0, hipStream_t s) {
 // origins, the exact window) is worked out once for them (that integer arithmetic, not the memory system, bounds a
 // lane-per-pixel version).
 // grid: x over (row, window line, group of PX pixels) items, 256 >> lg per work-group; y over chunks of 4 << lg channels.
-template <bool VEC>
+template <bool VEC, typename CT>
 __global__ __launch_bounds__(256) void cross_pool_kernel(const CrossParams p, int lg, FastDiv div_nq, FastDiv div_line) {
     constexpr int PX = 4;
     const int C = p.Co;                                     // channels pass through: p.in.C == p.Co
@@ -1233,7 +1252,7 @@ __global__ __launch_bounds__(256) void cross_pool_kernel(const CrossParams p, in
     const int ty = p.in.tSy * ri.ys - p.in.tPy, tx = p.in.tSx * ri.xs - p.in.tPx;
     const int ylo = max(ty, oiy), yhi = min(ty + p.in.tWy, oiy + p.in.wy);
     const int xlo = max(tx, oix), xhi = min(tx + p.in.tWx, oix + p.in.wx);
-    const float* const row = p.in.data + (size_t)r * (size_t)(p.in.wy * p.in.wx * C) + c0;
+    const CT* const row = reinterpret_cast<const CT*>(p.in.data) + (size_t)r * (size_t)(p.in.wy * p.in.wx * C) + c0;
     const int nv = min(4, C - c0);
     const int npx = min(PX, p.owx - pb0);
     double acc[PX][4];
@@ -1247,7 +1266,7 @@ __global__ __launch_bounds__(256) void cross_pool_kernel(const CrossParams p, in
         if (ny < 0) break;
         const int y = (int)fast_div((uint32_t)ny, p.div_sh);
         if (y * p.sh != ny || y < ylo || y >= yhi) continue;
-        const float* const line = row + (long long)((y - oiy) * p.in.wx - oix) * C;       // + x * C, x >= oix
+        const CT* const line = row + (long long)((y - oiy) * p.in.wx - oix) * C;          // + x * C, x >= oix
 #pragma unroll
         for (int q = 0; q < PX; ++q) {
             if (q >= npx) break;
@@ -1256,10 +1275,13 @@ __global__ __launch_bounds__(256) void cross_pool_kernel(const CrossParams p, in
                 if (nx < 0) break;
                 const int x = (int)fast_div((uint32_t)nx, p.div_sw);
                 if (x * p.sw != nx || x < xlo || x >= xhi) continue;
-                const float* a = line + (long long)x * C;
-                if (VEC) {
+                const CT* a = line + (long long)x * C;
+                if (VEC && std::is_same<CT, float>::value) {
                     const float4 v = *reinterpret_cast<const float4*>(a);
                     acc[q][0] += (double)v.x; acc[q][1] += (double)v.y; acc[q][2] += (double)v.z; acc[q][3] += (double)v.w;
+                } else if (VEC) {
+                    const double2 v0 = reinterpret_cast<const double2*>(a)[0], v1 = reinterpret_cast<const double2*>(a)[1];
+                    acc[q][0] += v0.x; acc[q][1] += v0.y; acc[q][2] += v1.x; acc[q][3] += v1.y;
                 } else {
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
@@ -1273,20 +1295,23 @@ __global__ __launch_bounds__(256) void cross_pool_kernel(const CrossParams p, in
         if (q >= npx) break;
         long long ridx, aoff;
         epilogue_row_info(p, ri, (int)r, pa, pb0 + q, ridx, aoff);
-        float* out = p.out + ((size_t)r * (size_t)(p.owy * p.owx) + (size_t)(pa * p.owx + pb0 + q)) * C + c0;
-        float res[4];
+        CT* out = reinterpret_cast<CT*>(p.out) + ((size_t)r * (size_t)(p.owy * p.owx) + (size_t)(pa * p.owx + pb0 + q)) * C + c0;
+        CT res[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             res[j] = 0.f;
             if (j < nv) {
                 double v = acc[q][j] * p.pool_scale;
-                if (aoff >= 0) v += (double)p.add.data[aoff + c0 + j];
+                if (aoff >= 0) v += (double)reinterpret_cast<const CT*>(p.add.data)[aoff + c0 + j];
                 if (p.out_grl) v *= (double)relax_factor(v, p.out_grl[ridx + c0 + j]);
-                res[j] = (float)v;
+                res[j] = (CT)v;
             }
         }
-        if (VEC) {
-            *reinterpret_cast<float4*>(out) = make_float4(res[0], res[1], res[2], res[3]);
+        if (VEC && std::is_same<CT, float>::value) {
+            *reinterpret_cast<float4*>(out) = make_float4((float)res[0], (float)res[1], (float)res[2], (float)res[3]);
+        } else if (VEC) {
+            reinterpret_cast<double2*>(out)[0] = make_double2((double)res[0], (double)res[1]);
+            reinterpret_cast<double2*>(out)[1] = make_double2((double)res[2], (double)res[3]);
         } else {
 #pragma unroll
             for (int j = 0; j < 4; ++j)
@@ -1304,13 +1329,34 @@ static void launch_cross_pool(const CrossParams& p, hipStream_t s) {
     const int per_wg = 256 >> lg;
     const dim3 grid((unsigned)((items + per_wg - 1) / per_wg), (unsigned)((cg + (1 << lg) - 1) >> lg));
     const FastDiv div_nq = make_fastdiv((uint32_t)nq), div_line = make_fastdiv((uint32_t)(p.owy * nq));
-    if ((p.Co & 3) == 0) hipLaunchKernelGGL((cross_pool_kernel<true>), grid, dim3(256), 0, s, p, lg, div_nq, div_line);
-    else hipLaunchKernelGGL((cross_pool_kernel<false>), grid, dim3(256), 0, s, p, lg, div_nq, div_line);
+    const bool vec = (p.Co & 3) == 0;
+    if (p.coef64) {
+        if (vec) hipLaunchKernelGGL((cross_pool_kernel<true, double>), grid, dim3(256), 0, s, p, lg, div_nq, div_line);
+        else hipLaunchKernelGGL((cross_pool_kernel<false, double>), grid, dim3(256), 0, s, p, lg, div_nq, div_line);
+    } else {
+        if (vec) hipLaunchKernelGGL((cross_pool_kernel<true, float>), grid, dim3(256), 0, s, p, lg, div_nq, div_line);
+        else hipLaunchKernelGGL((cross_pool_kernel<false, float>), grid, dim3(256), 0, s, p, lg, div_nq, div_line);
+    }
+}
+
+// float64 storage: the general LDS-tiled form for every layer
+static void launch_cross_f64(const CrossParams& p0, hipStream_t s) {
+    constexpr int BM = 64, BN = 64;
+    CrossParams p = p0;
+    p.ntiles_m = (p.nrows + BM - 1) / BM;
+    p.ntiles_n = (p.Co + BN - 1) / BN;
+    p.div_ntiles_n = make_fastdiv((uint32_t)p.ntiles_n);
+    p.div_opix = make_fastdiv((uint32_t)(p.owy * p.owx));
+    const long long total = (long long)p.ntiles_m * p.ntiles_n * p.owy * p.owx;
+    const unsigned blocks = (unsigned)(((total + 7) / 8) * 8);
+    if ((p.in.C & 3) == 0) hipLaunchKernelGGL((cross_kernel<BM, BN, true, false, double>), dim3(blocks), dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((cross_kernel<BM, BN, false, false, double>), dim3(blocks), dim3(256), 0, s, p);
 }
 
 void launch_cross(const CrossParams& p, hipStream_t s) {
     if (p.nrows <= 0 || p.Co <= 0) return;
     if (p.pool_scale != 0.0) { launch_cross_pool(p, s); return; }
+    if (p.coef64) { launch_cross_f64(p, s); return; }
     const int N = p.Co;
     // tile shapes measured on MI355X: 64x64 beats the larger tiles (their lower occupancy costs more than their
     // higher arithmetic intensity gains); narrow layers take a tall tile so that fewer MFMA columns are padding

@@ -84,6 +84,25 @@ __device__ __forceinline__ F4 buf_ld4(__amdgpu_buffer_rsrc_t rsrc, uint32_t off,
     return r;
 }
 
+// the same for float64 storage (32 bytes): r receives the 4 values
+typedef unsigned int uint2_t __attribute__((ext_vector_type(2)));
+template <bool VEC>
+__device__ __forceinline__ void buf_ld4_f64(__amdgpu_buffer_rsrc_t rsrc, uint32_t off, int nvalid, double (&r)[4]) {
+    if (VEC) {
+        const uint4_t v0 = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off, 0, 0);
+        const uint4_t v1 = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)(off == kOOB ? kOOB : off + 16u), 0, 0);
+        r[0] = __hiloint2double((int)v0.y, (int)v0.x); r[1] = __hiloint2double((int)v0.w, (int)v0.z);
+        r[2] = __hiloint2double((int)v1.y, (int)v1.x); r[3] = __hiloint2double((int)v1.w, (int)v1.z);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t o = (j < nvalid && off != kOOB) ? off + 8u * j : kOOB;
+            const uint2_t v = __builtin_amdgcn_raw_buffer_load_b64(rsrc, (int)o, 0, 0);
+            r[j] = __hiloint2double((int)v.y, (int)v.x);
+        }
+    }
+}
+
 // ReLU relaxation of one neuron packed in one float: |g| is the slope of the upper line, the sign bit
 // is set when the lower line is 0 (lam = 0) and clear when it is x (lam = 1).
 // A coefficient a over relu(x) becomes a * relax_factor(a, g) over x (Section 2: positive coefficients

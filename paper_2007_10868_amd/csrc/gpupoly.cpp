@@ -82,6 +82,7 @@ struct Plan {
 };
 
 const double kRoundCoef = 0x1p-24 * (1.0 + 0x1p-20);   // float32 rounding of a float64 value
+const double kRoundCoef64 = 0x1p-53 * (1.0 + 0x1p-20); // rounding of a product or sum of two float64 values (float64 storage)
 const int kMaxSlots = 6;
 
 }  // namespace
@@ -124,6 +125,7 @@ struct gp_net {
     struct GraphKey { int batch; const float* centers; float eps, clo, chi; void* ws; long long ws_bytes; hipStream_t stream; };
     GraphKey graph_key = {};
     bool float_inference = false;  // bounds also hold for every float32 evaluation order of the network (Section 4.1)
+    bool coef64 = false;           // coefficient blocks are stored in float64 (the paper's double precision build, Section 5)
     int* d_count = nullptr;
     int* h_count = nullptr;        // pinned: task counts read back while the GPU keeps working
     hipEvent_t count_ev = nullptr;
@@ -577,11 +579,11 @@ gp_status ensure_device(gp_net* net, int batch) {
 long long align_up(long long v, long long a) { return (v + a - 1) / a * a; }
 
 // bytes one task (both signs) needs for this plan
-long long task_bytes(const Plan& pl, int nsign) {
+long long task_bytes(const Plan& pl, int nsign, int csize) {
     // blocks; constant, slack (twice: rows are moved when tasks are removed), best; row lists and flags; chunk sums of
     // the scan of long rows (5 doubles per 512 coefficients)
     const long long chunks = pl.slot_elems > 1024 ? (pl.slot_elems + 511) / 512 : 0;
-    return (long long)nsign * (pl.n_slots * align_up(pl.slot_elems * 4, 16) + 5 * 8 + chunks * 40) + 16;
+    return (long long)nsign * (pl.n_slots * align_up(pl.slot_elems * csize, 16) + 5 * 8 + chunks * 40) + 16;
 }
 
 gp_status get_workspace(gp_net* net, long long want, char** ws, long long* bytes) {
@@ -639,7 +641,8 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
     if (total <= 0) return GP_OK;
     const bool early = net->early && !certify;
     const bool may_stop = early && ls.feeds_relu && !ls.req_bounds && start != (int)net->L.size() - 1;
-    const long long tb = task_bytes(pl, nsign);
+    const int csize = net->coef64 ? 8 : 4;              // bytes per stored coefficient
+    const long long tb = task_bytes(pl, nsign, csize);
     char* ws; long long ws_bytes;
     gp_status st = get_workspace(net, tb * total + 16384, &ws, &ws_bytes);
     if (st != GP_OK) return st;
@@ -670,7 +673,7 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
     const long long chunks_max = pl.slot_elems > 1024 ? (pl.slot_elems + 511) / 512 : 0;
     double* d_partial = (double*)(ws + align_up((d_done[1] + Rc_max) - (unsigned char*)ws, 256));
     char* slots0 = (char*)d_partial + align_up(nrows_max * chunks_max * 40, 256);
-    const long long slot_bytes = align_up(nrows_max * pl.slot_elems * 4, 256);
+    const long long slot_bytes = align_up(nrows_max * pl.slot_elems * csize, 256);
     if (slots0 + slot_bytes * pl.n_slots > ws + ws_bytes) return fail(net, GP_ERR_WORKSPACE, "workspace layout overflow");
 
     // per row: arithmetic of the crossings that follow each op of the plan
@@ -762,7 +765,8 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                 const int other = (slot + 1) % pl.n_slots;      // every other block is dead at a candidate
                 gp::CopyRowsParams cr;
                 cr.src = slot_ptr(slot); cr.dst = slot_ptr(other); cr.sel = d_sel;
-                cr.Ra_old = rm.Rc; cr.Ra_new = kept; cr.nsign = nsign; cr.nelem = (int)nelem;
+                cr.Ra_old = rm.Rc; cr.Ra_new = kept; cr.nsign = nsign;
+                cr.nelem = (int)nelem * (csize / 4);        // rows are copied as 4-byte words
                 gp::launch_copy_rows(cr, net->stream);
                 std::swap(phys[slot], phys[other]);
             }
@@ -812,6 +816,7 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                 }
                 ip.c = d_c; ip.err = d_err; ip.best = d_best;
                 ip.seeded = early ? 1 : 0;
+                ip.coef64 = net->coef64 ? 1 : 0;
                 gp::launch_init(ip, net->stream);
                 have_rows = true;
             } else if (op.kind == PlanOp::SCAN) {
@@ -844,7 +849,11 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                     if (i == 0) { sp.e1_a = e1; sp.xmax_a = net->L[q.a].d_xmax; }
                     else { sp.e1_b = e1; sp.xmax_b = net->L[q.a].d_xmax; }
                 }
-                sp.round_coef = op.rounded ? kRoundCoef : 0.0;
+                sp.round_coef = op.rounded ? (net->coef64 ? kRoundCoef64 : kRoundCoef) : 0.0;
+                sp.coef64 = net->coef64 ? 1 : 0;
+                // what vanishes when a coefficient is stored: below the subnormal step of the storage type, times the
+                // 2^20 by which a substituted ReLU slope (kept >= 2^-20) may have shrunk it
+                sp.coef_floor = net->coef64 ? 0x1p-1050 : 0x1p-128;
                 sp.do_consts = op.do_consts ? 1 : 0;
                 sp.update_best = op.update_best ? 1 : 0;
                 sp.c = d_c; sp.err = d_err; sp.best = d_best;
@@ -854,7 +863,7 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                 gp::launch_scan(sp, net->stream);
                 prof_mark(net, 1, true);
                 if (net->prof_on) {
-                    net->prof_bytes[1] += 4.0 * nrows * (double)block_elems(op.g_in, l);
+                    net->prof_bytes[1] += (double)csize * nrows * (double)block_elems(op.g_in, l);
                     net->prof_recs[1].push_back({1, start, op.layer_in, nrows, (int)block_elems(op.g_in, l), 0, l.C, 0, 0.0});
                 }
                 // a candidate over a hidden layer has just been folded into best: re-evaluate the criterion
@@ -871,6 +880,7 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                 cp.wt = a.d_wt;
                 cp.wt64 = a.d_wt64;
                 cp.pool_scale = pool_scale(a);
+                cp.coef64 = net->coef64 ? 1 : 0;
                 cp.kh = a.kh; cp.kw = a.kw; cp.sh = a.sh; cp.sw = a.sw; cp.ph = a.ph; cp.pw = a.pw;
                 cp.out = slot_ptr(op.slot_out);
                 if (a.type == T_DENSE) {   // a dense layer is a 1x1 convolution over the flattened predecessor
@@ -916,7 +926,7 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                     net->prof_flop[0] += per_row * nrows;
                     net->prof_recs[0].push_back({0, start, op.layer_in, nrows, (int)in_el, (int)out_el, (int)cin, (int)(taps * a.C),
                                                  per_row * nrows});
-                    net->prof_bytes[0] += 4.0 * nrows * (in_el + out_el) + 4.0 * (double)a.wt_host.size();
+                    net->prof_bytes[0] += (double)csize * nrows * (in_el + out_el) + 4.0 * (double)a.wt_host.size();
                 }
             } else if (op.kind == PlanOp::FINALIZE) {
                 if (certify) {
@@ -957,6 +967,7 @@ gp_status analyze_layers(gp_net* net, int batch) {
             rp.xmax = l.d_xmax; rp.flag = net->d_flag;
             rp.total = l.n * batch;
             rp.n = l.n;
+            rp.margin = net->coef64 ? 0x1p-50 : 0x1p-22;
             gp::launch_relu(rp, net->stream);
         } else {
             if (net->float_inference && l.type == T_ADD && l.d_eta_thru) {
@@ -1056,7 +1067,7 @@ gp_status reserve_workspace(gp_net* net, int batch) {
         const Layer& l = net->L[i];
         if (l.type == T_RELU || !l.need_bounds) continue;
         const Plan& pl = net->plans[i];
-        if (pl.valid) want = std::max(want, task_bytes(pl, 2) * l.n * batch + 16384);
+        if (pl.valid) want = std::max(want, task_bytes(pl, 2, net->coef64 ? 8 : 4) * l.n * batch + 16384);
     }
     char* ws; long long bytes;
     return get_workspace(net, want, &ws, &bytes);
@@ -1284,6 +1295,17 @@ gp_status gp_set_graph_replay(gp_net* net, int32_t on) {
     return GP_OK;
 }
 
+gp_status gp_set_coefficient_storage(gp_net* net, int32_t bits) {
+    if (!net) return GP_ERR_ARG;
+    if (bits != 32 && bits != 64) return fail(net, GP_ERR_ARG, "coefficient storage: 32 or 64 bits");
+    drop_graph(net);
+    if ((bits == 64) != net->coef64) {
+        net->coef64 = bits == 64;
+        net->analyzed = false;
+    }
+    return GP_OK;
+}
+
 gp_status gp_set_float_inference(gp_net* net, int32_t on) {
     if (!net) return GP_ERR_ARG;
     drop_graph(net);
@@ -1342,7 +1364,7 @@ gp_status gp_workspace_size(const gp_net* cnet, int32_t batch, int64_t* min_byte
         Plan* pl;
         st = get_plan(net, (int)i, &pl);
         if (st != GP_OK) return st;
-        long long tb = task_bytes(*pl, 2);
+        long long tb = task_bytes(*pl, 2, net->coef64 ? 8 : 4);
         mn = std::max(mn, tb + 16384);
         full = std::max(full, tb * net->L[i].n * batch + 16384);
     }

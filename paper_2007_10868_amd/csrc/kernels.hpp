@@ -51,7 +51,7 @@ struct RowMap {
 };
 
 struct BlockDesc {
-    const float* data;   // [nrows][wy][wx][C]
+    const float* data;   // [nrows][wy][wx][C]; float64 values instead when the parameter block's coef64 is set
     int H, W, C;         // dims of the layer the block ranges over
     int wy, wx;          // window size (already clipped to the layer)
     int Sy, Sx, Py, Px;  // window origin of a row at (ys,xs): clamp(S*ys - P, 0, H - wy)  (eqs. 6-9 with padding)
@@ -83,6 +83,7 @@ struct CrossParams {       // one back-substitution step through an affine layer
     BlockDesc add;         // optional block over the same input layer to be summed in (residual join)
     RowMap rm;
     int nrows;
+    int coef64;            // coefficient blocks (in, out, add) hold float64 instead of float32 values
 };
 
 struct ScanParams {        // per-row reductions over a block
@@ -110,6 +111,8 @@ struct ScanParams {        // per-row reductions over a block
     double* best;          // per-row best candidate so far (indexed by the row's place before any removal)
     const unsigned char* done;   // per task of the chunk (compact): 1 = termination criterion met, best is final; null: none
     double* partial;       // scratch for rows longer than 1024 coefficients: [nrows][ceil(nelem/512)][5]; null: not available
+    int coef64;            // the block holds float64 values
+    double coef_floor;     // smallest magnitude a stored coefficient resolves, times 2^20 (see scan_finish)
 };
 
 struct InitParams {
@@ -133,6 +136,7 @@ struct InitParams {
     const double* eta;     // mode 2: [batch][n_start] float32 evaluation error of the start neurons (added to c); null: none
     double* c; double* err; double* best;
     int seeded;            // best already holds the rows' interval image: leave it
+    int coef64;            // out holds float64 values
     FastDiv div_C, div_wx; // filled by the launcher
 };
 
@@ -153,6 +157,7 @@ struct ReluParams {
     double* xmax; int* flag;
     long long total;                        // batch * n
     long long n;                            // neurons per box
+    double margin;                          // relative margin of rho and kap: 2^-22 for float32 storage, 2^-50 for float64
 };
 
 struct BoxParams {

@@ -11,13 +11,16 @@ namespace gp {
 //   mode 2: +/- the row of the start layer's matrix, i.e. its filter placed in the window over the
 //           predecessor; constant = +/- bias.  Exact: no rounding.
 //   mode 3: minus a caller-given linear form over the whole last layer; constant = minus its offset
+// CT: storage type of the coefficients (float, or double: then one element per lane and no rounding at all)
+template <typename CT>
 __global__ __launch_bounds__(256) void init_kernel(const InitParams p) {
     // block = 4 rows x 64 elements; grid.x over row quadruples, grid.y over element chunks
+    constexpr bool F32 = std::is_same<CT, float>::value;
     const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (r >= p.nrows) return;
     const RowInfo ri = row_info(p.rm, r);
-    float* out = p.out + (size_t)r * p.nelem;
-    if (p.mode == 2 && p.dense && (p.nelem & 3) == 0) {
+    CT* out = reinterpret_cast<CT*>(p.out) + (size_t)r * p.nelem;
+    if (F32 && p.mode == 2 && p.dense && (p.nelem & 3) == 0) {
         // rows of a dense layer's matrix: four coefficients per lane (16-byte loads and stores)
         const float* w = p.wt + (size_t)ri.cs * p.nelem;
         const float* g = p.out_grl ? p.out_grl + (size_t)ri.b * p.nelem : nullptr;
@@ -33,7 +36,7 @@ __global__ __launch_bounds__(256) void init_kernel(const InitParams p) {
             }
             *reinterpret_cast<float4*>(out + e) = make_float4(v[0], v[1], v[2], v[3]);
         }
-    } else if (p.mode == 2 && !p.dense && (p.C & 3) == 0) {
+    } else if (F32 && p.mode == 2 && !p.dense && (p.C & 3) == 0) {
         // the start layer's filter placed in the row's window over the predecessor: four channels of a window pixel per
         // lane (16-byte loads and stores), pixel coordinates without divisions
         const int oy = clampi(p.Sy * ri.ys - p.Py, 0, p.H - p.wy), ox = clampi(p.Sx * ri.xs - p.Px, 0, p.W - p.wx);
@@ -61,7 +64,7 @@ __global__ __launch_bounds__(256) void init_kernel(const InitParams p) {
         }
     } else
     for (int e = blockIdx.y * 64 + (threadIdx.x & 63); e < p.nelem; e += gridDim.y * 64) {
-        float v = 0.f;
+        CT v = 0.f;
         if (p.mode == 0) {
             v = (e == ri.cs) ? ri.sign : 0.f;
         } else if (p.mode == 1) {
@@ -79,7 +82,7 @@ __global__ __launch_bounds__(256) void init_kernel(const InitParams p) {
         } else if (p.dense) {
             v = ri.sign * p.wt[(size_t)ri.cs * p.nelem + e];
             if (p.out_grl && v != 0.f)
-                v = (float)((double)v * (double)relax_factor((double)v, p.out_grl[(size_t)ri.b * p.nelem + e]));
+                v = (CT)((double)v * (double)relax_factor((double)v, p.out_grl[(size_t)ri.b * p.nelem + e]));
         } else {
             // window over the predecessor (dims H,W,C here), origin from the row's position
             int pix = (int)fast_div((uint32_t)e, p.div_C), c = e - pix * p.C;
@@ -91,7 +94,7 @@ __global__ __launch_bounds__(256) void init_kernel(const InitParams p) {
                 v = ri.sign * p.wt[((size_t)(f * p.kw + g) * p.Cs + ri.cs) * p.C + c];
             if (p.out_grl && v != 0.f) {
                 size_t j = (size_t)ri.b * ((size_t)p.H * p.W * p.C) + (size_t)(A * p.W + B) * p.C + c;
-                v = (float)((double)v * (double)relax_factor((double)v, p.out_grl[j]));
+                v = (CT)((double)v * (double)relax_factor((double)v, p.out_grl[j]));
             }
         }
         out[e] = v;
@@ -112,10 +115,11 @@ void launch_init(const InitParams& p0, hipStream_t s) {
     InitParams p = p0;
     p.div_C = make_fastdiv((uint32_t)std::max(p.C, 1));
     p.div_wx = make_fastdiv((uint32_t)std::max(p.wx, 1));
-    const bool vec4 = p.mode == 2 && (p.dense ? (p.nelem & 3) == 0 : (p.C & 3) == 0);
+    const bool vec4 = !p.coef64 && p.mode == 2 && (p.dense ? (p.nelem & 3) == 0 : (p.C & 3) == 0);
     const int per = vec4 ? p.nelem / 4 : p.nelem;   // items per row
     const int ychunks = (int)fmin((double)((per + 63) / 64), 64.0);
-    hipLaunchKernelGGL(init_kernel, dim3((p.nrows + 3) / 4, ychunks), dim3(256), 0, s, p);
+    if (p.coef64) hipLaunchKernelGGL(init_kernel<double>, dim3((p.nrows + 3) / 4, ychunks), dim3(256), 0, s, p);
+    else hipLaunchKernelGGL(init_kernel<float>, dim3((p.nrows + 3) / 4, ychunks), dim3(256), 0, s, p);
 }
 
 // running maximum of non-negative values, one slot per box; a wave whose lanes all target the same slot
@@ -185,9 +189,10 @@ __global__ void relu_kernel(const ReluParams p) {
             double d = fmax(d1, d2);
             d = d + (fabs(d) + fabs(u)) * 0x1p-50 + 0x1p-1000;
             lam = (u > -l) ? 1.f : 0.f;
-            // rounded up, including the float32 rounding of the stored product coefficient*g
-            rho = (u / gd) * (1.0 + 0x1p-22);
-            kap = (d / gd) * (1.0 + 0x1p-22);
+            // rounded up, including the rounding of the stored product coefficient*g (p.margin: four roundings of the
+            // storage type)
+            rho = (u / gd) * (1.0 + p.margin);
+            kap = (d / gd) * (1.0 + p.margin);
         }
         p.grl[i] = lam != 0.f ? g : -g;      // -0.0f encodes slope 0 with lam = 0
         p.rho[i] = rho;

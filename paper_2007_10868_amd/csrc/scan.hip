@@ -23,12 +23,13 @@ namespace gp {
 // One coefficient's contribution to the five per-row sums.  Written with explicit fused multiply-adds only, so that
 // every scan kernel performs exactly the same operations in the same order per lane and a row's result does not
 // depend on which kernel (i.e. on how many rows share the launch) handled it.
-__device__ __forceinline__ void scan_term(bool has_cand, bool do_consts, float mf, double cp, double cn, double X, double kp,
+template <typename CT>
+__device__ __forceinline__ void scan_term(bool has_cand, bool do_consts, CT mf, double cp, double cn, double X, double kp,
                                           double be, double& cand, double& absx, double& cst, double& cstabs, double& s1) {
     const double m = (double)mf;
     const double am = fabs(m);
     if (has_cand) {
-        cand = fma(m, mf >= 0.f ? cp : cn, cand);
+        cand = fma(m, mf >= (CT)0 ? cp : cn, cand);
         absx = fma(am, X, absx);
     }
     if (do_consts) {
@@ -43,7 +44,8 @@ __device__ __forceinline__ void scan_term(bool has_cand, bool do_consts, float m
 // (every one of them is paid in time here): the staged multiplier pair is (cpos - cneg, cneg), so that the candidate
 // term needs no select, m*c(m) = max(m,0)*(cpos - cneg) + m*cneg; and the magnitude of the constant terms, which only
 // scales a rounding slack, is not summed per coefficient but bounded per row by S1 * max_j(|bias_j| + kap_j).
-__device__ __forceinline__ void scan_term_staged(bool has_cand, bool do_consts, float mf, double dcp, double cn, double X,
+template <typename CT>
+__device__ __forceinline__ void scan_term_staged(bool has_cand, bool do_consts, CT mf, double dcp, double cn, double X,
                                                  double kp, double be, double& cand, double& absx, double& cst, double& s1) {
     const double m = (double)mf;
     const double am = fabs(m);
@@ -93,7 +95,7 @@ __device__ __forceinline__ void scan_finish(const ScanParams& p, int r, int nele
     err += t_absx * p.round_coef * (1.0 + esum);
     // values below the float32 subnormal step vanish; with a substituted ReLU the lost coefficient is
     // up to 2^20 times larger (slopes are kept >= 2^-20)
-    if (p.round_coef > 0.0 && p.xmax_self) err += 0x1p-128 * (double)nelem * s.xmax_self;
+    if (p.round_coef > 0.0 && p.xmax_self) err += p.coef_floor * (double)nelem * s.xmax_self;
     if (p.update_best && p.cpos) {
         double v = c + t_cand + err;
         // (the candidate's terms are at most 3*|m|*X in magnitude when the multiplier comes as a difference, see
@@ -114,12 +116,26 @@ __device__ __forceinline__ void scan_finish(const ScanParams& p, int r, int nele
     p.err[r] = err;
 }
 
+// V consecutive stored coefficients (V = 4: aligned to 4 values)
+template <typename CT, int V>
+__device__ __forceinline__ void scan_load(const CT* src, CT (&mf)[V]) {
+    if constexpr (V == 4 && std::is_same<CT, float>::value) {
+        const float4 t = *reinterpret_cast<const float4*>(src);
+        mf[0] = t.x; mf[1 % V] = t.y; mf[2 % V] = t.z; mf[3 % V] = t.w;
+    } else if constexpr (V == 4) {
+        const double2 t0 = reinterpret_cast<const double2*>(src)[0], t1 = reinterpret_cast<const double2*>(src)[1];
+        mf[0] = t0.x; mf[1 % V] = t0.y; mf[2 % V] = t1.x; mf[3 % V] = t1.y;
+    } else {
+        mf[0] = src[0];
+    }
+}
+
 constexpr int SCAN_G = 8;     // rows per wave of the 8-lanes-per-row layout
 
 // Short rows: LPR = 8 lanes per row, 8 rows per wave.  Every lane accumulates for its own row (few registers, many
 // resident waves) and fetches the constants of its own elements; lanes of different rows that meet the same neuron
 // read the same addresses.
-template <int V, int LPR>
+template <int V, int LPR, typename CT>
 __global__ __launch_bounds__(256) void scan_tall_kernel(const ScanParams p) {
     constexpr int RPW = 64 / LPR;                            // rows per wave
     const int tid = threadIdx.x, lane = tid & 63;
@@ -139,17 +155,12 @@ __global__ __launch_bounds__(256) void scan_tall_kernel(const ScanParams p) {
     const RowInfo ri = row_info(p.rm, r);
     const int oy = clampi(B.Sy * ri.ys - B.Py, 0, B.H - B.wy), ox = clampi(B.Sx * ri.xs - B.Px, 0, B.W - B.wx);
     const long long bbase = (long long)ri.b * p.batch_stride;
-    const float* src = B.data + (size_t)r * nelem;
+    const CT* src = reinterpret_cast<const CT*>(B.data) + (size_t)r * nelem;
     double cand = 0.0, absx = 0.0, cst = 0.0, cstabs = 0.0, s1 = 0.0;
     if (valid) {
         for (int e = sub * V; e < nelem; e += LPR * V) {
-            float mf[V];
-            if (V == 4) {
-                const float4 t = *reinterpret_cast<const float4*>(src + e);
-                mf[0] = t.x; mf[1 % V] = t.y; mf[2 % V] = t.z; mf[3 % V] = t.w;
-            } else {
-                mf[0] = src[e];
-            }
+            CT mf[V];
+            scan_load<CT, V>(src + e, mf);
             int c;
             long long j;
             if (full_row) {
@@ -200,7 +211,7 @@ constexpr int SCAN_CHUNK = 512;         // chunk of longer rows (20 KB of LDS: 8
 // U: row slices (8 lanes x V elements each) whose loads are in flight together.
 // CHUNKED: rows longer than SCAN_LDS_MAX are cut into chunks of SCAN_CHUNK coefficients, one work-group per (32 rows,
 // chunk); the five sums of a (row, chunk) go to p.partial and scan_combine_kernel adds a row's chunks in order.
-template <int V, int ROWS, int U, bool CHUNKED>
+template <int V, int ROWS, int U, bool CHUNKED, typename CT>
 __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) {
     constexpr int SCAN_LDS_ROWS = ROWS;
     constexpr int NT = ROWS * 8;
@@ -236,23 +247,16 @@ __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) 
     }
     if (tid == 0) s_qmax[0] = s_qmax[1] = 0ull;
     __syncthreads();
-    const float* src = B.data + (size_t)r * nelem;
+    const CT* src = reinterpret_cast<const CT*>(B.data) + (size_t)r * nelem;
     double cand = 0.0, absx = 0.0, cst = 0.0, cstabs = 0.0, s1 = 0.0;
-    auto load_slices = [&](int e0, float (&mf)[U][V]) {
+    auto load_slices = [&](int e0, CT (&mf)[U][V]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int e = e0 + u * 8 * V;
-            if (e < c1) {
-                if (V == 4) {
-                    const float4 t = *reinterpret_cast<const float4*>(src + e);
-                    mf[u][0] = t.x; mf[u][1 % V] = t.y; mf[u][2 % V] = t.z; mf[u][3 % V] = t.w;
-                } else {
-                    mf[u][0] = src[e];
-                }
-            }
+            if (e < c1) scan_load<CT, V>(src + e, mf[u]);
         }
     };
-    auto add_slices = [&](int e0, const float (&mf)[U][V]) {
+    auto add_slices = [&](int e0, const CT (&mf)[U][V]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int e = e0 + u * 8 * V;
@@ -310,7 +314,7 @@ __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) 
         if (valid && kk >= k0 && kk < k1) {
             const double s1_before = s1;
             for (int e0 = c0 + sub * V; e0 < c1; e0 += U * 8 * V) {
-                float mf[U][V];
+                CT mf[U][V];
                 load_slices(e0, mf);
                 add_slices(e0, mf);
             }
@@ -353,6 +357,27 @@ __global__ __launch_bounds__(256) void scan_combine_kernel(const ScanParams p, i
 }
 
 
+template <typename CT>
+static void launch_scan_t(const ScanParams& p, hipStream_t s, int nhalves, int nelem, bool vec) {
+    if (nelem <= 256 || (nelem > SCAN_LDS_MAX && !p.partial)) {      // cross-over of the two layouts measured on MI355X
+        const int groups = ((p.rm.Rc + SCAN_G - 1) / SCAN_G) * nhalves;
+        if (vec) hipLaunchKernelGGL((scan_tall_kernel<4, 8, CT>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((scan_tall_kernel<1, 8, CT>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
+    } else if (nelem <= SCAN_LDS_MAX) {
+        const size_t lds = (size_t)5 * ((nelem + 3) & ~3) * sizeof(double);
+        const int wgs = ((p.rm.Rc + 31) / 32) * nhalves;
+        if (vec) hipLaunchKernelGGL((scan_lds_kernel<4, 32, 4, false, CT>), dim3(wgs), dim3(256), lds, s, p);
+        else hipLaunchKernelGGL((scan_lds_kernel<1, 32, 4, false, CT>), dim3(wgs), dim3(256), lds, s, p);
+    } else {
+        const int nchunks = (nelem + SCAN_CHUNK - 1) / SCAN_CHUNK;
+        const dim3 grid(((p.rm.Rc + 31) / 32) * nhalves, nchunks);
+        const size_t lds = (size_t)5 * SCAN_CHUNK * sizeof(double);
+        if (vec) hipLaunchKernelGGL((scan_lds_kernel<4, 32, 4, true, CT>), grid, dim3(256), lds, s, p);
+        else hipLaunchKernelGGL((scan_lds_kernel<1, 32, 4, true, CT>), grid, dim3(256), lds, s, p);
+        hipLaunchKernelGGL(scan_combine_kernel, dim3((p.nrows + 255) / 256), dim3(256), 0, s, p, nchunks);
+    }
+}
+
 void launch_scan(const ScanParams& p, hipStream_t s) {
     if (p.nrows <= 0) return;
     const int nhalves = p.nrows / p.rm.Rc;
@@ -360,23 +385,8 @@ void launch_scan(const ScanParams& p, hipStream_t s) {
     const bool vec = (p.blk.C & 3) == 0;
     // the layout depends on the row length only, never on how many rows the launch has: a row's sums are formed in
     // the same order whether its box is analysed alone, in a batch, or in a chunk of a batch
-    if (nelem <= 256 || (nelem > SCAN_LDS_MAX && !p.partial)) {      // cross-over of the two layouts measured on MI355X
-        const int groups = ((p.rm.Rc + SCAN_G - 1) / SCAN_G) * nhalves;
-        if (vec) hipLaunchKernelGGL((scan_tall_kernel<4, 8>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
-        else hipLaunchKernelGGL((scan_tall_kernel<1, 8>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
-    } else if (nelem <= SCAN_LDS_MAX) {
-        const size_t lds = (size_t)5 * ((nelem + 3) & ~3) * sizeof(double);
-        const int wgs = ((p.rm.Rc + 31) / 32) * nhalves;
-        if (vec) hipLaunchKernelGGL((scan_lds_kernel<4, 32, 4, false>), dim3(wgs), dim3(256), lds, s, p);
-        else hipLaunchKernelGGL((scan_lds_kernel<1, 32, 4, false>), dim3(wgs), dim3(256), lds, s, p);
-    } else {
-        const int nchunks = (nelem + SCAN_CHUNK - 1) / SCAN_CHUNK;
-        const dim3 grid(((p.rm.Rc + 31) / 32) * nhalves, nchunks);
-        const size_t lds = (size_t)5 * SCAN_CHUNK * sizeof(double);
-        if (vec) hipLaunchKernelGGL((scan_lds_kernel<4, 32, 4, true>), grid, dim3(256), lds, s, p);
-        else hipLaunchKernelGGL((scan_lds_kernel<1, 32, 4, true>), grid, dim3(256), lds, s, p);
-        hipLaunchKernelGGL(scan_combine_kernel, dim3((p.nrows + 255) / 256), dim3(256), 0, s, p, nchunks);
-    }
+    if (p.coef64) launch_scan_t<double>(p, s, nhalves, nelem, vec);
+    else launch_scan_t<float>(p, s, nhalves, nelem, vec);
 }
 
 }  // namespace gp
