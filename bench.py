@@ -34,6 +34,8 @@ def main():
     ap.add_argument("--float-inference", action="store_true",
                     help="bounds that also cover every float32 evaluation order of the network (inference rounding)")
     ap.add_argument("--graph", action="store_true", help="replay the pass as a captured HIP graph")
+    ap.add_argument("--coef-bits", type=int, default=32, choices=(32, 64),
+                    help="storage of the coefficient blocks: float32 (default, the headline configuration) or float64")
     ap.add_argument("--weight-scale", type=float, default=1.0,
                     help="multiply every weight by this factor (well below 1: most ReLUs stable, as in robustly trained nets)")
     ap.add_argument("--eps", type=float, default=0.0, help="override the configuration's perturbation radius")
@@ -67,6 +69,8 @@ def main():
         g.set_float_inference(True)
     if args.graph:
         g.set_graph_replay(True)
+    if args.coef_bits == 64:
+        g.set_coefficient_storage(64)
     centers = np.stack([net.center(j % net.n_inputs) for j in range(batch)])
     t_centers = torch.tensor(centers, device="cuda")
     stream = torch.cuda.current_stream()
@@ -178,7 +182,7 @@ def main():
                gpu_ms_per_step=round(gpu_ms / args.steps, 4),
                higher_is_better=False, scaling="weak", vs_baseline=None, dtype="f64", data="synthetic",
                config=dict(workload=net.name, inputs_per_step=batch, eps=net.eps, neurons=int(sum(net.n_neurons(i) for i in range(1, net.out_layer + 1) if net.layers[i - 1]["type"] != "relu")),
-                           coefficient_storage="f32", accumulate="f64 MFMA", workspace_bytes=ws_bytes,
+                           coefficient_storage="f64" if args.coef_bits == 64 else "f32", accumulate="f64 MFMA", workspace_bytes=ws_bytes,
                            early_termination=bool(args.early_term), float_inference=bool(args.float_inference),
                            graph_replay=bool(args.graph)),
                roofline=roofline, cpu_baseline=cpu)
