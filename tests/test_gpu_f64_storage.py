@@ -144,3 +144,39 @@ def test_config1_sampled_neurons_in_float64_storage():
         d = max(np.max((olo - glo) / (1 + np.abs(olo))), np.max((ghi - ohi) / (1 + np.abs(ohi))))
         v = max(np.max((glo - olo) / (1 + np.abs(olo))), np.max((ohi - ghi) / (1 + np.abs(ohi))))
         assert d <= 1e-7 and v <= 1e-12, (lid, d, v)
+
+
+def _strip5_conv(seed=0):
+    from test_gpu_parity import strip5_conv
+    return strip5_conv(seed)
+
+
+@pytest.mark.parametrize("maker,eps,batch", [(strip_conv, 0.004, 2), (_strip5_conv, 0.002, 2), (lambda s: wl.config(2), 2.0 / 255.0, 3),
+                                             (lambda s: wl.config(3), 1.0 / 255.0, 1), (lambda s: wl.scaled_resnet(8, 16), 0.002, 2),
+                                             (lambda s: wl.lenet_pool(), 1.0 / 255.0, 1)])
+def test_float32_storage_tracks_float64_storage(maker, eps, batch):
+    """The narrow-layer kernels (direct MFMA, one lane per pixel, strips of pixels) exist for float32 storage only; the
+    float64 storage runs every layer through the general kernel and is within 1e-9 of the oracle.  So the float32
+    results must contain the float64 results (up to what slightly different slopes do: the float32 intervals are wider
+    by their slack, the slopes follow) and exceed them by no more than the float32 slack, which grows with depth (measured:
+    3e-6 on three-layer networks, 3e-5 on the deep ones; bar 2e-4): a check of those kernels at full size, several times
+    tighter than the 1e-3 bar and without the oracle's run time."""
+    net = maker(1)
+    centers = np.stack([np.random.default_rng(50 + j).random(net.n_in).astype(np.float32) for j in range(batch)])
+    g64 = make_gpu(net)
+    g64.set_coefficient_storage(64)
+    g64.analyze_batch(centers, eps)
+    g32 = make_gpu(net)
+    g32.analyze_batch(centers, eps)
+    worst = 0.0
+    for b in range(batch):
+        for lid in layers_of(net):
+            lo64, hi64 = g64.get_bounds_f64(lid, b)
+            lo32, hi32 = g32.get_bounds_f64(lid, b)
+            s_lo, s_hi = 1 + np.abs(lo64), 1 + np.abs(hi64)
+            loose = max(np.max((lo64 - lo32) / s_lo), np.max((hi32 - hi64) / s_hi))
+            inside = max(np.max((lo32 - lo64) / s_lo), np.max((hi64 - hi32) / s_hi))
+            worst = max(worst, loose)
+            assert loose <= 2e-4, f"{net.name} box {b} layer {lid}: float32 storage looser than float64 storage by {loose:.3e}"
+            assert inside <= 1e-5, f"{net.name} box {b} layer {lid}: float32 storage inside float64 storage by {inside:.3e}"
+    print(net.name, "float32 vs float64 storage: worst", worst)
