@@ -131,6 +131,7 @@ def main():
     # the same K steps replayed as one captured HIP graph per pass (no per-kernel events there, so this is reported
     # beside the metric, which stays the eager, event-instrumented region above)
     graph_ms = None
+    graph_single_ms = None
     if not args.graph and not args.early_term and ms_per_step < 2000.0:
         g.set_graph_replay(True)
         for _ in range(2):
@@ -141,6 +142,15 @@ def main():
             g.analyze_batch_dev(t_centers, net.eps)
         torch.cuda.synchronize()
         graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        if batch > 1:                      # ... and one input at a time, replayed
+            for _ in range(3):
+                g.analyze_batch_dev(one, net.eps)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(10):
+                g.analyze_batch_dev(one, net.eps)
+            torch.cuda.synchronize()
+            graph_single_ms = (time.perf_counter() - t0) * 1e3 / 10
         g.set_graph_replay(False)
 
     cross = prof["cross"]
@@ -190,6 +200,8 @@ def main():
         out["single_input_latency_ms"] = round(single_ms, 4)
     if graph_ms is not None:
         out["graph_replay"] = dict(ms_per_step=round(graph_ms, 4), ms_per_input=round(graph_ms / batch, 5))
+        if graph_single_ms is not None:
+            out["graph_replay"]["single_input_latency_ms"] = round(graph_single_ms, 4)
     if early is not None:
         out["early_termination"] = early
     print(json.dumps(out))
