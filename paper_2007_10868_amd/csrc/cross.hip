@@ -1339,9 +1339,9 @@ static void launch_cross_pool(const CrossParams& p, hipStream_t s) {
     }
 }
 
-// float64 storage: the general LDS-tiled form for every layer
-static void launch_cross_f64(const CrossParams& p0, hipStream_t s) {
-    constexpr int BM = 64, BN = 64;
+// float64 storage: the general LDS-tiled form for every layer (32 columns per tile when the layer has no more)
+template <int BM, int BN>
+static void launch_cross_f64_t(const CrossParams& p0, hipStream_t s) {
     CrossParams p = p0;
     p.ntiles_m = (p.nrows + BM - 1) / BM;
     p.ntiles_n = (p.Co + BN - 1) / BN;
@@ -1351,6 +1351,10 @@ static void launch_cross_f64(const CrossParams& p0, hipStream_t s) {
     const unsigned blocks = (unsigned)(((total + 7) / 8) * 8);
     if ((p.in.C & 3) == 0) hipLaunchKernelGGL((cross_kernel<BM, BN, true, false, double>), dim3(blocks), dim3(256), 0, s, p);
     else hipLaunchKernelGGL((cross_kernel<BM, BN, false, false, double>), dim3(blocks), dim3(256), 0, s, p);
+}
+static void launch_cross_f64(const CrossParams& p, hipStream_t s) {
+    if (p.Co <= 32) launch_cross_f64_t<64, 32>(p, s);
+    else launch_cross_f64_t<64, 64>(p, s);
 }
 
 void launch_cross(const CrossParams& p, hipStream_t s) {
