@@ -31,6 +31,16 @@ def affine_read_layers(net: wl.Net):
                    and net.layers[L["src"] - 1]["type"] != "relu"})
 
 
+def same_lower_lines(net: wl.Net, g1, g2, batch_index=0) -> bool:
+    """Whether two GPU analyses chose the same lower relaxation line for every ReLU neuron.  The choice switches at
+    u = -l, the only discontinuity of the analysis: two sound analyses whose intervals differ in the last digits can
+    choose differently there, and their later bounds then differ by far more than rounding, in both directions."""
+    for lid, L in enumerate(net.layers, start=1):
+        if L["type"] == "relu" and not np.array_equal(g1.get_relu_lambda(lid, batch_index), g2.get_relu_lambda(lid, batch_index)):
+            return False
+    return True
+
+
 def make_gpu(net: wl.Net):
     from paper_2007_10868_amd import Net
     g = Net(*net.input_shape)

@@ -9,7 +9,7 @@ import torch
 import workloads as wl
 from helpers import ball_box, forward
 from parity import (analysed_layers, affine_read_layers, check_samples_inside, compare_all, make_gpu, make_oracle,
-                    oracle_with_gpu_relaxation, oracle_with_gpu_ties)
+                    oracle_with_gpu_relaxation, oracle_with_gpu_ties, same_lower_lines)
 from test_gpu_avgpool import lenet_like, pooled_shortcut
 from test_gpu_early_term import check_early
 from test_gpu_parity import mid_resnet, odd_fc, pad0_conv, quad_fc, rect_conv, strip_conv, tiny_conv, tiny_fc, tiny_resnet
@@ -170,6 +170,7 @@ def test_float32_storage_tracks_float64_storage(maker, eps, batch):
     g32.analyze_batch(centers, eps)
     worst = 0.0
     for b in range(batch):
+        assert same_lower_lines(net, g32, g64, b), "a tie of the lower-line choice fell differently: pick another seed"
         for lid in layers_of(net):
             lo64, hi64 = g64.get_bounds_f64(lid, b)
             lo32, hi32 = g32.get_bounds_f64(lid, b)
