@@ -15,11 +15,13 @@
  *   - Neurons of a layer are numbered C,H,W-flattened (channel outermost) at this boundary.
  *   - Every call returns a gp_status; nothing throws or aborts across the boundary; a failed call
  *     leaves the net usable.  gp_last_error() gives a message for the last failure on that net.
- *   - Bounds are reported for: the input, every layer that feeds a ReLU, every ReLU layer, the last
- *     layer, and layers marked with gp_request_bounds().  Other layers: GP_ERR_STATE.
+ *   - Bounds are reported for: the input, every layer that feeds a ReLU, every ReLU layer, every layer
+ *     that an affine layer reads directly, the last layer, and layers marked with gp_request_bounds()
+ *     (with gp_set_float_inference also every residual sum layer).  Other layers: GP_ERR_STATE.
  *   - Soundness: reported bounds contain the exact real-arithmetic output range of the network
  *     with the given float32 weights over the box (rounding of the analysis itself is accounted
- *     for; rounding of a float inference of the network is not).
+ *     for); with gp_set_float_inference they also contain what a float32 evaluation of the network
+ *     computes, in any summation order.
  *   - Calls on one net must not overlap in time.  Different nets may be used from different threads.
  */
 #ifndef GPUPOLY_H
