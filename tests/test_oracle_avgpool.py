@@ -245,3 +245,58 @@ def test_float_inference_matters_for_a_point_box_average():
         assert lo[0] <= v <= hi[0]
         outside += not (plo[0] <= v <= phi[0])
     assert outside > 0
+
+
+def test_rectangular_window_stride_and_padding():
+    """kh != kw, stride_h != stride_w, pad_h != pad_w: against the NumPy DeepPoly on the exact matrix and sampled points
+    (a transposed stride or padding changes which inputs a window holds)."""
+    rng = np.random.default_rng(21)
+    net = wl.Net("rect_pool", (2, 7, 9))
+    W = (rng.standard_normal((3, 2, 2, 3)) * 0.4).astype(np.float32)
+    net.layers.append(dict(type="conv", src=0, W=W, b=(rng.standard_normal(3) * 0.1).astype(np.float32), stride=(1, 2), pad=(1, 0),
+                           shape=(3, 8, 4)))
+    net.layers.append(dict(type="relu", src=1, shape=(3, 8, 4)))
+    net.layers.append(dict(type="avgpool", src=2, kernel=(3, 2), stride=(2, 1), pad=(1, 0), shape=(3, 4, 3)))
+    net.layers.append(dict(type="relu", src=3, shape=(3, 4, 3)))
+    net.layers.append(dict(type="avgpool", src=4, kernel=(2, 3), stride=(1, 2), pad=(0, 2), shape=(3, 3, 3)))
+    Wd = (rng.standard_normal((4, 27)) * 0.3).astype(np.float32)
+    net.dense(5, Wd, np.zeros(4, np.float32))
+    c = rng.random(net.n_in).astype(np.float32)
+    o = make_oracle(net)
+    o.request_bounds(5)
+    o.analyze(c, 0.05)
+    lo0, hi0 = ball_box(c, 0.05)
+    ref = np_deeppoly(net, lo0, hi0)
+    vals = forward(net, sample_box(lo0, hi0, 3000, np.random.default_rng(22)))
+    for l in (1, 2, 3, 4, 6):
+        lo, hi = o.get_bounds(l)
+        assert np.all(vals[l] >= lo[None] - 1e-12) and np.all(vals[l] <= hi[None] + 1e-12)
+        if l != 6:          # (the NumPy version takes no candidate over layer 5, which is bounded here)
+            np.testing.assert_allclose(lo, ref[l][0], rtol=0, atol=1e-10)
+            np.testing.assert_allclose(hi, ref[l][1], rtol=0, atol=1e-10)
+    assert np.all(o.get_bounds(6)[0] >= ref[6][0] - 1e-10) and np.all(o.get_bounds(6)[1] <= ref[6][1] + 1e-10)
+
+
+def test_one_ninth_is_enclosed_in_exact_rationals():
+    """A 3x3 window that holds a single input (the corner of a padded 1x1 image): the output is x/9, and 1/9 is no
+    binary fraction.  For x = 1, -1 and 3 the bounds must enclose the rational value and be at most a few ulps apart on
+    each side (a weight rounded the wrong way for one of the signs leaves the rational value outside)."""
+    from fractions import Fraction
+    net = wl.Net("ninth", (1, 1, 1))
+    net.avgpool(0, 3, 1, 2)                  # output 3x3, every window holds the one pixel
+    W = np.array([[1, -1, 0, 0, 0, 0, 0, 0, 0]], np.float32)
+    for x in (1.0, -1.0, 3.0):
+        o = make_oracle(net)
+        o.analyze_box(np.array([x]), np.array([x]))
+        lo, hi = o.get_bounds(1)
+        exact = Fraction(x) / 9
+        for a, b in zip(lo, hi):
+            assert Fraction(float(a)) <= exact <= Fraction(float(b))
+            assert b - a <= 4 * np.spacing(abs(x) / 9)
+    # ... and through a later layer, with coefficients of both signs over the pooled neurons
+    net.dense(1, W, np.zeros(1, np.float32))
+    o = make_oracle(net)
+    o.analyze_box(np.array([1.0]), np.array([1.0]))
+    lo, hi = o.get_bounds(2)
+    assert lo[0] <= 0.0 <= hi[0] and hi[0] - lo[0] <= 4 * np.spacing(1 / 9)
+    assert hi[0] > 0.0 and lo[0] < 0.0       # 1/9 - 1/9 with outward-rounded ends is a proper interval around 0
