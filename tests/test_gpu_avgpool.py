@@ -250,3 +250,35 @@ def test_random_pooled_topology(seed):
                 glo, ghi = g.get_bounds_f64(lid)
                 v = vals[lid].astype(np.float64)
                 assert np.all(v >= glo) and np.all(v <= ghi), (net.name, order, lid)
+
+
+def test_pooling_as_the_last_layer_certify_forms_and_point_box():
+    """A network that ENDS in a pooling layer: certification rows and linear forms start on the pooled outputs, and a
+    point box (eps = 0) gives the forward value."""
+    rng = np.random.default_rng(3)
+    net = wl.Net("pool_last", (3, 8, 8))
+    W = (rng.standard_normal((5, 3, 3, 3)) * 0.3).astype(np.float32)
+    x = net.relu(net.conv(0, W, (rng.standard_normal(5) * 0.1).astype(np.float32), 1, 1))
+    net.avgpool(x, 8)                                            # global average: 5 outputs
+    c = rng.random(net.n_in).astype(np.float32)
+    g = make_gpu(net)
+    o = make_oracle(net)
+    g.analyze(c, 0.02)
+    oracle_with_gpu_ties(net, o, g, c, 0.02)
+    compare_all(net, g, o, what=net.name)
+    y = forward(net, c[None].astype(np.float64))[net.out_layer][0]
+    label = int(np.argmax(y))
+    (ok_g, m_g), (ok_o, m_o) = g.certify(label), o.certify(label)
+    assert np.all(m_g <= m_o + 1e-6 * (1 + np.abs(m_o))) and np.all(m_o - m_g <= 1e-3 * (1 + np.abs(m_o)))
+    coef = rng.standard_normal((4, 5)).astype(np.float32)
+    off = rng.standard_normal(4).astype(np.float32)
+    lb = g.bound_outputs(coef, off).astype(np.float64).reshape(-1)
+    ref = o.bound_outputs(coef.astype(np.float64), off.astype(np.float64))
+    assert np.all(lb <= ref + 2e-6 * (1 + np.abs(ref))) and np.all(ref - lb <= 1e-3 * (1 + np.abs(ref)))
+    g.analyze(c, 0.0)
+    lo, hi = g.get_bounds_f64(net.out_layer)
+    assert np.all(lo <= y + 1e-12) and np.all(hi >= y - 1e-12) and np.max(hi - lo) < 1e-5
+    g.set_coefficient_storage(64)
+    g.analyze(c, 0.0)
+    lo, hi = g.get_bounds_f64(net.out_layer)
+    assert np.all(lo <= y + 1e-12) and np.all(hi >= y - 1e-12) and np.max(hi - lo) < 1e-12
