@@ -63,7 +63,7 @@ __device__ __forceinline__ void epilogue_row_info(const CrossParams& p, const Ro
 // CT: storage type of the coefficient blocks (float; double for the float64 storage mode, which only this form and
 // cross_pool_kernel serve: 32 bytes per 4 channels, no conversion, no rounding but the final one to float64).
 template <int BM, int BN, bool VEC, bool DENSE, typename CT = float>
-__global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_kernel(const CrossParams p) {
+__global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 2) void cross_kernel(const CrossParams p) {
     constexpr bool A64 = std::is_same<CT, double>::value;
     constexpr uint32_t CS = sizeof(CT);
     constexpr int BK = 16;
@@ -534,7 +534,7 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 1) void cross_ker
 //   layout: lane l holds A[row l%16][k l/16] (as for 16x16x4), B[k l/16][column l%4] (the same B for every block), and
 //   receives D[row 4*((l%16)/4) + l/16][column l%4].
 template <int TM, int TN_, bool VEC>
-__global__ __launch_bounds__(256) void cross_direct_kernel(const CrossParams p) {
+__global__ __launch_bounds__(256, 2) void cross_direct_kernel(const CrossParams p) {
     constexpr bool SMALLN = (TN_ == 0);
     constexpr int TN = SMALLN ? 1 : TN_;
     constexpr int BK = 16;
@@ -1042,7 +1042,7 @@ static void launch_cross_image(const CrossParams& p0, hipStream_t s) {
 // in one box (so the whole geometry is scalar), whole 16-channel steps.
 // grid: (row tile of 128 rows, output row, strip) in the XCD-aware order of cross_kernel.
 template <int P, int KW>
-__global__ __launch_bounds__(256) void cross_strip_kernel(const CrossParams p) {
+__global__ __launch_bounds__(256, 2) void cross_strip_kernel(const CrossParams p) {
     constexpr int TM = 2;
     extern __shared__ __attribute__((aligned(16))) double s_w[];          // [tap][4][Ck + 2]
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
