@@ -237,12 +237,13 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 2) void cross_ker
         tapmask = (1ull << taps) - 1;
     }
     // taps beyond 64 (huge filters) are all visited
-    auto next_tap = [&](int t) -> int {          // first needed tap >= t, or taps
-        while (t < taps && t < 64 && !((tapmask >> t) & 1ull)) ++t;
-        return t;
+    auto next_tap = [&](int t) -> int {          // first needed tap >= t, or taps (find-first-set, no loop over the bits)
+        if (t >= 64 || t >= taps) return t;
+        const unsigned long long m = tapmask >> t;
+        return m ? min(t + (int)__builtin_ctzll(m), taps) : min(taps, 64);
     };
-    int n_taps = 0;
-    for (int t = next_tap(0); t < taps; t = next_tap(t + 1)) ++n_taps;
+    // needed taps: the mask's bits below `taps`, and every tap from the 64th on
+    const int n_taps = __builtin_popcountll(taps < 64 ? (tapmask & ((1ull << taps) - 1ull)) : tapmask) + max(taps - 64, 0);
     const int nIt = n_taps * kchunks;
 
     // the step the next loads are for moves on to tap t (uniform)
@@ -681,12 +682,13 @@ __global__ __launch_bounds__(256, 2) void cross_direct_kernel(const CrossParams 
         for (int off = 32; off > 0; off >>= 1) mine |= __shfl_xor(mine, off, 64);
         tapmask = wave_uniform(mine);
     }
-    auto next_tap = [&](int t) -> int {
-        while (t < taps && t < 64 && !((tapmask >> t) & 1ull)) ++t;
-        return t;
+    auto next_tap = [&](int t) -> int {          // see cross_kernel
+        if (t >= 64 || t >= taps) return t;
+        const unsigned long long m = tapmask >> t;
+        return m ? min(t + (int)__builtin_ctzll(m), taps) : min(taps, 64);
     };
-    int n_taps = 0;
-    for (int t = next_tap(0); t < taps; t = next_tap(t + 1)) ++n_taps;
+    // needed taps: the mask's bits below `taps`, and every tap from the 64th on
+    const int n_taps = __builtin_popcountll(taps < 64 ? (tapmask & ((1ull << taps) - 1ull)) : tapmask) + max(taps - 64, 0);
     const int nIt = n_taps * kchunks;
 
     // the step the next loads are for moves on to tap t (uniform)
