@@ -273,8 +273,17 @@ __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) 
     while (k0 < nvalid) {                                   // uniform over the work-group
         if (tid == 0) s_qmax[(run & 1) ^ 1] = 0ull;
         const int b0 = s_b[k0], oy0 = s_oy[k0], ox0 = s_ox[k0];
-        int k1 = k0 + 1;
-        while (k1 < nvalid && s_b[k1] == b0 && s_oy[k1] == oy0 && s_ox[k1] == ox0) ++k1;
+        // end of the run that starts at row k0: every lane tests one row, the first row that differs is found in the
+        // ballot (a loop over the rows costs three LDS round trips and a branch per row, 31 times for a dense layer)
+        int k1;
+        {
+            static_assert(SCAN_LDS_ROWS <= 64, "one lane per row");
+            const int my = lane < SCAN_LDS_ROWS ? lane : 0;
+            const bool same = lane < nvalid && s_b[my] == b0 && s_oy[my] == oy0 && s_ox[my] == ox0;
+            const unsigned long long differs = ~__ballot(same);               // lanes >= nvalid differ
+            const unsigned long long m = k0 + 1 < 64 ? differs >> (k0 + 1) : 0ull;
+            k1 = m ? min(k0 + 1 + (int)__builtin_ctzll(m), nvalid) : nvalid;
+        }
         const long long bbase = (long long)b0 * p.batch_stride;
         double qmax = 0.0;
         for (int e = c0 + tid; e < c1; e += NT) {
