@@ -112,6 +112,7 @@ struct ScanParams {        // per-row reductions over a block
     const unsigned char* done;   // per task of the chunk (compact): 1 = termination criterion met, best is final; null: none
     double* partial;       // scratch for rows longer than 1024 coefficients: [nrows][ceil(nelem/512)][5]; null: not available
     int coef64;            // the block holds float64 values
+    FastDiv div_C, div_wx; // filled by the launcher: blk.C, blk.wx
     double coef_floor;     // smallest magnitude a stored coefficient resolves, times 2^20 (see scan_finish)
 };
 

@@ -163,13 +163,12 @@ __global__ __launch_bounds__(256) void scan_tall_kernel(const ScanParams p) {
             scan_load<CT, V>(src + e, mf);
             int c;
             long long j;
+            const int pix = (int)fast_div((uint32_t)e, p.div_C);
+            c = e - pix * B.C;
             if (full_row) {
-                c = e % B.C;
                 j = bbase + (long long)oy * B.W * B.C + e;
             } else {
-                const int pix = e / B.C;
-                c = e - pix * B.C;
-                const int a = pix / B.wx, bb = pix - a * B.wx;
+                const int a = (int)fast_div((uint32_t)pix, p.div_wx), bb = pix - a * B.wx;
                 j = bbase + ((long long)((oy + a) * B.W + (ox + bb)) * B.C + c);
             }
 #pragma unroll
@@ -289,13 +288,12 @@ __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) 
         for (int e = c0 + tid; e < c1; e += NT) {
             int c;
             long long j;
+            const int pix = (int)fast_div((uint32_t)e, p.div_C);
+            c = e - pix * B.C;
             if (full_row) {
-                c = e % B.C;
                 j = bbase + (long long)oy0 * B.W * B.C + e;
             } else {
-                const int pix = e / B.C;
-                c = e - pix * B.C;
-                const int a = pix / B.wx, bb = pix - a * B.wx;
+                const int a = (int)fast_div((uint32_t)pix, p.div_wx), bb = pix - a * B.wx;
                 j = bbase + ((long long)((oy0 + a) * B.W + (ox0 + bb)) * B.C + c);
             }
             double cp = 0.0, cn = 0.0, X = 0.0, kp = 0.0, be = 0.0;
@@ -387,8 +385,11 @@ static void launch_scan_t(const ScanParams& p, hipStream_t s, int nhalves, int n
     }
 }
 
-void launch_scan(const ScanParams& p, hipStream_t s) {
-    if (p.nrows <= 0) return;
+void launch_scan(const ScanParams& p0, hipStream_t s) {
+    if (p0.nrows <= 0) return;
+    ScanParams p = p0;
+    p.div_C = make_fastdiv((uint32_t)p.blk.C);
+    p.div_wx = make_fastdiv((uint32_t)p.blk.wx);
     const int nhalves = p.nrows / p.rm.Rc;
     const int nelem = p.blk.wy * p.blk.wx * p.blk.C;
     const bool vec = (p.blk.C & 3) == 0;
