@@ -276,11 +276,14 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 2) void cross_ker
         if constexpr (A64) return a_raw64[i][j];
         else return (double)a_raw[i].v[j];
     };
-    auto load_tiles = [&]() {
+    // whole: the caller knows that the step is a whole 16-channel step of a dense layer and not its last one (no ragged
+    // form, no move to another tap): the load then has no branch
+    auto load_tiles = [&](auto whole_c) {
+        constexpr bool WHOLE = DENSE && VEC && decltype(whole_c)::value;
         const int rem = Ck - ld_d0;                                 // channels left in this tap (uniform)
         const uint32_t soffA = s_tapoff + (uint32_t)ld_d0 * CS;
         const uint32_t soffB = ((uint32_t)ld_t * (uint32_t)N * (uint32_t)Ck + (uint32_t)ld_d0) * 4u;
-        if (VEC && rem >= BK) {
+        if (WHOLE || (VEC && rem >= BK)) {
 #pragma unroll
             for (int i = 0; i < APT; ++i) {
                 if constexpr (A64) {        // (kOOB + 16 is still beyond every range)
@@ -313,10 +316,12 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 2) void cross_ker
                 b_raw[i] = buf_ld4<VEC>(rsrcB, (dok && b_voff[i] != kOOB) ? b_voff[i] + soffB : kOOB, rem - q4);
         }
         ld_d0 += BK;
-        if (ld_d0 >= Ck) {                                          // next needed tap (uniform, once per kchunks steps)
-            ld_d0 = 0;
-            ld_t = next_tap(ld_t + 1);
-            if (ld_t < taps) enter_tap(ld_t);
+        if constexpr (!WHOLE) {
+            if (ld_d0 >= Ck) {                                      // next needed tap (uniform, once per kchunks steps)
+                ld_d0 = 0;
+                ld_t = next_tap(ld_t + 1);
+                if (ld_t < taps) enter_tap(ld_t);
+            }
         }
     };
     // LDS addresses of this thread's stores and MFMA operand loads (fixed; the buffer index is an immediate)
@@ -335,7 +340,7 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 2) void cross_ker
             if (q < tail_q) {
 #pragma unroll
                 for (int i = 0; i < APT; ++i) {
-                    if (ld_row + 64 * i < BM) {
+                    if (BM % 64 == 0 || ld_row + 64 * i < BM) {    // (ld_row < 64)
                         double* dst = &As[0][ld_row][0] + (buf * BM + 64 * i) * LDK + q;
 #pragma unroll
                         for (int j = 0; j < 4; ++j) dst[4 * j] = a_val(i, j);
@@ -343,7 +348,7 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 2) void cross_ker
                 }
 #pragma unroll
                 for (int i = 0; i < BPT; ++i) {
-                    if (ld_row + 64 * i < BN) {
+                    if (BN % 64 == 0 || ld_row + 64 * i < BN) {
                         double* dst = &Bs[0][ld_row][0] + (buf * BN + 64 * i) * LDK + q;
 #pragma unroll
                         for (int j = 0; j < 4; ++j) dst[4 * j] = (double)b_raw[i].v[j];
@@ -354,7 +359,7 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 2) void cross_ker
         }
 #pragma unroll
         for (int i = 0; i < APT; ++i) {
-            if (ld_row + 64 * i < BM) {
+            if (BM % 64 == 0 || ld_row + 64 * i < BM) {    // (ld_row < 64)
                 double2* dst = reinterpret_cast<double2*>(a_st + (buf * BM + 64 * i) * LDK);
                 dst[0] = make_double2(a_val(i, 0), a_val(i, 1));
                 dst[1] = make_double2(a_val(i, 2), a_val(i, 3));
@@ -362,7 +367,7 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 2) void cross_ker
         }
 #pragma unroll
         for (int i = 0; i < BPT; ++i) {
-            if (ld_row + 64 * i < BN) {
+            if (BN % 64 == 0 || ld_row + 64 * i < BN) {
                 double2* dst = reinterpret_cast<double2*>(b_st + (buf * BN + 64 * i) * LDK);
                 dst[0] = make_double2((double)b_raw[i].v[0], (double)b_raw[i].v[1]);
                 dst[1] = make_double2((double)b_raw[i].v[2], (double)b_raw[i].v[3]);
@@ -428,36 +433,41 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 2) void cross_ker
         // t; one barrier.  The LDS and global latencies of the coming tiles pass while the MFMAs of the current one
         // run, and nothing but the barrier stands between the MFMA phases of consecutive steps.
         if (nIt > 0) {
-            load_tiles();                          // tile 0
+            load_tiles(std::false_type{});         // tile 0
             store_tiles(0, tail_q && last == 0);
-            if (nIt > 1) load_tiles();             // tile 1
+            if (nIt > 1) load_tiles(std::false_type{});             // tile 1
             __syncthreads();
             read_frags(C0{}, 0);
             if (nIt > 1) store_tiles(1, tail_q && last == 1);
-            if (nIt > 2) load_tiles();             // tile 2
+            if (nIt > 2) load_tiles(std::false_type{});             // tile 2
             __syncthreads();
             int t = 0;
-            for (; t + 2 <= nIt; t += 2) {
+            // STEADY: tiles t+2 .. t+4 exist and none of t+1 .. t+4 is the last one, so nothing in the pair of steps is
+            // conditional (the compiled loop then has no branch between its MFMAs); the last pairs take the general form
+            auto step_pair = [&](auto steady_c) {
+                constexpr bool STEADY = decltype(steady_c)::value;
                 read_frags(C1{}, 1);                       // tile t+1
                 mfma_head(C0{}, 4);                        // tile t (never the last one here), first part
                 __builtin_amdgcn_sched_barrier(0);
-                if (t + 2 < nIt) store_tiles(0, tail_q && t + 2 == last);   // tile t+2 (its loads were issued a step ago)
-                if (t + 3 < nIt) load_tiles();             // tile t+3
+                if (STEADY || t + 2 < nIt) store_tiles(0, !STEADY && tail_q && t + 2 == last);   // tile t+2 (its loads were issued a step ago)
+                if (STEADY || t + 3 < nIt) load_tiles(steady_c);   // tile t+3
                 __builtin_amdgcn_sched_barrier(0);
                 mfma_tail(C0{}, 4);                        // tile t, the rest
                 __builtin_amdgcn_sched_barrier(0);         // keep the barrier (and its wait for the LDS traffic) behind the MFMAs
                 __syncthreads();
-                const int q1 = (t + 1 == last) ? qlast : 4;
-                if (t + 2 < nIt) read_frags(C0{}, 0);      // tile t+2
+                const int q1 = (!STEADY && t + 1 == last) ? qlast : 4;
+                if (STEADY || t + 2 < nIt) read_frags(C0{}, 0);      // tile t+2
                 mfma_head(C1{}, q1);                       // tile t+1
                 __builtin_amdgcn_sched_barrier(0);
-                if (t + 3 < nIt) store_tiles(1, tail_q && t + 3 == last);   // tile t+3
-                if (t + 4 < nIt) load_tiles();             // tile t+4
+                if (STEADY || t + 3 < nIt) store_tiles(1, !STEADY && tail_q && t + 3 == last);   // tile t+3
+                if (STEADY || t + 4 < nIt) load_tiles(steady_c);   // tile t+4
                 __builtin_amdgcn_sched_barrier(0);
                 mfma_tail(C1{}, q1);
                 __builtin_amdgcn_sched_barrier(0);
                 __syncthreads();
-            }
+            };
+            for (; t + 5 < nIt; t += 2) step_pair(std::true_type{});
+            for (; t + 2 <= nIt; t += 2) step_pair(std::false_type{});
             if (t < nIt) { mfma_head(C0{}, qlast); mfma_tail(C0{}, qlast); }   // odd number of tiles: the last one
         }
     }
