@@ -1361,7 +1361,11 @@ static void launch_cross_f64_t(const CrossParams& p0, hipStream_t s) {
     p.div_opix = make_fastdiv((uint32_t)(p.owy * p.owx));
     const long long total = (long long)p.ntiles_m * p.ntiles_n * p.owy * p.owx;
     const unsigned blocks = (unsigned)(((total + 7) / 8) * 8);
-    if ((p.in.C & 3) == 0) hipLaunchKernelGGL((cross_kernel<BM, BN, true, false, double>), dim3(blocks), dim3(256), 0, s, p);
+    const bool vec = (p.in.C & 3) == 0;
+    const bool dense = p.kh * p.kw == 1 && p.in.wy * p.in.wx == 1 && p.owy * p.owx == 1 && p.sh == 1 && p.sw == 1 &&
+                       p.ph == 0 && p.pw == 0;
+    if (dense && vec) hipLaunchKernelGGL((cross_kernel<BM, BN, true, true, double>), dim3(blocks), dim3(256), 0, s, p);
+    else if (vec) hipLaunchKernelGGL((cross_kernel<BM, BN, true, false, double>), dim3(blocks), dim3(256), 0, s, p);
     else hipLaunchKernelGGL((cross_kernel<BM, BN, false, false, double>), dim3(blocks), dim3(256), 0, s, p);
 }
 static void launch_cross_f64(const CrossParams& p, hipStream_t s) {
