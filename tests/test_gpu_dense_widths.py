@@ -1,0 +1,62 @@
+"""GPU parity on chains of dense layers of randomly drawn widths (3 to 400 inputs, 5 to 330 neurons per layer) with 1 to
+130 boxes per pass.  The width of a layer is the length of the contraction of the crossing below it, so the draws vary
+the number of 16-channel steps (1 to 25: the branch-free steady part of the loop runs for none, some or most of
+them), the ragged last step (widths that are no multiple of 16, and of 4: scalar loads) and, through the number of rows
+of a launch, the tile shape (32x32, 64x32, 64x64).  Both coefficient storages are compared with the oracle given the
+same relaxation slopes: float32 storage to 1e-3 (the bar of Section 4's soundness discussion as the test suite reads
+it: looser by at most 1e-3 * (1 + |bound|)), float64 storage to 1e-8; neither may lie inside the oracle's interval by
+more than 1e-12."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from parity import affine_read_layers, analysed_layers, make_gpu, make_oracle, oracle_with_gpu_relaxation
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    torch.cuda.init()
+
+
+def dense_chain(seed):
+    rng = np.random.default_rng(seed)
+    net = wl.Net(f"dense_chain_{seed}", (1, 1, int(rng.integers(3, 400))))
+
+    def dense(src, n_out):
+        n = net.n_neurons(src)
+        Wt = (rng.standard_normal((n_out, n)) * np.sqrt(2.0 / n)).astype(np.float32)
+        return net.dense(src, Wt, (rng.standard_normal(n_out) * 0.1).astype(np.float32))
+
+    cur = 0
+    for _ in range(int(rng.integers(2, 5))):
+        cur = net.relu(dense(cur, int(rng.integers(5, 330))))
+    dense(cur, int(rng.integers(2, 40)))
+    net.eps = float(rng.choice([0.001, 0.004, 0.01]))
+    return net
+
+
+@pytest.mark.parametrize("seed", range(32))
+def test_dense_chain(seed):
+    net = dense_chain(seed)
+    rng = np.random.default_rng(50_000 + seed)
+    nb = int([1, 2, 7, 40, 130][seed % 5])
+    X = rng.random((nb, net.n_in)).astype(np.float32)
+    layers = sorted(set(analysed_layers(net)) | set(affine_read_layers(net)))
+    for bits, bar in ((32, 1e-3), (64, 1e-8)):
+        g = make_gpu(net)
+        g.set_coefficient_storage(bits)
+        g.analyze_batch(X, net.eps)
+        for b in sorted({0, nb - 1, int(rng.integers(0, nb))}):
+            o = make_oracle(net)
+            oracle_with_gpu_relaxation(net, o, g, X[b], net.eps, batch_index=b)
+            for lid in layers:
+                olo, ohi = o.get_bounds(lid)
+                glo, ghi = g.get_bounds_f64(lid, b)
+                loose = max(np.max((olo - glo) / (1 + np.abs(olo))), np.max((ghi - ohi) / (1 + np.abs(ohi))))
+                inside = max(np.max((glo - olo) / (1 + np.abs(olo))), np.max((ohi - ghi) / (1 + np.abs(ohi))))
+                assert loose <= bar and inside <= 1e-12, (bits, seed, nb, b, lid, loose, inside)
