@@ -67,7 +67,13 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 2) void cross_ker
     constexpr bool A64 = std::is_same<CT, double>::value;
     constexpr uint32_t CS = sizeof(CT);
     constexpr int BK = 16;
-    constexpr int LDK = 18;                          // doubles per tile row: 144 B, keeps 16-byte alignment, spreads banks
+    // float32 blocks are staged in LDS as they are and converted when a fragment is used: half the LDS traffic of a
+    // float64 tile (the kernel's LDS reads and writes take a large share of the LDS bandwidth at full MFMA rate), the
+    // same number of conversions per step for A, and the filter's conversions move from the staging to the use
+    constexpr bool LDS32 = !A64;
+    using LT = typename std::conditional<LDS32, float, double>::type;
+    // elements per tile row: keeps 16-byte alignment, spreads banks (float: 80 B, 16 lanes x 16 B hit 64 distinct banks)
+    constexpr int LDK = LDS32 ? 20 : 18;
     constexpr int WAVES_N = (BN >= 64 || BM < 64) ? 2 : 1;
     constexpr int WAVES_M = 4 / WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
@@ -76,8 +82,8 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 2) void cross_ker
     constexpr int BPT = (BN + 63) / 64;             // B columns per thread
     static_assert(TM >= 1 && TN >= 1, "tile");
 
-    __shared__ __attribute__((aligned(16))) double As[2][BM][LDK];
-    __shared__ __attribute__((aligned(16))) double Bs[2][BN][LDK];
+    __shared__ __attribute__((aligned(16))) LT As[2][BM][LDK];
+    __shared__ __attribute__((aligned(16))) LT Bs[2][BN][LDK];
     __shared__ unsigned long long s_tapmask;
     // per tile row, for the epilogue: where the row's output pixel sits in the relaxation array of the input layer and
     // in the addend block (-1: outside its window).  Worked out once per row by the thread that sets up the row's
@@ -325,10 +331,10 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 2) void cross_ker
         }
     };
     // LDS addresses of this thread's stores and MFMA operand loads (fixed; the buffer index is an immediate)
-    double* const a_st = &As[0][ld_row][q4];
-    double* const b_st = &Bs[0][ld_row][q4];
-    const double* const a_ld = &As[0][wm * WTM + lm][4 * lk];
-    const double* const b_ld = &Bs[0][wn * WTN + lm][4 * lk];
+    LT* const a_st = &As[0][ld_row][q4];
+    LT* const b_st = &Bs[0][ld_row][q4];
+    const LT* const a_ld = &As[0][wm * WTM + lm][4 * lk];
+    const LT* const b_ld = &Bs[0][wn * WTN + lm][4 * lk];
     // Last K step of a dense layer whose channel count is no multiple of 16 (e.g. 500 = 31*16 + 4): only tail_q of
     // the 4 channel quads exist.  Stored as usual they would sit in k-positions 0..4*tail_q-1, one in each of the 4
     // MFMA steps of the tile; stored transposed (channel j of quad q at k-position 4*j + q, for A and B alike) quad q
@@ -341,17 +347,20 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 2) void cross_ker
 #pragma unroll
                 for (int i = 0; i < APT; ++i) {
                     if (BM % 64 == 0 || ld_row + 64 * i < BM) {    // (ld_row < 64)
-                        double* dst = &As[0][ld_row][0] + (buf * BM + 64 * i) * LDK + q;
+                        LT* dst = &As[0][ld_row][0] + (buf * BM + 64 * i) * LDK + q;
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) dst[4 * j] = a_val(i, j);
+                        for (int j = 0; j < 4; ++j) {
+                            if constexpr (LDS32) dst[4 * j] = a_raw[i].v[j];
+                            else dst[4 * j] = a_val(i, j);
+                        }
                     }
                 }
 #pragma unroll
                 for (int i = 0; i < BPT; ++i) {
                     if (BN % 64 == 0 || ld_row + 64 * i < BN) {
-                        double* dst = &Bs[0][ld_row][0] + (buf * BN + 64 * i) * LDK + q;
+                        LT* dst = &Bs[0][ld_row][0] + (buf * BN + 64 * i) * LDK + q;
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) dst[4 * j] = (double)b_raw[i].v[j];
+                        for (int j = 0; j < 4; ++j) dst[4 * j] = (LT)b_raw[i].v[j];
                     }
                 }
             }
@@ -360,17 +369,27 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 2) void cross_ker
 #pragma unroll
         for (int i = 0; i < APT; ++i) {
             if (BM % 64 == 0 || ld_row + 64 * i < BM) {    // (ld_row < 64)
-                double2* dst = reinterpret_cast<double2*>(a_st + (buf * BM + 64 * i) * LDK);
-                dst[0] = make_double2(a_val(i, 0), a_val(i, 1));
-                dst[1] = make_double2(a_val(i, 2), a_val(i, 3));
+                if constexpr (LDS32) {
+                    *reinterpret_cast<float4*>(a_st + (buf * BM + 64 * i) * LDK) =
+                        make_float4(a_raw[i].v[0], a_raw[i].v[1], a_raw[i].v[2], a_raw[i].v[3]);
+                } else {
+                    double2* dst = reinterpret_cast<double2*>(a_st + (buf * BM + 64 * i) * LDK);
+                    dst[0] = make_double2(a_val(i, 0), a_val(i, 1));
+                    dst[1] = make_double2(a_val(i, 2), a_val(i, 3));
+                }
             }
         }
 #pragma unroll
         for (int i = 0; i < BPT; ++i) {
             if (BN % 64 == 0 || ld_row + 64 * i < BN) {
-                double2* dst = reinterpret_cast<double2*>(b_st + (buf * BN + 64 * i) * LDK);
-                dst[0] = make_double2((double)b_raw[i].v[0], (double)b_raw[i].v[1]);
-                dst[1] = make_double2((double)b_raw[i].v[2], (double)b_raw[i].v[3]);
+                if constexpr (LDS32) {
+                    *reinterpret_cast<float4*>(b_st + (buf * BN + 64 * i) * LDK) =
+                        make_float4(b_raw[i].v[0], b_raw[i].v[1], b_raw[i].v[2], b_raw[i].v[3]);
+                } else {
+                    double2* dst = reinterpret_cast<double2*>(b_st + (buf * BN + 64 * i) * LDK);
+                    dst[0] = make_double2((double)b_raw[i].v[0], (double)b_raw[i].v[1]);
+                    dst[1] = make_double2((double)b_raw[i].v[2], (double)b_raw[i].v[3]);
+                }
             }
         }
     };
@@ -384,9 +403,19 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 2) void cross_ker
     {
         // MFMA operand fragments of one K step: [half of the lane's 4 k-values][16-row tile], two sets so that the next
         // step's fragments are fetched from LDS while the MFMAs of the current step run
-        double2 av[2][2][TM], bv[2][2][TN];
+        double2 av[2][2][LDS32 ? 1 : TM], bv[2][2][LDS32 ? 1 : TN];
+        float4 av32[2][LDS32 ? TM : 1], bv32[2][LDS32 ? TN : 1];
         auto read_frags = [&](auto set_c, int buf) {
             constexpr int set = decltype(set_c)::value;
+            if constexpr (LDS32) {
+    #pragma unroll
+                for (int i = 0; i < TM; ++i)
+                    av32[set][i] = *reinterpret_cast<const float4*>(a_ld + (buf * BM + i * 16) * LDK);
+    #pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    bv32[set][j] = *reinterpret_cast<const float4*>(b_ld + (buf * BN + j * 16) * LDK);
+                return;
+            }
     #pragma unroll
             for (int h = 0; h < 2; ++h) {
     #pragma unroll
@@ -400,6 +429,21 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 2) void cross_ker
         // quarter q of a step's 16 MFMAs: k-value q of each lane's four (halves h = q/2, component q%2)
         auto mfma_q = [&](auto set_c, auto q_c) {
             constexpr int set = decltype(set_c)::value, q = decltype(q_c)::value, h = q >> 1;
+            if constexpr (LDS32) {
+                double a[TM], b[TN];
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+                    a[i] = (double)(q == 0 ? av32[set][i].x : q == 1 ? av32[set][i].y : q == 2 ? av32[set][i].z : av32[set][i].w);
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    b[j] = (double)(q == 0 ? bv32[set][j].x : q == 1 ? bv32[set][j].y : q == 2 ? bv32[set][j].z : bv32[set][j].w);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
+                return;
+            }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
