@@ -63,7 +63,7 @@ __device__ __forceinline__ void epilogue_row_info(const CrossParams& p, const Ro
 // CT: storage type of the coefficient blocks (float; double for the float64 storage mode, which only this form and
 // cross_pool_kernel serve: 32 bytes per 4 channels, no conversion, no rounding but the final one to float64).
 template <int BM, int BN, bool VEC, bool DENSE, typename CT = float>
-__global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 2) void cross_kernel(const CrossParams p) {
+__global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? (std::is_same<CT, float>::value ? 5 : 4) : 2) void cross_kernel(const CrossParams p) {
     constexpr bool A64 = std::is_same<CT, double>::value;
     constexpr uint32_t CS = sizeof(CT);
     constexpr int BK = 16;
