@@ -63,7 +63,7 @@ __device__ __forceinline__ void epilogue_row_info(const CrossParams& p, const Ro
 // CT: storage type of the coefficient blocks (float; double for the float64 storage mode, which only this form and
 // cross_pool_kernel serve: 32 bytes per 4 channels, no conversion, no rounding but the final one to float64).
 template <int BM, int BN, bool VEC, bool DENSE, typename CT = float>
-__global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? (std::is_same<CT, float>::value ? 5 : 4) : 2) void cross_kernel(const CrossParams p) {
+__global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? (std::is_same<CT, float>::value && !DENSE ? 5 : 4) : 2) void cross_kernel(const CrossParams p) {
     constexpr bool A64 = std::is_same<CT, double>::value;
     constexpr uint32_t CS = sizeof(CT);
     constexpr int BK = 16;
@@ -74,6 +74,12 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? (std::is_same<CT, flo
     using LT = typename std::conditional<LDS32, float, double>::type;
     // elements per tile row: keeps 16-byte alignment, spreads banks (float: 80 B, 16 lanes x 16 B hit 64 distinct banks)
     constexpr int LDK = LDS32 ? 20 : 18;
+    // dense layers: the weights are read from their float64 copy and staged as float64, so that no conversion of the
+    // filter operand is left in the K loop (the copy of a dense layer is small and stays in L2)
+    constexpr bool BL32 = LDS32 && !DENSE;
+    constexpr bool BG64 = DENSE && VEC && !A64;      // the host launches this form only with p.wt64 present
+    using LTB = typename std::conditional<BL32, float, double>::type;
+    constexpr int LDKB = BL32 ? 20 : 18;
     constexpr int WAVES_N = (BN >= 64 || BM < 64) ? 2 : 1;
     constexpr int WAVES_M = 4 / WAVES_N;
     constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
@@ -83,7 +89,7 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? (std::is_same<CT, flo
     static_assert(TM >= 1 && TN >= 1, "tile");
 
     __shared__ __attribute__((aligned(16))) LT As[2][BM][LDK];
-    __shared__ __attribute__((aligned(16))) LT Bs[2][BN][LDK];
+    __shared__ __attribute__((aligned(16))) LTB Bs[2][BN][LDKB];
     __shared__ unsigned long long s_tapmask;
     // per tile row, for the epilogue: where the row's output pixel sits in the relaxation array of the input layer and
     // in the addend block (-1: outside its window).  Worked out once per row by the thread that sets up the row's
@@ -120,6 +126,8 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? (std::is_same<CT, flo
         (void*)(reinterpret_cast<const CT*>(p.in.data) + (size_t)r_tile * row_elems), 0, (int)((uint32_t)rows_here * row_elems * CS), 0x00020000);
     const __amdgpu_buffer_rsrc_t rsrcB =
         __builtin_amdgcn_make_buffer_rsrc((void*)p.wt, 0, (int)((uint32_t)taps * N * Ck * 4u), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrcB64 = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(BG64 ? (const void*)p.wt64 : (const void*)p.wt), 0, (int)((uint32_t)taps * N * Ck * (BG64 ? 8u : 4u)), 0x00020000);
 
     // ---- loader bookkeeping: thread -> (tile row ld_row (+64*i), channel quad q4)
     const int ld_row = tid >> 2, q4 = (tid & 3) * 4;
@@ -278,6 +286,11 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? (std::is_same<CT, flo
     // channel advance goes through the scalar offset operand of the buffer load.
     F4 a_raw[APT], b_raw[BPT];
     double a_raw64[A64 ? APT : 1][4];
+    double b_raw64[BG64 ? BPT : 1][4];
+    auto b_val = [&](int i, int j) -> double {
+        if constexpr (BG64) return b_raw64[i][j];
+        else return (double)b_raw[i].v[j];
+    };
     auto a_val = [&](int i, int j) -> double {
         if constexpr (A64) return a_raw64[i][j];
         else return (double)a_raw[i].v[j];
@@ -305,9 +318,17 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? (std::is_same<CT, flo
             }
 #pragma unroll
             for (int i = 0; i < BPT; ++i) {
-                uint4_t v = __builtin_amdgcn_raw_buffer_load_b128(rsrcB, (int)b_voff[i], (int)soffB, 0);
-                b_raw[i].v[0] = __uint_as_float(v.x); b_raw[i].v[1] = __uint_as_float(v.y);
-                b_raw[i].v[2] = __uint_as_float(v.z); b_raw[i].v[3] = __uint_as_float(v.w);
+                if constexpr (BG64) {       // byte offsets of the float64 copy are twice those of the float32 one
+                    const uint32_t o = b_voff[i] == kOOB ? kOOB : 2u * b_voff[i];
+                    const uint4_t v0 = __builtin_amdgcn_raw_buffer_load_b128(rsrcB64, (int)o, (int)(2u * soffB), 0);
+                    const uint4_t v1 = __builtin_amdgcn_raw_buffer_load_b128(rsrcB64, (int)(o + 16u), (int)(2u * soffB), 0);
+                    b_raw64[i][0] = __hiloint2double((int)v0.y, (int)v0.x); b_raw64[i][1] = __hiloint2double((int)v0.w, (int)v0.z);
+                    b_raw64[i][2] = __hiloint2double((int)v1.y, (int)v1.x); b_raw64[i][3] = __hiloint2double((int)v1.w, (int)v1.z);
+                } else {
+                    uint4_t v = __builtin_amdgcn_raw_buffer_load_b128(rsrcB, (int)b_voff[i], (int)soffB, 0);
+                    b_raw[i].v[0] = __uint_as_float(v.x); b_raw[i].v[1] = __uint_as_float(v.y);
+                    b_raw[i].v[2] = __uint_as_float(v.z); b_raw[i].v[3] = __uint_as_float(v.w);
+                }
             }
         } else {                                                    // ragged last chunk of a tap, or unaligned channels
             const bool dok = q4 < rem;
@@ -318,8 +339,11 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? (std::is_same<CT, flo
                 else a_raw[i] = buf_ld4<VEC>(rsrcA, off, rem - q4);
             }
 #pragma unroll
-            for (int i = 0; i < BPT; ++i)
-                b_raw[i] = buf_ld4<VEC>(rsrcB, (dok && b_voff[i] != kOOB) ? b_voff[i] + soffB : kOOB, rem - q4);
+            for (int i = 0; i < BPT; ++i) {
+                const bool ok = dok && b_voff[i] != kOOB;
+                if constexpr (BG64) buf_ld4_f64<VEC>(rsrcB64, ok ? 2u * (b_voff[i] + soffB) : kOOB, rem - q4, b_raw64[i]);
+                else b_raw[i] = buf_ld4<VEC>(rsrcB, ok ? b_voff[i] + soffB : kOOB, rem - q4);
+            }
         }
         ld_d0 += BK;
         if constexpr (!WHOLE) {
@@ -332,9 +356,9 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? (std::is_same<CT, flo
     };
     // LDS addresses of this thread's stores and MFMA operand loads (fixed; the buffer index is an immediate)
     LT* const a_st = &As[0][ld_row][q4];
-    LT* const b_st = &Bs[0][ld_row][q4];
+    LTB* const b_st = &Bs[0][ld_row][q4];
     const LT* const a_ld = &As[0][wm * WTM + lm][4 * lk];
-    const LT* const b_ld = &Bs[0][wn * WTN + lm][4 * lk];
+    const LTB* const b_ld = &Bs[0][wn * WTN + lm][4 * lk];
     // Last K step of a dense layer whose channel count is no multiple of 16 (e.g. 500 = 31*16 + 4): only tail_q of
     // the 4 channel quads exist.  Stored as usual they would sit in k-positions 0..4*tail_q-1, one in each of the 4
     // MFMA steps of the tile; stored transposed (channel j of quad q at k-position 4*j + q, for A and B alike) quad q
@@ -358,9 +382,12 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? (std::is_same<CT, flo
 #pragma unroll
                 for (int i = 0; i < BPT; ++i) {
                     if (BN % 64 == 0 || ld_row + 64 * i < BN) {
-                        LT* dst = &Bs[0][ld_row][0] + (buf * BN + 64 * i) * LDK + q;
+                        LTB* dst = &Bs[0][ld_row][0] + (buf * BN + 64 * i) * LDKB + q;
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) dst[4 * j] = (LT)b_raw[i].v[j];
+                        for (int j = 0; j < 4; ++j) {
+                            if constexpr (BL32) dst[4 * j] = b_raw[i].v[j];
+                            else dst[4 * j] = b_val(i, j);
+                        }
                     }
                 }
             }
@@ -382,13 +409,13 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? (std::is_same<CT, flo
 #pragma unroll
         for (int i = 0; i < BPT; ++i) {
             if (BN % 64 == 0 || ld_row + 64 * i < BN) {
-                if constexpr (LDS32) {
-                    *reinterpret_cast<float4*>(b_st + (buf * BN + 64 * i) * LDK) =
+                if constexpr (BL32) {
+                    *reinterpret_cast<float4*>(b_st + (buf * BN + 64 * i) * LDKB) =
                         make_float4(b_raw[i].v[0], b_raw[i].v[1], b_raw[i].v[2], b_raw[i].v[3]);
                 } else {
-                    double2* dst = reinterpret_cast<double2*>(b_st + (buf * BN + 64 * i) * LDK);
-                    dst[0] = make_double2((double)b_raw[i].v[0], (double)b_raw[i].v[1]);
-                    dst[1] = make_double2((double)b_raw[i].v[2], (double)b_raw[i].v[3]);
+                    double2* dst = reinterpret_cast<double2*>(b_st + (buf * BN + 64 * i) * LDKB);
+                    dst[0] = make_double2(b_val(i, 0), b_val(i, 1));
+                    dst[1] = make_double2(b_val(i, 2), b_val(i, 3));
                 }
             }
         }
@@ -403,17 +430,25 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? (std::is_same<CT, flo
     {
         // MFMA operand fragments of one K step: [half of the lane's 4 k-values][16-row tile], two sets so that the next
         // step's fragments are fetched from LDS while the MFMAs of the current step run
-        double2 av[2][2][LDS32 ? 1 : TM], bv[2][2][LDS32 ? 1 : TN];
-        float4 av32[2][LDS32 ? TM : 1], bv32[2][LDS32 ? TN : 1];
+        double2 av[2][2][LDS32 ? 1 : TM], bv[2][2][BL32 ? 1 : TN];
+        float4 av32[2][LDS32 ? TM : 1], bv32[2][BL32 ? TN : 1];
         auto read_frags = [&](auto set_c, int buf) {
             constexpr int set = decltype(set_c)::value;
             if constexpr (LDS32) {
     #pragma unroll
                 for (int i = 0; i < TM; ++i)
                     av32[set][i] = *reinterpret_cast<const float4*>(a_ld + (buf * BM + i * 16) * LDK);
+                if constexpr (BL32) {
     #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    bv32[set][j] = *reinterpret_cast<const float4*>(b_ld + (buf * BN + j * 16) * LDK);
+                    for (int j = 0; j < TN; ++j)
+                        bv32[set][j] = *reinterpret_cast<const float4*>(b_ld + (buf * BN + j * 16) * LDKB);
+                } else {
+    #pragma unroll
+                    for (int h = 0; h < 2; ++h)
+    #pragma unroll
+                        for (int j = 0; j < TN; ++j)
+                            bv[set][h][j] = *reinterpret_cast<const double2*>(b_ld + (buf * BN + j * 16) * LDKB + 2 * h);
+                }
                 return;
             }
     #pragma unroll
@@ -423,7 +458,7 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? (std::is_same<CT, flo
                     av[set][h][i] = *reinterpret_cast<const double2*>(a_ld + (buf * BM + i * 16) * LDK + 2 * h);
     #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    bv[set][h][j] = *reinterpret_cast<const double2*>(b_ld + (buf * BN + j * 16) * LDK + 2 * h);
+                    bv[set][h][j] = *reinterpret_cast<const double2*>(b_ld + (buf * BN + j * 16) * LDKB + 2 * h);
             }
         };
         // quarter q of a step's 16 MFMAs: k-value q of each lane's four (halves h = q/2, component q%2)
@@ -436,7 +471,8 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? (std::is_same<CT, flo
                     a[i] = (double)(q == 0 ? av32[set][i].x : q == 1 ? av32[set][i].y : q == 2 ? av32[set][i].z : av32[set][i].w);
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    b[j] = (double)(q == 0 ? bv32[set][j].x : q == 1 ? bv32[set][j].y : q == 2 ? bv32[set][j].z : bv32[set][j].w);
+                    if constexpr (BL32) b[j] = (double)(q == 0 ? bv32[set][j].x : q == 1 ? bv32[set][j].y : q == 2 ? bv32[set][j].z : bv32[set][j].w);
+                    else b[j] = (q & 1) ? bv[set][h][j].y : bv[set][h][j].x;
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -1267,7 +1303,10 @@ static void launch_cross_t(const CrossParams& p0, hipStream_t s) {
     if constexpr (BN >= 32 && BM <= 64) {
         const bool dense = p.kh * p.kw == 1 && p.in.wy * p.in.wx == 1 && p.owy * p.owx == 1 && p.sh == 1 && p.sw == 1 &&
                            p.ph == 0 && p.pw == 0;
-        if (dense) {
+        // the 16-byte form reads the weights' float64 copy through a 32-bit range: the general form serves a layer
+        // without the copy or beyond that size
+        const bool copy_ok = p.wt64 != nullptr && (long long)p.Co * p.in.C * 8 < (1ll << 31);
+        if (dense && (!vec || copy_ok)) {
             if (vec) hipLaunchKernelGGL((cross_kernel<BM, BN, true, true>), dim3(blocks), dim3(256), 0, s, p);
             else hipLaunchKernelGGL((cross_kernel<BM, BN, false, true>), dim3(blocks), dim3(256), 0, s, p);
             return;
