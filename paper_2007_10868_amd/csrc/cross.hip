@@ -77,7 +77,7 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? (std::is_same<CT, flo
     // dense layers: the weights are read from their float64 copy and staged as float64, so that no conversion of the
     // filter operand is left in the K loop (the copy of a dense layer is small and stays in L2)
     constexpr bool BL32 = LDS32 && !DENSE;
-    constexpr bool BG64 = DENSE && VEC && !A64;      // the host launches this form only with p.wt64 present
+    constexpr bool BG64 = DENSE && VEC;     // the host launches this form only with p.wt64 present
     using LTB = typename std::conditional<BL32, float, double>::type;
     constexpr int LDKB = BL32 ? 20 : 18;
     constexpr int WAVES_N = (BN >= 64 || BM < 64) ? 2 : 1;
@@ -1447,7 +1447,8 @@ static void launch_cross_f64_t(const CrossParams& p0, hipStream_t s) {
     const bool vec = (p.in.C & 3) == 0;
     const bool dense = p.kh * p.kw == 1 && p.in.wy * p.in.wx == 1 && p.owy * p.owx == 1 && p.sh == 1 && p.sw == 1 &&
                        p.ph == 0 && p.pw == 0;
-    if (dense && vec) hipLaunchKernelGGL((cross_kernel<BM, BN, true, true, double>), dim3(blocks), dim3(256), 0, s, p);
+    const bool copy_ok = p.wt64 != nullptr && (long long)p.Co * p.in.C * 8 < (1ll << 31);   // see launch_cross_t
+    if (dense && vec && copy_ok) hipLaunchKernelGGL((cross_kernel<BM, BN, true, true, double>), dim3(blocks), dim3(256), 0, s, p);
     else if (vec) hipLaunchKernelGGL((cross_kernel<BM, BN, true, false, double>), dim3(blocks), dim3(256), 0, s, p);
     else hipLaunchKernelGGL((cross_kernel<BM, BN, false, false, double>), dim3(blocks), dim3(256), 0, s, p);
 }
