@@ -46,7 +46,7 @@ struct Layer {
     std::vector<double> beff_host; // [C] summed bias of those layers (float64: the sum of two float32 is kept exact)
     // device
     float* d_wt = nullptr;
-    double* d_wt64 = nullptr;      // the same in float64: dense layers (cross_kernel's dense form) and layers with at most 4 input channels (cross_image_kernel)
+    double* d_wt64 = nullptr;      // the same in float64: the filter operand of the float64 MFMAs, read without conversion
     float* d_wti = nullptr;
     float* d_bias = nullptr;
     double* d_beff = nullptr;
@@ -520,8 +520,7 @@ gp_status ensure_device(gp_net* net, int batch) {
             if (!l.wt_host.empty() && !l.d_wt) {
                 HIP_TRY(net, hipMalloc((void**)&l.d_wt, l.wt_host.size() * sizeof(float)));
                 HIP_TRY(net, hipMemcpy(l.d_wt, l.wt_host.data(), l.wt_host.size() * sizeof(float), hipMemcpyHostToDevice));
-                const Layer& pr = net->L[l.a];
-                if (l.type == T_DENSE || (long long)pr.C <= 4) {
+                {   // (twice the bytes of the float32 weights again; ResNet-34: 170 MB)
                     std::vector<double> w64(l.wt_host.begin(), l.wt_host.end());
                     HIP_TRY(net, hipMalloc((void**)&l.d_wt64, w64.size() * sizeof(double)));
                     HIP_TRY(net, hipMemcpy(l.d_wt64, w64.data(), w64.size() * sizeof(double), hipMemcpyHostToDevice));

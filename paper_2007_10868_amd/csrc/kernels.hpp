@@ -64,7 +64,7 @@ struct BlockDesc {
 struct CrossParams {       // one back-substitution step through an affine layer (Algorithm 1 per row)
     BlockDesc in;          // block over the layer's OUTPUT neurons
     const float* wt;       // [kh*kw][Co][in.C]  (the layer's own output channels innermost)
-    const double* wt64;    // the same values in float64; present (non-null) for dense layers and when Co <= 4
+    const double* wt64;    // the same values in float64 (every layer with weights has the copy)
     double pool_scale;     // 0: a layer with a filter; else the layer is average pooling (channels pass through,
                            //   Co == in.C, wt unused) and this is 1/(kh*kw)
     int kh, kw, sh, sw, ph, pw;
