@@ -14,6 +14,11 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "deeppoly_oracle.c")
 _LIB = os.path.join(_HERE, "libdeeppoly_oracle.so")
+# The mutation checks of the test suite (tests/test_oracle_mutations.py) point this at a copy of the C file with
+# one mistake planted, and run single pins against it in a process of their own; nothing else sets it.
+if os.environ.get("DEEPPOLY_ORACLE_SRC"):
+    _SRC = os.path.abspath(os.environ["DEEPPOLY_ORACLE_SRC"])
+    _LIB = os.path.splitext(_SRC)[0] + ".so"
 _lib = None
 
 # -frounding-math: the code switches the rounding mode; -ffp-contract=off: no fused multiply-add

@@ -84,6 +84,7 @@ struct Plan {
 const double kRoundCoef = 0x1p-24 * (1.0 + 0x1p-20);   // float32 rounding of a float64 value
 const double kRoundCoef64 = 0x1p-53 * (1.0 + 0x1p-20); // rounding of a product or sum of two float64 values (float64 storage)
 const int kMaxSlots = 6;
+const long long kMaxLayerWeights = 1LL << 28;
 
 }  // namespace
 
@@ -507,6 +508,43 @@ bool has_bounds(const gp_net* net, int lid) {
     return lid == 0 || l.type == T_RELU || l.need_bounds;
 }
 
+// everything whose size depends on the batch
+void release_batch_state(gp_net* net) {
+    for (auto& l : net->L) free_layer_bounds(l);
+    dfree(net->d_labels); net->d_labels = nullptr;
+    dfree(net->d_margins); net->d_margins = nullptr;
+    dfree(net->d_xmax_all); net->d_xmax_all = nullptr;
+}
+
+gp_status allocate_batch_state(gp_net* net, int batch) {
+    HIP_TRY(net, hipMalloc((void**)&net->d_xmax_all, sizeof(double) * batch * net->L.size()));
+    for (size_t i = 0; i < net->L.size(); ++i) {
+        Layer& l = net->L[i];
+        size_t cnt = (size_t)l.n * batch;
+        // with early termination every layer carries intervals (its interval image at least)
+        if (has_bounds(net, (int)i) || net->early) {
+            HIP_TRY(net, hipMalloc((void**)&l.d_lo, cnt * sizeof(double)));
+            HIP_TRY(net, hipMalloc((void**)&l.d_hi, cnt * sizeof(double)));
+            l.d_xmax = net->d_xmax_all + i * (size_t)batch;
+        }
+        if (net->early && l.need_bounds && l.type != T_RELU && i > 0)
+            HIP_TRY(net, hipMalloc((void**)&l.d_term, cnt * sizeof(int)));
+        if (net->float_inference && (is_affine(l) || l.type == T_ADD))
+            HIP_TRY(net, hipMalloc((void**)&l.d_eta, cnt * sizeof(double)));
+        if (net->float_inference && l.type == T_ADD && (summand_passes_eta(net, l.a) || summand_passes_eta(net, l.b)))
+            HIP_TRY(net, hipMalloc((void**)&l.d_eta_thru, cnt * sizeof(double)));
+        if (l.type == T_RELU) {
+            HIP_TRY(net, hipMalloc((void**)&l.d_grl, cnt * sizeof(float)));
+            HIP_TRY(net, hipMalloc((void**)&l.d_rho, cnt * sizeof(double)));
+            HIP_TRY(net, hipMalloc((void**)&l.d_kap, cnt * sizeof(double)));
+        }
+    }
+    long long nout = net->L.back().n;
+    HIP_TRY(net, hipMalloc((void**)&net->d_labels, sizeof(int) * batch));
+    HIP_TRY(net, hipMalloc((void**)&net->d_margins, sizeof(float) * batch * std::max<long long>(nout - 1, 1)));
+    return GP_OK;
+}
+
 gp_status ensure_device(gp_net* net, int batch) {
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) return fail(net, GP_ERR_DEVICE, "no HIP device");
@@ -540,36 +578,15 @@ gp_status ensure_device(gp_net* net, int batch) {
         net->weights_uploaded = true;
     }
     if (net->batch != batch) {
+        // Nothing is sized for any batch while this block runs: batch = 0 until the last allocation has succeeded, and a
+        // failure on the way frees what was allocated, so that the next call (at whatever batch) starts from scratch
+        // instead of launching kernels on buffers that are gone or sized for the batch that failed.
         drop_graph(net);
-        for (auto& l : net->L) free_layer_bounds(l);
-        dfree(net->d_labels); net->d_labels = nullptr;
-        dfree(net->d_margins); net->d_margins = nullptr;
-        dfree(net->d_xmax_all); net->d_xmax_all = nullptr;
-        HIP_TRY(net, hipMalloc((void**)&net->d_xmax_all, sizeof(double) * batch * net->L.size()));
-        for (size_t i = 0; i < net->L.size(); ++i) {
-            Layer& l = net->L[i];
-            size_t cnt = (size_t)l.n * batch;
-            // with early termination every layer carries intervals (its interval image at least)
-            if (has_bounds(net, (int)i) || net->early) {
-                HIP_TRY(net, hipMalloc((void**)&l.d_lo, cnt * sizeof(double)));
-                HIP_TRY(net, hipMalloc((void**)&l.d_hi, cnt * sizeof(double)));
-                l.d_xmax = net->d_xmax_all + i * (size_t)batch;
-            }
-            if (net->early && l.need_bounds && l.type != T_RELU && i > 0)
-                HIP_TRY(net, hipMalloc((void**)&l.d_term, cnt * sizeof(int)));
-            if (net->float_inference && (is_affine(l) || l.type == T_ADD))
-                HIP_TRY(net, hipMalloc((void**)&l.d_eta, cnt * sizeof(double)));
-            if (net->float_inference && l.type == T_ADD && (summand_passes_eta(net, l.a) || summand_passes_eta(net, l.b)))
-                HIP_TRY(net, hipMalloc((void**)&l.d_eta_thru, cnt * sizeof(double)));
-            if (l.type == T_RELU) {
-                HIP_TRY(net, hipMalloc((void**)&l.d_grl, cnt * sizeof(float)));
-                HIP_TRY(net, hipMalloc((void**)&l.d_rho, cnt * sizeof(double)));
-                HIP_TRY(net, hipMalloc((void**)&l.d_kap, cnt * sizeof(double)));
-            }
-        }
-        long long nout = net->L.back().n;
-        HIP_TRY(net, hipMalloc((void**)&net->d_labels, sizeof(int) * batch));
-        HIP_TRY(net, hipMalloc((void**)&net->d_margins, sizeof(float) * batch * std::max<long long>(nout - 1, 1)));
+        net->batch = 0;
+        net->analyzed = false;
+        release_batch_state(net);
+        const gp_status st = allocate_batch_state(net, batch);
+        if (st != GP_OK) { release_batch_state(net); (void)hipGetLastError(); return st; }   // (the sticky error is reported here, once)
         net->batch = batch;
     }
     return GP_OK;
@@ -656,6 +673,9 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
         }
     Rc_max = std::min(Rc_max, ((1LL << 31) - 256) / (nsign * max_pix));
     if (Rc_max <= 0) return fail(net, GP_ERR_WORKSPACE, "workspace of %lld bytes cannot hold one row (%lld bytes)", ws_bytes, tb);
+    // a tile of up to 128 rows of a block is addressed through 32-bit byte offsets of one buffer resource
+    if (128LL * pl.slot_elems * csize >= (1LL << 31))
+        return fail(net, GP_ERR_SHAPE, "a row's coefficient block of %lld elements is too long for the kernels' 32-bit offsets", pl.slot_elems);
     // when the rows do not fit at once, chunks start at multiples of 64 tasks (kernels that want rows grouped by position)
     if (Rc_max < total && Rc_max > 64) Rc_max -= Rc_max % 64;
     Rc_max = std::min(Rc_max, total);
@@ -1145,7 +1165,9 @@ gp_status gp_add_dense(gp_net* net, int32_t in_layer, int32_t out_dim, const flo
     if (out_dim <= 0 || !W) return fail(net, GP_ERR_ARG, "dense: bad out_dim or null weights");
     const Layer& p = net->L[in_layer];
     const long long n_in = p.n;
-    if (n_in * (long long)out_dim > (1LL << 31)) return fail(net, GP_ERR_SHAPE, "dense layer too large");
+    // the kernels address a layer's weights through 32-bit byte offsets of a buffer resource, also in their float64
+    // copy: 2^28 weights (2 GiB as float64) is the limit
+    if (n_in * (long long)out_dim >= kMaxLayerWeights) return fail(net, GP_ERR_SHAPE, "dense layer too large (2^28 weights or more)");
     if (!all_finite(W, (size_t)n_in * out_dim) || (b && !all_finite(b, out_dim)))
         return fail(net, GP_ERR_NONFINITE, "dense: NaN/Inf in weights");
     Layer l;
@@ -1186,6 +1208,7 @@ gp_status gp_add_conv2d(gp_net* net, int32_t in_layer, int32_t c_out, int32_t kh
     if (p.H + 2 * pad_h < kh || p.W + 2 * pad_w < kw) return fail(net, GP_ERR_SHAPE, "conv2d: kernel larger than padded input");
     if (pad_h >= kh || pad_w >= kw) return fail(net, GP_ERR_SHAPE, "conv2d: padding must be smaller than the kernel");
     const int ho = (p.H + 2 * pad_h - kh) / stride_h + 1, wo = (p.W + 2 * pad_w - kw) / stride_w + 1;
+    if ((long long)c_out * p.C * kh * kw >= kMaxLayerWeights) return fail(net, GP_ERR_SHAPE, "conv2d: filter too large (2^28 weights or more)");
     const size_t nw = (size_t)c_out * p.C * kh * kw;
     if (!all_finite(W, nw) || (b && !all_finite(b, c_out))) return fail(net, GP_ERR_NONFINITE, "conv2d: NaN/Inf in weights");
     if ((long long)c_out * ho * wo > (1LL << 30)) return fail(net, GP_ERR_SHAPE, "conv2d: layer too large");

@@ -114,11 +114,13 @@ def _np_backsub(net, mats, bounds, relax, start, c0, upper, candidates):
                 c = c + Mn @ d
 
 
-def np_deeppoly(net: wl.Net, lo0, hi0, lambda_policy=0, candidates=0, extra_rows=None):
+def np_deeppoly(net: wl.Net, lo0, hi0, lambda_policy=0, candidates=0, extra_rows=None, lam_override=None):
     """All-neurons-at-once DeepPoly with plain float64 matrices (no outward rounding).
 
     Returns {layer id: (l, u)} for the input, ReLU inputs, ReLU layers and the last layer.
-    extra_rows: optional matrix over the last layer; its lower bounds are returned under key "extra"."""
+    extra_rows: optional matrix over the last layer; its lower bounds are returned under key "extra".
+    lam_override: optional {ReLU layer id: array of 0/1}: the slope of the lower line to take for the neurons that
+    are unstable here (the choice switches at u = -l, where two analyses that differ in the last bits can disagree)."""
     nL = len(net.layers)
     mats = {i: affine_matrix(net, i) for i, L in enumerate(net.layers, start=1) if L["type"] in ("dense", "conv", "avgpool")}
     feeds_relu = {L["src"] for L in net.layers if L["type"] == "relu"}
@@ -143,6 +145,8 @@ def np_deeppoly(net: wl.Net, lo0, hi0, lambda_policy=0, candidates=0, extra_rows
             g = np.where(l >= 0, 1.0, np.where(u <= 0, 0.0, u / den))
             d = np.where(uns, -l * u / den, 0.0)
             lam_u = {0: (u > -l).astype(np.float64), 1: np.zeros_like(l), 2: np.ones_like(l)}[lambda_policy]
+            if lam_override is not None and i in lam_override:
+                lam_u = np.asarray(lam_override[i], np.float64)
             lam = np.where(l >= 0, 1.0, np.where(u <= 0, 0.0, lam_u))
             relax[i] = (g, d, lam)
             bounds[i] = (np.maximum(l, 0), np.maximum(u, 0))

@@ -145,6 +145,22 @@ def test_argument_errors():
     assert lib.gp_num_layers(None) == -1
 
 
+def test_layers_beyond_the_32_bit_offsets_of_the_kernels_are_refused():
+    """The crossing kernels address a layer's weights (also their float64 copy) through 32-bit byte offsets: a layer of
+    2^28 weights or more is an error at construction, before a single weight is read."""
+    lib = load_library()
+    h = C.c_void_p()
+    assert lib.gp_net_create(1 << 14, 1, 1, C.byref(h)) == 0
+    dummy = (C.c_float * 4)()
+    lid = C.c_int32(-1)
+    assert lib.gp_add_dense(h, 0, 1 << 14, dummy, None, C.byref(lid)) == 2
+    assert b"2^28" in lib.gp_last_error(h)
+    lib.gp_net_destroy(h)
+    assert lib.gp_net_create(1 << 13, 4, 4, C.byref(h)) == 0
+    assert lib.gp_add_conv2d(h, 0, 1 << 12, 3, 3, 1, 1, 1, 1, dummy, None, C.byref(lid)) == 2     # 2^13 * 2^12 * 9 weights
+    lib.gp_net_destroy(h)
+
+
 def test_unsupported_topology_is_reported_not_guessed():
     n = Net(4, 1, 1)
     a = n.add_dense(0, np.eye(4, dtype=np.float32))

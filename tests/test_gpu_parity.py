@@ -150,6 +150,65 @@ def test_small_networks_match_oracle_and_contain_samples(maker, eps):
     compare_all(net, g, o, what=net.name + " (GPU slopes)", contain_tol=STRICT_CONTAIN_TOL)
 
 
+SMALL_NETS = [(tiny_fc, 0.1), (odd_fc, 0.05), (quad_fc, 0.03), (tiny_conv, 0.05), (pad0_conv, 0.03), (tiny_resnet, 0.02),
+              (mid_resnet, 0.01), (rect_conv, 0.04), (strip_conv, 0.004), (strip5_conv, 0.002)]
+
+
+@pytest.mark.parametrize("maker,eps", SMALL_NETS)
+def test_small_networks_match_the_literal_interval_coefficient_oracle(maker, eps):
+    """The same comparison against the oracle in the paper's literal scheme (Section 4.1: every coefficient stays an
+    interval until the end of the back-substitution, nothing is re-centred on the way).  On networks of this depth the
+    two oracle modes agree to rounding noise, so the library must meet the same bar against either."""
+    net = maker(1)
+    c = np.random.default_rng(5).random(net.n_in).astype(np.float32)
+    g = make_gpu(net)
+    g.analyze(c, eps)
+    o = make_oracle(net)
+    o.set_collapse(False)
+    oracle_with_gpu_ties(net, o, g, c, eps)
+    worst = compare_all(net, g, o, what=net.name + " (literal oracle)")
+    print(net.name, "against the literal oracle: worst looseness / allowed =", worst)
+
+
+@pytest.mark.parametrize("cfg,inputs", [(0, (0, 9)), (1, (0,)), (2, (0,))])
+def test_configs_match_the_literal_interval_coefficient_oracle(cfg, inputs):
+    """Configurations FC 6x100, FC 9x500 and small conv against the literal scheme of Section 4.1."""
+    net = wl.config(cfg)
+    g = make_gpu(net)
+    o = make_oracle(net)
+    o.set_collapse(False)
+    for j in inputs:
+        c = net.center(j)
+        g.analyze(c, net.eps)
+        oracle_with_gpu_ties(net, o, g, c, net.eps)
+        worst = compare_all(net, g, o, what=f"{net.name} input {j} (literal oracle)")
+        print(net.name, "input", j, "against the literal oracle: worst looseness / allowed =", worst)
+
+
+def test_failed_allocation_at_a_larger_batch_leaves_the_net_usable():
+    """A batch whose per-layer arrays do not fit the device fails with GP_ERR_NOMEM; the next analysis at the earlier
+    batch size must allocate afresh and give the same bits as before (no kernel ever runs on freed or missing arrays)."""
+    from paper_2007_10868_amd import GpuPolyError, load_library
+    net = odd_fc(2)
+    c = np.random.default_rng(9).random(net.n_in).astype(np.float32)
+    g = make_gpu(net)
+    g.analyze(c, 0.02)
+    ref = {l: g.get_bounds_f64(l) for l in analysed_layers(net)}
+    lib = load_library()
+    huge = 1 << 28                      # 101 neurons x 2^28 boxes x 8 bytes = 217 GB per array: the second one cannot fit
+    one_center = torch.zeros(net.n_in, dtype=torch.float32, device="cuda")
+    # (the library fails while sizing its arrays, before it reads a single centre)
+    st = lib.gp_analyze_batch_dev(g._h, huge, C.c_void_p(one_center.data_ptr()), 0.02, 0.0, 1.0)
+    assert st == 4, st
+    with pytest.raises(GpuPolyError) as e:
+        g.get_bounds_f64(net.out_layer)
+    assert e.value.status == 3          # no successful analysis any more
+    g.analyze(c, 0.02)
+    for l in analysed_layers(net):
+        lo, hi = g.get_bounds_f64(l)
+        assert np.array_equal(lo, ref[l][0]) and np.array_equal(hi, ref[l][1]), l
+
+
 def test_config0_fc6x100_all_inputs_and_certify():
     net = wl.config(0)
     g = make_gpu(net)
