@@ -113,6 +113,9 @@ def clear_overrides(net: wl.Net, o: OracleNet):
             o.set_gamma_override(lid, None)
 
 
+LOG = []       # (what, looseness / allowed, containment violation) of every comparison made, for reports
+
+
 def compare_layer(glo, ghi, olo, ohi, what="", contain_tol=None):
     """Returns (max looseness / allowed, max containment violation / scale); asserts the bar."""
     glo, ghi = np.asarray(glo, np.float64), np.asarray(ghi, np.float64)
@@ -120,6 +123,7 @@ def compare_layer(glo, ghi, olo, ohi, what="", contain_tol=None):
     s_lo, s_hi = 1.0 + np.abs(olo), 1.0 + np.abs(ohi)
     loose = max(np.max((olo - glo) / s_lo), np.max((ghi - ohi) / s_hi))
     viol = max(np.max((glo - olo) / s_lo), np.max((ohi - ghi) / s_hi))
+    LOG.append((what, float(loose / REL_TOL), float(viol)))
     assert loose <= REL_TOL, f"{what}: GPU bound looser than oracle by {loose:.3e} (relative), allowed {REL_TOL}"
     tol = CONTAIN_TOL if contain_tol is None else contain_tol
     assert viol <= tol, f"{what}: GPU bound inside the oracle bound by {viol:.3e} (relative), allowed {tol}"

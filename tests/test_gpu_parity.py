@@ -438,11 +438,38 @@ def test_config3_deep_conv_one_input():
     print("conv_deep worst looseness / allowed =", worst, "lambda ties forced:", forced)
 
 
-def _sampled_rows_against_teacher_forced_oracle(net, g, o, c, eps, rows_per_layer, rng, what):
+def stratified_rows(shape, count, rng):
+    """Rows (C,H,W-flattened neuron indices) of a layer of the given shape that cover the cases its kernels treat
+    differently: the four corners and the edge midpoints (dependence windows clipped and shifted at the borders), the
+    positions one step inside a corner, positions of either parity (a stride-2 shortcut reads every other position),
+    the centre and random interior positions; at each position the first, the last and a random channel (first and
+    last row of a tile, ragged channel tiles).  `count` rows at most, taken round-robin over the positions so that
+    a small count still holds every kind."""
+    C, H, W = shape
+    if C * H * W <= count:
+        return np.arange(C * H * W, dtype=np.int32)
+    pos = [(0, 0), (0, W - 1), (H - 1, 0), (H - 1, W - 1),                       # corners
+           (0, W // 2), (H - 1, W // 2), (H // 2, 0), (H // 2, W - 1),           # edge midpoints
+           (min(1, H - 1), min(1, W - 1)), (max(H - 2, 0), max(W - 2, 0)),       # one step inside
+           (min(1, H - 1), min(2, W - 1)), (min(2, H - 1), min(1, W - 1)),       # odd/even and even/odd
+           (H // 2, W // 2)]
+    pos += [(int(rng.integers(0, H)), int(rng.integers(0, W))) for _ in range(3)]
+    pos = list(dict.fromkeys(pos))
+    rows = []
+    for p in range(4):
+        for i, (y, x) in enumerate(pos):
+            kind = (p + i) % 4          # first channel, last channel, two random ones: every pass mixes the kinds
+            c = 0 if kind == 0 else C - 1 if kind == 1 else int(rng.integers(0, C))
+            rows.append((c * H + y) * W + x)
+    rows = list(dict.fromkeys(rows))[:count]
+    return np.sort(np.array(rows, dtype=np.int32))
+
+
+def _sampled_rows_against_teacher_forced_oracle(net, g, o, c, eps, rows_per_layer, rng, what, batch_index=0):
     """The oracle gets the GPU's intervals of all earlier layers as data (teacher forcing) and bounds a
-    sample of rows of each analysed layer on its own; the two must agree to the usual bar."""
+    stratified sample of rows of each analysed layer on its own; the two must agree to the usual bar."""
     o.set_ball(c, eps)
-    worst = 0.0
+    worst, n_rows = 0.0, 0
     for lid in range(1, o.num_layers):
         L = net.layers[lid - 1]
         if L["type"] == "relu":
@@ -450,14 +477,14 @@ def _sampled_rows_against_teacher_forced_oracle(net, g, o, c, eps, rows_per_laye
             continue
         if lid not in analysed_layers(net):
             continue
-        glo, ghi = g.get_bounds_f64(lid)
-        n = glo.size
-        rows = np.sort(rng.choice(n, size=min(rows_per_layer, n), replace=False)).astype(np.int32)
+        glo, ghi = g.get_bounds_f64(lid, batch_index)
+        rows = stratified_rows(net.shape_of(lid), rows_per_layer, rng)
         olo, ohi = o.bound_rows(lid, rows)
         r, _ = compare_layer(glo[rows], ghi[rows], olo, ohi, f"{what} layer {lid}")
         worst = max(worst, r)
+        n_rows += rows.size
         o.set_bounds(lid, glo, ghi)
-    return worst
+    return worst, n_rows
 
 
 def test_scaled_resnet34_full_parity():
@@ -477,19 +504,87 @@ def test_scaled_resnet34_full_parity():
     compare_all(net, g, o, what=net.name + " (GPU slopes)", contain_tol=STRICT_CONTAIN_TOL)
 
 
-def test_config4_resnet34_sampled_rows():
-    """The full 1M-neuron configuration: the whole oracle pass would take hours, so rows are sampled
-    per layer with teacher forcing, and every neuron is checked against sampled concrete outputs."""
+@pytest.mark.parametrize("j,rows_per_layer", [(0, 64), (1, 32)])
+def test_config4_resnet34_sampled_rows(j, rows_per_layer):
+    """The full 1M-neuron configuration: the whole oracle pass would take hours, so a stratified sample of rows
+    (corners, edges, interior, first and last channels) of every analysed layer is bounded by the oracle with teacher
+    forcing, and every neuron is checked against sampled concrete outputs."""
     net = wl.config(4)
     g = make_gpu(net)
     o = make_oracle(net)
-    c = net.center(0)
+    c = net.center(j)
     g.analyze(c, net.eps)
-    rng = np.random.default_rng(5)
-    worst = _sampled_rows_against_teacher_forced_oracle(net, g, o, c, net.eps, 6, rng, "resnet34")
+    rng = np.random.default_rng(5 + j)
+    worst, n_rows = _sampled_rows_against_teacher_forced_oracle(net, g, o, c, net.eps, rows_per_layer, rng, f"resnet34 input {j}")
     lo0, hi0 = ball_box(c, net.eps)
     check_samples_inside(net, g, lo0, hi0, 64, rng, what="resnet34")
-    print("resnet34 sampled rows: worst looseness / allowed =", worst)
+    print(f"resnet34 input {j}: {n_rows} sampled rows, worst looseness / allowed = {worst}")
+
+
+def _workspace_like_bench(g, batch):
+    g.set_stream(torch.cuda.current_stream())
+    _, full = g.workspace_size(batch)
+    free, _ = torch.cuda.mem_get_info()
+    ws = torch.empty(int(min(full, free * 0.6)), dtype=torch.uint8, device="cuda")
+    g.set_workspace(ws)
+    return ws
+
+
+def test_config2_in_the_benchmark_launch_configuration():
+    """Small conv exactly as bench.py times it: all 100 inputs in one batched pass, centres resident on the device,
+    workspace from a torch tensor.  Full oracle parity on two of the inputs, sampled outputs on every tenth, and
+    bit-equality of a batched result with a single-input pass."""
+    net = wl.config(2)
+    batch = net.n_inputs
+    g = make_gpu(net)
+    centers = np.stack([net.center(j) for j in range(batch)])
+    ws = _workspace_like_bench(g, batch)
+    g.analyze_batch_dev(torch.tensor(centers, device="cuda"), net.eps)
+    o = make_oracle(net)
+    for b in (3, 99):
+        oracle_with_gpu_ties(net, o, g, centers[b], net.eps, batch_index=b)
+        compare_all(net, g, o, batch_index=b, what=f"conv_small x100, input {b}")
+    rng = np.random.default_rng(8)
+    for b in range(0, batch, 10):
+        lo0, hi0 = ball_box(centers[b], net.eps)
+        check_samples_inside(net, g, lo0, hi0, 200, rng, batch_index=b, what=f"conv_small x100, input {b}")
+    batched = {l: g.get_bounds_f64(l, 99) for l in analysed_layers(net)}
+    g1 = make_gpu(net)
+    g1.analyze(centers[99], net.eps)
+    for l in analysed_layers(net):
+        lo, hi = g1.get_bounds_f64(l)
+        assert np.array_equal(lo, batched[l][0]) and np.array_equal(hi, batched[l][1]), l
+    del ws
+
+
+def test_config3_in_the_benchmark_launch_configuration():
+    """Deep conv exactly as bench.py times it: all 20 inputs in one batched pass.  Full oracle parity on one input of
+    the batch, a stratified sample of rows per layer (teacher forcing) on another, sampled outputs on four, and
+    bit-equality of a batched result with a single-input pass."""
+    net = wl.config(3)
+    batch = net.n_inputs
+    g = make_gpu(net)
+    centers = np.stack([net.center(j) for j in range(batch)])
+    ws = _workspace_like_bench(g, batch)
+    g.analyze_batch_dev(torch.tensor(centers, device="cuda"), net.eps)
+    o = make_oracle(net)
+    oracle_with_gpu_ties(net, o, g, centers[19], net.eps, batch_index=19)
+    worst = compare_all(net, g, o, batch_index=19, what="conv_deep x20, input 19")
+    rng = np.random.default_rng(9)
+    o2 = make_oracle(net)
+    w2, n_rows = _sampled_rows_against_teacher_forced_oracle(net, g, o2, centers[7], net.eps, 64, rng,
+                                                             "conv_deep x20, input 7", batch_index=7)
+    for b in (0, 7, 13, 19):
+        lo0, hi0 = ball_box(centers[b], net.eps)
+        check_samples_inside(net, g, lo0, hi0, 100, rng, batch_index=b, what=f"conv_deep x20, input {b}")
+    batched = {l: g.get_bounds_f64(l, 7) for l in analysed_layers(net)}
+    g1 = make_gpu(net)
+    g1.analyze(centers[7], net.eps)
+    for l in analysed_layers(net):
+        lo, hi = g1.get_bounds_f64(l)
+        assert np.array_equal(lo, batched[l][0]) and np.array_equal(hi, batched[l][1]), l
+    print("conv_deep x20: worst looseness / allowed =", worst, "; sampled rows:", n_rows, "worst", w2)
+    del ws
 
 
 @pytest.mark.parametrize("maker,eps", [(odd_fc, 0.02), (tiny_conv, 0.05), (mid_resnet, 0.005)])
