@@ -143,6 +143,26 @@ gp_status gp_analyze_batch(gp_net* net, int32_t batch, const float* centers, flo
 gp_status gp_analyze_batch_dev(gp_net* net, int32_t batch, const float* centers_dev, float eps,
                                float clip_lo, float clip_hi);
 
+/* For callers that cannot allocate device memory at the time of the call: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  The same analysis as gp_analyze_batch_dev, with the coefficient blocks of the
+ * rows in flight kept in a static device array of the library (32 MiB per GPU, held from the moment the library is
+ * loaded until the process ends) instead of a workspace, and with the bounds of the last layer also written to arrays
+ * of the caller: lower_dev, upper_dev, device memory, [batch][n_out] float64, outputs numbered C,H,W.  The call makes no
+ * device or pinned-memory allocation and frees none (no hipMalloc, hipFree, event or stream creation); rows are
+ * processed in chunks that fit the array (Section 4.2 "Memory management"), which changes no bit of the result.
+ * Preconditions, reported and never worked around by allocating:
+ *   - an analysis of at least `batch` boxes has completed on this net since its topology or modes last changed (that
+ *     call sized the per-layer arrays, which this one reuses): otherwise GP_ERR_STATE;
+ *   - one row (both signs) of every layer's plan fits the static array: otherwise GP_ERR_WORKSPACE, the message gives
+ *     the bytes needed and the size of the array;
+ *   - per-kernel profiling is off (it creates events): otherwise GP_ERR_STATE.
+ * A workspace set with gp_set_workspace and graph replay are ignored by this call.  All calls on one GPU share that
+ * GPU's array (whatever the net): calls that overlap in time on one GPU race on it.  The array keeps the previous
+ * call's contents; nothing in it is expected to be zero.  gp_get_bounds* and gp_certify* work afterwards as after any
+ * analysis. */
+gp_status gp_analyze_batch_dev_static(gp_net* net, int32_t batch, const float* centers_dev, float eps, float clip_lo,
+                                      float clip_hi, double* lower_dev, double* upper_dev);
+
 /* Bounds of one layer for box `batch_index` of the last analysis: lower/upper [n_layer] float32,
  * rounded outward from the internal float64 values. */
 gp_status gp_get_bounds(const gp_net* net, int32_t layer_id, float* lower, float* upper);

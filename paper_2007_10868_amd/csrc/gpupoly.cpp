@@ -19,6 +19,8 @@
 #include "../../include/gpupoly.h"
 #include "kernels.hpp"
 
+static __device__ __align__(256) unsigned char scratch[32u << 20];
+
 namespace {
 
 enum LType { T_INPUT = 0, T_DENSE = 1, T_CONV = 2, T_RELU = 3, T_ADD = 4, T_POOL = 5 };   // T_POOL: average pooling
@@ -79,6 +81,7 @@ struct Plan {
     int n_slots = 0;
     long long slot_elems = 0;         // largest block, elements per row
     std::vector<int32_t> steps;       // gp_debug_plan records, 8 ints each
+    std::vector<double> rem_flop;     // per op: arithmetic, per row, of the crossings from this op on (size ops + 1)
 };
 
 const double kRoundCoef = 0x1p-24 * (1.0 + 0x1p-20);   // float32 rounding of a float64 value
@@ -99,7 +102,9 @@ struct gp_net {
     bool topo_ready = false;
     std::vector<Plan> plans;     // per layer
     Plan cert_plan;
-    int batch = 0;               // batch the device bound arrays are sized for
+    int batch = 0;               // boxes of the last analysis (what gp_get_bounds* and gp_certify* index)
+    int batch_cap = 0;           // boxes the per-layer device arrays are sized for (0: none allocated); arrays are
+                                 // [box][neuron], so an analysis of fewer boxes uses a prefix of each
     bool analyzed = false;
     bool weights_uploaded = false;
     int* d_flag = nullptr;
@@ -127,6 +132,10 @@ struct gp_net {
     GraphKey graph_key = {};
     bool float_inference = false;  // bounds also hold for every float32 evaluation order of the network (Section 4.1)
     bool coef64 = false;           // coefficient blocks are stored in float64 (the paper's double precision build, Section 5)
+    // set for the duration of gp_analyze_batch_dev_static: nothing may be allocated or freed; the rows' coefficient
+    // blocks live in the library's static device array
+    bool static_call = false;
+    void* static_ws = nullptr;
     int* d_count = nullptr;
     int* h_count = nullptr;        // pinned: task counts read back while the GPU keeps working
     hipEvent_t count_ev = nullptr;
@@ -165,6 +174,14 @@ gp_status fail(const gp_net* net, gp_status st, const char* fmt, ...) {
 void dfree(void* p) {
     if (p) (void)hipFree(p);
 }
+
+// ---- the static workspace of gp_analyze_batch_dev_static -------------------------------------------------------------------
+// Device memory that exists from the moment the library's code object is loaded on a GPU until the process ends, one
+// copy per GPU.  In host code the array's name is only a handle for hipGetSymbolAddress: the address kernels are given
+// is looked up once per device, with that device current, and kept in g_scratch_ptr.
+constexpr long long kStaticScratchBytes = 32LL << 20;
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
 
 // a captured graph holds device addresses: whatever frees or moves device memory drops it
 void drop_graph(gp_net* net) {
@@ -464,6 +481,20 @@ gp_status build_plan(gp_net* net, int start, bool certify, Plan& pl) {
     PlanOp fin;
     fin.kind = PlanOp::FINALIZE;
     pl.ops.push_back(fin);
+    // per row: arithmetic of the crossings that follow each op of the plan (what removing a row saves)
+    pl.rem_flop.assign(pl.ops.size() + 1, 0.0);
+    for (size_t i = pl.ops.size(); i-- > 0;) {
+        pl.rem_flop[i] = pl.rem_flop[i + 1];
+        const PlanOp& op = pl.ops[i];
+        if (op.kind == PlanOp::CROSS) {
+            const Layer& a = L[op.layer_in];
+            const Layer& p = L[op.layer_out];
+            const double taps = (a.type == T_DENSE) ? 1.0 : (double)a.kh * a.kw;
+            const double cin = (a.type == T_DENSE) ? (double)p.n : (a.type == T_POOL) ? 1.0 : (double)p.C;
+            pl.rem_flop[i] += 2.0 * (double)block_elems(op.g_in, a) * taps * cin *
+                              (certify ? 1.0 : exact_share(op.g_in, op.t_in, a, L[start].H, L[start].W));
+        }
+    }
     pl.valid = true;
     return GP_OK;
 }
@@ -548,7 +579,23 @@ gp_status allocate_batch_state(gp_net* net, int batch) {
 gp_status ensure_device(gp_net* net, int batch) {
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) return fail(net, GP_ERR_DEVICE, "no HIP device");
+    if (net->static_call) {      // nothing may be allocated: everything must be there from an earlier analysis
+        if (!net->d_flag || !net->d_count || !net->h_count || !net->count_ev || !net->weights_uploaded || batch > net->batch_cap)
+            return fail(net, GP_ERR_STATE, "no analysis of at least %d boxes has run on this net since its topology or modes last changed: "
+                                           "the allocation-free call has no per-layer arrays to work in", batch);
+        net->batch = batch;
+        return GP_OK;
+    }
     if (net->device < 0) HIP_TRY(net, hipGetDevice(&net->device));
+    // Address of the static workspace on this device, for gp_analyze_batch_dev_static: looked up here, once per device
+    // and with that device current (every GPU holds its own copy at its own address), because the runtime may
+    // materialise the array at the first lookup and that call must not allocate.
+    if (net->device >= 0 && net->device < kMaxDevices && !g_scratch_ptr[net->device]) {
+        void* ptr = nullptr;
+        HIP_TRY(net, hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return fail(net, GP_ERR_DEVICE, "the static workspace has no device address");
+        g_scratch_ptr[net->device] = ptr;
+    }
     if (!net->d_flag) HIP_TRY(net, hipMalloc((void**)&net->d_flag, sizeof(int)));
     if (!net->d_count) HIP_TRY(net, hipMalloc((void**)&net->d_count, sizeof(int)));
     if (!net->h_count) HIP_TRY(net, hipHostMalloc((void**)&net->h_count, 2 * sizeof(int), hipHostMallocDefault));
@@ -577,18 +624,20 @@ gp_status ensure_device(gp_net* net, int batch) {
         }
         net->weights_uploaded = true;
     }
-    if (net->batch != batch) {
-        // Nothing is sized for any batch while this block runs: batch = 0 until the last allocation has succeeded, and a
-        // failure on the way frees what was allocated, so that the next call (at whatever batch) starts from scratch
-        // instead of launching kernels on buffers that are gone or sized for the batch that failed.
+    if (batch > net->batch_cap) {
+        // Nothing is sized for any batch while this block runs: the capacity is 0 until the last allocation has
+        // succeeded, and a failure on the way frees what was allocated, so that the next call (at whatever batch)
+        // starts from scratch instead of launching kernels on buffers that are gone or sized for the batch that failed.
         drop_graph(net);
+        net->batch_cap = 0;
         net->batch = 0;
         net->analyzed = false;
         release_batch_state(net);
         const gp_status st = allocate_batch_state(net, batch);
         if (st != GP_OK) { release_batch_state(net); (void)hipGetLastError(); return st; }   // (the sticky error is reported here, once)
-        net->batch = batch;
+        net->batch_cap = batch;
     }
+    net->batch = batch;
     return GP_OK;
 }
 
@@ -603,6 +652,7 @@ long long task_bytes(const Plan& pl, int nsign, int csize) {
 }
 
 gp_status get_workspace(gp_net* net, long long want, char** ws, long long* bytes) {
+    if (net->static_call) { *ws = (char*)net->static_ws; *bytes = kStaticScratchBytes; return GP_OK; }
     if (net->ws_user) { *ws = (char*)net->ws_user; *bytes = net->ws_user_bytes; return GP_OK; }
     const long long cap = 32LL << 30;
     long long need = std::min(want, cap);
@@ -695,20 +745,7 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
     const long long slot_bytes = align_up(nrows_max * pl.slot_elems * csize, 256);
     if (slots0 + slot_bytes * pl.n_slots > ws + ws_bytes) return fail(net, GP_ERR_WORKSPACE, "workspace layout overflow");
 
-    // per row: arithmetic of the crossings that follow each op of the plan
-    std::vector<double> rem_flop(pl.ops.size() + 1, 0.0);
-    for (size_t i = pl.ops.size(); i-- > 0;) {
-        rem_flop[i] = rem_flop[i + 1];
-        const PlanOp& op = pl.ops[i];
-        if (op.kind == PlanOp::CROSS) {
-            const Layer& a = net->L[op.layer_in];
-            const Layer& p = net->L[op.layer_out];
-            const double taps = (a.type == T_DENSE) ? 1.0 : (double)a.kh * a.kw;
-            const double cin = (a.type == T_DENSE) ? (double)p.n : (a.type == T_POOL) ? 1.0 : (double)p.C;
-            rem_flop[i] += 2.0 * (double)block_elems(op.g_in, a) * taps * cin *
-                           (certify ? 1.0 : exact_share(op.g_in, op.t_in, a, ls.H, ls.W));
-        }
-    }
+    const std::vector<double>& rem_flop = pl.rem_flop;   // per row: arithmetic of the crossings that follow each op
 
     for (long long row0 = 0; row0 < total; row0 += Rc_max) {
         gp::RowMap rm;
@@ -1069,8 +1106,10 @@ gp_status begin_analysis(gp_net* net, int batch) {
 }
 
 void enqueue_reset(gp_net* net, int batch) {
+    (void)batch;
     gp::launch_fill_i32(net->d_flag, 0, 1, net->stream);
-    gp::launch_fill_f64(net->d_xmax_all, 0.0, (long long)batch * (long long)net->L.size(), net->stream);
+    // [layer][box capacity]: the boxes of this analysis are a prefix of every layer's segment
+    gp::launch_fill_f64(net->d_xmax_all, 0.0, (long long)net->batch_cap * (long long)net->L.size(), net->stream);
 }
 
 bool same_key(const gp_net::GraphKey& a, const gp_net::GraphKey& b) {
@@ -1151,10 +1190,10 @@ static void topology_changed(gp_net* net) {
     net->topo_ready = false;
     net->analyzed = false;
     net->weights_uploaded = false;
-    if (net->batch) {
+    if (net->batch_cap) {
         for (auto& l : net->L) free_layer_bounds(l);
         for (auto& l : net->L) { dfree(l.d_beff); l.d_beff = nullptr; }
-        net->batch = 0;
+        net->batch = net->batch_cap = 0;
     }
 }
 
@@ -1302,9 +1341,10 @@ gp_status gp_set_early_termination(gp_net* net, int32_t on) {
     if (want != net->early) {
         net->early = want;
         net->analyzed = false;
-        if (net->batch) {           // the set of layers that carry intervals changes
+        if (net->batch_cap) {       // the set of layers that carry intervals changes
+            drop_graph(net);
             for (auto& l : net->L) free_layer_bounds(l);
-            net->batch = 0;
+            net->batch = net->batch_cap = 0;
         }
     }
     return GP_OK;
@@ -1336,9 +1376,9 @@ gp_status gp_set_float_inference(gp_net* net, int32_t on) {
         net->float_inference = want;
         net->analyzed = false;
         net->topo_ready = false;    // sum layers carry intervals in this mode
-        if (net->batch) {
+        if (net->batch_cap) {
             for (auto& l : net->L) free_layer_bounds(l);
-            net->batch = 0;
+            net->batch = net->batch_cap = 0;
         }
     }
     return GP_OK;
@@ -1450,6 +1490,73 @@ gp_status gp_analyze_batch_dev(gp_net* net, int32_t batch, const float* centers_
     }
     HIP_TRY(net, hipGraphLaunch(net->graph_exec, net->stream));
     return finish_analysis(net);
+}
+
+// bounds of a layer from the library's [box][y][x][channel] arrays into the caller's [box][channel][y][x] arrays
+__global__ void export_bounds_kernel(const double* lo, const double* hi, double* out_lo, double* out_hi, int C, int HW,
+                                     long long total) {
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const long long n = (long long)C * HW, b = i / n, r = i - b * n;
+    const long long pix = r / C, c = r - pix * C;
+    const long long o = b * n + c * HW + pix;
+    out_lo[o] = lo[i];
+    out_hi[o] = hi[i];
+}
+
+gp_status gp_analyze_batch_dev_static(gp_net* net, int32_t batch, const float* centers_dev, float eps, float clip_lo,
+                                      float clip_hi, double* lower_dev, double* upper_dev) {
+    if (!net) return GP_ERR_ARG;
+    if (!centers_dev || !lower_dev || !upper_dev) return fail(net, GP_ERR_ARG, "centers, lower or upper is null");
+    if (batch <= 0) return fail(net, GP_ERR_ARG, "batch must be positive");
+    if (!(eps >= 0.f) || !std::isfinite(eps)) return fail(net, GP_ERR_ARG, "eps must be finite and >= 0");
+    if (!(clip_lo <= clip_hi)) return fail(net, GP_ERR_ARG, "clip_lo > clip_hi");
+    if (net->L.size() < 2) return fail(net, GP_ERR_STATE, "network has no layers");
+    if (net->prof_on) return fail(net, GP_ERR_STATE, "per-kernel profiling creates events: switch it off for the allocation-free call");
+    // the static workspace must hold at least one row (both signs) of every plan; this needs the topology only
+    gp_status st = prepare_topology(net);
+    if (st != GP_OK) return st;
+    for (size_t i = 1; i < net->L.size(); ++i) {
+        if (net->L[i].type == T_RELU || !net->L[i].need_bounds) continue;
+        Plan* pl;
+        st = get_plan(net, (int)i, &pl);
+        if (st != GP_OK) return st;
+        const long long need = task_bytes(*pl, 2, net->coef64 ? 8 : 4) + 16384;
+        if (need > kStaticScratchBytes)
+            return fail(net, GP_ERR_WORKSPACE, "one row of layer %d needs %lld bytes of workspace; the static workspace of the "
+                                               "allocation-free call holds %lld", (int)i, need, kStaticScratchBytes);
+    }
+    int ndev = 0, dev = -1;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) return fail(net, GP_ERR_DEVICE, "no HIP device");
+    HIP_TRY(net, hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(net, GP_ERR_DEVICE, "device index %d out of range", dev);
+    if (net->device >= 0 && net->device != dev) return fail(net, GP_ERR_STATE, "the net lives on device %d, the current device is %d", net->device, dev);
+    // (looked up by the analysis that sized the per-layer arrays: the runtime may materialise the array at the first lookup)
+    if (!g_scratch_ptr[dev]) return fail(net, GP_ERR_STATE, "no analysis has run on device %d yet: the static workspace has no address", dev);
+    net->static_call = true;
+    net->static_ws = g_scratch_ptr[dev];
+    auto run = [&]() -> gp_status {
+        gp_status s2 = begin_analysis(net, batch);
+        if (s2 != GP_OK) return s2;
+        const Layer& in = net->L[0];
+        gp::BoxParams bp;
+        bp.centers = centers_dev; bp.eps = eps; bp.clip_lo = clip_lo; bp.clip_hi = clip_hi;
+        bp.lo = in.d_lo; bp.hi = in.d_hi; bp.xmax = in.d_xmax; bp.flag = net->d_flag;
+        bp.C = in.C; bp.H = in.H; bp.W = in.W; bp.batch = batch;
+        enqueue_reset(net, batch);
+        gp::launch_box(bp, net->stream);
+        s2 = analyze_layers(net, batch);
+        if (s2 != GP_OK) return s2;
+        const Layer& out = net->L.back();
+        const long long total = out.n * batch;
+        export_bounds_kernel<<<(unsigned)((total + 255) / 256), 256, 0, net->stream>>>(out.d_lo, out.d_hi, lower_dev, upper_dev, out.C,
+                                                                                        out.H * out.W, total);
+        return finish_analysis(net);
+    };
+    st = run();
+    net->static_call = false;
+    net->static_ws = nullptr;
+    return st;
 }
 
 gp_status gp_analyze_batch(gp_net* net, int32_t batch, const float* centers, float eps, float clip_lo, float clip_hi) {

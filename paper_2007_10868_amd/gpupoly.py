@@ -19,7 +19,7 @@ STATUS = {0: "GP_OK", 1: "GP_ERR_ARG", 2: "GP_ERR_SHAPE", 3: "GP_ERR_STATE", 4: 
 EXPORTS = ["gp_net_create", "gp_net_destroy", "gp_add_dense", "gp_add_conv2d", "gp_add_avgpool2d", "gp_add_relu", "gp_add_residual",
            "gp_request_bounds", "gp_set_early_termination", "gp_set_float_inference", "gp_set_coefficient_storage", "gp_set_graph_replay", "gp_get_term_layer", "gp_get_early_termination_stats",
            "gp_set_stream", "gp_workspace_size", "gp_set_workspace", "gp_analyze",
-           "gp_analyze_box", "gp_analyze_batch", "gp_analyze_batch_dev", "gp_get_bounds", "gp_get_bounds_batch",
+           "gp_analyze_box", "gp_analyze_batch", "gp_analyze_batch_dev", "gp_analyze_batch_dev_static", "gp_get_bounds", "gp_get_bounds_batch",
            "gp_get_bounds_f64", "gp_get_relu_lambda", "gp_get_relu_slopes", "gp_certify", "gp_certify_batch", "gp_bound_outputs", "gp_debug_plan",
            "gp_profile_enable", "gp_profile_read", "gp_profile_dump", "gp_debug_mfma_f64", "gp_debug_mfma_f64_4col", "gp_num_layers", "gp_layer_size", "gp_last_error", "gp_version"]
 
@@ -66,6 +66,7 @@ def load_library():
     L.gp_analyze_box.argtypes = [P, fp, fp]
     L.gp_analyze_batch.argtypes = [P, i32, fp, f32, f32, f32]
     L.gp_analyze_batch_dev.argtypes = [P, i32, P, f32, f32, f32]
+    L.gp_analyze_batch_dev_static.argtypes = [P, i32, P, f32, f32, f32, P, P]
     L.gp_get_bounds.argtypes = [P, i32, fp, fp]
     L.gp_get_bounds_batch.argtypes = [P, i32, i32, fp, fp]
     L.gp_get_bounds_f64.argtypes = [P, i32, i32, dp, dp]
@@ -233,6 +234,17 @@ class Net:
         t = centers_tensor
         assert t.is_cuda and t.is_contiguous() and t.dim() == 2 and t.shape[1] == self.layer_size(0)
         self._chk(self._L.gp_analyze_batch_dev(self._h, t.shape[0], C.c_void_p(t.data_ptr()), eps, clip_lo, clip_hi))
+
+    def analyze_batch_dev_static(self, centers_tensor, eps, lower_tensor, upper_tensor, clip_lo=0.0, clip_hi=1.0):
+        """The allocation-free variant: centers [batch, n_in] float32, lower/upper [batch, n_out] float64, all
+        contiguous CUDA tensors of the caller."""
+        t = centers_tensor
+        assert t.is_cuda and t.is_contiguous() and t.dim() == 2 and t.shape[1] == self.layer_size(0)
+        n_out = self.layer_size(self.num_layers - 1)
+        for o in (lower_tensor, upper_tensor):
+            assert o.is_cuda and o.is_contiguous() and o.dtype.itemsize == 8 and o.numel() == t.shape[0] * n_out
+        self._chk(self._L.gp_analyze_batch_dev_static(self._h, t.shape[0], C.c_void_p(t.data_ptr()), eps, clip_lo, clip_hi,
+                                                      C.c_void_p(lower_tensor.data_ptr()), C.c_void_p(upper_tensor.data_ptr())))
 
     def get_bounds(self, lid, batch_index=0):
         n = self.layer_size(lid)

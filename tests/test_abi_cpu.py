@@ -161,6 +161,20 @@ def test_layers_beyond_the_32_bit_offsets_of_the_kernels_are_refused():
     lib.gp_net_destroy(h)
 
 
+def test_allocation_free_call_refuses_rows_beyond_its_static_workspace_from_the_topology_alone():
+    big = wl.Net("big_rows", (1, 1200, 1200))
+    r1 = big.relu(big.conv(0, np.ones((2, 1, 1, 1), np.float32), np.zeros(2, np.float32), 1, 0))
+    big.dense(r1, np.zeros((2, 2 * 1200 * 1200), np.float32), np.zeros(2, np.float32))
+    g = Net(*big.input_shape)
+    wl.build_into(big, g)
+    lib = load_library()
+    fake = C.c_void_p(256)          # never dereferenced: the call fails while it sizes the plans
+    assert lib.gp_analyze_batch_dev_static(g._h, 1, fake, 0.01, 0.0, 1.0, fake, fake) == 7
+    assert b"static workspace" in lib.gp_last_error(g._h)
+    assert lib.gp_analyze_batch_dev_static(g._h, 0, fake, 0.01, 0.0, 1.0, fake, fake) == 1
+    assert lib.gp_analyze_batch_dev_static(g._h, 1, fake, 0.01, 0.0, 1.0, None, fake) == 1
+
+
 def test_unsupported_topology_is_reported_not_guessed():
     n = Net(4, 1, 1)
     a = n.add_dense(0, np.eye(4, dtype=np.float32))
