@@ -19,3 +19,17 @@ def gpu_device():
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     return torch.device("cuda:0")
+
+
+def pytest_sessionfinish(session, exitstatus):
+    """PARITY_LOG=<file>: write looseness and containment of every GPU/oracle comparison of the session (one line each)."""
+    path = os.environ.get("PARITY_LOG")
+    if not path:
+        return
+    try:
+        import parity
+    except Exception:
+        return
+    with open(path, "w") as f:
+        for what, loose, viol in parity.LOG:
+            f.write(f"{loose:.4e}\t{viol:.4e}\t{what}\n")

@@ -8,11 +8,16 @@ import workloads as wl
 from oracle import OracleNet
 
 REL_TOL = 1e-3          # a GPU bound may be looser than the oracle's by at most REL_TOL * (1 + |b|)
-# ... and must contain it.  With the oracle's own relaxation slopes this holds only up to the effect of the
-# slopes differing slightly (GPU: float32 slope computed from intervals that are wider by the rounding
-# slack, i.e. by up to ~1e-5 relative; every slope in [0,1] is sound, so neither analysis dominates the
-# other).  The difference grows with depth; a tenth of the looseness bar is allowed:
-CONTAIN_TOL = 1e-4
+# ... and must contain it.  The oracle's relaxation slopes differ from the library's in the last float32 bits (the
+# library's are float32 values computed from intervals that are wider by its rounding slack; every slope in [0,1] is
+# sound, so neither analysis dominates the other in principle).  Measured on the five configurations, the ten small
+# networks and the scaled 34-layer residual net: the library's interval contained the free-running oracle's in every
+# one of the comparisons (worst violation <= 0); the bar leaves room for the slope effect only:
+CONTAIN_TOL = 1e-6
+# With early termination a stopped neuron keeps the intersection of its interval image and its candidates so far, and
+# the two sides reach that intersection from slightly different slopes: 2 877 comparisons of the GPU suite, worst
+# violation 1.3e-6 (scaled 34-layer residual net; 1.3e-7 elsewhere).  Twice the measured worst:
+EARLY_CONTAIN_TOL = 3e-6
 # When the oracle is told to use the GPU's slopes and lower-line choices, every transformer is monotone
 # in the intervals and the GPU intervals must contain the oracle's up to float64 rounding noise:
 STRICT_CONTAIN_TOL = 1e-9

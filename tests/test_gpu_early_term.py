@@ -11,7 +11,7 @@ import torch
 
 import workloads as wl
 from helpers import ball_box, forward
-from parity import (analysed_layers, bounded_affine_layers, check_samples_inside, compare_all, make_gpu, make_oracle,
+from parity import (EARLY_CONTAIN_TOL, analysed_layers, bounded_affine_layers, check_samples_inside, compare_all, make_gpu, make_oracle,
                     oracle_early_with_gpu_decisions)
 from test_gpu_parity import mid_resnet, odd_fc, pad0_conv, rect_conv, tiny_conv, tiny_fc, tiny_resnet
 
@@ -31,7 +31,7 @@ def check_early(net, g, center, eps, batch_index=0, what="", samples=200, seed=0
     # (1) replayed decisions: full parity
     o = make_oracle(net)
     oracle_early_with_gpu_decisions(net, o, g, center, eps, batch_index)
-    compare_all(net, g, o, batch_index, what)
+    compare_all(net, g, o, batch_index, what, contain_tol=EARLY_CONTAIN_TOL)
     # (2) the oracle's own decisions
     of = make_oracle(net)
     of.set_early_termination(True)
