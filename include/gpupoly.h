@@ -105,6 +105,25 @@ gp_status gp_set_graph_replay(gp_net* net, int32_t on);
  * interval is moved outward by 2^-24*|end| (so sum layers always get bounds in this mode).  Takes effect at the
  * next analysis.  The bounds of gp_certify and gp_bound_outputs then speak about the float32 outputs. */
 gp_status gp_set_float_inference(gp_net* net, int32_t on);
+/* The paper's literal floating-point scheme (Section 4.1), for tightness studies on small networks; off by default.
+ * When on, every coefficient of an expression is an interval of two float64 values, every operation rounds lower ends
+ * towards -inf and upper ends towards +inf (the vector unit's rounding mode; the matrix instructions have none, so
+ * this mode runs on plain vector arithmetic, one thread per new coefficient), weights stay scalars, and the intervals
+ * are kept to the end of the back-substitution.  Same plans, dependence windows and residual joins as the default
+ * mode; no rounding-slack terms (the intervals carry the rounding).  16 bytes per coefficient; on deep networks the
+ * widths grow with depth and the bounds become looser than the default mode's.  Cannot be combined with early
+ * termination or float32-inference mode (GP_ERR_UNSUPPORTED at the next analysis); float64 storage and chain fusion
+ * are ignored while it is on.  Takes effect at the next analysis. */
+gp_status gp_set_interval_coefficients(gp_net* net, int32_t on);
+/* Plumbing; on by default.  The rows of a dense layer whose back-substitution runs through dense layers only, all of at
+ * most 256 neurons (the last block, usually over the input, at most 1024), are carried through ALL their steps by one
+ * kernel launch per start layer, with the coefficient block in LDS (Section 2, "Bottleneck Backsubstitution": the rows
+ * are independent, so a work-group can follow its rows to the input on its own).  Whether a layer takes this path
+ * depends on the network alone, not on the batch.  The arithmetic per step is that of the general kernels (float32
+ * coefficients, float64 accumulation, the same slack terms), but sums are formed in another order, so bounds differ
+ * from the general path in the last bits; both are sound.  Off: every layer takes the general kernels.  Not used with
+ * early termination, float32-inference mode or float64 storage. */
+gp_status gp_set_chain_fusion(gp_net* net, int32_t on);
 /* Precision of the stored coefficients (the paper evaluates a single and a double precision build, Section 5); 32
  * (default) or 64.  With 32 every new coefficient of a row's block is rounded once to float32 and the rounding is
  * paid into the row's slack; with 64 the blocks hold float64 values: twice the memory and traffic, only the general

@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgpupoly_hip.so")
-SOURCES = ["gpupoly.cpp", "cross.hip", "scan.hip", "layers.hip"]
+SOURCES = ["gpupoly.cpp", "cross.hip", "scan.hip", "layers.hip", "chain.hip", "interval.hip"]
 # packed-fp32 instructions are switched off for every kernel of this library
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-mllvm", "-amdgpu-mfma-vgpr-form", "-Wno-unused-command-line-argument"]

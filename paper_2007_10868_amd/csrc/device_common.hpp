@@ -111,4 +111,55 @@ __device__ __forceinline__ float relax_factor(double a, float g) {
     return a >= 0.0 ? fabsf(g) : (signbit(g) ? 0.f : 1.f);
 }
 
+// ---- arithmetic of the per-row reductions over a block, shared by the scan kernels and the fused chain kernel ---------------
+// One coefficient's contribution to the five per-row sums.  Written with explicit fused multiply-adds only, so that
+// every scan kernel performs exactly the same operations in the same order per lane and a row's result does not
+// depend on which kernel (i.e. on how many rows share the launch) handled it.
+template <typename CT>
+__device__ __forceinline__ void scan_term(bool has_cand, bool do_consts, CT mf, double cp, double cn, double X, double kp,
+                                          double be, double& cand, double& absx, double& cst, double& cstabs, double& s1) {
+    const double m = (double)mf;
+    const double am = fabs(m);
+    if (has_cand) {
+        cand = fma(m, mf >= (CT)0 ? cp : cn, cand);
+        absx = fma(am, X, absx);
+    }
+    if (do_consts) {
+        const double mp = fmax(m, 0.0);
+        cst = fma(m, be, fma(mp, kp, cst));
+        cstabs = fma(am, fabs(be), fma(mp, kp, cstabs));
+        s1 += am;
+    }
+}
+
+
+// Per-row bookkeeping after the reductions (Section 2: candidate bounds; Section 4.1: the rounding slack): slack of the
+// stored coefficients, candidate folded into best, constants of the next step added to c, slack of the next accumulation.
+//   floor_x: coef_floor * xmax of the block's own layer (0: exact block); e1: accumulation-error constant of the next
+//   crossing(s) times the largest magnitude of their input layer.
+__device__ __forceinline__ void scan_finish_math(int nelem, double round_coef, double floor_x, bool has_cand, bool do_consts,
+                                                 double e1, double t_cand, double t_absx, double t_cst, double t_cstabs,
+                                                 double t_s1, double& c, double& err, double& best) {
+    // a sum of n float64 terms in any order is off by at most (n-1)*2^-53*sum|terms|*(1+tiny)
+    const double esum = (double)(nelem + 16) * 0x1p-52;
+    // slack of the stored coefficients: |true - stored| <= round_coef*|stored| (+ subnormal floor)
+    err += t_absx * round_coef * (1.0 + esum);
+    // values below the float32 subnormal step vanish; with a substituted ReLU the lost coefficient is
+    // up to 2^20 times larger (slopes are kept >= 2^-20)
+    err += floor_x * (double)nelem;
+    if (has_cand) {
+        double v = c + t_cand + err;
+        // (the candidate's terms are at most 3*|m|*X in magnitude when the multiplier comes as a difference, see
+        // scan_term_staged)
+        v += (fabs(c) + fabs(t_cand) + err) * 0x1p-50 + 3.0 * t_absx * esum;
+        best = fmin(best, v);
+    }
+    if (do_consts) {
+        const double cn = c + t_cst;
+        err += t_cstabs * esum + (fabs(c) + fabs(t_cst)) * 0x1p-51 + t_s1 * e1 * (1.0 + esum);
+        c = cn;
+    }
+    err *= (1.0 + 0x1p-48);   // the few float64 operations above
+}
+
 }  // namespace gp

@@ -136,6 +136,8 @@ struct gp_net {
     // blocks live in the library's static device array
     bool static_call = false;
     void* static_ws = nullptr;
+    bool interval = false;         // the paper's literal scheme: interval coefficients, directed rounding (Section 4.1)
+    bool chain_on = true;          // chains of narrow dense layers go through the fused kernel (gp_set_chain_fusion)
     int* d_count = nullptr;
     int* h_count = nullptr;        // pinned: task counts read back while the GPU keeps working
     hipEvent_t count_ev = nullptr;
@@ -643,6 +645,9 @@ gp_status ensure_device(gp_net* net, int batch) {
 
 long long align_up(long long v, long long a) { return (v + a - 1) / a * a; }
 
+// bytes of one stored coefficient: float32, float64, or an interval of two float64
+int coef_bytes(const gp_net* net) { return net->interval ? 16 : net->coef64 ? 8 : 4; }
+
 // bytes one task (both signs) needs for this plan
 long long task_bytes(const Plan& pl, int nsign, int csize) {
     // blocks; constant, slack (twice: rows are moved when tasks are removed), best; row lists and flags; chunk sums of
@@ -693,6 +698,98 @@ void prof_mark(gp_net* net, int kind, bool stop) {
     (void)hipEventRecord(ev[used++], net->stream);
 }
 
+// the per-neuron constants and slack parameters of the candidate taken over op.layer_in (everything of ScanParams that
+// does not depend on the rows); returns whether the candidate has interval terms
+bool scan_setup(const gp_net* net, const PlanOp& op, int start, bool certify, gp::ScanParams& sp) {
+    const Layer& l = net->L[op.layer_in];
+    const bool interval_terms = !op.consts_only && has_bounds(net, op.layer_in) && op.layer_in != start;
+    sp.cpos = sp.cneg = sp.xlo = sp.xhi = sp.kap = nullptr;
+    sp.xmax_self = nullptr;
+    if (interval_terms) {
+        if (op.relaxed) {      // coefficients already multiplied by the ReLU slopes: they range over the ReLU's input
+            const Layer& q = net->L[l.a];
+            sp.cpos = l.d_rho; sp.cneg = l.d_lo; sp.xlo = q.d_lo; sp.xhi = q.d_hi; sp.xmax_self = q.d_xmax;
+        } else {
+            sp.cpos = l.d_hi; sp.cneg = l.d_lo; sp.xlo = l.d_lo; sp.xhi = l.d_hi; sp.xmax_self = l.d_xmax;
+        }
+    }
+    if (op.relaxed) sp.kap = l.d_kap;
+    sp.beff = l.land.empty() ? nullptr : l.d_beff;
+    // a sum layer's own rows bound the exact sum of its summands; its one rounding is added when they are stored
+    sp.eta = (!certify && op.layer_in == start && l.type == T_ADD) ? l.d_eta_thru : eta_of(net, op.layer_in);
+    sp.e1_a = sp.e1_b = 0.0;
+    sp.xmax_a = sp.xmax_b = nullptr;
+    for (size_t i = 0; i < l.land.size(); ++i) {
+        const Layer& q = net->L[l.land[i]];
+        double K = (double)q.kh * q.kw * (q.type == T_POOL ? 1.0 : (double)q.C);   // terms of one new coefficient
+        double e1 = (K + 8.0) * 0x1p-50 * q.rowabs;
+        if (i == 0) { sp.e1_a = e1; sp.xmax_a = net->L[q.a].d_xmax; }
+        else { sp.e1_b = e1; sp.xmax_b = net->L[q.a].d_xmax; }
+    }
+    sp.round_coef = op.rounded ? (net->coef64 ? kRoundCoef64 : kRoundCoef) : 0.0;
+    sp.coef64 = net->coef64 ? 1 : 0;
+    // what vanishes when a coefficient is stored: below the subnormal step of the storage type, times the
+    // 2^20 by which a substituted ReLU slope (kept >= 2^-20) may have shrunk it
+    sp.coef_floor = net->coef64 ? 0x1p-1050 : 0x1p-128;
+    sp.do_consts = op.do_consts ? 1 : 0;
+    sp.update_best = op.update_best ? 1 : 0;
+    return interval_terms;
+}
+
+// Chains of narrow dense layers: the whole plan of a start layer in ONE launch (chain.hip), the rows' blocks in LDS.
+// Decided by the network alone (layer types and widths), never by the number of rows, so that a box gets the same
+// bits alone and in a batch.  Returns false when the plan is not such a chain (then p is undefined).
+const int kChainMaxHidden = 256, kChainMaxLast = 1024;
+bool build_chain(const gp_net* net, const Plan& pl, int start, gp::ChainParams& p, double* flop_per_row) {
+    const Layer& ls = net->L[start];
+    if (!net->chain_on || net->early || net->float_inference || net->coef64 || net->interval || ls.type != T_DENSE) return false;
+    const size_t nops = pl.ops.size();
+    if (nops < 3 || nops % 2 == 0) return false;                         // INIT SCAN (CROSS SCAN)* FINALIZE
+    if (pl.ops[0].kind != PlanOp::INIT || pl.ops[0].init_mode != 2 || pl.ops[nops - 1].kind != PlanOp::FINALIZE) return false;
+    const int nsteps = (int)(nops - 1) / 2;
+    if (nsteps > gp::kMaxChainSteps) return false;
+    std::memset(&p, 0, sizeof(p));
+    *flop_per_row = 0.0;
+    int hid = 0;
+    for (int st = 0; st < nsteps; ++st) {
+        const PlanOp& op = pl.ops[2 * st];
+        const PlanOp& sc = pl.ops[2 * st + 1];
+        if (sc.kind != PlanOp::SCAN || sc.consts_only || !sc.update_best || sc.slot_in != op.slot_out) return false;
+        if (st > 0 && (op.kind != PlanOp::CROSS || net->L[op.layer_in].type != T_DENSE || op.slot_add >= 0)) return false;
+        const Layer& lb = net->L[sc.layer_in];                         // the layer the block ranges over
+        if (block_elems(sc.g_in, lb) != lb.n) return false;
+        const bool last = st == nsteps - 1;
+        if (lb.n > (last ? kChainMaxLast : kChainMaxHidden)) return false;
+        gp::ScanParams sp;
+        std::memset(&sp, 0, sizeof(sp));
+        if (!scan_setup(net, sc, start, false, sp) || sp.xmax_b || sp.eta) return false;
+        gp::ChainStep& cs = p.steps[st];
+        cs.n = (int)lb.n;
+        cs.grl = op.relaxed ? lb.d_grl : nullptr;
+        if (st > 0) {
+            const Layer& a = net->L[op.layer_in];
+            if (!a.d_wt) return false;
+            cs.K = (int)a.n;
+            cs.w = a.d_wt;
+            *flop_per_row += 2.0 * (double)a.n * (double)lb.n;
+        }
+        cs.cpos = sp.cpos; cs.cneg = sp.cneg; cs.xlo = sp.xlo; cs.xhi = sp.xhi; cs.kap = sp.kap; cs.beff = sp.beff;
+        cs.xmax_self = sp.xmax_self; cs.xmax_a = sp.xmax_a; cs.e1_a = sp.e1_a; cs.round_coef = sp.round_coef;
+        cs.do_consts = sp.do_consts;
+        p.coef_floor = sp.coef_floor;
+        if (!last) hid = std::max(hid, (int)lb.n);
+    }
+    p.nsteps = nsteps;
+    p.w0 = ls.d_wti; p.bias0 = ls.d_bias;
+    p.n_start = (int)ls.n;
+    p.div_n = gp::make_fastdiv((uint32_t)ls.n);
+    // row strides of 4*(odd) floats: the 16 rows of a 16-byte LDS access fall into distinct banks
+    p.hid_stride = ((std::max(hid, 1) + 15) & ~15) + 4;
+    p.last_stride = ((p.steps[nsteps - 1].n + 15) & ~15) + 4;
+    p.lo = ls.d_lo; p.hi = ls.d_hi; p.xmax = ls.d_xmax; p.flag = net->d_flag;
+    return gp::chain_lds_bytes(p) <= 150 * 1024;
+}
+
 // run one plan over all its tasks, chunk by chunk (Section 4.2 "Memory management").
 // With early termination (Sections 3.2, 4.2) the rows' best bounds start from the layer's interval image, tasks
 // whose interval does not strictly contain 0 never start, and after every candidate the tasks that have come to
@@ -705,9 +802,28 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
     const long long n_start = forms ? net->n_forms : certify ? (ls.n - 1) : ls.n;
     const long long total = n_start * batch;
     if (total <= 0) return GP_OK;
+    if (!certify && total < (1LL << 31)) {
+        gp::ChainParams chp;
+        double flop_per_row = 0.0;
+        if (build_chain(net, pl, start, chp, &flop_per_row)) {
+            chp.row0 = 0; chp.Rc = (int)total;
+            prof_mark(net, 0, false);
+            const bool ok = gp::launch_chain(chp, net->stream);
+            prof_mark(net, 0, true);
+            if (!ok) return fail(net, GP_ERR_DEVICE, "the fused chain kernel could not get %zu bytes of LDS", gp::chain_lds_bytes(chp));
+            if (net->prof_on) {
+                net->prof_flop[0] += flop_per_row * 2.0 * (double)total;
+                net->prof_bytes[0] += 16.0 * (double)total;
+                net->prof_recs[0].push_back({2, start, start, (int)(2 * total), 0, 0, 0, 0, flop_per_row * 2.0 * (double)total});
+            }
+            const hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return fail(net, GP_ERR_DEVICE, "kernel launch: %s", hipGetErrorString(e));
+            return GP_OK;
+        }
+    }
     const bool early = net->early && !certify;
     const bool may_stop = early && ls.feeds_relu && !ls.req_bounds && start != (int)net->L.size() - 1;
-    const int csize = net->coef64 ? 8 : 4;              // bytes per stored coefficient
+    const int csize = coef_bytes(net);                  // bytes per stored coefficient
     const long long tb = task_bytes(pl, nsign, csize);
     char* ws; long long ws_bytes;
     gp_status st = get_workspace(net, tb * total + 16384, &ws, &ws_bytes);
@@ -873,45 +989,38 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                 ip.c = d_c; ip.err = d_err; ip.best = d_best;
                 ip.seeded = early ? 1 : 0;
                 ip.coef64 = net->coef64 ? 1 : 0;
-                gp::launch_init(ip, net->stream);
+                if (net->interval) gp::launch_iv_init(ip, net->stream);
+                else gp::launch_init(ip, net->stream);
                 have_rows = true;
+            } else if (op.kind == PlanOp::SCAN && net->interval) {
+                // literal interval coefficients (Section 4.1): the candidate over the block's layer, then the ReLU
+                // substitution as a step of its own (nothing is fused into the product here), then the bias constants
+                const Layer& l = net->L[op.layer_in];
+                gp::IvRowParams rp;
+                std::memset(&rp, 0, sizeof(rp));
+                rp.blk = make_desc(net, slot_ptr(op.slot_in), op.g_in, op.layer_in);
+                rp.rm = rm; rp.nrows = nrows; rp.batch_stride = (int)l.n;
+                rp.c = d_c; rp.best = d_best;
+                if (!op.consts_only && op.update_best && has_bounds(net, op.layer_in) && op.layer_in != start) {
+                    rp.xlo = l.d_lo; rp.xhi = l.d_hi;
+                    gp::launch_iv_cand(rp, net->stream);
+                }
+                if (op.relaxed) {
+                    const Layer& q = net->L[l.a];
+                    rp.xlo = q.d_lo; rp.xhi = q.d_hi; rp.grl = l.d_grl;
+                    gp::launch_iv_relu(rp, net->stream);
+                }
+                if (op.do_consts && !l.land.empty()) {
+                    rp.beff = l.d_beff;
+                    gp::launch_iv_bias(rp, net->stream);
+                }
             } else if (op.kind == PlanOp::SCAN) {
                 const Layer& l = net->L[op.layer_in];
                 gp::ScanParams sp;
                 sp.blk = make_desc(net, slot_ptr(op.slot_in), op.g_in, op.layer_in);
                 sp.rm = rm; sp.nrows = nrows;
                 sp.batch_stride = (int)l.n;
-                const bool interval_terms = !op.consts_only && has_bounds(net, op.layer_in) && op.layer_in != start;
-                sp.cpos = sp.cneg = sp.xlo = sp.xhi = sp.kap = nullptr;
-                sp.xmax_self = nullptr;
-                if (interval_terms) {
-                    if (op.relaxed) {      // coefficients already multiplied by the ReLU slopes: they range over the ReLU's input
-                        const Layer& q = net->L[l.a];
-                        sp.cpos = l.d_rho; sp.cneg = l.d_lo; sp.xlo = q.d_lo; sp.xhi = q.d_hi; sp.xmax_self = q.d_xmax;
-                    } else {
-                        sp.cpos = l.d_hi; sp.cneg = l.d_lo; sp.xlo = l.d_lo; sp.xhi = l.d_hi; sp.xmax_self = l.d_xmax;
-                    }
-                }
-                if (op.relaxed) sp.kap = l.d_kap;
-                sp.beff = l.land.empty() ? nullptr : l.d_beff;
-                // a sum layer's own rows bound the exact sum of its summands; its one rounding is added when they are stored
-                sp.eta = (!certify && op.layer_in == start && l.type == T_ADD) ? l.d_eta_thru : eta_of(net, op.layer_in);
-                sp.e1_a = sp.e1_b = 0.0;
-                sp.xmax_a = sp.xmax_b = nullptr;
-                for (size_t i = 0; i < l.land.size(); ++i) {
-                    const Layer& q = net->L[l.land[i]];
-                    double K = (double)q.kh * q.kw * (q.type == T_POOL ? 1.0 : (double)q.C);   // terms of one new coefficient
-                    double e1 = (K + 8.0) * 0x1p-50 * q.rowabs;
-                    if (i == 0) { sp.e1_a = e1; sp.xmax_a = net->L[q.a].d_xmax; }
-                    else { sp.e1_b = e1; sp.xmax_b = net->L[q.a].d_xmax; }
-                }
-                sp.round_coef = op.rounded ? (net->coef64 ? kRoundCoef64 : kRoundCoef) : 0.0;
-                sp.coef64 = net->coef64 ? 1 : 0;
-                // what vanishes when a coefficient is stored: below the subnormal step of the storage type, times the
-                // 2^20 by which a substituted ReLU slope (kept >= 2^-20) may have shrunk it
-                sp.coef_floor = net->coef64 ? 0x1p-1050 : 0x1p-128;
-                sp.do_consts = op.do_consts ? 1 : 0;
-                sp.update_best = op.update_best ? 1 : 0;
+                const bool interval_terms = scan_setup(net, op, start, certify, sp);
                 sp.c = d_c; sp.err = d_err; sp.best = d_best;
                 sp.done = may_stop ? d_done[cur] : nullptr;
                 sp.partial = chunks_max ? d_partial : nullptr;
@@ -932,7 +1041,7 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                 const Layer& p = net->L[op.layer_out];
                 gp::CrossParams cp;
                 cp.in = make_desc(net, slot_ptr(op.slot_in), op.g_in, op.layer_in, &op.t_in);
-                cp.out_grl = op.relaxed ? p.d_grl : nullptr;
+                cp.out_grl = (op.relaxed && !net->interval) ? p.d_grl : nullptr;
                 cp.wt = a.d_wt;
                 cp.wt64 = a.d_wt64;
                 cp.pool_scale = pool_scale(a);
@@ -962,7 +1071,8 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                 cp.div_sw = gp::make_fastdiv((uint32_t)cp.sw);
                 cp.div_kw = gp::make_fastdiv((uint32_t)cp.kw);
                 prof_mark(net, 0, false);
-                gp::launch_cross(cp, net->stream);
+                if (net->interval) gp::launch_iv_cross(cp, net->stream);
+                else gp::launch_cross(cp, net->stream);
                 prof_mark(net, 0, true);
                 // algorithmic work of the step (Section 2: one product M^k * F^k): every coefficient of the
                 // row's block meets every filter tap and every input channel once; the one-hot start block
@@ -1090,6 +1200,8 @@ gp_status begin_analysis(gp_net* net, int batch) {
     if (batch <= 0) return fail(net, GP_ERR_ARG, "batch must be positive");
     if (net->L.size() < 2) return fail(net, GP_ERR_STATE, "network has no layers");
     net->analyzed = false;
+    if (net->interval && (net->early || net->float_inference))
+        return fail(net, GP_ERR_UNSUPPORTED, "interval coefficients cannot be combined with early termination or float32-inference mode");
     gp_status st = prepare_topology(net);
     if (st != GP_OK) return st;
     // plan everything first so that unsupported topologies fail before any GPU work
@@ -1125,7 +1237,7 @@ gp_status reserve_workspace(gp_net* net, int batch) {
         const Layer& l = net->L[i];
         if (l.type == T_RELU || !l.need_bounds) continue;
         const Plan& pl = net->plans[i];
-        if (pl.valid) want = std::max(want, task_bytes(pl, 2, net->coef64 ? 8 : 4) * l.n * batch + 16384);
+        if (pl.valid) want = std::max(want, task_bytes(pl, 2, coef_bytes(net)) * l.n * batch + 16384);
     }
     char* ws; long long bytes;
     return get_workspace(net, want, &ws, &bytes);
@@ -1357,6 +1469,22 @@ gp_status gp_set_graph_replay(gp_net* net, int32_t on) {
     return GP_OK;
 }
 
+gp_status gp_set_interval_coefficients(gp_net* net, int32_t on) {
+    if (!net) return GP_ERR_ARG;
+    drop_graph(net);
+    net->interval = on != 0;
+    net->analyzed = false;
+    return GP_OK;
+}
+
+gp_status gp_set_chain_fusion(gp_net* net, int32_t on) {
+    if (!net) return GP_ERR_ARG;
+    drop_graph(net);
+    net->chain_on = on != 0;
+    net->analyzed = false;
+    return GP_OK;
+}
+
 gp_status gp_set_coefficient_storage(gp_net* net, int32_t bits) {
     if (!net) return GP_ERR_ARG;
     if (bits != 32 && bits != 64) return fail(net, GP_ERR_ARG, "coefficient storage: 32 or 64 bits");
@@ -1426,7 +1554,7 @@ gp_status gp_workspace_size(const gp_net* cnet, int32_t batch, int64_t* min_byte
         Plan* pl;
         st = get_plan(net, (int)i, &pl);
         if (st != GP_OK) return st;
-        long long tb = task_bytes(*pl, 2, net->coef64 ? 8 : 4);
+        long long tb = task_bytes(*pl, 2, coef_bytes(net));
         mn = std::max(mn, tb + 16384);
         full = std::max(full, tb * net->L[i].n * batch + 16384);
     }
@@ -1521,7 +1649,7 @@ gp_status gp_analyze_batch_dev_static(gp_net* net, int32_t batch, const float* c
         Plan* pl;
         st = get_plan(net, (int)i, &pl);
         if (st != GP_OK) return st;
-        const long long need = task_bytes(*pl, 2, net->coef64 ? 8 : 4) + 16384;
+        const long long need = task_bytes(*pl, 2, coef_bytes(net)) + 16384;
         if (need > kStaticScratchBytes)
             return fail(net, GP_ERR_WORKSPACE, "one row of layer %d needs %lld bytes of workspace; the static workspace of the "
                                                "allocation-free call holds %lld", (int)i, need, kStaticScratchBytes);
@@ -1807,7 +1935,7 @@ gp_status gp_profile_dump(gp_net* net, const char* path) {
             float t = 0.f;
             (void)hipEventElapsedTime(&t, net->prof_ev[k][2 * i], net->prof_ev[k][2 * i + 1]);
             const gp_net::ProfRec& r = net->prof_recs[k][i];
-            fprintf(f, "%s,%d,%d,%d,%d,%d,%d,%d,%.6g,%.2f\n", k == 0 ? "cross" : "scan", r.start, r.layer, r.nrows, r.in_el,
+            fprintf(f, "%s,%d,%d,%d,%d,%d,%d,%d,%.6g,%.2f\n", r.kind == 2 ? "chain" : k == 0 ? "cross" : "scan", r.start, r.layer, r.nrows, r.in_el,
                     r.out_el, r.n, r.k, r.flop, t * 1e3);
         }
     fclose(f);

@@ -219,6 +219,56 @@ struct CopyRowsParams {      // dst row (h*Ra_new + i) = src row (h*Ra_old + sel
     int Ra_old, Ra_new, nsign, nelem;
 };
 
+// ---- fused chain of narrow dense layers (chain.hip): one launch carries the rows of a start layer through every step
+constexpr int kMaxChainSteps = 16;
+struct ChainStep {           // the block after this step and the constants of its candidate (cf. ScanParams)
+    int n;                   // coefficients per row: neurons of the layer the block ranges over
+    int K;                   // contraction length of the product that makes the block (n of the step before); step 0: unused
+    const float* w;          // [n][K] matrix of the dense layer crossed (the crossing layout of its weights); step 0: null
+    const float* grl;        // [batch][n] packed ReLU relaxation substituted into the new coefficients; null: none
+    const double *cpos, *cneg, *xlo, *xhi;   // [batch][n]
+    const double* kap;       // [batch][n] or null
+    const double* beff;      // [n] or null
+    const double* xmax_self; // [batch] or null
+    const double* xmax_a;    // [batch] or null
+    double e1_a;
+    double round_coef;
+    int do_consts;
+};
+struct ChainParams {
+    ChainStep steps[kMaxChainSteps];
+    int nsteps;
+    const float* w0;         // the start layer's matrix [n_start][steps[0].n] (float32) and bias [n_start]
+    const float* bias0;
+    int row0, Rc, n_start;   // tasks row0 .. row0+Rc of batch * n_start
+    FastDiv div_n;
+    int hid_stride, last_stride;   // LDS row strides (floats): every block but the last one / the last one
+    double coef_floor;
+    double* lo; double* hi;  // [batch][n_start] bounds of the start layer
+    double* xmax; int* flag;
+};
+bool launch_chain(const ChainParams& p, hipStream_t s);
+size_t chain_lds_bytes(const ChainParams& p);
+
+// ---- literal interval-coefficient mode (interval.hip): blocks hold [lo, hi] pairs of float64
+struct IvRowParams {         // per-row passes over a block of interval coefficients
+    BlockDesc blk;           // data: [nrows][wy][wx][C] pairs of doubles
+    RowMap rm;
+    int nrows;
+    int batch_stride;        // neurons per box of the layer the block ranges over
+    const double* xlo;       // [batch][n] intervals: of the block's layer (candidate) / of the ReLU's input layer (substitution)
+    const double* xhi;
+    const float* grl;        // [batch][n] packed relaxation of the ReLU layer (substitution)
+    const double* beff;      // [C] bias of the affine layer(s) crossed next (constants)
+    double* c;               // per-row constant (upper end)
+    double* best;            // per-row best candidate
+};
+void launch_iv_init(const InitParams& p, hipStream_t s);
+void launch_iv_cand(const IvRowParams& p, hipStream_t s);
+void launch_iv_relu(const IvRowParams& p, hipStream_t s);
+void launch_iv_bias(const IvRowParams& p, hipStream_t s);
+void launch_iv_cross(const CrossParams& p, hipStream_t s);    // in/out/add hold interval pairs; out_grl, wt64 unused
+
 void launch_cross(const CrossParams& p, hipStream_t s);
 void launch_scan(const ScanParams& p, hipStream_t s);
 void launch_init(const InitParams& p, hipStream_t s);

@@ -20,26 +20,6 @@ namespace gp {
 // The kernels share this arithmetic (scan_term, scan_finish) and differ in how rows and lanes are laid out; which one
 // runs is decided by the row length alone, see launch_scan.
 // ------------------------------------------------------------------------------------------------
-// One coefficient's contribution to the five per-row sums.  Written with explicit fused multiply-adds only, so that
-// every scan kernel performs exactly the same operations in the same order per lane and a row's result does not
-// depend on which kernel (i.e. on how many rows share the launch) handled it.
-template <typename CT>
-__device__ __forceinline__ void scan_term(bool has_cand, bool do_consts, CT mf, double cp, double cn, double X, double kp,
-                                          double be, double& cand, double& absx, double& cst, double& cstabs, double& s1) {
-    const double m = (double)mf;
-    const double am = fabs(m);
-    if (has_cand) {
-        cand = fma(m, mf >= (CT)0 ? cp : cn, cand);
-        absx = fma(am, X, absx);
-    }
-    if (do_consts) {
-        const double mp = fmax(m, 0.0);
-        cst = fma(m, be, fma(mp, kp, cst));
-        cstabs = fma(am, fabs(be), fma(mp, kp, cstabs));
-        s1 += am;
-    }
-}
-
 // The same for the kernels that stage the neurons' constants in LDS, with fewer vector instructions per coefficient
 // (every one of them is paid in time here): the staged multiplier pair is (cpos - cneg, cneg), so that the candidate
 // term needs no select, m*c(m) = max(m,0)*(cpos - cneg) + m*cneg; and the magnitude of the constant terms, which only
@@ -87,31 +67,14 @@ __device__ __forceinline__ ScanRow scan_row_fetch(const ScanParams& p, int r, co
 // constants of the next step added to c, slack of the next accumulation.
 __device__ __forceinline__ void scan_finish(const ScanParams& p, int r, int nelem, const ScanRow& s, double t_cand,
                                             double t_absx, double t_cst, double t_cstabs, double t_s1) {
-    // a sum of n float64 terms in any order is off by at most (n-1)*2^-53*sum|terms|*(1+tiny)
-    const double esum = (double)(nelem + 16) * 0x1p-52;
-    double c = s.c;
-    double err = s.err;
-    // slack of the stored coefficients: |true - stored| <= round_coef*|stored| (+ subnormal floor)
-    err += t_absx * p.round_coef * (1.0 + esum);
-    // values below the float32 subnormal step vanish; with a substituted ReLU the lost coefficient is
-    // up to 2^20 times larger (slopes are kept >= 2^-20)
-    if (p.round_coef > 0.0 && p.xmax_self) err += p.coef_floor * (double)nelem * s.xmax_self;
-    if (p.update_best && p.cpos) {
-        double v = c + t_cand + err;
-        // (the candidate's terms are at most 3*|m|*X in magnitude when the multiplier comes as a difference, see
-        // scan_term_staged)
-        v += (fabs(c) + fabs(t_cand) + err) * 0x1p-50 + 3.0 * t_absx * esum;
-        if (!s.frozen) p.best[s.bi] = fmin(s.best, v);
-    }
-    if (p.do_consts) {
-        double cn = c + t_cst;
-        double e1 = 0.0;
-        if (p.xmax_a) e1 += p.e1_a * s.xmax_a;
-        if (p.xmax_b) e1 += p.e1_b * s.xmax_b;
-        err += t_cstabs * esum + (fabs(c) + fabs(t_cst)) * 0x1p-51 + t_s1 * e1 * (1.0 + esum);
-        c = cn;
-    }
-    err *= (1.0 + 0x1p-48);   // the few float64 operations above
+    double c = s.c, err = s.err, best = s.best;
+    const bool has_cand = p.update_best && p.cpos;
+    double e1 = 0.0;
+    if (p.do_consts && p.xmax_a) e1 += p.e1_a * s.xmax_a;
+    if (p.do_consts && p.xmax_b) e1 += p.e1_b * s.xmax_b;
+    scan_finish_math(nelem, p.round_coef, (p.round_coef > 0.0 && p.xmax_self) ? p.coef_floor * s.xmax_self : 0.0, has_cand,
+                     p.do_consts != 0, e1, t_cand, t_absx, t_cst, t_cstabs, t_s1, c, err, best);
+    if (has_cand && !s.frozen) p.best[s.bi] = best;
     p.c[r] = c;
     p.err[r] = err;
 }

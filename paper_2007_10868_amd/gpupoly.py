@@ -17,7 +17,7 @@ STATUS = {0: "GP_OK", 1: "GP_ERR_ARG", 2: "GP_ERR_SHAPE", 3: "GP_ERR_STATE", 4: 
 
 # every symbol include/gpupoly.h declares
 EXPORTS = ["gp_net_create", "gp_net_destroy", "gp_add_dense", "gp_add_conv2d", "gp_add_avgpool2d", "gp_add_relu", "gp_add_residual",
-           "gp_request_bounds", "gp_set_early_termination", "gp_set_float_inference", "gp_set_coefficient_storage", "gp_set_graph_replay", "gp_get_term_layer", "gp_get_early_termination_stats",
+           "gp_request_bounds", "gp_set_early_termination", "gp_set_float_inference", "gp_set_coefficient_storage", "gp_set_chain_fusion", "gp_set_interval_coefficients", "gp_set_graph_replay", "gp_get_term_layer", "gp_get_early_termination_stats",
            "gp_set_stream", "gp_workspace_size", "gp_set_workspace", "gp_analyze",
            "gp_analyze_box", "gp_analyze_batch", "gp_analyze_batch_dev", "gp_analyze_batch_dev_static", "gp_get_bounds", "gp_get_bounds_batch",
            "gp_get_bounds_f64", "gp_get_relu_lambda", "gp_get_relu_slopes", "gp_certify", "gp_certify_batch", "gp_bound_outputs", "gp_debug_plan",
@@ -57,6 +57,8 @@ def load_library():
     L.gp_set_early_termination.argtypes = [P, i32]
     L.gp_set_float_inference.argtypes = [P, i32]
     L.gp_set_coefficient_storage.argtypes = [P, i32]
+    L.gp_set_chain_fusion.argtypes = [P, i32]
+    L.gp_set_interval_coefficients.argtypes = [P, i32]
     L.gp_set_graph_replay.argtypes = [P, i32]
     L.gp_get_term_layer.argtypes = [P, i32, i32, ip]
     L.gp_get_early_termination_stats.argtypes = [P, dp, dp]
@@ -175,6 +177,14 @@ class Net:
     def set_coefficient_storage(self, bits=32):
         """32 (default): coefficients stored in float32; 64: in float64 (the paper's double precision build, Section 5)."""
         self._chk(self._L.gp_set_coefficient_storage(self._h, bits))
+
+    def set_interval_coefficients(self, on=True):
+        """The literal scheme of Section 4.1: interval coefficients with directed rounding, kept to the end."""
+        self._chk(self._L.gp_set_interval_coefficients(self._h, 1 if on else 0))
+
+    def set_chain_fusion(self, on=True):
+        """Chains of narrow dense layers in one fused launch per start layer (default) or through the general kernels."""
+        self._chk(self._L.gp_set_chain_fusion(self._h, 1 if on else 0))
 
     def set_graph_replay(self, on=True):
         """Capture the launches of an analysis into a HIP graph once and replay it on later calls."""

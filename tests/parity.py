@@ -15,9 +15,11 @@ REL_TOL = 1e-3          # a GPU bound may be looser than the oracle's by at most
 # one of the comparisons (worst violation <= 0); the bar leaves room for the slope effect only:
 CONTAIN_TOL = 1e-6
 # With early termination a stopped neuron keeps the intersection of its interval image and its candidates so far, and
-# the two sides reach that intersection from slightly different slopes: 2 877 comparisons of the GPU suite, worst
-# violation 1.3e-6 (scaled 34-layer residual net; 1.3e-7 elsewhere).  Twice the measured worst:
-EARLY_CONTAIN_TOL = 3e-6
+# the two sides reach that intersection from slightly different slopes.  Measured over the GPU suite (2 877
+# comparisons): worst violation 1.3e-6 in one build and 8.8e-6 in another that differs only in the order of some float64
+# sums (scaled 34-layer residual net both times; 1.3e-7 on every other network): which neurons stop where moves with
+# the last bits, and the figure with it.  Five times the worst seen:
+EARLY_CONTAIN_TOL = 5e-5
 # When the oracle is told to use the GPU's slopes and lower-line choices, every transformer is monotone
 # in the intervals and the GPU intervals must contain the oracle's up to float64 rounding noise:
 STRICT_CONTAIN_TOL = 1e-9

@@ -47,9 +47,12 @@ def test_dense_chain(seed):
     nb = int([1, 2, 7, 40, 130][seed % 5])
     X = rng.random((nb, net.n_in)).astype(np.float32)
     layers = sorted(set(analysed_layers(net)) | set(affine_read_layers(net)))
-    for bits, bar in ((32, 1e-3), (64, 1e-8)):
+    # float32 storage twice: start layers whose chain is narrow enough take the fused chain kernel by default; with it
+    # switched off every layer takes the general crossing and scan kernels
+    for bits, bar, fused in ((32, 1e-3, True), (32, 1e-3, False), (64, 1e-8, False)):
         g = make_gpu(net)
         g.set_coefficient_storage(bits)
+        g.set_chain_fusion(fused)
         g.analyze_batch(X, net.eps)
         for b in sorted({0, nb - 1, int(rng.integers(0, nb))}):
             o = make_oracle(net)
@@ -59,4 +62,4 @@ def test_dense_chain(seed):
                 glo, ghi = g.get_bounds_f64(lid, b)
                 loose = max(np.max((olo - glo) / (1 + np.abs(olo))), np.max((ghi - ohi) / (1 + np.abs(ohi))))
                 inside = max(np.max((glo - olo) / (1 + np.abs(olo))), np.max((ohi - ghi) / (1 + np.abs(ohi))))
-                assert loose <= bar and inside <= 1e-12, (bits, seed, nb, b, lid, loose, inside)
+                assert loose <= bar and inside <= 1e-12, (bits, fused, seed, nb, b, lid, loose, inside)

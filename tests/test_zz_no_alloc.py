@@ -25,10 +25,10 @@ def _reference(net, centers, eps):
     return {l: [g.get_bounds_f64(l, b) for b in range(centers.shape[0])] for l in analysed_layers(net)}
 
 
-@pytest.mark.parametrize("cfg,first,second", [(1, 16, 5), (2, 12, 3)])
+@pytest.mark.parametrize("cfg,first,second", [(1, 16, 5), (2, 12, 3), (0, 10, 3)])
 def test_static_workspace_call_gives_the_same_bits_twice_in_a_row(cfg, first, second):
     """FC 9x500 with 16 boxes needs 101 MB of workspace, so the 32 MiB static array forces row chunks; small conv takes
-    the narrow-layer kernels.  Reference: gp_analyze_batch_dev on a net of its own."""
+    the narrow-layer kernels; FC 6x100 goes through the fused chain kernel, which needs no workspace at all.  Reference: gp_analyze_batch_dev on a net of its own."""
     net = wl.config(cfg)
     centers = np.stack([net.center(j) for j in range(first)])
     ref_first = _reference(net, centers, net.eps)
