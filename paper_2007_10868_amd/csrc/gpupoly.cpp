@@ -807,11 +807,13 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
         double flop_per_row = 0.0;
         if (build_chain(net, pl, start, chp, &flop_per_row)) {
             chp.row0 = 0; chp.Rc = (int)total;
-            prof_mark(net, 0, false);
+            // (timed as a crossing launch when it contains products; a plan without any is bookkeeping only)
+            const bool timed = flop_per_row > 0.0;
+            if (timed) prof_mark(net, 0, false);
             const bool ok = gp::launch_chain(chp, net->stream);
-            prof_mark(net, 0, true);
+            if (timed) prof_mark(net, 0, true);
             if (!ok) return fail(net, GP_ERR_DEVICE, "the fused chain kernel could not get %zu bytes of LDS", gp::chain_lds_bytes(chp));
-            if (net->prof_on) {
+            if (net->prof_on && timed) {
                 net->prof_flop[0] += flop_per_row * 2.0 * (double)total;
                 net->prof_bytes[0] += 16.0 * (double)total;
                 net->prof_recs[0].push_back({2, start, start, (int)(2 * total), 0, 0, 0, 0, flop_per_row * 2.0 * (double)total});

@@ -47,7 +47,8 @@ def test_fused_chain_matches_oracle_and_general_kernels(name, maker, eps):
     g = make_gpu(net)
     n_dense = sum(1 for L in net.layers if L["type"] == "dense")
     cross, scan = launches(g, X, eps)
-    assert (cross, scan) == (n_dense, 0), (cross, scan)        # every start layer went through the fused kernel, once
+    assert (cross, scan) == (n_dense - 1, 0), (cross, scan)    # every start layer went through the fused kernel, once (the first
+                                                                # one has no product in it and is not counted as a crossing launch)
     fused = {l: [g.get_bounds_f64(l, b) for b in range(5)] for l in analysed_layers(net)}
     for b in (0, 4):
         o = make_oracle(net)
@@ -85,7 +86,7 @@ def test_which_layers_take_the_fused_path():
     X = rng.random((2, net.n_in)).astype(np.float32)
     g = make_gpu(net)
     cross, scan = launches(g, X, 0.01)
-    assert cross == 2 + (2 + 3) and scan == (3 + 4)
+    assert cross == 1 + (2 + 3) and scan == (3 + 4)
     o = make_oracle(net)
     oracle_with_gpu_ties(net, o, g, X[1], 0.01, batch_index=1)
     compare_all(net, g, o, batch_index=1, what="mixed")
