@@ -131,8 +131,16 @@ def measure(args, cfg, net, batch, steps, warmup, extras, n_cpu):
     early = None
     if args.early_term:
         done, full_flop = g.early_termination_stats()
+        # share of the ReLU inputs of the first box whose sign is decided (the regime Section 3.2 speaks about)
+        n_relu_in, n_stable = 0, 0
+        for L in net.layers:
+            if L["type"] == "relu":
+                lo, hi = g.get_bounds_f64(L["src"], 0)
+                n_relu_in += lo.size
+                n_stable += int(np.sum((lo >= 0) | (hi <= 0)))
         early = dict(crossing_flop_done=done, crossing_flop_without_removal=full_flop,
-                     fraction=round(done / full_flop, 4) if full_flop > 0 else None)
+                     fraction=round(done / full_flop, 4) if full_flop > 0 else None,
+                     stable_relu_inputs=round(n_stable / max(n_relu_in, 1), 4))
     ms_per_step = wall_ms / steps
     ms_per_input = ms_per_step / batch
 

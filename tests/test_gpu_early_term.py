@@ -175,3 +175,21 @@ def test_scaled_resnet():
     stopped = check_early(net, g, c, eps, what=net.name, samples=20)
     done, full = g.early_termination_stats()
     print(f"{net.name}: {stopped} neurons stopped early; crossing work {done / full:.3f} of full")
+
+
+def test_contracted_resnet34_every_neuron_with_replayed_decisions():
+    """The 1M-neuron residual configuration in the regime early termination is for: every weight times 0.05, so that
+    99.9 % of the ReLU inputs have a decided sign and almost every row stops at once (50 ms per input on the GPU).  The
+    oracle in its early-termination mode then finishes a whole pass in well under a minute, so EVERY interval of EVERY
+    layer is compared (966 666 back-substituted neurons, decisions replayed), the oracle's own decisions are compared
+    with the library's, and sampled outputs are checked."""
+    net = wl.contracted(wl.config(4), 0.05)
+    c = net.center(0)
+    g = make_gpu(net)
+    g.set_early_termination(True)
+    g.analyze(c, net.eps)
+    stopped = check_early(net, g, c, net.eps, what="resnet34 x0.05", samples=32)
+    done, full = g.early_termination_stats()
+    n_relu_in = sum(net.n_neurons(L["src"]) for L in net.layers if L["type"] == "relu")
+    print(f"contracted resnet34: {stopped} of {n_relu_in} ReLU inputs stopped early; crossing work {done / full:.5f} of full")
+    assert stopped > 0.99 * n_relu_in and done < 0.01 * full
