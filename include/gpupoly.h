@@ -230,6 +230,15 @@ gp_status gp_profile_read(gp_net* net, int64_t* launches, double* total_ms, doub
  * algorithmic flop, duration in us), written to `path`; call it before gp_profile_read. */
 gp_status gp_profile_dump(gp_net* net, const char* path);
 
+/* Study hook: the unit roundoff at which the accumulation-error term of a crossing is priced.  A crossing adds
+ * (K+8) * unit * (largest absolute row sum of the layer's matrix) * max|x| * sum|m| to a row's slack for the sum of K
+ * products it forms per new coefficient; the default 2^-50 covers the float64 matrix instruction.  A larger value
+ * makes the analysis report the bounds it would report if the products were accumulated in a narrower format with that
+ * unit roundoff and the same a-priori error term (2^-24: float32; Section 4.1 discusses the cost of sound floating
+ * point) - the arithmetic itself stays float64, so the bounds stay sound - which is how the slack of such a kernel is
+ * measured against the oracle before anyone builds it.  unit in [2^-50, 2^-8]. */
+gp_status gp_debug_set_accumulation_roundoff(gp_net* net, double unit);
+
 /* Self-check of the matrix instruction the crossing kernel relies on: D[16][16] = A[16][K] * B[K][16]
  * in float64 MFMA (K a multiple of 4; A, B, D row-major in device memory), enqueued on hip_stream.
  * The rounding slack of a crossing assumes |D - exact| <= (K+8) * 2^-50 * sum|terms|; tests check it. */

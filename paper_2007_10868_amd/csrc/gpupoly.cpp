@@ -136,6 +136,7 @@ struct gp_net {
     // blocks live in the library's static device array
     bool static_call = false;
     void* static_ws = nullptr;
+    double acc_unit = 0x1p-50;     // unit roundoff the accumulation-error term is priced at (gp_debug_set_accumulation_roundoff)
     bool interval = false;         // the paper's literal scheme: interval coefficients, directed rounding (Section 4.1)
     bool chain_on = true;          // chains of narrow dense layers go through the fused kernel (gp_set_chain_fusion)
     int* d_count = nullptr;
@@ -722,7 +723,7 @@ bool scan_setup(const gp_net* net, const PlanOp& op, int start, bool certify, gp
     for (size_t i = 0; i < l.land.size(); ++i) {
         const Layer& q = net->L[l.land[i]];
         double K = (double)q.kh * q.kw * (q.type == T_POOL ? 1.0 : (double)q.C);   // terms of one new coefficient
-        double e1 = (K + 8.0) * 0x1p-50 * q.rowabs;
+        double e1 = (K + 8.0) * net->acc_unit * q.rowabs;
         if (i == 0) { sp.e1_a = e1; sp.xmax_a = net->L[q.a].d_xmax; }
         else { sp.e1_b = e1; sp.xmax_b = net->L[q.a].d_xmax; }
     }
@@ -1468,6 +1469,15 @@ gp_status gp_set_graph_replay(gp_net* net, int32_t on) {
     if (!net) return GP_ERR_ARG;
     net->graph_on = on != 0;
     if (!net->graph_on) drop_graph(net);
+    return GP_OK;
+}
+
+gp_status gp_debug_set_accumulation_roundoff(gp_net* net, double unit) {
+    if (!net) return GP_ERR_ARG;
+    if (!(unit >= 0x1p-50) || !(unit <= 0x1p-8)) return fail(net, GP_ERR_ARG, "unit roundoff must lie in [2^-50, 2^-8]");
+    drop_graph(net);
+    net->acc_unit = unit;
+    net->analyzed = false;
     return GP_OK;
 }
 

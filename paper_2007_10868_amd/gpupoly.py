@@ -20,7 +20,7 @@ EXPORTS = ["gp_net_create", "gp_net_destroy", "gp_add_dense", "gp_add_conv2d", "
            "gp_request_bounds", "gp_set_early_termination", "gp_set_float_inference", "gp_set_coefficient_storage", "gp_set_chain_fusion", "gp_set_interval_coefficients", "gp_set_graph_replay", "gp_get_term_layer", "gp_get_early_termination_stats",
            "gp_set_stream", "gp_workspace_size", "gp_set_workspace", "gp_analyze",
            "gp_analyze_box", "gp_analyze_batch", "gp_analyze_batch_dev", "gp_analyze_batch_dev_static", "gp_get_bounds", "gp_get_bounds_batch",
-           "gp_get_bounds_f64", "gp_get_relu_lambda", "gp_get_relu_slopes", "gp_certify", "gp_certify_batch", "gp_bound_outputs", "gp_debug_plan",
+           "gp_get_bounds_f64", "gp_get_relu_lambda", "gp_get_relu_slopes", "gp_certify", "gp_certify_batch", "gp_bound_outputs", "gp_debug_plan", "gp_debug_set_accumulation_roundoff",
            "gp_profile_enable", "gp_profile_read", "gp_profile_dump", "gp_debug_mfma_f64", "gp_debug_mfma_f64_4col", "gp_num_layers", "gp_layer_size", "gp_last_error", "gp_version"]
 
 
@@ -58,6 +58,7 @@ def load_library():
     L.gp_set_float_inference.argtypes = [P, i32]
     L.gp_set_coefficient_storage.argtypes = [P, i32]
     L.gp_set_chain_fusion.argtypes = [P, i32]
+    L.gp_debug_set_accumulation_roundoff.argtypes = [P, C.c_double]
     L.gp_set_interval_coefficients.argtypes = [P, i32]
     L.gp_set_graph_replay.argtypes = [P, i32]
     L.gp_get_term_layer.argtypes = [P, i32, i32, ip]
@@ -181,6 +182,10 @@ class Net:
     def set_interval_coefficients(self, on=True):
         """The literal scheme of Section 4.1: interval coefficients with directed rounding, kept to the end."""
         self._chk(self._L.gp_set_interval_coefficients(self._h, 1 if on else 0))
+
+    def debug_set_accumulation_roundoff(self, unit: float):
+        """Price the accumulation-error term of every crossing at this unit roundoff (default 2^-50); a study hook."""
+        self._chk(self._L.gp_debug_set_accumulation_roundoff(self._h, float(unit)))
 
     def set_chain_fusion(self, on=True):
         """Chains of narrow dense layers in one fused launch per start layer (default) or through the general kernels."""
