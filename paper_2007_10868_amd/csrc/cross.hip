@@ -1271,6 +1271,163 @@ __global__ __launch_bounds__(256, 2) void cross_strip_kernel(const CrossParams p
     }
 }
 
+// The strip kernel for 3x3 filters, walking the window: in the kernel above every block row is fetched by the three
+// output rows it reaches (three work-groups) and measured HBM traffic is 2.2x the block's bytes at 3.4 TB/s, which is
+// what bounds those launches.  Here a work-group owns a strip of P output pixels over the WHOLE height of the window
+// and walks the block rows from the bottom of the window up; a block value is loaded and converted once and multiplied
+// into the three output rows it reaches (filter rows f = 0, 1, 2 -> output rows y - ph + f), whose accumulators are
+// live at the same time; an output row is finished, and stored, after the third block row that reaches it.  Walking UP
+// makes an output row receive its filter rows in ascending f, then taps, then channel steps: the order of
+// cross_direct_kernel and of the kernel above, with the same instruction on the same operands, so a row gets the same
+// bits from any of the three.  The walk is unrolled by three block rows so that the accumulator an output row uses
+// (row mod 3) is a compile-time index.
+// grid: (row tile of 128 rows, strip) in the XCD-aware order of cross_kernel; p.div_opix divides by the strips per tile.
+template <int P>
+__global__ __launch_bounds__(256, 2) void cross_stripwalk_kernel(const CrossParams p) {
+    constexpr int TM = 2, KW = 3, KH = 3;
+    extern __shared__ __attribute__((aligned(16))) double s_w[];          // [tap][4][Ck + 2]
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lk = lane >> 4, lm = lane & 15;
+    const int Ck = p.in.C, N = p.Co, ldw = Ck + 2;
+    const int nstrips = (p.owx + P - 1) / P;
+    const uint32_t total = (uint32_t)nstrips * (uint32_t)p.ntiles_m;
+    const uint32_t per_xcd = (total + 7u) >> 3;
+    const uint32_t logical = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+    if (logical >= total) return;
+    {   // filter -> LDS (all waves, before any of them leaves)
+        const int cnt = KH * KW * 4 * Ck;
+        for (int idx = tid; idx < cnt; idx += 256) {
+            const int c = idx % Ck, tn = idx / Ck, n = tn & 3, t = tn >> 2;
+            s_w[tn * ldw + c] = n < N ? p.wt64[((size_t)t * N + n) * Ck + c] : 0.0;
+        }
+        __syncthreads();
+    }
+    const uint32_t rt = fast_div(logical, p.div_opix);
+    const int pb0 = (int)(logical - rt * (uint32_t)nstrips) * P;
+    const int Pv = min(P, p.owx - pb0);
+    const int r_wave = (int)rt * 128 + wave * 32;
+    if (r_wave >= p.nrows) return;
+    const int rows_here = min(32, p.nrows - r_wave);
+    const RowInfo u0 = row_info(p.rm, r_wave), u1 = row_info(p.rm, r_wave + rows_here - 1);
+    if (!(u0.b == u1.b && u0.ys == u1.ys && u0.xs == u1.xs)) return;       // excluded by the launcher's conditions
+    const int opix = p.owy * p.owx;
+    const uint32_t row_elems = (uint32_t)(p.in.wy * p.in.wx * Ck);
+    const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(p.in.data + (size_t)r_wave * row_elems), 0, (int)((uint32_t)rows_here * row_elems * 4u), 0x00020000);
+    // geometry of the wave's common position (scalar)
+    const int oiy = clampi(p.in.Sy * u0.ys - p.in.Py, 0, p.in.H - p.in.wy), oix = clampi(p.in.Sx * u0.xs - p.in.Px, 0, p.in.W - p.in.wx);
+    const int A0 = clampi(p.oSy * u0.ys - p.oPy, 0, p.Ho - p.owy), B0 = clampi(p.oSx * u0.xs - p.oPx, 0, p.Wo - p.owx) + pb0;
+    const int ty = p.in.tSy * u0.ys - p.in.tPy, tx = p.in.tSx * u0.xs - p.in.tPx;
+    const int ylo = max(max(ty, oiy), 0), yhi = min(min(ty + p.in.tWy, oiy + p.in.wy), p.in.H);
+    const int xlo = max(max(tx, oix), 0), xhi = min(min(tx + p.in.tWx, oix + p.in.wx), p.in.W);
+    uint32_t a_voff[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int rl = i * 16 + lm;
+        a_voff[i] = rl < rows_here ? ((uint32_t)rl * row_elems + 4u * (uint32_t)lk) * 4u : kOOB;
+    }
+    const double* const w_lane = s_w + (lm & 3) * ldw + 4 * lk;
+    double acc[3][TM][P];
+#pragma unroll
+    for (int sl = 0; sl < 3; ++sl)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int q = 0; q < P; ++q) acc[sl][i][q] = 0.0;
+    const int n = lm & 3;
+    const bool has_add = p.add.data != nullptr;
+    const int add_oy = has_add ? clampi(p.add.Sy * u0.ys - p.add.Py, 0, p.add.H - p.add.wy) : 0;
+    const int add_ox = has_add ? clampi(p.add.Sx * u0.xs - p.add.Px, 0, p.add.W - p.add.wx) : 0;
+    constexpr int NJ = P + KW - 1;
+    const int xj0 = B0 + p.pw - (KW - 1);
+
+    // block row t (relative: y = A0 + ph + t) reaches the window's output rows pa = t + f; C = t mod 3 (compile time)
+    auto block_row = [&](int t, auto Cc) {
+        constexpr int C = decltype(Cc)::value;
+        const int y = A0 + p.ph + t;
+        if (y >= ylo && y < yhi) {
+            const uint32_t row_off = (uint32_t)((y - oiy) * p.in.wx - oix) * (uint32_t)Ck;
+#pragma unroll
+            for (int jj = 0; jj < NJ; ++jj) {
+                const int j = NJ - 1 - jj;
+                const int x = xj0 + j;
+                if (x < xlo || x >= xhi) continue;                                      // uniform
+                for (int d0 = 0; d0 < Ck; d0 += 16) {
+                    const uint32_t soff = (row_off + (uint32_t)x * (uint32_t)Ck + (uint32_t)d0) * 4u;
+                    uint4_t raw[TM];
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) raw[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, (int)a_voff[i], (int)soff, 0);
+                    double av[TM][4];
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) {
+                        av[i][0] = (double)__uint_as_float(raw[i].x); av[i][1] = (double)__uint_as_float(raw[i].y);
+                        av[i][2] = (double)__uint_as_float(raw[i].z); av[i][3] = (double)__uint_as_float(raw[i].w);
+                    }
+#pragma unroll
+                    for (int f = 0; f < KH; ++f) {
+                        const int pa = t + f;
+                        if (pa < 0 || pa >= p.owy) continue;                            // uniform: window's top and bottom
+                        const double* const w_row = w_lane + f * KW * 4 * ldw;
+                        double bf[KW][4];
+#pragma unroll
+                        for (int g = 0; g < KW; ++g) {
+                            const int q = j - (KW - 1) + g;
+                            if (q < 0 || q >= P) continue;                              // compile time
+                            const double2* src = reinterpret_cast<const double2*>(w_row + g * 4 * ldw + d0);
+                            const double2 v0 = src[0], v1 = src[1];
+                            bf[g][0] = v0.x; bf[g][1] = v0.y; bf[g][2] = v1.x; bf[g][3] = v1.y;
+                        }
+#pragma unroll
+                        for (int k = 0; k < 4; ++k)
+#pragma unroll
+                            for (int g = 0; g < KW; ++g) {
+                                const int q = j - (KW - 1) + g;
+                                if (q < 0 || q >= P) continue;                          // compile time
+#pragma unroll
+                                for (int i = 0; i < TM; ++i)
+                                    acc[(C + f) % 3][i][q] =
+                                        __builtin_amdgcn_mfma_f64_4x4x4f64(av[i][k], bf[g][k], acc[(C + f) % 3][i][q], 0, 0, 0);
+                            }
+                    }
+                }
+            }
+        }
+        // output row pa = t + 2 has now received its three filter rows: store it and free its accumulators
+        const int pa = t + 2;
+        if (pa >= 0 && pa < p.owy) {
+            const int A = A0 + pa;
+#pragma unroll
+            for (int q = 0; q < P; ++q) {
+                if (q < Pv) {
+                    const int B = B0 + q, pix = pa * p.owx + pb0 + q;
+                    const long long ridx = (long long)u0.b * ((long long)p.Ho * p.Wo * N) + (long long)(A * p.Wo + B) * N;
+                    const int ay = A - add_oy, ax = B - add_ox;
+                    const bool add_in = has_add && ay >= 0 && ay < p.add.wy && ax >= 0 && ax < p.add.wx;
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) {
+                        const int rl = i * 16 + 4 * (lm >> 2) + lk;
+                        const int r = r_wave + rl;
+                        if (r >= p.nrows || n >= N) continue;
+                        double v = acc[(C + 2) % 3][i][q];
+                        if (add_in) v += (double)p.add.data[((size_t)r * p.add.wy * p.add.wx + (size_t)(ay * p.add.wx + ax)) * N + n];
+                        if (p.out_grl) v *= (double)relax_factor(v, p.out_grl[ridx + n]);
+                        p.out[((size_t)r * opix + pix) * N + n] = (float)v;
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < TM; ++i) acc[(C + 2) % 3][i][q] = 0.0;
+            }
+        }
+    };
+    // relative block rows from the bottom of the window (owy - 1) up to -2, in groups whose first member is 2 (mod 3)
+    const int t_first = (p.owy - 1) + (2 - (p.owy - 1) % 3 + 3) % 3;       // smallest t >= owy - 1 with t = 2 (mod 3)
+    for (int tt = t_first; tt >= -1; tt -= 3) {
+        if (tt <= p.owy - 1) block_row(tt, std::integral_constant<int, 2>{});
+        if (tt - 1 <= p.owy - 1) block_row(tt - 1, std::integral_constant<int, 1>{});
+        if (tt - 2 <= p.owy - 1 && tt - 2 >= -2) block_row(tt - 2, std::integral_constant<int, 0>{});
+    }
+}
+
 // does the strip kernel apply?  (stride 1, filter rows of 3 taps, whole channel steps, filter fits in LDS, and every group
 // of 32 consecutive rows is one position of the start layer in one box)
 static bool strip_applies(const CrossParams& p, size_t& lds) {
@@ -1288,6 +1445,12 @@ static void launch_cross_strip(const CrossParams& p0, size_t lds, hipStream_t s)
     p.div_opix = make_fastdiv((uint32_t)(p.owy * nstrips));
     const long long total = (long long)p.ntiles_m * p.owy * nstrips;
     const unsigned blocks = (unsigned)(((total + 7) / 8) * 8);
+    if (p.kw == 3 && p.kh == 3) {       // 3x3: the form that walks the window and reads every block row once
+        p.div_opix = make_fastdiv((uint32_t)nstrips);
+        const long long wtotal = (long long)p.ntiles_m * nstrips;
+        hipLaunchKernelGGL((cross_stripwalk_kernel<P>), dim3((unsigned)(((wtotal + 7) / 8) * 8)), dim3(256), lds, s, p);
+        return;
+    }
     if (p.kw == 3) hipLaunchKernelGGL((cross_strip_kernel<P, 3>), dim3(blocks), dim3(256), lds, s, p);
     else hipLaunchKernelGGL((cross_strip_kernel<P, 5>), dim3(blocks), dim3(256), lds, s, p);
 }
