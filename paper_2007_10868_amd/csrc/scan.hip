@@ -168,13 +168,22 @@ __global__ __launch_bounds__(256) void scan_tall_kernel(const ScanParams p) {
 // lanes of different rows read the same LDS words (broadcast).  Rows of a work-group that do not share box and
 // window origin are handled run by run.
 constexpr int SCAN_LDS_MAX = 1024;      // longest row whose constants are staged whole (40 KB of LDS)
+constexpr int SCAN_TALL_MAX = 64;       // longest row that takes scan_tall_kernel
+constexpr int SCAN_PRE_ROWS = 16384;    // launches up to this many rows take the form that requests everything up front
 constexpr int SCAN_CHUNK = 512;         // chunk of longer rows (20 KB of LDS: 8 work-groups per CU)
 // ROWS per work-group (8 lanes each); the grouping does not touch a row's arithmetic.
 // U: row slices (8 lanes x V elements each) whose loads are in flight together.
 // CHUNKED: rows longer than SCAN_LDS_MAX are cut into chunks of SCAN_CHUNK coefficients, one work-group per (32 rows,
 // chunk); the five sums of a (row, chunk) go to p.partial and scan_combine_kernel adds a row's chunks in order.
-template <int V, int ROWS, int U, bool CHUNKED, typename CT>
+// HC / DC: the launch has candidate multipliers (p.cpos) / adds the constants of the next step (p.do_consts).  As
+// compile-time constants they leave the loop over a row's coefficients without branches, so that the LDS reads of a
+// slice are issued together and their latency passes once per slice instead of once per coefficient.
+// PRE: the row fits U slices per lane; they and the row's scalars are requested before the constants are staged, so
+// that a launch with few rows (whose time is a chain of memory round trips, not bandwidth) waits for the constants,
+// the row and the scalars at once instead of one after the other.  None of this touches a row's arithmetic or its order.
+template <int V, int ROWS, int U, bool CHUNKED, typename CT, bool HC, bool DC, bool PRE = false>
 __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) {
+    static_assert(!(PRE && CHUNKED), "a chunked row does not fit the lane's registers");
     constexpr int SCAN_LDS_ROWS = ROWS;
     constexpr int NT = ROWS * 8;
     extern __shared__ __attribute__((aligned(16))) double s_const[];     // [5][nelem_pad]
@@ -208,9 +217,7 @@ __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) 
         s_ox[kk] = clampi(B.Sx * ri.xs - B.Px, 0, B.W - B.wx);
     }
     if (tid == 0) s_qmax[0] = s_qmax[1] = 0ull;
-    __syncthreads();
     const CT* src = reinterpret_cast<const CT*>(B.data) + (size_t)r * nelem;
-    double cand = 0.0, absx = 0.0, cst = 0.0, cstabs = 0.0, s1 = 0.0;
     auto load_slices = [&](int e0, CT (&mf)[U][V]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -218,16 +225,40 @@ __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) 
             if (e < c1) scan_load<CT, V>(src + e, mf[u]);
         }
     };
+    // (the row's scalars first: the loads behind a dependent one would have to arrive before it could be used)
+    CT mf_pre[PRE ? U : 1][PRE ? V : 1];
+    ScanRow row_pre;
+    if constexpr (PRE) {
+        if (valid && sub == 0) row_pre = scan_row_fetch(p, r, ri);
+        if (valid) load_slices(c0 + sub * V, mf_pre);
+    }
+    __syncthreads();
+    double cand = 0.0, absx = 0.0, cst = 0.0, cstabs = 0.0, s1 = 0.0;
     auto add_slices = [&](int e0, const CT (&mf)[U][V]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int e = e0 + u * 8 * V;
             if (e < c1) {
                 const int k = e - c0;
+                // the slice's constants: V consecutive doubles of each staged array (V = 4: 32-byte aligned)
+                double kcp[V], kcn[V], kX[V], kkp[V], kbe[V];
+                auto fetch = [&](const double* a, double (&d)[V]) {
+                    if constexpr (V == 4) {
+                        const double2 t0 = reinterpret_cast<const double2*>(a + k)[0];
+                        const double2 t1 = reinterpret_cast<const double2*>(a + k)[1];
+                        d[0] = t0.x; d[1 % V] = t0.y; d[2 % V] = t1.x; d[3 % V] = t1.y;
+                    } else {
+#pragma unroll
+                        for (int v = 0; v < V; ++v) d[v] = a[k + v];
+                    }
+                };
+#pragma unroll
+                for (int v = 0; v < V; ++v) kcp[v] = kcn[v] = kX[v] = kkp[v] = kbe[v] = 0.0;
+                if constexpr (HC) { fetch(s_cp, kcp); fetch(s_cn, kcn); fetch(s_X, kX); }
+                if constexpr (DC) { fetch(s_kp, kkp); fetch(s_be, kbe); }
 #pragma unroll
                 for (int v = 0; v < V; ++v)
-                    scan_term_staged(p.cpos != nullptr, p.do_consts != 0, mf[u][v], s_cp[k + v], s_cn[k + v], s_X[k + v],
-                                     s_kp[k + v], s_be[k + v], cand, absx, cst, s1);
+                    scan_term_staged(HC, DC, mf[u][v], kcp[v], kcn[v], kX[v], kkp[v], kbe[v], cand, absx, cst, s1);
             }
         }
     };
@@ -260,12 +291,12 @@ __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) 
                 j = bbase + ((long long)((oy0 + a) * B.W + (ox0 + bb)) * B.C + c);
             }
             double cp = 0.0, cn = 0.0, X = 0.0, kp = 0.0, be = 0.0;
-            if (p.cpos) {
+            if constexpr (HC) {
                 cp = p.cpos[j];
                 cn = p.cneg[j];
                 X = fmax(fabs(p.xlo[j]), fabs(p.xhi[j]));
             }
-            if (p.do_consts) {
+            if constexpr (DC) {
                 if (p.kap) kp = p.kap[j];
                 if (p.beff) be = p.beff[c];
                 if (p.eta) { const double et = p.eta[j]; kp += 2.0 * et; be -= et; }
@@ -274,7 +305,7 @@ __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) 
             s_cp[k] = cp - cn; s_cn[k] = cn; s_X[k] = X; s_kp[k] = kp; s_be[k] = be;
             qmax = fmax(qmax, fabs(be) + kp);
         }
-        if (p.do_consts) {
+        if constexpr (DC) {
 #pragma unroll
             for (int off = 32; off > 0; off >>= 1) qmax = fmax(qmax, __shfl_xor(qmax, off, 64));
             // non-negative doubles order like their bit patterns
@@ -283,10 +314,14 @@ __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) 
         __syncthreads();
         if (valid && kk >= k0 && kk < k1) {
             const double s1_before = s1;
-            for (int e0 = c0 + sub * V; e0 < c1; e0 += U * 8 * V) {
-                CT mf[U][V];
-                load_slices(e0, mf);
-                add_slices(e0, mf);
+            if constexpr (PRE) {
+                add_slices(c0 + sub * V, mf_pre);
+            } else {
+                for (int e0 = c0 + sub * V; e0 < c1; e0 += U * 8 * V) {
+                    CT mf[U][V];
+                    load_slices(e0, mf);
+                    add_slices(e0, mf);
+                }
             }
             // magnitude of the row's constant terms (scales a rounding slack only): a row lies in exactly one run
             cstabs = (s1 - s1_before) * __longlong_as_double((long long)s_qmax[run & 1]) * (1.0 + 0x1p-50);
@@ -307,6 +342,8 @@ __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) 
         if constexpr (CHUNKED) {
             double* out = p.partial + ((size_t)r * gridDim.y + blockIdx.y) * 5;
             out[0] = cand; out[1] = absx; out[2] = cst; out[3] = cstabs; out[4] = s1;
+        } else if constexpr (PRE) {
+            scan_finish(p, r, nelem, row_pre, cand, absx, cst, cstabs, s1);
         } else {
             scan_finish(p, r, nelem, scan_row_fetch(p, r, ri), cand, absx, cst, cstabs, s1);
         }
@@ -327,24 +364,41 @@ __global__ __launch_bounds__(256) void scan_combine_kernel(const ScanParams p, i
 }
 
 
-template <typename CT>
-static void launch_scan_t(const ScanParams& p, hipStream_t s, int nhalves, int nelem, bool vec) {
-    if (nelem <= 256 || (nelem > SCAN_LDS_MAX && !p.partial)) {      // cross-over of the two layouts measured on MI355X
-        const int groups = ((p.rm.Rc + SCAN_G - 1) / SCAN_G) * nhalves;
-        if (vec) hipLaunchKernelGGL((scan_tall_kernel<4, 8, CT>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
-        else hipLaunchKernelGGL((scan_tall_kernel<1, 8, CT>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
-    } else if (nelem <= SCAN_LDS_MAX) {
+// rows whose constants are staged in LDS (up to SCAN_LDS_MAX coefficients whole, longer ones in chunks)
+template <typename CT, bool HC, bool DC>
+static void launch_scan_lds(const ScanParams& p, hipStream_t s, int nhalves, int nelem, bool vec) {
+    if (nelem <= SCAN_LDS_MAX) {
         const size_t lds = (size_t)5 * ((nelem + 3) & ~3) * sizeof(double);
         const int wgs = ((p.rm.Rc + 31) / 32) * nhalves;
-        if (vec) hipLaunchKernelGGL((scan_lds_kernel<4, 32, 4, false, CT>), dim3(wgs), dim3(256), lds, s, p);
-        else hipLaunchKernelGGL((scan_lds_kernel<1, 32, 4, false, CT>), dim3(wgs), dim3(256), lds, s, p);
+        // (which of the forms runs does not touch a row's arithmetic)
+        if (vec && nelem <= 512 && p.nrows <= SCAN_PRE_ROWS)
+            hipLaunchKernelGGL((scan_lds_kernel<4, 32, 16, false, CT, HC, DC, true>), dim3(wgs), dim3(256), lds, s, p);
+        else if (vec) hipLaunchKernelGGL((scan_lds_kernel<4, 32, 4, false, CT, HC, DC>), dim3(wgs), dim3(256), lds, s, p);
+        else hipLaunchKernelGGL((scan_lds_kernel<1, 32, 4, false, CT, HC, DC>), dim3(wgs), dim3(256), lds, s, p);
     } else {
         const int nchunks = (nelem + SCAN_CHUNK - 1) / SCAN_CHUNK;
         const dim3 grid(((p.rm.Rc + 31) / 32) * nhalves, nchunks);
         const size_t lds = (size_t)5 * SCAN_CHUNK * sizeof(double);
-        if (vec) hipLaunchKernelGGL((scan_lds_kernel<4, 32, 4, true, CT>), grid, dim3(256), lds, s, p);
-        else hipLaunchKernelGGL((scan_lds_kernel<1, 32, 4, true, CT>), grid, dim3(256), lds, s, p);
+        if (vec) hipLaunchKernelGGL((scan_lds_kernel<4, 32, 4, true, CT, HC, DC>), grid, dim3(256), lds, s, p);
+        else hipLaunchKernelGGL((scan_lds_kernel<1, 32, 4, true, CT, HC, DC>), grid, dim3(256), lds, s, p);
         hipLaunchKernelGGL(scan_combine_kernel, dim3((p.nrows + 255) / 256), dim3(256), 0, s, p, nchunks);
+    }
+}
+
+template <typename CT>
+static void launch_scan_t(const ScanParams& p, hipStream_t s, int nhalves, int nelem, bool vec) {
+    // cross-over of the two layouts measured on MI355X (rows of 48: 109 against 126 us for 819 200 rows; 75: 292 against
+    // 191 us for 1 310 720 rows; 256: 398 against 135 us for 409 600 rows)
+    if (nelem <= SCAN_TALL_MAX || (nelem > SCAN_LDS_MAX && !p.partial)) {
+        const int groups = ((p.rm.Rc + SCAN_G - 1) / SCAN_G) * nhalves;
+        if (vec) hipLaunchKernelGGL((scan_tall_kernel<4, 8, CT>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((scan_tall_kernel<1, 8, CT>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
+    } else {
+        const bool hc = p.cpos != nullptr, dc = p.do_consts != 0;
+        if (hc && dc) launch_scan_lds<CT, true, true>(p, s, nhalves, nelem, vec);
+        else if (hc) launch_scan_lds<CT, true, false>(p, s, nhalves, nelem, vec);
+        else if (dc) launch_scan_lds<CT, false, true>(p, s, nhalves, nelem, vec);
+        else launch_scan_lds<CT, false, false>(p, s, nhalves, nelem, vec);
     }
 }
 
