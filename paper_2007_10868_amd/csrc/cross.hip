@@ -1038,90 +1038,206 @@ static void launch_cross_direct(const CrossParams& p0, hipStream_t s) {
 // peak on this chip equals the float64 MFMA peak).  Lanes are grouped by the pixel's PARITY CLASS, i.e. by
 // ((A + ph) mod sh, (B + pw) mod sw) of its absolute position (A, B): within a class every lane uses the same taps
 // f = cy + t*sh, g = cx + u*sw, so tap and channel loops are uniform and the (float64) filter values come through
-// scalar loads.  Consecutive lanes are consecutive pixels of the class in a row's window: their block reads are
-// consecutive window entries (64 contiguous bytes per 16 channels each).
-// grid: x over (row, pixel of the class) / 256, y over the sh*sw classes.
-template <bool VEC>
-__global__ __launch_bounds__(256) void cross_image_kernel(const CrossParams p) {
-    const int N = p.Co, Ck = p.in.C;
-    const long long gid = blockIdx.x * 256LL + threadIdx.x;
-    const uint32_t ppc = (uint32_t)(p.cls_ny * p.cls_nx);
-    if (gid >= (long long)p.nrows * ppc) return;
-    const uint32_t r = fast_div((uint32_t)gid, p.div_cls);
-    const uint32_t k = (uint32_t)gid - r * ppc;
-    const uint32_t ky = fast_div(k, p.div_cls_nx), kx = k - ky * (uint32_t)p.cls_nx;
-    const int cy = (int)fast_div(blockIdx.y, p.div_sw), cx = (int)blockIdx.y - cy * p.sw;      // the class (uniform)
-    const RowInfo ri = row_info(p.rm, (int)r);
-    const int oy = clampi(p.oSy * ri.ys - p.oPy, 0, p.Ho - p.owy), ox = clampi(p.oSx * ri.xs - p.oPx, 0, p.Wo - p.owx);
-    // first window pixel of the class: pa = cy - (oy + ph) (mod sh)
-    const uint32_t my = (uint32_t)(oy + p.ph), mx = (uint32_t)(ox + p.pw);
-    int pa = cy - (int)(my - fast_div(my, p.div_sh) * (uint32_t)p.sh);
-    int pb = cx - (int)(mx - fast_div(mx, p.div_sw) * (uint32_t)p.sw);
-    pa += (pa < 0 ? p.sh : 0) + (int)ky * p.sh;
-    pb += (pb < 0 ? p.sw : 0) + (int)kx * p.sw;
-    if (pa >= p.owy || pb >= p.owx) return;
-    const int A = oy + pa, B = ox + pb;
-    // tap (f, g) = (cy + t*sh, cx + u*sw) reads layer-output pixel (y0 - t, x0 - u)
-    const int y0 = (int)fast_div((uint32_t)(A + p.ph - cy), p.div_sh), x0 = (int)fast_div((uint32_t)(B + p.pw - cx), p.div_sw);
-    // the part of the row's stored window that lies in its exact dependence window (see cross_kernel)
-    const int oiy = clampi(p.in.Sy * ri.ys - p.in.Py, 0, p.in.H - p.in.wy), oix = clampi(p.in.Sx * ri.xs - p.in.Px, 0, p.in.W - p.in.wx);
-    const int ty = p.in.tSy * ri.ys - p.in.tPy, tx = p.in.tSx * ri.xs - p.in.tPx;
-    const int ylo = max(ty, oiy), yhi = min(ty + p.in.tWy, oiy + p.in.wy);
-    const int xlo = max(tx, oix), xhi = min(tx + p.in.tWx, oix + p.in.wx);
-    const float* const row = p.in.data + (size_t)r * (size_t)(p.in.wy * p.in.wx * Ck);
-    double acc[4] = {0.0, 0.0, 0.0, 0.0};
-    for (int t = 0, f = cy; f < p.kh; ++t, f += p.sh) {                  // uniform loops
-        const int y = y0 - t;
-        const bool yok = y >= ylo && y < yhi;
-        for (int u = 0, g = cx; g < p.kw; ++u, g += p.sw) {
-            const int x = x0 - u;
-            if (!(yok && x >= xlo && x < xhi)) continue;
-            const float* a = row + (size_t)((y - oiy) * p.in.wx + (x - oix)) * Ck;
-            const double* w = p.wt64 + (size_t)(f * p.kw + g) * N * Ck;     // [n][c], uniform
-            if (VEC) {
-                for (int c = 0; c < Ck; c += 4) {
-                    const float4 v = *reinterpret_cast<const float4*>(a + c);
-                    const double av[4] = {(double)v.x, (double)v.y, (double)v.z, (double)v.w};
+// scalar loads.
+// A work-group owns R consecutive rows.  It copies their blocks into LDS once, converted to float64 (a block value is
+// used by every output pixel a tap links it to, ceil(kh/sh)*ceil(kw/sw) of them: read per use from global memory, the
+// lanes of a wave fetched 16 bytes each out of 64 different 64-byte segments and the vector L1 set the pace).  In LDS a
+// block pixel is padded by 2 doubles, so that lanes on neighbouring pixels hit different banks.  A wave then takes a
+// (class, group of 64*NIT items) unit: per tap and 4-channel step the filter values are loaded once and used for the
+// NIT items of every lane.  A tap that misses an item's window reads a pixel of zeros instead (adding 0*w leaves a
+// sum as it is), so the loops have no divergent branch.  Per (item, column) the products are added in the order tap
+// row, tap column, channel, whatever R and NIT are.
+// grid: x over groups of R rows.
+constexpr int IMG_NIT = 4;
+constexpr int IMG_RMAX = 64;            // rows per work-group at most (their geometry sits in a table in LDS)
+template <int NN, bool VEC>      // NN: input channels of the layer (columns of the step)
+__global__ __launch_bounds__(256) void cross_image_kernel(const CrossParams p, int R, int pstride, int ngroups) {
+    constexpr int NIT = IMG_NIT;
+    extern __shared__ __attribute__((aligned(16))) double s_blk[];       // [R * window pixels + 1][pstride]
+    // what an item needs of its row, worked out once per row: {box, oy, ox, (oy+ph) mod sh}, {(ox+pw) mod sw, oiy, oix,
+    // 0}, {exact window inside the stored one: first row | rows << 16, first column | columns << 16, 0, 0}
+    __shared__ int4 s_row[IMG_RMAX][3];
+    constexpr int N = NN;
+    const int Ck = p.in.C;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int npix_in = p.in.wy * p.in.wx, row_elems = npix_in * Ck;
+    const int r0 = blockIdx.x * R, rows_here = min(R, p.nrows - r0);
+    const int ppc = p.cls_ny * p.cls_nx;
+    const int zero_pix = R * npix_in;                                    // the pixel of zeros
+    if (tid < rows_here) {
+        const RowInfo ri = row_info(p.rm, r0 + tid);
+        const int oy = clampi(p.oSy * ri.ys - p.oPy, 0, p.Ho - p.owy), ox = clampi(p.oSx * ri.xs - p.oPx, 0, p.Wo - p.owx);
+        const uint32_t my = (uint32_t)(oy + p.ph), mx = (uint32_t)(ox + p.pw);
+        const int oiy = clampi(p.in.Sy * ri.ys - p.in.Py, 0, p.in.H - p.in.wy), oix = clampi(p.in.Sx * ri.xs - p.in.Px, 0, p.in.W - p.in.wx);
+        // the part of the row's stored window that lies in its exact dependence window (see cross_kernel)
+        const int ty = p.in.tSy * ri.ys - p.in.tPy, tx = p.in.tSx * ri.xs - p.in.tPx;
+        const int ylo = max(ty, oiy), yhi = min(ty + p.in.tWy, oiy + p.in.wy);
+        const int xlo = max(tx, oix), xhi = min(tx + p.in.tWx, oix + p.in.wx);
+        s_row[tid][0] = make_int4(ri.b, oy, ox, (int)(my - fast_div(my, p.div_sh) * (uint32_t)p.sh));
+        s_row[tid][1] = make_int4((int)(mx - fast_div(mx, p.div_sw) * (uint32_t)p.sw), oiy, oix, 0);
+        s_row[tid][2] = make_int4((int)((uint32_t)(ylo - oiy) | ((uint32_t)max(yhi - ylo, 0) << 16)),
+                                  (int)((uint32_t)(xlo - oix) | ((uint32_t)max(xhi - xlo, 0) << 16)), 0, 0);
+    }
+    // ---- the rows' blocks -> LDS (float64)
+    {
+        const float* src = p.in.data + (size_t)r0 * row_elems;
+        const int total = rows_here * row_elems;
+        if (VEC) {
+            for (int e = tid * 4; e < total; e += 1024) {
+                const float4 v = *reinterpret_cast<const float4*>(src + e);
+                const int pix = (int)fast_div((uint32_t)e, p.div_ntiles_n);      // div_ntiles_n: the launcher's divider by Ck
+                double* dst = s_blk + pix * pstride + (e - pix * Ck);
+                reinterpret_cast<double2*>(dst)[0] = make_double2((double)v.x, (double)v.y);
+                reinterpret_cast<double2*>(dst)[1] = make_double2((double)v.z, (double)v.w);
+            }
+        } else {
+            for (int e = tid; e < total; e += 256) {
+                const int pix = (int)fast_div((uint32_t)e, p.div_ntiles_n);
+                s_blk[pix * pstride + (e - pix * Ck)] = (double)src[e];
+            }
+        }
+        for (int c = tid; c < pstride; c += 256) s_blk[zero_pix * pstride + c] = 0.0;
+    }
+    __syncthreads();
+    const int ncls = p.sh * p.sw;
+    for (int unit = wave; unit < ncls * ngroups; unit += 4) {              // uniform per wave
+        const int cls = unit % ncls, grp = unit / ncls;
+        const int cy = (int)fast_div((uint32_t)cls, p.div_sw), cx = cls - cy * p.sw;
+        // ---- the lane's items
+        int base[NIT], yrel[NIT], xrel[NIT];             // LDS pixel index of the row's block; tap (0,0) reads window entry (yrel, xrel)
+        uint32_t yrng[NIT], xrng[NIT];                   // exact dependence window inside the stored one: first | size << 16
+        int item_rho[NIT], item_pix[NIT];                // row within the group; window pixel pa << 16 | pb (-1: no item)
 #pragma unroll
-                    for (int n = 0; n < 4; ++n)
-                        if (n < N) {
+        for (int i = 0; i < NIT; ++i) {
+            const int idx = (grp * NIT + i) * 64 + lane;
+            item_pix[i] = -1;
+            base[i] = 0; yrel[i] = xrel[i] = 0; yrng[i] = xrng[i] = 0; item_rho[i] = 0;
+            if (idx >= rows_here * ppc) continue;
+            const uint32_t rho = fast_div((uint32_t)idx, p.div_cls);
+            const uint32_t k = (uint32_t)idx - rho * (uint32_t)ppc;
+            const uint32_t ky = fast_div(k, p.div_cls_nx), kx = k - ky * (uint32_t)p.cls_nx;
+            const int4 g0 = s_row[rho][0], g1 = s_row[rho][1], g2 = s_row[rho][2];
+            // first window pixel of the class: pa = cy - (oy + ph) (mod sh)
+            int pa = cy - g0.w, pb = cx - g1.x;
+            pa += (pa < 0 ? p.sh : 0) + (int)ky * p.sh;
+            pb += (pb < 0 ? p.sw : 0) + (int)kx * p.sw;
+            if (pa >= p.owy || pb >= p.owx) continue;
+            const int A = g0.y + pa, B = g0.z + pb;
+            // tap (f, g) = (cy + t*sh, cx + u*sw) reads layer-output pixel (y0 - t, x0 - u)
+            const int y0 = (int)fast_div((uint32_t)(A + p.ph - cy), p.div_sh), x0 = (int)fast_div((uint32_t)(B + p.pw - cx), p.div_sw);
+            base[i] = (int)rho * npix_in;
+            yrel[i] = y0 - g1.y; xrel[i] = x0 - g1.z;
+            yrng[i] = (uint32_t)g2.x; xrng[i] = (uint32_t)g2.y;
+            item_rho[i] = (int)rho; item_pix[i] = (pa << 16) | pb;
+        }
+        double acc[NIT][N];
 #pragma unroll
-                            for (int j = 0; j < 4; ++j) acc[n] = fma(av[j], w[n * Ck + c + j], acc[n]);
-                        }
+        for (int i = 0; i < NIT; ++i)
+#pragma unroll
+            for (int n = 0; n < N; ++n) acc[i][n] = 0.0;
+        for (int t = 0, f = cy; f < p.kh; ++t, f += p.sh) {                  // uniform loops
+            for (int u = 0, g = cx; g < p.kw; ++u, g += p.sw) {
+                const double* a[NIT];
+#pragma unroll
+                for (int i = 0; i < NIT; ++i) {
+                    const int y = yrel[i] - t, x = xrel[i] - u;
+                    const bool ok = item_pix[i] >= 0 && (unsigned)(y - (int)(yrng[i] & 0xffffu)) < (yrng[i] >> 16) &&
+                                    (unsigned)(x - (int)(xrng[i] & 0xffffu)) < (xrng[i] >> 16);
+                    a[i] = s_blk + (ok ? base[i] + y * p.in.wx + x : zero_pix) * pstride;
                 }
-            } else {
-                for (int c = 0; c < Ck; ++c) {
-                    const double av = (double)a[c];
+                const double* w = p.wt64 + (size_t)(f * p.kw + g) * N * Ck;     // [n][c], uniform
+                if (VEC) {
+                    for (int c = 0; c < Ck; c += 4) {
+                        // the block values of all items first, so that their LDS latencies pass together
+                        double av[NIT][4];
 #pragma unroll
-                    for (int n = 0; n < 4; ++n)
-                        if (n < N) acc[n] = fma(av, w[n * Ck + c], acc[n]);
+                        for (int i = 0; i < NIT; ++i) {
+                            const double2 a0 = reinterpret_cast<const double2*>(a[i] + c)[0];
+                            const double2 a1 = reinterpret_cast<const double2*>(a[i] + c)[1];
+                            av[i][0] = a0.x; av[i][1] = a0.y; av[i][2] = a1.x; av[i][3] = a1.y;
+                        }
+                        double wv[N][4];
+#pragma unroll
+                        for (int n = 0; n < N; ++n)
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) wv[n][j] = w[n * Ck + c + j];
+#pragma unroll
+                        for (int i = 0; i < NIT; ++i)
+#pragma unroll
+                            for (int n = 0; n < N; ++n)
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) acc[i][n] = fma(av[i][j], wv[n][j], acc[i][n]);
+                    }
+                } else {
+                    for (int c = 0; c < Ck; ++c) {
+                        double av[NIT];
+#pragma unroll
+                        for (int i = 0; i < NIT; ++i) av[i] = a[i][c];
+#pragma unroll
+                        for (int i = 0; i < NIT; ++i)
+#pragma unroll
+                            for (int n = 0; n < N; ++n) acc[i][n] = fma(av[i], w[n * Ck + c], acc[i][n]);
+                    }
                 }
             }
         }
-    }
-    long long ridx, aoff;
-    epilogue_row_info(p, ri, (int)r, pa, pb, ridx, aoff);
-    float* out = p.out + ((size_t)r * (size_t)(p.owy * p.owx) + (size_t)(pa * p.owx + pb)) * N;
 #pragma unroll
-    for (int n = 0; n < 4; ++n)
-        if (n < N) {
-            double v = acc[n];
-            if (aoff >= 0) v += (double)p.add.data[aoff + n];
-            if (p.out_grl) v *= (double)relax_factor(v, p.out_grl[ridx + n]);
-            out[n] = (float)v;
+        for (int i = 0; i < NIT; ++i) {
+            if (item_pix[i] < 0) continue;
+            const int r = r0 + item_rho[i];
+            const int pa = item_pix[i] >> 16, pb = item_pix[i] & 0xffff;
+            const int4 g0 = s_row[item_rho[i]][0];
+            // place of the pixel in the packed relaxation of the input layer, [box][Ho*Wo*Co]
+            long long ridx = (long long)g0.x * ((long long)p.Ho * p.Wo * N) + (long long)((g0.y + pa) * p.Wo + (g0.z + pb)) * N;
+            long long aoff = -1;
+            if (p.add.data) epilogue_row_info(p, row_info(p.rm, r), r, pa, pb, ridx, aoff);
+            float* out = p.out + ((size_t)r * (size_t)(p.owy * p.owx) + (size_t)(pa * p.owx + pb)) * N;
+#pragma unroll
+            for (int n = 0; n < N; ++n) {
+                double v = acc[i][n];
+                if (aoff >= 0) v += (double)p.add.data[aoff + n];
+                if (p.out_grl) v *= (double)relax_factor(v, p.out_grl[ridx + n]);
+                out[n] = (float)v;
+            }
         }
+    }
 }
 
-static void launch_cross_image(const CrossParams& p0, hipStream_t s) {
+// false: a row's block does not fit the work-group's LDS (the caller takes another form)
+static bool launch_cross_image(const CrossParams& p0, hipStream_t s) {
     CrossParams p = p0;
     p.cls_ny = (p.owy + p.sh - 1) / p.sh;
     p.cls_nx = (p.owx + p.sw - 1) / p.sw;
     p.div_cls = make_fastdiv((uint32_t)(p.cls_ny * p.cls_nx));
     p.div_cls_nx = make_fastdiv((uint32_t)p.cls_nx);
-    const long long items = (long long)p.nrows * p.cls_ny * p.cls_nx;      // < 2^31: rows * window pixels is
-    const dim3 grid((unsigned)((items + 255) / 256), (unsigned)(p.sh * p.sw));
-    if ((p.in.C & 3) == 0) hipLaunchKernelGGL((cross_image_kernel<true>), grid, dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((cross_image_kernel<false>), grid, dim3(256), 0, s, p);
+    p.div_ntiles_n = make_fastdiv((uint32_t)p.in.C);
+    const int ppc = p.cls_ny * p.cls_nx, ncls = p.sh * p.sw;
+    const int npix_in = p.in.wy * p.in.wx;
+    const int pstride = ((p.in.C + 1) & ~1) + 2;                     // even (16-byte reads), + 2 against bank conflicts
+    const long long lds_max = 60 * 1024 / 8;                         // doubles
+    const long long r_lds = (lds_max / pstride - 1) / npix_in;
+    if (r_lds < 1) return false;
+    // rows per work-group: enough items for the four waves (one (class, 64*NIT items) unit each)
+    const int per_wave = 64 * IMG_NIT;
+    long long R = (long long)per_wave * (ncls >= 4 ? 1 : 4 / ncls) / ppc;
+    R = std::max(1ll, std::min(std::min(R, r_lds), (long long)IMG_RMAX));
+    const int ngroups = (int)((R * ppc + per_wave - 1) / per_wave);
+    const size_t lds = (size_t)(R * npix_in + 1) * pstride * sizeof(double);
+    const dim3 grid((unsigned)((p.nrows + R - 1) / R));
+    const bool vec = (p.in.C & 3) == 0;
+    auto go = [&](auto nn) {
+        constexpr int NN = decltype(nn)::value;
+        if (vec) hipLaunchKernelGGL((cross_image_kernel<NN, true>), grid, dim3(256), lds, s, p, (int)R, pstride, ngroups);
+        else hipLaunchKernelGGL((cross_image_kernel<NN, false>), grid, dim3(256), lds, s, p, (int)R, pstride, ngroups);
+    };
+    switch (p.Co) {
+        case 1: go(std::integral_constant<int, 1>{}); break;
+        case 2: go(std::integral_constant<int, 2>{}); break;
+        case 3: go(std::integral_constant<int, 3>{}); break;
+        default: go(std::integral_constant<int, 4>{}); break;
+    }
+    return true;
 }
 
 // Image layers behind a stride-1 layer with a long K per pixel (3x3 or 5x5 filters over 32 or 64 channels).  With 4 output
@@ -1634,7 +1750,7 @@ void launch_cross(const CrossParams& p, hipStream_t s) {
     // lane's loads are 16 bytes out of a 128-byte line, which the L1 no longer absorbs for longer K (measured: 1.6x
     // faster than the MFMA kernel at K = 64, 0.75x at K = 288)
     const int k_pixel = ((p.kh + p.sh - 1) / p.sh) * ((p.kw + p.sw - 1) / p.sw) * p.in.C;
-    if (N <= 4 && p.wt64 && k_pixel <= 128) { launch_cross_image(p, s); return; }
+    if (N <= 4 && p.wt64 && k_pixel <= 128 && launch_cross_image(p, s)) return;
     size_t strip_lds = 0;
     if (N <= 4 && strip_applies(p, strip_lds)) { launch_cross_strip(p, strip_lds, s); return; }
     if (N <= 4) { launch_cross_direct<2, 0>(p, s); return; }

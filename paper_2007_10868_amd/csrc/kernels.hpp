@@ -78,7 +78,7 @@ struct CrossParams {       // one back-substitution step through an affine layer
     int ntiles_m, ntiles_n;                      // filled by the launcher: tiles of rows / of input channels
     FastDiv div_ntiles_n, div_opix;
     int lds_wt;                                  // filled by the launcher (cross_direct_kernel, image layers): filter staged in LDS
-    int cls_ny, cls_nx;                          // filled by the launcher (cross_image_kernel): pixels per parity class
+    int cls_ny, cls_nx;                          // filled by the launcher (cross_image_kernel): pixels per parity class (it also sets div_ntiles_n to a divider by in.C)
     FastDiv div_cls, div_cls_nx;
     BlockDesc add;         // optional block over the same input layer to be summed in (residual join)
     RowMap rm;
