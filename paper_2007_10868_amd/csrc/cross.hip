@@ -558,6 +558,29 @@ __global__ __launch_bounds__(256, (BM == 64 && BN == 64) ? 4 : 2) void cross_ker
     // float32 -> store.  D[i][j]: register r of lane l holds i = 4*r + l/16, j = l%16.
     __syncthreads();                                   // s_ridx, s_aoff (a tile without any tap has met no barrier yet)
     const bool has_add = p.add.data != nullptr;
+    // A tile that no tap reaches (its pixel lies outside the exact dependence window of all of its rows) and that has no
+    // addend holds zeros: written 16 bytes per thread where the alignment allows, with nothing to wait for.  (0 times a
+    // relaxation factor is the same +0.)
+    if (nIt == 0 && !has_add) {
+        const int ncols = min(BN, N - n0);
+        CT* const out0 = reinterpret_cast<CT*>(p.out) + ((size_t)r_tile * opix + pix) * N + n0;
+        const size_t row_stride = (size_t)opix * N;
+        if constexpr (!A64) {
+            if ((N & 3) == 0 && (ncols & 3) == 0) {
+                const int nq = ncols >> 2;
+                for (int idx = tid; idx < rows_here * nq; idx += 256) {
+                    const int rl = idx / nq, q = idx - rl * nq;
+                    *reinterpret_cast<float4*>(out0 + (size_t)rl * row_stride + 4 * q) = make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+                return;
+            }
+        }
+        for (int idx = tid; idx < rows_here * ncols; idx += 256) {
+            const int rl = idx / ncols, c = idx - rl * ncols;
+            out0[(size_t)rl * row_stride + c] = (CT)0;
+        }
+        return;
+    }
     // a dense layer's relaxation entry depends on the row's box only: when the whole tile lies in one box (within the
     // +x half and within the -x half rows are ordered by box) the lane's columns need one load each instead of one per row
     float g_same[TN];
@@ -803,6 +826,14 @@ __global__ __launch_bounds__(256, 2) void cross_direct_kernel(const CrossParams 
     };
     int ld_t = next_tap(0), ld_d0 = 0;
     if (ld_t < taps) enter_tap(ld_t);
+    // the epilogue's relaxation entries on the uniform path, requested now so that their latency passes under the K loop
+    const long long u_ridx = (long long)u0.b * ((long long)p.Ho * p.Wo * N) + (long long)(u_A * p.Wo + u_B) * N;
+    float g_uni[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = SMALLN ? n0 + (lm & 3) : n0 + j * 16 + lm;
+        g_uni[j] = (uni && p.out_grl && n < N) ? p.out_grl[u_ridx + n] : 0.f;
+    }
     F4 a_raw[TM], b_raw[TN];
     auto load_step = [&]() {
         const int rem = Ck - ld_d0;
@@ -961,7 +992,6 @@ __global__ __launch_bounds__(256, 2) void cross_direct_kernel(const CrossParams 
     // ---- epilogue, as in cross_kernel; on the uniform path the pixel's place in the relaxation array and in the
     // addend's window is the same for all rows (the addend block itself is per row)
     const bool has_add = p.add.data != nullptr;
-    const long long u_ridx = (long long)u0.b * ((long long)p.Ho * p.Wo * N) + (long long)(u_A * p.Wo + u_B) * N;
     long long u_aoff = -1;
     const long long u_astride = (long long)p.add.wy * p.add.wx * N;
     if (uni && has_add) {
@@ -969,22 +999,42 @@ __global__ __launch_bounds__(256, 2) void cross_direct_kernel(const CrossParams 
         const int ax = u_B - clampi(p.add.Sx * u0.xs - p.add.Px, 0, p.add.W - p.add.wx);
         if (ay >= 0 && ay < p.add.wy && ax >= 0 && ax < p.add.wx) u_aoff = (long long)(ay * p.add.wx + ax) * N;
     }
-    // uniform path: the lane's columns have ONE relaxation entry each, whatever the row: the two multipliers a
-    // coefficient can take (upper slope for a >= 0, lower slope 0 or 1 for a < 0) are formed once per column
+    // uniform path: the lane's columns have ONE relaxation entry each, whatever the row (g_uni, requested before the K
+    // loop): the two multipliers a coefficient can take (upper slope for a >= 0, lower slope 0 or 1 for a < 0) are
+    // formed once per column
     double g_pos[TN], g_neg[TN];
     if (uni && p.out_grl) {
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            const int n = SMALLN ? n0 + (lm & 3) : n0 + j * 16 + lm;
-            const float g = n < N ? p.out_grl[u_ridx + n] : 0.f;
-            g_pos[j] = (double)fabsf(g);
-            g_neg[j] = signbit(g) ? 0.0 : 1.0;
+            g_pos[j] = (double)fabsf(g_uni[j]);
+            g_neg[j] = signbit(g_uni[j]) ? 0.0 : 1.0;
         }
     }
     // stores through a buffer resource over the wave's rows: 32-bit offsets
     const uint32_t out_row_bytes = (uint32_t)opix * (uint32_t)N * 4u;
     const __amdgpu_buffer_rsrc_t rsrcO = __builtin_amdgcn_make_buffer_rsrc(
         (void*)(p.out + (size_t)r_wave * opix * N), 0, (int)((uint32_t)rows_here * out_row_bytes), 0x00020000);
+    // A tile that no tap reaches (its pixel lies outside the exact dependence window of all of the wave's rows) and that
+    // has no addend holds zeros: they are written 16 bytes per lane, with nothing to wait for.  (0 times a relaxation
+    // factor is the same +0.)
+    if (nIt == 0 && !has_add) {
+        const int ncols = min(BN, N - n0);
+        if ((N & 3) == 0 && (ncols & 3) == 0) {
+            const int nq = ncols >> 2;
+            for (int idx = lane; idx < rows_here * nq; idx += 64) {
+                const int rl = idx / nq, q = idx - rl * nq;
+                __builtin_amdgcn_raw_buffer_store_b128(uint4_t{0u, 0u, 0u, 0u}, rsrcO,
+                    (int)((uint32_t)rl * out_row_bytes + ((uint32_t)pix * (uint32_t)N + (uint32_t)(n0 + 4 * q)) * 4u), 0, 0);
+            }
+        } else {
+            for (int idx = lane; idx < rows_here * ncols; idx += 64) {
+                const int rl = idx / ncols, c = idx - rl * ncols;
+                __builtin_amdgcn_raw_buffer_store_b32(0u, rsrcO,
+                    (int)((uint32_t)rl * out_row_bytes + ((uint32_t)pix * (uint32_t)N + (uint32_t)(n0 + c)) * 4u), 0, 0);
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
