@@ -122,7 +122,9 @@ gp_status gp_set_interval_coefficients(gp_net* net, int32_t on);
  * depends on the network alone, not on the batch.  The arithmetic per step is that of the general kernels (float32
  * coefficients, float64 accumulation, the same slack terms), but sums are formed in another order, so bounds differ
  * from the general path in the last bits; both are sound.  Off: every layer takes the general kernels.  Not used with
- * early termination, float32-inference mode or float64 storage. */
+ * early termination, float32-inference mode or float64 storage.  The fused path serves latency (a few boxes per call);
+ * with more than about 6000 rows per start layer (2 * neurons * boxes) the general kernels are faster, and a caller
+ * that passes hundreds of boxes per call should switch it off. */
 gp_status gp_set_chain_fusion(gp_net* net, int32_t on);
 /* Precision of the stored coefficients (the paper evaluates a single and a double precision build, Section 5); 32
  * (default) or 64.  With 32 every new coefficient of a row's block is rounded once to float32 and the rounding is
