@@ -11,7 +11,9 @@ import pytest
 import torch
 
 import workloads as wl
-from parity import affine_read_layers, analysed_layers, make_gpu, make_oracle, oracle_with_gpu_relaxation
+from helpers import ball_box
+from parity import (affine_read_layers, analysed_layers, check_samples_inside, make_gpu, make_oracle,
+                    oracle_with_gpu_relaxation)
 
 pytestmark = pytest.mark.gpu
 
@@ -63,3 +65,38 @@ def test_dense_chain(seed):
                 loose = max(np.max((olo - glo) / (1 + np.abs(olo))), np.max((ghi - ohi) / (1 + np.abs(ohi))))
                 inside = max(np.max((glo - olo) / (1 + np.abs(olo))), np.max((ohi - ghi) / (1 + np.abs(ohi))))
                 assert loose <= bar and inside <= 1e-12, (bits, fused, seed, nb, b, lid, loose, inside)
+
+
+def test_accumulation_roundoff_hook_only_widens_and_stays_sound():
+    """The study hook that prices the accumulation-error term at another unit roundoff (Section 4.1, explicit error
+    term): the default is 2^-50 (setting it changes nothing), a larger unit gives bounds that contain the default ones
+    and are looser by no more than the ratio of the units allows, out-of-range units are refused."""
+    from paper_2007_10868_amd import GpuPolyError
+    net = wl.fc_net("roundoff_fc", [96, 80, 64], n_in=50, n_out=6, seed=21)
+    rng = np.random.default_rng(3)
+    c = rng.random(net.n_in).astype(np.float32)
+    eps = 0.01
+    g = make_gpu(net)
+    g.set_chain_fusion(False)
+    g.analyze(c, eps)
+    base = {l: g.get_bounds_f64(l) for l in analysed_layers(net)}
+    g.debug_set_accumulation_roundoff(2.0 ** -50)
+    g.analyze(c, eps)
+    for l in base:
+        lo, hi = g.get_bounds_f64(l)
+        assert np.array_equal(lo, base[l][0]) and np.array_equal(hi, base[l][1]), l
+    g.debug_set_accumulation_roundoff(2.0 ** -24)
+    g.analyze(c, eps)
+    grew = False
+    for l in base:
+        lo, hi = g.get_bounds_f64(l)
+        assert (lo <= base[l][0]).all() and (hi >= base[l][1]).all(), l
+        grew = grew or (hi > base[l][1]).any()
+        # float32-unit slack: still small against the bounds themselves on a net of this size
+        assert np.max(hi - base[l][1]) <= 1e-2 * (1.0 + np.max(np.abs(base[l][1]))), l
+    assert grew
+    lo0, hi0 = ball_box(c, eps)
+    check_samples_inside(net, g, lo0, hi0, 2000, rng, what="roundoff 2^-24")
+    for bad in (2.0 ** -60, 2.0 ** -4, float("nan")):
+        with pytest.raises(GpuPolyError):
+            g.debug_set_accumulation_roundoff(bad)
