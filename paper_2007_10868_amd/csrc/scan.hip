@@ -98,7 +98,8 @@ constexpr int SCAN_G = 8;     // rows per wave of the 8-lanes-per-row layout
 // Short rows: LPR = 8 lanes per row, 8 rows per wave.  Every lane accumulates for its own row (few registers, many
 // resident waves) and fetches the constants of its own elements; lanes of different rows that meet the same neuron
 // read the same addresses.
-template <int V, int LPR, typename CT>
+// HC / DC: see scan_lds_kernel.
+template <int V, int LPR, typename CT, bool HC, bool DC>
 __global__ __launch_bounds__(256) void scan_tall_kernel(const ScanParams p) {
     constexpr int RPW = 64 / LPR;                            // rows per wave
     const int tid = threadIdx.x, lane = tid & 63;
@@ -137,17 +138,17 @@ __global__ __launch_bounds__(256) void scan_tall_kernel(const ScanParams p) {
 #pragma unroll
             for (int v = 0; v < V; ++v) {
                 double cp = 0.0, cn = 0.0, X = 0.0, kp = 0.0, be = 0.0;
-                if (p.cpos) {
+                if constexpr (HC) {
                     cp = p.cpos[j + v];
                     cn = p.cneg[j + v];
                     X = fmax(fabs(p.xlo[j + v]), fabs(p.xhi[j + v]));
                 }
-                if (p.do_consts) {
+                if constexpr (DC) {
                     if (p.kap) kp = p.kap[j + v];
                     if (p.beff) be = p.beff[c + v];
                     if (p.eta) { const double et = p.eta[j + v]; kp += 2.0 * et; be -= et; }
                 }
-                scan_term(p.cpos != nullptr, p.do_consts != 0, mf[v], cp, cn, X, kp, be, cand, absx, cst, cstabs, s1);
+                scan_term(HC, DC, mf[v], cp, cn, X, kp, be, cand, absx, cst, cstabs, s1);
             }
         }
     }
@@ -391,8 +392,17 @@ static void launch_scan_t(const ScanParams& p, hipStream_t s, int nhalves, int n
     // 191 us for 1 310 720 rows; 256: 398 against 135 us for 409 600 rows)
     if (nelem <= SCAN_TALL_MAX || (nelem > SCAN_LDS_MAX && !p.partial)) {
         const int groups = ((p.rm.Rc + SCAN_G - 1) / SCAN_G) * nhalves;
-        if (vec) hipLaunchKernelGGL((scan_tall_kernel<4, 8, CT>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
-        else hipLaunchKernelGGL((scan_tall_kernel<1, 8, CT>), dim3((groups + 3) / 4), dim3(256), 0, s, p);
+        const dim3 grid((groups + 3) / 4);
+        const bool hc = p.cpos != nullptr, dc = p.do_consts != 0;
+        auto go = [&](auto hc_c, auto dc_c) {
+            constexpr bool H = decltype(hc_c)::value, D = decltype(dc_c)::value;
+            if (vec) hipLaunchKernelGGL((scan_tall_kernel<4, 8, CT, H, D>), grid, dim3(256), 0, s, p);
+            else hipLaunchKernelGGL((scan_tall_kernel<1, 8, CT, H, D>), grid, dim3(256), 0, s, p);
+        };
+        if (hc && dc) go(std::true_type{}, std::true_type{});
+        else if (hc) go(std::true_type{}, std::false_type{});
+        else if (dc) go(std::false_type{}, std::true_type{});
+        else go(std::false_type{}, std::false_type{});
     } else {
         const bool hc = p.cpos != nullptr, dc = p.do_consts != 0;
         if (hc && dc) launch_scan_lds<CT, true, true>(p, s, nhalves, nelem, vec);
