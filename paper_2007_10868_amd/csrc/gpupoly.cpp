@@ -88,6 +88,7 @@ const double kRoundCoef = 0x1p-24 * (1.0 + 0x1p-20);   // float32 rounding of a 
 const double kRoundCoef64 = 0x1p-53 * (1.0 + 0x1p-20); // rounding of a product or sum of two float64 values (float64 storage)
 const int kMaxSlots = 6;
 const long long kMaxLayerWeights = 1LL << 28;
+const int kGenMinRows = 16384;        // launches with more rows let the scan make a start layer's own rows (run_plan)
 
 }  // namespace
 
@@ -963,6 +964,8 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                 gp::launch_fill_i32(ls.d_term + row0, 0, rm.Rc, net->stream);
             }
         }
+        bool gen_pending = false, gen_write = false;      // an INIT left to the scan that follows it
+        gp::GenParams gen = {};
         for (size_t oi = 0; oi < pl.ops.size(); ++oi) {
             const PlanOp& op = pl.ops[oi];
             const int nrows = rm.Rc * nsign;
@@ -992,7 +995,26 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                 ip.c = d_c; ip.err = d_err; ip.best = d_best;
                 ip.seeded = early ? 1 : 0;
                 ip.coef64 = net->coef64 ? 1 : 0;
-                if (net->interval) gp::launch_iv_init(ip, net->stream);
+                // The start layer's own matrix rows followed by their scan: the scan makes the rows itself (same values,
+                // same roundings), so the block is not read back, and not even written when no later step reads it
+                // (the first layer's rows over the input).  The bits are those of the two-kernel form, so the choice may
+                // depend on the launch: with few rows the two kernels, which spread over more work-groups, are faster
+                // (one box of FC 9x500: 1.40 against 1.46 ms per pass).
+                gen_pending = false;
+                if (op.init_mode == 2 && nrows > kGenMinRows && !net->interval && !net->coef64 && !early && !ip.eta && oi + 1 < pl.ops.size() &&
+                    pl.ops[oi + 1].kind == PlanOp::SCAN && pl.ops[oi + 1].slot_in == op.slot_out && !pl.ops[oi + 1].consts_only) {
+                    gen_pending = true;
+                    gen.wt = ip.wt; gen.bias = ip.bias; gen.out_grl = ip.out_grl;
+                    gen.H = ip.H; gen.W = ip.W; gen.C = ip.C;
+                    gen.wy = ip.wy; gen.wx = ip.wx; gen.Sy = ip.Sy; gen.Sx = ip.Sx; gen.Py = ip.Py; gen.Px = ip.Px;
+                    gen.kh = ip.kh; gen.kw = ip.kw; gen.sh = ip.sh; gen.sw = ip.sw; gen.ph = ip.ph; gen.pw = ip.pw;
+                    gen.dense = ip.dense; gen.Cs = ip.Cs;
+                    gen_write = false;
+                    for (size_t k = oi + 2; k < pl.ops.size(); ++k) {
+                        if (pl.ops[k].slot_in == op.slot_out || pl.ops[k].slot_add == op.slot_out) { gen_write = true; break; }
+                        if (pl.ops[k].slot_out == op.slot_out) break;          // the slot is written again before anyone reads it
+                    }
+                } else if (net->interval) gp::launch_iv_init(ip, net->stream);
                 else gp::launch_init(ip, net->stream);
                 have_rows = true;
             } else if (op.kind == PlanOp::SCAN && net->interval) {
@@ -1027,6 +1049,7 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                 sp.c = d_c; sp.err = d_err; sp.best = d_best;
                 sp.done = may_stop ? d_done[cur] : nullptr;
                 sp.partial = chunks_max ? d_partial : nullptr;
+                if (gen_pending) { sp.gen = 1; sp.gen_write = gen_write ? 1 : 0; sp.g = gen; gen_pending = false; }
                 prof_mark(net, 1, false);
                 gp::launch_scan(sp, net->stream);
                 prof_mark(net, 1, true);

@@ -86,6 +86,16 @@ struct CrossParams {       // one back-substitution step through an affine layer
     int coef64;            // coefficient blocks (in, out, add) hold float64 instead of float32 values
 };
 
+struct GenParams {         // a start layer's own matrix rows (InitParams mode 2), for the scan that makes them itself
+    const float* wt;       // [tap][Cs][C] (predecessor channels innermost); dense: [Cs][nelem]
+    const float* bias;     // [Cs]
+    const float* out_grl;  // packed relaxation of the predecessor when it is a ReLU layer (applied), else null
+    int H, W, C;           // dims of the predecessor
+    int wy, wx, Sy, Sx, Py, Px;
+    int kh, kw, sh, sw, ph, pw, dense;
+    int Cs;                // channels of the start layer
+};
+
 struct ScanParams {        // per-row reductions over a block
     BlockDesc blk;
     RowMap rm;
@@ -114,6 +124,12 @@ struct ScanParams {        // per-row reductions over a block
     int coef64;            // the block holds float64 values
     FastDiv div_C, div_wx; // filled by the launcher: blk.C, blk.wx
     double coef_floor;     // smallest magnitude a stored coefficient resolves, times 2^20 (see scan_finish)
+    // gen: the block does not exist yet.  It holds the rows that init_kernel would write in mode 2 (float32 storage, no
+    // seeded bounds, no inference-rounding term): the scan computes a row's coefficients where it would have loaded
+    // them, takes the row's constant from the bias (err = 0, best = +inf), and writes the coefficients to blk.data only
+    // if gen_write is set (a block that no later step reads is never stored).
+    int gen = 0, gen_write = 0;
+    GenParams g = {};
 };
 
 struct InitParams {

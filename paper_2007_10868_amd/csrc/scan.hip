@@ -49,15 +49,20 @@ struct ScanRow {
 };
 __device__ __forceinline__ ScanRow scan_row_fetch(const ScanParams& p, int r, const RowInfo& ri) {
     ScanRow s;
-    s.c = p.c[r];
-    s.err = p.err[r];
+    if (p.gen) {           // the row starts here: constant = +/- bias, no slack yet
+        s.c = (double)(ri.sign * p.g.bias[ri.cs]);
+        s.err = 0.0;
+    } else {
+        s.c = p.c[r];
+        s.err = p.err[r];
+    }
     s.xmax_self = (p.round_coef > 0.0 && p.xmax_self) ? p.xmax_self[ri.b] : 0.0;
     s.bi = 0; s.best = 0.0; s.frozen = true;
     if (p.update_best && p.cpos) {
         // a task that met the termination criterion keeps the bounds it had at that moment
         s.frozen = p.done && p.done[r >= p.rm.Rc ? r - p.rm.Rc : r];
         s.bi = best_index(p.rm, r);
-        s.best = p.best[s.bi];
+        s.best = p.gen ? INFINITY : p.best[s.bi];
     }
     s.xmax_a = (p.do_consts && p.xmax_a) ? p.xmax_a[ri.b] : 0.0;
     s.xmax_b = (p.do_consts && p.xmax_b) ? p.xmax_b[ri.b] : 0.0;
@@ -75,6 +80,7 @@ __device__ __forceinline__ void scan_finish(const ScanParams& p, int r, int nele
     scan_finish_math(nelem, p.round_coef, (p.round_coef > 0.0 && p.xmax_self) ? p.coef_floor * s.xmax_self : 0.0, has_cand,
                      p.do_consts != 0, e1, t_cand, t_absx, t_cst, t_cstabs, t_s1, c, err, best);
     if (has_cand && !s.frozen) p.best[s.bi] = best;
+    else if (p.gen && !has_cand) p.best[best_index(p.rm, r)] = INFINITY;
     p.c[r] = c;
     p.err[r] = err;
 }
@@ -93,14 +99,70 @@ __device__ __forceinline__ void scan_load(const CT* src, CT (&mf)[V]) {
     }
 }
 
+// The same V coefficients of a row that does not exist yet (p.gen): the start layer's own matrix row, i.e. its filter
+// placed in the row's window over the predecessor, times the sign of the row and the predecessor's ReLU substitution
+// (Section 2: the neuron's affine expression) - the values and roundings of init_kernel's mode 2 - written to the block
+// when a later step reads it.  V = 4: e is a multiple of 4 and the 4 values are channels of one window pixel.
+template <int V>
+__device__ __forceinline__ void scan_gen(const ScanParams& p, const RowInfo& ri, int r, int nelem, int e, float (&mf)[V]) {
+    const GenParams& g = p.g;
+    float w[V], gr[V];
+#pragma unroll
+    for (int k = 0; k < V; ++k) { w[k] = 0.f; gr[k] = 1.f; }
+    if (g.dense) {
+        const float* ws = g.wt + (size_t)ri.cs * nelem + e;
+        const float* gs = g.out_grl ? g.out_grl + (size_t)ri.b * nelem + e : nullptr;
+        if constexpr (V == 4) {
+            const float4 t = *reinterpret_cast<const float4*>(ws);
+            w[0] = t.x; w[1 % V] = t.y; w[2 % V] = t.z; w[3 % V] = t.w;
+            if (gs) { const float4 u = *reinterpret_cast<const float4*>(gs); gr[0] = u.x; gr[1 % V] = u.y; gr[2 % V] = u.z; gr[3 % V] = u.w; }
+        } else {
+            w[0] = ws[0];
+            if (gs) gr[0] = gs[0];
+        }
+    } else {
+        const uint32_t pix = fast_div((uint32_t)e, p.div_C);
+        const int c = e - (int)pix * g.C;
+        const uint32_t a = fast_div(pix, p.div_wx);
+        const int A = clampi(g.Sy * ri.ys - g.Py, 0, g.H - g.wy) + (int)a;
+        const int B = clampi(g.Sx * ri.xs - g.Px, 0, g.W - g.wx) + (int)(pix - a * (uint32_t)g.wx);
+        const int f = A - (ri.ys * g.sh - g.ph), gg = B - (ri.xs * g.sw - g.pw);
+        if (f >= 0 && f < g.kh && gg >= 0 && gg < g.kw) {
+            const float* ws = g.wt + ((size_t)(f * g.kw + gg) * g.Cs + ri.cs) * g.C + c;
+            const float* gs = g.out_grl ? g.out_grl + (size_t)ri.b * ((size_t)g.H * g.W * g.C) + (size_t)(A * g.W + B) * g.C + c : nullptr;
+            if constexpr (V == 4) {
+                const float4 t = *reinterpret_cast<const float4*>(ws);
+                w[0] = t.x; w[1 % V] = t.y; w[2 % V] = t.z; w[3 % V] = t.w;
+                if (gs) { const float4 u = *reinterpret_cast<const float4*>(gs); gr[0] = u.x; gr[1 % V] = u.y; gr[2 % V] = u.z; gr[3 % V] = u.w; }
+            } else {
+                w[0] = ws[0];
+                if (gs) gr[0] = gs[0];
+            }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < V; ++k) {
+        float v = ri.sign * w[k];
+        if (g.out_grl && v != 0.f) v = (float)((double)v * (double)relax_factor((double)v, gr[k]));
+        mf[k] = v;
+    }
+    if (p.gen_write) {
+        float* dst = const_cast<float*>(p.blk.data) + (size_t)r * nelem + e;
+        if constexpr (V == 4) *reinterpret_cast<float4*>(dst) = make_float4(mf[0], mf[1 % V], mf[2 % V], mf[3 % V]);
+        else dst[0] = mf[0];
+    }
+}
+
 constexpr int SCAN_G = 8;     // rows per wave of the 8-lanes-per-row layout
 
 // Short rows: LPR = 8 lanes per row, 8 rows per wave.  Every lane accumulates for its own row (few registers, many
 // resident waves) and fetches the constants of its own elements; lanes of different rows that meet the same neuron
 // read the same addresses.
 // HC / DC: see scan_lds_kernel.
-template <int V, int LPR, typename CT, bool HC, bool DC>
+// GEN: the rows are made here (p.gen, see scan_gen).
+template <int V, int LPR, typename CT, bool HC, bool DC, bool GEN = false>
 __global__ __launch_bounds__(256) void scan_tall_kernel(const ScanParams p) {
+    static_assert(!GEN || std::is_same<CT, float>::value, "generated rows are float32 blocks");
     constexpr int RPW = 64 / LPR;                            // rows per wave
     const int tid = threadIdx.x, lane = tid & 63;
     const BlockDesc& B = p.blk;
@@ -124,7 +186,8 @@ __global__ __launch_bounds__(256) void scan_tall_kernel(const ScanParams p) {
     if (valid) {
         for (int e = sub * V; e < nelem; e += LPR * V) {
             CT mf[V];
-            scan_load<CT, V>(src + e, mf);
+            if constexpr (GEN) scan_gen<V>(p, ri, r, nelem, e, mf);
+            else scan_load<CT, V>(src + e, mf);
             int c;
             long long j;
             const int pix = (int)fast_div((uint32_t)e, p.div_C);
@@ -182,9 +245,11 @@ constexpr int SCAN_CHUNK = 512;         // chunk of longer rows (20 KB of LDS: 8
 // PRE: the row fits U slices per lane; they and the row's scalars are requested before the constants are staged, so
 // that a launch with few rows (whose time is a chain of memory round trips, not bandwidth) waits for the constants,
 // the row and the scalars at once instead of one after the other.  None of this touches a row's arithmetic or its order.
-template <int V, int ROWS, int U, bool CHUNKED, typename CT, bool HC, bool DC, bool PRE = false>
+// GEN: the rows are made here (p.gen, see scan_gen).
+template <int V, int ROWS, int U, bool CHUNKED, typename CT, bool HC, bool DC, bool PRE = false, bool GEN = false>
 __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) {
     static_assert(!(PRE && CHUNKED), "a chunked row does not fit the lane's registers");
+    static_assert(!GEN || std::is_same<CT, float>::value, "generated rows are float32 blocks");
     constexpr int SCAN_LDS_ROWS = ROWS;
     constexpr int NT = ROWS * 8;
     extern __shared__ __attribute__((aligned(16))) double s_const[];     // [5][nelem_pad]
@@ -223,7 +288,10 @@ __global__ __launch_bounds__(ROWS * 8) void scan_lds_kernel(const ScanParams p) 
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int e = e0 + u * 8 * V;
-            if (e < c1) scan_load<CT, V>(src + e, mf[u]);
+            if (e < c1) {
+                if constexpr (GEN) scan_gen<V>(p, ri, r, nelem, e, mf[u]);
+                else scan_load<CT, V>(src + e, mf[u]);
+            }
         }
     };
     // (the row's scalars first: the loads behind a dependent one would have to arrive before it could be used)
@@ -366,49 +434,48 @@ __global__ __launch_bounds__(256) void scan_combine_kernel(const ScanParams p, i
 
 
 // rows whose constants are staged in LDS (up to SCAN_LDS_MAX coefficients whole, longer ones in chunks)
-template <typename CT, bool HC, bool DC>
+template <typename CT, bool HC, bool DC, bool GEN>
 static void launch_scan_lds(const ScanParams& p, hipStream_t s, int nhalves, int nelem, bool vec) {
     if (nelem <= SCAN_LDS_MAX) {
         const size_t lds = (size_t)5 * ((nelem + 3) & ~3) * sizeof(double);
         const int wgs = ((p.rm.Rc + 31) / 32) * nhalves;
         // (which of the forms runs does not touch a row's arithmetic)
         if (vec && nelem <= 512 && p.nrows <= SCAN_PRE_ROWS)
-            hipLaunchKernelGGL((scan_lds_kernel<4, 32, 16, false, CT, HC, DC, true>), dim3(wgs), dim3(256), lds, s, p);
-        else if (vec) hipLaunchKernelGGL((scan_lds_kernel<4, 32, 4, false, CT, HC, DC>), dim3(wgs), dim3(256), lds, s, p);
-        else hipLaunchKernelGGL((scan_lds_kernel<1, 32, 4, false, CT, HC, DC>), dim3(wgs), dim3(256), lds, s, p);
+            hipLaunchKernelGGL((scan_lds_kernel<4, 32, 16, false, CT, HC, DC, true, GEN>), dim3(wgs), dim3(256), lds, s, p);
+        else if (vec) hipLaunchKernelGGL((scan_lds_kernel<4, 32, 4, false, CT, HC, DC, false, GEN>), dim3(wgs), dim3(256), lds, s, p);
+        else hipLaunchKernelGGL((scan_lds_kernel<1, 32, 4, false, CT, HC, DC, false, GEN>), dim3(wgs), dim3(256), lds, s, p);
     } else {
         const int nchunks = (nelem + SCAN_CHUNK - 1) / SCAN_CHUNK;
         const dim3 grid(((p.rm.Rc + 31) / 32) * nhalves, nchunks);
         const size_t lds = (size_t)5 * SCAN_CHUNK * sizeof(double);
-        if (vec) hipLaunchKernelGGL((scan_lds_kernel<4, 32, 4, true, CT, HC, DC>), grid, dim3(256), lds, s, p);
-        else hipLaunchKernelGGL((scan_lds_kernel<1, 32, 4, true, CT, HC, DC>), grid, dim3(256), lds, s, p);
+        if (vec) hipLaunchKernelGGL((scan_lds_kernel<4, 32, 4, true, CT, HC, DC, false, GEN>), grid, dim3(256), lds, s, p);
+        else hipLaunchKernelGGL((scan_lds_kernel<1, 32, 4, true, CT, HC, DC, false, GEN>), grid, dim3(256), lds, s, p);
         hipLaunchKernelGGL(scan_combine_kernel, dim3((p.nrows + 255) / 256), dim3(256), 0, s, p, nchunks);
     }
 }
 
-template <typename CT>
+template <typename CT, bool GEN>
 static void launch_scan_t(const ScanParams& p, hipStream_t s, int nhalves, int nelem, bool vec) {
+    const bool hc = p.cpos != nullptr, dc = p.do_consts != 0;
     // cross-over of the two layouts measured on MI355X (rows of 48: 109 against 126 us for 819 200 rows; 75: 292 against
     // 191 us for 1 310 720 rows; 256: 398 against 135 us for 409 600 rows)
     if (nelem <= SCAN_TALL_MAX || (nelem > SCAN_LDS_MAX && !p.partial)) {
         const int groups = ((p.rm.Rc + SCAN_G - 1) / SCAN_G) * nhalves;
         const dim3 grid((groups + 3) / 4);
-        const bool hc = p.cpos != nullptr, dc = p.do_consts != 0;
         auto go = [&](auto hc_c, auto dc_c) {
             constexpr bool H = decltype(hc_c)::value, D = decltype(dc_c)::value;
-            if (vec) hipLaunchKernelGGL((scan_tall_kernel<4, 8, CT, H, D>), grid, dim3(256), 0, s, p);
-            else hipLaunchKernelGGL((scan_tall_kernel<1, 8, CT, H, D>), grid, dim3(256), 0, s, p);
+            if (vec) hipLaunchKernelGGL((scan_tall_kernel<4, 8, CT, H, D, GEN>), grid, dim3(256), 0, s, p);
+            else hipLaunchKernelGGL((scan_tall_kernel<1, 8, CT, H, D, GEN>), grid, dim3(256), 0, s, p);
         };
         if (hc && dc) go(std::true_type{}, std::true_type{});
         else if (hc) go(std::true_type{}, std::false_type{});
         else if (dc) go(std::false_type{}, std::true_type{});
         else go(std::false_type{}, std::false_type{});
     } else {
-        const bool hc = p.cpos != nullptr, dc = p.do_consts != 0;
-        if (hc && dc) launch_scan_lds<CT, true, true>(p, s, nhalves, nelem, vec);
-        else if (hc) launch_scan_lds<CT, true, false>(p, s, nhalves, nelem, vec);
-        else if (dc) launch_scan_lds<CT, false, true>(p, s, nhalves, nelem, vec);
-        else launch_scan_lds<CT, false, false>(p, s, nhalves, nelem, vec);
+        if (hc && dc) launch_scan_lds<CT, true, true, GEN>(p, s, nhalves, nelem, vec);
+        else if (hc) launch_scan_lds<CT, true, false, GEN>(p, s, nhalves, nelem, vec);
+        else if (dc) launch_scan_lds<CT, false, true, GEN>(p, s, nhalves, nelem, vec);
+        else launch_scan_lds<CT, false, false, GEN>(p, s, nhalves, nelem, vec);
     }
 }
 
@@ -422,8 +489,9 @@ void launch_scan(const ScanParams& p0, hipStream_t s) {
     const bool vec = (p.blk.C & 3) == 0;
     // the layout depends on the row length only, never on how many rows the launch has: a row's sums are formed in
     // the same order whether its box is analysed alone, in a batch, or in a chunk of a batch
-    if (p.coef64) launch_scan_t<double>(p, s, nhalves, nelem, vec);
-    else launch_scan_t<float>(p, s, nhalves, nelem, vec);
+    if (p.coef64) launch_scan_t<double, false>(p, s, nhalves, nelem, vec);       // (the host never sets gen with float64 blocks)
+    else if (p.gen) launch_scan_t<float, true>(p, s, nhalves, nelem, vec);
+    else launch_scan_t<float, false>(p, s, nhalves, nelem, vec);
 }
 
 }  // namespace gp

@@ -145,9 +145,12 @@ def _plant(tmp, name, find, repl):
 
 def test_every_planted_mistake_fails_its_pin(tmp_path):
     tmp = str(tmp_path)
-    clean = os.path.join(tmp, "clean.c")
-    shutil.copy(SRC, clean)
-    jobs = [("clean", clean, node) for node in sorted({m[3] for m in MUTATIONS})]
+    # (one untouched copy per pin: the jobs run side by side and each builds the library next to its source)
+    jobs = []
+    for k, node in enumerate(sorted({m[3] for m in MUTATIONS})):
+        clean = os.path.join(tmp, f"clean_{k}.c")
+        shutil.copy(SRC, clean)
+        jobs.append(("clean", clean, node))
     jobs += [(name, _plant(tmp, name, find, repl), node) for name, find, repl, node in MUTATIONS]
     with ThreadPoolExecutor(max_workers=4) as pool:
         results = list(pool.map(lambda j: _run_pin(j[1], j[2]), jobs))
