@@ -312,6 +312,10 @@ __global__ __launch_bounds__(CH_THREADS) void chain_kernel(const ChainParams p) 
         if (!isfinite(x)) x = 0.0;
         // non-negative doubles order like their bit patterns
         atomicMax(reinterpret_cast<unsigned long long*>(p.xmax + s_box[tid]), (unsigned long long)__double_as_longlong(x));
+        if (p.has_relu) {      // the ReLU layer that reads these bounds, neuron by neuron
+            const double xr = relu_neuron(p.relu, g, l, u);
+            atomicMax(reinterpret_cast<unsigned long long*>(p.relu.xmax + s_box[tid]), (unsigned long long)__double_as_longlong(xr));
+        }
     }
 }
 

@@ -162,4 +162,37 @@ __device__ __forceinline__ void scan_finish_math(int nelem, double round_coef, d
     err *= (1.0 + 0x1p-48);   // the few float64 operations above
 }
 
+// ReLU layer, one neuron: intervals [max(l,0), max(u,0)] and the relaxation  lam*x <= relu(x) <= gam*x + del  (Section 2,
+// ReLU transformer).  Any gam in [0,1] is sound when del >= max(-gam*l, u - gam*u); gam is the float32 nearest to
+// u/(u-l).  Returns the neuron's largest magnitude (0 when not finite).  Shared by relu_kernel and by the kernels that
+// store a layer's bounds and know that a ReLU layer reads them.
+__device__ __forceinline__ double relu_neuron(const ReluParams& p, long long i, double l, double u) {
+    if (!isfinite(l) || !isfinite(u)) *p.flag = 1;
+    p.lo[i] = fmax(l, 0.0);
+    p.hi[i] = fmax(u, 0.0);
+    float g, lam;
+    double rho = 0.0, kap = 0.0;
+    if (l >= 0.0) { g = 1.f; lam = 1.f; rho = u; }
+    else if (u <= 0.0) { g = 0.f; lam = 0.f; }
+    else {
+        g = (float)(u / (u - l));
+        g = fminf(fmaxf(g, 0x1p-20f), 1.f);       // a positive coefficient must stay recoverable from its product with g
+        const double gd = (double)g;
+        const double d1 = -gd * l, d2 = u - gd * u;     // each off by a few ulps at most
+        double d = fmax(d1, d2);
+        d = d + (fabs(d) + fabs(u)) * 0x1p-50 + 0x1p-1000;
+        lam = (u > -l) ? 1.f : 0.f;
+        // rounded up, including the rounding of the stored product coefficient*g (p.margin: four roundings of the
+        // storage type)
+        rho = (u / gd) * (1.0 + p.margin);
+        kap = (d / gd) * (1.0 + p.margin);
+    }
+    p.grl[i] = lam != 0.f ? g : -g;      // -0.0f encodes slope 0 with lam = 0
+    p.rho[i] = rho;
+    p.kap[i] = kap;
+    double x = fmax(u, 0.0);
+    if (!isfinite(x)) x = 0.0;
+    return x;
+}
+
 }  // namespace gp

@@ -140,6 +140,7 @@ struct gp_net {
     double acc_unit = 0x1p-50;     // unit roundoff the accumulation-error term is priced at (gp_debug_set_accumulation_roundoff)
     bool interval = false;         // the paper's literal scheme: interval coefficients, directed rounding (Section 4.1)
     bool chain_on = true;          // chains of narrow dense layers go through the fused kernel (gp_set_chain_fusion)
+    int relu_reader = -1;          // during run_plan: the ReLU layer whose constants the launch that stores the bounds writes too (-1: none)
     int* d_count = nullptr;
     int* h_count = nullptr;        // pinned: task counts read back while the GPU keeps working
     hipEvent_t count_ev = nullptr;
@@ -792,6 +793,19 @@ bool build_chain(const gp_net* net, const Plan& pl, int start, gp::ChainParams& 
     return gp::chain_lds_bytes(p) <= 150 * 1024;
 }
 
+// the ReLU layer lid: where its intervals and relaxation go
+gp::ReluParams relu_params(gp_net* net, int lid, int batch) {
+    Layer& l = net->L[lid];
+    gp::ReluParams rp;
+    rp.plo = net->L[l.a].d_lo; rp.phi = net->L[l.a].d_hi;
+    rp.lo = l.d_lo; rp.hi = l.d_hi; rp.grl = l.d_grl; rp.rho = l.d_rho; rp.kap = l.d_kap;
+    rp.xmax = l.d_xmax; rp.flag = net->d_flag;
+    rp.total = l.n * batch;
+    rp.n = l.n;
+    rp.margin = net->coef64 ? 0x1p-50 : 0x1p-22;
+    return rp;
+}
+
 // run one plan over all its tasks, chunk by chunk (Section 4.2 "Memory management").
 // With early termination (Sections 3.2, 4.2) the rows' best bounds start from the layer's interval image, tasks
 // whose interval does not strictly contain 0 never start, and after every candidate the tasks that have come to
@@ -809,6 +823,8 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
         double flop_per_row = 0.0;
         if (build_chain(net, pl, start, chp, &flop_per_row)) {
             chp.row0 = 0; chp.Rc = (int)total;
+            chp.has_relu = net->relu_reader >= 0 ? 1 : 0;
+            if (chp.has_relu) chp.relu = relu_params(net, net->relu_reader, batch);
             // (timed as a crossing launch when it contains products; a plan without any is bookkeeping only)
             const bool timed = flop_per_row > 0.0;
             if (timed) prof_mark(net, 0, false);
@@ -1129,6 +1145,9 @@ gp_status run_plan(gp_net* net, const Plan& pl, int start, bool certify, int bat
                     fp.lo = net->L[start].d_lo; fp.hi = net->L[start].d_hi;
                     fp.xmax = net->L[start].d_xmax; fp.flag = net->d_flag;
                     fp.widen = (net->float_inference && net->L[start].type == T_ADD) ? 0x1p-24 * (1.0 + 0x1p-20) : 0.0;
+                    fp.has_relu = net->relu_reader >= 0 ? 1 : 0;
+                    if (fp.has_relu) fp.relu = relu_params(net, net->relu_reader, batch);
+                    else std::memset(&fp.relu, 0, sizeof(fp.relu));
                     gp::launch_finalize(fp, net->stream);
                 }
             }
@@ -1150,17 +1169,12 @@ gp_status check_flag(gp_net* net) {
 // all layers after the input box is on the device
 gp_status analyze_layers(gp_net* net, int batch) {
     int nl = (int)net->L.size();
+    std::vector<char> relu_done(nl, 0);
     for (int i = 1; i < nl; ++i) {
         Layer& l = net->L[i];
         if (l.type == T_RELU) {
-            gp::ReluParams rp;
-            rp.plo = net->L[l.a].d_lo; rp.phi = net->L[l.a].d_hi;
-            rp.lo = l.d_lo; rp.hi = l.d_hi; rp.grl = l.d_grl; rp.rho = l.d_rho; rp.kap = l.d_kap;
-            rp.xmax = l.d_xmax; rp.flag = net->d_flag;
-            rp.total = l.n * batch;
-            rp.n = l.n;
-            rp.margin = net->coef64 ? 0x1p-50 : 0x1p-22;
-            gp::launch_relu(rp, net->stream);
+            if (relu_done[i]) continue;        // written by the launch that stored its predecessor's bounds
+            gp::launch_relu(relu_params(net, i, batch), net->stream);
         } else {
             if (net->float_inference && l.type == T_ADD && l.d_eta_thru) {
                 gp::SumEtaParams ep;
@@ -1199,7 +1213,16 @@ gp_status analyze_layers(gp_net* net, int batch) {
                 Plan* pl;
                 gp_status st = get_plan(net, i, &pl);
                 if (st != GP_OK) return st;
+                // A ReLU layer that reads this layer: the launch that stores the layer's bounds writes the ReLU's
+                // intervals and relaxation as well (same arithmetic, one launch fewer).  Early termination keeps the
+                // kernel of its own (it seeds the ReLU layer's state between the two).
+                net->relu_reader = -1;
+                if (!net->early)
+                    for (int j = i + 1; j < nl; ++j)
+                        if (net->L[j].type == T_RELU && net->L[j].a == i && !relu_done[j]) { net->relu_reader = j; break; }
                 st = run_plan(net, *pl, i, false, batch);
+                if (net->relu_reader >= 0 && st == GP_OK) relu_done[net->relu_reader] = 1;
+                net->relu_reader = -1;
                 if (st != GP_OK) return st;
             }
             if (net->float_inference && l.type == T_ADD) {

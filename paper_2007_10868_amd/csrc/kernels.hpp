@@ -157,15 +157,6 @@ struct InitParams {
     FastDiv div_C, div_wx; // filled by the launcher
 };
 
-struct FinalizeParams {
-    RowMap rm;
-    const double* best;
-    double* lo; double* hi;   // [batch][n_start] of the start layer
-    double* xmax;             // [batch] running max of |bounds| of that layer, per box
-    int* flag;                // set to 1 on NaN/Inf
-    double widen;             // each end moves outward by widen*|end| (a sum layer's one float32 rounding); 0: none
-};
-
 struct ReluParams {
     const double* plo; const double* phi;   // predecessor intervals [total]
     double* lo; double* hi;                 // this layer's intervals
@@ -176,6 +167,18 @@ struct ReluParams {
     long long n;                            // neurons per box
     double margin;                          // relative margin of rho and kap: 2^-22 for float32 storage, 2^-50 for float64
 };
+
+struct FinalizeParams {
+    RowMap rm;
+    const double* best;
+    double* lo; double* hi;   // [batch][n_start] of the start layer
+    double* xmax;             // [batch] running max of |bounds| of that layer, per box
+    int* flag;                // set to 1 on NaN/Inf
+    double widen;             // each end moves outward by widen*|end| (a sum layer's one float32 rounding); 0: none
+    int has_relu;             // a ReLU layer reads this layer: its intervals and relaxation (relu, plo/phi unused) are
+    ReluParams relu;          //   written by the same launch, neuron by neuron, as relu_kernel would write them
+};
+
 
 struct BoxParams {
     const float* centers;   // [batch][n] in C,H,W order (device)
@@ -262,6 +265,8 @@ struct ChainParams {
     double coef_floor;
     double* lo; double* hi;  // [batch][n_start] bounds of the start layer
     double* xmax; int* flag;
+    int has_relu;            // as in FinalizeParams
+    ReluParams relu;
 };
 bool launch_chain(const ChainParams& p, hipStream_t s);
 size_t chain_lds_bytes(const ChainParams& p);

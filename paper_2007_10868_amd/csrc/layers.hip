@@ -140,7 +140,7 @@ __device__ __forceinline__ void atomic_max_nonneg(double* base, int slot, double
 __global__ void finalize_kernel(const FinalizeParams p) {
     const int r = blockIdx.x * blockDim.x + threadIdx.x;
     const bool valid = r < p.rm.Rc;
-    double x = 0.0;
+    double x = 0.0, xr = 0.0;
     int slot = 0;
     if (valid) {
         const long long g = (long long)p.rm.row0 + r;
@@ -156,8 +156,10 @@ __global__ void finalize_kernel(const FinalizeParams p) {
         x = fmax(fabs(u), fabs(l));
         if (!isfinite(x)) x = 0.0;
         slot = (int)(g / p.rm.n_start);
+        if (p.has_relu) xr = relu_neuron(p.relu, g, l, u);     // (the stored ends, widened if they were)
     }
     atomic_max_nonneg(p.xmax, slot, x, valid);
+    if (p.has_relu) atomic_max_nonneg(p.relu.xmax, slot, xr, valid);      // uniform
 }
 
 void launch_finalize(const FinalizeParams& p, hipStream_t s) {
@@ -173,32 +175,7 @@ __global__ void relu_kernel(const ReluParams p) {
     double x = 0.0;
     int slot = 0;
     if (valid) {
-        const double l = p.plo[i], u = p.phi[i];
-        if (!isfinite(l) || !isfinite(u)) *p.flag = 1;
-        p.lo[i] = fmax(l, 0.0);
-        p.hi[i] = fmax(u, 0.0);
-        float g, lam;
-        double rho = 0.0, kap = 0.0;
-        if (l >= 0.0) { g = 1.f; lam = 1.f; rho = u; }
-        else if (u <= 0.0) { g = 0.f; lam = 0.f; }
-        else {
-            g = (float)(u / (u - l));
-            g = fminf(fmaxf(g, 0x1p-20f), 1.f);       // a positive coefficient must stay recoverable from its product with g
-            const double gd = (double)g;
-            const double d1 = -gd * l, d2 = u - gd * u;     // each off by a few ulps at most
-            double d = fmax(d1, d2);
-            d = d + (fabs(d) + fabs(u)) * 0x1p-50 + 0x1p-1000;
-            lam = (u > -l) ? 1.f : 0.f;
-            // rounded up, including the rounding of the stored product coefficient*g (p.margin: four roundings of the
-            // storage type)
-            rho = (u / gd) * (1.0 + p.margin);
-            kap = (d / gd) * (1.0 + p.margin);
-        }
-        p.grl[i] = lam != 0.f ? g : -g;      // -0.0f encodes slope 0 with lam = 0
-        p.rho[i] = rho;
-        p.kap[i] = kap;
-        x = fmax(u, 0.0);
-        if (!isfinite(x)) x = 0.0;
+        x = relu_neuron(p, i, p.plo[i], p.phi[i]);
         slot = (int)(i / p.n);
     }
     atomic_max_nonneg(p.xmax, slot, x, valid);
