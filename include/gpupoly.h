@@ -115,8 +115,8 @@ gp_status gp_set_float_inference(gp_net* net, int32_t on);
  * termination or float32-inference mode (GP_ERR_UNSUPPORTED at the next analysis); float64 storage and chain fusion
  * are ignored while it is on.  Takes effect at the next analysis. */
 gp_status gp_set_interval_coefficients(gp_net* net, int32_t on);
-/* Plumbing; on by default.  The rows of a dense layer whose back-substitution runs through dense layers only, all of at
- * most 256 neurons (the last block, usually over the input, at most 1024), are carried through ALL their steps by one
+/* Plumbing; on by default.  The rows of a dense layer of at most 256 neurons whose back-substitution runs through dense
+ * layers only, all of at most 256 neurons (the last block, usually over the input, at most 1024), are carried through ALL their steps by one
  * kernel launch per start layer, with the coefficient block in LDS (Section 2, "Bottleneck Backsubstitution": the rows
  * are independent, so a work-group can follow its rows to the input on its own).  Whether a layer takes this path
  * depends on the network alone, not on the batch.  The arithmetic per step is that of the general kernels (float32

@@ -746,6 +746,9 @@ const int kChainMaxHidden = 256, kChainMaxLast = 1024;
 bool build_chain(const gp_net* net, const Plan& pl, int start, gp::ChainParams& p, double* flop_per_row) {
     const Layer& ls = net->L[start];
     if (!net->chain_on || net->early || net->float_inference || net->coef64 || net->interval || ls.type != T_DENSE) return false;
+    // a wide start layer has many rows per box; its rows go through the general kernels like those of a wide hidden layer
+    // (measured on the 500 own rows per box of FC 9x500's first layer, 784 wide: 0.37 against 0.09 ms at 100 boxes)
+    if (ls.n > kChainMaxHidden) return false;
     const size_t nops = pl.ops.size();
     if (nops < 3 || nops % 2 == 0) return false;                         // INIT SCAN (CROSS SCAN)* FINALIZE
     if (pl.ops[0].kind != PlanOp::INIT || pl.ops[0].init_mode != 2 || pl.ops[nops - 1].kind != PlanOp::FINALIZE) return false;

@@ -79,14 +79,15 @@ def test_fused_chain_matches_oracle_and_general_kernels(name, maker, eps):
 
 
 def test_which_layers_take_the_fused_path():
-    """Decided by the network alone: a hidden layer of more than 256 neurons, or a non-dense layer below, sends a start
-    layer to the general kernels; modes the fused kernel does not implement switch it off altogether."""
+    """Decided by the network alone: more than 256 neurons in the start layer itself or in a hidden layer below it, or a
+    non-dense layer below, send a start layer to the general kernels; modes the fused kernel does not implement switch
+    it off altogether."""
     rng = np.random.default_rng(0)
-    net = wl.fc_net("mixed", [64, 300, 64], n_in=50, n_out=6, seed=4)     # start layers 1 and 3 are chains, 5 and 7 cross 300
+    net = wl.fc_net("mixed", [64, 300, 64], n_in=50, n_out=6, seed=4)     # start layer 1 is a chain, 3 is 300 wide, 5 and 7 cross 300
     X = rng.random((2, net.n_in)).astype(np.float32)
     g = make_gpu(net)
     cross, scan = launches(g, X, 0.01)
-    assert cross == 1 + (2 + 3) and scan == (3 + 4)
+    assert cross == 1 + (2 + 3) and scan == 2 + (3 + 4)
     o = make_oracle(net)
     oracle_with_gpu_ties(net, o, g, X[1], 0.01, batch_index=1)
     compare_all(net, g, o, batch_index=1, what="mixed")
