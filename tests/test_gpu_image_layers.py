@@ -64,3 +64,40 @@ def test_image_step_batched_equals_single(case):
             lo1, hi1 = gs.get_bounds_f64(lid)
             lo2, hi2 = gb.get_bounds_f64(lid, j)
             assert np.array_equal(lo1, lo2) and np.array_equal(hi1, hi2), (net.name, j, lid)
+
+
+LARGE = [
+    # conv 6 channels (no 4-channel groups): rows of 150 and of 18 coefficients made by the scans of large launches
+    ("conv6", lambda: wl.conv_net("gen_conv6", (2, 13, 13), [(6, 3, 1, 0), (4, 5, 1, 0)], [12], n_out=4, seed=431), 50, False),
+    # conv 8 channels: 16-byte groups; the dense start layer's rows range over a 12x12x8 block (chunks of 512 coefficients)
+    ("conv8", lambda: wl.conv_net("gen_conv8", (3, 13, 13), [(8, 2, 1, 0)], [170], n_out=4, seed=432), 50, False),
+    # dense rows with the fused chain kernel switched off
+    ("dense", lambda: wl.fc_net("gen_fc", [120, 96], n_in=40, n_out=5, seed=433), 90, True),
+]
+
+
+@pytest.mark.parametrize("name,maker,batch,chain_off", LARGE, ids=[c[0] for c in LARGE])
+def test_rows_made_by_the_scan_equal_the_stored_ones(name, maker, batch, chain_off):
+    """Launches of more than 16 384 rows let the scan compute a start layer's own matrix rows instead of reading them back
+    (and never store the rows over the input): the bounds must be the bits of the two-kernel form, which the same
+    boxes take when they are analysed one at a time; one box is also compared with the oracle."""
+    net = maker()
+    rng = np.random.default_rng(77)
+    cs = rng.random((batch, net.n_in)).astype(np.float32)
+    eps = 0.02
+    gb = make_gpu(net)
+    gs = make_gpu(net)
+    if chain_off:
+        gb.set_chain_fusion(False)
+        gs.set_chain_fusion(False)
+    gb.analyze_batch(cs, eps)
+    for j in (0, batch // 2, batch - 1):
+        gs.analyze(cs[j], eps)
+        for lid in analysed_layers(net):
+            lo1, hi1 = gs.get_bounds_f64(lid)
+            lo2, hi2 = gb.get_bounds_f64(lid, j)
+            assert np.array_equal(lo1, lo2) and np.array_equal(hi1, hi2), (net.name, j, lid)
+    j = batch - 1
+    o = make_oracle(net)
+    oracle_with_gpu_ties(net, o, gb, cs[j], eps, batch_index=j)
+    compare_all(net, gb, o, batch_index=j, what=net.name)
